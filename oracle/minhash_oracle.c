@@ -1,0 +1,165 @@
+/*
+ * CPU oracle for b-bit minwise-hash signatures.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the checker that the GPU library is compared against.  It is
+ * deliberately plain, single-threaded and slow, shares no code, header, table
+ * or trick with the GPU path, and must never be called from the product path.
+ *
+ * What it computes is the definition itself, written out:
+ *
+ *   - a data vector is a set S of nonzero feature indices in {0..D-1}
+ *     (Section 1.1);
+ *   - the j-th hashed value of S is the minimum, over the nonzero locations t
+ *     of S, of the mapped location h_j(t) (Section 2, last paragraph);
+ *   - h_j is the 2-universal hash  ((a1 + a2 t) mod p) mod D  (Section 2,
+ *     eq. "eqn_h_2U"), the 4-universal hash
+ *     ((a1 + a2 t + a3 t^2 + a4 t^3) mod p) mod D  (eq. "eqn_h_4U"), or the j-th
+ *     column of an explicit "fully random permutation matrix" of size D x k
+ *     (Section 1.5);
+ *   - only the lowest b bits of every minimum are kept (Section 1.1), and a
+ *     data vector becomes k b-bit integers (Section 1.1, after eq. "eqn_R_b").
+ *
+ * Readings where the paper is silent (all stated in the repository's design
+ * notes): coefficients are 0-based here, c[j][i] multiplies t^i; the whole
+ * polynomial is reduced mod p before mod D; the minimum of an empty set is
+ * 0xFFFFFFFF; value j occupies bits [j*b, (j+1)*b) of the row's bit string,
+ * bit q of the string being bit (q mod 8) of byte (q div 8); pad bits are 0.
+ *
+ * Arithmetic: unsigned __int128 and the % operator.  No Mersenne folding, no
+ * power-of-two shortcut for mod D.  The cubic is reduced term by term only to
+ * stay inside 128 bits, which is legal because reduction mod p is a ring
+ * homomorphism.
+ *
+ * Pins: tests/test_oracle_pins.py (closed forms, explicit permutations on tiny
+ * D, modular-inverse and power identities through Python's big integers, the
+ * collision identity of Section 1.1 eq. (1) and Theorem 1 on planted pairs,
+ * the truncation example, union/subset/order invariants).
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+typedef unsigned __int128 u128;
+
+enum {
+    ORACLE_2U_M31 = 0,
+    ORACLE_4U_M31 = 1,
+    ORACLE_2U_M61 = 2,
+    ORACLE_4U_M61 = 3,
+    ORACLE_PERM = 4
+};
+
+#define ORACLE_EMPTY_MIN 0xFFFFFFFFu
+
+static int family_prime_degree(int family, uint64_t *p, int *deg)
+{
+    switch (family) {
+    case ORACLE_2U_M31: *p = 2147483647ull; *deg = 2; return 0;
+    case ORACLE_4U_M31: *p = 2147483647ull; *deg = 4; return 0;
+    case ORACLE_2U_M61: *p = 2305843009213693951ull; *deg = 2; return 0;
+    case ORACLE_4U_M61: *p = 2305843009213693951ull; *deg = 4; return 0;
+    default: return -1;
+    }
+}
+
+/* (c[0] + c[1] t + ... + c[deg-1] t^(deg-1)) mod p, then mod D.
+ * Section 2, eqs. "eqn_h_2U" and "eqn_h_4U". */
+static uint64_t hash_location(const uint64_t *c, int deg, uint64_t p, uint64_t D, uint64_t t)
+{
+    u128 acc = 0;
+    u128 power = 1;              /* t^i mod p */
+    for (int i = 0; i < deg; ++i) {
+        u128 term = ((u128)(c[i] % p) * power) % p;
+        acc = (acc + term) % p;
+        if (i + 1 < deg) power = (power * (u128)(t % p)) % p;
+    }
+    return (uint64_t)(acc % (u128)D);
+}
+
+/*
+ * Full (untruncated) minima: minima[i*k + j] = min over t in row i of h_j(t),
+ * or 0xFFFFFFFF for an empty row.  Host pointers throughout.
+ * Returns 0, or a negative code for arguments it cannot interpret.
+ */
+int minhash_minima_oracle(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows,
+                          uint64_t D, int32_t k, int32_t family, const void *params,
+                          int64_t perm_ld, uint32_t *minima)
+{
+    if (n_rows < 0 || k < 1 || D < 1 || D > (1ull << 32)) return -1;
+    if (n_rows == 0) return 0;
+    if (!row_ptr || !params || !minima) return -1;
+
+    uint64_t p = 0;
+    int deg = 0;
+    if (family == ORACLE_PERM) {
+        if (perm_ld < k) return -5;
+    } else {
+        if (family_prime_degree(family, &p, &deg) != 0) return -2;
+        if (D >= p) return -3;
+    }
+
+    for (int64_t i = 0; i < n_rows; ++i) {
+        int64_t lo = row_ptr[i], hi = row_ptr[i + 1];
+        for (int32_t j = 0; j < k; ++j) {
+            uint64_t m = ORACLE_EMPTY_MIN;
+            for (int64_t e = lo; e < hi; ++e) {
+                uint64_t t = col_idx[e];
+                uint64_t v;
+                if (family == ORACLE_PERM) {
+                    const uint32_t *table = (const uint32_t *)params;
+                    v = table[(size_t)t * (size_t)perm_ld + (size_t)j];
+                } else {
+                    const uint64_t *coeffs = (const uint64_t *)params;
+                    v = hash_location(coeffs + (size_t)j * (size_t)deg, deg, p, D, t);
+                }
+                if (v < m) m = v;
+            }
+            minima[(size_t)i * (size_t)k + (size_t)j] = (uint32_t)m;
+        }
+    }
+    return 0;
+}
+
+/*
+ * Keep the lowest b bits of each of the k values and lay them out as one bit
+ * string per row, one bit at a time.  out rows are out_stride bytes apart and
+ * are cleared first, so pad bits and pad bytes are 0.
+ */
+int minhash_pack_oracle(const uint32_t *minima, int64_t n_rows, int32_t k, int32_t b,
+                        uint8_t *out, int64_t out_stride)
+{
+    if (n_rows < 0 || k < 1 || b < 1 || b > 32) return -4;
+    int64_t sig_bytes = ((int64_t)k * b + 7) / 8;
+    if (out_stride < sig_bytes) return -5;
+    if (n_rows == 0) return 0;
+    if (!minima || !out) return -1;
+    for (int64_t i = 0; i < n_rows; ++i) {
+        uint8_t *row = out + (size_t)i * (size_t)out_stride;
+        memset(row, 0, (size_t)out_stride);
+        for (int32_t j = 0; j < k; ++j) {
+            uint32_t z = minima[(size_t)i * (size_t)k + (size_t)j];
+            for (int32_t bit = 0; bit < b; ++bit) {
+                if ((z >> bit) & 1u) {
+                    int64_t q = (int64_t)j * b + bit;
+                    row[q / 8] |= (uint8_t)(1u << (q % 8));
+                }
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Same argument list as the GPU library's entry point, minus workspace,
+ * stream and flags, with host pointers.  scratch holds n_rows*k uint32.
+ */
+int minhash_signatures_oracle(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows,
+                              uint64_t D, int32_t k, int32_t b, int32_t family,
+                              const void *params, int64_t perm_ld,
+                              uint8_t *out, int64_t out_stride, uint32_t *scratch)
+{
+    if (b < 1 || b > 32 || k < 1) return -4;
+    int rc = minhash_minima_oracle(row_ptr, col_idx, n_rows, D, k, family, params, perm_ld, scratch);
+    if (rc != 0) return rc;
+    return minhash_pack_oracle(scratch, n_rows, k, b, out, out_stride);
+}
