@@ -1,0 +1,143 @@
+/*
+ * minhash.h - C ABI of the MI355X (gfx950) b-bit minwise-hash signature library.
+ *
+ * The library turns every sparse binary data vector, given as the set of its
+ * nonzero feature indices (CSR without a values array), into k b-bit integers:
+ * for each of k hash functions (or explicit permutations) the minimum hashed
+ * location over the row's nonzeros, of which only the lowest b bits are kept.
+ * All pointers are plain pointers; which side of the bus they live on is stated
+ * per argument.  The library owns no memory: every buffer, including the
+ * workspace, belongs to the caller.  No call throws; errors are return codes.
+ */
+#ifndef MINHASH_H
+#define MINHASH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MINHASH_VERSION 100   /* 1.00 */
+
+/* Hash families.  p is the Mersenne prime the polynomial is reduced by. */
+enum {
+    MINHASH_2U_M31 = 0,  /* ((c0 + c1 t) mod (2^31-1)) mod D                  Section 2, eq. "eqn_h_2U" */
+    MINHASH_4U_M31 = 1,  /* ((c0 + c1 t + c2 t^2 + c3 t^3) mod (2^31-1)) mod D Section 2, eq. "eqn_h_4U";
+                            Mersenne reduction as in Section 3.4               */
+    MINHASH_2U_M61 = 2,  /* 2U with p = 2^61-1 (Section 3.4, last paragraph)   */
+    MINHASH_4U_M61 = 3,  /* not implemented: returns MINHASH_ERR_FAMILY        */
+    MINHASH_PERM   = 4   /* explicit D x k permutation matrix, Section 1.5     */
+};
+
+/* Return codes. */
+enum {
+    MINHASH_OK            =  0,
+    MINHASH_ERR_ARG       = -1,  /* null pointer, negative size, n_rows or nnz bound too large */
+    MINHASH_ERR_FAMILY    = -2,  /* unknown or unimplemented family                            */
+    MINHASH_ERR_D         = -3,  /* D == 0, D > 2^32, or D >= p for a hash family              */
+    MINHASH_ERR_KB        = -4,  /* k < 1, k > MINHASH_MAX_K, b < 1 or b > 32                  */
+    MINHASH_ERR_STRIDE    = -5,  /* out_stride < ceil(k*b/8) or perm_ld < k                    */
+    MINHASH_ERR_WORKSPACE = -6,  /* workspace null, misaligned or smaller than required        */
+    MINHASH_ERR_HIP       = -7,  /* a HIP runtime call failed; see minhash_last_hip_error()    */
+    MINHASH_ERR_COEFF     = -8,  /* minhash_check_coeffs: a coefficient is >= p                */
+    MINHASH_ERR_DATA      = -9   /* minhash_status: VALIDATE found an index >= D or a
+                                    decreasing row_ptr                                         */
+};
+
+#define MINHASH_MAX_K            65536
+#define MINHASH_FLAG_VALIDATE    1u   /* check col_idx < D and row_ptr monotone on the device */
+#define MINHASH_WORKSPACE_ALIGN  256
+
+/*
+ * minhash_signatures - the whole hot path for one batch of rows.
+ *
+ * For every row i and every j < k it computes
+ *     m[i][j] = min over t in col_idx[row_ptr[i] .. row_ptr[i+1]) of h_j(t)
+ * (Section 2, last paragraph: every nonzero location t is mapped to h_j(t) and
+ * the minimum of the mapped locations is the j-th hashed value), keeps the
+ * lowest b bits of m[i][j] (Section 1.1) and writes them as bits
+ * [j*b, (j+1)*b) of row i's bit string at out + i*out_stride, bit q of the
+ * string being bit (q mod 8) of byte (q div 8).  Bytes from ceil(k*b/8) up to
+ * out_stride, and the unused high bits of the last signature byte, are written
+ * as 0.  The minimum of an empty row is 0xFFFFFFFF, so all its fields are ones.
+ *
+ *   row_ptr   device, n_rows+1 int64, non-decreasing offsets into col_idx;
+ *             row_ptr[0] need not be 0
+ *   col_idx   device, uint32 feature indices in [0, D); any order, duplicates
+ *             allowed (the result depends only on the set)
+ *   n_rows    0 <= n_rows < 2^31; 0 is a successful no-op
+ *   D         size of the feature universe, 1 <= D <= 2^32, D < p for hash
+ *             families.  D a power of two takes a faster path
+ *   k, b      number of functions (1..MINHASH_MAX_K), bits kept (1..32; b = 32
+ *             stores the full minima as little-endian uint32)
+ *   family    one of MINHASH_*
+ *   params    device.  Hash families: uint64 c[k][deg], deg = 2 (2U) or 4 (4U),
+ *             c[j][i] multiplies t^i and lies in [0, p) (the paper numbers the
+ *             same coefficients a_{i+1,j}).  MINHASH_PERM: uint32
+ *             table[D][perm_ld], index-major, table[t][j] = pi_j(t)
+ *   perm_ld   MINHASH_PERM: row pitch of the table in elements, >= k; else 0
+ *   out       device, n_rows*out_stride bytes, written completely
+ *   out_stride >= ceil(k*b/8)
+ *   workspace device, MINHASH_WORKSPACE_ALIGN-aligned, at least
+ *             minhash_workspace_bytes(n_rows, nnz_upper_bound, k, family) bytes
+ *             with nnz_upper_bound >= row_ptr[n_rows]-row_ptr[0]; contents on
+ *             entry are ignored; two calls may share it only on one stream
+ *   stream    hipStream_t (NULL = the default stream); all work is enqueued on
+ *             it and the call returns without synchronising
+ *   flags     0 or MINHASH_FLAG_VALIDATE
+ *
+ * Returns MINHASH_OK once everything is enqueued, or a negative code found
+ * before any launch (nothing has been enqueued then).  Indices >= D or a
+ * decreasing row_ptr are undefined behaviour unless MINHASH_FLAG_VALIDATE is
+ * set, in which case offending entries are skipped and minhash_status reports
+ * MINHASH_ERR_DATA.
+ */
+int minhash_signatures(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows,
+                       uint64_t D, int32_t k, int32_t b, int32_t family,
+                       const void *params, int64_t perm_ld,
+                       uint8_t *out, int64_t out_stride,
+                       void *workspace, size_t workspace_bytes,
+                       void *stream, uint32_t flags);
+
+/*
+ * Same computation, for measurement: brackets the hash / gather kernel (the
+ * step that evaluates h_j(t) and keeps the running minima, Section 3.2 phase 2)
+ * with HIP events on `stream`, waits for the stream, and stores that kernel's
+ * duration in milliseconds in *kernel_ms (host pointer, may be NULL).
+ */
+int minhash_signatures_profiled(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows,
+                                uint64_t D, int32_t k, int32_t b, int32_t family,
+                                const void *params, int64_t perm_ld,
+                                uint8_t *out, int64_t out_stride,
+                                void *workspace, size_t workspace_bytes,
+                                void *stream, uint32_t flags, float *kernel_ms);
+
+/* Bytes of device workspace a call with at most nnz_upper_bound nonzeros needs
+ * (load-balancer work list plus partial minima of rows that are split across
+ * wavefronts).  Returns 0 for arguments minhash_signatures would reject. */
+size_t minhash_workspace_bytes(int64_t n_rows, int64_t nnz_upper_bound, int32_t k, int32_t family);
+
+/* Host-side check that every coefficient of host_coeffs[k][deg] is below the
+ * family's prime (Section 2: coefficients are drawn from {0, ..., p-1}).
+ * Returns MINHASH_OK, MINHASH_ERR_COEFF, or an argument error. */
+int minhash_check_coeffs(const uint64_t *host_coeffs, int32_t k, int32_t family);
+
+/* Waits for `stream`, then returns MINHASH_OK or MINHASH_ERR_DATA according to
+ * what the last call that used `workspace` with MINHASH_FLAG_VALIDATE found. */
+int minhash_status(const void *workspace, void *stream);
+
+/* Static text for a return code; never NULL. */
+const char *minhash_error_string(int code);
+
+/* Text of the HIP error behind the last MINHASH_ERR_HIP on this host thread. */
+const char *minhash_last_hip_error(void);
+
+/* MINHASH_VERSION of the loaded library. */
+int minhash_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MINHASH_H */

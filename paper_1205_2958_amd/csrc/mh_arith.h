@@ -1,0 +1,257 @@
+// Exact integer arithmetic of the hash families, written for the gfx950 VALU.
+//
+// Everything here is unsigned integer work; results are bit-exact values of
+//     h(t) = ((c0 + c1 t [+ c2 t^2 + c3 t^3]) mod p) mod D      (Section 2, eqs. eqn_h_2U, eqn_h_4U)
+// for the Mersenne primes p = 2^31-1 and p = 2^61-1.  Section 3.4 replaces the
+// modulo by shifts and masks because 2^31 = 1 (mod p): a value v = 2^31 S + y
+// is congruent to S + y.  The same fact is used here, arranged so that one
+// evaluation costs one 32x32->64 multiply-add plus a handful of half-cost
+// integer instructions:
+//
+//   * The multiplicand is doubled when the nonzero is staged (2t instead of t),
+//     so the 64-bit product is 2W and its two 32-bit halves are S = W >> 31 and
+//     2 (W mod 2^31): the fold is one shift and one add, no funnel shift.
+//   * The polynomial carries an offset of +1 (W = X + 1).  S + y then lies in
+//     [1, 2^32) and X mod p is  S + y - 1  when S + y <= p  and  S + y - 2^31
+//     otherwise, i.e.  (x + (x >> 31) - 1) & p  with x = S + y: the canonical
+//     residue without a compare.  (Section 3.4's routine ends with the same
+//     "subtract p if the folded value reached p" step; a non-canonical residue
+//     p would give p mod D instead of 0.)
+//   * For the cubic, t, t^2 mod p, t^3 mod p are computed once per nonzero while
+//     staging, so the k functions need three multiply-adds each and a single
+//     fold.  Coefficients and powers are re-centred to (-p/2, p/2) so that the
+//     doubled sum of three products still fits 64 bits; a multiple of p added
+//     to the constant term keeps it positive.
+//
+// The functions compile for the host as well, so that a CPU test can compare
+// them with the % operator on edge values and random inputs.
+#pragma once
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define MH_HD __host__ __device__ __forceinline__
+#else
+#define MH_HD inline
+#endif
+
+namespace mh {
+
+constexpr uint32_t P31 = 0x7FFFFFFFu;
+constexpr uint64_t P61 = (1ull << 61) - 1;
+constexpr uint32_t EMPTY_MIN = 0xFFFFFFFFu;   // minimum of an empty set
+
+// ---------------------------------------------------------------- mod D
+// D a power of two: and with D-1.  Otherwise r mod D for r < 2^31 by one
+// multiply-high with M = floor(2^32 / D): q = floor(r M / 2^32) is the true
+// quotient or one less, so r - q D lies in [0, 2D) and min(v, v - D) in
+// unsigned arithmetic finishes it.
+struct ModD {
+    uint32_t D;      // low 32 bits of D (D = 2^32 only occurs with the permutation family)
+    uint32_t mask;   // D - 1 when D is a power of two
+    uint32_t M;      // floor(2^32 / D) for D >= 2 not a power of two
+    uint32_t pow2;
+};
+
+MH_HD ModD make_mod_d(uint64_t D)
+{
+    ModD m;
+    m.D = (uint32_t)D;
+    m.pow2 = (D & (D - 1)) == 0 ? 1u : 0u;
+    m.mask = (uint32_t)(D - 1);
+    m.M = m.pow2 ? 0u : (uint32_t)((1ull << 32) / D);
+    return m;
+}
+
+MH_HD uint32_t mulhi_u32(uint32_t a, uint32_t b) { return (uint32_t)(((uint64_t)a * b) >> 32); }
+
+template <bool POW2>
+MH_HD uint32_t reduce_mod_d(uint32_t r, const ModD& md)   // r < 2^31
+{
+    if (POW2) return r & md.mask;
+    uint32_t q = mulhi_u32(r, md.M);
+    uint32_t v = r - q * md.D;
+    uint32_t w = v - md.D;
+    return w < v ? w : v;
+}
+
+// ---------------------------------------------------------------- p = 2^31 - 1, helpers for staging
+MH_HD uint32_t m31_reduce64(uint64_t v)     // v < 2^64 -> canonical residue
+{
+    v = (v & P31) + (v >> 31);              // < 2^31 + 2^33
+    v = (v & P31) + (v >> 31);              // < 2^31 + 8
+    uint32_t r = (uint32_t)v;
+    return r >= P31 ? r - P31 : r;
+}
+MH_HD uint32_t m31_mul(uint32_t a, uint32_t b) { return m31_reduce64((uint64_t)a * b); }
+
+// centre a canonical residue into [-(p-1)/2, (p-1)/2]
+MH_HD int32_t m31_centre(uint32_t r) { return r > (P31 >> 1) ? (int32_t)(r - P31) : (int32_t)r; }
+
+// x = S + y in [1, 2^32) congruent to X + 1  ->  canonical X mod p
+MH_HD uint32_t m31_finish(uint32_t x) { return (x + (x >> 31) - 1u) & P31; }
+
+// ---------------------------------------------------------------- 2U, p = 2^31 - 1
+struct Fn2U31 {
+    uint32_t c1;     // linear coefficient
+    uint64_t add;    // 2 (c0 + 1)
+};
+MH_HD Fn2U31 prep_2u31(uint64_t c0, uint64_t c1)
+{
+    Fn2U31 f;
+    f.c1 = (uint32_t)c1;
+    f.add = 2 * c0 + 2;
+    return f;
+}
+MH_HD uint32_t stage_2u31(uint32_t t) { return t << 1; }      // t < D < 2^31
+
+// x = S + y for the 2U polynomial
+MH_HD uint32_t fold_2u31(const Fn2U31& f, uint32_t t2)
+{
+    // 2W = c1 (2t) + 2 (c0 + 1) < 2^63;  hi = W >> 31 < 2^31,  lo = 2 (W mod 2^31)
+    uint64_t w2 = (uint64_t)f.c1 * t2 + f.add;
+    return (uint32_t)(w2 >> 32) + ((uint32_t)w2 >> 1);
+}
+
+template <bool POW2>
+MH_HD uint32_t hash_2u31(const Fn2U31& f, uint32_t t2, const ModD& md)
+{
+    return reduce_mod_d<POW2>(m31_finish(fold_2u31(f, t2)), md);
+}
+
+// Power-of-two D = mask + 1: the complement  mask - h(t)  of the hashed location.
+// With x in [1, 2^32) congruent to X + 1 and c = x >> 31 the location is
+// (x + c - 1) & mask, so its complement is (-(x + c)) & mask = (s - x) & mask with
+// s = -c the arithmetic shift of x: three half-cost instructions, no "- 1".
+// Keeping the running MAXIMUM of complements and taking mask - max at the end
+// gives the minimum location.
+MH_HD uint32_t m31_complement(uint32_t x, uint32_t mask)
+{
+    uint32_t s = (uint32_t)((int32_t)x >> 31);
+    return (s - x) & mask;
+}
+MH_HD uint32_t hash_compl_2u31(const Fn2U31& f, uint32_t t2, uint32_t mask)
+{
+    return m31_complement(fold_2u31(f, t2), mask);
+}
+
+// ---------------------------------------------------------------- 4U, p = 2^31 - 1
+// K31 p is added to the constant term so that the centred sum stays positive:
+// three products of magnitude at most ((p-1)/2)^2 need K31 p >= 3 ((p-1)/2)^2.
+constexpr uint64_t H31 = (uint64_t)(P31 >> 1);                               // (p-1)/2 = 2^30 - 1
+constexpr uint64_t K31 = (3 * H31 * H31 + (uint64_t)P31 - 1) / (uint64_t)P31;
+
+struct Fn4U31 {
+    int32_t c1, c2, c3;   // centred coefficients of t, t^2, t^3
+    uint64_t add;         // 2 (c0 + 1 + K31 p)
+};
+MH_HD Fn4U31 prep_4u31(uint64_t c0, uint64_t c1, uint64_t c2, uint64_t c3)
+{
+    Fn4U31 f;
+    f.c1 = m31_centre((uint32_t)c1);
+    f.c2 = m31_centre((uint32_t)c2);
+    f.c3 = m31_centre((uint32_t)c3);
+    f.add = 2 * (c0 + 1 + K31 * (uint64_t)P31);
+    return f;
+}
+struct Pow4U31 { int32_t t1, t2, t3; };   // 2 * centred (t, t^2 mod p, t^3 mod p)
+MH_HD Pow4U31 stage_4u31(uint32_t t)      // t < D < p
+{
+    uint32_t s = m31_mul(t, t);
+    uint32_t c = m31_mul(s, t);
+    Pow4U31 w;
+    w.t1 = 2 * m31_centre(t);
+    w.t2 = 2 * m31_centre(s);
+    w.t3 = 2 * m31_centre(c);
+    return w;
+}
+
+MH_HD uint32_t fold_4u31(const Fn4U31& f, const Pow4U31& w)
+{
+    // 2W' = add + c1 t1 + c2 t2 + c3 t3, exact in two's complement, 0 < 2W' < 0.75 * 2^64
+    // (each product fits int64; the running sum is kept unsigned so that wrapping is defined)
+    uint64_t w2 = f.add;
+    w2 += (uint64_t)((int64_t)f.c1 * w.t1);
+    w2 += (uint64_t)((int64_t)f.c2 * w.t2);
+    w2 += (uint64_t)((int64_t)f.c3 * w.t3);
+    uint32_t hi = (uint32_t)(w2 >> 32), lo = (uint32_t)w2;
+    // W' = 2^62 s1 + 2^31 s0 + y  ==  s1 + s0 + y  (mod p);  at most 2^32 - 2
+    return (lo >> 1) + (hi & P31) + (hi >> 31);
+}
+
+template <bool POW2>
+MH_HD uint32_t hash_4u31(const Fn4U31& f, const Pow4U31& w, const ModD& md)
+{
+    return reduce_mod_d<POW2>(m31_finish(fold_4u31(f, w)), md);
+}
+MH_HD uint32_t hash_compl_4u31(const Fn4U31& f, const Pow4U31& w, uint32_t mask)
+{
+    return m31_complement(fold_4u31(f, w), mask);
+}
+
+// ---------------------------------------------------------------- 2U, p = 2^61 - 1
+// W = c1 t + c0 + 1 with c1 = 2^32 e1 + e0, t < 2^31:
+//   L = e0 t + (c0 + 1)            < 2^63 + 2^61
+//   H = e1 t + (L >> 32)           < 2^62
+//   W = 2^32 H + (L mod 2^32) = 2^61 (H >> 29) + [ (H mod 2^29) : L mod 2^32 ]
+// and 2^61 = 1 (mod p), so x = y + (H >> 29) with y the 61-bit bracket; x lies in
+// [1, 2^61 + 2^33) and X mod p is x - 1 if bit 61 of x is clear, x - 2^61 otherwise.
+struct Fn2U61 {
+    uint32_t e0, e1;   // c1 = 2^32 e1 + e0
+    uint64_t add;      // c0 + 1
+};
+MH_HD Fn2U61 prep_2u61(uint64_t c0, uint64_t c1)
+{
+    Fn2U61 f;
+    f.e0 = (uint32_t)c1;
+    f.e1 = (uint32_t)(c1 >> 32);
+    f.add = c0 + 1;
+    return f;
+}
+
+// canonical residue (61 bits) for t < 2^31
+MH_HD uint64_t residue_2u61(const Fn2U61& f, uint32_t t)
+{
+    uint64_t L = (uint64_t)f.e0 * t + f.add;
+    uint64_t H = (uint64_t)f.e1 * t + (L >> 32);
+    uint64_t y = ((H & 0x1FFFFFFFull) << 32) | (L & 0xFFFFFFFFull);
+    uint64_t x = y + (H >> 29);
+    uint64_t c = x >> 61;
+    return (x + c - 1) & P61;
+}
+
+// low 32 bits of the canonical residue only (all that a power-of-two D <= 2^32 needs)
+MH_HD uint32_t residue_lo_2u61(const Fn2U61& f, uint32_t t)
+{
+    uint64_t L = (uint64_t)f.e0 * t + f.add;
+    uint64_t H = (uint64_t)f.e1 * t + (L >> 32);
+    uint32_t Hl = (uint32_t)H, Hh = (uint32_t)(H >> 32);
+    uint32_t s_lo = (Hl >> 29) | (Hh << 3);          // (H >> 29) mod 2^32
+    uint32_t s_hi = Hh >> 29;
+    uint32_t x_lo = (uint32_t)L + s_lo;
+    uint32_t carry = x_lo < s_lo ? 1u : 0u;
+    uint32_t x_hi = (Hl & 0x1FFFFFFFu) + s_hi + carry;
+    return x_lo + (x_hi >> 29) - 1u;
+}
+
+// canonical residue for any t < 2^32 (the slow path: D above 2^31 or not a power of two)
+MH_HD uint64_t residue_wide_2u61(const Fn2U61& f, uint32_t t)
+{
+    uint64_t L0 = (uint64_t)f.e0 * t;
+    uint64_t L = L0 + f.add;                               // may wrap once
+    uint64_t carry = L < L0 ? 1ull : 0ull;
+    uint64_t H = (uint64_t)f.e1 * t + (L >> 32) + (carry << 32);   // < 2^62
+    uint64_t y = ((H & 0x1FFFFFFFull) << 32) | (L & 0xFFFFFFFFull);
+    uint64_t x = y + (H >> 29);
+    uint64_t c = x >> 61;
+    return (x + c - 1) & P61;
+}
+
+// POW2 here also means D <= 2^31, so that t < 2^31
+template <bool POW2>
+MH_HD uint32_t hash_2u61(const Fn2U61& f, uint32_t t, const ModD& md, uint64_t D)
+{
+    if (POW2) return residue_lo_2u61(f, t) & md.mask;
+    return (uint32_t)(residue_wide_2u61(f, t) % D);
+}
+
+}  // namespace mh

@@ -1,0 +1,852 @@
+// b-bit minwise-hash signatures on MI355X (gfx950): kernels and the C ABI.
+//
+// One call of minhash_signatures enqueues, on the caller's stream:
+//
+//   mh_reset_kernel      clears the work-list header in the workspace
+//   mh_bin_rows_kernel   load balancer: reads row_ptr, emits one work item per
+//                        row, or one per CHUNK nonzeros for long rows (which
+//                        also get a slot of partial minima in the workspace)
+//   mh_fill_kernel       sets the partial minima of split rows to 0xFFFFFFFF
+//   mh_hash_kernel<..>   (hash families) or mh_perm_kernel<..> (permutation
+//                        table): the hot loop.  Persistent wavefronts take
+//                        (item, function-tile) units from an atomic ticket.
+//                        A wavefront stages 256 nonzeros at a time into LDS
+//                        with coalesced loads (pre-computing what depends on t
+//                        alone), then every lane evaluates its 8 hash functions
+//                        on each staged nonzero, read back as LDS broadcasts,
+//                        keeping 8 running minima in registers (Section 2, last
+//                        paragraph: map every nonzero t to h_j(t), keep the
+//                        minimum).  When k needs fewer than 64 lanes the spare
+//                        lanes take slices of the nonzeros and are merged by a
+//                        butterfly of cross-lane minima.  Whole rows are
+//                        truncated to b bits, packed and stored by the same
+//                        wavefront; chunks of split rows are merged with
+//                        atomicMin, which is exact because the minimum over a
+//                        union is the minimum of the parts.
+//   mh_finalize_kernel   packs and stores the split rows.
+//
+// Wavefronts never synchronise with each other inside a kernel: each has its
+// own LDS region and its own work units, so there is no barrier anywhere.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include "minhash.h"
+#include "mh_arith.h"
+
+namespace {
+
+using namespace mh;
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int WAVE = 64;
+constexpr int WAVES_PER_BLOCK = 4;
+constexpr int BLOCK = WAVE * WAVES_PER_BLOCK;
+constexpr int TILE = 256;              // nonzeros staged per wavefront per step (4 per lane)
+constexpr int HASH_FPL = 8;            // hash functions per lane
+constexpr int HASH_FTILE = WAVE * HASH_FPL;   // 512 functions per wavefront pass
+constexpr int PERM_FPL = 4;            // permutations per lane (one 16-byte load)
+constexpr int PERM_FTILE = WAVE * PERM_FPL;   // 256
+constexpr int MAX_FTILE = HASH_FTILE;
+constexpr uint32_t CHUNK = 8192;       // rows longer than this are split into chunks of this many nonzeros
+constexpr uint32_t NO_SLOT = 0xFFFFFFFFu;
+
+struct WorkHeader {                    // first 256 bytes of the workspace
+    uint32_t n_items;
+    uint32_t n_split;
+    uint32_t ticket;
+    uint32_t status;                   // bit 0: bad row_ptr, bit 1: index >= D, bit 2: work list overflow
+    uint32_t pad[60];
+};
+static_assert(sizeof(WorkHeader) == 256, "header size");
+
+struct Item {                          // one unit of row work
+    int64_t begin;                     // offset of the first nonzero in col_idx
+    uint32_t len;                      // number of nonzeros (<= CHUNK unless the row is whole)
+    uint32_t row;
+    uint32_t slot;                     // NO_SLOT for a whole row, else index of the split row's partial minima
+    uint32_t pad;
+};
+static_assert(sizeof(Item) == 24 || sizeof(Item) == 32, "item size");
+
+struct Layout {                        // host and device agree on the workspace layout through this
+    size_t items_off, split_rows_off, scratch_off, total;
+    uint64_t cap_items, cap_split;
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k)
+{
+    Layout L;
+    L.cap_items = (uint64_t)n_rows + (uint64_t)nnz_ub / CHUNK + 1;
+    uint64_t by_len = (uint64_t)nnz_ub / CHUNK;
+    L.cap_split = by_len < (uint64_t)n_rows ? by_len : (uint64_t)n_rows;
+    L.items_off = sizeof(WorkHeader);
+    L.split_rows_off = align_up(L.items_off + L.cap_items * sizeof(Item), 256);
+    L.scratch_off = align_up(L.split_rows_off + L.cap_split * sizeof(uint32_t), 256);
+    L.total = align_up(L.scratch_off + L.cap_split * (size_t)k * sizeof(uint32_t), 256);
+    return L;
+}
+
+struct KArgs {
+    const int64_t* row_ptr;
+    const uint32_t* col_idx;
+    const void* params;
+    uint8_t* out;
+    int64_t out_stride;
+    int64_t perm_ld;
+    WorkHeader* hdr;
+    Item* items;
+    uint32_t* split_rows;
+    uint32_t* scratch;
+    uint64_t D;
+    uint64_t cap_items, cap_split;
+    ModD md;
+    int64_t n_rows;
+    int32_t k, b;
+    int32_t n_ftiles;
+    int32_t log2_fl;                   // lanes covering one function tile = 1 << log2_fl
+    int32_t sig_bytes;
+    uint32_t validate;
+};
+
+// ------------------------------------------------------------------ small helpers
+__device__ __forceinline__ uint32_t wave_bcast(uint32_t v, int src_lane)
+{
+    return (uint32_t)__shfl((int)v, src_lane, WAVE);
+}
+__device__ __forceinline__ uint32_t first_lane_value(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
+}
+// keeps a wave-uniform value in a vector register: integer instructions whose
+// operands all sit in vector registers issue at twice the rate of those that
+// read a scalar register
+__device__ __forceinline__ uint32_t in_vgpr(uint32_t v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
+}
+__device__ __forceinline__ void wave_sync_lds()
+{
+    // orders this wavefront's LDS writes before its later LDS reads (the hardware
+    // executes a wavefront's LDS instructions in order; this stops the compiler)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+// three-operand extrema: one instruction folds two new values into the running one
+__device__ __forceinline__ uint32_t umin3(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t d;
+    asm("v_min3_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+__device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c)
+{
+    uint32_t d;
+    asm("v_max3_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+
+// ------------------------------------------------------------------ reset / bin / fill
+__global__ void mh_reset_kernel(WorkHeader* hdr)
+{
+    if (threadIdx.x < 64) reinterpret_cast<uint32_t*>(hdr)[threadIdx.x] = 0;
+}
+
+// One thread per row.  Wave-level prefix sums make one atomic per wavefront.
+__global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int64_t row = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+    uint32_t n_it = 0, is_split = 0;
+    int64_t begin = 0, nnz = 0;
+    if (row < a.n_rows) {
+        begin = a.row_ptr[row];
+        nnz = a.row_ptr[row + 1] - begin;
+        if (nnz < 0) {                 // decreasing row_ptr: treat as empty, flag it
+            if (a.validate) atomicOr(&a.hdr->status, 1u);
+            nnz = 0;
+        }
+        is_split = nnz > (int64_t)CHUNK ? 1u : 0u;
+        n_it = is_split ? (uint32_t)((nnz + CHUNK - 1) / CHUNK) : 1u;
+    }
+    // inclusive scans over the wavefront
+    uint32_t inc_it = n_it, inc_sp = is_split;
+    for (int d = 1; d < WAVE; d <<= 1) {
+        uint32_t v1 = (uint32_t)__shfl_up((int)inc_it, d, WAVE);
+        uint32_t v2 = (uint32_t)__shfl_up((int)inc_sp, d, WAVE);
+        if (lane >= d) { inc_it += v1; inc_sp += v2; }
+    }
+    uint32_t tot_it = wave_bcast(inc_it, WAVE - 1), tot_sp = wave_bcast(inc_sp, WAVE - 1);
+    uint32_t base_it = 0, base_sp = 0;
+    if (lane == WAVE - 1) {
+        if (tot_it) base_it = atomicAdd(&a.hdr->n_items, tot_it);
+        if (tot_sp) base_sp = atomicAdd(&a.hdr->n_split, tot_sp);
+    }
+    base_it = wave_bcast(base_it, WAVE - 1);
+    base_sp = wave_bcast(base_sp, WAVE - 1);
+    if (row >= a.n_rows) return;
+    uint64_t first = (uint64_t)base_it + inc_it - n_it;
+    uint32_t slot = NO_SLOT;
+    if (is_split) {
+        uint64_t s = (uint64_t)base_sp + inc_sp - 1;
+        if (s >= a.cap_split) { atomicOr(&a.hdr->status, 4u); return; }
+        slot = (uint32_t)s;
+        a.split_rows[slot] = (uint32_t)row;
+    }
+    if (first + n_it > a.cap_items) { atomicOr(&a.hdr->status, 4u); return; }
+    for (uint32_t c = 0; c < n_it; ++c) {
+        Item it;
+        it.begin = begin + (int64_t)c * CHUNK;
+        int64_t rest = nnz - (int64_t)c * CHUNK;
+        it.len = is_split ? (uint32_t)(rest < (int64_t)CHUNK ? rest : (int64_t)CHUNK) : (uint32_t)nnz;
+        it.row = (uint32_t)row;
+        it.slot = slot;
+        it.pad = 0;
+        a.items[first + c] = it;
+    }
+}
+
+__global__ __launch_bounds__(BLOCK) void mh_fill_kernel(KArgs a)
+{
+    const uint32_t n_split = a.hdr->n_split < a.cap_split ? a.hdr->n_split : (uint32_t)a.cap_split;
+    const uint64_t total = (uint64_t)n_split * (uint64_t)a.k;
+    for (uint64_t i = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; i < total; i += (uint64_t)gridDim.x * BLOCK)
+        a.scratch[i] = EMPTY_MIN;
+}
+
+// ------------------------------------------------------------------ truncate + pack + store (one wavefront)
+// mins[0 .. nf) are the full minima of functions j0 .. j0+nf of `row`; j0 is a
+// multiple of ftile, so the bits start at a byte offset that is a multiple of 4.
+// Value j takes bits [j b, (j+1) b) of the row's little-endian bit string
+// (Section 1.1: only the lowest b bits of each hashed value are stored).
+__device__ __forceinline__ void wave_pack_store(const KArgs& a, const uint32_t* mins, uint32_t row, int j0, int nf,
+                                                bool last_tile, int lane)
+{
+    const int b = a.b;
+    const uint32_t maskb = b >= 32 ? 0xFFFFFFFFu : ((1u << b) - 1u);
+    uint8_t* dst = a.out + (int64_t)row * a.out_stride;
+    const int64_t byte0 = ((int64_t)j0 * b) >> 3;
+    const int nbytes = (int)((((int64_t)nf * b) + 7) >> 3);
+    const int ndw = (nbytes + 3) >> 2;
+    uint8_t* base = dst + byte0;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(base) & 3u) == 0);
+    for (int w = lane; w < ndw; w += WAVE) {
+        const int bit_lo = w * 32;
+        int j = bit_lo / b;
+        uint32_t word = 0;
+        for (; j < nf && j * b < bit_lo + 32; ++j) {
+            uint32_t v = mins[j] & maskb;
+            int pos = j * b - bit_lo;
+            word |= pos >= 0 ? (v << pos) : (v >> (-pos));
+        }
+        if (aligned && 4 * w + 3 < nbytes) {
+            *reinterpret_cast<uint32_t*>(base + 4 * w) = word;
+        } else {
+            for (int q = 0; q < 4; ++q)
+                if (4 * w + q < nbytes) base[4 * w + q] = (uint8_t)(word >> (8 * q));
+        }
+    }
+    if (last_tile) {                   // pad bytes up to the row pitch are zero
+        for (int64_t q = a.sig_bytes + lane; q < a.out_stride; q += WAVE) dst[q] = 0;
+    }
+}
+
+// ------------------------------------------------------------------ hash-family policies
+// A policy evaluates one function on one staged nonzero and returns a value that
+// the kernel folds into a running extremum: the hashed location itself (running
+// minimum), or, when TRACK_MAX, its complement mask - h(t) (running maximum),
+// which saves one instruction per evaluation for power-of-two D.
+template <bool POW2>
+struct Pol2U31 {
+    static constexpr int NW = 1;
+    static constexpr bool TRACK_MAX = POW2;
+    using Fn = Fn2U31;
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    {
+        return valid ? prep_2u31(c[0], c[1]) : prep_2u31(0, 0);
+    }
+    static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = stage_2u31(t); }
+    static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t)
+    {
+        if (POW2) return hash_compl_2u31(f, w[0], md.mask);
+        return hash_2u31<false>(f, w[0], md);
+    }
+    static constexpr int DEG = 2;
+};
+
+template <bool POW2>
+struct Pol4U31 {
+    static constexpr int NW = 3;
+    static constexpr bool TRACK_MAX = POW2;
+    using Fn = Fn4U31;
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    {
+        return valid ? prep_4u31(c[0], c[1], c[2], c[3]) : prep_4u31(0, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w)
+    {
+        Pow4U31 p = stage_4u31(t);
+        w[0] = (uint32_t)p.t1; w[1] = (uint32_t)p.t2; w[2] = (uint32_t)p.t3;
+    }
+    static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t)
+    {
+        Pow4U31 p;
+        p.t1 = (int32_t)w[0]; p.t2 = (int32_t)w[1]; p.t3 = (int32_t)w[2];
+        if (POW2) return hash_compl_4u31(f, p, md.mask);
+        return hash_4u31<false>(f, p, md);
+    }
+    static constexpr int DEG = 4;
+};
+
+template <bool POW2>
+struct Pol2U61 {
+    static constexpr int NW = 1;
+    static constexpr bool TRACK_MAX = false;
+    using Fn = Fn2U61;
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    {
+        return valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
+    }
+    static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
+    static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t D)
+    {
+        return hash_2u61<POW2>(f, w[0], md, D);
+    }
+    static constexpr int DEG = 2;
+};
+
+// ------------------------------------------------------------------ staging
+// Loads up to TILE nonzeros of [begin+off, begin+len) into 4 registers per lane
+// (element lane + 64 q), coalesced.  Slots past the end take `pad`, an element of
+// the same row: the minimum is idempotent, so duplicates change nothing.
+__device__ __forceinline__ void load_tile(const uint32_t* col, int64_t begin, uint32_t len, uint32_t off, uint32_t pad,
+                                          int lane, uint32_t (&r)[4])
+{
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t e = off + (uint32_t)lane + (uint32_t)(WAVE * q);
+        r[q] = e < len ? __builtin_nontemporal_load(col + begin + e) : pad;
+    }
+}
+
+// ------------------------------------------------------------------ the hash kernel
+template <class Pol>
+__global__ __launch_bounds__(BLOCK) void mh_hash_kernel(KArgs a)
+{
+    __shared__ uint32_t s_tile[WAVES_PER_BLOCK][Pol::NW][TILE];
+    __shared__ uint32_t s_mins[WAVES_PER_BLOCK][HASH_FTILE];
+
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wave = threadIdx.x >> 6;
+    uint32_t(*tile)[TILE] = s_tile[wave];
+    uint32_t* mins = s_mins[wave];
+
+    const int fl_lanes = 1 << a.log2_fl;            // lanes that cover one function tile
+    const int n_slices = WAVE >> a.log2_fl;         // the other lane bits take slices of the nonzeros
+    const int fl = lane & (fl_lanes - 1);
+    const int slice = lane >> a.log2_fl;
+
+    const uint32_t n_items = a.hdr->n_items < a.cap_items ? a.hdr->n_items : (uint32_t)a.cap_items;
+    const uint64_t n_units = (uint64_t)n_items * (uint64_t)a.n_ftiles;
+
+    ModD md = a.md;
+    md.mask = in_vgpr(md.mask);
+    md.D = in_vgpr(md.D);
+    md.M = in_vgpr(md.M);
+
+    typename Pol::Fn fn[HASH_FPL];
+    int cur_ftile = -1;
+
+    for (;;) {
+        uint32_t ticket = 0;
+        if (lane == 0) ticket = atomicAdd(&a.hdr->ticket, 1u);
+        ticket = first_lane_value(ticket);
+        if ((uint64_t)ticket >= n_units) break;      // every wavefront reaches this: tickets only grow
+        const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
+        const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
+        const int j_base = ftile * HASH_FTILE + fl * HASH_FPL;
+        if (ftile != cur_ftile) {
+            const uint64_t* coeffs = static_cast<const uint64_t*>(a.params);
+#pragma unroll
+            for (int r = 0; r < HASH_FPL; ++r) {
+                int j = j_base + r;
+                bool valid = j < a.k;
+                fn[r] = Pol::load(coeffs + (size_t)(valid ? j : 0) * Pol::DEG, valid);
+            }
+            cur_ftile = ftile;
+        }
+        const Item it = a.items[item_idx];
+        const int64_t begin = it.begin;
+        const uint32_t len = it.len;
+
+        uint32_t m[HASH_FPL];
+#pragma unroll
+        for (int r = 0; r < HASH_FPL; ++r) m[r] = Pol::TRACK_MAX ? 0u : EMPTY_MIN;
+
+        if (len > 0) {
+            uint32_t pad = a.col_idx[begin];
+            uint32_t regs[4];
+            load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
+            for (uint32_t off = 0; off < len; off += TILE) {
+                // stage: pre-compute what depends on t alone, one nonzero per lane and register
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint32_t t = regs[q];
+                    if (a.validate && (uint64_t)t >= a.D) {
+                        atomicOr(&a.hdr->status, 2u);
+                        t = 0;
+                    }
+                    uint32_t w[Pol::NW];
+                    Pol::stage(t, w);
+#pragma unroll
+                    for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
+                }
+                wave_sync_lds();
+                if (off + TILE < len) load_tile(a.col_idx, begin, len, off + TILE, pad, lane, regs);
+
+                const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
+                const int n_steps = (int)((in_tile + 4u * n_slices - 1u) / (4u * n_slices));
+                for (int s = 0; s < n_steps; ++s) {
+                    const int e = 4 * (s * n_slices + slice);
+                    uint32_t w[4][Pol::NW];
+#pragma unroll
+                    for (int i = 0; i < Pol::NW; ++i) {
+                        uint4 v = *reinterpret_cast<const uint4*>(&tile[i][e]);
+                        w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; u += 2) {
+#pragma unroll
+                        for (int r = 0; r < HASH_FPL; ++r) {
+                            uint32_t k0 = Pol::key(fn[r], w[u], md, a.D);
+                            uint32_t k1 = Pol::key(fn[r], w[u + 1], md, a.D);
+                            m[r] = Pol::TRACK_MAX ? umax3(m[r], k0, k1) : umin3(m[r], k0, k1);
+                        }
+                    }
+                }
+                wave_sync_lds();
+            }
+            if (Pol::TRACK_MAX) {      // back from complements to the minimum location
+#pragma unroll
+                for (int r = 0; r < HASH_FPL; ++r) m[r] = md.mask - m[r];
+            }
+        } else if (Pol::TRACK_MAX) {
+#pragma unroll
+            for (int r = 0; r < HASH_FPL; ++r) m[r] = EMPTY_MIN;
+        }
+        // merge the slices of nonzeros (lanes that share fl)
+        for (int d = fl_lanes; d < WAVE; d <<= 1) {
+#pragma unroll
+            for (int r = 0; r < HASH_FPL; ++r) {
+                uint32_t o = (uint32_t)__shfl_xor((int)m[r], d, WAVE);
+                m[r] = o < m[r] ? o : m[r];
+            }
+        }
+        const int nf_tile = a.k - ftile * HASH_FTILE < HASH_FTILE ? a.k - ftile * HASH_FTILE : HASH_FTILE;
+        if (it.slot == NO_SLOT) {
+            if (slice == 0) {
+#pragma unroll
+                for (int r = 0; r < HASH_FPL; ++r) mins[fl * HASH_FPL + r] = m[r];
+            }
+            wave_sync_lds();
+            wave_pack_store(a, mins, it.row, ftile * HASH_FTILE, nf_tile, ftile == a.n_ftiles - 1, lane);
+            wave_sync_lds();
+        } else if (slice == 0) {
+            uint32_t* part = a.scratch + (size_t)it.slot * (size_t)a.k;
+#pragma unroll
+            for (int r = 0; r < HASH_FPL; ++r)
+                if (j_base + r < a.k) atomicMin(part + j_base + r, m[r]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ the permutation-table kernel
+// table[t][j] = pi_j(t), index-major (Section 1.5: a permutation matrix of size
+// D x k): the k values of one nonzero are contiguous, so each nonzero costs one
+// coalesced read of 4k bytes.  VEC4: lane l reads entries 4l..4l+3 with one
+// 16-byte load (needs perm_ld % 4 == 0 and a 16-byte aligned table); otherwise
+// lane l reads entries l, l+64, l+128, l+192.
+template <bool VEC4>
+__global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
+{
+    __shared__ uint32_t s_tile[WAVES_PER_BLOCK][TILE];
+    __shared__ uint32_t s_mins[WAVES_PER_BLOCK][PERM_FTILE];
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wave = threadIdx.x >> 6;
+    uint32_t* tile = s_tile[wave];
+    uint32_t* mins = s_mins[wave];
+    const uint32_t* table = static_cast<const uint32_t*>(a.params);
+
+    const uint32_t n_items = a.hdr->n_items < a.cap_items ? a.hdr->n_items : (uint32_t)a.cap_items;
+    const uint64_t n_units = (uint64_t)n_items * (uint64_t)a.n_ftiles;
+    constexpr int U = 8;               // nonzeros in flight per lane
+
+    for (;;) {
+        uint32_t ticket = 0;
+        if (lane == 0) ticket = atomicAdd(&a.hdr->ticket, 1u);
+        ticket = first_lane_value(ticket);
+        if ((uint64_t)ticket >= n_units) break;
+        const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
+        const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
+        const Item it = a.items[item_idx];
+        const int64_t begin = it.begin;
+        const uint32_t len = it.len;
+        const int j0 = ftile * PERM_FTILE;
+        const int nf_tile = a.k - j0 < PERM_FTILE ? a.k - j0 : PERM_FTILE;
+
+        // function slots of this lane and whether they exist
+        int jl[PERM_FPL];
+        bool ok[PERM_FPL];
+#pragma unroll
+        for (int r = 0; r < PERM_FPL; ++r) {
+            jl[r] = VEC4 ? lane * PERM_FPL + r : lane + WAVE * r;
+            ok[r] = jl[r] < nf_tile;
+        }
+        uint32_t m[PERM_FPL];
+#pragma unroll
+        for (int r = 0; r < PERM_FPL; ++r) m[r] = EMPTY_MIN;
+
+        if (len > 0) {
+            uint32_t pad = a.col_idx[begin];
+            uint32_t regs[4];
+            load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
+            for (uint32_t off = 0; off < len; off += TILE) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    uint32_t t = regs[q];
+                    if (a.validate && (uint64_t)t >= a.D) {
+                        atomicOr(&a.hdr->status, 2u);
+                        t = 0;
+                    }
+                    tile[lane + WAVE * q] = t;
+                }
+                wave_sync_lds();
+                if (off + TILE < len) load_tile(a.col_idx, begin, len, off + TILE, pad, lane, regs);
+                const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
+                const int n_steps = (int)((in_tile + U - 1) / U);
+                for (int s = 0; s < n_steps; ++s) {
+                    uint32_t tt[U];
+#pragma unroll
+                    for (int u = 0; u < U; u += 4) {
+                        uint4 v = *reinterpret_cast<const uint4*>(&tile[s * U + u]);
+                        tt[u] = v.x; tt[u + 1] = v.y; tt[u + 2] = v.z; tt[u + 3] = v.w;
+                    }
+                    if (VEC4) {
+                        u32x4 g[U];
+                        const bool lane_ok = lane * PERM_FPL < nf_tile;
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const uint32_t t = first_lane_value(tt[u]);
+                            const uint32_t* rowp = table + (size_t)t * (size_t)a.perm_ld + j0;
+                            const u32x4 none = {EMPTY_MIN, EMPTY_MIN, EMPTY_MIN, EMPTY_MIN};
+                            g[u] = lane_ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(rowp) + lane) : none;
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            m[0] = g[u].x < m[0] ? g[u].x : m[0];
+                            m[1] = g[u].y < m[1] ? g[u].y : m[1];
+                            m[2] = g[u].z < m[2] ? g[u].z : m[2];
+                            m[3] = g[u].w < m[3] ? g[u].w : m[3];
+                        }
+                    } else {
+                        uint32_t g[U][PERM_FPL];
+#pragma unroll
+                        for (int u = 0; u < U; ++u) {
+                            const uint32_t t = first_lane_value(tt[u]);
+                            const uint32_t* rowp = table + (size_t)t * (size_t)a.perm_ld + j0;
+#pragma unroll
+                            for (int r = 0; r < PERM_FPL; ++r)
+                                g[u][r] = ok[r] ? __builtin_nontemporal_load(rowp + jl[r]) : EMPTY_MIN;
+                        }
+#pragma unroll
+                        for (int u = 0; u < U; ++u)
+#pragma unroll
+                            for (int r = 0; r < PERM_FPL; ++r) m[r] = g[u][r] < m[r] ? g[u][r] : m[r];
+                    }
+                }
+                wave_sync_lds();
+            }
+        }
+        if (it.slot == NO_SLOT) {
+#pragma unroll
+            for (int r = 0; r < PERM_FPL; ++r) mins[jl[r]] = m[r];
+            wave_sync_lds();
+            wave_pack_store(a, mins, it.row, j0, nf_tile, ftile == a.n_ftiles - 1, lane);
+            wave_sync_lds();
+        } else {
+            uint32_t* part = a.scratch + (size_t)it.slot * (size_t)a.k + j0;
+#pragma unroll
+            for (int r = 0; r < PERM_FPL; ++r)
+                if (ok[r]) atomicMin(part + jl[r], m[r]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------ finalize split rows
+__global__ __launch_bounds__(BLOCK) void mh_finalize_kernel(KArgs a, int ftile_size)
+{
+    __shared__ uint32_t s_mins[WAVES_PER_BLOCK][MAX_FTILE];
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int wave = threadIdx.x >> 6;
+    uint32_t* mins = s_mins[wave];
+    const uint32_t n_split = a.hdr->n_split < a.cap_split ? a.hdr->n_split : (uint32_t)a.cap_split;
+    const uint64_t n_units = (uint64_t)n_split * (uint64_t)a.n_ftiles;
+    const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_BLOCK;
+    for (uint64_t u = (uint64_t)blockIdx.x * WAVES_PER_BLOCK + wave; u < n_units; u += n_waves) {
+        const uint32_t slot = (uint32_t)(u / (uint64_t)a.n_ftiles);
+        const int ftile = (int)(u - (uint64_t)slot * (uint64_t)a.n_ftiles);
+        const int j0 = ftile * ftile_size;
+        const int nf = a.k - j0 < ftile_size ? a.k - j0 : ftile_size;
+        const uint32_t* part = a.scratch + (size_t)slot * (size_t)a.k + j0;
+        for (int j = lane; j < nf; j += WAVE) mins[j] = part[j];
+        wave_sync_lds();
+        wave_pack_store(a, mins, a.split_rows[slot], j0, nf, ftile == a.n_ftiles - 1, lane);
+        wave_sync_lds();
+    }
+}
+
+// ------------------------------------------------------------------ host side
+thread_local char g_hip_error[256] = "";
+
+int hip_fail(hipError_t e, const char* what)
+{
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+    return MINHASH_ERR_HIP;
+}
+
+bool family_prime(int32_t family, uint64_t* p, int* deg)
+{
+    switch (family) {
+    case MINHASH_2U_M31: *p = P31; *deg = 2; return true;
+    case MINHASH_4U_M31: *p = P31; *deg = 4; return true;
+    case MINHASH_2U_M61: *p = P61; *deg = 2; return true;
+    case MINHASH_4U_M61: *p = P61; *deg = 4; return true;
+    default: return false;
+    }
+}
+
+int validate_shape(int64_t n_rows, int64_t nnz_ub, int32_t k, int32_t family)
+{
+    if (n_rows < 0 || n_rows >= (1ll << 31) || nnz_ub < 0) return MINHASH_ERR_ARG;
+    if (family != MINHASH_PERM) {
+        uint64_t p; int deg;
+        if (!family_prime(family, &p, &deg) || family == MINHASH_4U_M61) return MINHASH_ERR_FAMILY;
+    }
+    if (k < 1 || k > MINHASH_MAX_K) return MINHASH_ERR_KB;
+    return MINHASH_OK;
+}
+
+int g_num_cus = 0;
+int device_cus()
+{
+    if (g_num_cus == 0) {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 256;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+        g_num_cus = cus;
+    }
+    return g_num_cus;
+}
+
+template <class Pol>
+void launch_hash(const KArgs& a, int blocks, hipStream_t s)
+{
+    hipLaunchKernelGGL(mh_hash_kernel<Pol>, dim3(blocks), dim3(BLOCK), 0, s, a);
+}
+
+int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_t D, int32_t k, int32_t b,
+        int32_t family, const void* params, int64_t perm_ld, uint8_t* out, int64_t out_stride, void* workspace,
+        size_t workspace_bytes, void* stream, uint32_t flags, float* kernel_ms, bool profiled)
+{
+    if (kernel_ms) *kernel_ms = 0.0f;
+    // ---- everything that can be rejected without touching the GPU
+    int rc = validate_shape(n_rows, 0, k, family);
+    if (rc != MINHASH_OK) return rc;
+    if (b < 1 || b > 32) return MINHASH_ERR_KB;
+    if (D < 1 || D > (1ull << 32)) return MINHASH_ERR_D;
+    if (family != MINHASH_PERM) {
+        uint64_t p; int deg;
+        family_prime(family, &p, &deg);
+        if (D >= p) return MINHASH_ERR_D;
+        if (perm_ld != 0) return MINHASH_ERR_STRIDE;
+    } else if (perm_ld < k) {
+        return MINHASH_ERR_STRIDE;
+    }
+    const int64_t sig_bytes = ((int64_t)k * b + 7) / 8;
+    if (out_stride < sig_bytes) return MINHASH_ERR_STRIDE;
+    if (flags & ~MINHASH_FLAG_VALIDATE) return MINHASH_ERR_ARG;
+    if (n_rows == 0) return MINHASH_OK;
+    if (!row_ptr || !params || !out) return MINHASH_ERR_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % MINHASH_WORKSPACE_ALIGN) != 0) return MINHASH_ERR_WORKSPACE;
+    // The nonzero bound the workspace was sized for is not passed in; recover the
+    // largest bound this workspace can serve and let the device-side capacity
+    // checks refuse anything beyond it.
+    if (workspace_bytes < make_layout(n_rows, 0, k).total) return MINHASH_ERR_WORKSPACE;
+    int64_t lo = 0, hi = (int64_t)1 << 46;
+    while (lo < hi) {                              // largest nnz bound whose layout fits
+        int64_t mid = lo + (hi - lo + 1) / 2;
+        if (make_layout(n_rows, mid, k).total <= workspace_bytes) lo = mid; else hi = mid - 1;
+    }
+    const Layout L = make_layout(n_rows, lo, k);
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = static_cast<char*>(workspace);
+    KArgs a;
+    memset(&a, 0, sizeof(a));
+    a.row_ptr = row_ptr; a.col_idx = col_idx; a.params = params; a.out = out;
+    a.out_stride = out_stride; a.perm_ld = perm_ld;
+    a.hdr = reinterpret_cast<WorkHeader*>(ws);
+    a.items = reinterpret_cast<Item*>(ws + L.items_off);
+    a.split_rows = reinterpret_cast<uint32_t*>(ws + L.split_rows_off);
+    a.scratch = reinterpret_cast<uint32_t*>(ws + L.scratch_off);
+    a.D = D; a.cap_items = L.cap_items; a.cap_split = L.cap_split;
+    a.md = make_mod_d(D);
+    a.n_rows = n_rows; a.k = k; a.b = b;
+    a.sig_bytes = (int32_t)sig_bytes;
+    a.validate = (flags & MINHASH_FLAG_VALIDATE) ? 1u : 0u;
+
+    const bool perm = family == MINHASH_PERM;
+    const int ftile_size = perm ? PERM_FTILE : HASH_FTILE;
+    a.n_ftiles = (k + ftile_size - 1) / ftile_size;
+    if (!perm) {
+        int lanes_needed = ((k < HASH_FTILE ? k : HASH_FTILE) + HASH_FPL - 1) / HASH_FPL;
+        int lg = 0;
+        while ((1 << lg) < lanes_needed) ++lg;
+        a.log2_fl = lg;
+    } else {
+        a.log2_fl = 6;
+    }
+
+    if (L.cap_items * (uint64_t)a.n_ftiles >= (1ull << 32)) return MINHASH_ERR_ARG;   // tickets are 32-bit
+
+    const int cus = device_cus();
+    hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, s, a.hdr);
+    const int bin_blocks = (int)((n_rows + BLOCK - 1) / BLOCK);
+    hipLaunchKernelGGL(mh_bin_rows_kernel, dim3(bin_blocks), dim3(BLOCK), 0, s, a);
+    if (L.cap_split > 0) hipLaunchKernelGGL(mh_fill_kernel, dim3(cus * 2), dim3(BLOCK), 0, s, a);
+
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (profiled) {
+        hipError_t e = hipEventCreate(&e0);
+        if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+        e = hipEventCreate(&e1);
+        if (e != hipSuccess) { hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
+        hipEventRecord(e0, s);
+    }
+    const int main_blocks = cus * 4;               // 16 persistent wavefronts per CU
+    const bool pow2 = a.md.pow2 != 0;
+    switch (family) {
+    case MINHASH_2U_M31:
+        if (pow2) launch_hash<Pol2U31<true>>(a, main_blocks, s); else launch_hash<Pol2U31<false>>(a, main_blocks, s);
+        break;
+    case MINHASH_4U_M31:
+        if (pow2) launch_hash<Pol4U31<true>>(a, main_blocks, s); else launch_hash<Pol4U31<false>>(a, main_blocks, s);
+        break;
+    case MINHASH_2U_M61:
+        // the 32-bit-multiplicand arithmetic needs t < 2^31
+        if (pow2 && D <= (1ull << 31)) launch_hash<Pol2U61<true>>(a, main_blocks, s);
+        else launch_hash<Pol2U61<false>>(a, main_blocks, s);
+        break;
+    default: {
+        const bool vec4 = (perm_ld % 4 == 0) && (reinterpret_cast<uintptr_t>(params) % 16 == 0);
+        if (vec4) hipLaunchKernelGGL(mh_perm_kernel<true>, dim3(main_blocks), dim3(BLOCK), 0, s, a);
+        else hipLaunchKernelGGL(mh_perm_kernel<false>, dim3(main_blocks), dim3(BLOCK), 0, s, a);
+        break;
+    }
+    }
+    if (profiled) hipEventRecord(e1, s);
+    if (L.cap_split > 0) hipLaunchKernelGGL(mh_finalize_kernel, dim3(cus * 2), dim3(BLOCK), 0, s, a, ftile_size);
+
+    hipError_t le = hipGetLastError();
+    if (profiled) {
+        hipError_t se = hipStreamSynchronize(s);
+        float ms = 0.0f;
+        if (se == hipSuccess && le == hipSuccess) hipEventElapsedTime(&ms, e0, e1);
+        hipEventDestroy(e0);
+        hipEventDestroy(e1);
+        if (se != hipSuccess) return hip_fail(se, "hipStreamSynchronize");
+        if (kernel_ms) *kernel_ms = ms;
+    }
+    if (le != hipSuccess) return hip_fail(le, "kernel launch");
+    return MINHASH_OK;
+}
+
+}  // namespace
+
+// ==================================================================== C ABI
+extern "C" {
+
+int minhash_signatures(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_t D, int32_t k,
+                       int32_t b, int32_t family, const void* params, int64_t perm_ld, uint8_t* out,
+                       int64_t out_stride, void* workspace, size_t workspace_bytes, void* stream, uint32_t flags)
+{
+    return run(row_ptr, col_idx, n_rows, D, k, b, family, params, perm_ld, out, out_stride, workspace,
+               workspace_bytes, stream, flags, nullptr, false);
+}
+
+int minhash_signatures_profiled(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_t D,
+                                int32_t k, int32_t b, int32_t family, const void* params, int64_t perm_ld,
+                                uint8_t* out, int64_t out_stride, void* workspace, size_t workspace_bytes,
+                                void* stream, uint32_t flags, float* kernel_ms)
+{
+    return run(row_ptr, col_idx, n_rows, D, k, b, family, params, perm_ld, out, out_stride, workspace,
+               workspace_bytes, stream, flags, kernel_ms, true);
+}
+
+size_t minhash_workspace_bytes(int64_t n_rows, int64_t nnz_upper_bound, int32_t k, int32_t family)
+{
+    if (validate_shape(n_rows, nnz_upper_bound, k, family) != MINHASH_OK) return 0;
+    if (nnz_upper_bound > ((int64_t)1 << 46)) return 0;
+    return make_layout(n_rows, nnz_upper_bound, k).total;
+}
+
+int minhash_check_coeffs(const uint64_t* host_coeffs, int32_t k, int32_t family)
+{
+    uint64_t p; int deg;
+    if (!family_prime(family, &p, &deg)) return MINHASH_ERR_FAMILY;
+    if (k < 1 || k > MINHASH_MAX_K) return MINHASH_ERR_KB;
+    if (!host_coeffs) return MINHASH_ERR_ARG;
+    for (int64_t i = 0; i < (int64_t)k * deg; ++i)
+        if (host_coeffs[i] >= p) return MINHASH_ERR_COEFF;
+    return MINHASH_OK;
+}
+
+int minhash_status(const void* workspace, void* stream)
+{
+    if (!workspace) return MINHASH_ERR_ARG;
+    hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    WorkHeader h;
+    e = hipMemcpy(&h, workspace, sizeof(uint32_t) * 4, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
+    if (h.status & 4u) return MINHASH_ERR_WORKSPACE;
+    return h.status ? MINHASH_ERR_DATA : MINHASH_OK;
+}
+
+const char* minhash_error_string(int code)
+{
+    switch (code) {
+    case MINHASH_OK: return "ok";
+    case MINHASH_ERR_ARG: return "invalid argument";
+    case MINHASH_ERR_FAMILY: return "unknown or unimplemented hash family";
+    case MINHASH_ERR_D: return "D out of range (need 1 <= D <= 2^32 and D < p for hash families)";
+    case MINHASH_ERR_KB: return "k or b out of range";
+    case MINHASH_ERR_STRIDE: return "out_stride or perm_ld too small";
+    case MINHASH_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case MINHASH_ERR_HIP: return "HIP runtime error";
+    case MINHASH_ERR_COEFF: return "hash coefficient not below the prime";
+    case MINHASH_ERR_DATA: return "input data invalid (index >= D or decreasing row_ptr)";
+    default: return "unknown error code";
+    }
+}
+
+const char* minhash_last_hip_error(void) { return g_hip_error; }
+
+int minhash_version(void) { return MINHASH_VERSION; }
+
+}  // extern "C"

@@ -1,0 +1,183 @@
+"""Thin Python binding of the C-ABI library declared in ``include/minhash.h``.
+
+Argument marshalling only: every step of the path (row binning, hashing,
+minima, truncation, packing) runs in the HIP kernels of ``libminhash.so``.
+PyTorch is used for device memory and streams, nothing else.  There is no CPU
+fallback: if the shared library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+FAMILY_2U_M31 = 0
+FAMILY_4U_M31 = 1
+FAMILY_2U_M61 = 2
+FAMILY_4U_M61 = 3
+FAMILY_PERM = 4
+FLAG_VALIDATE = 1
+WORKSPACE_ALIGN = 256
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libminhash.so")
+
+EXPORTS = (
+    "minhash_signatures",
+    "minhash_signatures_profiled",
+    "minhash_workspace_bytes",
+    "minhash_check_coeffs",
+    "minhash_status",
+    "minhash_error_string",
+    "minhash_last_hip_error",
+    "minhash_version",
+)
+
+
+class MinhashError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__("minhash error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libminhash.so; raises if it has not been built (python -m paper_1205_2958_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -m paper_1205_2958_amd.build`; "
+                "there is no fallback implementation" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, u64, u32, sz = (ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint64,
+                                      ctypes.c_uint32, ctypes.c_size_t)
+        sig = [vp, vp, i64, u64, i32, i32, i32, vp, i64, vp, i64, vp, sz, vp, u32]
+        L.minhash_signatures.argtypes = sig
+        L.minhash_signatures.restype = ctypes.c_int
+        L.minhash_signatures_profiled.argtypes = sig + [ctypes.POINTER(ctypes.c_float)]
+        L.minhash_signatures_profiled.restype = ctypes.c_int
+        L.minhash_workspace_bytes.argtypes = [i64, i64, i32, i32]
+        L.minhash_workspace_bytes.restype = sz
+        L.minhash_check_coeffs.argtypes = [vp, i32, i32]
+        L.minhash_check_coeffs.restype = ctypes.c_int
+        L.minhash_status.argtypes = [vp, vp]
+        L.minhash_status.restype = ctypes.c_int
+        L.minhash_error_string.argtypes = [ctypes.c_int]
+        L.minhash_error_string.restype = ctypes.c_char_p
+        L.minhash_last_hip_error.argtypes = []
+        L.minhash_last_hip_error.restype = ctypes.c_char_p
+        L.minhash_version.argtypes = []
+        L.minhash_version.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def error_string(code: int) -> str:
+    return lib().minhash_error_string(code).decode()
+
+
+def _raise(code: int):
+    text = error_string(code)
+    if code == -7:
+        text += " (" + lib().minhash_last_hip_error().decode() + ")"
+    raise MinhashError(code, text)
+
+
+def version() -> int:
+    return lib().minhash_version()
+
+
+def workspace_bytes(n_rows: int, nnz_upper_bound: int, k: int, family: int) -> int:
+    return int(lib().minhash_workspace_bytes(n_rows, nnz_upper_bound, k, family))
+
+
+def check_coeffs(host_coeffs, family: int) -> None:
+    """host_coeffs: NumPy uint64 [k, degree] on the host."""
+    import numpy as np
+
+    c = np.ascontiguousarray(host_coeffs, dtype=np.uint64)
+    rc = lib().minhash_check_coeffs(c.ctypes.data_as(ctypes.c_void_p), c.shape[0], family)
+    if rc != 0:
+        _raise(rc)
+
+
+def alloc_workspace(n_rows: int, nnz_upper_bound: int, k: int, family: int, device) -> torch.Tensor:
+    nbytes = workspace_bytes(n_rows, nnz_upper_bound, k, family)
+    if nbytes == 0:
+        raise MinhashError(-1, "workspace size query rejected the arguments")
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    assert ws.data_ptr() % WORKSPACE_ALIGN == 0
+    return ws
+
+
+def _ptr(t: Optional[torch.Tensor]) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream_handle(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream
+
+
+def _marshal(row_ptr, col_idx, D, k, b, family, params, out, out_stride, perm_ld, workspace, stream):
+    if row_ptr.dtype != torch.int64 or not row_ptr.is_contiguous():
+        raise TypeError("row_ptr must be a contiguous int64 tensor")
+    if col_idx.element_size() != 4 or not col_idx.is_contiguous():
+        raise TypeError("col_idx must be a contiguous tensor of 4-byte unsigned indices (int32/uint32 storage)")
+    if not params.is_contiguous():
+        raise TypeError("params must be contiguous")
+    n_rows = row_ptr.numel() - 1
+    sig_bytes = (k * b + 7) // 8
+    if out_stride is None:
+        out_stride = out.shape[1] if out is not None else sig_bytes
+    if out is None:
+        out = torch.empty((n_rows, out_stride), dtype=torch.uint8, device=row_ptr.device)
+    if family == FAMILY_PERM:
+        if perm_ld is None:
+            perm_ld = params.shape[1]
+    else:
+        perm_ld = 0
+    if workspace is None:
+        workspace = alloc_workspace(n_rows, col_idx.numel(), k, family, row_ptr.device)
+    args = [_ptr(row_ptr), _ptr(col_idx), n_rows, D, k, b, family, _ptr(params), perm_ld, _ptr(out), out_stride,
+            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream_handle(stream)]
+    return args, out, workspace
+
+
+def minhash_signatures(row_ptr: torch.Tensor, col_idx: torch.Tensor, D: int, k: int, b: int, family: int,
+                       params: torch.Tensor, out: Optional[torch.Tensor] = None, out_stride: Optional[int] = None,
+                       perm_ld: Optional[int] = None, workspace: Optional[torch.Tensor] = None, stream=None,
+                       flags: int = 0) -> torch.Tensor:
+    """Enqueues the signature computation on ``stream`` (default: torch's current
+    stream) and returns the uint8 [n_rows, out_stride] output tensor.  Does not
+    synchronise.  All tensors live on the GPU; see include/minhash.h for layouts."""
+    args, out, workspace = _marshal(row_ptr, col_idx, D, k, b, family, params, out, out_stride, perm_ld, workspace,
+                                    stream)
+    rc = lib().minhash_signatures(*args, flags)
+    if rc != 0:
+        _raise(rc)
+    return out
+
+
+def minhash_signatures_profiled(row_ptr, col_idx, D, k, b, family, params, out=None, out_stride=None, perm_ld=None,
+                                workspace=None, stream=None, flags: int = 0) -> Tuple[torch.Tensor, float]:
+    """Same, but waits for the stream and also returns the duration (ms) of the
+    hash / gather kernel measured with HIP events on that stream."""
+    args, out, workspace = _marshal(row_ptr, col_idx, D, k, b, family, params, out, out_stride, perm_ld, workspace,
+                                    stream)
+    ms = ctypes.c_float(0.0)
+    rc = lib().minhash_signatures_profiled(*args, flags, ctypes.byref(ms))
+    if rc != 0:
+        _raise(rc)
+    return out, float(ms.value)
+
+
+def status(workspace: torch.Tensor, stream=None) -> int:
+    """Waits for the stream; 0, or the negative code of what VALIDATE found."""
+    return int(lib().minhash_status(_ptr(workspace), _stream_handle(stream)))

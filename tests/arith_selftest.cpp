@@ -1,0 +1,140 @@
+// Host build of the GPU library's integer arithmetic (csrc/mh_arith.h), compared
+// with the plain definition  ((polynomial) mod p) mod D  evaluated with 128-bit
+// integers and the % operator.  Prints "OK <count>" or the first mismatch.
+#include <cstdint>
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "mh_arith.h"
+
+typedef unsigned __int128 u128;
+
+static uint64_t rng_state = 0x9E3779B97F4A7C15ull;
+static uint64_t rnd()
+{
+    rng_state ^= rng_state << 13; rng_state ^= rng_state >> 7; rng_state ^= rng_state << 17;
+    return rng_state;
+}
+
+static uint64_t ref_poly(const uint64_t* c, int deg, uint64_t p, uint64_t D, uint64_t t)
+{
+    u128 acc = 0, pw = 1;
+    for (int i = 0; i < deg; ++i) { acc = (acc + (u128)c[i] * pw) % p; pw = pw * t % p; }
+    return (uint64_t)(acc % D);
+}
+
+static long checks = 0;
+#define FAIL(...) do { printf("MISMATCH " __VA_ARGS__); printf("\n"); exit(1); } while (0)
+
+static void check31(uint64_t D, const uint64_t* c, uint32_t t)
+{
+    using namespace mh;
+    ModD md = make_mod_d(D);
+    uint64_t want2 = ref_poly(c, 2, P31, D, t), want4 = ref_poly(c, 4, P31, D, t);
+    Fn2U31 f2 = prep_2u31(c[0], c[1]);
+    Fn4U31 f4 = prep_4u31(c[0], c[1], c[2], c[3]);
+    uint32_t g2, g4;
+    if (md.pow2) {
+        g2 = hash_2u31<true>(f2, stage_2u31(t), md);
+        g4 = hash_4u31<true>(f4, stage_4u31(t), md);
+        uint32_t k2 = md.mask - hash_compl_2u31(f2, stage_2u31(t), md.mask);
+        uint32_t k4 = md.mask - hash_compl_4u31(f4, stage_4u31(t), md.mask);
+        if (k2 != want2) FAIL("2U31 complement D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
+                              (unsigned long long)c[0], (unsigned long long)c[1], k2, (unsigned long long)want2);
+        if (k4 != want4) FAIL("4U31 complement D=%llu t=%u got %u want %llu", (unsigned long long)D, t, k4,
+                              (unsigned long long)want4);
+    } else {
+        g2 = hash_2u31<false>(f2, stage_2u31(t), md);
+        g4 = hash_4u31<false>(f4, stage_4u31(t), md);
+    }
+    if (g2 != want2) FAIL("2U31 D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
+                          (unsigned long long)c[0], (unsigned long long)c[1], g2, (unsigned long long)want2);
+    if (g4 != want4) FAIL("4U31 D=%llu t=%u c=(%llu,%llu,%llu,%llu) got %u want %llu", (unsigned long long)D, t,
+                          (unsigned long long)c[0], (unsigned long long)c[1], (unsigned long long)c[2],
+                          (unsigned long long)c[3], g4, (unsigned long long)want4);
+    checks += 2;
+}
+
+static void check61(uint64_t D, const uint64_t* c, uint32_t t)
+{
+    using namespace mh;
+    ModD md = make_mod_d(D);
+    uint64_t want = ref_poly(c, 2, P61, D, t);
+    Fn2U61 f = prep_2u61(c[0], c[1]);
+    u128 full = ((u128)c[1] * t + c[0]) % P61;
+    if (t < (1u << 31)) {
+        uint64_t r = residue_2u61(f, t);
+        if (r != (uint64_t)full) FAIL("2U61 residue t=%u got %llu want %llu", t, (unsigned long long)r,
+                                      (unsigned long long)(uint64_t)full);
+    }
+    if (residue_wide_2u61(f, t) != (uint64_t)full) FAIL("2U61 wide residue t=%u", t);
+    uint32_t g = (md.pow2 && D <= (1ull << 31)) ? hash_2u61<true>(f, t, md, D) : hash_2u61<false>(f, t, md, D);
+    if (g != want) FAIL("2U61 D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
+                        (unsigned long long)c[0], (unsigned long long)c[1], g, (unsigned long long)want);
+    ++checks;
+}
+
+int main()
+{
+    using namespace mh;
+    const uint64_t p31 = P31, p61 = P61;
+    // m31_reduce64 against % on edge and random 64-bit values (Section 3.4's reduction)
+    {
+        std::vector<uint64_t> vs = {0, 1, p31 - 1, p31, p31 + 1, 2 * p31 - 1, 2 * p31, 2 * p31 + 1, 1ull << 31, (1ull << 32) - 1,
+                                    (p31 - 1) * (p31 - 1), (p31 - 1) * (p31 - 1) + (p31 - 1), (1ull << 62) - 1,
+                                    1ull << 62, ~0ull, ~0ull - 1, (1ull << 63), p31 << 31, (p31 << 31) + p31};
+        for (int i = 0; i < 2000000; ++i) vs.push_back(rnd() >> (rnd() % 40));
+        for (uint64_t v : vs) {
+            if (m31_reduce64(v) != v % p31) FAIL("m31_reduce64(%llu)", (unsigned long long)v);
+            ++checks;
+        }
+    }
+    // mod-D by multiply-high
+    {
+        std::vector<uint64_t> Ds = {3, 5, 6, 7, 10, 1000003, 16609143, 1010017424, 2147483646, 2147483645, (1u << 30) + 1, (1u << 30) - 1};
+        for (uint64_t D : Ds) {
+            ModD md = make_mod_d(D);
+            std::vector<uint32_t> rs = {0, 1, (uint32_t)D - 1, (uint32_t)D, (uint32_t)D + 1, P31 - 1, P31 - 2, (uint32_t)(2 * D % P31)};
+            for (int i = 0; i < 200000; ++i) rs.push_back((uint32_t)(rnd() % P31));
+            for (uint32_t r : rs) {
+                if (r >= P31) continue;
+                if (reduce_mod_d<false>(r, md) != r % D) FAIL("mod D=%llu r=%u", (unsigned long long)D, r);
+                ++checks;
+            }
+        }
+    }
+    std::vector<uint64_t> D31 = {1, 2, 1 << 10, 1 << 24, 1u << 30, 3, 1000003, 16609143, 1010017424, p31 - 1};
+    std::vector<uint64_t> D61 = {1, 2, 1 << 24, 1u << 30, 1ull << 31, 1ull << 32, 3, 1010017424, (1ull << 32) - 1, (1ull << 31) + 7};
+    std::vector<uint64_t> edge31 = {0, 1, 2, p31 - 1, p31 - 2, (p31 - 1) / 2, (p31 - 1) / 2 + 1, (p31 + 1) / 2 + 1, 1 << 16, 12345};
+    std::vector<uint64_t> edge61 = {0, 1, 2, p61 - 1, p61 - 2, (p61 - 1) / 2, (p61 + 1) / 2, 1ull << 32, (1ull << 32) - 1, 1ull << 60};
+    for (uint64_t D : D31) {
+        std::vector<uint32_t> ts = {0, 1, (uint32_t)(D - 1), (uint32_t)(D / 2), (uint32_t)((D - 1) / 3)};
+        // all edge combinations for (c0, c1), with edge c2, c3
+        for (uint64_t c0 : edge31) for (uint64_t c1 : edge31) for (uint32_t t : ts) {
+            uint64_t c[4] = {c0, c1, edge31[(c0 + t) % edge31.size()], edge31[(c1 + 3) % edge31.size()]};
+            check31(D, c, t);
+        }
+        for (int i = 0; i < 300000; ++i) {
+            uint64_t c[4] = {rnd() % p31, rnd() % p31, rnd() % p31, rnd() % p31};
+            if (i % 7 == 0) c[rnd() % 4] = edge31[rnd() % edge31.size()];
+            uint32_t t = (uint32_t)(rnd() % D);
+            check31(D, c, t);
+        }
+    }
+    for (uint64_t D : D61) {
+        std::vector<uint32_t> ts = {0, 1, (uint32_t)(D - 1), (uint32_t)(D / 2), (uint32_t)((D - 1) / 3)};
+        for (uint64_t c0 : edge61) for (uint64_t c1 : edge61) for (uint32_t t : ts) {
+            uint64_t c[2] = {c0, c1};
+            check61(D, c, t);
+        }
+        for (int i = 0; i < 300000; ++i) {
+            uint64_t c[2] = {rnd() % p61, rnd() % p61};
+            if (i % 7 == 0) c[rnd() % 2] = edge61[rnd() % edge61.size()];
+            uint32_t t = (uint32_t)(rnd() % D);
+            check61(D, c, t);
+        }
+    }
+    printf("OK %ld\n", checks);
+    return 0;
+}

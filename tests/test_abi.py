@@ -1,0 +1,115 @@
+"""The C-ABI library without a GPU: it loads, exports what the header declares,
+and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1205_2958_amd import minhash as mh
+from paper_1205_2958_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "minhash.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(mh.LIB_PATH):
+        from paper_1205_2958_amd import build
+        build.build()
+    return mh.lib()
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(minhash_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert len(names) >= 8
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(mh.EXPORTS) == names
+
+
+def test_version_and_error_strings(lib):
+    assert mh.version() == 100
+    for code in range(0, -10, -1):
+        assert mh.error_string(code) and mh.error_string(code) != "unknown error code"
+    assert mh.error_string(-99) == "unknown error code"
+
+
+def test_workspace_size_query():
+    small = mh.workspace_bytes(1000, 650_000, 64, mh.FAMILY_2U_M31)
+    big = mh.workspace_bytes(350_000, 1_300_000_000, 500, mh.FAMILY_2U_M31)
+    assert 0 < small < big
+    assert small % mh.WORKSPACE_ALIGN == 0 and big % mh.WORKSPACE_ALIGN == 0
+    assert mh.workspace_bytes(-1, 10, 64, 0) == 0
+    assert mh.workspace_bytes(10, -1, 64, 0) == 0
+    assert mh.workspace_bytes(10, 10, 0, 0) == 0
+    assert mh.workspace_bytes(10, 10, 64, 9) == 0
+    assert mh.workspace_bytes(10, 10, 64, mh.FAMILY_4U_M61) == 0
+    assert mh.workspace_bytes(1 << 31, 10, 64, 0) == 0
+
+
+def test_coefficient_range_check():
+    for fam in (mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61):
+        c = W.coefficients(16, fam, seed=1)
+        mh.check_coeffs(c, fam)
+        c[3, 1] = W.family_prime(fam)
+        with pytest.raises(mh.MinhashError) as e:
+            mh.check_coeffs(c, fam)
+        assert e.value.code == -8
+    with pytest.raises(mh.MinhashError):
+        mh.check_coeffs(np.zeros((4, 2), dtype=np.uint64), mh.FAMILY_PERM)
+
+
+def _call(lib, n_rows=4, D=1 << 24, k=64, b=8, family=0, perm_ld=0, out_stride=64, ws=0x1000, ws_bytes=1 << 20,
+          row_ptr=0x1000, col_idx=0x1000, params=0x1000, out=0x1000, flags=0):
+    return lib.minhash_signatures(row_ptr, col_idx, n_rows, D, k, b, family, params, perm_ld, out, out_stride, ws,
+                                  ws_bytes, 0, flags)
+
+
+def test_bad_arguments_are_rejected_before_any_launch(lib):
+    # (no GPU in this process: had any of these reached a HIP call it would fail differently)
+    assert _call(lib, n_rows=0) == 0                                  # empty batch is a no-op
+    assert _call(lib, n_rows=-1) == -1
+    assert _call(lib, n_rows=1 << 31) == -1
+    assert _call(lib, family=7) == -2
+    assert _call(lib, family=mh.FAMILY_4U_M61) == -2
+    assert _call(lib, D=0) == -3
+    assert _call(lib, D=(1 << 32) + 1) == -3
+    assert _call(lib, D=(1 << 31) - 1) == -3                          # D must be below p = 2^31 - 1
+    assert _call(lib, D=(1 << 31), family=mh.FAMILY_2U_M31) == -3
+    assert _call(lib, k=0) == -4
+    assert _call(lib, k=65537, out_stride=1 << 20) == -4
+    assert _call(lib, b=0) == -4
+    assert _call(lib, b=33, out_stride=1 << 20) == -4
+    assert _call(lib, out_stride=63) == -5
+    assert _call(lib, family=mh.FAMILY_PERM, perm_ld=63) == -5
+    assert _call(lib, perm_ld=64) == -5                               # perm_ld must be 0 for hash families
+    assert _call(lib, flags=2) == -1
+    assert _call(lib, row_ptr=0) == -1
+    assert _call(lib, params=0) == -1
+    assert _call(lib, out=0) == -1
+    assert _call(lib, ws=0) == -6
+    assert _call(lib, ws=0x1001) == -6                                # misaligned
+    assert _call(lib, ws_bytes=128) == -6                             # too small for the work list
+
+
+def test_profiled_entry_point_validates_the_same_way(lib):
+    ms = ctypes.c_float(-1.0)
+    rc = lib.minhash_signatures_profiled(0x1000, 0x1000, 4, 0, 64, 8, 0, 0x1000, 0, 0x1000, 64, 0x1000, 1 << 20, 0, 0,
+                                         ctypes.byref(ms))
+    assert rc == -3 and ms.value == 0.0
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(mh, "_lib", None)
+    monkeypatch.setattr(mh, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(FileNotFoundError):
+        mh.lib()

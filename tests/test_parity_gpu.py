@@ -1,0 +1,257 @@
+"""GPU library against the CPU oracle, bit for bit (integer work: no tolerance).
+
+Everything goes through the C ABI (via the ctypes binding).  Small cases are
+compared on every byte; the full-size workloads are compared on sampled rows
+(shortest, longest, split and random ones), which the oracle computes one by
+one.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_1205_2958_amd import minhash as mh
+from paper_1205_2958_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def _to_dev(a: np.ndarray) -> torch.Tensor:
+    if a.dtype == np.uint32:
+        return torch.from_numpy(a.view(np.int32)).to(DEV)
+    if a.dtype == np.uint64:
+        return torch.from_numpy(a.view(np.int64)).to(DEV)
+    return torch.from_numpy(a).to(DEV)
+
+
+def gpu_signatures(rp, col, D, k, b, family, params, out_stride=None, flags=0, poison=True):
+    rp_d, col_d, par_d = _to_dev(np.ascontiguousarray(rp)), _to_dev(np.ascontiguousarray(col)), _to_dev(params)
+    n = rp.shape[0] - 1
+    sig = (k * b + 7) // 8
+    out_stride = sig if out_stride is None else out_stride
+    out = torch.full((n, out_stride), 0xAA if poison else 0, dtype=torch.uint8, device=DEV)
+    ws = mh.alloc_workspace(n, int(col.shape[0]), k, family, DEV)
+    ws.fill_(0xCD)                       # the library must not rely on workspace contents
+    mh.minhash_signatures(rp_d, col_d, D, k, b, family, par_d, out=out, out_stride=out_stride, workspace=ws,
+                          flags=flags)
+    st = mh.status(ws) if n > 0 else 0     # an empty batch is a no-op and leaves the workspace untouched
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), st
+
+
+def check_case(rp, col, D, k, b, family, params, out_stride=None):
+    got, st = gpu_signatures(rp, col, D, k, b, family, params, out_stride)
+    want = oracle.signatures(rp, col, D, k, b, family, params, out_stride)
+    assert st == 0
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        r, c = bad[0]
+        raise AssertionError("first mismatch at row %d byte %d: gpu %d oracle %d (%d bytes differ, nnz of row %d)"
+                             % (r, c, got[r, c], want[r, c], len(bad), rp[r + 1] - rp[r]))
+
+
+# lengths around every boundary of the kernel: empty, below/at/above a 4-nonzero
+# step, a 256-nonzero tile, the 8192-nonzero split point, several chunks
+EDGE_NNZ = [0, 1, 2, 3, 4, 5, 7, 8, 9, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1000, 0, 4095, 8191, 8192, 8193, 16384,
+            16385, 20000, 1, 0]
+
+
+def edge_rows(D, seed, extra=()):
+    nnz = np.array(EDGE_NNZ + list(extra), dtype=np.int64)
+    nnz = np.minimum(nnz, D)
+    return W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed)
+
+
+# ------------------------------------------------------------------ config 1, every byte
+def test_tiny_2u_workload_every_row():
+    w = W.WORKLOADS["tiny_2u"]
+    nnz = w.nnz()
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, w.D, w.data_seed)
+    check_case(rp, col, w.D, w.k, w.b, w.family, W.coefficients(w.k, w.family, w.param_seed))
+
+
+# ------------------------------------------------------------------ families x edge lengths at the real k
+@pytest.mark.parametrize("family,D,b", [
+    (mh.FAMILY_2U_M31, 1 << 24, 8),
+    (mh.FAMILY_4U_M31, 1 << 24, 8),
+    (mh.FAMILY_2U_M61, 1 << 30, 1),
+])
+def test_hash_families_k500_edge_lengths(family, D, b):
+    rp, col = edge_rows(D, seed=42 + family, extra=(50000,))
+    check_case(rp, col, D, 500, b, family, W.coefficients(500, family, seed=77 + family))
+
+
+@pytest.mark.parametrize("k", [1, 7, 8, 9, 31, 63, 64, 65, 100, 200, 511, 512, 513, 1030])
+def test_function_counts(k):
+    D = 1 << 24
+    rp, col = edge_rows(D, seed=5)
+    check_case(rp, col, D, k, 8, mh.FAMILY_2U_M31, W.coefficients(k, mh.FAMILY_2U_M31, seed=k))
+
+
+@pytest.mark.parametrize("b", [1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 16, 24, 31, 32])
+def test_bit_widths_and_unaligned_rows(b):
+    D, k = 1 << 24, 77
+    rp, col = edge_rows(D, seed=6)
+    sig = (k * b + 7) // 8
+    c = W.coefficients(k, mh.FAMILY_2U_M31, seed=b)
+    check_case(rp, col, D, k, b, mh.FAMILY_2U_M31, c)
+    check_case(rp, col, D, k, b, mh.FAMILY_2U_M31, c, out_stride=sig + 3)     # pad bytes, odd pitch
+
+
+@pytest.mark.parametrize("family", [mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61])
+@pytest.mark.parametrize("D", [1, 2, 1 << 10, 1 << 20, 1 << 30, 3, 1000003, 16609143, 1010017424])
+def test_universe_sizes_including_non_powers_of_two(family, D):
+    nnz = np.minimum(np.array([0, 1, 2, 5, 64, 300, 1000, 9000], dtype=np.int64), D)
+    if D & (D - 1):
+        rng = np.random.Generator(np.random.PCG64(D))
+        rows = [np.unique(rng.integers(0, D, size=int(m))).astype(np.uint32) for m in nnz]
+        nnz = np.array([r.shape[0] for r in rows], dtype=np.int64)
+        col = np.concatenate(rows)
+    elif D >= 4:
+        col = W.csr_indices_np(nnz, D, seed=9)
+    else:
+        col = np.concatenate([np.arange(m, dtype=np.uint32) for m in nnz])
+    rp = W.row_ptr_from_nnz(nnz)
+    k = 40
+    c = W.coefficients(k, family, seed=D % 1000)
+    c[0, :] = W.family_prime(family) - 1                   # largest coefficients
+    c[1, :] = 0
+    check_case(rp, col, D, k, 8, family, c)
+    check_case(rp, col, D, k, 32, family, c)               # full minima
+
+
+def test_m61_large_universes():
+    for D in (1 << 31, 1 << 32, (1 << 32) - 5):
+        rng = np.random.Generator(np.random.PCG64(3))
+        nnz = np.array([1, 10, 500, 9000], dtype=np.int64)
+        col = np.concatenate([np.sort(rng.integers(0, D, size=int(m), dtype=np.uint64)).astype(np.uint32)
+                              for m in nnz] + [np.array([D - 1], dtype=np.uint32)])
+        nnz = np.append(nnz, 1)
+        rp = W.row_ptr_from_nnz(nnz)
+        c = W.coefficients(24, mh.FAMILY_2U_M61, seed=4)
+        c[0, :] = W.M61 - 1
+        check_case(rp, col, D, 24, 32, mh.FAMILY_2U_M61, c)
+
+
+def test_extreme_coefficients_and_indices():
+    """Residue 0, residue p-1, t = 0, t = D-1, zero and maximal coefficients."""
+    D = 1 << 24
+    col = np.array([0, D - 1, 1, 0, 0, D - 1, D - 1, 12345], dtype=np.uint32)
+    rp = np.array([0, 2, 3, 4, 6, 8], dtype=np.int64)
+    for family in (mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61):
+        p, deg = W.family_prime(family), W.family_degree(family)
+        vals = [0, 1, p - 1, p - 2, (p - 1) // 2, (p + 1) // 2, D % p, 2]
+        rows = []
+        for i, v0 in enumerate(vals):
+            for v1 in vals:
+                rows.append([v0, v1] + [vals[(i + j) % len(vals)] for j in range(deg - 2)])
+        c = np.array(rows, dtype=np.uint64)
+        check_case(rp, col, D, c.shape[0], 32, family, c)
+
+
+def test_order_duplicates_and_row_ptr_offset():
+    D, k = 1 << 24, 64
+    rng = np.random.Generator(np.random.PCG64(8))
+    base = W.csr_indices_np(np.array([700, 9000], dtype=np.int64), D, seed=3)
+    s, t = base[:700], base[700:]
+    shuffled = s[rng.permutation(700)]
+    dup = np.concatenate([shuffled, shuffled[:100], t[rng.permutation(9000)], t[:300]])
+    junk = np.arange(17, dtype=np.uint32)                   # row_ptr[0] = 17: leading entries are not part of any row
+    col = np.concatenate([junk, s, t, dup[:800], dup[800:]])
+    rp = np.array([17, 717, 9717, 10517, 10517 + 9300], dtype=np.int64)
+    c = W.coefficients(k, mh.FAMILY_2U_M31, seed=1)
+    got, st = gpu_signatures(rp, col, D, k, 8, mh.FAMILY_2U_M31, c)
+    assert st == 0
+    want = oracle.signatures(rp, col, D, k, 8, mh.FAMILY_2U_M31, c)
+    assert np.array_equal(got, want)
+    assert np.array_equal(got[0], got[2]) and np.array_equal(got[1], got[3])
+
+
+def test_empty_batch_and_all_empty_rows():
+    D, k, b = 1 << 24, 64, 8
+    c = W.coefficients(k, mh.FAMILY_2U_M31, seed=1)
+    rp = np.zeros(1, dtype=np.int64)
+    got, st = gpu_signatures(rp, np.zeros(0, np.uint32), D, k, b, mh.FAMILY_2U_M31, c)
+    assert got.shape == (0, 64) and st == 0
+    rp = np.zeros(301, dtype=np.int64)
+    col = np.zeros(4, dtype=np.uint32)                       # never read
+    got, st = gpu_signatures(rp, col, D, k, 4, mh.FAMILY_2U_M31, c, out_stride=40)
+    assert st == 0
+    assert np.all(got[:, :32] == 0xFF) and np.all(got[:, 32:] == 0)
+
+
+# ------------------------------------------------------------------ permutation tables
+@pytest.mark.parametrize("k,ld,b,D", [(200, 200, 4, 1 << 15), (201, 201, 4, 1 << 12), (201, 204, 1, 1 << 12),
+                                      (64, 64, 8, 1 << 12), (3, 3, 32, 1 << 15), (300, 300, 4, 1 << 12),
+                                      (513, 516, 2, 1 << 12)])
+def test_permutation_tables(k, ld, b, D):
+    table = W.perm_table_np(D, k, seed=k, perm_ld=ld)
+    if ld > k:
+        table[:, k:] = 0                                    # pad columns smaller than any entry must be ignored
+    rp, col = edge_rows(D, seed=12)
+    check_case(rp, col, D, k, b, mh.FAMILY_PERM, table)
+
+
+def test_permutation_table_offset_pointer_takes_scalar_path():
+    D, k = 1 << 10, 50
+    table = W.perm_table_np(D, k, seed=2, perm_ld=52)
+    rp, col = edge_rows(D, seed=13)
+    want = oracle.signatures(rp, col, D, k, 4, mh.FAMILY_PERM, table)
+    big = torch.zeros(D * 52 + 1, dtype=torch.int32, device=DEV)
+    big[1:] = _to_dev(table).reshape(-1)
+    view = big[1:].view(D, 52)                              # 4-byte aligned only
+    out = torch.empty((rp.shape[0] - 1, 25), dtype=torch.uint8, device=DEV)
+    mh.minhash_signatures(_to_dev(rp), _to_dev(col), D, k, 4, mh.FAMILY_PERM, view, out=out, perm_ld=52)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
+# ------------------------------------------------------------------ validation flag
+def test_validate_flag_reports_bad_input():
+    D, k = 1 << 16, 16
+    c = W.coefficients(k, mh.FAMILY_2U_M31, seed=1)
+    rp, col = edge_rows(D, seed=14)
+    _, st = gpu_signatures(rp, col, D, k, 8, mh.FAMILY_2U_M31, c, flags=mh.FLAG_VALIDATE)
+    assert st == 0
+    bad = col.copy()
+    bad[100] = D                                             # index out of range
+    _, st = gpu_signatures(rp, bad, D, k, 8, mh.FAMILY_2U_M31, c, flags=mh.FLAG_VALIDATE)
+    assert st == -9
+    table = W.perm_table_np(D, k, seed=3)
+    _, st = gpu_signatures(rp, bad, D, k, 8, mh.FAMILY_PERM, table, flags=mh.FLAG_VALIDATE)
+    assert st == -9
+    rp_bad = rp.copy()
+    rp_bad[5] = rp_bad[4] - 1                                # decreasing row_ptr
+    _, st = gpu_signatures(rp_bad, col, D, k, 8, mh.FAMILY_2U_M31, c, flags=mh.FLAG_VALIDATE)
+    assert st == -9
+
+
+def test_profiled_entry_point_gives_the_same_bits_and_a_duration():
+    w = W.WORKLOADS["tiny_2u"]
+    nnz = w.nnz()
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, w.D, w.data_seed)
+    c = W.coefficients(w.k, w.family, w.param_seed)
+    ref, _ = gpu_signatures(rp, col, w.D, w.k, w.b, w.family, c)
+    out, ms = mh.minhash_signatures_profiled(_to_dev(rp), _to_dev(col), w.D, w.k, w.b, w.family, _to_dev(c))
+    assert ms > 0.0
+    assert np.array_equal(out.cpu().numpy(), ref)
+
+
+def test_streams_and_workspace_reuse():
+    D, k = 1 << 24, 500
+    rp, col = edge_rows(D, seed=15)
+    c = W.coefficients(k, mh.FAMILY_2U_M31, seed=2)
+    want = oracle.signatures(rp, col, D, k, 8, mh.FAMILY_2U_M31, c)
+    rp_d, col_d, c_d = _to_dev(rp), _to_dev(col), _to_dev(c)
+    ws = mh.alloc_workspace(rp.shape[0] - 1, col.shape[0], k, mh.FAMILY_2U_M31, DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    outs = []
+    with torch.cuda.stream(side):
+        for _ in range(3):                                   # same workspace, same stream, back to back
+            outs.append(mh.minhash_signatures(rp_d, col_d, D, k, 8, mh.FAMILY_2U_M31, c_d, workspace=ws, stream=side))
+    side.synchronize()
+    for o in outs:
+        assert np.array_equal(o.cpu().numpy(), want)
