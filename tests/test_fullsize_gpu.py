@@ -1,0 +1,102 @@
+"""Full-size workloads, in the launch configuration bench.py times: the GPU
+library's output on sampled rows (longest, shortest, around the split point,
+random) against the CPU oracle, row by row and bit for bit.  The rows are
+generated on the GPU with the torch generator; each sampled row is also
+re-generated with the NumPy generator, which must give the same indices."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_1205_2958_amd import minhash as mh
+from paper_1205_2958_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+SPLIT = 8192          # rows longer than this are processed in chunks and merged
+
+
+def _sample_rows(nnz, n_random, seed, eval_budget, k):
+    order = np.argsort(nnz, kind="stable")
+    picks = list(order[:3]) + list(order[-2:])
+    near = np.argsort(np.abs(nnz - SPLIT), kind="stable")[:4]          # both sides of the split point
+    picks += list(near)
+    above = np.where(nnz > SPLIT)[0]
+    if above.size:
+        picks += list(above[:2])
+    rng = np.random.Generator(np.random.PCG64(seed))
+    picks += list(rng.integers(0, len(nnz), size=n_random))
+    picks += [0, len(nnz) - 1]
+    out, spent = [], 0.0
+    for r in dict.fromkeys(int(p) for p in picks):
+        cost = float(nnz[r]) * k
+        if out and spent + cost > eval_budget:
+            continue
+        out.append(r)
+        spent += cost
+    return out
+
+
+def _run_workload(name, batch=0):
+    w = W.WORKLOADS[name]
+    nnz = w.nnz(batch)
+    rp_np = W.row_ptr_from_nnz(nnz)
+    seed = w.data_seed + batch
+    col = W.csr_indices_torch(nnz, w.D, seed, DEV)
+    rp = torch.from_numpy(rp_np).to(DEV)
+    if w.family == W.FAMILY_PERM:
+        params = W.perm_table_torch(w.D, w.k, w.param_seed, DEV)
+        params_np = None
+    else:
+        params_np = W.coefficients(w.k, w.family, w.param_seed)
+        params = torch.from_numpy(params_np.view(np.int64)).to(DEV)
+    out = torch.full((len(nnz), w.sig_bytes()), 0xAA, dtype=torch.uint8, device=DEV)
+    ws = mh.alloc_workspace(len(nnz), int(rp_np[-1]), w.k, w.family, DEV)
+    mh.minhash_signatures(rp, col, w.D, w.k, w.b, w.family, params, out=out, workspace=ws)
+    assert mh.status(ws) == 0
+    return w, nnz, rp_np, seed, col, params, params_np, out
+
+
+def _check_rows(w, nnz, rp_np, seed, col, params, params_np, out, rows):
+    for r in rows:
+        lo, hi = int(rp_np[r]), int(rp_np[r + 1])
+        idx = col[lo:hi].cpu().numpy().view(np.uint32)
+        regenerated = W.csr_indices_np(nnz[r:r + 1], w.D, seed, row_offset=r)
+        assert np.array_equal(idx, regenerated), "generators disagree on row %d" % r
+        one_rp = np.array([0, hi - lo], dtype=np.int64)
+        if w.family == W.FAMILY_PERM:
+            # only the table rows this set touches travel to the host: table[t] for t in the set,
+            # re-indexed 0..nnz-1 (the oracle just reads table[t][j])
+            sub = params[col[lo:hi].long()].cpu().numpy().view(np.uint32)
+            want = oracle.signatures(one_rp, np.arange(hi - lo, dtype=np.uint32), max(hi - lo, 1), w.k, w.b, w.family, sub)
+        else:
+            want = oracle.signatures(one_rp, idx, w.D, w.k, w.b, w.family, params_np)
+        got = out[r].cpu().numpy()
+        assert np.array_equal(got, want[0]), "row %d (nnz %d) differs from the oracle" % (r, hi - lo)
+
+
+@pytest.mark.parametrize("name,n_random,budget", [
+    ("large_2u", 24, 3.0e8),
+    ("large_4u", 16, 2.0e8),
+    ("perm_table", 16, 1.5e8),
+])
+def test_large_workloads_sampled_rows(name, n_random, budget):
+    w, nnz, rp_np, seed, col, params, params_np, out = _run_workload(name)
+    rows = _sample_rows(nnz, n_random, seed=17, eval_budget=budget, k=w.k)
+    assert len(rows) >= 8
+    _check_rows(w, nnz, rp_np, seed, col, params, params_np, out, rows)
+    # every row was written: none still holds the poison pattern the buffer was filled with
+    assert out.shape == (350_000, w.sig_bytes())
+    assert bool((out != 0xAA).any(dim=1).all().item())
+
+
+@pytest.mark.parametrize("batch", [0, 9])
+def test_heavy_tailed_m61_batch_sampled_rows(batch):
+    w, nnz, rp_np, seed, col, params, params_np, out = _run_workload("huge_2u_m61", batch)
+    assert nnz.max() == 1_000_000                     # the batch contains rows at the cap
+    order = np.argsort(nnz, kind="stable")
+    rows = [int(order[-1])]                           # one row at the 10^6 cap: 122 chunks merged by atomicMin
+    rows += _sample_rows(nnz, 24, seed=18 + batch, eval_budget=4.0e8, k=w.k)
+    _check_rows(w, nnz, rp_np, seed, col, params, params_np, out, list(dict.fromkeys(rows)))
+    # b = 1, k = 500: 63 bytes per row, the last 4 bits of the last byte are pad and must be 0
+    assert int((out[:, 62] & 0xF0).max().item()) == 0
