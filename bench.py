@@ -97,6 +97,9 @@ def main() -> int:
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS rows (debugging; invalidates the metric)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle work per core for the CPU baseline (0: skip)")
     ap.add_argument("--perm-ld", type=int, default=0)
+    ap.add_argument("--calib", action="store_true",
+                    help="also launch one plain streaming kernel of known size (reads 1 GiB, writes 1 GiB) so that "
+                         "FETCH_SIZE / WRITE_SIZE counters of a profiler run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this path runs on one GPU; rows are independent, so more GPUs would each take a slice of "
@@ -152,6 +155,13 @@ def main() -> int:
     def step():
         mh.minhash_signatures(rp, col, w.D, w.k, w.b, family, params, out=out, workspace=ws, stream=stream,
                               perm_ld=perm_ld if family == W.FAMILY_PERM else None)
+
+    if args.calib:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)          # one elementwise kernel: 2^30 bytes in, 2^30 bytes out
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

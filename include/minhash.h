@@ -91,8 +91,8 @@ enum {
  * Returns MINHASH_OK once everything is enqueued, or a negative code found
  * before any launch (nothing has been enqueued then).  Indices >= D or a
  * decreasing row_ptr are undefined behaviour unless MINHASH_FLAG_VALIDATE is
- * set, in which case offending entries are skipped and minhash_status reports
- * MINHASH_ERR_DATA.
+ * set; then no access leaves the buffers, minhash_status reports
+ * MINHASH_ERR_DATA, and the signatures of the affected rows are unspecified.
  */
 int minhash_signatures(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows,
                        uint64_t D, int32_t k, int32_t b, int32_t family,
@@ -124,8 +124,11 @@ size_t minhash_workspace_bytes(int64_t n_rows, int64_t nnz_upper_bound, int32_t 
  * Returns MINHASH_OK, MINHASH_ERR_COEFF, or an argument error. */
 int minhash_check_coeffs(const uint64_t *host_coeffs, int32_t k, int32_t family);
 
-/* Waits for `stream`, then returns MINHASH_OK or MINHASH_ERR_DATA according to
- * what the last call that used `workspace` with MINHASH_FLAG_VALIDATE found. */
+/* Waits for `stream`, then reports on the last non-empty call that used
+ * `workspace`: MINHASH_ERR_WORKSPACE if row_ptr described more nonzeros than the
+ * workspace was sized for (the output of that call is unspecified, nothing was
+ * written outside the buffers), MINHASH_ERR_DATA if MINHASH_FLAG_VALIDATE found
+ * bad input, else MINHASH_OK. */
 int minhash_status(const void *workspace, void *stream);
 
 /* Static text for a return code; never NULL. */

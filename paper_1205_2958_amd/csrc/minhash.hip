@@ -4,9 +4,9 @@
 //
 //   mh_reset_kernel      clears the work-list header in the workspace
 //   mh_bin_rows_kernel   load balancer: reads row_ptr, emits one work item per
-//                        row, or one per CHUNK nonzeros for long rows (which
-//                        also get a slot of partial minima in the workspace)
-//   mh_fill_kernel       sets the partial minima of split rows to 0xFFFFFFFF
+//                        row, or one per CHUNK nonzeros for long rows (each
+//                        chunk gets a vector of k partial minima in the
+//                        workspace)
 //   mh_hash_kernel<..>   (hash families) or mh_perm_kernel<..> (permutation
 //                        table): the hot loop.  Persistent wavefronts take
 //                        (item, function-tile) units from an atomic ticket.
@@ -20,10 +20,11 @@
 //                        lanes take slices of the nonzeros and are merged by a
 //                        butterfly of cross-lane minima.  Whole rows are
 //                        truncated to b bits, packed and stored by the same
-//                        wavefront; chunks of split rows are merged with
-//                        atomicMin, which is exact because the minimum over a
-//                        union is the minimum of the parts.
-//   mh_finalize_kernel   packs and stores the split rows.
+//                        wavefront; a chunk of a split row stores its k
+//                        partial minima with plain coalesced stores.
+//   mh_finalize_kernel   takes the minimum over the chunks of every split row
+//                        (exact: the minimum over a union is the minimum of the
+//                        minima of the parts), truncates, packs and stores.
 //
 // Wavefronts never synchronise with each other inside a kernel: each has its
 // own LDS region and its own work units, so there is no barrier anywhere.
@@ -55,9 +56,10 @@ constexpr uint32_t NO_SLOT = 0xFFFFFFFFu;
 struct WorkHeader {                    // first 256 bytes of the workspace
     uint32_t n_items;
     uint32_t n_split;
+    uint32_t n_parts;
     uint32_t ticket;
     uint32_t status;                   // bit 0: bad row_ptr, bit 1: index >= D, bit 2: work list overflow
-    uint32_t pad[60];
+    uint32_t pad[59];
 };
 static_assert(sizeof(WorkHeader) == 256, "header size");
 
@@ -65,14 +67,21 @@ struct Item {                          // one unit of row work
     int64_t begin;                     // offset of the first nonzero in col_idx
     uint32_t len;                      // number of nonzeros (<= CHUNK unless the row is whole)
     uint32_t row;
-    uint32_t slot;                     // NO_SLOT for a whole row, else index of the split row's partial minima
+    uint32_t slot;                     // NO_SLOT for a whole row, else index of this chunk's vector of partial minima
     uint32_t pad;
 };
 static_assert(sizeof(Item) == 24 || sizeof(Item) == 32, "item size");
 
+struct SplitRow {                      // a row processed as several chunks
+    uint32_t row;
+    uint32_t first_part;               // its chunks own partial vectors first_part .. first_part + n_parts - 1
+    uint32_t n_parts;
+    uint32_t pad;
+};
+
 struct Layout {                        // host and device agree on the workspace layout through this
     size_t items_off, split_rows_off, scratch_off, total;
-    uint64_t cap_items, cap_split;
+    uint64_t cap_items, cap_split, cap_parts;
 };
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -83,10 +92,11 @@ inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k)
     L.cap_items = (uint64_t)n_rows + (uint64_t)nnz_ub / CHUNK + 1;
     uint64_t by_len = (uint64_t)nnz_ub / CHUNK;
     L.cap_split = by_len < (uint64_t)n_rows ? by_len : (uint64_t)n_rows;
+    L.cap_parts = by_len + L.cap_split;            // sum over split rows of ceil(nnz / CHUNK)
     L.items_off = sizeof(WorkHeader);
     L.split_rows_off = align_up(L.items_off + L.cap_items * sizeof(Item), 256);
-    L.scratch_off = align_up(L.split_rows_off + L.cap_split * sizeof(uint32_t), 256);
-    L.total = align_up(L.scratch_off + L.cap_split * (size_t)k * sizeof(uint32_t), 256);
+    L.scratch_off = align_up(L.split_rows_off + L.cap_split * sizeof(SplitRow), 256);
+    L.total = align_up(L.scratch_off + L.cap_parts * (size_t)k * sizeof(uint32_t), 256);
     return L;
 }
 
@@ -99,10 +109,10 @@ struct KArgs {
     int64_t perm_ld;
     WorkHeader* hdr;
     Item* items;
-    uint32_t* split_rows;
-    uint32_t* scratch;
+    SplitRow* split_rows;
+    uint32_t* scratch;                 // [cap_parts][k] partial minima of chunks
     uint64_t D;
-    uint64_t cap_items, cap_split;
+    uint64_t cap_items, cap_split, cap_parts;
     ModD md;
     int64_t n_rows;
     int32_t k, b;
@@ -174,49 +184,64 @@ __global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
         is_split = nnz > (int64_t)CHUNK ? 1u : 0u;
         n_it = is_split ? (uint32_t)((nnz + CHUNK - 1) / CHUNK) : 1u;
     }
-    // inclusive scans over the wavefront
-    uint32_t inc_it = n_it, inc_sp = is_split;
+    // inclusive scans over the wavefront: items, split rows, partial vectors
+    const uint32_t n_pt = is_split ? n_it : 0u;
+    uint32_t inc_it = n_it, inc_sp = is_split, inc_pt = n_pt;
     for (int d = 1; d < WAVE; d <<= 1) {
         uint32_t v1 = (uint32_t)__shfl_up((int)inc_it, d, WAVE);
         uint32_t v2 = (uint32_t)__shfl_up((int)inc_sp, d, WAVE);
-        if (lane >= d) { inc_it += v1; inc_sp += v2; }
+        uint32_t v3 = (uint32_t)__shfl_up((int)inc_pt, d, WAVE);
+        if (lane >= d) { inc_it += v1; inc_sp += v2; inc_pt += v3; }
     }
     uint32_t tot_it = wave_bcast(inc_it, WAVE - 1), tot_sp = wave_bcast(inc_sp, WAVE - 1);
-    uint32_t base_it = 0, base_sp = 0;
+    uint32_t tot_pt = wave_bcast(inc_pt, WAVE - 1);
+    uint32_t base_it = 0, base_sp = 0, base_pt = 0;
     if (lane == WAVE - 1) {
         if (tot_it) base_it = atomicAdd(&a.hdr->n_items, tot_it);
         if (tot_sp) base_sp = atomicAdd(&a.hdr->n_split, tot_sp);
+        if (tot_pt) base_pt = atomicAdd(&a.hdr->n_parts, tot_pt);
     }
     base_it = wave_bcast(base_it, WAVE - 1);
     base_sp = wave_bcast(base_sp, WAVE - 1);
+    base_pt = wave_bcast(base_pt, WAVE - 1);
     if (row >= a.n_rows) return;
-    uint64_t first = (uint64_t)base_it + inc_it - n_it;
-    uint32_t slot = NO_SLOT;
+    const uint64_t first = (uint64_t)base_it + inc_it - n_it;
+    const uint64_t first_part = (uint64_t)base_pt + inc_pt - n_pt;
+    // An overflow can only happen when the workspace was sized for fewer nonzeros than
+    // row_ptr describes.  Every allocated work-list entry inside the capacity is still
+    // written (as an empty row), so that the consumer never reads an undefined entry.
+    bool overflow = first + n_it > a.cap_items;
+    uint64_t sidx = 0;
     if (is_split) {
-        uint64_t s = (uint64_t)base_sp + inc_sp - 1;
-        if (s >= a.cap_split) { atomicOr(&a.hdr->status, 4u); return; }
-        slot = (uint32_t)s;
-        a.split_rows[slot] = (uint32_t)row;
+        sidx = (uint64_t)base_sp + inc_sp - 1;
+        overflow = overflow || sidx >= a.cap_split || first_part + n_it > a.cap_parts;
     }
-    if (first + n_it > a.cap_items) { atomicOr(&a.hdr->status, 4u); return; }
+    if (overflow) {
+        atomicOr(&a.hdr->status, 4u);
+        for (uint32_t c = 0; c < n_it && first + c < a.cap_items; ++c) {
+            Item it; it.begin = begin; it.len = 0; it.row = (uint32_t)row; it.slot = NO_SLOT; it.pad = 1;
+            a.items[first + c] = it;
+        }
+        if (is_split && sidx < a.cap_split) {
+            SplitRow sr; sr.row = (uint32_t)row; sr.first_part = 0; sr.n_parts = 0; sr.pad = 1;
+            a.split_rows[sidx] = sr;
+        }
+        return;
+    }
+    if (is_split) {
+        SplitRow sr; sr.row = (uint32_t)row; sr.first_part = (uint32_t)first_part; sr.n_parts = n_it; sr.pad = 0;
+        a.split_rows[sidx] = sr;
+    }
     for (uint32_t c = 0; c < n_it; ++c) {
         Item it;
         it.begin = begin + (int64_t)c * CHUNK;
         int64_t rest = nnz - (int64_t)c * CHUNK;
         it.len = is_split ? (uint32_t)(rest < (int64_t)CHUNK ? rest : (int64_t)CHUNK) : (uint32_t)nnz;
         it.row = (uint32_t)row;
-        it.slot = slot;
+        it.slot = is_split ? (uint32_t)(first_part + c) : NO_SLOT;
         it.pad = 0;
         a.items[first + c] = it;
     }
-}
-
-__global__ __launch_bounds__(BLOCK) void mh_fill_kernel(KArgs a)
-{
-    const uint32_t n_split = a.hdr->n_split < a.cap_split ? a.hdr->n_split : (uint32_t)a.cap_split;
-    const uint64_t total = (uint64_t)n_split * (uint64_t)a.k;
-    for (uint64_t i = (uint64_t)blockIdx.x * BLOCK + threadIdx.x; i < total; i += (uint64_t)gridDim.x * BLOCK)
-        a.scratch[i] = EMPTY_MIN;
 }
 
 // ------------------------------------------------------------------ truncate + pack + store (one wavefront)
@@ -460,7 +485,7 @@ __global__ __launch_bounds__(BLOCK) void mh_hash_kernel(KArgs a)
             uint32_t* part = a.scratch + (size_t)it.slot * (size_t)a.k;
 #pragma unroll
             for (int r = 0; r < HASH_FPL; ++r)
-                if (j_base + r < a.k) atomicMin(part + j_base + r, m[r]);
+                if (j_base + r < a.k) part[j_base + r] = m[r];
         }
     }
 }
@@ -582,7 +607,7 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
             uint32_t* part = a.scratch + (size_t)it.slot * (size_t)a.k + j0;
 #pragma unroll
             for (int r = 0; r < PERM_FPL; ++r)
-                if (ok[r]) atomicMin(part + jl[r], m[r]);
+                if (ok[r]) part[jl[r]] = m[r];
         }
     }
 }
@@ -598,14 +623,21 @@ __global__ __launch_bounds__(BLOCK) void mh_finalize_kernel(KArgs a, int ftile_s
     const uint64_t n_units = (uint64_t)n_split * (uint64_t)a.n_ftiles;
     const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_BLOCK;
     for (uint64_t u = (uint64_t)blockIdx.x * WAVES_PER_BLOCK + wave; u < n_units; u += n_waves) {
-        const uint32_t slot = (uint32_t)(u / (uint64_t)a.n_ftiles);
-        const int ftile = (int)(u - (uint64_t)slot * (uint64_t)a.n_ftiles);
+        const uint32_t sidx = (uint32_t)(u / (uint64_t)a.n_ftiles);
+        const int ftile = (int)(u - (uint64_t)sidx * (uint64_t)a.n_ftiles);
         const int j0 = ftile * ftile_size;
         const int nf = a.k - j0 < ftile_size ? a.k - j0 : ftile_size;
-        const uint32_t* part = a.scratch + (size_t)slot * (size_t)a.k + j0;
-        for (int j = lane; j < nf; j += WAVE) mins[j] = part[j];
+        const SplitRow sr = a.split_rows[sidx];
+        for (int j = lane; j < nf; j += WAVE) {
+            uint32_t v = EMPTY_MIN;
+            for (uint32_t c = 0; c < sr.n_parts; ++c) {
+                uint32_t o = a.scratch[(size_t)(sr.first_part + c) * (size_t)a.k + j0 + j];
+                v = o < v ? o : v;
+            }
+            mins[j] = v;
+        }
         wave_sync_lds();
-        wave_pack_store(a, mins, a.split_rows[slot], j0, nf, ftile == a.n_ftiles - 1, lane);
+        wave_pack_store(a, mins, sr.row, j0, nf, ftile == a.n_ftiles - 1, lane);
         wave_sync_lds();
     }
 }
@@ -702,9 +734,9 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     a.out_stride = out_stride; a.perm_ld = perm_ld;
     a.hdr = reinterpret_cast<WorkHeader*>(ws);
     a.items = reinterpret_cast<Item*>(ws + L.items_off);
-    a.split_rows = reinterpret_cast<uint32_t*>(ws + L.split_rows_off);
+    a.split_rows = reinterpret_cast<SplitRow*>(ws + L.split_rows_off);
     a.scratch = reinterpret_cast<uint32_t*>(ws + L.scratch_off);
-    a.D = D; a.cap_items = L.cap_items; a.cap_split = L.cap_split;
+    a.D = D; a.cap_items = L.cap_items; a.cap_split = L.cap_split; a.cap_parts = L.cap_parts;
     a.md = make_mod_d(D);
     a.n_rows = n_rows; a.k = k; a.b = b;
     a.sig_bytes = (int32_t)sig_bytes;
@@ -728,7 +760,6 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, s, a.hdr);
     const int bin_blocks = (int)((n_rows + BLOCK - 1) / BLOCK);
     hipLaunchKernelGGL(mh_bin_rows_kernel, dim3(bin_blocks), dim3(BLOCK), 0, s, a);
-    if (L.cap_split > 0) hipLaunchKernelGGL(mh_fill_kernel, dim3(cus * 2), dim3(BLOCK), 0, s, a);
 
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (profiled) {
@@ -822,7 +853,7 @@ int minhash_status(const void* workspace, void* stream)
     hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
     WorkHeader h;
-    e = hipMemcpy(&h, workspace, sizeof(uint32_t) * 4, hipMemcpyDeviceToHost);
+    e = hipMemcpy(&h, workspace, sizeof(uint32_t) * 8, hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy");
     if (h.status & 4u) return MINHASH_ERR_WORKSPACE;
     return h.status ? MINHASH_ERR_DATA : MINHASH_OK;

@@ -228,6 +228,24 @@ def test_validate_flag_reports_bad_input():
     assert st == -9
 
 
+def test_workspace_sized_for_too_few_nonzeros_is_reported_not_overrun():
+    """The work list is bounded by the workspace: a batch that does not fit is
+    reported through minhash_status (its output is unspecified) and nothing is
+    written outside the workspace; the same batch with a fitting workspace is exact."""
+    D, k = 1 << 24, 64
+    nnz = np.array([5, 30000, 7, 100, 20000, 3], dtype=np.int64)
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed=21)
+    c = W.coefficients(k, mh.FAMILY_2U_M31, seed=3)
+    want = oracle.signatures(rp, col, D, k, 8, mh.FAMILY_2U_M31, c)
+    ws = mh.alloc_workspace(len(nnz), 100, k, mh.FAMILY_2U_M31, DEV)       # sized for 100 nonzeros, not 50 115
+    out = mh.minhash_signatures(_to_dev(rp), _to_dev(col), D, k, 8, mh.FAMILY_2U_M31, _to_dev(c), workspace=ws)
+    assert mh.status(ws) == -6
+    ws = mh.alloc_workspace(len(nnz), int(nnz.sum()), k, mh.FAMILY_2U_M31, DEV)
+    out = mh.minhash_signatures(_to_dev(rp), _to_dev(col), D, k, 8, mh.FAMILY_2U_M31, _to_dev(c), workspace=ws)
+    assert mh.status(ws) == 0
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
 def test_profiled_entry_point_gives_the_same_bits_and_a_duration():
     w = W.WORKLOADS["tiny_2u"]
     nnz = w.nnz()
