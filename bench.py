@@ -87,6 +87,76 @@ def cpu_baseline(w: W.Workload, params: np.ndarray, target_evals_per_core: float
     return rec, n_sample, sig
 
 
+def stream_mode(args, w, params_np, cpu_rec, n_sample, cpu_sig) -> int:
+    """The heavy-tailed workload end to end: batches resident in pinned host memory,
+    H2D copy / kernels / D2H copy overlapped on three streams."""
+    import torch
+    from paper_1205_2958_amd import minhash as mh
+
+    dev = torch.device("cuda:0")
+    n_batches = args.batches or w.n_batches()
+    params = torch.from_numpy(params_np.view(np.int64)).to(dev)
+    batches, total_nnz, total_rows, max_nnz = [], 0, 0, 0
+    t0 = time.perf_counter()
+    # Pinned host memory on the GPU box is capped near 64 GiB, less than the 80 GB of
+    # indices of all ten batches: the first `distinct` batches are staged, later ones
+    # re-send the staged bytes of batch (i mod distinct).  Rates are unaffected; the
+    # parity tests cover the first and the last batch with their own data.
+    distinct = min(n_batches, args.distinct_batches)
+    for bi in range(n_batches):
+        if bi >= distinct:
+            rp_h, col_h = batches[bi % distinct]
+            batches.append((rp_h, col_h))
+            total_nnz += sum(p.numel() for p in col_h)
+            total_rows += rp_h.numel() - 1
+            continue
+        nnz = w.nnz(bi)
+        rp_np = W.row_ptr_from_nnz(nnz)
+        col = W.csr_indices_torch(nnz, w.D, w.data_seed + bi, dev)
+        piece = 1 << 28                     # 1 GiB pieces: the pinned allocator rounds sizes up to powers of two
+        col_h = []
+        for at in range(0, col.numel(), piece):
+            h = torch.empty(min(piece, col.numel() - at), dtype=torch.int32, pin_memory=True)
+            h.copy_(col[at: at + h.numel()])
+            col_h.append(h)
+        del col
+        rp_h = torch.from_numpy(rp_np).pin_memory()
+        batches.append((rp_h, col_h))
+        total_nnz += int(rp_np[-1])
+        total_rows += len(nnz)
+        max_nnz = max(max_nnz, int(rp_np[-1]))
+        print("batch %d staged in pinned host memory: %d rows, %d nonzeros" % (bi, len(nnz), int(rp_np[-1])),
+              file=sys.stderr, flush=True)
+    torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t0
+    mh.stream_batches(batches[:1], w.D, w.k, w.b, w.family, params, w.batch_rows, max_nnz)     # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    outs = mh.stream_batches(batches, w.D, w.k, w.b, w.family, params, w.batch_rows, max_nnz)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    evals = float(total_nnz) * w.k
+    parity = None
+    if cpu_sig is not None:
+        n_cmp = min(n_sample, outs[0].shape[0])
+        parity = bool(np.array_equal(outs[0][:n_cmp].numpy(), cpu_sig[:n_cmp]))
+    rec = {
+        "metric": "hash-evals/sec (nnz*k), host-resident batches streamed over PCIe",
+        "value": evals / dt, "unit": "hash-evals/s", "n_gpus": 1, "steps": 1, "warmup": 1, "ms_per_step": dt * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u32/u64 integer",
+        "data": "synthetic (seeded; stands in for the paper's expanded rcv1 shape)",
+        "config": {"workload": w.name + " streamed", "n_rows": total_rows, "nnz": total_nnz, "D": w.D, "k": w.k, "b": w.b,
+                   "family": w.family, "batches": n_batches, "distinct_batches_in_pinned_memory": distinct,
+                   "setup_s": round(gen_s, 1)},
+        "rows_per_s": total_rows / dt,
+        "h2d_GBps_sustained": (4.0 * total_nnz + 8.0 * total_rows) / dt / 1e9,
+        "roofline": None, "cpu_baseline": cpu_rec,
+        "parity_sample_rows": n_sample if parity is not None else 0, "parity_sample_ok": parity,
+    }
+    print(json.dumps(rec))
+    return 0 if parity in (None, True) else 1
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,6 +167,13 @@ def main() -> int:
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS rows (debugging; invalidates the metric)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle work per core for the CPU baseline (0: skip)")
     ap.add_argument("--perm-ld", type=int, default=0)
+    ap.add_argument("--stream", action="store_true",
+                    help="huge_2u_m61 only: all 10 batches of 200 000 rows start in pinned host memory and are streamed "
+                         "host-to-device, hashed and copied back with copies and kernels overlapped; the timed region "
+                         "runs from the first copy to the last signature on the host (PCIe-inclusive, reported apart)")
+    ap.add_argument("--batches", type=int, default=0, help="with --stream: number of batches (default: all)")
+    ap.add_argument("--distinct-batches", type=int, default=7,
+                    help="with --stream: batches held in pinned host memory (8 GB each)")
     ap.add_argument("--calib", action="store_true",
                     help="also launch one plain streaming kernel of known size (reads 1 GiB, writes 1 GiB) so that "
                          "FETCH_SIZE / WRITE_SIZE counters of a profiler run can be scaled")
@@ -128,6 +205,9 @@ def main() -> int:
         return 2
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+
+    if args.stream:
+        return stream_mode(args, w, params_np, cpu_rec, n_sample, cpu_sig)
 
     nnz = w.nnz(0)
     if args.rows:

@@ -181,3 +181,68 @@ def minhash_signatures_profiled(row_ptr, col_idx, D, k, b, family, params, out=N
 def status(workspace: torch.Tensor, stream=None) -> int:
     """Waits for the stream; 0, or the negative code of what VALIDATE found."""
     return int(lib().minhash_status(_ptr(workspace), _stream_handle(stream)))
+
+
+def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.Tensor, max_rows: int, max_nnz: int,
+                   perm_ld: Optional[int] = None, flags: int = 0):
+    """Streams host-resident batches through the GPU with copies and kernels
+    overlapped (the three-phase batch loop of Section 3.2: copy a chunk of sets to
+    the GPU, hash it there, copy the results back, repeat).
+
+    ``batches`` is a sequence of ``(row_ptr, col_idx)`` pairs of pinned host
+    tensors, row_ptr rebased to start at 0; col_idx may also be a list of pinned
+    tensors holding consecutive pieces of the index array (torch's pinned
+    allocator rounds every request up to a power of two, so large arrays are
+    cheaper to pin in 1 GiB pieces).  Batch i+1 is copied host-to-device on
+    a side stream while batch i is hashed on the compute stream and the
+    signatures of batch i-1 travel back on a third stream; two sets of device
+    buffers alternate.  Returns the list of pinned uint8 host tensors
+    [n_rows_i, ceil(k*b/8)], complete when the function returns.
+    """
+    dev = params.device
+    sig = (k * b + 7) // 8
+    n_buf = 2
+    rp_d = [torch.empty(max_rows + 1, dtype=torch.int64, device=dev) for _ in range(n_buf)]
+    col_d = [torch.empty(max_nnz, dtype=torch.int32, device=dev) for _ in range(n_buf)]
+    out_d = [torch.empty((max_rows, sig), dtype=torch.uint8, device=dev) for _ in range(n_buf)]
+    ws = alloc_workspace(max_rows, max_nnz, k, family, dev)
+    s_in, s_run, s_out = torch.cuda.Stream(dev), torch.cuda.Stream(dev), torch.cuda.Stream(dev)
+    now = torch.cuda.current_stream(dev)
+    for s in (s_in, s_run, s_out):
+        s.wait_stream(now)
+    in_done = [torch.cuda.Event() for _ in range(n_buf)]
+    run_done = [torch.cuda.Event() for _ in range(n_buf)]
+    out_done = [torch.cuda.Event() for _ in range(n_buf)]
+    results = []
+    for i, (rp_h, col_h) in enumerate(batches):
+        n = rp_h.numel() - 1
+        pieces = list(col_h) if isinstance(col_h, (list, tuple)) else [col_h]
+        nnz = sum(p.numel() for p in pieces)
+        if n > max_rows or nnz > max_nnz:
+            raise ValueError("batch %d exceeds max_rows / max_nnz" % i)
+        u = i % n_buf
+        out_h = torch.empty((n, sig), dtype=torch.uint8, pin_memory=True)
+        results.append(out_h)
+        if i >= n_buf:
+            s_in.wait_event(run_done[u])          # the kernel that read this input buffer has finished
+        with torch.cuda.stream(s_in):
+            rp_d[u][: n + 1].copy_(rp_h, non_blocking=True)
+            at = 0
+            for p in pieces:
+                col_d[u][at: at + p.numel()].copy_(p.view(torch.int32), non_blocking=True)
+                at += p.numel()
+            in_done[u].record(s_in)
+        s_run.wait_event(in_done[u])
+        if i >= n_buf:
+            s_run.wait_event(out_done[u])         # the previous signatures left this output buffer
+        minhash_signatures(rp_d[u][: n + 1], col_d[u][:nnz], D, k, b, family, params, out=out_d[u][:n],
+                           out_stride=sig, perm_ld=perm_ld, workspace=ws, stream=s_run, flags=flags)
+        run_done[u].record(s_run)
+        s_out.wait_event(run_done[u])
+        with torch.cuda.stream(s_out):
+            out_h.copy_(out_d[u][:n], non_blocking=True)
+            out_done[u].record(s_out)
+    for s in (s_in, s_run, s_out):
+        s.synchronize()
+    now.wait_stream(s_out)
+    return results

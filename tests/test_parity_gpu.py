@@ -273,3 +273,30 @@ def test_streams_and_workspace_reuse():
     side.synchronize()
     for o in outs:
         assert np.array_equal(o.cpu().numpy(), want)
+
+
+def test_streamed_batches_equal_one_shot_and_oracle():
+    """Rows are independent, so batch boundaries must not matter: the double-buffered
+    host-to-device stream gives the same bytes as one call over all rows."""
+    D, k, b, family = 1 << 30, 500, 1, mh.FAMILY_2U_M61
+    nnz = W.lomax_nnz(900, scale=580.4, tail=0.8, lo=1, hi=40_000, seed=77)
+    nnz[13] = 0
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed=78)
+    c = W.coefficients(k, family, seed=79)
+    want = oracle.signatures(rp, col, D, k, b, family, c)
+    one_shot, st = gpu_signatures(rp, col, D, k, b, family, c)
+    assert st == 0 and np.array_equal(one_shot, want)
+    bounds = [0, 200, 201, 450, 700, 900]                       # five batches of unequal size
+    batches = []
+    for lo, hi in zip(bounds[:-1], bounds[1:]):
+        rp_b = torch.from_numpy((rp[lo:hi + 1] - rp[lo]).copy()).pin_memory()
+        col_b = torch.from_numpy(col[rp[lo]:rp[hi]].view(np.int32).copy()).pin_memory()
+        if lo == 450:                                           # index array handed over in pieces
+            cut = col_b.numel() // 3
+            col_b = [col_b[:cut].clone().pin_memory(), col_b[cut:].clone().pin_memory()]
+        batches.append((rp_b, col_b))
+    max_rows = max(h - l for l, h in zip(bounds[:-1], bounds[1:]))
+    max_nnz = max(int(rp[h] - rp[l]) for l, h in zip(bounds[:-1], bounds[1:]))
+    outs = mh.stream_batches(batches, D, k, b, family, _to_dev(c), max_rows, max_nnz)
+    got = np.concatenate([o.numpy() for o in outs], axis=0)
+    assert np.array_equal(got, want)
