@@ -40,6 +40,10 @@ SLOTS_PER_EVAL = {
 }
 ALU_PEAK_SLOTS = 256 * 4 * 16 * 2.4e9                      # 39.3e12 lane-slots/s
 HBM_PEAK = 8.0e12
+# HBM bytes per launch of the dominant kernel on the full workload, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for a plain 1 GiB streaming kernel
+# (profiles/mh_hash_kernel_2u_m31__large_2u.txt, profiles/mh_perm_kernel__perm_table.txt).
+MEASURED_TRAFFIC_BYTES = {"large_2u": 5.954e9, "perm_table": 1.1653e12}
 
 
 def _oracle_worker(args):
@@ -280,6 +284,8 @@ def main() -> int:
                 "model": "%.1f issue slots per hash evaluation; peak = 256 CU x 4 SIMD x 16 lanes x 2.4 GHz "
                          "full-issue lane-slots/s (simple 2-operand integer ops count 1/2)" % slots}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    if not args.rows:
+        roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name)
 
     rec = {
         "metric": "hash-evals/sec (nnz*k)",
