@@ -294,6 +294,7 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 template <bool POW2>
 struct Pol2U31 {
     static constexpr int NW = 1;
+    static constexpr int MIN_WAVES = 6;        // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool TRACK_MAX = POW2;
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
@@ -314,6 +315,7 @@ struct Pol2U31 {
 template <bool POW2>
 struct Pol4U31 {
     static constexpr int NW = 3;
+    static constexpr int MIN_WAVES = 4;
     static constexpr bool TRACK_MAX = POW2;
     using Fn = Fn4U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
@@ -333,16 +335,14 @@ struct Pol4U31 {
         return hash_4u31<false>(f, p, md);
     }
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                const uint32_t* wb, const ModD& md, uint64_t D)
-    {
-        pair_generic<Pol4U31<POW2>>(fn, m, wa, wb, md, D);
-    }
+                                                const uint32_t* wb, const ModD& md, uint64_t D);
     static constexpr int DEG = 4;
 };
 
 template <bool POW2>
 struct Pol2U61 {
     static constexpr int NW = 1;
+    static constexpr int MIN_WAVES = 6;
     static constexpr bool TRACK_MAX = false;
     using Fn = Fn2U61;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
@@ -423,6 +423,72 @@ __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
 }
 
+// 4U, p = 2^31-1, power-of-two D, same idea: three chained multiply-adds per
+// evaluation are issued function-major so that each waits for a result that is
+// 16 instructions old; the fold of nonzero A overlaps the last multiply-adds of
+// nonzero B.  Arithmetic of hash_compl_4u31 (mh_arith.h), instruction for instruction.
+__device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
+                                               const uint32_t* wa, const uint32_t* wb, uint32_t mask, uint32_t p31)
+{
+    uint64_t aa[HASH_FPL], ab[HASH_FPL], cy;
+    uint32_t ya[HASH_FPL], yb[HASH_FPL], ua[HASH_FPL], ub[HASH_FPL], va[HASH_FPL], vb[HASH_FPL];
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %4" : "=v"(aa[g]), "=s"(cy) : "v"(fn[g].c1), "v"(wa[0]), "v"(fn[g].add));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %4" : "=v"(ab[g]), "=s"(cy) : "v"(fn[g].c1), "v"(wb[0]), "v"(fn[g].add));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(aa[g]), "=s"(cy) : "v"(fn[g].c2), "v"(wa[1]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(ab[g]), "=s"(cy) : "v"(fn[g].c2), "v"(wb[1]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(aa[g]), "=s"(cy) : "v"(fn[g].c3), "v"(wa[2]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(ab[g]), "=s"(cy) : "v"(fn[g].c3), "v"(wb[2]));
+        asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(ya[g]) : "v"((uint32_t)aa[g]));
+        asm volatile("v_and_b32 %0, %1, %2" : "=v"(ua[g]) : "v"((uint32_t)(aa[g] >> 32)), "v"(p31));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(va[g]) : "v"((uint32_t)(aa[g] >> 32)));
+        asm volatile("v_add_u32 %0, %0, %1" : "+v"(ya[g]) : "v"(ua[g]));
+        asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(yb[g]) : "v"((uint32_t)ab[g]));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_add_u32 %0, %0, %1" : "+v"(ya[g]) : "v"(va[g]));
+        asm volatile("v_and_b32 %0, %1, %2" : "=v"(ub[g]) : "v"((uint32_t)(ab[g] >> 32)), "v"(p31));
+        asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(vb[g]) : "v"((uint32_t)(ab[g] >> 32)));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_ashrrev_i32 %0, 31, %1" : "=v"(ua[g]) : "v"(ya[g]));
+        asm volatile("v_add_u32 %0, %0, %1" : "+v"(yb[g]) : "v"(ub[g]));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_sub_u32 %0, %1, %0" : "+v"(ya[g]) : "v"(ua[g]));
+        asm volatile("v_add_u32 %0, %0, %1" : "+v"(yb[g]) : "v"(vb[g]));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_and_b32 %0, %0, %1" : "+v"(ya[g]) : "v"(mask));
+        asm volatile("v_ashrrev_i32 %0, 31, %1" : "=v"(ub[g]) : "v"(yb[g]));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_sub_u32 %0, %1, %0" : "+v"(yb[g]) : "v"(ub[g]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(yb[g]) : "v"(mask));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
+}
+
 template <>
 __device__ __forceinline__ void Pol2U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                     const uint32_t* wb, const ModD& md, uint64_t)
@@ -434,6 +500,19 @@ __device__ __forceinline__ void Pol2U31<false>::pair(const Fn (&fn)[HASH_FPL], u
                                                      const uint32_t* wb, const ModD& md, uint64_t D)
 {
     pair_generic<Pol2U31<false>>(fn, m, wa, wb, md, D);
+}
+
+template <>
+__device__ __forceinline__ void Pol4U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+                                                    const uint32_t* wb, const ModD& md, uint64_t)
+{
+    pair_4u31_pow2(fn, m, wa, wb, md.mask, md.M);      // md.M carries 2^31-1 in a vector register for this policy
+}
+template <>
+__device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+                                                     const uint32_t* wb, const ModD& md, uint64_t D)
+{
+    pair_generic<Pol4U31<false>>(fn, m, wa, wb, md, D);
 }
 
 // ------------------------------------------------------------------ staging
@@ -452,7 +531,7 @@ __device__ __forceinline__ void load_tile(const uint32_t* col, int64_t begin, ui
 
 // ------------------------------------------------------------------ the hash kernel
 template <class Pol>
-__global__ __launch_bounds__(BLOCK) void mh_hash_kernel(KArgs a)
+__global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_WAVES, 8))) void mh_hash_kernel(KArgs a)
 {
     __shared__ uint32_t s_tile[WAVES_PER_BLOCK][Pol::NW][TILE];
     __shared__ uint32_t s_mins[WAVES_PER_BLOCK][HASH_FTILE];
@@ -471,6 +550,7 @@ __global__ __launch_bounds__(BLOCK) void mh_hash_kernel(KArgs a)
     const uint64_t n_units = (uint64_t)n_items * (uint64_t)a.n_ftiles;
 
     ModD md = a.md;
+    if (md.pow2) md.M = P31;           // unused by the mask path; the 4U fold wants 2^31-1 in a vector register
     md.mask = in_vgpr(md.mask);
     md.D = in_vgpr(md.D);
     md.M = in_vgpr(md.M);
