@@ -37,6 +37,7 @@ SLOTS_PER_EVAL = {
     W.FAMILY_2U_M31: 1.0 + 5 * 0.5 + 0.5,                  # mad; shr,add,ashr,sub,and; half a max3
     W.FAMILY_4U_M31: 3.0 + 8 * 0.5 + 0.5,                  # 3 mad; shr,and,shr,add,add,ashr,sub,and; half a max3
     W.FAMILY_2U_M61: 2.0 + 1.0 + 2.0 + 7 * 0.5 + 0.5,      # 2 mad; funnel shift; add/addc; 7 simple; half a min3
+    W.FAMILY_2U_MS32: 1.0 + 0.5 + 0.5,                      # mad; and; half a min3
 }
 ALU_PEAK_SLOTS = 256 * 4 * 16 * 2.4e9                      # 39.3e12 lane-slots/s
 HBM_PEAK = 8.0e12
@@ -167,7 +168,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large_2u", choices=["tiny_2u", "large_2u", "large_4u", "perm_table",
-                                                                 "huge_2u_m61"])
+                                                                 "huge_2u_m61", "large_2u_ms32"])
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS rows (debugging; invalidates the metric)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle work per core for the CPU baseline (0: skip)")
     ap.add_argument("--perm-ld", type=int, default=0)
@@ -198,7 +199,8 @@ def main() -> int:
     cpu_rec, n_sample, cpu_sig = None, 0, None
     if args.cpu_seconds > 0 and family != W.FAMILY_PERM:
         procs = max(1, min(16, os.cpu_count() or 1))
-        rate_guess = {W.FAMILY_2U_M31: 3.0e7, W.FAMILY_4U_M31: 1.2e7, W.FAMILY_2U_M61: 2.0e7}[family]
+        rate_guess = {W.FAMILY_2U_M31: 3.0e7, W.FAMILY_4U_M31: 1.2e7, W.FAMILY_2U_M61: 2.0e7,
+                      W.FAMILY_2U_MS32: 6.0e7}[family]
         cpu_rec, n_sample, cpu_sig = cpu_baseline(w, params_np, rate_guess * args.cpu_seconds, procs)
 
     import torch

@@ -28,7 +28,11 @@ enum {
                             Mersenne reduction as in Section 3.4               */
     MINHASH_2U_M61 = 2,  /* 2U with p = 2^61-1 (Section 3.4, last paragraph)   */
     MINHASH_4U_M61 = 3,  /* not implemented: returns MINHASH_ERR_FAMILY        */
-    MINHASH_PERM   = 4   /* explicit D x k permutation matrix, Section 1.5     */
+    MINHASH_PERM   = 4,  /* explicit D x k permutation matrix, Section 1.5     */
+    MINHASH_2U_MS32 = 5, /* ((c0 + c1 t) mod 2^32) mod 2^s, D = 2^s, c1 odd: the multiply-shift 2U of
+                            Section 3.3, eq. "eqn_h_s", as printed (lowest s bits)              */
+    MINHASH_2U_MS32_HIGH = 6 /* the same 32-bit value, of which the HIGHEST s bits are kept (the form of
+                            the scheme Section 3.3 cites); needs D >= 2                         */
 };
 
 /* Return codes. */
@@ -41,7 +45,8 @@ enum {
     MINHASH_ERR_STRIDE    = -5,  /* out_stride < ceil(k*b/8) or perm_ld < k                    */
     MINHASH_ERR_WORKSPACE = -6,  /* workspace null, misaligned or smaller than required        */
     MINHASH_ERR_HIP       = -7,  /* a HIP runtime call failed; see minhash_last_hip_error()    */
-    MINHASH_ERR_COEFF     = -8,  /* minhash_check_coeffs: a coefficient is >= p                */
+    MINHASH_ERR_COEFF     = -8,  /* minhash_check_coeffs: a coefficient is >= p (multiply-shift:
+                                    >= 2^32, or the multiplier is even)                        */
     MINHASH_ERR_DATA      = -9   /* minhash_status: VALIDATE found an index >= D or a
                                     decreasing row_ptr                                         */
 };
@@ -68,14 +73,16 @@ enum {
  *   col_idx   device, uint32 feature indices in [0, D); any order, duplicates
  *             allowed (the result depends only on the set)
  *   n_rows    0 <= n_rows < 2^31; 0 is a successful no-op
- *   D         size of the feature universe, 1 <= D <= 2^32, D < p for hash
- *             families.  D a power of two takes a faster path
+ *   D         size of the feature universe, 1 <= D <= 2^32, D < p for the
+ *             Mersenne families, a power of two for the multiply-shift families.
+ *             D a power of two takes a faster path
  *   k, b      number of functions (1..MINHASH_MAX_K), bits kept (1..32; b = 32
  *             stores the full minima as little-endian uint32)
  *   family    one of MINHASH_*
  *   params    device.  Hash families: uint64 c[k][deg], deg = 2 (2U) or 4 (4U),
  *             c[j][i] multiplies t^i and lies in [0, p) (the paper numbers the
- *             same coefficients a_{i+1,j}).  MINHASH_PERM: uint32
+ *             same coefficients a_{i+1,j}); multiply-shift: c[j][0] < 2^32 and
+ *             c[j][1] < 2^32 odd.  MINHASH_PERM: uint32
  *             table[D][perm_ld], index-major, table[t][j] = pi_j(t)
  *   perm_ld   MINHASH_PERM: row pitch of the table in elements, >= k; else 0
  *   out       device, n_rows*out_stride bytes, written completely
@@ -120,7 +127,8 @@ int minhash_signatures_profiled(const int64_t *row_ptr, const uint32_t *col_idx,
 size_t minhash_workspace_bytes(int64_t n_rows, int64_t nnz_upper_bound, int32_t k, int32_t family);
 
 /* Host-side check that every coefficient of host_coeffs[k][deg] is below the
- * family's prime (Section 2: coefficients are drawn from {0, ..., p-1}).
+ * family's prime (Section 2: coefficients are drawn from {0, ..., p-1}), or, for
+ * the multiply-shift families, below 2^32 with an odd multiplier (Section 3.3).
  * Returns MINHASH_OK, MINHASH_ERR_COEFF, or an argument error. */
 int minhash_check_coeffs(const uint64_t *host_coeffs, int32_t k, int32_t family);
 

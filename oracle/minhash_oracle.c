@@ -16,6 +16,11 @@
  *     ((a1 + a2 t + a3 t^2 + a4 t^3) mod p) mod D  (eq. "eqn_h_4U"), or the j-th
  *     column of an explicit "fully random permutation matrix" of size D x k
  *     (Section 1.5);
+ *   - or h_j is the multiply-shift form  ((a1 + a2 t) mod 2^32) mod 2^s  with
+ *     D = 2^s and a2 odd (Section 3.3, eq. "eqn_h_s"), which is what the paper
+ *     times as "2U".  The paper prints "mod 2^s" (the lowest s bits) while citing
+ *     a scheme that keeps the highest s bits of the 32-bit value; both are here,
+ *     as two families;
  *   - only the lowest b bits of every minimum are kept (Section 1.1), and a
  *     data vector becomes k b-bit integers (Section 1.1, after eq. "eqn_R_b").
  *
@@ -46,7 +51,9 @@ enum {
     ORACLE_4U_M31 = 1,
     ORACLE_2U_M61 = 2,
     ORACLE_4U_M61 = 3,
-    ORACLE_PERM = 4
+    ORACLE_PERM = 4,
+    ORACLE_2U_MS32 = 5,        /* multiply-shift 2U, lowest s bits  */
+    ORACLE_2U_MS32_HIGH = 6    /* multiply-shift 2U, highest s bits */
 };
 
 #define ORACLE_EMPTY_MIN 0xFFFFFFFFu
@@ -76,6 +83,16 @@ static uint64_t hash_location(const uint64_t *c, int deg, uint64_t p, uint64_t D
     return (uint64_t)(acc % (u128)D);
 }
 
+/* Section 3.3, eq. "eqn_h_s": ((c[0] + c[1] t) mod 2^32) mod 2^s with D = 2^s.
+ * high != 0 keeps the s highest bits of the 32-bit value instead of the s lowest. */
+static uint64_t hash_multiply_shift(const uint64_t *c, uint64_t D, uint64_t t, int high)
+{
+    u128 two32 = (u128)1 << 32;
+    u128 v = ((u128)c[0] + (u128)c[1] * (u128)t) % two32;
+    if (!high) return (uint64_t)(v % (u128)D);
+    return (uint64_t)(v / (two32 / (u128)D));
+}
+
 /*
  * Full (untruncated) minima: minima[i*k + j] = min over t in row i of h_j(t),
  * or 0xFFFFFFFF for an empty row.  Host pointers throughout.
@@ -91,8 +108,12 @@ int minhash_minima_oracle(const int64_t *row_ptr, const uint32_t *col_idx, int64
 
     uint64_t p = 0;
     int deg = 0;
+    int multiply_shift = (family == ORACLE_2U_MS32 || family == ORACLE_2U_MS32_HIGH);
     if (family == ORACLE_PERM) {
         if (perm_ld < k) return -5;
+    } else if (multiply_shift) {
+        if ((D & (D - 1)) != 0) return -3;                 /* D = 2^s */
+        if (family == ORACLE_2U_MS32_HIGH && D < 2) return -3;
     } else {
         if (family_prime_degree(family, &p, &deg) != 0) return -2;
         if (D >= p) return -3;
@@ -108,6 +129,9 @@ int minhash_minima_oracle(const int64_t *row_ptr, const uint32_t *col_idx, int64
                 if (family == ORACLE_PERM) {
                     const uint32_t *table = (const uint32_t *)params;
                     v = table[(size_t)t * (size_t)perm_ld + (size_t)j];
+                } else if (multiply_shift) {
+                    const uint64_t *coeffs = (const uint64_t *)params;
+                    v = hash_multiply_shift(coeffs + (size_t)j * 2, D, t, family == ORACLE_2U_MS32_HIGH);
                 } else {
                     const uint64_t *coeffs = (const uint64_t *)params;
                     v = hash_location(coeffs + (size_t)j * (size_t)deg, deg, p, D, t);

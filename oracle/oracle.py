@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "minhash_oracle.c")
 _LIB = os.path.join(_HERE, "libminhash_oracle.so")
 
-FAMILY_2U_M31, FAMILY_4U_M31, FAMILY_2U_M61, FAMILY_4U_M61, FAMILY_PERM = range(5)
+FAMILY_2U_M31, FAMILY_4U_M31, FAMILY_2U_M61, FAMILY_4U_M61, FAMILY_PERM, FAMILY_2U_MS32, FAMILY_2U_MS32_HIGH = range(7)
 EMPTY_MIN = 0xFFFFFFFF
 
 

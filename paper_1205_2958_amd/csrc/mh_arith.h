@@ -254,4 +254,26 @@ MH_HD uint32_t hash_2u61(const Fn2U61& f, uint32_t t, const ModD& md, uint64_t D
     return (uint32_t)(residue_wide_2u61(f, t) % D);
 }
 
+// ---------------------------------------------------------------- multiply-shift 2U (Section 3.3, eq. eqn_h_s)
+// ((c0 + c1 t) mod 2^32) mod 2^s: the low word of one multiply-add, then a mask
+// (lowest s bits, as the paper prints it) or a shift (highest s bits, the form of
+// the scheme it cites).  The integer overflow does the "mod 2^32".
+struct Fn2UMS32 {
+    uint32_t c1;
+    uint64_t add;    // c0, widened: the addend of the 64-bit multiply-add whose low word is used
+};
+MH_HD Fn2UMS32 prep_2ums32(uint64_t c0, uint64_t c1)
+{
+    Fn2UMS32 f;
+    f.c1 = (uint32_t)c1;
+    f.add = (uint64_t)(uint32_t)c0;
+    return f;
+}
+template <bool HIGH>
+MH_HD uint32_t hash_2ums32(const Fn2UMS32& f, uint32_t t, uint32_t mask, uint32_t shift)
+{
+    uint32_t v = (uint32_t)((uint64_t)f.c1 * t + f.add);
+    return HIGH ? (v >> shift) : (v & mask);      // shift = 32 - s, 0 <= shift <= 31
+}
+
 }  // namespace mh

@@ -489,6 +489,50 @@ __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
 }
 
+// multiply-shift 2U: md.mask = D - 1, md.M = 32 - log2(D)
+template <bool HIGH>
+struct Pol2UMS32 {
+    static constexpr int NW = 1;
+    static constexpr int MIN_WAVES = 6;
+    static constexpr bool TRACK_MAX = false;
+    using Fn = Fn2UMS32;
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    {
+        return valid ? prep_2ums32(c[0], c[1]) : prep_2ums32(0, 0);
+    }
+    static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
+    static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t)
+    {
+        return hash_2ums32<HIGH>(f, w[0], md.mask, md.M);
+    }
+    // stage-major order for the same reason as in pair_2u31_pow2: 16 multiply-adds,
+    // 16 masks or shifts, 8 three-operand minima
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+                                                const uint32_t* wb, const ModD& md, uint64_t)
+    {
+        uint64_t pa[HASH_FPL], pb[HASH_FPL], cy;
+        uint32_t xa[HASH_FPL], xb[HASH_FPL];
+#pragma unroll
+        for (int g = 0; g < HASH_FPL; ++g)
+            asm volatile("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(pa[g]), "=s"(cy) : "v"(fn[g].c1), "v"(wa[0]), "v"(fn[g].add));
+#pragma unroll
+        for (int g = 0; g < HASH_FPL; ++g) {
+            asm volatile("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(pb[g]), "=s"(cy) : "v"(fn[g].c1), "v"(wb[0]), "v"(fn[g].add));
+            if (HIGH) asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(xa[g]) : "v"(md.M), "v"((uint32_t)pa[g]));
+            else asm volatile("v_and_b32 %0, %1, %2" : "=v"(xa[g]) : "v"(md.mask), "v"((uint32_t)pa[g]));
+        }
+#pragma unroll
+        for (int g = 0; g < HASH_FPL; ++g) {
+            if (HIGH) asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(xb[g]) : "v"(md.M), "v"((uint32_t)pb[g]));
+            else asm volatile("v_and_b32 %0, %1, %2" : "=v"(xb[g]) : "v"(md.mask), "v"((uint32_t)pb[g]));
+        }
+#pragma unroll
+        for (int g = 0; g < HASH_FPL; ++g)
+            asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
+    }
+    static constexpr int DEG = 2;
+};
+
 template <>
 __device__ __forceinline__ void Pol2U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                     const uint32_t* wb, const ModD& md, uint64_t)
@@ -550,7 +594,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
     const uint64_t n_units = (uint64_t)n_items * (uint64_t)a.n_ftiles;
 
     ModD md = a.md;
-    if (md.pow2) md.M = P31;           // unused by the mask path; the 4U fold wants 2^31-1 in a vector register
+    if (Pol::NW == 3 && md.pow2) md.M = P31;   // the 4U fold wants 2^31-1 in a vector register; the mask path does not use M
     md.mask = in_vgpr(md.mask);
     md.D = in_vgpr(md.D);
     md.M = in_vgpr(md.M);
@@ -815,9 +859,13 @@ int hip_fail(hipError_t e, const char* what)
     return MINHASH_ERR_HIP;
 }
 
+bool is_multiply_shift(int32_t family) { return family == MINHASH_2U_MS32 || family == MINHASH_2U_MS32_HIGH; }
+
 bool family_prime(int32_t family, uint64_t* p, int* deg)
 {
     switch (family) {
+    case MINHASH_2U_MS32:
+    case MINHASH_2U_MS32_HIGH: *p = 1ull << 32; *deg = 2; return true;     // modulus 2^32, not a prime
     case MINHASH_2U_M31: *p = P31; *deg = 2; return true;
     case MINHASH_4U_M31: *p = P31; *deg = 4; return true;
     case MINHASH_2U_M61: *p = P61; *deg = 2; return true;
@@ -875,7 +923,11 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     if (rc != MINHASH_OK) return rc;
     if (b < 1 || b > 32) return MINHASH_ERR_KB;
     if (D < 1 || D > (1ull << 32)) return MINHASH_ERR_D;
-    if (family != MINHASH_PERM) {
+    if (is_multiply_shift(family)) {
+        if ((D & (D - 1)) != 0) return MINHASH_ERR_D;                   // D = 2^s
+        if (family == MINHASH_2U_MS32_HIGH && D < 2) return MINHASH_ERR_D;
+        if (perm_ld != 0) return MINHASH_ERR_STRIDE;
+    } else if (family != MINHASH_PERM) {
         uint64_t p; int deg;
         family_prime(family, &p, &deg);
         if (D >= p) return MINHASH_ERR_D;
@@ -912,6 +964,11 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     a.scratch = reinterpret_cast<uint32_t*>(ws + L.scratch_off);
     a.D = D; a.cap_items = L.cap_items; a.cap_split = L.cap_split; a.cap_parts = L.cap_parts;
     a.md = make_mod_d(D);
+    if (is_multiply_shift(family)) {
+        int sbits = 0;
+        while ((1ull << sbits) < D) ++sbits;
+        a.md.M = (uint32_t)(32 - sbits);                                // shift that keeps the s highest bits
+    }
     a.n_rows = n_rows; a.k = k; a.b = b;
     a.sig_bytes = (int32_t)sig_bytes;
     a.validate = (flags & MINHASH_FLAG_VALIDATE) ? 1u : 0u;
@@ -957,7 +1014,9 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         if (pow2 && D <= (1ull << 31)) launch_hash<Pol2U61<true>>(a, main_blocks, s);
         else launch_hash<Pol2U61<false>>(a, main_blocks, s);
         break;
-    default: {
+    case MINHASH_2U_MS32: launch_hash<Pol2UMS32<false>>(a, main_blocks, s); break;
+    case MINHASH_2U_MS32_HIGH: launch_hash<Pol2UMS32<true>>(a, main_blocks, s); break;
+    case MINHASH_PERM: {
         const bool vec4 = (perm_ld % 4 == 0) && (reinterpret_cast<uintptr_t>(params) % 16 == 0);
         static const int blocks_v = resident_blocks(mh_perm_kernel<true>, cus);
         static const int blocks_s = resident_blocks(mh_perm_kernel<false>, cus);
@@ -965,6 +1024,9 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         else hipLaunchKernelGGL(mh_perm_kernel<false>, dim3(blocks_s), dim3(BLOCK), 0, s, a);
         break;
     }
+    default:                                       // unreachable: the family was validated above
+        if (profiled) { hipEventDestroy(e0); hipEventDestroy(e1); }
+        return MINHASH_ERR_FAMILY;
     }
     if (profiled) hipEventRecord(e1, s);
     if (L.cap_split > 0) hipLaunchKernelGGL(mh_finalize_kernel, dim3(cus * 2), dim3(BLOCK), 0, s, a, ftile_size);
@@ -1020,6 +1082,9 @@ int minhash_check_coeffs(const uint64_t* host_coeffs, int32_t k, int32_t family)
     if (!host_coeffs) return MINHASH_ERR_ARG;
     for (int64_t i = 0; i < (int64_t)k * deg; ++i)
         if (host_coeffs[i] >= p) return MINHASH_ERR_COEFF;
+    if (is_multiply_shift(family))
+        for (int64_t j = 0; j < k; ++j)
+            if ((host_coeffs[2 * j + 1] & 1u) == 0) return MINHASH_ERR_COEFF;   // the multiplier must be odd
     return MINHASH_OK;
 }
 

@@ -18,6 +18,8 @@ FAMILY_4U_M31 = 1
 FAMILY_2U_M61 = 2
 FAMILY_4U_M61 = 3
 FAMILY_PERM = 4
+FAMILY_2U_MS32 = 5
+FAMILY_2U_MS32_HIGH = 6
 FLAG_VALIDATE = 1
 WORKSPACE_ALIGN = 256
 

@@ -35,6 +35,8 @@ FAMILY_4U_M31 = 1
 FAMILY_2U_M61 = 2
 FAMILY_4U_M61 = 3
 FAMILY_PERM = 4
+FAMILY_2U_MS32 = 5        # multiply-shift 2U of Section 3.3, lowest s bits
+FAMILY_2U_MS32_HIGH = 6   # the same, highest s bits
 
 _FEISTEL_ROUNDS = 6
 _MASK31 = 0x7FFFFFFF
@@ -201,7 +203,7 @@ def family_prime(family: int) -> int:
 
 def family_degree(family: int) -> int:
     """Number of coefficients per function (2 for 2U, 4 for 4U)."""
-    if family in (FAMILY_2U_M31, FAMILY_2U_M61):
+    if family in (FAMILY_2U_M31, FAMILY_2U_M61, FAMILY_2U_MS32, FAMILY_2U_MS32_HIGH):
         return 2
     if family in (FAMILY_4U_M31, FAMILY_4U_M61):
         return 4
@@ -209,8 +211,14 @@ def family_degree(family: int) -> int:
 
 
 def coefficients(k: int, family: int, seed: int) -> np.ndarray:
-    """uint64 [k, degree]; every coefficient uniform in {0, ..., p-1}."""
+    """uint64 [k, degree]; every coefficient uniform in {0, ..., p-1}.  For the
+    multiply-shift families: c0 uniform in [0, 2^32), c1 uniform over the odd
+    numbers below 2^32 (Section 3.3)."""
     rng = np.random.Generator(np.random.PCG64(seed))
+    if family in (FAMILY_2U_MS32, FAMILY_2U_MS32_HIGH):
+        c = rng.integers(0, 1 << 32, size=(k, 2), dtype=np.uint64)
+        c[:, 1] |= np.uint64(1)
+        return c
     p = family_prime(family)
     return rng.integers(0, p, size=(k, family_degree(family)), dtype=np.uint64)
 
@@ -315,6 +323,9 @@ WORKLOADS = {
                          dict(median=math.exp(7.721), sigma=1.0, lo=1, hi=50_000)),
     "perm_table": Workload("perm_table", 350_000, 1 << 24, FAMILY_PERM, 200, 4, 1002, 3004, "lognormal",
                            dict(median=math.exp(7.721), sigma=1.0, lo=1, hi=50_000)),
+    # the hash the paper itself times as "GPU 2U" (Section 3.3), on the webspam-shaped rows
+    "large_2u_ms32": Workload("large_2u_ms32", 350_000, 1 << 24, FAMILY_2U_MS32, 500, 8, 1002, 2006, "lognormal",
+                              dict(median=math.exp(7.721), sigma=1.0, lo=1, hi=50_000)),
     "huge_2u_m61": Workload("huge_2u_m61", 2_000_000, 1 << 30, FAMILY_2U_M61, 500, 1, 1005, 2005, "lomax",
                             dict(scale=580.4, tail=0.8, lo=1, hi=1_000_000), batch_rows=200_000),
 }

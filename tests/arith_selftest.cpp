@@ -135,6 +135,24 @@ int main()
             check61(D, c, t);
         }
     }
+    // multiply-shift 2U (Section 3.3): ((c0 + c1 t) mod 2^32) mod 2^s, lowest or highest s bits
+    for (int sbits = 0; sbits <= 32; ++sbits) {
+        uint64_t D = 1ull << sbits;
+        uint32_t mask = (uint32_t)(D - 1), shift = (uint32_t)(32 - sbits);
+        for (int i = 0; i < 20000; ++i) {
+            uint64_t c0 = rnd() & 0xFFFFFFFFull, c1 = (rnd() & 0xFFFFFFFFull) | 1ull;
+            if (i % 5 == 0) c0 = 0xFFFFFFFFull;
+            if (i % 7 == 0) c1 = 0xFFFFFFFFull;
+            uint32_t t = (uint32_t)(rnd() % D);
+            if (i % 11 == 0) t = (uint32_t)(D - 1);
+            u128 v = ((u128)c0 + (u128)c1 * t) % ((u128)1 << 32);
+            Fn2UMS32 f = prep_2ums32(c0, c1);
+            if (hash_2ums32<false>(f, t, mask, shift) != (uint64_t)(v % D)) FAIL("multiply-shift low s=%d", sbits);
+            if (sbits >= 1 && hash_2ums32<true>(f, t, mask, shift) != (uint64_t)(v / (((u128)1 << 32) / D)))
+                FAIL("multiply-shift high s=%d", sbits);
+            checks += 2;
+        }
+    }
     printf("OK %ld\n", checks);
     return 0;
 }

@@ -240,6 +240,53 @@ def pin_big_integer_cross_check(o):
                     assert got[r, j] == (poly % p) % D, (family, D, t, j)
 
 
+# ---------------------------------------------------------------- multiply-shift 2U (Section 3.3)
+FMS, FMS_HIGH = W.FAMILY_2U_MS32, W.FAMILY_2U_MS32_HIGH
+
+
+def pin_multiply_shift_against_numpy_uint32(o):
+    """Section 3.3, eq. eqn_h_s: ((a1 + a2 t) mod 2^32) mod 2^s.  NumPy's uint32
+    arithmetic wraps modulo 2^32 by itself, which is the overflow the paper relies
+    on; the lowest s bits are a mask, the highest s bits a shift."""
+    rng = np.random.Generator(np.random.PCG64(51))
+    for D in (2, 1 << 8, 1 << 24, 1 << 30, 1 << 32):
+        s_bits = D.bit_length() - 1
+        k = 20
+        c = W.coefficients(k, FMS, seed=52 + s_bits)
+        c[0] = (0xFFFFFFFF, 0xFFFFFFFF)
+        c[1] = (0, 1)
+        rows = _random_rows(rng, 40, D, 30) + [[0], [D - 1], [0, D - 1]]
+        rp, col = _csr(rows)
+        low = o.minima(rp, col, D, k, FMS, c)
+        high = o.minima(rp, col, D, k, FMS_HIGH, c)
+        c0 = c[:, 0].astype(np.uint32)[:, None]
+        c1 = c[:, 1].astype(np.uint32)[:, None]
+        for i, srow in enumerate(rows):
+            t = np.array(srow, dtype=np.uint32)[None, :]
+            with np.errstate(over="ignore"):
+                v = c0 + c1 * t                                   # uint32, wraps
+            assert np.array_equal(low[i], (v & np.uint32(D - 1)).min(axis=1)), (D, i)
+            assert np.array_equal(high[i], (v >> np.uint32(32 - s_bits)).min(axis=1) if s_bits else None), (D, i)
+
+
+def pin_multiply_shift_is_a_bijection_of_the_universe(o):
+    """With an odd multiplier the lowest-s-bits map t -> h(t) permutes [0, 2^s): over
+    single-element rows every location appears exactly once, and a row holding the
+    whole universe has minimum 0.  The identity multiplier gives h(t) = (c0 + t) mod D."""
+    D, k = 256, 6
+    c = W.coefficients(k, FMS, seed=53)
+    c[0] = (5, 1)
+    rp, col = _csr([[t] for t in range(D)] + [list(range(D))])
+    m = o.minima(rp, col, D, k, FMS, c)
+    for j in range(k):
+        assert sorted(m[:D, j].tolist()) == list(range(D))
+        assert m[D, j] == 0
+    assert m[:D, 0].tolist() == [(5 + t) % D for t in range(D)]
+    hi = o.minima(rp, col, D, 1, FMS_HIGH, np.array([[0, 1 << 24]], dtype=np.uint64) | np.uint64(0))
+    # multiplier 2^24 is even, hence not a legal draw, but the arithmetic is defined: (t * 2^24 mod 2^32) >> 24 = t
+    assert hi[:D, 0].tolist() == list(range(D))
+
+
 # ---------------------------------------------------------------- ranges, sentinel
 def pin_ranges_and_empty_rows(o):
     """Minima of non-empty rows lie in [0, D); an empty row gives 0xFFFFFFFF in every
@@ -411,6 +458,8 @@ FAST_PINS = [
     pin_small_coefficients_no_wrap,
     pin_4u_with_zero_high_terms_is_2u,
     pin_big_integer_cross_check,
+    pin_multiply_shift_against_numpy_uint32,
+    pin_multiply_shift_is_a_bijection_of_the_universe,
     pin_ranges_and_empty_rows,
     pin_lowest_bits_example,
     pin_bit_layout_by_hand,

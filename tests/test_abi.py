@@ -66,6 +66,18 @@ def test_coefficient_range_check():
         assert e.value.code == -8
     with pytest.raises(mh.MinhashError):
         mh.check_coeffs(np.zeros((4, 2), dtype=np.uint64), mh.FAMILY_PERM)
+    for fam in (mh.FAMILY_2U_MS32, mh.FAMILY_2U_MS32_HIGH):
+        c = W.coefficients(16, fam, seed=2)
+        mh.check_coeffs(c, fam)
+        bad = c.copy()
+        bad[5, 1] &= np.uint64(0xFFFFFFFE)                         # even multiplier
+        with pytest.raises(mh.MinhashError) as e:
+            mh.check_coeffs(bad, fam)
+        assert e.value.code == -8
+        bad = c.copy()
+        bad[2, 0] = 1 << 32                                        # constant term too wide
+        with pytest.raises(mh.MinhashError):
+            mh.check_coeffs(bad, fam)
 
 
 def _call(lib, n_rows=4, D=1 << 24, k=64, b=8, family=0, perm_ld=0, out_stride=64, ws=0x1000, ws_bytes=1 << 20,
@@ -85,6 +97,9 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert _call(lib, D=(1 << 32) + 1) == -3
     assert _call(lib, D=(1 << 31) - 1) == -3                          # D must be below p = 2^31 - 1
     assert _call(lib, D=(1 << 31), family=mh.FAMILY_2U_M31) == -3
+    assert _call(lib, family=mh.FAMILY_2U_MS32, D=1000) == -3         # multiply-shift needs D = 2^s
+    assert _call(lib, family=mh.FAMILY_2U_MS32_HIGH, D=1) == -3
+    assert _call(lib, family=mh.FAMILY_2U_MS32, D=1 << 32, n_rows=0) == 0
     assert _call(lib, k=0) == -4
     assert _call(lib, k=65537, out_stride=1 << 20) == -4
     assert _call(lib, b=0) == -4

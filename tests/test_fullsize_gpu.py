@@ -79,6 +79,7 @@ def _check_rows(w, nnz, rp_np, seed, col, params, params_np, out, rows):
     ("large_2u", 24, 3.0e8),
     ("large_4u", 16, 2.0e8),
     ("perm_table", 16, 1.5e8),
+    ("large_2u_ms32", 24, 3.0e8),
 ])
 def test_large_workloads_sampled_rows(name, n_random, budget):
     w, nnz, rp_np, seed, col, params, params_np, out = _run_workload(name)

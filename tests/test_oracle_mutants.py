@@ -35,6 +35,10 @@ MUTANTS = [
     ("msb_first_bytes", "(uint8_t)(1u << (q % 8))", "(uint8_t)(0x80u >> (q % 8))"),
     ("highest_bits_kept", "if ((z >> bit) & 1u)", "if ((z >> (32 - b + bit)) & 1u)"),
     ("field_stride_off", "int64_t q = (int64_t)j * b + bit;", "int64_t q = (int64_t)j * (b < 32 ? b + 0 : b) + bit + (j > 0 && b == 3);"),
+    ("multiply_shift_mod_2_31", "u128 two32 = (u128)1 << 32;", "u128 two32 = (u128)1 << 31;"),
+    ("multiply_shift_high_is_low", "if (!high) return (uint64_t)(v % (u128)D);", "if (1) return (uint64_t)(v % (u128)D);"),
+    ("multiply_shift_coefficients_swapped", "u128 v = ((u128)c[0] + (u128)c[1] * (u128)t) % two32;",
+     "u128 v = ((u128)c[1] + (u128)c[0] * (u128)t) % two32;"),
     ("wrong_prime_31", "case ORACLE_2U_M31: *p = 2147483647ull;", "case ORACLE_2U_M31: *p = 2147483648ull;"),
     ("wrong_prime_61", "case ORACLE_2U_M61: *p = 2305843009213693951ull;", "case ORACLE_2U_M61: *p = 2305843009213693953ull;"),
 ]

@@ -122,6 +122,22 @@ def test_universe_sizes_including_non_powers_of_two(family, D):
     check_case(rp, col, D, k, 32, family, c)               # full minima
 
 
+@pytest.mark.parametrize("family", [mh.FAMILY_2U_MS32, mh.FAMILY_2U_MS32_HIGH])
+@pytest.mark.parametrize("D,k,b", [(1 << 24, 500, 8), (2, 9, 1), (1 << 10, 64, 4), (1 << 30, 130, 12), (1 << 32, 40, 32)])
+def test_multiply_shift_families(family, D, k, b):
+    if D >= 4 and D <= (1 << 30):
+        rp, col = edge_rows(D, seed=31)
+    else:
+        rng = np.random.Generator(np.random.PCG64(32))
+        nnz = np.array([0, 1, 3, 200, 9000], dtype=np.int64)
+        col = np.concatenate([rng.integers(0, D, size=int(m), dtype=np.uint64).astype(np.uint32) for m in nnz]
+                             + [np.array([D - 1, 0], dtype=np.uint32)])
+        rp = W.row_ptr_from_nnz(np.append(nnz, 2))
+    c = W.coefficients(k, family, seed=33 + k)
+    c[0] = (0xFFFFFFFF, 0xFFFFFFFF)
+    check_case(rp, col, D, k, b, family, c)
+
+
 def test_m61_large_universes():
     for D in (1 << 31, 1 << 32, (1 << 32) - 5):
         rng = np.random.Generator(np.random.PCG64(3))
