@@ -179,6 +179,8 @@ def main() -> int:
     ap.add_argument("--batches", type=int, default=0, help="with --stream: number of batches (default: all)")
     ap.add_argument("--distinct-batches", type=int, default=7,
                     help="with --stream: batches held in pinned host memory (8 GB each)")
+    ap.add_argument("--generic-mod", action="store_true",
+                    help="ablation: hash with the plain %% operator instead of the Mersenne reduction (2U/4U, p = 2^31-1)")
     ap.add_argument("--calib", action="store_true",
                     help="also launch one plain streaming kernel of known size (reads 1 GiB, writes 1 GiB) so that "
                          "FETCH_SIZE / WRITE_SIZE counters of a profiler run can be scaled")
@@ -238,9 +240,11 @@ def main() -> int:
     ws = mh.alloc_workspace(n_rows, total_nnz, w.k, family, dev)
     stream = torch.cuda.current_stream()
 
+    flags = mh.FLAG_GENERIC_MOD if args.generic_mod else 0
+
     def step():
         mh.minhash_signatures(rp, col, w.D, w.k, w.b, family, params, out=out, workspace=ws, stream=stream,
-                              perm_ld=perm_ld if family == W.FAMILY_PERM else None)
+                              perm_ld=perm_ld if family == W.FAMILY_PERM else None, flags=flags)
 
     if args.calib:
         src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
@@ -271,7 +275,8 @@ def main() -> int:
     kms = []
     for _ in range(args.steps):
         _, ms = mh.minhash_signatures_profiled(rp, col, w.D, w.k, w.b, family, params, out=out, workspace=ws,
-                                               stream=stream, perm_ld=perm_ld if family == W.FAMILY_PERM else None)
+                                               stream=stream, perm_ld=perm_ld if family == W.FAMILY_PERM else None,
+                                               flags=flags)
         kms.append(ms)
     k_ms = float(np.mean(kms))
     if family == W.FAMILY_PERM:
@@ -302,7 +307,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "u32/u64 integer" if family != W.FAMILY_PERM else "u32",
         "data": "synthetic (seeded; stands in for the paper's webspam / rcv1 shapes)",
-        "config": {"workload": w.name, "n_rows": n_rows, "nnz": total_nnz, "D": w.D, "k": w.k, "b": w.b,
+        "config": {"workload": w.name + (" (generic % ablation)" if args.generic_mod else ""), "n_rows": n_rows, "nnz": total_nnz, "D": w.D, "k": w.k, "b": w.b,
                    "family": family, "setup_s": round(gen_s, 2)},
         "rows_per_s": n_rows / (dt / args.steps),
         "roofline": roof,

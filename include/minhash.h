@@ -53,6 +53,10 @@ enum {
 
 #define MINHASH_MAX_K            65536
 #define MINHASH_FLAG_VALIDATE    1u   /* check col_idx < D and row_ptr monotone on the device */
+#define MINHASH_FLAG_GENERIC_MOD 2u   /* MINHASH_2U_M31 / MINHASH_4U_M31 only: evaluate with the plain % operator
+                                         (runtime moduli, Horner form) instead of the Mersenne reduction.  Same
+                                         results; exists to measure what Section 3.4 saves ("4U (Mod)" against
+                                         "4U (Bit)" in the paper's timing tables)                              */
 #define MINHASH_WORKSPACE_ALIGN  256
 
 /*
@@ -93,7 +97,7 @@ enum {
  *             entry are ignored; two calls may share it only on one stream
  *   stream    hipStream_t (NULL = the default stream); all work is enqueued on
  *             it and the call returns without synchronising
- *   flags     0 or MINHASH_FLAG_VALIDATE
+ *   flags     0 or an OR of MINHASH_FLAG_* values
  *
  * Returns MINHASH_OK once everything is enqueued, or a negative code found
  * before any launch (nothing has been enqueued then).  Indices >= D or a

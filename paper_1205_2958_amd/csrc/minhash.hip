@@ -120,6 +120,7 @@ struct KArgs {
     int32_t log2_fl;                   // lanes covering one function tile = 1 << log2_fl
     int32_t sig_bytes;
     uint32_t validate;
+    uint64_t prime;                    // runtime modulus of the generic-% ablation kernels
 };
 
 // ------------------------------------------------------------------ small helpers
@@ -489,6 +490,40 @@ __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
 }
 
+// Ablation: the definition evaluated with the % operator on runtime moduli (Horner
+// form keeps every product below 2^62).  This is what Section 3.4's shift/mask
+// routine replaces; it exists only to be timed against the Mersenne kernels.
+template <int DEGREE>
+struct PolGenericMod {
+    static constexpr int NW = 1;
+    static constexpr int MIN_WAVES = 4;
+    static constexpr bool TRACK_MAX = false;
+    static constexpr int DEG = DEGREE;
+    struct Fn { uint64_t c[DEGREE]; uint64_t p; };
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    {
+        Fn f;
+#pragma unroll
+        for (int i = 0; i < DEGREE; ++i) f.c[i] = valid ? c[i] : 0;
+        f.p = 0;
+        return f;
+    }
+    static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
+    static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD&, uint64_t D)
+    {
+        const uint64_t t = w[0];
+        uint64_t acc = f.c[DEGREE - 1];
+#pragma unroll
+        for (int i = DEGREE - 2; i >= 0; --i) acc = (acc * t + f.c[i]) % f.p;
+        return (uint32_t)(acc % D);
+    }
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+                                                const uint32_t* wb, const ModD& md, uint64_t D)
+    {
+        pair_generic<PolGenericMod<DEGREE>>(fn, m, wa, wb, md, D);
+    }
+};
+
 // multiply-shift 2U: md.mask = D - 1, md.M = 32 - log2(D)
 template <bool HIGH>
 struct Pol2UMS32 {
@@ -573,6 +608,11 @@ __device__ __forceinline__ void load_tile(const uint32_t* col, int64_t begin, ui
     }
 }
 
+// only the ablation policy carries a runtime modulus
+template <class Fn>
+__device__ __forceinline__ auto set_runtime_prime(Fn& f, uint64_t p) -> decltype(f.p, void()) { f.p = p; }
+__device__ __forceinline__ void set_runtime_prime(...) {}
+
 // ------------------------------------------------------------------ the hash kernel
 template <class Pol>
 __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_WAVES, 8))) void mh_hash_kernel(KArgs a)
@@ -617,6 +657,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                 int j = j_base + r;
                 bool valid = j < a.k;
                 fn[r] = Pol::load(coeffs + (size_t)(valid ? j : 0) * Pol::DEG, valid);
+                set_runtime_prime(fn[r], a.prime);
             }
             cur_ftile = ftile;
         }
@@ -937,7 +978,9 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     }
     const int64_t sig_bytes = ((int64_t)k * b + 7) / 8;
     if (out_stride < sig_bytes) return MINHASH_ERR_STRIDE;
-    if (flags & ~MINHASH_FLAG_VALIDATE) return MINHASH_ERR_ARG;
+    if (flags & ~(MINHASH_FLAG_VALIDATE | MINHASH_FLAG_GENERIC_MOD)) return MINHASH_ERR_ARG;
+    const bool generic_mod = (flags & MINHASH_FLAG_GENERIC_MOD) != 0;
+    if (generic_mod && family != MINHASH_2U_M31 && family != MINHASH_4U_M31) return MINHASH_ERR_ARG;
     if (n_rows == 0) return MINHASH_OK;
     if (!row_ptr || !params || !out) return MINHASH_ERR_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % MINHASH_WORKSPACE_ALIGN) != 0) return MINHASH_ERR_WORKSPACE;
@@ -972,6 +1015,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     a.n_rows = n_rows; a.k = k; a.b = b;
     a.sig_bytes = (int32_t)sig_bytes;
     a.validate = (flags & MINHASH_FLAG_VALIDATE) ? 1u : 0u;
+    a.prime = P31;
 
     const bool perm = family == MINHASH_PERM;
     const int ftile_size = perm ? PERM_FTILE : HASH_FTILE;
@@ -1002,7 +1046,9 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     }
     const int main_blocks = cus;
     const bool pow2 = a.md.pow2 != 0;
-    switch (family) {
+    switch (generic_mod ? -family - 1 : family) {
+    case -MINHASH_2U_M31 - 1: launch_hash<PolGenericMod<2>>(a, main_blocks, s); break;
+    case -MINHASH_4U_M31 - 1: launch_hash<PolGenericMod<4>>(a, main_blocks, s); break;
     case MINHASH_2U_M31:
         if (pow2) launch_hash<Pol2U31<true>>(a, main_blocks, s); else launch_hash<Pol2U31<false>>(a, main_blocks, s);
         break;

@@ -138,6 +138,21 @@ def test_multiply_shift_families(family, D, k, b):
     check_case(rp, col, D, k, b, family, c)
 
 
+@pytest.mark.parametrize("family", [mh.FAMILY_2U_M31, mh.FAMILY_4U_M31])
+@pytest.mark.parametrize("D", [1 << 24, 16609143])
+def test_generic_modulo_ablation_kernels_give_the_same_bits(family, D):
+    nnz = np.array([0, 1, 5, 300, 2000, 9000], dtype=np.int64)
+    rng = np.random.Generator(np.random.PCG64(41))
+    rows = [np.unique(rng.integers(0, D, size=int(m))).astype(np.uint32) for m in nnz]
+    rp = W.row_ptr_from_nnz(np.array([r.shape[0] for r in rows], dtype=np.int64))
+    col = np.concatenate(rows)
+    c = W.coefficients(100, family, seed=42)
+    c[0, :] = W.M31 - 1
+    want = oracle.signatures(rp, col, D, 100, 8, family, c)
+    got, st = gpu_signatures(rp, col, D, 100, 8, family, c, flags=mh.FLAG_GENERIC_MOD)
+    assert st == 0 and np.array_equal(got, want)
+
+
 def test_m61_large_universes():
     for D in (1 << 31, 1 << 32, (1 << 32) - 5):
         rng = np.random.Generator(np.random.PCG64(3))
