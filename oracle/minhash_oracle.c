@@ -24,6 +24,11 @@
  *   - only the lowest b bits of every minimum are kept (Section 1.1), and a
  *     data vector becomes k b-bit integers (Section 1.1, after eq. "eqn_R_b").
  *
+ * The file also holds the three consumers of a signature that Section 1.1
+ * defines: the 2^b x k expansion, the count of equal b-bit values of two rows
+ * (k times P_b-hat), and the estimator R_b-hat of eq. "eqn_R_b" with Theorem 1's
+ * C terms.
+ *
  * Readings where the paper is silent (all stated in the repository's design
  * notes): coefficients are 0-based here, c[j][i] multiplies t^i; the whole
  * polynomial is reduced mod p before mod D; the minimum of an empty set is
@@ -40,6 +45,7 @@
  * collision identity of Section 1.1 eq. (1) and Theorem 1 on planted pairs,
  * the truncation example, union/subset/order invariants).
  */
+#include <math.h>
 #include <stddef.h>
 #include <stdint.h>
 #include <string.h>
@@ -186,4 +192,90 @@ int minhash_signatures_oracle(const int64_t *row_ptr, const uint32_t *col_idx, i
     int rc = minhash_minima_oracle(row_ptr, col_idx, n_rows, D, k, family, params, perm_ld, scratch);
     if (rc != 0) return rc;
     return minhash_pack_oracle(scratch, n_rows, k, b, out, out_stride);
+}
+
+/* ======================================================================
+ * Consumers of the signature (Section 1.1, Theorem 1 and eq. "eqn_R_b").
+ * ====================================================================== */
+
+/* value j of a packed row: bits [j*b, (j+1)*b) of the little-endian bit string, read one bit at a time */
+static uint32_t packed_field(const uint8_t *row, int32_t j, int32_t b)
+{
+    uint32_t v = 0;
+    for (int32_t bit = 0; bit < b; ++bit) {
+        int64_t q = (int64_t)j * b + bit;
+        if ((row[q / 8] >> (q % 8)) & 1u) v |= (1u << bit);
+    }
+    return v;
+}
+
+/*
+ * Expansion into the 2^b x k-length binary vector with exactly k ones (Section
+ * 1.1, paragraph after eq. "eqn_R_b"): the j-th one of row i sits at position
+ * j*2^b + s_ij.  out[i*k + j] is that position.  Needs k*2^b <= 2^32.
+ */
+int minhash_expand_oracle(const uint8_t *sig, int64_t n_rows, int64_t sig_stride, int32_t k, int32_t b,
+                          uint32_t *out)
+{
+    if (n_rows < 0 || k < 1 || b < 1 || b > 32) return -4;
+    if (((unsigned __int128)k << b) > ((unsigned __int128)1 << 32)) return -4;
+    if (sig_stride < ((int64_t)k * b + 7) / 8) return -5;
+    if (n_rows == 0) return 0;
+    if (!sig || !out) return -1;
+    for (int64_t i = 0; i < n_rows; ++i)
+        for (int32_t j = 0; j < k; ++j)
+            out[(size_t)i * (size_t)k + (size_t)j] =
+                (uint32_t)(((uint64_t)j << b) + packed_field(sig + (size_t)i * (size_t)sig_stride, j, b));
+    return 0;
+}
+
+/*
+ * k * P_b-hat of eq. "eqn_R_b": for every listed pair of rows the number of j
+ * with equal b-bit values.  pairs holds 2*n_pairs row numbers.
+ */
+int minhash_match_counts_oracle(const uint8_t *sig, int64_t n_rows, int64_t sig_stride, int32_t k, int32_t b,
+                                const int64_t *pairs, int64_t n_pairs, uint32_t *counts)
+{
+    if (n_rows < 0 || n_pairs < 0 || k < 1 || b < 1 || b > 32) return -4;
+    if (sig_stride < ((int64_t)k * b + 7) / 8) return -5;
+    if (n_pairs == 0) return 0;
+    if (!sig || !pairs || !counts) return -1;
+    for (int64_t q = 0; q < n_pairs; ++q) {
+        int64_t r1 = pairs[2 * q], r2 = pairs[2 * q + 1];
+        if (r1 < 0 || r1 >= n_rows || r2 < 0 || r2 >= n_rows) return -1;
+        uint32_t c = 0;
+        for (int32_t j = 0; j < k; ++j)
+            if (packed_field(sig + (size_t)r1 * (size_t)sig_stride, j, b) ==
+                packed_field(sig + (size_t)r2 * (size_t)sig_stride, j, b)) ++c;
+        counts[q] = c;
+    }
+    return 0;
+}
+
+/*
+ * R_b-hat = (P_b-hat - C_{1,b}) / (1 - C_{2,b})  (eq. "eqn_R_b"), with the C and A
+ * terms given with Theorem 1:  r = f/D,  A = r (1-r)^(2^b - 1) / (1 - (1-r)^(2^b)),
+ * C1 = A1 r2/(r1+r2) + A2 r1/(r1+r2),  C2 = A1 r1/(r1+r2) + A2 r2/(r1+r2).
+ * f1, f2 are the sizes of the two sets (both >= 1).  Double precision.
+ */
+static double theorem1_A(double r, int32_t b)
+{
+    double n = ldexp(1.0, b);                     /* 2^b */
+    return r * pow(1.0 - r, n - 1.0) / (1.0 - pow(1.0 - r, n));
+}
+int minhash_resemblance_oracle(const uint32_t *counts, const int64_t *f1, const int64_t *f2, int64_t n_pairs,
+                               uint64_t D, int32_t k, int32_t b, double *r_hat)
+{
+    if (n_pairs < 0 || k < 1 || b < 1 || b > 32 || D < 1) return -4;
+    if (n_pairs == 0) return 0;
+    if (!counts || !f1 || !f2 || !r_hat) return -1;
+    for (int64_t q = 0; q < n_pairs; ++q) {
+        double r1 = (double)f1[q] / (double)D, r2 = (double)f2[q] / (double)D;
+        double A1 = theorem1_A(r1, b), A2 = theorem1_A(r2, b);
+        double C1 = A1 * r2 / (r1 + r2) + A2 * r1 / (r1 + r2);
+        double C2 = A1 * r1 / (r1 + r2) + A2 * r2 / (r1 + r2);
+        double P = (double)counts[q] / (double)k;
+        r_hat[q] = (P - C1) / (1.0 - C2);
+    }
+    return 0;
 }

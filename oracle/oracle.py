@@ -25,7 +25,7 @@ def build(force: bool = False) -> str:
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         tmp = _LIB + ".tmp%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", _SRC, "-o", tmp])
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", _SRC, "-o", tmp, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -39,6 +39,12 @@ def _bind(path: str):
     lib.minhash_pack_oracle.restype = ctypes.c_int
     lib.minhash_signatures_oracle.argtypes = [vp, vp, i64, u64, i32, i32, i32, vp, i64, vp, i64, vp]
     lib.minhash_signatures_oracle.restype = ctypes.c_int
+    lib.minhash_expand_oracle.argtypes = [vp, i64, i64, i32, i32, vp]
+    lib.minhash_expand_oracle.restype = ctypes.c_int
+    lib.minhash_match_counts_oracle.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp]
+    lib.minhash_match_counts_oracle.restype = ctypes.c_int
+    lib.minhash_resemblance_oracle.argtypes = [vp, vp, vp, i64, u64, i32, i32, vp]
+    lib.minhash_resemblance_oracle.restype = ctypes.c_int
     return lib
 
 
@@ -106,6 +112,39 @@ class Oracle:
         return out
 
 
+    def expand(self, sig, k, b) -> np.ndarray:
+        """uint32 [n_rows, k]: positions of the ones of the 2^b x k expansion."""
+        sig = np.ascontiguousarray(sig, dtype=np.uint8)
+        n = sig.shape[0]
+        out = np.empty((n, k), dtype=np.uint32)
+        rc = self._lib.minhash_expand_oracle(_ptr(sig), n, sig.shape[1], k, b, _ptr(out))
+        if rc != 0:
+            raise ValueError("oracle rejected the arguments: %d" % rc)
+        return out
+
+    def match_counts(self, sig, k, b, pairs) -> np.ndarray:
+        """uint32 [n_pairs]: number of equal b-bit values for each pair of rows."""
+        sig = np.ascontiguousarray(sig, dtype=np.uint8)
+        pairs = np.ascontiguousarray(pairs, dtype=np.int64).reshape(-1, 2)
+        out = np.empty(pairs.shape[0], dtype=np.uint32)
+        rc = self._lib.minhash_match_counts_oracle(_ptr(sig), sig.shape[0], sig.shape[1], k, b, _ptr(pairs),
+                                                   pairs.shape[0], _ptr(out))
+        if rc != 0:
+            raise ValueError("oracle rejected the arguments: %d" % rc)
+        return out
+
+    def resemblance(self, counts, f1, f2, D, k, b) -> np.ndarray:
+        """float64 [n_pairs]: the estimator R_b-hat of eq. eqn_R_b."""
+        counts = np.ascontiguousarray(counts, dtype=np.uint32)
+        f1 = np.ascontiguousarray(f1, dtype=np.int64)
+        f2 = np.ascontiguousarray(f2, dtype=np.int64)
+        out = np.empty(counts.shape[0], dtype=np.float64)
+        rc = self._lib.minhash_resemblance_oracle(_ptr(counts), _ptr(f1), _ptr(f2), counts.shape[0], D, k, b, _ptr(out))
+        if rc != 0:
+            raise ValueError("oracle rejected the arguments: %d" % rc)
+        return out
+
+
 _default = None
 
 
@@ -126,6 +165,18 @@ def pack(minima_arr, b, out_stride=None) -> np.ndarray:
 
 def signatures(row_ptr, col_idx, D, k, b, family, params, out_stride=None) -> np.ndarray:
     return default().signatures(row_ptr, col_idx, D, k, b, family, params, out_stride)
+
+
+def expand(sig, k, b) -> np.ndarray:
+    return default().expand(sig, k, b)
+
+
+def match_counts(sig, k, b, pairs) -> np.ndarray:
+    return default().match_counts(sig, k, b, pairs)
+
+
+def resemblance(counts, f1, f2, D, k, b) -> np.ndarray:
+    return default().resemblance(counts, f1, f2, D, k, b)
 
 
 def unpack(packed: np.ndarray, k: int, b: int) -> np.ndarray:

@@ -257,15 +257,19 @@ def perm_table_torch(D: int, k: int, seed: int, device, perm_ld: Optional[int] =
 # --------------------------------------------------------------------------
 # planted-resemblance pairs for the statistical checks
 # --------------------------------------------------------------------------
-def planted_pairs(n_pairs: int, D: int, union: int, shared: int, seed: int):
+def planted_pairs(n_pairs: int, D: int, union: int, shared: int, seed: int, only1: Optional[int] = None):
     """CSR of 2*n_pairs rows: rows 2i and 2i+1 are sets with
     |S1 ∩ S2| = shared and |S1 ∪ S2| = union (resemblance shared/union); the
-    non-shared elements are split evenly.  Returns (row_ptr, col_idx, f1, f2).
+    non-shared elements are split evenly unless ``only1`` gives the number that
+    belong to S1 alone.  Returns (row_ptr, col_idx, f1, f2).
     """
     if not 0 <= shared <= union:
         raise ValueError("need 0 <= shared <= union")
     rest = union - shared
-    only1 = rest // 2
+    if only1 is None:
+        only1 = rest // 2
+    if not 0 <= only1 <= rest:
+        raise ValueError("need 0 <= only1 <= union - shared")
     only2 = rest - only1
     f1, f2 = shared + only1, shared + only2
     pool = csr_indices_np(np.full(n_pairs, union, dtype=np.int64), D, seed).reshape(n_pairs, union)

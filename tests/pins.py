@@ -446,6 +446,68 @@ def pin_collision_probability_hashes(o, n_pairs=40, k=200):
                 assert abs(gb - pb) <= tolb, (family, shared, b, gb, pb)
 
 
+# ---------------------------------------------------------------- consumers of the signature
+def pin_expansion_has_k_ones_and_inner_product_counts_matches(o):
+    """Section 1.1: a signature expands into a 2^b x k vector with exactly k ones,
+    and P_b-hat is the inner product of two such vectors divided by k.  The j-th
+    one lies in block j; the inner product of two expansions (size of the
+    intersection of the index sets) is the number of equal b-bit values, which is
+    also counted here with NumPy on the unpacked fields."""
+    from oracle import oracle as loader
+    rng = np.random.Generator(np.random.PCG64(61))
+    for k, b in ((500, 8), (77, 3), (13, 1), (64, 16), (9, 12), (4, 30)):
+        m = rng.integers(0, 1 << 32, size=(12, k), dtype=np.uint64).astype(np.uint32)
+        m[1] = m[0]
+        m[2, : k // 2] = m[0, : k // 2]
+        sig = o.pack(m, b, out_stride=(k * b + 7) // 8 + 2)
+        fields = loader.unpack(sig, k, b)
+        idx = o.expand(sig, k, b)
+        assert idx.shape == (12, k)
+        block = (np.arange(k, dtype=np.uint64) << np.uint64(b))
+        assert np.array_equal(idx.astype(np.uint64), block[None, :] + fields.astype(np.uint64))
+        pairs = np.array([[0, 1], [0, 2], [3, 4], [5, 5], [11, 0]], dtype=np.int64)
+        counts = o.match_counts(sig, k, b, pairs)
+        for q, (r1, r2) in enumerate(pairs):
+            assert counts[q] == len(set(idx[r1].tolist()) & set(idx[r2].tolist()))
+            assert counts[q] == int((fields[r1] == fields[r2]).sum())
+        assert counts[0] == k and counts[3] == k and counts[1] >= k // 2
+
+
+def pin_estimator_closed_forms(o):
+    """eq. eqn_R_b with Theorem 1's terms.  Equal densities r1 = r2 = r give C1 = C2 = A,
+    so R-hat = (P - A)/(1 - A); for b = 1, A = (1-r)/(2-r): with r = 1/2, A = 1/3, and
+    P = 2/3 gives exactly 1/2.  P = 1 gives 1 for any equal densities.  For very sparse
+    sets A tends to 2^-b, and for b = 32 the estimator is P-hat itself."""
+    r = o.resemblance(np.array([2], dtype=np.uint32), [8], [8], 16, 3, 1)
+    assert abs(r[0] - 0.5) < 1e-15
+    for b in (1, 2, 4, 8, 16):
+        r = o.resemblance(np.array([500, 250], dtype=np.uint32), [3000, 3000], [3000, 3000], 1 << 24, 500, b)
+        assert abs(r[0] - 1.0) < 1e-12
+        a = 2.0 ** -b
+        assert abs(r[1] - (0.5 - a) / (1 - a)) < 1e-3
+    r = o.resemblance(np.array([123], dtype=np.uint32), [4000], [900], 1 << 30, 500, 32)
+    assert abs(r[0] - 123 / 500) < 1e-9
+
+
+def pin_estimator_is_unbiased_for_unequal_set_sizes(o, n_pairs=150, k=400):
+    """Nested sets of very different density (r1 = 0.05, r2 = 0.49, R = 0.1) under true
+    random permutations: the mean of R_b-hat must sit on R.  With densities this
+    unequal C1 and C2 differ by more than 0.1, so exchanging them, or the roles of
+    r1 and r2, shifts the mean far outside the tolerance."""
+    D, f1, f2 = 1 << 12, 200, 2000
+    table = W.perm_table_np(D, k, seed=6262)
+    rp, col, g1, g2 = W.planted_pairs(n_pairs, D, union=f2, shared=f1, seed=6363, only1=0)
+    assert (g1, g2) == (f1, f2)
+    pairs = np.arange(2 * n_pairs, dtype=np.int64).reshape(-1, 2)
+    for b in (1, 2, 4):
+        sig = o.signatures(rp, col, D, k, b, FPERM, table)
+        counts = o.match_counts(sig, k, b, pairs)
+        est = o.resemblance(counts, np.full(n_pairs, f1), np.full(n_pairs, f2), D, k, b)
+        mean, sd = float(est.mean()), float(est.std(ddof=1))
+        tol = 4.5 * sd / math.sqrt(n_pairs) + 3e-3            # Theorem 1 assumes large D
+        assert abs(mean - f1 / f2) <= tol, (b, mean, tol)
+
+
 FAST_PINS = [
     pin_explicit_permutations_all_subsets,
     pin_explicit_permutations_random_sets,
@@ -466,6 +528,9 @@ FAST_PINS = [
     pin_pack_roundtrip_all_b,
     pin_signatures_equal_pack_of_minima,
     pin_min_invariants,
+    pin_expansion_has_k_ones_and_inner_product_counts_matches,
+    pin_estimator_closed_forms,
+    pin_estimator_is_unbiased_for_unequal_set_sizes,
 ]
 STAT_PINS = [pin_collision_probability_permutations, pin_collision_probability_hashes]
 ALL_PINS = FAST_PINS + STAT_PINS

@@ -39,6 +39,14 @@ MUTANTS = [
     ("multiply_shift_high_is_low", "if (!high) return (uint64_t)(v % (u128)D);", "if (1) return (uint64_t)(v % (u128)D);"),
     ("multiply_shift_coefficients_swapped", "u128 v = ((u128)c[0] + (u128)c[1] * (u128)t) % two32;",
      "u128 v = ((u128)c[1] + (u128)c[0] * (u128)t) % two32;"),
+    ("estimator_c1_c2_exchanged", "r_hat[q] = (P - C1) / (1.0 - C2);", "r_hat[q] = (P - C2) / (1.0 - C1);"),
+    ("estimator_densities_exchanged", "double C1 = A1 * r2 / (r1 + r2) + A2 * r1 / (r1 + r2);",
+     "double C1 = A1 * r1 / (r1 + r2) + A2 * r2 / (r1 + r2);"),
+    ("estimator_exponent_off_by_one", "return r * pow(1.0 - r, n - 1.0) / (1.0 - pow(1.0 - r, n));",
+     "return r * pow(1.0 - r, n) / (1.0 - pow(1.0 - r, n));"),
+    ("expansion_block_stride", "(uint32_t)(((uint64_t)j << b) + packed_field(", "(uint32_t)(((uint64_t)j * b) + packed_field("),
+    ("match_counts_compare_wrong_field", "packed_field(sig + (size_t)r2 * (size_t)sig_stride, j, b)) ++c;",
+     "packed_field(sig + (size_t)r2 * (size_t)sig_stride, (j + 1) % k, b)) ++c;"),
     ("wrong_prime_31", "case ORACLE_2U_M31: *p = 2147483647ull;", "case ORACLE_2U_M31: *p = 2147483648ull;"),
     ("wrong_prime_61", "case ORACLE_2U_M61: *p = 2305843009213693951ull;", "case ORACLE_2U_M61: *p = 2305843009213693953ull;"),
 ]
@@ -52,7 +60,7 @@ def test_some_pin_catches(name, old, new, tmp_path):
     src = tmp_path / ("mutant_%s.c" % name)
     lib = tmp_path / ("libmutant_%s.so" % name)
     src.write_text(mutated)
-    subprocess.check_call(["gcc", "-O1", "-std=c11", "-w", "-fPIC", "-shared", str(src), "-o", str(lib)])
+    subprocess.check_call(["gcc", "-O1", "-std=c11", "-w", "-fPIC", "-shared", str(src), "-o", str(lib), "-lm"])
     mutant = loader.Oracle(str(lib))
     caught = None
     for pin in pins.FAST_PINS:
