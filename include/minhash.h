@@ -143,6 +143,31 @@ int minhash_check_coeffs(const uint64_t *host_coeffs, int32_t k, int32_t family)
  * bad input, else MINHASH_OK. */
 int minhash_status(const void *workspace, void *stream);
 
+/* ---------------------------------------------------------------- consumers
+ * What Section 1.1 does with a signature.  `sig` is the output of
+ * minhash_signatures: device, rows sig_stride bytes apart, k values of b bits.
+ * All three enqueue on `stream` and return without synchronising. */
+
+/* The 2^b x k-length binary vector with exactly k ones that a signature is
+ * expanded into at run time (Section 1.1, paragraph after eq. "eqn_R_b"):
+ * out_idx[i*k + j] = j*2^b + s_ij, the position of the j-th one of row i.
+ * out_idx: device, n_rows*k uint32.  Needs k*2^b <= 2^32 (else MINHASH_ERR_KB). */
+int minhash_expand_indices(const uint8_t *sig, int64_t n_rows, int64_t sig_stride, int32_t k, int32_t b,
+                           uint32_t *out_idx, void *stream);
+
+/* k * P_b-hat of eq. "eqn_R_b": counts[q] = number of j whose b-bit values are
+ * equal in rows pairs[2q] and pairs[2q+1] (the inner product of the two expanded
+ * vectors).  pairs: device, 2*n_pairs int64 row numbers; a row number outside
+ * [0, n_rows) gives counts[q] = 0xFFFFFFFF.  counts: device, n_pairs uint32. */
+int minhash_match_counts(const uint8_t *sig, int64_t n_rows, int64_t sig_stride, int32_t k, int32_t b,
+                         const int64_t *pairs, int64_t n_pairs, uint32_t *counts, void *stream);
+
+/* R_b-hat = (counts/k - C_{1,b}) / (1 - C_{2,b})  (eq. "eqn_R_b") with the C and A
+ * terms stated with Theorem 1, from the set sizes f1[q], f2[q] >= 1 and D, in
+ * double precision.  counts, f1, f2, r_hat: device, n_pairs entries each. */
+int minhash_resemblance_estimates(const uint32_t *counts, const int64_t *f1, const int64_t *f2, int64_t n_pairs,
+                                  uint64_t D, int32_t k, int32_t b, double *r_hat, void *stream);
+
 /* Static text for a return code; never NULL. */
 const char *minhash_error_string(int code);
 

@@ -13,7 +13,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRC = os.path.join(HERE, "csrc", "minhash.hip")
+SRCS = [os.path.join(HERE, "csrc", "minhash.hip"), os.path.join(HERE, "csrc", "consumers.hip")]
 LIB = os.path.join(HERE, "libminhash.so")
 
 HIPCC_FLAGS = [
@@ -26,7 +26,7 @@ HIPCC_FLAGS = [
 def build(verbose: bool = False, extra=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra) + [SRC, "-o", tmp]
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra) + SRCS + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)

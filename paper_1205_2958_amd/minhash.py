@@ -33,6 +33,9 @@ EXPORTS = (
     "minhash_workspace_bytes",
     "minhash_check_coeffs",
     "minhash_status",
+    "minhash_expand_indices",
+    "minhash_match_counts",
+    "minhash_resemblance_estimates",
     "minhash_error_string",
     "minhash_last_hip_error",
     "minhash_version",
@@ -70,6 +73,12 @@ def lib() -> ctypes.CDLL:
         L.minhash_check_coeffs.restype = ctypes.c_int
         L.minhash_status.argtypes = [vp, vp]
         L.minhash_status.restype = ctypes.c_int
+        L.minhash_expand_indices.argtypes = [vp, i64, i64, i32, i32, vp, vp]
+        L.minhash_expand_indices.restype = ctypes.c_int
+        L.minhash_match_counts.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp, vp]
+        L.minhash_match_counts.restype = ctypes.c_int
+        L.minhash_resemblance_estimates.argtypes = [vp, vp, vp, i64, u64, i32, i32, vp, vp]
+        L.minhash_resemblance_estimates.restype = ctypes.c_int
         L.minhash_error_string.argtypes = [ctypes.c_int]
         L.minhash_error_string.restype = ctypes.c_char_p
         L.minhash_last_hip_error.argtypes = []
@@ -184,6 +193,45 @@ def minhash_signatures_profiled(row_ptr, col_idx, D, k, b, family, params, out=N
 def status(workspace: torch.Tensor, stream=None) -> int:
     """Waits for the stream; 0, or the negative code of what VALIDATE found."""
     return int(lib().minhash_status(_ptr(workspace), _stream_handle(stream)))
+
+
+def expand_indices(sig: torch.Tensor, k: int, b: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """int32-storage [n_rows, k] tensor of uint32 positions j*2^b + s_ij (see include/minhash.h)."""
+    n = sig.shape[0]
+    if out is None:
+        out = torch.empty((n, k), dtype=torch.int32, device=sig.device)
+    rc = lib().minhash_expand_indices(_ptr(sig), n, sig.stride(0), k, b, _ptr(out), _stream_handle(stream))
+    if rc != 0:
+        _raise(rc)
+    return out
+
+
+def match_counts(sig: torch.Tensor, k: int, b: int, pairs: torch.Tensor, out: Optional[torch.Tensor] = None,
+                 stream=None) -> torch.Tensor:
+    """int32-storage [n_pairs] tensor of uint32 counts of equal b-bit values; pairs is int64 [n_pairs, 2]."""
+    n_pairs = pairs.shape[0]
+    if pairs.dtype != torch.int64 or not pairs.is_contiguous():
+        raise TypeError("pairs must be a contiguous int64 tensor [n_pairs, 2]")
+    if out is None:
+        out = torch.empty(n_pairs, dtype=torch.int32, device=sig.device)
+    rc = lib().minhash_match_counts(_ptr(sig), sig.shape[0], sig.stride(0), k, b, _ptr(pairs), n_pairs, _ptr(out),
+                                    _stream_handle(stream))
+    if rc != 0:
+        _raise(rc)
+    return out
+
+
+def resemblance_estimates(counts: torch.Tensor, f1: torch.Tensor, f2: torch.Tensor, D: int, k: int, b: int,
+                          out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """float64 [n_pairs] tensor of R_b-hat; f1, f2 are int64 set sizes."""
+    n_pairs = counts.shape[0]
+    if out is None:
+        out = torch.empty(n_pairs, dtype=torch.float64, device=counts.device)
+    rc = lib().minhash_resemblance_estimates(_ptr(counts), _ptr(f1), _ptr(f2), n_pairs, D, k, b, _ptr(out),
+                                             _stream_handle(stream))
+    if rc != 0:
+        _raise(rc)
+    return out
 
 
 def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.Tensor, max_rows: int, max_nnz: int,

@@ -129,3 +129,20 @@ def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(mh, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(FileNotFoundError):
         mh.lib()
+
+
+def test_consumer_entry_points_validate_before_any_launch(lib):
+    P = 0x1000
+    assert lib.minhash_expand_indices(P, 0, 500, 500, 8, P, 0) == 0              # no rows: no-op
+    assert lib.minhash_expand_indices(P, 4, 499, 500, 8, P, 0) == -5             # pitch below the signature size
+    assert lib.minhash_expand_indices(P, 4, 500, 500, 0, P, 0) == -4
+    assert lib.minhash_expand_indices(P, 4, 2000, 500, 32, P, 0) == -4           # k * 2^b must fit 32 bits
+    assert lib.minhash_expand_indices(0, 4, 500, 500, 8, P, 0) == -1
+    assert lib.minhash_match_counts(P, 4, 500, 500, 8, P, 0, P, 0) == 0
+    assert lib.minhash_match_counts(P, 4, 500, 500, 8, 0, 3, P, 0) == -1
+    assert lib.minhash_match_counts(P, 4, 500, 500, 8, P, -1, P, 0) == -1
+    assert lib.minhash_match_counts(P, 4, 10, 500, 8, P, 3, P, 0) == -5
+    assert lib.minhash_resemblance_estimates(P, P, P, 0, 1 << 24, 500, 8, P, 0) == 0
+    assert lib.minhash_resemblance_estimates(P, P, P, 5, 0, 500, 8, P, 0) == -3
+    assert lib.minhash_resemblance_estimates(P, P, P, 5, 1 << 24, 500, 33, P, 0) == -4
+    assert lib.minhash_resemblance_estimates(0, P, P, 5, 1 << 24, 500, 8, P, 0) == -1
