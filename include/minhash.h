@@ -168,6 +168,29 @@ int minhash_match_counts(const uint8_t *sig, int64_t n_rows, int64_t sig_stride,
 int minhash_resemblance_estimates(const uint32_t *counts, const int64_t *f1, const int64_t *f2, int64_t n_pairs,
                                   uint64_t D, int32_t k, int32_t b, double *r_hat, void *stream);
 
+/* ---------------------------------------------------------------- ingest (host only)
+ * Phase 1 of the batch loop of Section 3.2: sets are read from disk before they
+ * go to the GPU, and Section 3.6 finds this loading dominant once hashing is on
+ * the GPU.  LibSVM text, one data vector per line: "<label> <index>:<value> ...";
+ * a listed feature is a member of the set, values are ignored (binary data,
+ * Section 1.1).  Blank lines and lines starting with '#' are skipped.  `text` is
+ * host memory (e.g. an mmap of the file), len bytes, not necessarily
+ * NUL-terminated; index_base is 1 for standard LibSVM files (written indices
+ * start at 1 and are stored minus 1) or 0; the work is split over n_threads
+ * host threads.  Neither function touches the GPU. */
+
+/* Pass 1: number of rows, of nonzeros, and the largest stored index (so that the
+ * caller can choose D > max_index and allocate, e.g., pinned arrays).
+ * MINHASH_ERR_DATA for a malformed line or an index below index_base / above 2^32-1+index_base. */
+int minhash_libsvm_count(const char *text, size_t len, int32_t index_base, int32_t n_threads,
+                         int64_t *n_rows, int64_t *nnz, uint32_t *max_index);
+
+/* Pass 2: fills row_ptr[n_rows+1] (offsets from 0), col_idx[nnz] (order as
+ * written in the file) and, if not NULL, labels[n_rows], all host memory of the
+ * sizes pass 1 returned (MINHASH_ERR_ARG if they do not match this text). */
+int minhash_libsvm_parse(const char *text, size_t len, int32_t index_base, int32_t n_threads,
+                         int64_t n_rows, int64_t nnz, int64_t *row_ptr, uint32_t *col_idx, float *labels);
+
 /* Static text for a return code; never NULL. */
 const char *minhash_error_string(int code);
 

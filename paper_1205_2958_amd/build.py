@@ -13,11 +13,12 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SRCS = [os.path.join(HERE, "csrc", "minhash.hip"), os.path.join(HERE, "csrc", "consumers.hip")]
+SRCS = [os.path.join(HERE, "csrc", "minhash.hip"), os.path.join(HERE, "csrc", "consumers.hip"),
+        os.path.join(HERE, "csrc", "ingest.hip")]
 LIB = os.path.join(HERE, "libminhash.so")
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-pthread",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
 ]

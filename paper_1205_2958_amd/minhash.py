@@ -36,6 +36,8 @@ EXPORTS = (
     "minhash_expand_indices",
     "minhash_match_counts",
     "minhash_resemblance_estimates",
+    "minhash_libsvm_count",
+    "minhash_libsvm_parse",
     "minhash_error_string",
     "minhash_last_hip_error",
     "minhash_version",
@@ -79,6 +81,11 @@ def lib() -> ctypes.CDLL:
         L.minhash_match_counts.restype = ctypes.c_int
         L.minhash_resemblance_estimates.argtypes = [vp, vp, vp, i64, u64, i32, i32, vp, vp]
         L.minhash_resemblance_estimates.restype = ctypes.c_int
+        L.minhash_libsvm_count.argtypes = [vp, sz, i32, i32, ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                           ctypes.POINTER(u32)]
+        L.minhash_libsvm_count.restype = ctypes.c_int
+        L.minhash_libsvm_parse.argtypes = [vp, sz, i32, i32, i64, i64, vp, vp, vp]
+        L.minhash_libsvm_parse.restype = ctypes.c_int
         L.minhash_error_string.argtypes = [ctypes.c_int]
         L.minhash_error_string.restype = ctypes.c_char_p
         L.minhash_last_hip_error.argtypes = []
@@ -232,6 +239,30 @@ def resemblance_estimates(counts: torch.Tensor, f1: torch.Tensor, f2: torch.Tens
     if rc != 0:
         _raise(rc)
     return out
+
+
+def parse_libsvm(buf, index_base: int = 1, n_threads: int = 16, pin_memory: bool = False, labels: bool = True):
+    """Parses LibSVM text held in ``buf`` (bytes, bytearray, mmap or anything with the
+    buffer protocol) into host tensors (row_ptr int64 [n+1], col_idx int32-storage
+    uint32 [nnz], labels float32 [n] or None) and returns them with the largest index.
+    The arrays can be pinned so that they feed ``stream_batches`` directly."""
+    import numpy as np
+
+    view = np.frombuffer(buf, dtype=np.uint8)
+    ptr = view.ctypes.data if view.size else 0
+    n_rows, nnz, mx = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_uint32(0)
+    rc = lib().minhash_libsvm_count(ptr, view.size, index_base, n_threads, ctypes.byref(n_rows), ctypes.byref(nnz),
+                                    ctypes.byref(mx))
+    if rc != 0:
+        _raise(rc)
+    row_ptr = torch.empty(n_rows.value + 1, dtype=torch.int64, pin_memory=pin_memory)
+    col_idx = torch.empty(nnz.value, dtype=torch.int32, pin_memory=pin_memory)
+    lab = torch.empty(n_rows.value, dtype=torch.float32) if labels else None
+    rc = lib().minhash_libsvm_parse(ptr, view.size, index_base, n_threads, n_rows.value, nnz.value, row_ptr.data_ptr(),
+                                    col_idx.data_ptr(), lab.data_ptr() if labels else 0)
+    if rc != 0:
+        _raise(rc)
+    return row_ptr, col_idx, lab, int(mx.value)
 
 
 def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.Tensor, max_rows: int, max_nnz: int,
