@@ -51,15 +51,17 @@ constexpr int PERM_FPL = 4;            // permutations per lane (one 16-byte loa
 constexpr int PERM_FTILE = WAVE * PERM_FPL;   // 256
 constexpr int MAX_FTILE = HASH_FTILE;
 constexpr uint32_t CHUNK = 8192;       // rows longer than this are split into chunks of this many nonzeros
+constexpr uint32_t LONG_ITEM = 2048;   // work items with more nonzeros than this are handed out first
 constexpr uint32_t NO_SLOT = 0xFFFFFFFFu;
 
 struct WorkHeader {                    // first 256 bytes of the workspace
-    uint32_t n_items;
+    uint32_t n_long;                   // work items longer than LONG_ITEM: items[0 .. n_long)
+    uint32_t n_short;                  // the others: items[cap_long .. cap_long + n_short)
     uint32_t n_split;
     uint32_t n_parts;
     uint32_t ticket;
     uint32_t status;                   // bit 0: bad row_ptr, bit 1: index >= D, bit 2: work list overflow
-    uint32_t pad[59];
+    uint32_t pad[58];
 };
 static_assert(sizeof(WorkHeader) == 256, "header size");
 
@@ -81,7 +83,7 @@ struct SplitRow {                      // a row processed as several chunks
 
 struct Layout {                        // host and device agree on the workspace layout through this
     size_t items_off, split_rows_off, scratch_off, total;
-    uint64_t cap_items, cap_split, cap_parts;
+    uint64_t cap_long, cap_short, cap_split, cap_parts;
 };
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -89,12 +91,13 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k)
 {
     Layout L;
-    L.cap_items = (uint64_t)n_rows + (uint64_t)nnz_ub / CHUNK + 1;
+    L.cap_long = (uint64_t)nnz_ub / LONG_ITEM + 1;                    // items with more than LONG_ITEM nonzeros
+    L.cap_short = (uint64_t)n_rows + (uint64_t)nnz_ub / CHUNK + 1;    // whole short rows and short last chunks
     uint64_t by_len = (uint64_t)nnz_ub / CHUNK;
     L.cap_split = by_len < (uint64_t)n_rows ? by_len : (uint64_t)n_rows;
     L.cap_parts = by_len + L.cap_split;            // sum over split rows of ceil(nnz / CHUNK)
     L.items_off = sizeof(WorkHeader);
-    L.split_rows_off = align_up(L.items_off + L.cap_items * sizeof(Item), 256);
+    L.split_rows_off = align_up(L.items_off + (L.cap_long + L.cap_short) * sizeof(Item), 256);
     L.scratch_off = align_up(L.split_rows_off + L.cap_split * sizeof(SplitRow), 256);
     L.total = align_up(L.scratch_off + L.cap_parts * (size_t)k * sizeof(uint32_t), 256);
     return L;
@@ -112,7 +115,7 @@ struct KArgs {
     SplitRow* split_rows;
     uint32_t* scratch;                 // [cap_parts][k] partial minima of chunks
     uint64_t D;
-    uint64_t cap_items, cap_split, cap_parts;
+    uint64_t cap_long, cap_short, cap_split, cap_parts;
     ModD md;
     int64_t n_rows;
     int32_t k, b;
@@ -168,7 +171,10 @@ __global__ void mh_reset_kernel(WorkHeader* hdr)
     if (threadIdx.x < 64) reinterpret_cast<uint32_t*>(hdr)[threadIdx.x] = 0;
 }
 
-// One thread per row.  Wave-level prefix sums make one atomic per wavefront.
+// One thread per row.  Wave-level prefix sums make one atomic per wavefront and
+// counter.  Items longer than LONG_ITEM go to the front of the work list, the
+// rest behind them: the persistent wavefronts draw tickets in list order, so the
+// long items start first and the short ones fill the tail of the launch.
 __global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
 {
     const int lane = threadIdx.x & (WAVE - 1);
@@ -185,44 +191,54 @@ __global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
         is_split = nnz > (int64_t)CHUNK ? 1u : 0u;
         n_it = is_split ? (uint32_t)((nnz + CHUNK - 1) / CHUNK) : 1u;
     }
-    // inclusive scans over the wavefront: items, split rows, partial vectors
+    // length of the last (or only) item of the row, and how many of its items are long
+    const int64_t last_len = row < a.n_rows ? nnz - (int64_t)(n_it - 1) * CHUNK : 0;
+    const uint32_t last_long = last_len > (int64_t)LONG_ITEM ? 1u : 0u;
+    const uint32_t n_lg = row < a.n_rows ? (n_it - 1) + last_long : 0u;      // full chunks are always long
+    const uint32_t n_sh = row < a.n_rows ? 1u - last_long : 0u;
     const uint32_t n_pt = is_split ? n_it : 0u;
-    uint32_t inc_it = n_it, inc_sp = is_split, inc_pt = n_pt;
+    // inclusive scans over the wavefront: long items, short items, split rows, partial vectors
+    uint32_t inc_lg = n_lg, inc_sh = n_sh, inc_sp = is_split, inc_pt = n_pt;
     for (int d = 1; d < WAVE; d <<= 1) {
-        uint32_t v1 = (uint32_t)__shfl_up((int)inc_it, d, WAVE);
+        uint32_t v0 = (uint32_t)__shfl_up((int)inc_lg, d, WAVE);
+        uint32_t v1 = (uint32_t)__shfl_up((int)inc_sh, d, WAVE);
         uint32_t v2 = (uint32_t)__shfl_up((int)inc_sp, d, WAVE);
         uint32_t v3 = (uint32_t)__shfl_up((int)inc_pt, d, WAVE);
-        if (lane >= d) { inc_it += v1; inc_sp += v2; inc_pt += v3; }
+        if (lane >= d) { inc_lg += v0; inc_sh += v1; inc_sp += v2; inc_pt += v3; }
     }
-    uint32_t tot_it = wave_bcast(inc_it, WAVE - 1), tot_sp = wave_bcast(inc_sp, WAVE - 1);
-    uint32_t tot_pt = wave_bcast(inc_pt, WAVE - 1);
-    uint32_t base_it = 0, base_sp = 0, base_pt = 0;
+    const uint32_t tot_lg = wave_bcast(inc_lg, WAVE - 1), tot_sh = wave_bcast(inc_sh, WAVE - 1);
+    const uint32_t tot_sp = wave_bcast(inc_sp, WAVE - 1), tot_pt = wave_bcast(inc_pt, WAVE - 1);
+    uint32_t base_lg = 0, base_sh = 0, base_sp = 0, base_pt = 0;
     if (lane == WAVE - 1) {
-        if (tot_it) base_it = atomicAdd(&a.hdr->n_items, tot_it);
+        if (tot_lg) base_lg = atomicAdd(&a.hdr->n_long, tot_lg);
+        if (tot_sh) base_sh = atomicAdd(&a.hdr->n_short, tot_sh);
         if (tot_sp) base_sp = atomicAdd(&a.hdr->n_split, tot_sp);
         if (tot_pt) base_pt = atomicAdd(&a.hdr->n_parts, tot_pt);
     }
-    base_it = wave_bcast(base_it, WAVE - 1);
+    base_lg = wave_bcast(base_lg, WAVE - 1);
+    base_sh = wave_bcast(base_sh, WAVE - 1);
     base_sp = wave_bcast(base_sp, WAVE - 1);
     base_pt = wave_bcast(base_pt, WAVE - 1);
     if (row >= a.n_rows) return;
-    const uint64_t first = (uint64_t)base_it + inc_it - n_it;
+    const uint64_t first_lg = (uint64_t)base_lg + inc_lg - n_lg;
+    const uint64_t first_sh = (uint64_t)base_sh + inc_sh - n_sh;
     const uint64_t first_part = (uint64_t)base_pt + inc_pt - n_pt;
     // An overflow can only happen when the workspace was sized for fewer nonzeros than
     // row_ptr describes.  Every allocated work-list entry inside the capacity is still
     // written (as an empty row), so that the consumer never reads an undefined entry.
-    bool overflow = first + n_it > a.cap_items;
+    bool overflow = first_lg + n_lg > a.cap_long || first_sh + n_sh > a.cap_short;
     uint64_t sidx = 0;
     if (is_split) {
         sidx = (uint64_t)base_sp + inc_sp - 1;
         overflow = overflow || sidx >= a.cap_split || first_part + n_it > a.cap_parts;
     }
+    Item* long_items = a.items;
+    Item* short_items = a.items + a.cap_long;
     if (overflow) {
         atomicOr(&a.hdr->status, 4u);
-        for (uint32_t c = 0; c < n_it && first + c < a.cap_items; ++c) {
-            Item it; it.begin = begin; it.len = 0; it.row = (uint32_t)row; it.slot = NO_SLOT; it.pad = 1;
-            a.items[first + c] = it;
-        }
+        Item it; it.begin = begin; it.len = 0; it.row = (uint32_t)row; it.slot = NO_SLOT; it.pad = 1;
+        for (uint32_t c = 0; c < n_lg && first_lg + c < a.cap_long; ++c) long_items[first_lg + c] = it;
+        for (uint32_t c = 0; c < n_sh && first_sh + c < a.cap_short; ++c) short_items[first_sh + c] = it;
         if (is_split && sidx < a.cap_split) {
             SplitRow sr; sr.row = (uint32_t)row; sr.first_part = 0; sr.n_parts = 0; sr.pad = 1;
             a.split_rows[sidx] = sr;
@@ -236,12 +252,13 @@ __global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
     for (uint32_t c = 0; c < n_it; ++c) {
         Item it;
         it.begin = begin + (int64_t)c * CHUNK;
-        int64_t rest = nnz - (int64_t)c * CHUNK;
+        const int64_t rest = nnz - (int64_t)c * CHUNK;
         it.len = is_split ? (uint32_t)(rest < (int64_t)CHUNK ? rest : (int64_t)CHUNK) : (uint32_t)nnz;
         it.row = (uint32_t)row;
         it.slot = is_split ? (uint32_t)(first_part + c) : NO_SLOT;
         it.pad = 0;
-        a.items[first + c] = it;
+        if (it.len > LONG_ITEM) long_items[first_lg + c] = it;       // chunks before the last are full, hence long
+        else short_items[first_sh] = it;
     }
 }
 
@@ -298,7 +315,7 @@ struct Pol2U31 {
     static constexpr int MIN_WAVES = 6;        // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool TRACK_MAX = POW2;
     using Fn = Fn2U31;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
     {
         return valid ? prep_2u31(c[0], c[1]) : prep_2u31(0, 0);
     }
@@ -319,7 +336,7 @@ struct Pol4U31 {
     static constexpr int MIN_WAVES = 4;
     static constexpr bool TRACK_MAX = POW2;
     using Fn = Fn4U31;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
     {
         return valid ? prep_4u31(c[0], c[1], c[2], c[3]) : prep_4u31(0, 0, 0, 0);
     }
@@ -346,7 +363,7 @@ struct Pol2U61 {
     static constexpr int MIN_WAVES = 6;
     static constexpr bool TRACK_MAX = false;
     using Fn = Fn2U61;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
     {
         return valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
     }
@@ -500,12 +517,12 @@ struct PolGenericMod {
     static constexpr bool TRACK_MAX = false;
     static constexpr int DEG = DEGREE;
     struct Fn { uint64_t c[DEGREE]; uint64_t p; };
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t prime)
     {
         Fn f;
 #pragma unroll
         for (int i = 0; i < DEGREE; ++i) f.c[i] = valid ? c[i] : 0;
-        f.p = 0;
+        f.p = prime;                   // a kernel argument, so that the compiler cannot specialise the % on it
         return f;
     }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
@@ -531,7 +548,7 @@ struct Pol2UMS32 {
     static constexpr int MIN_WAVES = 6;
     static constexpr bool TRACK_MAX = false;
     using Fn = Fn2UMS32;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
     {
         return valid ? prep_2ums32(c[0], c[1]) : prep_2ums32(0, 0);
     }
@@ -608,11 +625,6 @@ __device__ __forceinline__ void load_tile(const uint32_t* col, int64_t begin, ui
     }
 }
 
-// only the ablation policy carries a runtime modulus
-template <class Fn>
-__device__ __forceinline__ auto set_runtime_prime(Fn& f, uint64_t p) -> decltype(f.p, void()) { f.p = p; }
-__device__ __forceinline__ void set_runtime_prime(...) {}
-
 // ------------------------------------------------------------------ the hash kernel
 template <class Pol>
 __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_WAVES, 8))) void mh_hash_kernel(KArgs a)
@@ -630,8 +642,9 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
     const int fl = lane & (fl_lanes - 1);
     const int slice = lane >> a.log2_fl;
 
-    const uint32_t n_items = a.hdr->n_items < a.cap_items ? a.hdr->n_items : (uint32_t)a.cap_items;
-    const uint64_t n_units = (uint64_t)n_items * (uint64_t)a.n_ftiles;
+    const uint32_t n_long = a.hdr->n_long < a.cap_long ? a.hdr->n_long : (uint32_t)a.cap_long;
+    const uint32_t n_short = a.hdr->n_short < a.cap_short ? a.hdr->n_short : (uint32_t)a.cap_short;
+    const uint64_t n_units = ((uint64_t)n_long + n_short) * (uint64_t)a.n_ftiles;
 
     ModD md = a.md;
     if (Pol::NW == 3 && md.pow2) md.M = P31;   // the 4U fold wants 2^31-1 in a vector register; the mask path does not use M
@@ -656,12 +669,11 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             for (int r = 0; r < HASH_FPL; ++r) {
                 int j = j_base + r;
                 bool valid = j < a.k;
-                fn[r] = Pol::load(coeffs + (size_t)(valid ? j : 0) * Pol::DEG, valid);
-                set_runtime_prime(fn[r], a.prime);
+                fn[r] = Pol::load(coeffs + (size_t)(valid ? j : 0) * Pol::DEG, valid, a.prime);
             }
             cur_ftile = ftile;
         }
-        const Item it = a.items[item_idx];
+        const Item it = item_idx < n_long ? a.items[item_idx] : a.items[a.cap_long + (item_idx - n_long)];
         const int64_t begin = it.begin;
         const uint32_t len = it.len;
 
@@ -756,8 +768,9 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
     uint32_t* mins = s_mins[wave];
     const uint32_t* table = static_cast<const uint32_t*>(a.params);
 
-    const uint32_t n_items = a.hdr->n_items < a.cap_items ? a.hdr->n_items : (uint32_t)a.cap_items;
-    const uint64_t n_units = (uint64_t)n_items * (uint64_t)a.n_ftiles;
+    const uint32_t n_long = a.hdr->n_long < a.cap_long ? a.hdr->n_long : (uint32_t)a.cap_long;
+    const uint32_t n_short = a.hdr->n_short < a.cap_short ? a.hdr->n_short : (uint32_t)a.cap_short;
+    const uint64_t n_units = ((uint64_t)n_long + n_short) * (uint64_t)a.n_ftiles;
     constexpr int U = 8;               // nonzeros in flight per lane
 
     for (;;) {
@@ -767,7 +780,7 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
         if ((uint64_t)ticket >= n_units) break;
         const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
         const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
-        const Item it = a.items[item_idx];
+        const Item it = item_idx < n_long ? a.items[item_idx] : a.items[a.cap_long + (item_idx - n_long)];
         const int64_t begin = it.begin;
         const uint32_t len = it.len;
         const int j0 = ftile * PERM_FTILE;
@@ -926,16 +939,17 @@ int validate_shape(int64_t n_rows, int64_t nnz_ub, int32_t k, int32_t family)
     return MINHASH_OK;
 }
 
-int g_num_cus = 0;
+int query_cus()
+{
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+    return cus;
+}
 int device_cus()
 {
-    if (g_num_cus == 0) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess) return 256;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
-        g_num_cus = cus;
-    }
-    return g_num_cus;
+    static const int cus = query_cus();    // one GPU per process
+    return cus;
 }
 
 // persistent grid: as many blocks as are resident at once, no more
@@ -1005,7 +1019,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     a.items = reinterpret_cast<Item*>(ws + L.items_off);
     a.split_rows = reinterpret_cast<SplitRow*>(ws + L.split_rows_off);
     a.scratch = reinterpret_cast<uint32_t*>(ws + L.scratch_off);
-    a.D = D; a.cap_items = L.cap_items; a.cap_split = L.cap_split; a.cap_parts = L.cap_parts;
+    a.D = D; a.cap_long = L.cap_long; a.cap_short = L.cap_short; a.cap_split = L.cap_split; a.cap_parts = L.cap_parts;
     a.md = make_mod_d(D);
     if (is_multiply_shift(family)) {
         int sbits = 0;
@@ -1029,7 +1043,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         a.log2_fl = 6;
     }
 
-    if (L.cap_items * (uint64_t)a.n_ftiles >= (1ull << 32)) return MINHASH_ERR_ARG;   // tickets are 32-bit
+    if ((L.cap_long + L.cap_short) * (uint64_t)a.n_ftiles >= (1ull << 32)) return MINHASH_ERR_ARG;   // tickets are 32-bit
 
     const int cus = device_cus();
     hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, s, a.hdr);
