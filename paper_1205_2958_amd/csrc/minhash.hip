@@ -4,7 +4,7 @@
 //
 //   mh_reset_kernel      clears the work-list header in the workspace
 //   mh_bin_rows_kernel   load balancer: reads row_ptr, emits one work item per
-//                        row, or one per CHUNK nonzeros for long rows (each
+//                        row, or one per chunk of nonzeros for long rows (each
 //                        chunk gets a vector of k partial minima in the
 //                        workspace)
 //   mh_hash_kernel<..>   (hash families) or mh_perm_kernel<..> (permutation
@@ -50,7 +50,10 @@ constexpr int HASH_FTILE = WAVE * HASH_FPL;   // 512 functions per wavefront pas
 constexpr int PERM_FPL = 4;            // permutations per lane (one 16-byte load)
 constexpr int PERM_FTILE = WAVE * PERM_FPL;   // 256
 constexpr int MAX_FTILE = HASH_FTILE;
-constexpr uint32_t CHUNK = 8192;       // rows longer than this are split into chunks of this many nonzeros
+constexpr uint32_t MAX_CHUNK = 8192;   // rows longer than the chunk size are split into chunks of that many nonzeros;
+constexpr uint32_t MIN_CHUNK = 512;    // the size is chosen per call on the device (see mh_reset_kernel)
+constexpr uint64_t SMALL_BATCH_PARTS = 32768;           // partial vectors reserved so that small batches can use
+constexpr uint64_t SMALL_BATCH_BYTES = 64ull << 20;     // small chunks, capped to this many bytes
 constexpr uint32_t LONG_ITEM = 2048;   // work items with more nonzeros than this are handed out first
 constexpr uint32_t NO_SLOT = 0xFFFFFFFFu;
 
@@ -59,15 +62,16 @@ struct WorkHeader {                    // first 256 bytes of the workspace
     uint32_t n_short;                  // the others: items[cap_long .. cap_long + n_short)
     uint32_t n_split;
     uint32_t n_parts;
+    uint32_t chunk;                    // chunk size of this call, a power of two in [MIN_CHUNK, MAX_CHUNK]
     uint32_t ticket;
     uint32_t status;                   // bit 0: bad row_ptr, bit 1: index >= D, bit 2: work list overflow
-    uint32_t pad[58];
+    uint32_t pad[57];
 };
 static_assert(sizeof(WorkHeader) == 256, "header size");
 
 struct Item {                          // one unit of row work
     int64_t begin;                     // offset of the first nonzero in col_idx
-    uint32_t len;                      // number of nonzeros (<= CHUNK unless the row is whole)
+    uint32_t len;                      // number of nonzeros (at most the chunk size)
     uint32_t row;
     uint32_t slot;                     // NO_SLOT for a whole row, else index of this chunk's vector of partial minima
     uint32_t pad;
@@ -91,11 +95,21 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k)
 {
     Layout L;
-    L.cap_long = (uint64_t)nnz_ub / LONG_ITEM + 1;                    // items with more than LONG_ITEM nonzeros
-    L.cap_short = (uint64_t)n_rows + (uint64_t)nnz_ub / CHUNK + 1;    // whole short rows and short last chunks
-    uint64_t by_len = (uint64_t)nnz_ub / CHUNK;
-    L.cap_split = by_len < (uint64_t)n_rows ? by_len : (uint64_t)n_rows;
-    L.cap_parts = by_len + L.cap_split;            // sum over split rows of ceil(nnz / CHUNK)
+    const uint64_t n = (uint64_t)n_rows, nnz = (uint64_t)nnz_ub;
+    L.cap_long = nnz / LONG_ITEM + 1;                                 // items with more than LONG_ITEM nonzeros
+    const uint64_t by_min = nnz / MIN_CHUNK;
+    L.cap_split = by_min < n ? by_min : n;                            // rows longer than the smallest chunk size
+    // one partial vector per chunk of a split row: at most nnz/chunk + (split rows) for the chunk size in use.
+    // Large batches use MAX_CHUNK; a reserve lets small batches use smaller chunks (the device picks the size
+    // that fits, see mh_reset_kernel).
+    const uint64_t by_max = nnz / MAX_CHUNK;
+    uint64_t reserve = SMALL_BATCH_BYTES / (sizeof(uint32_t) * (uint64_t)k);
+    if (reserve > SMALL_BATCH_PARTS) reserve = SMALL_BATCH_PARTS;
+    uint64_t small_need = by_min + L.cap_split;                       // what MIN_CHUNK would need
+    if (reserve > small_need) reserve = small_need;
+    L.cap_parts = by_max + (by_max < n ? by_max : n);
+    if (L.cap_parts < reserve) L.cap_parts = reserve;
+    L.cap_short = n + L.cap_parts + 1;                                // whole rows, plus chunks not longer than LONG_ITEM
     L.items_off = sizeof(WorkHeader);
     L.split_rows_off = align_up(L.items_off + (L.cap_long + L.cap_short) * sizeof(Item), 256);
     L.scratch_off = align_up(L.split_rows_off + L.cap_split * sizeof(SplitRow), 256);
@@ -122,6 +136,7 @@ struct KArgs {
     int32_t n_ftiles;
     int32_t log2_fl;                   // lanes covering one function tile = 1 << log2_fl
     int32_t sig_bytes;
+    uint32_t target_items;             // work items wanted for a balanced launch (a few per resident wavefront)
     uint32_t validate;
     uint64_t prime;                    // runtime modulus of the generic-% ablation kernels
 };
@@ -166,9 +181,29 @@ __device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c)
 }
 
 // ------------------------------------------------------------------ reset / bin / fill
-__global__ void mh_reset_kernel(WorkHeader* hdr)
+// Clears the header and picks the chunk size of this call: the largest power of two
+// in [MIN_CHUNK, MAX_CHUNK] that still yields target_items work items, as long as the
+// partial vectors of the resulting chunks fit the workspace.  Large batches get
+// MAX_CHUNK; a batch of a few hundred rows gets its long rows cut finely enough to
+// occupy the whole GPU instead of waiting for one wavefront per row.
+__global__ void mh_reset_kernel(KArgs a)
 {
-    if (threadIdx.x < 64) reinterpret_cast<uint32_t*>(hdr)[threadIdx.x] = 0;
+    uint32_t* words = reinterpret_cast<uint32_t*>(a.hdr);
+    if (threadIdx.x < 64 && threadIdx.x != offsetof(WorkHeader, chunk) / 4) words[threadIdx.x] = 0;
+    if (threadIdx.x == 0) {
+        const int64_t total = a.row_ptr[a.n_rows] - a.row_ptr[0];
+        uint32_t chunk = MAX_CHUNK;
+        if (total > 0) {
+            const uint64_t nnz = (uint64_t)total, n = (uint64_t)a.n_rows;
+            while (chunk > MIN_CHUNK) {
+                if (nnz / chunk >= a.target_items) break;
+                const uint64_t by_next = nnz / (chunk / 2);
+                if (by_next + (by_next < n ? by_next : n) > a.cap_parts) break;
+                chunk /= 2;
+            }
+        }
+        a.hdr->chunk = chunk;
+    }
 }
 
 // One thread per row.  Wave-level prefix sums make one atomic per wavefront and
@@ -179,6 +214,8 @@ __global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
 {
     const int lane = threadIdx.x & (WAVE - 1);
     const int64_t row = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+    uint32_t CHUNK = a.hdr->chunk;
+    if (CHUNK < MIN_CHUNK || CHUNK > MAX_CHUNK) CHUNK = MAX_CHUNK;
     uint32_t n_it = 0, is_split = 0;
     int64_t begin = 0, nnz = 0;
     if (row < a.n_rows) {
@@ -194,8 +231,9 @@ __global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
     // length of the last (or only) item of the row, and how many of its items are long
     const int64_t last_len = row < a.n_rows ? nnz - (int64_t)(n_it - 1) * CHUNK : 0;
     const uint32_t last_long = last_len > (int64_t)LONG_ITEM ? 1u : 0u;
-    const uint32_t n_lg = row < a.n_rows ? (n_it - 1) + last_long : 0u;      // full chunks are always long
-    const uint32_t n_sh = row < a.n_rows ? 1u - last_long : 0u;
+    const uint32_t full_long = CHUNK > LONG_ITEM ? 1u : 0u;                  // are full chunks long items?
+    const uint32_t n_lg = row < a.n_rows ? (n_it - 1) * full_long + last_long : 0u;
+    const uint32_t n_sh = row < a.n_rows ? n_it - n_lg : 0u;
     const uint32_t n_pt = is_split ? n_it : 0u;
     // inclusive scans over the wavefront: long items, short items, split rows, partial vectors
     uint32_t inc_lg = n_lg, inc_sh = n_sh, inc_sp = is_split, inc_pt = n_pt;
@@ -249,6 +287,7 @@ __global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
         SplitRow sr; sr.row = (uint32_t)row; sr.first_part = (uint32_t)first_part; sr.n_parts = n_it; sr.pad = 0;
         a.split_rows[sidx] = sr;
     }
+    uint32_t n_long_done = 0, n_short_done = 0;
     for (uint32_t c = 0; c < n_it; ++c) {
         Item it;
         it.begin = begin + (int64_t)c * CHUNK;
@@ -257,8 +296,8 @@ __global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
         it.row = (uint32_t)row;
         it.slot = is_split ? (uint32_t)(first_part + c) : NO_SLOT;
         it.pad = 0;
-        if (it.len > LONG_ITEM) long_items[first_lg + c] = it;       // chunks before the last are full, hence long
-        else short_items[first_sh] = it;
+        if (it.len > LONG_ITEM) long_items[first_lg + (n_long_done++)] = it;
+        else short_items[first_sh + (n_short_done++)] = it;
     }
 }
 
@@ -312,7 +351,7 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 template <bool POW2>
 struct Pol2U31 {
     static constexpr int NW = 1;
-    static constexpr int MIN_WAVES = 6;        // wavefronts per SIMD the register allocation must leave room for
+    static constexpr int MIN_WAVES = 5;        // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool TRACK_MAX = POW2;
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
@@ -360,7 +399,7 @@ struct Pol4U31 {
 template <bool POW2>
 struct Pol2U61 {
     static constexpr int NW = 1;
-    static constexpr int MIN_WAVES = 6;
+    static constexpr int MIN_WAVES = 5;
     static constexpr bool TRACK_MAX = false;
     using Fn = Fn2U61;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
@@ -545,7 +584,7 @@ struct PolGenericMod {
 template <bool HIGH>
 struct Pol2UMS32 {
     static constexpr int NW = 1;
-    static constexpr int MIN_WAVES = 6;
+    static constexpr int MIN_WAVES = 5;
     static constexpr bool TRACK_MAX = false;
     using Fn = Fn2UMS32;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
@@ -633,7 +672,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
     __shared__ uint32_t s_mins[WAVES_PER_BLOCK][HASH_FTILE];
 
     const int lane = threadIdx.x & (WAVE - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: keep it in a scalar register
     uint32_t(*tile)[TILE] = s_tile[wave];
     uint32_t* mins = s_mins[wave];
 
@@ -655,10 +694,19 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
     typename Pol::Fn fn[HASH_FPL];
     int cur_ftile = -1;
 
+    // The first unit of a wavefront is its own index in the grid; later ones come from an
+    // atomic counter that starts behind the grid.  A batch with fewer units than resident
+    // wavefronts therefore costs no atomic at all (thousands of wavefronts hitting one
+    // address would otherwise dominate a small call).
+    const uint32_t grid_waves = gridDim.x * WAVES_PER_BLOCK;
+    bool first_unit = true;
     for (;;) {
-        uint32_t ticket = 0;
-        if (lane == 0) ticket = atomicAdd(&a.hdr->ticket, 1u);
-        ticket = first_lane_value(ticket);
+        uint32_t ticket = blockIdx.x * WAVES_PER_BLOCK + wave;
+        if (!first_unit) {
+            if (lane == 0) ticket = grid_waves + atomicAdd(&a.hdr->ticket, 1u);
+            ticket = first_lane_value(ticket);
+        }
+        first_unit = false;
         if ((uint64_t)ticket >= n_units) break;      // every wavefront reaches this: tickets only grow
         const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
         const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
@@ -763,7 +811,7 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
     __shared__ uint32_t s_tile[WAVES_PER_BLOCK][TILE];
     __shared__ uint32_t s_mins[WAVES_PER_BLOCK][PERM_FTILE];
     const int lane = threadIdx.x & (WAVE - 1);
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint32_t* tile = s_tile[wave];
     uint32_t* mins = s_mins[wave];
     const uint32_t* table = static_cast<const uint32_t*>(a.params);
@@ -773,10 +821,15 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
     const uint64_t n_units = ((uint64_t)n_long + n_short) * (uint64_t)a.n_ftiles;
     constexpr int U = 8;               // nonzeros in flight per lane
 
+    const uint32_t grid_waves = gridDim.x * WAVES_PER_BLOCK;      // first unit = own index, then the atomic counter
+    bool first_unit = true;
     for (;;) {
-        uint32_t ticket = 0;
-        if (lane == 0) ticket = atomicAdd(&a.hdr->ticket, 1u);
-        ticket = first_lane_value(ticket);
+        uint32_t ticket = blockIdx.x * WAVES_PER_BLOCK + wave;
+        if (!first_unit) {
+            if (lane == 0) ticket = grid_waves + atomicAdd(&a.hdr->ticket, 1u);
+            ticket = first_lane_value(ticket);
+        }
+        first_unit = false;
         if ((uint64_t)ticket >= n_units) break;
         const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
         const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
@@ -1030,6 +1083,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     a.sig_bytes = (int32_t)sig_bytes;
     a.validate = (flags & MINHASH_FLAG_VALIDATE) ? 1u : 0u;
     a.prime = P31;
+    a.target_items = 0;
 
     const bool perm = family == MINHASH_PERM;
     const int ftile_size = perm ? PERM_FTILE : HASH_FTILE;
@@ -1046,7 +1100,8 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     if ((L.cap_long + L.cap_short) * (uint64_t)a.n_ftiles >= (1ull << 32)) return MINHASH_ERR_ARG;   // tickets are 32-bit
 
     const int cus = device_cus();
-    hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, s, a.hdr);
+    a.target_items = (uint32_t)cus * 24u * 2u;     // two items per wavefront of a fully occupied launch
+    hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, s, a);
     const int bin_blocks = (int)((n_rows + BLOCK - 1) / BLOCK);
     hipLaunchKernelGGL(mh_bin_rows_kernel, dim3(bin_blocks), dim3(BLOCK), 0, s, a);
 

@@ -331,3 +331,36 @@ def test_streamed_batches_equal_one_shot_and_oracle():
     outs = mh.stream_batches(batches, D, k, b, family, _to_dev(c), max_rows, max_nnz)
     got = np.concatenate([o.numpy() for o in outs], axis=0)
     assert np.array_equal(got, want)
+
+
+def test_call_is_capturable_in_a_hip_graph_and_replays_exactly():
+    """The entry point only enqueues kernels (no allocation, no memset node, no sync), so a
+    serving loop can capture it once and replay it; every replay, with eager work and
+    synchronisations in between and new input bytes in the same buffers, must be exact."""
+    D, k, b, family = 1 << 24, 500, 8, mh.FAMILY_2U_M31
+    nnz = np.array([0, 3, 700, 9000, 20000, 64, 1, 2500], dtype=np.int64)
+    rp = W.row_ptr_from_nnz(nnz)
+    c = W.coefficients(k, family, seed=5)
+    cols = [W.csr_indices_np(nnz, D, seed=100 + i) for i in range(4)]
+    wants = [oracle.signatures(rp, col, D, k, b, family, c) for col in cols]
+    rp_d, c_d = _to_dev(rp), _to_dev(c)
+    col_d = _to_dev(cols[0]).clone()
+    out = torch.zeros((len(nnz), 500), dtype=torch.uint8, device=DEV)
+    ws = mh.alloc_workspace(len(nnz), int(nnz.sum()), k, family, DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                            # warm-up outside the capture
+        mh.minhash_signatures(rp_d, col_d, D, k, b, family, c_d, out=out, workspace=ws, stream=side)
+    side.synchronize()
+    assert np.array_equal(out.cpu().numpy(), wants[0])
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        mh.minhash_signatures(rp_d, col_d, D, k, b, family, c_d, out=out, workspace=ws,
+                              stream=torch.cuda.current_stream())
+    for i in (1, 2, 3, 0):
+        col_d.copy_(_to_dev(cols[i]))                        # eager work between replays
+        out.fill_(0x55)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.cpu().numpy(), wants[i]), "replay with input %d" % i
