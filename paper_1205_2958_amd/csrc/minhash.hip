@@ -2,14 +2,16 @@
 //
 // One call of minhash_signatures enqueues, on the caller's stream:
 //
-//   mh_reset_kernel      clears the work-list header in the workspace
+//   mh_reset_kernel      clears the work-list header in the workspace and picks
+//                        the chunk size of this call from the batch's size
 //   mh_bin_rows_kernel   load balancer: reads row_ptr, emits one work item per
 //                        row, or one per chunk of nonzeros for long rows (each
 //                        chunk gets a vector of k partial minima in the
-//                        workspace)
+//                        workspace); long items are listed first
 //   mh_hash_kernel<..>   (hash families) or mh_perm_kernel<..> (permutation
 //                        table): the hot loop.  Persistent wavefronts take
-//                        (item, function-tile) units from an atomic ticket.
+//                        (item, function-tile) units: their own grid index
+//                        first, then tickets from an atomic counter.
 //                        A wavefront stages 256 nonzeros at a time into LDS
 //                        with coalesced loads (pre-computing what depends on t
 //                        alone), then every lane evaluates its 8 hash functions
