@@ -486,63 +486,44 @@ __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
 // evaluation are issued function-major so that each waits for a result that is
 // 16 instructions old; the fold of nonzero A overlaps the last multiply-adds of
 // nonzero B.  Arithmetic of hash_compl_4u31 (mh_arith.h), instruction for instruction.
+__device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], const uint32_t* w,
+                                               uint32_t mask, uint32_t p31)
+{
+    uint64_t acc[HASH_FPL], cy;
+    uint32_t u[HASH_FPL], v[HASH_FPL];
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %4" : "=v"(acc[g]), "=s"(cy) : "v"(fn[g].c1), "v"(w[0]), "v"(fn[g].add));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(acc[g]), "=s"(cy) : "v"(fn[g].c2), "v"(w[1]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(acc[g]), "=s"(cy) : "v"(fn[g].c3), "v"(w[2]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(y[g]) : "v"((uint32_t)acc[g]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(u[g]) : "v"((uint32_t)(acc[g] >> 32)), "v"(p31));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(v[g]) : "v"((uint32_t)(acc[g] >> 32)));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(y[g]) : "v"(u[g]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(y[g]) : "v"(v[g]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_ashrrev_i32 %0, 31, %1" : "=v"(u[g]) : "v"(y[g]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_sub_u32 %0, %1, %0" : "+v"(y[g]) : "v"(u[g]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(y[g]) : "v"(mask));
+}
+
 __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
                                                const uint32_t* wa, const uint32_t* wb, uint32_t mask, uint32_t p31)
 {
-    uint64_t aa[HASH_FPL], ab[HASH_FPL], cy;
-    uint32_t ya[HASH_FPL], yb[HASH_FPL], ua[HASH_FPL], ub[HASH_FPL], va[HASH_FPL], vb[HASH_FPL];
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
-        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %4" : "=v"(aa[g]), "=s"(cy) : "v"(fn[g].c1), "v"(wa[0]), "v"(fn[g].add));
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
-        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %4" : "=v"(ab[g]), "=s"(cy) : "v"(fn[g].c1), "v"(wb[0]), "v"(fn[g].add));
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
-        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(aa[g]), "=s"(cy) : "v"(fn[g].c2), "v"(wa[1]));
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
-        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(ab[g]), "=s"(cy) : "v"(fn[g].c2), "v"(wb[1]));
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
-        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(aa[g]), "=s"(cy) : "v"(fn[g].c3), "v"(wa[2]));
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) {
-        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(ab[g]), "=s"(cy) : "v"(fn[g].c3), "v"(wb[2]));
-        asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(ya[g]) : "v"((uint32_t)aa[g]));
-        asm volatile("v_and_b32 %0, %1, %2" : "=v"(ua[g]) : "v"((uint32_t)(aa[g] >> 32)), "v"(p31));
-    }
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) {
-        asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(va[g]) : "v"((uint32_t)(aa[g] >> 32)));
-        asm volatile("v_add_u32 %0, %0, %1" : "+v"(ya[g]) : "v"(ua[g]));
-        asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(yb[g]) : "v"((uint32_t)ab[g]));
-    }
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) {
-        asm volatile("v_add_u32 %0, %0, %1" : "+v"(ya[g]) : "v"(va[g]));
-        asm volatile("v_and_b32 %0, %1, %2" : "=v"(ub[g]) : "v"((uint32_t)(ab[g] >> 32)), "v"(p31));
-        asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(vb[g]) : "v"((uint32_t)(ab[g] >> 32)));
-    }
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) {
-        asm volatile("v_ashrrev_i32 %0, 31, %1" : "=v"(ua[g]) : "v"(ya[g]));
-        asm volatile("v_add_u32 %0, %0, %1" : "+v"(yb[g]) : "v"(ub[g]));
-    }
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) {
-        asm volatile("v_sub_u32 %0, %1, %0" : "+v"(ya[g]) : "v"(ua[g]));
-        asm volatile("v_add_u32 %0, %0, %1" : "+v"(yb[g]) : "v"(vb[g]));
-    }
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) {
-        asm volatile("v_and_b32 %0, %0, %1" : "+v"(ya[g]) : "v"(mask));
-        asm volatile("v_ashrrev_i32 %0, 31, %1" : "=v"(ub[g]) : "v"(yb[g]));
-    }
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_sub_u32 %0, %1, %0" : "+v"(yb[g]) : "v"(ub[g]));
-#pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(yb[g]) : "v"(mask));
+    uint32_t ya[HASH_FPL], yb[HASH_FPL];
+    half_4u31_pow2(fn, ya, wa, mask, p31);
+    half_4u31_pow2(fn, yb, wb, mask, p31);
 #pragma unroll
     for (int g = 0; g < HASH_FPL; ++g)
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
