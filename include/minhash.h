@@ -27,7 +27,7 @@ enum {
     MINHASH_4U_M31 = 1,  /* ((c0 + c1 t + c2 t^2 + c3 t^3) mod (2^31-1)) mod D Section 2, eq. "eqn_h_4U";
                             Mersenne reduction as in Section 3.4               */
     MINHASH_2U_M61 = 2,  /* 2U with p = 2^61-1 (Section 3.4, last paragraph)   */
-    MINHASH_4U_M61 = 3,  /* not implemented: returns MINHASH_ERR_FAMILY        */
+    MINHASH_4U_M61 = 3,  /* 4U (eq. "eqn_h_4U") with p = 2^61-1                 */
     MINHASH_PERM   = 4,  /* explicit D x k permutation matrix, Section 1.5     */
     MINHASH_2U_MS32 = 5, /* ((c0 + c1 t) mod 2^32) mod 2^s, D = 2^s, c1 odd: the multiply-shift 2U of
                             Section 3.3, eq. "eqn_h_s", as printed (lowest s bits)              */
@@ -39,7 +39,7 @@ enum {
 enum {
     MINHASH_OK            =  0,
     MINHASH_ERR_ARG       = -1,  /* null pointer, negative size, n_rows or nnz bound too large */
-    MINHASH_ERR_FAMILY    = -2,  /* unknown or unimplemented family                            */
+    MINHASH_ERR_FAMILY    = -2,  /* unknown family                                             */
     MINHASH_ERR_D         = -3,  /* D == 0, D > 2^32, or D >= p for a hash family              */
     MINHASH_ERR_KB        = -4,  /* k < 1, k > MINHASH_MAX_K, b < 1 or b > 32                  */
     MINHASH_ERR_STRIDE    = -5,  /* out_stride < ceil(k*b/8) or perm_ld < k                    */

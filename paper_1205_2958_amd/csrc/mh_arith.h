@@ -254,6 +254,69 @@ MH_HD uint32_t hash_2u61(const Fn2U61& f, uint32_t t, const ModD& md, uint64_t D
     return (uint32_t)(residue_wide_2u61(f, t) % D);
 }
 
+// ---------------------------------------------------------------- 4U, p = 2^61-1 (eq. eqn_4U with the prime of Section 3.4's last paragraph)
+// Horner form: three steps acc <- acc t + c, each one 62-bit x 32-bit product
+// built from two widening multiply-adds (the low word of the addend joins the low
+// product, its high word the high product, so neither overflows 64 bits for any
+// t < 2^32), followed by the 2^61 = 1 (mod p) fold of residue_2u61.  The fold is
+// left partial between steps: acc stays below 2^61 + 2^34, which the next step
+// accepts.  The last addend carries the +1 offset, so the final x lies in
+// [1, 2^61 + 2^34) and the canonical residue is (x + (x >> 61) - 1) & p.
+struct Fn4U61 {
+    uint32_t c3lo, c3hi, c2lo, c2hi, c1lo, c1hi, a0lo, a0hi;   // a0 = c0 + 1 <= p
+};
+MH_HD Fn4U61 prep_4u61(uint64_t c0, uint64_t c1, uint64_t c2, uint64_t c3)
+{
+    Fn4U61 f;
+    f.c3lo = (uint32_t)c3; f.c3hi = (uint32_t)(c3 >> 32);
+    f.c2lo = (uint32_t)c2; f.c2hi = (uint32_t)(c2 >> 32);
+    f.c1lo = (uint32_t)c1; f.c1hi = (uint32_t)(c1 >> 32);
+    f.a0lo = (uint32_t)(c0 + 1); f.a0hi = (uint32_t)((c0 + 1) >> 32);
+    return f;
+}
+
+// one Horner step on (lo, hi) words; hi < 2^30 on entry and on exit
+MH_HD void horner_step_61(uint32_t& lo, uint32_t& hi, uint32_t t, uint32_t add_lo, uint32_t add_hi)
+{
+    uint64_t L = (uint64_t)lo * t + add_lo;                 // <= (2^32-1)^2 + 2^32 - 1 < 2^64
+    uint64_t H = (uint64_t)hi * t + (L >> 32) + add_hi;     // < 2^62 + 2^33
+    uint32_t Hl = (uint32_t)H, Hh = (uint32_t)(H >> 32);
+    uint32_t s_lo = (Hl >> 29) | (Hh << 3);                 // (H >> 29) mod 2^32
+    uint32_t s_hi = Hh >> 29;                               // (H >> 29) >> 32: 0..2
+    uint32_t x_lo = (uint32_t)L + s_lo;
+    uint32_t carry = x_lo < s_lo ? 1u : 0u;
+    lo = x_lo;
+    hi = (Hl & 0x1FFFFFFFu) + s_hi + carry;                 // < 2^29 + 4
+}
+
+// canonical residue (61 bits) for any t < 2^32
+MH_HD uint64_t residue_4u61(const Fn4U61& f, uint32_t t)
+{
+    uint32_t lo = f.c3lo, hi = f.c3hi;
+    horner_step_61(lo, hi, t, f.c2lo, f.c2hi);
+    horner_step_61(lo, hi, t, f.c1lo, f.c1hi);
+    horner_step_61(lo, hi, t, f.a0lo, f.a0hi);
+    uint64_t x = ((uint64_t)hi << 32) | lo;
+    return (x + (x >> 61) - 1) & P61;
+}
+
+// low 32 bits of the canonical residue (all that a power-of-two D <= 2^32 needs)
+MH_HD uint32_t residue_lo_4u61(const Fn4U61& f, uint32_t t)
+{
+    uint32_t lo = f.c3lo, hi = f.c3hi;
+    horner_step_61(lo, hi, t, f.c2lo, f.c2hi);
+    horner_step_61(lo, hi, t, f.c1lo, f.c1hi);
+    horner_step_61(lo, hi, t, f.a0lo, f.a0hi);
+    return lo + (hi >> 29) - 1u;
+}
+
+template <bool POW2>
+MH_HD uint32_t hash_4u61(const Fn4U61& f, uint32_t t, const ModD& md, uint64_t D)
+{
+    if (POW2) return residue_lo_4u61(f, t) & md.mask;
+    return (uint32_t)(residue_4u61(f, t) % D);
+}
+
 // ---------------------------------------------------------------- multiply-shift 2U (Section 3.3, eq. eqn_h_s)
 // ((c0 + c1 t) mod 2^32) mod 2^s: the low word of one multiply-add, then a mask
 // (lowest s bits, as the paper prints it) or a shift (highest s bits, the form of

@@ -424,6 +424,32 @@ struct Pol2U61 {
     static constexpr int DEG = 2;
 };
 
+// 4U with p = 2^61-1: three Horner steps per evaluation on the raw index (any t <
+// 2^32, so one policy serves every D).  Eight functions hold 64 coefficient words.
+template <bool POW2>
+struct Pol4U61 {
+    static constexpr int NW = 1;
+    static constexpr int MIN_WAVES = 2;
+    static constexpr bool PREFETCH = false;
+    static constexpr bool TRACK_MAX = false;
+    using Fn = Fn4U61;
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
+    {
+        return valid ? prep_4u61(c[0], c[1], c[2], c[3]) : prep_4u61(0, 0, 0, 0);
+    }
+    static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
+    static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t D)
+    {
+        return hash_4u61<POW2>(f, w[0], md, D);
+    }
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+                                                const uint32_t* wb, const ModD& md, uint64_t D)
+    {
+        pair_generic<Pol4U61<POW2>>(fn, m, wa, wb, md, D);
+    }
+    static constexpr int DEG = 4;
+};
+
 // ------------------------------------------------------------------ two nonzeros x 8 functions
 // The unit of the hot loop: fold the 16 evaluations of two staged nonzeros into
 // the 8 running extrema.  The generic form leaves the schedule to the compiler.
@@ -997,7 +1023,7 @@ int validate_shape(int64_t n_rows, int64_t nnz_ub, int32_t k, int32_t family)
     if (n_rows < 0 || n_rows >= (1ll << 31) || nnz_ub < 0) return MINHASH_ERR_ARG;
     if (family != MINHASH_PERM) {
         uint64_t p; int deg;
-        if (!family_prime(family, &p, &deg) || family == MINHASH_4U_M61) return MINHASH_ERR_FAMILY;
+        if (!family_prime(family, &p, &deg)) return MINHASH_ERR_FAMILY;
     }
     if (k < 1 || k > MINHASH_MAX_K) return MINHASH_ERR_KB;
     return MINHASH_OK;
@@ -1140,6 +1166,9 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         if (pow2 && D <= (1ull << 31)) launch_hash<Pol2U61<true>>(a, main_blocks, s);
         else launch_hash<Pol2U61<false>>(a, main_blocks, s);
         break;
+    case MINHASH_4U_M61:
+        if (pow2) launch_hash<Pol4U61<true>>(a, main_blocks, s); else launch_hash<Pol4U61<false>>(a, main_blocks, s);
+        break;
     case MINHASH_2U_MS32: launch_hash<Pol2UMS32<false>>(a, main_blocks, s); break;
     case MINHASH_2U_MS32_HIGH: launch_hash<Pol2UMS32<true>>(a, main_blocks, s); break;
     case MINHASH_PERM: {
@@ -1231,7 +1260,7 @@ const char* minhash_error_string(int code)
     switch (code) {
     case MINHASH_OK: return "ok";
     case MINHASH_ERR_ARG: return "invalid argument";
-    case MINHASH_ERR_FAMILY: return "unknown or unimplemented hash family";
+    case MINHASH_ERR_FAMILY: return "unknown hash family";
     case MINHASH_ERR_D: return "D out of range (need 1 <= D <= 2^32 and D < p for hash families)";
     case MINHASH_ERR_KB: return "k or b out of range";
     case MINHASH_ERR_STRIDE: return "out_stride or perm_ld too small";

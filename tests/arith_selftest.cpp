@@ -73,6 +73,16 @@ static void check61(uint64_t D, const uint64_t* c, uint32_t t)
     if (g != want) FAIL("2U61 D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
                         (unsigned long long)c[0], (unsigned long long)c[1], g, (unsigned long long)want);
     ++checks;
+    // 4U with the same prime: Horner form against the power-sum definition
+    uint64_t want4 = ref_poly(c, 4, P61, D, t);
+    Fn4U61 f4 = prep_4u61(c[0], c[1], c[2], c[3]);
+    u128 full4 = 0, pw = 1;
+    for (int i = 0; i < 4; ++i) { full4 = (full4 + (u128)c[i] * pw) % P61; pw = pw * t % P61; }
+    if (residue_4u61(f4, t) != (uint64_t)full4) FAIL("4U61 residue t=%u c=(%llu,%llu,%llu,%llu)", t, (unsigned long long)c[0],
+                                                     (unsigned long long)c[1], (unsigned long long)c[2], (unsigned long long)c[3]);
+    uint32_t g4 = md.pow2 ? hash_4u61<true>(f4, t, md, D) : hash_4u61<false>(f4, t, md, D);
+    if (g4 != want4) FAIL("4U61 D=%llu t=%u got %u want %llu", (unsigned long long)D, t, g4, (unsigned long long)want4);
+    ++checks;
 }
 
 int main()
@@ -124,13 +134,16 @@ int main()
     }
     for (uint64_t D : D61) {
         std::vector<uint32_t> ts = {0, 1, (uint32_t)(D - 1), (uint32_t)(D / 2), (uint32_t)((D - 1) / 3)};
+        ts.push_back(0xFFFFFFFFu % (uint32_t)(D > 0xFFFFFFFFull ? 0xFFFFFFFFull : D));
         for (uint64_t c0 : edge61) for (uint64_t c1 : edge61) for (uint32_t t : ts) {
-            uint64_t c[2] = {c0, c1};
+            uint64_t c[4] = {c0, c1, edge61[(c0 + t) % edge61.size()], edge61[(c1 + 3) % edge61.size()]};
             check61(D, c, t);
+            uint64_t e[4] = {c[2], c[3], c0, c1};          // every edge pair also as (c2, c3)
+            check61(D, e, t);
         }
         for (int i = 0; i < 300000; ++i) {
-            uint64_t c[2] = {rnd() % p61, rnd() % p61};
-            if (i % 7 == 0) c[rnd() % 2] = edge61[rnd() % edge61.size()];
+            uint64_t c[4] = {rnd() % p61, rnd() % p61, rnd() % p61, rnd() % p61};
+            if (i % 7 == 0) c[rnd() % 4] = edge61[rnd() % edge61.size()];
             uint32_t t = (uint32_t)(rnd() % D);
             check61(D, c, t);
         }

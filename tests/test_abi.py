@@ -52,12 +52,12 @@ def test_workspace_size_query():
     assert mh.workspace_bytes(10, -1, 64, 0) == 0
     assert mh.workspace_bytes(10, 10, 0, 0) == 0
     assert mh.workspace_bytes(10, 10, 64, 9) == 0
-    assert mh.workspace_bytes(10, 10, 64, mh.FAMILY_4U_M61) == 0
+    assert mh.workspace_bytes(10, 10, 64, mh.FAMILY_4U_M61) > 0
     assert mh.workspace_bytes(1 << 31, 10, 64, 0) == 0
 
 
 def test_coefficient_range_check():
-    for fam in (mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61):
+    for fam in (mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61, mh.FAMILY_4U_M61):
         c = W.coefficients(16, fam, seed=1)
         mh.check_coeffs(c, fam)
         c[3, 1] = W.family_prime(fam)
@@ -92,7 +92,9 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert _call(lib, n_rows=-1) == -1
     assert _call(lib, n_rows=1 << 31) == -1
     assert _call(lib, family=7) == -2
-    assert _call(lib, family=mh.FAMILY_4U_M61) == -2
+    assert _call(lib, family=-1) == -2
+    assert _call(lib, family=mh.FAMILY_4U_M61, D=1 << 32, n_rows=0) == 0
+    assert _call(lib, family=mh.FAMILY_4U_M61, flags=2) == -1           # no % ablation for p = 2^61 - 1
     assert _call(lib, D=0) == -3
     assert _call(lib, D=(1 << 32) + 1) == -3
     assert _call(lib, D=(1 << 31) - 1) == -3                          # D must be below p = 2^31 - 1

@@ -77,6 +77,7 @@ def test_tiny_2u_workload_every_row():
     (mh.FAMILY_2U_M31, 1 << 24, 8),
     (mh.FAMILY_4U_M31, 1 << 24, 8),
     (mh.FAMILY_2U_M61, 1 << 30, 1),
+    (mh.FAMILY_4U_M61, 1 << 30, 2),
 ])
 def test_hash_families_k500_edge_lengths(family, D, b):
     rp, col = edge_rows(D, seed=42 + family, extra=(50000,))
@@ -100,7 +101,7 @@ def test_bit_widths_and_unaligned_rows(b):
     check_case(rp, col, D, k, b, mh.FAMILY_2U_M31, c, out_stride=sig + 3)     # pad bytes, odd pitch
 
 
-@pytest.mark.parametrize("family", [mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61])
+@pytest.mark.parametrize("family", [mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61, mh.FAMILY_4U_M61])
 @pytest.mark.parametrize("D", [1, 2, 1 << 10, 1 << 20, 1 << 30, 3, 1000003, 16609143, 1010017424])
 def test_universe_sizes_including_non_powers_of_two(family, D):
     nnz = np.minimum(np.array([0, 1, 2, 5, 64, 300, 1000, 9000], dtype=np.int64), D)
@@ -161,9 +162,10 @@ def test_m61_large_universes():
                               for m in nnz] + [np.array([D - 1], dtype=np.uint32)])
         nnz = np.append(nnz, 1)
         rp = W.row_ptr_from_nnz(nnz)
-        c = W.coefficients(24, mh.FAMILY_2U_M61, seed=4)
-        c[0, :] = W.M61 - 1
-        check_case(rp, col, D, 24, 32, mh.FAMILY_2U_M61, c)
+        for family in (mh.FAMILY_2U_M61, mh.FAMILY_4U_M61):
+            c = W.coefficients(24, family, seed=4)
+            c[0, :] = W.M61 - 1
+            check_case(rp, col, D, 24, 32, family, c)
 
 
 def test_extreme_coefficients_and_indices():
@@ -171,7 +173,7 @@ def test_extreme_coefficients_and_indices():
     D = 1 << 24
     col = np.array([0, D - 1, 1, 0, 0, D - 1, D - 1, 12345], dtype=np.uint32)
     rp = np.array([0, 2, 3, 4, 6, 8], dtype=np.int64)
-    for family in (mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61):
+    for family in (mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61, mh.FAMILY_4U_M61):
         p, deg = W.family_prime(family), W.family_degree(family)
         vals = [0, 1, p - 1, p - 2, (p - 1) // 2, (p + 1) // 2, D % p, 2]
         rows = []
