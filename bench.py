@@ -39,6 +39,11 @@ SLOTS_PER_EVAL = {
     W.FAMILY_2U_M61: 2.0 + 1.0 + 2.0 + 7 * 0.5 + 0.5,      # 2 mad; funnel shift; add/addc; 7 simple; half a min3
     W.FAMILY_2U_MS32: 1.0 + 0.5 + 0.5,                      # mad; and; half a min3
 }
+# other D (--universe): exact multiply-high quotient appended
+SLOTS_PER_EVAL_OTHER_D = {
+    W.FAMILY_2U_M31: 1.0 + 2 * 0.5 + 0.5 + 1.0 + 1.0 + 0.5 + 1.0 + 0.5,   # mad; shr,add; sub; min; mulhi; shr; mad; half a min3
+    W.FAMILY_4U_M31: 3.0 + 5 * 0.5 + 2 * 0.5 + 1.0 + 1.0 + 0.5 + 1.0 + 0.5,
+}
 ALU_PEAK_SLOTS = 256 * 4 * 16 * 2.4e9                      # 39.3e12 lane-slots/s
 HBM_PEAK = 8.0e12
 # HBM bytes per launch of the dominant kernel on the full workload, from two rocprofv3 --pmc runs
@@ -53,7 +58,7 @@ def _oracle_worker(args):
     return oracle.signatures(rp, col, D, k, b, family, params)
 
 
-def cpu_baseline(w: W.Workload, params: np.ndarray, target_evals_per_core: float, procs: int):
+def cpu_baseline(w: W.Workload, params: np.ndarray, target_evals_per_core: float, procs: int, universe: int = 0):
     """Times the unchanged single-threaded oracle on the first rows of the workload,
     sharded over `procs` processes.  Returns (record, rows, signatures)."""
     import multiprocessing as mp
@@ -65,6 +70,10 @@ def cpu_baseline(w: W.Workload, params: np.ndarray, target_evals_per_core: float
     nnz = nnz_all[:n_sample]
     rp = W.row_ptr_from_nnz(nnz)
     col = W.csr_indices_np(nnz, w.D, w.data_seed)
+    D = w.D
+    if universe:
+        D = universe
+        col = (col % np.uint32(D)).astype(np.uint32)
     # shards balanced by nonzeros
     bounds = [0]
     per = rp[-1] / procs
@@ -74,12 +83,12 @@ def cpu_baseline(w: W.Workload, params: np.ndarray, target_evals_per_core: float
     bounds = sorted(set(min(max(b, 0), n_sample) for b in bounds))
     jobs = []
     for lo, hi in zip(bounds[:-1], bounds[1:]):
-        jobs.append((rp[lo:hi + 1] - rp[lo], col[rp[lo]:rp[hi]], w.D, w.k, w.b, w.family, params))
+        jobs.append((rp[lo:hi + 1] - rp[lo], col[rp[lo]:rp[hi]], D, w.k, w.b, w.family, params))
     ctx = mp.get_context("fork")
     from oracle import oracle
     oracle.build()
     with ctx.Pool(len(jobs)) as pool:
-        pool.map(_oracle_worker, [(np.zeros(2, np.int64), np.zeros(0, np.uint32), w.D, w.k, w.b, w.family, params)] * len(jobs))
+        pool.map(_oracle_worker, [(np.zeros(2, np.int64), np.zeros(0, np.uint32), D, w.k, w.b, w.family, params)] * len(jobs))
         t0 = time.perf_counter()
         parts = pool.map(_oracle_worker, jobs, chunksize=1)
         dt = time.perf_counter() - t0
@@ -253,6 +262,9 @@ def main() -> int:
                     help="with --stream: batches held in pinned host memory (8 GB each)")
     ap.add_argument("--generic-mod", action="store_true",
                     help="ablation: hash with the plain %% operator instead of the Mersenne reduction (2U/4U, p = 2^31-1)")
+    ap.add_argument("--universe", type=int, default=0,
+                    help="hash families with p = 2^31-1: run with this universe size D instead of the workload's power of "
+                         "two (indices are folded into [0, D)), e.g. 16609143, to time the path for other D")
     ap.add_argument("--calib", action="store_true",
                     help="also launch one plain streaming kernel of known size (reads 1 GiB, writes 1 GiB) so that "
                          "FETCH_SIZE / WRITE_SIZE counters of a profiler run can be scaled")
@@ -266,6 +278,11 @@ def main() -> int:
         return consumers_mode(args)
     w = W.WORKLOADS[args.workload]
     family = w.family
+    if args.universe and (family not in SLOTS_PER_EVAL_OTHER_D or args.stream or args.generic_mod
+                          or not 1 <= args.universe < w.D):
+        print("bench.py: --universe needs a 2U/4U workload with p = 2^31-1 and a D below the workload's", file=sys.stderr)
+        return 2
+    D = args.universe or w.D
     if family == W.FAMILY_PERM:
         params_np = None
     else:
@@ -277,7 +294,7 @@ def main() -> int:
         procs = max(1, min(16, os.cpu_count() or 1))
         rate_guess = {W.FAMILY_2U_M31: 3.0e7, W.FAMILY_4U_M31: 1.2e7, W.FAMILY_2U_M61: 2.0e7,
                       W.FAMILY_2U_MS32: 6.0e7}[family]
-        cpu_rec, n_sample, cpu_sig = cpu_baseline(w, params_np, rate_guess * args.cpu_seconds, procs)
+        cpu_rec, n_sample, cpu_sig = cpu_baseline(w, params_np, rate_guess * args.cpu_seconds, procs, args.universe)
 
     import torch
     from paper_1205_2958_amd import minhash as mh
@@ -299,6 +316,8 @@ def main() -> int:
     total_nnz = int(rp_np[-1])
     t0 = time.perf_counter()
     col = W.csr_indices_torch(nnz, w.D, w.data_seed, dev)
+    if args.universe:
+        col.remainder_(D)                   # indices are below 2^31, so the int32 view is non-negative
     rp = torch.from_numpy(rp_np).to(dev)
     perm_ld = 0
     if family == W.FAMILY_PERM:
@@ -317,7 +336,7 @@ def main() -> int:
     flags = mh.FLAG_GENERIC_MOD if args.generic_mod else 0
 
     def step():
-        mh.minhash_signatures(rp, col, w.D, w.k, w.b, family, params, out=out, workspace=ws, stream=stream,
+        mh.minhash_signatures(rp, col, D, w.k, w.b, family, params, out=out, workspace=ws, stream=stream,
                               perm_ld=perm_ld if family == W.FAMILY_PERM else None, flags=flags)
 
     if args.calib:
@@ -348,7 +367,7 @@ def main() -> int:
     # ---- dominant kernel alone, HIP events on the launch stream
     kms = []
     for _ in range(args.steps):
-        _, ms = mh.minhash_signatures_profiled(rp, col, w.D, w.k, w.b, family, params, out=out, workspace=ws,
+        _, ms = mh.minhash_signatures_profiled(rp, col, D, w.k, w.b, family, params, out=out, workspace=ws,
                                                stream=stream, perm_ld=perm_ld if family == W.FAMILY_PERM else None,
                                                flags=flags)
         kms.append(ms)
@@ -359,13 +378,13 @@ def main() -> int:
                 "traffic": None, "kernel": "mh_perm_kernel", "kernel_ms": k_ms,
                 "model": "4k+4 bytes per nonzero (one table row + the index) + row_ptr + packed output"}
     else:
-        slots = SLOTS_PER_EVAL[family]
+        slots = SLOTS_PER_EVAL_OTHER_D[family] if (D & (D - 1)) else SLOTS_PER_EVAL[family]
         roof = {"bound": "alu", "achieved": evals * slots / (k_ms * 1e-3) / 1e12, "peak": ALU_PEAK_SLOTS / 1e12,
                 "unit": "TOP/s", "traffic": None, "kernel": "mh_hash_kernel", "kernel_ms": k_ms,
                 "model": "%.1f issue slots per hash evaluation; peak = 256 CU x 4 SIMD x 16 lanes x 2.4 GHz "
                          "full-issue lane-slots/s (simple 2-operand integer ops count 1/2)" % slots}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    if not args.rows:
+    if not args.rows and not args.universe:
         roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name)
 
     rec = {
@@ -381,7 +400,9 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "u32/u64 integer" if family != W.FAMILY_PERM else "u32",
         "data": "synthetic (seeded; stands in for the paper's webspam / rcv1 shapes)",
-        "config": {"workload": w.name + (" (generic % ablation)" if args.generic_mod else ""), "n_rows": n_rows, "nnz": total_nnz, "D": w.D, "k": w.k, "b": w.b,
+        "config": {"workload": w.name + (" (generic % ablation)" if args.generic_mod else "")
+                   + (" with indices folded into D = %d" % D if args.universe else ""),
+                   "n_rows": n_rows, "nnz": total_nnz, "D": D, "k": w.k, "b": w.b,
                    "family": family, "setup_s": round(gen_s, 2)},
         "rows_per_s": n_rows / (dt / args.steps),
         "roofline": roof,

@@ -41,15 +41,19 @@ constexpr uint64_t P61 = (1ull << 61) - 1;
 constexpr uint32_t EMPTY_MIN = 0xFFFFFFFFu;   // minimum of an empty set
 
 // ---------------------------------------------------------------- mod D
-// D a power of two: and with D-1.  Otherwise r mod D for r < 2^31 by one
-// multiply-high with M = floor(2^32 / D): q = floor(r M / 2^32) is the true
-// quotient or one less, so r - q D lies in [0, 2D) and min(v, v - D) in
-// unsigned arithmetic finishes it.
+// D a power of two: and with D-1.  Otherwise r mod D for r < 2^31 through the
+// exact quotient by an invariant divisor: with l = ceil(log2 D) and
+// M = ceil(2^(31+l) / D) < 2^32, floor(r / D) = floor(r M / 2^(31+l)) for every
+// r < 2^31 (M D = 2^(31+l) + e with 0 <= e < D <= 2^l, so r M / 2^(31+l) exceeds
+// r / D by less than 1 / D).  One multiply-high, one shift by l - 1, one
+// multiply-subtract; no correction step.
 struct ModD {
-    uint32_t D;      // low 32 bits of D (D = 2^32 only occurs with the permutation family)
+    uint32_t D;      // low 32 bits of D (D = 2^32 only occurs with power-of-two paths)
     uint32_t mask;   // D - 1 when D is a power of two
-    uint32_t M;      // floor(2^32 / D) for D >= 2 not a power of two
+    uint32_t M;      // ceil(2^(31+l) / D) for D >= 3 not a power of two
+    uint32_t sh;     // l - 1
     uint32_t pow2;
+    uint64_t M64;    // floor((2^64 - 1) / D): 61-bit residues mod D, see reduce61_mod_d
 };
 
 MH_HD ModD make_mod_d(uint64_t D)
@@ -58,7 +62,15 @@ MH_HD ModD make_mod_d(uint64_t D)
     m.D = (uint32_t)D;
     m.pow2 = (D & (D - 1)) == 0 ? 1u : 0u;
     m.mask = (uint32_t)(D - 1);
-    m.M = m.pow2 ? 0u : (uint32_t)((1ull << 32) / D);
+    m.M = 0;
+    m.sh = 0;
+    m.M64 = ~0ull / D;
+    if (!m.pow2 && D < (1ull << 31)) {       // the exact-quotient path serves p = 2^31-1 only (D < p)
+        uint32_t l = 0;
+        while ((1ull << l) < D) ++l;         // l >= 2
+        m.M = (uint32_t)(((1ull << (31 + l)) + D - 1) / D);
+        m.sh = l - 1;
+    }
     return m;
 }
 
@@ -68,10 +80,20 @@ template <bool POW2>
 MH_HD uint32_t reduce_mod_d(uint32_t r, const ModD& md)   // r < 2^31
 {
     if (POW2) return r & md.mask;
-    uint32_t q = mulhi_u32(r, md.M);
-    uint32_t v = r - q * md.D;
-    uint32_t w = v - md.D;
-    return w < v ? w : v;
+    uint32_t q = mulhi_u32(r, md.M) >> md.sh;
+    return r - q * md.D;
+}
+
+// r mod D for r < 2^61 and any D in [1, 2^32] (the p = 2^61-1 families with a D that
+// the mask path cannot serve): q = floor(r M64 / 2^64) falls short of the true
+// quotient by at most one, because r (2^64 / D - M64) < 2 r < 2^64 / 4; one
+// conditional subtraction finishes it.
+MH_HD uint64_t mulhi_u64(uint64_t a, uint64_t b) { return (uint64_t)(((unsigned __int128)a * b) >> 64); }
+MH_HD uint32_t reduce61_mod_d(uint64_t r, const ModD& md, uint64_t D)
+{
+    uint64_t q = mulhi_u64(r, md.M64);
+    uint64_t v = r - q * D;
+    return (uint32_t)(v >= D ? v - D : v);
 }
 
 // ---------------------------------------------------------------- p = 2^31 - 1, helpers for staging
@@ -116,6 +138,24 @@ template <bool POW2>
 MH_HD uint32_t hash_2u31(const Fn2U31& f, uint32_t t2, const ModD& md)
 {
     return reduce_mod_d<POW2>(m31_finish(fold_2u31(f, t2)), md);
+}
+
+// Other D: without the +1 offset the folded value x = S + y lies in [0, 2p)
+// (S = X >> 31 < D - 1 < p and y <= p), so the canonical residue is the unsigned
+// minimum of x and x - p, and the exact quotient finishes it: one instruction
+// fewer than m31_finish.
+MH_HD Fn2U31 prep_2u31_raw(uint64_t c0, uint64_t c1)
+{
+    Fn2U31 f;
+    f.c1 = (uint32_t)c1;
+    f.add = 2 * c0;
+    return f;
+}
+MH_HD uint32_t hash_2u31_raw(const Fn2U31& f, uint32_t t2, const ModD& md)
+{
+    uint32_t x = fold_2u31(f, t2);
+    uint32_t y = x - P31;
+    return reduce_mod_d<false>(y < x ? y : x, md);
 }
 
 // Power-of-two D = mask + 1: the complement  mask - h(t)  of the hashed location.
@@ -183,6 +223,14 @@ MH_HD uint32_t hash_4u31(const Fn4U31& f, const Pow4U31& w, const ModD& md)
 {
     return reduce_mod_d<POW2>(m31_finish(fold_4u31(f, w)), md);
 }
+// Other D: x in [1, 2p] congruent to X + 1, so X mod p is the unsigned minimum of
+// x - 1 and x - 1 - p = x - 2^31 (an xor with the sign bit).
+MH_HD uint32_t hash_4u31_np2(const Fn4U31& f, const Pow4U31& w, const ModD& md)
+{
+    uint32_t x = fold_4u31(f, w);
+    uint32_t a = x - 1u, b = x ^ 0x80000000u;
+    return reduce_mod_d<false>(b < a ? b : a, md);
+}
 MH_HD uint32_t hash_compl_4u31(const Fn4U31& f, const Pow4U31& w, uint32_t mask)
 {
     return m31_complement(fold_4u31(f, w), mask);
@@ -233,7 +281,7 @@ MH_HD uint32_t residue_lo_2u61(const Fn2U61& f, uint32_t t)
     return x_lo + (x_hi >> 29) - 1u;
 }
 
-// canonical residue for any t < 2^32 (the slow path: D above 2^31 or not a power of two)
+// canonical residue for any t < 2^32 (D above 2^31 or not a power of two)
 MH_HD uint64_t residue_wide_2u61(const Fn2U61& f, uint32_t t)
 {
     uint64_t L0 = (uint64_t)f.e0 * t;
@@ -251,7 +299,7 @@ template <bool POW2>
 MH_HD uint32_t hash_2u61(const Fn2U61& f, uint32_t t, const ModD& md, uint64_t D)
 {
     if (POW2) return residue_lo_2u61(f, t) & md.mask;
-    return (uint32_t)(residue_wide_2u61(f, t) % D);
+    return reduce61_mod_d(residue_wide_2u61(f, t), md, D);
 }
 
 // ---------------------------------------------------------------- 4U, p = 2^61-1 (eq. eqn_4U with the prime of Section 3.4's last paragraph)
@@ -314,7 +362,7 @@ template <bool POW2>
 MH_HD uint32_t hash_4u61(const Fn4U61& f, uint32_t t, const ModD& md, uint64_t D)
 {
     if (POW2) return residue_lo_4u61(f, t) & md.mask;
-    return (uint32_t)(residue_4u61(f, t) % D);
+    return reduce61_mod_d(residue_4u61(f, t), md, D);
 }
 
 // ---------------------------------------------------------------- multiply-shift 2U (Section 3.3, eq. eqn_h_s)

@@ -160,6 +160,34 @@ __device__ __forceinline__ uint32_t in_vgpr(uint32_t v)
     asm volatile("" : "+v"(v));
     return v;
 }
+// the same for a constant that only some kernels read: without "volatile" an
+// unused copy is dropped instead of holding a register
+__device__ __forceinline__ uint32_t in_vgpr_if_used(uint32_t v)
+{
+    asm("" : "+v"(v));
+    return v;
+}
+// the mod-D constants of a launch plus the other wave-uniform constants the
+// hand-ordered inner steps read, each held in a vector register
+struct ModDV : ModD {
+    uint32_t p31;    // 2^31 - 1
+    uint32_t sign;   // 2^31
+    uint32_t negD;   // 2^32 - D
+};
+__device__ __forceinline__ ModDV vector_constants(const ModD& src)
+{
+    ModDV v;
+    v.pow2 = src.pow2;
+    v.M64 = src.M64;
+    v.D = in_vgpr(src.D);
+    v.mask = in_vgpr(src.mask);
+    v.M = in_vgpr(src.M);
+    v.sh = in_vgpr_if_used(src.sh);
+    v.p31 = in_vgpr_if_used(P31);
+    v.sign = in_vgpr_if_used(0x80000000u);
+    v.negD = in_vgpr_if_used(0u - src.D);
+    return v;
+}
 __device__ __forceinline__ void wave_sync_lds()
 {
     // orders this wavefront's LDS writes before its later LDS reads (the hardware
@@ -344,7 +372,7 @@ __device__ __forceinline__ void wave_pack_store(const KArgs& a, const uint32_t* 
 struct KArgs;
 template <class Pol>
 __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
-                                             const uint32_t* wa, const uint32_t* wb, const ModD& md, uint64_t D);
+                                             const uint32_t* wa, const uint32_t* wb, const ModDV& md, uint64_t D);
 
 // A policy evaluates one function on one staged nonzero and returns a value that
 // the kernel folds into a running extremum: the hashed location itself (running
@@ -353,29 +381,30 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 template <bool POW2>
 struct Pol2U31 {
     static constexpr int NW = 1;
-    static constexpr int MIN_WAVES = 5;        // wavefronts per SIMD the register allocation must leave room for
+    static constexpr int MIN_WAVES = POW2 ? 5 : 4;   // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool PREFETCH = false;   // LDS words of the next step are read one step ahead
     static constexpr bool TRACK_MAX = POW2;
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
     {
+        if (!POW2) return valid ? prep_2u31_raw(c[0], c[1]) : prep_2u31_raw(0, 0);
         return valid ? prep_2u31(c[0], c[1]) : prep_2u31(0, 0);
     }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = stage_2u31(t); }
     static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t)
     {
         if (POW2) return hash_compl_2u31(f, w[0], md.mask);
-        return hash_2u31<false>(f, w[0], md);
+        return hash_2u31_raw(f, w[0], md);
     }
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                const uint32_t* wb, const ModD& md, uint64_t D);
+                                                const uint32_t* wb, const ModDV& md, uint64_t D);
     static constexpr int DEG = 2;
 };
 
 template <bool POW2>
 struct Pol4U31 {
     static constexpr int NW = 3;
-    static constexpr int MIN_WAVES = 4;
+    static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool PREFETCH = true;
     static constexpr bool TRACK_MAX = POW2;
     using Fn = Fn4U31;
@@ -393,10 +422,10 @@ struct Pol4U31 {
         Pow4U31 p;
         p.t1 = (int32_t)w[0]; p.t2 = (int32_t)w[1]; p.t3 = (int32_t)w[2];
         if (POW2) return hash_compl_4u31(f, p, md.mask);
-        return hash_4u31<false>(f, p, md);
+        return hash_4u31_np2(f, p, md);
     }
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                const uint32_t* wb, const ModD& md, uint64_t D);
+                                                const uint32_t* wb, const ModDV& md, uint64_t D);
     static constexpr int DEG = 4;
 };
 
@@ -417,7 +446,7 @@ struct Pol2U61 {
         return hash_2u61<POW2>(f, w[0], md, D);
     }
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                const uint32_t* wb, const ModD& md, uint64_t D)
+                                                const uint32_t* wb, const ModDV& md, uint64_t D)
     {
         pair_generic<Pol2U61<POW2>>(fn, m, wa, wb, md, D);
     }
@@ -443,7 +472,7 @@ struct Pol4U61 {
         return hash_4u61<POW2>(f, w[0], md, D);
     }
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                const uint32_t* wb, const ModD& md, uint64_t D)
+                                                const uint32_t* wb, const ModDV& md, uint64_t D)
     {
         pair_generic<Pol4U61<POW2>>(fn, m, wa, wb, md, D);
     }
@@ -455,7 +484,7 @@ struct Pol4U61 {
 // the 8 running extrema.  The generic form leaves the schedule to the compiler.
 template <class Pol>
 __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
-                                             const uint32_t* wa, const uint32_t* wb, const ModD& md, uint64_t D)
+                                             const uint32_t* wa, const uint32_t* wb, const ModDV& md, uint64_t D)
 {
 #pragma unroll
     for (int r = 0; r < HASH_FPL; ++r) {
@@ -464,6 +493,18 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
         m[r] = Pol::TRACK_MAX ? umax3(m[r], k0, k1) : umin3(m[r], k0, k1);
     }
 }
+
+// widening multiply-add; the carry-out pair it must name is never read
+#define MH_MAD(KIND, DST, A, B, C)                                                                                 \
+    do {                                                                                                           \
+        uint64_t cy_;                                                                                              \
+        asm volatile("v_mad_" #KIND " %0, %1, %2, %3, %4" : "=v"(DST), "=s"(cy_) : "v"(A), "v"(B), "v"(C));        \
+    } while (0)
+#define MH_MAD_ACC(KIND, ACC, A, B)                                                                                \
+    do {                                                                                                           \
+        uint64_t cy_;                                                                                              \
+        asm volatile("v_mad_" #KIND " %0, %1, %2, %3, %0" : "+v"(ACC), "=s"(cy_) : "v"(A), "v"(B));                \
+    } while (0)
 
 // 2U, p = 2^31-1, power-of-two D, with the instruction order fixed by hand.
 // On gfx950 a SIMD issues the simple integer instructions (shift right, add,
@@ -476,14 +517,14 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], uint32_t ta,
                                                uint32_t tb, uint32_t mask)
 {
-    uint64_t pa[HASH_FPL], pb[HASH_FPL], cy;
+    uint64_t pa[HASH_FPL], pb[HASH_FPL];
     uint32_t xa[HASH_FPL], xb[HASH_FPL], sa[HASH_FPL], sb[HASH_FPL];
 #pragma unroll
     for (int g = 0; g < HASH_FPL; ++g)
-        asm volatile("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(pa[g]), "=s"(cy) : "v"(fn[g].c1), "v"(ta), "v"(fn[g].add));
+        MH_MAD(u64_u32, pa[g], fn[g].c1, ta, fn[g].add);
 #pragma unroll
     for (int g = 0; g < HASH_FPL; ++g) {
-        asm volatile("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(pb[g]), "=s"(cy) : "v"(fn[g].c1), "v"(tb), "v"(fn[g].add));
+        MH_MAD(u64_u32, pb[g], fn[g].c1, tb, fn[g].add);
         asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(xa[g]) : "v"((uint32_t)pa[g]));
         asm volatile("v_add_u32 %0, %0, %1" : "+v"(xa[g]) : "v"((uint32_t)(pa[g] >> 32)));
     }
@@ -518,17 +559,17 @@ __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
 __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], const uint32_t* w,
                                                uint32_t mask, uint32_t p31)
 {
-    uint64_t acc[HASH_FPL], cy;
+    uint64_t acc[HASH_FPL];
     uint32_t u[HASH_FPL], v[HASH_FPL];
 #pragma unroll
     for (int g = 0; g < HASH_FPL; ++g)
-        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %4" : "=v"(acc[g]), "=s"(cy) : "v"(fn[g].c1), "v"(w[0]), "v"(fn[g].add));
+        MH_MAD(i64_i32, acc[g], fn[g].c1, w[0], fn[g].add);
 #pragma unroll
     for (int g = 0; g < HASH_FPL; ++g)
-        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(acc[g]), "=s"(cy) : "v"(fn[g].c2), "v"(w[1]));
+        MH_MAD_ACC(i64_i32, acc[g], fn[g].c2, w[1]);
 #pragma unroll
     for (int g = 0; g < HASH_FPL; ++g)
-        asm volatile("v_mad_i64_i32 %0, %1, %2, %3, %0" : "+v"(acc[g]), "=s"(cy) : "v"(fn[g].c3), "v"(w[2]));
+        MH_MAD_ACC(i64_i32, acc[g], fn[g].c3, w[2]);
 #pragma unroll
     for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(y[g]) : "v"((uint32_t)acc[g]));
 #pragma unroll
@@ -558,13 +599,125 @@ __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
 }
 
+// Other D, p = 2^31-1: the same stage-major order with the exact quotient of
+// mh_arith.h appended.  The canonical residue r is written into the low word of
+// the register pair that held the product, so that the closing multiply-add
+// r + q (2^32 - D) can take the pair as its 64-bit addend (only the low word of
+// its result is used).  Arithmetic of hash_2u31_raw / hash_4u31_np2.
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void pair_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], uint32_t ta,
+                                              uint32_t tb, const ModDV& md)
+{
+    u32x2 pa[HASH_FPL], pb[HASH_FPL];
+    uint32_t xa[HASH_FPL], xb[HASH_FPL], ya[HASH_FPL], yb[HASH_FPL], r;
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        MH_MAD(u64_u32, pa[g], fn[g].c1, ta, fn[g].add);
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        MH_MAD(u64_u32, pb[g], fn[g].c1, tb, fn[g].add);
+        asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(xa[g]) : "v"(pa[g].x));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_add_u32 %0, %0, %1" : "+v"(xa[g]) : "v"(pa[g].y));
+        asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(xb[g]) : "v"(pb[g].x));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_sub_u32 %0, %1, %2" : "=v"(ya[g]) : "v"(xa[g]), "v"(md.p31));
+        asm volatile("v_add_u32 %0, %0, %1" : "+v"(xb[g]) : "v"(pb[g].y));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_min_u32 %0, %1, %2" : "=v"(r) : "v"(xa[g]), "v"(ya[g]));
+        pa[g].x = r;
+        asm volatile("v_sub_u32 %0, %1, %2" : "=v"(yb[g]) : "v"(xb[g]), "v"(md.p31));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(xa[g]) : "v"(pa[g].x), "v"(md.M));
+        asm volatile("v_min_u32 %0, %1, %2" : "=v"(r) : "v"(xb[g]), "v"(yb[g]));
+        pb[g].x = r;
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(xa[g]) : "v"(md.sh));
+        asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(xb[g]) : "v"(pb[g].x), "v"(md.M));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        MH_MAD_ACC(u64_u32, pa[g], xa[g], md.negD);
+        asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(xb[g]) : "v"(md.sh));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        MH_MAD_ACC(u64_u32, pb[g], xb[g], md.negD);
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(pa[g].x), "v"(pb[g].x));
+}
+
+__device__ __forceinline__ void half_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], u32x2 (&acc)[HASH_FPL], const uint32_t* w,
+                                              const ModDV& md)
+{
+    uint32_t y[HASH_FPL], u[HASH_FPL], v[HASH_FPL], r;
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        MH_MAD(i64_i32, acc[g], fn[g].c1, w[0], fn[g].add);
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        MH_MAD_ACC(i64_i32, acc[g], fn[g].c2, w[1]);
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        MH_MAD_ACC(i64_i32, acc[g], fn[g].c3, w[2]);
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(y[g]) : "v"(acc[g].x));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(u[g]) : "v"(acc[g].y), "v"(md.p31));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(v[g]) : "v"(acc[g].y));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(y[g]) : "v"(u[g]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(y[g]) : "v"(v[g]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add_u32 %0, -1, %1" : "=v"(u[g]) : "v"(y[g]));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_xor_b32 %0, %0, %1" : "+v"(y[g]) : "v"(md.sign));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_min_u32 %0, %1, %2" : "=v"(r) : "v"(u[g]), "v"(y[g]));
+        acc[g].x = r;
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(u[g]) : "v"(acc[g].x), "v"(md.M));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(u[g]) : "v"(md.sh));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        MH_MAD_ACC(u64_u32, acc[g], u[g], md.negD);
+}
+
+__device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+                                              const uint32_t* wb, const ModDV& md)
+{
+    u32x2 ya[HASH_FPL], yb[HASH_FPL];
+    half_4u31_np2(fn, ya, wa, md);
+    half_4u31_np2(fn, yb, wb, md);
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g].x), "v"(yb[g].x));
+}
+
 // Ablation: the definition evaluated with the % operator on runtime moduli (Horner
 // form keeps every product below 2^62).  This is what Section 3.4's shift/mask
 // routine replaces; it exists only to be timed against the Mersenne kernels.
 template <int DEGREE>
 struct PolGenericMod {
     static constexpr int NW = 1;
-    static constexpr int MIN_WAVES = 4;
+    static constexpr int MIN_WAVES = 3;        // no spills, so that the ablation times the arithmetic only
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr int DEG = DEGREE;
@@ -587,7 +740,7 @@ struct PolGenericMod {
         return (uint32_t)(acc % D);
     }
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                const uint32_t* wb, const ModD& md, uint64_t D)
+                                                const uint32_t* wb, const ModDV& md, uint64_t D)
     {
         pair_generic<PolGenericMod<DEGREE>>(fn, m, wa, wb, md, D);
     }
@@ -613,16 +766,16 @@ struct Pol2UMS32 {
     // stage-major order for the same reason as in pair_2u31_pow2: 16 multiply-adds,
     // 16 masks or shifts, 8 three-operand minima
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                const uint32_t* wb, const ModD& md, uint64_t)
+                                                const uint32_t* wb, const ModDV& md, uint64_t)
     {
-        uint64_t pa[HASH_FPL], pb[HASH_FPL], cy;
+        uint64_t pa[HASH_FPL], pb[HASH_FPL];
         uint32_t xa[HASH_FPL], xb[HASH_FPL];
 #pragma unroll
         for (int g = 0; g < HASH_FPL; ++g)
-            asm volatile("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(pa[g]), "=s"(cy) : "v"(fn[g].c1), "v"(wa[0]), "v"(fn[g].add));
+            MH_MAD(u64_u32, pa[g], fn[g].c1, wa[0], fn[g].add);
 #pragma unroll
         for (int g = 0; g < HASH_FPL; ++g) {
-            asm volatile("v_mad_u64_u32 %0, %1, %2, %3, %4" : "=v"(pb[g]), "=s"(cy) : "v"(fn[g].c1), "v"(wb[0]), "v"(fn[g].add));
+            MH_MAD(u64_u32, pb[g], fn[g].c1, wb[0], fn[g].add);
             if (HIGH) asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(xa[g]) : "v"(md.M), "v"((uint32_t)pa[g]));
             else asm volatile("v_and_b32 %0, %1, %2" : "=v"(xa[g]) : "v"(md.mask), "v"((uint32_t)pa[g]));
         }
@@ -640,28 +793,28 @@ struct Pol2UMS32 {
 
 template <>
 __device__ __forceinline__ void Pol2U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                    const uint32_t* wb, const ModD& md, uint64_t)
+                                                    const uint32_t* wb, const ModDV& md, uint64_t)
 {
     pair_2u31_pow2(fn, m, wa[0], wb[0], md.mask);
 }
 template <>
 __device__ __forceinline__ void Pol2U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                     const uint32_t* wb, const ModD& md, uint64_t D)
+                                                     const uint32_t* wb, const ModDV& md, uint64_t D)
 {
-    pair_generic<Pol2U31<false>>(fn, m, wa, wb, md, D);
+    pair_2u31_np2(fn, m, wa[0], wb[0], md);
 }
 
 template <>
 __device__ __forceinline__ void Pol4U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                    const uint32_t* wb, const ModD& md, uint64_t)
+                                                    const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_4u31_pow2(fn, m, wa, wb, md.mask, md.M);      // md.M carries 2^31-1 in a vector register for this policy
+    pair_4u31_pow2(fn, m, wa, wb, md.mask, md.p31);
 }
 template <>
 __device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                     const uint32_t* wb, const ModD& md, uint64_t D)
+                                                     const uint32_t* wb, const ModDV& md, uint64_t D)
 {
-    pair_generic<Pol4U31<false>>(fn, m, wa, wb, md, D);
+    pair_4u31_np2(fn, m, wa, wb, md);
 }
 
 // ------------------------------------------------------------------ staging
@@ -699,11 +852,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
     const uint32_t n_short = a.hdr->n_short < a.cap_short ? a.hdr->n_short : (uint32_t)a.cap_short;
     const uint64_t n_units = ((uint64_t)n_long + n_short) * (uint64_t)a.n_ftiles;
 
-    ModD md = a.md;
-    if (Pol::NW == 3 && md.pow2) md.M = P31;   // the 4U fold wants 2^31-1 in a vector register; the mask path does not use M
-    md.mask = in_vgpr(md.mask);
-    md.D = in_vgpr(md.D);
-    md.M = in_vgpr(md.M);
+    const ModDV md = vector_constants(a.md);
 
     typename Pol::Fn fn[HASH_FPL];
     int cur_ftile = -1;
