@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 
 from paper_1205_2958_amd import workloads as W  # noqa: E402
 
-# Issue-slot model of one hash evaluation ("Rooflines").  One slot
+# Issue-slot model of one hash evaluation.  One slot
 # = one 64-lane instruction at the full-issue rate of 16 lanes/clk/SIMD; simple
 # two-operand integer instructions on vector registers issue at twice that rate
 # and count one half.
