@@ -84,6 +84,20 @@ def test_hash_families_k500_edge_lengths(family, D, b):
     check_case(rp, col, D, 500, b, family, W.coefficients(500, family, seed=77 + family))
 
 
+@pytest.mark.parametrize("family", [mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61, mh.FAMILY_4U_M61])
+@pytest.mark.parametrize("D", [16609143, 1010017424])
+def test_real_universe_sizes_k500_edge_lengths(family, D):
+    """The universe sizes of the paper's two datasets (Table 1) are not powers of two:
+    the real k, long and split rows, indices folded into [0, D)."""
+    rp, col = edge_rows(1 << 30, seed=52 + family, extra=(50000,))
+    col = (col % np.uint32(D)).astype(np.uint32)
+    col[-1] = D - 1
+    k = 500 if family != mh.FAMILY_4U_M61 else 130
+    c = W.coefficients(k, family, seed=78 + family)
+    c[3, :] = W.family_prime(family) - 1
+    check_case(rp, col, D, k, 8, family, c)
+
+
 @pytest.mark.parametrize("k", [1, 7, 8, 9, 31, 63, 64, 65, 100, 200, 511, 512, 513, 1030])
 def test_function_counts(k):
     D = 1 << 24
