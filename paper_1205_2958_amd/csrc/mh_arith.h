@@ -267,18 +267,19 @@ MH_HD uint64_t residue_2u61(const Fn2U61& f, uint32_t t)
     return (x + c - 1) & P61;
 }
 
-// low 32 bits of the canonical residue only (all that a power-of-two D <= 2^32 needs)
+// low 32 bits of the canonical residue only (all that a power-of-two D needs), t < 2^31.
+// Then H < 2^60 + 2^32, so H >> 29 fits 32 bits: x_lo = L_lo + (H >> 29) with carry c1,
+// and bit 61 of x is set exactly when c1 = 1 and bits 32..60 of W are all ones.
 MH_HD uint32_t residue_lo_2u61(const Fn2U61& f, uint32_t t)
 {
     uint64_t L = (uint64_t)f.e0 * t + f.add;
     uint64_t H = (uint64_t)f.e1 * t + (L >> 32);
     uint32_t Hl = (uint32_t)H, Hh = (uint32_t)(H >> 32);
-    uint32_t s_lo = (Hl >> 29) | (Hh << 3);          // (H >> 29) mod 2^32
-    uint32_t s_hi = Hh >> 29;
+    uint32_t s_lo = (Hl >> 29) | (Hh << 3);          // H >> 29
     uint32_t x_lo = (uint32_t)L + s_lo;
-    uint32_t carry = x_lo < s_lo ? 1u : 0u;
-    uint32_t x_hi = (Hl & 0x1FFFFFFFu) + s_hi + carry;
-    return x_lo + (x_hi >> 29) - 1u;
+    uint32_t c1 = x_lo < s_lo ? 1u : 0u;
+    uint32_t c2 = ((Hl | 0xE0000000u) == 0xFFFFFFFFu) ? c1 : 0u;
+    return x_lo + c2 - 1u;
 }
 
 // canonical residue for any t < 2^32 (D above 2^31 or not a power of two)

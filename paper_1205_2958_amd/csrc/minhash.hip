@@ -34,6 +34,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "minhash.h"
 #include "mh_arith.h"
 
@@ -42,6 +44,7 @@ namespace {
 using namespace mh;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int WAVE = 64;
 constexpr int WAVES_PER_BLOCK = 4;
@@ -173,6 +176,7 @@ struct ModDV : ModD {
     uint32_t p31;    // 2^31 - 1
     uint32_t sign;   // 2^31
     uint32_t negD;   // 2^32 - D
+    uint32_t top3;   // 0xE0000000
 };
 __device__ __forceinline__ ModDV vector_constants(const ModD& src)
 {
@@ -186,6 +190,7 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
     v.p31 = in_vgpr_if_used(P31);
     v.sign = in_vgpr_if_used(0x80000000u);
     v.negD = in_vgpr_if_used(0u - src.D);
+    v.top3 = in_vgpr_if_used(0xE0000000u);
     return v;
 }
 __device__ __forceinline__ void wave_sync_lds()
@@ -429,16 +434,26 @@ struct Pol4U31 {
     static constexpr int DEG = 4;
 };
 
+// The power-of-two path of 2U with p = 2^61-1 keeps, per function, a register pair
+// whose high word stays zero: the second multiply-add takes {high word of L, 0}
+// as its 64-bit addend, and only the low word is rewritten per evaluation.
+struct Fn2U61V : Fn2U61 {
+    mutable u32x2 hz;
+};
+
 template <bool POW2>
 struct Pol2U61 {
     static constexpr int NW = 1;
-    static constexpr int MIN_WAVES = 5;
+    static constexpr int MIN_WAVES = POW2 ? 4 : 5;
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
-    using Fn = Fn2U61;
+    using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
     {
-        return valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
+        Fn f;
+        static_cast<Fn2U61&>(f) = valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
+        if constexpr (POW2) f.hz = u32x2{0u, 0u};
+        return f;
     }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
     static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t D)
@@ -446,10 +461,7 @@ struct Pol2U61 {
         return hash_2u61<POW2>(f, w[0], md, D);
     }
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                const uint32_t* wb, const ModDV& md, uint64_t D)
-    {
-        pair_generic<Pol2U61<POW2>>(fn, m, wa, wb, md, D);
-    }
+                                                const uint32_t* wb, const ModDV& md, uint64_t D);
     static constexpr int DEG = 2;
 };
 
@@ -604,7 +616,6 @@ __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
 // the register pair that held the product, so that the closing multiply-add
 // r + q (2^32 - D) can take the pair as its 64-bit addend (only the low word of
 // its result is used).  Arithmetic of hash_2u31_raw / hash_4u31_np2.
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ void pair_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], uint32_t ta,
                                               uint32_t tb, const ModDV& md)
@@ -711,6 +722,46 @@ __device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g].x), "v"(yb[g].x));
 }
 
+// 2U, p = 2^61-1, power-of-two D <= 2^31: residue_lo_2u61 of mh_arith.h, eight
+// functions on one nonzero, stage by stage.  The two carries travel in scalar
+// register pairs: c1 out of x_lo = L_lo + (H >> 29), c2 out of
+// (H_lo | 0xE0000000) + c1, which is set exactly when bit 61 of x is; the last
+// add-with-carry forms x_lo + c2 - 1.
+__device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t t,
+                                               const ModDV& md)
+{
+    u32x2 L[HASH_FPL], H[HASH_FPL];
+    uint32_t s[HASH_FPL], o[HASH_FPL], r;
+    uint64_t c1[HASH_FPL], c2[HASH_FPL], c3;
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) MH_MAD(u64_u32, L[g], fn[g].e0, t, fn[g].add);
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) {
+        asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "v"(L[g].y));
+        fn[g].hz.x = r;
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) MH_MAD(u64_u32, H[g], fn[g].e1, t, fn[g].hz);
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_or_b32 %0, %1, %2" : "=v"(o[g]) : "v"(H[g].x), "v"(md.top3));
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_add_co_u32 %0, %1, %2, %3" : "=v"(s[g]), "=s"(c1[g]) : "v"(L[g].x), "v"(s[g]));
+    // the two add-with-carry stages run two evaluations apart, so that no statement
+    // reads what its predecessor wrote
+#pragma unroll
+    for (int g = 0; g < HASH_FPL + 2; ++g) {
+        if (g < HASH_FPL)
+            asm volatile("v_addc_co_u32 %0, %1, %2, 0, %3" : "=v"(o[g]), "=s"(c2[g]) : "v"(o[g]), "s"(c1[g]));
+        if (g >= 2)
+            asm volatile("v_addc_co_u32 %0, %1, %2, -1, %3" : "=v"(y[g - 2]), "=s"(c3) : "v"(s[g - 2]), "s"(c2[g - 2]));
+    }
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(y[g]) : "v"(md.mask));
+}
+
 // Ablation: the definition evaluated with the % operator on runtime moduli (Horner
 // form keeps every product below 2^62).  This is what Section 3.4's shift/mask
 // routine replaces; it exists only to be timed against the Mersenne kernels.
@@ -815,6 +866,24 @@ __device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], u
                                                      const uint32_t* wb, const ModDV& md, uint64_t D)
 {
     pair_4u31_np2(fn, m, wa, wb, md);
+}
+
+template <>
+__device__ __forceinline__ void Pol2U61<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+                                                    const uint32_t* wb, const ModDV& md, uint64_t)
+{
+    uint32_t ya[HASH_FPL], yb[HASH_FPL];
+    half_2u61_pow2(fn, ya, wa[0], md);
+    half_2u61_pow2(fn, yb, wb[0], md);
+#pragma unroll
+    for (int g = 0; g < HASH_FPL; ++g)
+        asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
+}
+template <>
+__device__ __forceinline__ void Pol2U61<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+                                                     const uint32_t* wb, const ModDV& md, uint64_t D)
+{
+    pair_generic<Pol2U61<false>>(fn, m, wa, wb, md, D);
 }
 
 // ------------------------------------------------------------------ staging
