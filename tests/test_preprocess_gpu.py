@@ -1,0 +1,48 @@
+"""The file-to-signature command end to end on the GPU (parse, batch loop of
+Section 3.2, hash, expand) against the oracle run on the same rows."""
+import json
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+from paper_1205_2958_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _write_libsvm(path, rp, col, labels):
+    with open(path, "w") as f:
+        for i in range(len(rp) - 1):
+            feats = " ".join("%d:1" % (int(t) + 1) for t in col[rp[i]:rp[i + 1]])
+            f.write(("%+d" % labels[i]) + (" " + feats if feats else "") + "\n")
+
+
+@pytest.mark.parametrize("family_name,universe", [("2u", 0), ("4u", 16609143), ("2u61", 1 << 30), ("ms32", 0)])
+def test_file_to_signatures(tmp_path, family_name, universe):
+    from paper_1205_2958_amd import preprocess
+
+    rng = np.random.Generator(np.random.PCG64(71))
+    nnz = np.concatenate([rng.integers(0, 400, size=700), [0, 9000, 1, 20000]]).astype(np.int64)
+    rp = W.row_ptr_from_nnz(nnz)
+    col = W.csr_indices_np(nnz, 1 << 22, seed=72)
+    labels = rng.choice([-1, 1], size=len(nnz))
+    src = tmp_path / "data.svm"
+    _write_libsvm(src, rp, col, labels)
+    k, b = 130, 4
+    prefix = str(tmp_path / "out")
+    meta = preprocess.run(str(src), prefix, k, b, family_name, seed=5, universe=universe, batch_rows=256,
+                          index_base=1, threads=4, expand=True, log=lambda *_: None)
+    assert meta["rows"] == len(nnz) and meta["nonzeros"] == int(rp[-1])
+    assert json.load(open(prefix + ".json"))["D"] == meta["D"]
+    family = preprocess.FAMILIES[family_name]
+    D = meta["D"]
+    expect_D = universe or int(col.max()) + 1
+    if family_name == "ms32":
+        expect_D = 1 << (expect_D - 1).bit_length()        # multiply-shift hashes into a power of two
+    assert D == expect_D
+    want = oracle.signatures(rp, col, D, k, b, family, W.coefficients(k, family, 5))
+    sig = np.load(prefix + ".sig.npy")
+    assert np.array_equal(sig, want)
+    assert np.array_equal(np.load(prefix + ".labels.npy"), labels.astype(np.float32))
+    assert np.array_equal(np.load(prefix + ".expanded.npy").view(np.uint32), oracle.expand(want, k, b))
