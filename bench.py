@@ -37,7 +37,7 @@ SLOTS_PER_EVAL = {
     W.FAMILY_2U_M31: 1.0 + 5 * 0.5 + 0.5,                  # mad; shr,add,ashr,sub,and; half a max3
     W.FAMILY_4U_M31: 3.0 + 8 * 0.5 + 0.5,                  # 3 mad; shr,and,shr,add,add,ashr,sub,and; half a max3
     W.FAMILY_2U_M61: 2.0 + 1.0 + 3.0 + 3 * 0.5 + 0.5,      # 2 mad; funnel shift; add, 2 add-with-carry; mov,or,and; half a min3
-    W.FAMILY_2U_MS32: 1.0 + 0.5 + 0.5,                      # mad; and; half a min3
+    W.FAMILY_2U_MS32: 1.0 + 0.5,                            # mad; half a min3 (mask or shift once per row)
 }
 # other D (--universe): exact multiply-high quotient appended
 SLOTS_PER_EVAL_OTHER_D = {

@@ -388,4 +388,22 @@ MH_HD uint32_t hash_2ums32(const Fn2UMS32& f, uint32_t t, uint32_t mask, uint32_
     return HIGH ? (v >> shift) : (v & mask);      // shift = 32 - s, 0 <= shift <= 31
 }
 
+// The running minimum needs neither the mask nor the shift per evaluation.
+// Highest s bits: v -> v >> shift is monotone, so the minimum of the shifted
+// values is the shifted minimum of the 32-bit values.  Lowest s bits: with both
+// coefficients multiplied by 2^shift the 32-bit value is (v mod 2^s) 2^shift, an
+// order-preserving image of the lowest s bits, and the same final shift brings
+// the minimum back.  The hot loop is then one multiply-add and one minimum.
+template <bool HIGH>
+MH_HD Fn2UMS32 prep_2ums32_key(uint64_t c0, uint64_t c1, uint32_t shift)    // shift = 32 - s, 0 <= shift <= 32
+{
+    if (HIGH) return prep_2ums32(c0, c1);
+    Fn2UMS32 f;
+    f.c1 = shift >= 32 ? 0u : (uint32_t)c1 << shift;
+    f.add = shift >= 32 ? 0ull : (uint64_t)((uint32_t)c0 << shift);
+    return f;
+}
+MH_HD uint32_t key_2ums32(const Fn2UMS32& f, uint32_t t) { return (uint32_t)((uint64_t)f.c1 * t + f.add); }
+MH_HD uint32_t finish_2ums32(uint32_t min_key, uint32_t shift) { return shift >= 32 ? 0u : min_key >> shift; }
+
 }  // namespace mh

@@ -374,7 +374,6 @@ __device__ __forceinline__ void wave_pack_store(const KArgs& a, const uint32_t* 
 }
 
 // ------------------------------------------------------------------ hash-family policies
-struct KArgs;
 template <class Pol>
 __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
                                              const uint32_t* wa, const uint32_t* wb, const ModDV& md, uint64_t D);
@@ -389,8 +388,9 @@ struct Pol2U31 {
     static constexpr int MIN_WAVES = POW2 ? 5 : 4;   // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool PREFETCH = false;   // LDS words of the next step are read one step ahead
     static constexpr bool TRACK_MAX = POW2;
+    static constexpr bool SHIFT_END = false;
     using Fn = Fn2U31;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
         if (!POW2) return valid ? prep_2u31_raw(c[0], c[1]) : prep_2u31_raw(0, 0);
         return valid ? prep_2u31(c[0], c[1]) : prep_2u31(0, 0);
@@ -412,8 +412,9 @@ struct Pol4U31 {
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool PREFETCH = true;
     static constexpr bool TRACK_MAX = POW2;
+    static constexpr bool SHIFT_END = false;
     using Fn = Fn4U31;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
         return valid ? prep_4u31(c[0], c[1], c[2], c[3]) : prep_4u31(0, 0, 0, 0);
     }
@@ -447,8 +448,9 @@ struct Pol2U61 {
     static constexpr int MIN_WAVES = POW2 ? 4 : 5;
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
+    static constexpr bool SHIFT_END = false;
     using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
         Fn f;
         static_cast<Fn2U61&>(f) = valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
@@ -473,8 +475,9 @@ struct Pol4U61 {
     static constexpr int MIN_WAVES = 2;
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
+    static constexpr bool SHIFT_END = false;
     using Fn = Fn4U61;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
         return valid ? prep_4u61(c[0], c[1], c[2], c[3]) : prep_4u61(0, 0, 0, 0);
     }
@@ -771,14 +774,15 @@ struct PolGenericMod {
     static constexpr int MIN_WAVES = 3;        // no spills, so that the ablation times the arithmetic only
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
+    static constexpr bool SHIFT_END = false;
     static constexpr int DEG = DEGREE;
     struct Fn { uint64_t c[DEGREE]; uint64_t p; };
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t prime)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
         Fn f;
 #pragma unroll
         for (int i = 0; i < DEGREE; ++i) f.c[i] = valid ? c[i] : 0;
-        f.p = prime;                   // a kernel argument, so that the compiler cannot specialise the % on it
+        f.p = a.prime;                 // a kernel argument, so that the compiler cannot specialise the % on it
         return f;
     }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
@@ -797,47 +801,39 @@ struct PolGenericMod {
     }
 };
 
-// multiply-shift 2U: md.mask = D - 1, md.M = 32 - log2(D)
+// multiply-shift 2U: md.M = 32 - log2(D).  The kernel tracks the minimum of an
+// order-preserving 32-bit key and shifts it down once per row (mh_arith.h), so
+// the unit of the hot loop is 16 multiply-adds and 8 three-operand minima.
 template <bool HIGH>
 struct Pol2UMS32 {
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = 5;
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
+    static constexpr bool SHIFT_END = true;
     using Fn = Fn2UMS32;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, uint64_t)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
-        return valid ? prep_2ums32(c[0], c[1]) : prep_2ums32(0, 0);
+        return valid ? prep_2ums32_key<HIGH>(c[0], c[1], a.md.M) : prep_2ums32_key<HIGH>(0, 0, a.md.M);
     }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
-    static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t)
+    static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD&, uint64_t)
     {
-        return hash_2ums32<HIGH>(f, w[0], md.mask, md.M);
+        return key_2ums32(f, w[0]);
     }
-    // stage-major order for the same reason as in pair_2u31_pow2: 16 multiply-adds,
-    // 16 masks or shifts, 8 three-operand minima
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                const uint32_t* wb, const ModDV& md, uint64_t)
+                                                const uint32_t* wb, const ModDV&, uint64_t)
     {
         uint64_t pa[HASH_FPL], pb[HASH_FPL];
-        uint32_t xa[HASH_FPL], xb[HASH_FPL];
 #pragma unroll
         for (int g = 0; g < HASH_FPL; ++g)
             MH_MAD(u64_u32, pa[g], fn[g].c1, wa[0], fn[g].add);
 #pragma unroll
-        for (int g = 0; g < HASH_FPL; ++g) {
+        for (int g = 0; g < HASH_FPL; ++g)
             MH_MAD(u64_u32, pb[g], fn[g].c1, wb[0], fn[g].add);
-            if (HIGH) asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(xa[g]) : "v"(md.M), "v"((uint32_t)pa[g]));
-            else asm volatile("v_and_b32 %0, %1, %2" : "=v"(xa[g]) : "v"(md.mask), "v"((uint32_t)pa[g]));
-        }
-#pragma unroll
-        for (int g = 0; g < HASH_FPL; ++g) {
-            if (HIGH) asm volatile("v_lshrrev_b32 %0, %1, %2" : "=v"(xb[g]) : "v"(md.M), "v"((uint32_t)pb[g]));
-            else asm volatile("v_and_b32 %0, %1, %2" : "=v"(xb[g]) : "v"(md.mask), "v"((uint32_t)pb[g]));
-        }
 #pragma unroll
         for (int g = 0; g < HASH_FPL; ++g)
-            asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
+            asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"((uint32_t)pa[g]), "v"((uint32_t)pb[g]));
     }
     static constexpr int DEG = 2;
 };
@@ -949,7 +945,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             for (int r = 0; r < HASH_FPL; ++r) {
                 int j = j_base + r;
                 bool valid = j < a.k;
-                fn[r] = Pol::load(coeffs + (size_t)(valid ? j : 0) * Pol::DEG, valid, a.prime);
+                fn[r] = Pol::load(coeffs + (size_t)(valid ? j : 0) * Pol::DEG, valid, a);
             }
             cur_ftile = ftile;
         }
@@ -1023,6 +1019,10 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             if (Pol::TRACK_MAX) {      // back from complements to the minimum location
 #pragma unroll
                 for (int r = 0; r < HASH_FPL; ++r) m[r] = md.mask - m[r];
+            }
+            if (Pol::SHIFT_END) {      // from the order-preserving key back to the hashed location
+#pragma unroll
+                for (int r = 0; r < HASH_FPL; ++r) m[r] = finish_2ums32(m[r], a.md.M);
             }
         } else if (Pol::TRACK_MAX) {
 #pragma unroll

@@ -164,6 +164,22 @@ int main()
             if (sbits >= 1 && hash_2ums32<true>(f, t, mask, shift) != (uint64_t)(v / (((u128)1 << 32) / D)))
                 FAIL("multiply-shift high s=%d", sbits);
             checks += 2;
+            // the keys the kernel takes the minimum of: same value after the final shift, and
+            // ordered like the hashed locations (checked on a second index under the same function)
+            Fn2UMS32 fl = prep_2ums32_key<false>(c0, c1, shift), fh = prep_2ums32_key<true>(c0, c1, shift);
+            uint32_t t2 = (uint32_t)(rnd() % D);
+            uint32_t h1 = hash_2ums32<false>(f, t, mask, shift), h2 = hash_2ums32<false>(f, t2, mask, shift);
+            uint32_t k1 = key_2ums32(fl, t), k2 = key_2ums32(fl, t2);
+            if (finish_2ums32(k1, shift) != h1 || finish_2ums32(k2, shift) != h2 || (h1 < h2) != (k1 < k2))
+                FAIL("multiply-shift low key s=%d", sbits);
+            if (sbits >= 1) {
+                uint32_t g1 = hash_2ums32<true>(f, t, mask, shift), g2 = hash_2ums32<true>(f, t2, mask, shift);
+                uint32_t q1 = key_2ums32(fh, t), q2 = key_2ums32(fh, t2);
+                uint32_t lo = q1 < q2 ? q1 : q2;
+                if (finish_2ums32(q1, shift) != g1 || finish_2ums32(lo, shift) != (g1 < g2 ? g1 : g2))
+                    FAIL("multiply-shift high key s=%d", sbits);
+            }
+            checks += 2;
         }
     }
     printf("OK %ld\n", checks);
