@@ -43,6 +43,14 @@ namespace {
 
 using namespace mh;
 
+// alignment (log2 bytes) and default phase of the hot loops, see fix_loop_phase
+#ifndef MH_LOOP_ALIGN
+#define MH_LOOP_ALIGN 5
+#endif
+#ifndef MH_LOOP_PHASE_DEFAULT
+#define MH_LOOP_PHASE_DEFAULT 20
+#endif
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -155,6 +163,65 @@ __device__ __forceinline__ uint32_t first_lane_value(uint32_t v)
 {
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
 }
+
+// Hands work units to a persistent wavefront by ticket.  The first ticket of a
+// wavefront is its own index in the grid, later ones come from an atomic counter
+// that starts behind the grid, so a call with fewer units than resident
+// wavefronts costs no atomic at all.  Tickets map to units in three regions:
+// units of long items, one per ticket (they are listed first); then runs of
+// consecutive units, sized so that a wavefront still draws about 32 of them; then
+// the last 16 units per wavefront one per ticket again, so that the tail is made
+// of single short items.  A single address takes fewer than 10^8 atomics a
+// second, which bounded a batch of millions of short rows when every unit cost
+// one; batches of the benchmark's size get runs of one and are handed out unit
+// by unit as before.  All values are wavefront-uniform.
+struct UnitDispenser {
+    uint32_t n_units;       // the host refuses batches whose unit count does not fit 32 bits
+    uint32_t single;        // tickets below this are units of long items
+    uint32_t n_runs, run;   // then n_runs tickets of `run` units each
+    uint32_t grid_waves;
+    uint32_t next, end;     // units of the current ticket still to do
+
+    __device__ __forceinline__ void init(uint64_t units, uint64_t single_units, uint32_t waves, uint32_t index)
+    {
+        n_units = (uint32_t)units;
+        single = (uint32_t)(single_units < units ? single_units : units);
+        grid_waves = waves;
+        const uint32_t rest = n_units - single;
+        const uint32_t want = rest / (waves * 32u);
+        run = want < 1 ? 1u : (want > 32 ? 32u : want);
+        const uint32_t tail = rest < waves * 16u ? rest : waves * 16u;
+        n_runs = run > 1 ? (rest - tail) / run : 0u;
+        next = end = 0;
+        set_ticket(index);          // the first ticket needs no atomic
+    }
+    __device__ __forceinline__ void set_ticket(uint32_t tk)
+    {
+        if (tk < single) {
+            next = tk;
+            end = tk + 1;
+        } else if (tk - single < n_runs) {
+            next = single + (tk - single) * run;
+            end = next + run;
+        } else {
+            const uint64_t u = (uint64_t)single + (uint64_t)n_runs * run + (tk - single - n_runs);
+            next = u < n_units ? (uint32_t)u : n_units;
+            end = next + 1;
+        }
+    }
+    // false when nothing is left; every wavefront gets there because tickets only grow
+    __device__ __forceinline__ bool take(uint32_t* counter, int lane, uint32_t* unit)
+    {
+        if (next >= end) {
+            uint32_t tk = 0;
+            if (lane == 0) tk = grid_waves + atomicAdd(counter, 1u);
+            set_ticket(first_lane_value(tk));
+        }
+        if (next >= n_units) return false;
+        *unit = next++;
+        return true;
+    }
+};
 // keeps a wave-uniform value in a vector register: integer instructions whose
 // operands all sit in vector registers issue at twice the rate of those that
 // read a scalar register
@@ -192,6 +259,20 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
     v.negD = in_vgpr_if_used(0u - src.D);
     v.top3 = in_vgpr_if_used(0xE0000000u);
     return v;
+}
+// Placed first in the body of a hot loop.  The instructions of these loops are 4
+// or 8 bytes long, and on gfx950 the same loop runs up to 5 % faster or slower
+// depending on where its instructions fall relative to 32-byte boundaries (2U:
+// 82.0 ms with the body starting 28 bytes past a boundary, 86.7 ms at 0); where
+// the compiler happens to put the loop would otherwise decide that, and change
+// with unrelated edits.  Aligning here (the padding is s_nop, at most seven per
+// iteration) and adding PHASE / 4 more fixes the position; each policy names its
+// phase, found by timing all eight.
+template <int PHASE>
+__device__ __forceinline__ void fix_loop_phase()
+{
+    static_assert(PHASE >= 0 && PHASE < (1 << MH_LOOP_ALIGN) && PHASE % 4 == 0, "phase in bytes");
+    asm volatile(".p2align %c0\n\t.rept %c1\n\ts_nop 0\n\t.endr" : : "n"(MH_LOOP_ALIGN), "n"(PHASE / 4));
 }
 __device__ __forceinline__ void wave_sync_lds()
 {
@@ -389,6 +470,7 @@ struct Pol2U31 {
     static constexpr bool PREFETCH = false;   // LDS words of the next step are read one step ahead
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
+    static constexpr int LOOP_PHASE = POW2 ? 28 : 0;   // timed: 82.0 ms at 28, 86.7 ms at 0 (power-of-two D)
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -413,6 +495,7 @@ struct Pol4U31 {
     static constexpr bool PREFETCH = true;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
+    static constexpr int LOOP_PHASE = POW2 ? 4 : 20;
     using Fn = Fn4U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -449,6 +532,7 @@ struct Pol2U61 {
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr int LOOP_PHASE = MH_LOOP_PHASE_DEFAULT;
     using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -476,6 +560,7 @@ struct Pol4U61 {
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr int LOOP_PHASE = MH_LOOP_PHASE_DEFAULT;
     using Fn = Fn4U61;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -775,6 +860,7 @@ struct PolGenericMod {
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr int LOOP_PHASE = MH_LOOP_PHASE_DEFAULT;
     static constexpr int DEG = DEGREE;
     struct Fn { uint64_t c[DEGREE]; uint64_t p; };
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
@@ -811,6 +897,7 @@ struct Pol2UMS32 {
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = true;
+    static constexpr int LOOP_PHASE = MH_LOOP_PHASE_DEFAULT;
     using Fn = Fn2UMS32;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
@@ -922,20 +1009,12 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
     typename Pol::Fn fn[HASH_FPL];
     int cur_ftile = -1;
 
-    // The first unit of a wavefront is its own index in the grid; later ones come from an
-    // atomic counter that starts behind the grid.  A batch with fewer units than resident
-    // wavefronts therefore costs no atomic at all (thousands of wavefronts hitting one
-    // address would otherwise dominate a small call).
-    const uint32_t grid_waves = gridDim.x * WAVES_PER_BLOCK;
-    bool first_unit = true;
+    UnitDispenser units;
+    units.init(n_units, (uint64_t)n_long * (uint64_t)a.n_ftiles, gridDim.x * WAVES_PER_BLOCK,
+               blockIdx.x * WAVES_PER_BLOCK + wave);
     for (;;) {
-        uint32_t ticket = blockIdx.x * WAVES_PER_BLOCK + wave;
-        if (!first_unit) {
-            if (lane == 0) ticket = grid_waves + atomicAdd(&a.hdr->ticket, 1u);
-            ticket = first_lane_value(ticket);
-        }
-        first_unit = false;
-        if ((uint64_t)ticket >= n_units) break;      // every wavefront reaches this: tickets only grow
+        uint32_t ticket;
+        if (!units.take(&a.hdr->ticket, lane, &ticket)) break;
         const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
         const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
         const int j_base = ftile * HASH_FTILE + fl * HASH_FPL;
@@ -988,6 +1067,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                     for (int i = 0; i < Pol::NW; ++i)
                         nxt[i] = *reinterpret_cast<const uint4*>(&tile[i][4 * slice]);
                     for (int s = 0; s < n_steps; ++s) {
+                        fix_loop_phase<Pol::LOOP_PHASE>();
                         uint32_t w[4][Pol::NW];
 #pragma unroll
                         for (int i = 0; i < Pol::NW; ++i) {
@@ -1003,6 +1083,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                     }
                 } else {
                     for (int s = 0; s < n_steps; ++s) {
+                        fix_loop_phase<Pol::LOOP_PHASE>();
                         const int e = 4 * (s * n_slices + slice);
                         uint32_t w[4][Pol::NW];
 #pragma unroll
@@ -1076,16 +1157,12 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
     const uint64_t n_units = ((uint64_t)n_long + n_short) * (uint64_t)a.n_ftiles;
     constexpr int U = 8;               // nonzeros in flight per lane
 
-    const uint32_t grid_waves = gridDim.x * WAVES_PER_BLOCK;      // first unit = own index, then the atomic counter
-    bool first_unit = true;
+    UnitDispenser units;
+    units.init(n_units, (uint64_t)n_long * (uint64_t)a.n_ftiles, gridDim.x * WAVES_PER_BLOCK,
+               blockIdx.x * WAVES_PER_BLOCK + wave);
     for (;;) {
-        uint32_t ticket = blockIdx.x * WAVES_PER_BLOCK + wave;
-        if (!first_unit) {
-            if (lane == 0) ticket = grid_waves + atomicAdd(&a.hdr->ticket, 1u);
-            ticket = first_lane_value(ticket);
-        }
-        first_unit = false;
-        if ((uint64_t)ticket >= n_units) break;
+        uint32_t ticket;
+        if (!units.take(&a.hdr->ticket, lane, &ticket)) break;
         const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
         const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
         const Item it = item_idx < n_long ? a.items[item_idx] : a.items[a.cap_long + (item_idx - n_long)];
@@ -1352,7 +1429,8 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         a.log2_fl = 6;
     }
 
-    if ((L.cap_long + L.cap_short) * (uint64_t)a.n_ftiles >= (1ull << 32)) return MINHASH_ERR_ARG;   // tickets are 32-bit
+    // tickets and unit numbers are 32 bits wide; tickets run past the last unit by one per resident wavefront
+    if ((L.cap_long + L.cap_short) * (uint64_t)a.n_ftiles >= (1ull << 32) - (1ull << 24)) return MINHASH_ERR_ARG;
 
     const int cus = device_cus();
     a.target_items = (uint32_t)cus * 24u * 2u;     // two items per wavefront of a fully occupied launch

@@ -330,6 +330,9 @@ WORKLOADS = {
     # the hash the paper itself times as "GPU 2U" (Section 3.3), on the webspam-shaped rows
     "large_2u_ms32": Workload("large_2u_ms32", 350_000, 1 << 24, FAMILY_2U_MS32, 500, 8, 1002, 2006, "lognormal",
                               dict(median=math.exp(7.721), sigma=1.0, lo=1, hi=50_000)),
+    # many short rows (the unexpanded rcv1 has about 73 nonzeros per document): per-row costs, not arithmetic
+    "short_rows_2u": Workload("short_rows_2u", 2_000_000, 1 << 24, FAMILY_2U_M31, 500, 8, 1007, 2007, "lognormal",
+                              dict(median=60.0, sigma=0.6, lo=1, hi=5_000)),
     "huge_2u_m61": Workload("huge_2u_m61", 2_000_000, 1 << 30, FAMILY_2U_M61, 500, 1, 1005, 2005, "lomax",
                             dict(scale=580.4, tail=0.8, lo=1, hi=1_000_000), batch_rows=200_000),
 }

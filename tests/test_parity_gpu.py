@@ -182,6 +182,34 @@ def test_m61_large_universes():
             check_case(rp, col, D, 24, 32, family, c)
 
 
+def test_m61_fold_carries_engineered():
+    """Coefficients chosen so that W = c1 t + c0 + 1 has bits 32..60 all ones (or all but
+    one) and the fold's low-word addition lands just below, at and above a carry: the
+    cases in which bit 61 of the folded value is set, which random inputs never reach."""
+    D, p = 1 << 30, W.M61
+    ts = [(1 << 29) - 1, (1 << 30) - 1, 12345677, 3]
+    rows, n_hit = [], 0
+    for t in ts:
+        for A in (1, 5, 1 << 20, (t * (p - 1)) >> 61):
+            for s in (-1, 0, 1, 7):
+                for middle in ((1 << 61) - (1 << 32), (1 << 61) - (1 << 32) - (1 << 45)):
+                    B = (1 << 32) + s - A                       # B + A = 2^32 + s: carry iff s >= 0
+                    if not 0 <= B < (1 << 32):
+                        continue
+                    T = (A << 61) + middle + B                  # the value W must take
+                    c1 = min(T // t, p - 1)
+                    c0 = T - c1 * t - 1
+                    if 0 <= c0 < p:
+                        rows.append([c0, c1])
+                        n_hit += 1
+    assert n_hit >= 60
+    c = np.array(rows, dtype=np.uint64)
+    col = np.array(ts, dtype=np.uint32)
+    rp = np.arange(len(ts) + 1, dtype=np.int64)
+    check_case(rp, col, D, c.shape[0], 32, mh.FAMILY_2U_M61, c)
+    check_case(np.array([0, len(ts)], dtype=np.int64), col, D, c.shape[0], 32, mh.FAMILY_2U_M61, c)
+
+
 def test_extreme_coefficients_and_indices():
     """Residue 0, residue p-1, t = 0, t = D-1, zero and maximal coefficients."""
     D = 1 << 24
