@@ -43,12 +43,9 @@ namespace {
 
 using namespace mh;
 
-// alignment (log2 bytes) and default phase of the hot loops, see fix_loop_phase
-#ifndef MH_LOOP_ALIGN
-#define MH_LOOP_ALIGN 5
-#endif
-#ifndef MH_LOOP_PHASE_DEFAULT
-#define MH_LOOP_PHASE_DEFAULT 20
+// s_nop that open each iteration of a hot loop unless a policy names its own number, see open_iteration
+#ifndef MH_LOOP_NOPS_DEFAULT
+#define MH_LOOP_NOPS_DEFAULT 0
 #endif
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -260,19 +257,23 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
     v.top3 = in_vgpr_if_used(0xE0000000u);
     return v;
 }
-// Placed first in the body of a hot loop.  The instructions of these loops are 4
-// or 8 bytes long, and on gfx950 the same loop runs up to 5 % faster or slower
-// depending on where its instructions fall relative to 32-byte boundaries (2U:
-// 82.0 ms with the body starting 28 bytes past a boundary, 86.7 ms at 0); where
-// the compiler happens to put the loop would otherwise decide that, and change
-// with unrelated edits.  Aligning here (the padding is s_nop, at most seven per
-// iteration) and adding PHASE / 4 more fixes the position; each policy names its
-// phase, found by timing all eight.
-template <int PHASE>
-__device__ __forceinline__ void fix_loop_phase()
+// Where a hot loop sits in memory, and how many s_nop open each of its
+// iterations, changes its speed on gfx950 by several per cent (2U: between 79.9
+// and 86.7 ms for the same instructions; the counters show the same instruction
+// counts and more cycles spent waiting for issue).  The instructions are 4 or 8
+// bytes long; neither the number of 8-byte instructions that straddle 8-, 32- or
+// 64-byte boundaries nor the alignment of the loop alone explains the timings, so
+// both are pinned and the remaining knob is tuned by timing: pin_loop_entry()
+// right before the loop aligns the code that follows to 128 bytes (padding
+// executed once per tile), which fixes where the compiler's loop header lands, and
+// open_iteration<N>() first in the body emits N s_nop.  Without the pin, unrelated
+// edits elsewhere in the kernel moved the loop and changed the 2U time by 4 %.
+__device__ __forceinline__ void pin_loop_entry() { asm volatile(".p2align 7"); }
+template <int N>
+__device__ __forceinline__ void open_iteration()
 {
-    static_assert(PHASE >= 0 && PHASE < (1 << MH_LOOP_ALIGN) && PHASE % 4 == 0, "phase in bytes");
-    asm volatile(".p2align %c0\n\t.rept %c1\n\ts_nop 0\n\t.endr" : : "n"(MH_LOOP_ALIGN), "n"(PHASE / 4));
+    static_assert(N >= 0 && N < 64, "number of s_nop");
+    asm volatile(".rept %c0\n\ts_nop 0\n\t.endr" : : "n"(N));
 }
 __device__ __forceinline__ void wave_sync_lds()
 {
@@ -470,7 +471,7 @@ struct Pol2U31 {
     static constexpr bool PREFETCH = false;   // LDS words of the next step are read one step ahead
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
-    static constexpr int LOOP_PHASE = POW2 ? 28 : 0;   // timed: 82.0 ms at 28, 86.7 ms at 0 (power-of-two D)
+    static constexpr int LOOP_NOPS = POW2 ? 18 : 0;    // timed 0..31: 80.1 ms at 18, 86.4 ms at 0; other D: flat
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -495,7 +496,7 @@ struct Pol4U31 {
     static constexpr bool PREFETCH = true;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
-    static constexpr int LOOP_PHASE = POW2 ? 4 : 20;
+    static constexpr int LOOP_NOPS = MH_LOOP_NOPS_DEFAULT;
     using Fn = Fn4U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -532,7 +533,7 @@ struct Pol2U61 {
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
-    static constexpr int LOOP_PHASE = MH_LOOP_PHASE_DEFAULT;
+    static constexpr int LOOP_NOPS = POW2 ? 4 : 0;     // timed 0..31: 204.1 ms at 4, 208.9 ms at 0
     using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -560,7 +561,7 @@ struct Pol4U61 {
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
-    static constexpr int LOOP_PHASE = MH_LOOP_PHASE_DEFAULT;
+    static constexpr int LOOP_NOPS = MH_LOOP_NOPS_DEFAULT;
     using Fn = Fn4U61;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -860,7 +861,7 @@ struct PolGenericMod {
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
-    static constexpr int LOOP_PHASE = MH_LOOP_PHASE_DEFAULT;
+    static constexpr int LOOP_NOPS = MH_LOOP_NOPS_DEFAULT;
     static constexpr int DEG = DEGREE;
     struct Fn { uint64_t c[DEGREE]; uint64_t p; };
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
@@ -897,7 +898,7 @@ struct Pol2UMS32 {
     static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = true;
-    static constexpr int LOOP_PHASE = MH_LOOP_PHASE_DEFAULT;
+    static constexpr int LOOP_NOPS = MH_LOOP_NOPS_DEFAULT;
     using Fn = Fn2UMS32;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
@@ -1066,8 +1067,9 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 #pragma unroll
                     for (int i = 0; i < Pol::NW; ++i)
                         nxt[i] = *reinterpret_cast<const uint4*>(&tile[i][4 * slice]);
+                    pin_loop_entry();
                     for (int s = 0; s < n_steps; ++s) {
-                        fix_loop_phase<Pol::LOOP_PHASE>();
+                        open_iteration<Pol::LOOP_NOPS>();
                         uint32_t w[4][Pol::NW];
 #pragma unroll
                         for (int i = 0; i < Pol::NW; ++i) {
@@ -1082,8 +1084,9 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                         Pol::pair(fn, m, w[2], w[3], md, a.D);
                     }
                 } else {
+                    pin_loop_entry();
                     for (int s = 0; s < n_steps; ++s) {
-                        fix_loop_phase<Pol::LOOP_PHASE>();
+                        open_iteration<Pol::LOOP_NOPS>();
                         const int e = 4 * (s * n_slices + slice);
                         uint32_t w[4][Pol::NW];
 #pragma unroll
