@@ -47,6 +47,9 @@ using namespace mh;
 #ifndef MH_LOOP_NOPS_DEFAULT
 #define MH_LOOP_NOPS_DEFAULT 0
 #endif
+#ifndef MH_MID_NOPS_DEFAULT
+#define MH_MID_NOPS_DEFAULT 0
+#endif
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -266,13 +269,14 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
 // both are pinned and the remaining knob is tuned by timing: pin_loop_entry()
 // right before the loop aligns the code that follows to 128 bytes (padding
 // executed once per tile), which fixes where the compiler's loop header lands, and
-// open_iteration<N>() first in the body emits N s_nop.  Without the pin, unrelated
-// edits elsewhere in the kernel moved the loop and changed the 2U time by 4 %.
+// open_iteration<N>() emits N s_nop, first in the body (LOOP_NOPS) and between its
+// two halves (MID_NOPS).  Without the pin, unrelated edits elsewhere in the kernel
+// moved the loop and changed the 2U time by 4 %.
 __device__ __forceinline__ void pin_loop_entry() { asm volatile(".p2align 7"); }
 template <int N>
 __device__ __forceinline__ void open_iteration()
 {
-    static_assert(N >= 0 && N < 64, "number of s_nop");
+    static_assert(N >= 0 && N < 128, "number of s_nop");
     asm volatile(".rept %c0\n\ts_nop 0\n\t.endr" : : "n"(N));
 }
 __device__ __forceinline__ void wave_sync_lds()
@@ -472,6 +476,7 @@ struct Pol2U31 {
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
     static constexpr int LOOP_NOPS = POW2 ? 18 : 0;    // timed 0..31: 80.1 ms at 18, 86.4 ms at 0; other D: flat
+    static constexpr int MID_NOPS = POW2 ? 13 : 0;   // s_nop between the two halves of an iteration: 77.7 ms at 13, 79.9 ms at 0
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -497,6 +502,7 @@ struct Pol4U31 {
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
     static constexpr int LOOP_NOPS = MH_LOOP_NOPS_DEFAULT;
+    static constexpr int MID_NOPS = POW2 ? 32 : 0;   // 149.8 ms at 32, 153.2 ms at 0
     using Fn = Fn4U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -534,6 +540,7 @@ struct Pol2U61 {
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
     static constexpr int LOOP_NOPS = POW2 ? 4 : 0;     // timed 0..31: 204.1 ms at 4, 208.9 ms at 0
+    static constexpr int MID_NOPS = POW2 ? 10 : 0;   // 202.8 ms at 10, 203.9 ms at 0
     using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -562,6 +569,7 @@ struct Pol4U61 {
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
     static constexpr int LOOP_NOPS = MH_LOOP_NOPS_DEFAULT;
+    static constexpr int MID_NOPS = MH_MID_NOPS_DEFAULT;
     using Fn = Fn4U61;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -862,6 +870,7 @@ struct PolGenericMod {
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
     static constexpr int LOOP_NOPS = MH_LOOP_NOPS_DEFAULT;
+    static constexpr int MID_NOPS = MH_MID_NOPS_DEFAULT;
     static constexpr int DEG = DEGREE;
     struct Fn { uint64_t c[DEGREE]; uint64_t p; };
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
@@ -899,6 +908,7 @@ struct Pol2UMS32 {
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = true;
     static constexpr int LOOP_NOPS = MH_LOOP_NOPS_DEFAULT;
+    static constexpr int MID_NOPS = MH_MID_NOPS_DEFAULT;
     using Fn = Fn2UMS32;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
@@ -1081,6 +1091,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                         for (int i = 0; i < Pol::NW; ++i)
                             nxt[i] = *reinterpret_cast<const uint4*>(&tile[i][e]);
                         Pol::pair(fn, m, w[0], w[1], md, a.D);
+                        open_iteration<Pol::MID_NOPS>();
                         Pol::pair(fn, m, w[2], w[3], md, a.D);
                     }
                 } else {
@@ -1095,6 +1106,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                             w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
                         }
                         Pol::pair(fn, m, w[0], w[1], md, a.D);
+                        open_iteration<Pol::MID_NOPS>();
                         Pol::pair(fn, m, w[2], w[3], md, a.D);
                     }
                 }
