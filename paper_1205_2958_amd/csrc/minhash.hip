@@ -269,15 +269,20 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
 // both are pinned and the remaining knob is tuned by timing: pin_loop_entry()
 // right before the loop aligns the code that follows to 128 bytes (padding
 // executed once per tile), which fixes where the compiler's loop header lands, and
-// open_iteration<N>() emits N s_nop, first in the body (LOOP_NOPS) and between its
-// two halves (MID_NOPS).  Without the pin, unrelated edits elsewhere in the kernel
+// open_iteration<N>() idles for N cycles, first in the body (LOOP_NOPS) and between
+// its two halves (MID_NOPS); N one-cycle s_nop and one s_nop of N cycles time the same,
+// so it is the pause that matters, not the bytes.  Without the pin, unrelated edits elsewhere in the kernel
 // moved the loop and changed the 2U time by 4 %.
 __device__ __forceinline__ void pin_loop_entry() { asm volatile(".p2align 7"); }
 template <int N>
-__device__ __forceinline__ void open_iteration()
+__device__ __forceinline__ void open_iteration()      // N idle cycles: s_nop k idles k + 1 cycles, k <= 15
 {
-    static_assert(N >= 0 && N < 128, "number of s_nop");
-    asm volatile(".rept %c0\n\ts_nop 0\n\t.endr" : : "n"(N));
+    static_assert(N >= 0 && N <= 64, "idle cycles");
+    if (N > 48) asm volatile("s_nop 15");
+    if (N > 32) asm volatile("s_nop 15");
+    if (N > 16) asm volatile("s_nop 15");
+    if (N % 16 != 0) asm volatile("s_nop %c0" : : "n"((N % 16 + 15) % 16));
+    else if (N > 0) asm volatile("s_nop 15");
 }
 __device__ __forceinline__ void wave_sync_lds()
 {
