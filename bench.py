@@ -40,14 +40,14 @@ from paper_1205_2958_amd import workloads as W  # noqa: E402
 # issue slots per evaluation, one slot = one 64-lane instruction at 16 lanes/clk/SIMD.
 ISSUE_MIX = {
     W.FAMILY_2U_M31: (1.0 + 0.5, 5.0),         # mad, half a max3; shr,add,ashr,sub,and
-    W.FAMILY_4U_M31: (3.0 + 0.5, 8.0),         # 3 mad, half a max3; shr,and,shr,add,add,ashr,sub,and
+    W.FAMILY_4U_M31: (3.0 + 1.0 + 0.5, 6.0),   # 3 mad, add3, half a max3; shr,and,shr,ashr,sub,and
     W.FAMILY_2U_M61: (2.0 + 1.0 + 3.0 + 0.5, 3.0),   # 2 mad, funnel shift, add + 2 add-with-carry, half a min3; mov,or,and
     W.FAMILY_2U_MS32: (1.0 + 0.5, 0.0),        # mad, half a min3 (mask or shift once per row)
 }
 # other D (--universe): exact multiply-high quotient appended
 ISSUE_MIX_OTHER_D = {
     W.FAMILY_2U_M31: (1.0 + 1.0 + 1.0 + 1.0 + 0.5, 4.0),     # mad, min, mulhi, mad, half a min3; shr,add,sub,shr
-    W.FAMILY_4U_M31: (3.0 + 1.0 + 1.0 + 1.0 + 0.5, 8.0),     # 3 mad, min, mulhi, mad, half a min3; 5 fold ops, add,xor, shr
+    W.FAMILY_4U_M31: (3.0 + 1.0 + 1.0 + 1.0 + 1.0 + 0.5, 6.0),   # 3 mad, add3, min, mulhi, mad, half a min3; shr,and,shr, add,xor, shr
 }
 
 
