@@ -255,12 +255,14 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
 }
 // Issue priority of this wavefront among those of its SIMD.  The hand-ordered steps
 // raise it for their runs of full-issue instructions (multiply-adds, three-operand
-// extrema) and lower it for their runs of simple ones: a SIMD issues the simple
-// instructions of two wavefronts together, so those are best left to fill in
-// around a wavefront that holds the issue port with full-issue work.  2U: 82 ms
-// without, 68.5 ms with; the reverse assignment takes 96 ms.  (Without it the
-// same loop ran between 78 and 87 ms depending on where the compiler placed it and
-// on idle cycles added at the top of an iteration; with it neither matters.)
+// adds and extrema, carry chains) and lower it for their runs of simple ones.  A
+// SIMD issues the simple instructions of two wavefronts together, and a simple
+// instruction alongside another wavefront's full-issue one, so the issue port
+// should go to whoever has full-issue work while simple instructions fill in
+// around it.  2U: 78-82 ms without, 67.5 ms with; the reverse assignment takes
+// 96 ms; the level (1..3) makes no difference.  Without priorities the same loop
+// ran anywhere between 78 and 87 ms depending on where the compiler placed it
+// and on idle cycles inserted into an iteration; with them neither matters.
 template <int P>
 __device__ __forceinline__ void issue_priority()
 {
@@ -598,11 +600,13 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // 2U, p = 2^31-1, power-of-two D, with the instruction order fixed by hand.
 // On gfx950 a SIMD issues the simple integer instructions (shift right, add,
 // sub, and) of two different wavefronts together, but only while neither
-// depends on its predecessor; multiply-adds and three-operand extrema issue
-// alone.  Sixteen independent evaluations are therefore emitted stage by stage,
-// the two nonzeros half a stage apart, so that neighbouring instructions never
-// depend on each other and every wavefront's stream mixes both classes.  The
-// arithmetic is hash_compl_2u31 of mh_arith.h, instruction for instruction.
+// depends on its predecessor; multiply-adds and three-operand extrema take the
+// full issue width.  Sixteen independent evaluations are therefore emitted stage
+// by stage, the two nonzeros half a stage apart, so that neighbouring
+// instructions never depend on each other; the runs of full-issue instructions
+// (both ends of the step) execute at raised priority, the run of simple ones in
+// the middle at the normal one (see issue_priority).  The arithmetic is
+// hash_compl_2u31 of mh_arith.h, instruction for instruction.
 __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], uint32_t ta,
                                                uint32_t tb, uint32_t mask)
 {
