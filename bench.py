@@ -304,8 +304,9 @@ def main() -> int:
     cpu_rec, n_sample, cpu_sig = None, 0, None
     if args.cpu_seconds > 0 and family != W.FAMILY_PERM:
         procs = max(1, min(16, os.cpu_count() or 1))
-        rate_guess = {W.FAMILY_2U_M31: 3.0e7, W.FAMILY_4U_M31: 1.2e7, W.FAMILY_2U_M61: 2.0e7,
-                      W.FAMILY_2U_MS32: 6.0e7}[family]
+        # evaluations per second and core the oracle reaches on the GPU machine's host, to size the sample
+        rate_guess = {W.FAMILY_2U_M31: 7.0e7, W.FAMILY_4U_M31: 2.8e7, W.FAMILY_2U_M61: 1.6e7,
+                      W.FAMILY_2U_MS32: 1.0e8}[family]
         cpu_rec, n_sample, cpu_sig = cpu_baseline(w, params_np, rate_guess * args.cpu_seconds, procs, args.universe)
 
     import torch
