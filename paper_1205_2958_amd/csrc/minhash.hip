@@ -462,7 +462,6 @@ template <bool POW2>
 struct Pol2U31 {
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = POW2 ? 5 : 4;   // wavefronts per SIMD the register allocation must leave room for
-    static constexpr bool PREFETCH = false;   // LDS words of the next step are read one step ahead
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
     using Fn = Fn2U31;
@@ -486,7 +485,6 @@ template <bool POW2>
 struct Pol4U31 {
     static constexpr int NW = 3;
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
-    static constexpr bool PREFETCH = true;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
     using Fn = Fn4U31;
@@ -522,7 +520,6 @@ template <bool POW2>
 struct Pol2U61 {
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = POW2 ? 4 : 5;
-    static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
     using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
@@ -549,7 +546,6 @@ template <bool POW2>
 struct Pol4U61 {
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = 2;
-    static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
     using Fn = Fn4U61;
@@ -841,7 +837,6 @@ template <int DEGREE>
 struct PolGenericMod {
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = 3;        // no spills, so that the ablation times the arithmetic only
-    static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
     static constexpr int DEG = DEGREE;
@@ -877,7 +872,6 @@ template <bool HIGH>
 struct Pol2UMS32 {
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = 5;
-    static constexpr bool PREFETCH = false;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = true;
     using Fn = Fn2UMS32;
@@ -1041,39 +1035,16 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 
                 const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
                 const int n_steps = (int)((in_tile + 4u * n_slices - 1u) / (4u * n_slices));
-                if constexpr (Pol::PREFETCH) {
-                    // the words of step s+1 are fetched while step s computes (the last
-                    // step re-reads its own words: always inside the tile)
-                    uint4 nxt[Pol::NW];
+                for (int s = 0; s < n_steps; ++s) {
+                    const int e = 4 * (s * n_slices + slice);
+                    uint32_t w[4][Pol::NW];
 #pragma unroll
-                    for (int i = 0; i < Pol::NW; ++i)
-                        nxt[i] = *reinterpret_cast<const uint4*>(&tile[i][4 * slice]);
-                    for (int s = 0; s < n_steps; ++s) {
-                        uint32_t w[4][Pol::NW];
-#pragma unroll
-                        for (int i = 0; i < Pol::NW; ++i) {
-                            uint4 v = nxt[i];
-                            w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
-                        }
-                        const int e = 4 * ((s + 1 < n_steps ? s + 1 : s) * n_slices + slice);
-#pragma unroll
-                        for (int i = 0; i < Pol::NW; ++i)
-                            nxt[i] = *reinterpret_cast<const uint4*>(&tile[i][e]);
-                        Pol::pair(fn, m, w[0], w[1], md, a.D);
-                        Pol::pair(fn, m, w[2], w[3], md, a.D);
+                    for (int i = 0; i < Pol::NW; ++i) {
+                        uint4 v = *reinterpret_cast<const uint4*>(&tile[i][e]);
+                        w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
                     }
-                } else {
-                    for (int s = 0; s < n_steps; ++s) {
-                        const int e = 4 * (s * n_slices + slice);
-                        uint32_t w[4][Pol::NW];
-#pragma unroll
-                        for (int i = 0; i < Pol::NW; ++i) {
-                            uint4 v = *reinterpret_cast<const uint4*>(&tile[i][e]);
-                            w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
-                        }
-                        Pol::pair(fn, m, w[0], w[1], md, a.D);
-                        Pol::pair(fn, m, w[2], w[3], md, a.D);
-                    }
+                    Pol::pair(fn, m, w[0], w[1], md, a.D);
+                    Pol::pair(fn, m, w[2], w[3], md, a.D);
                 }
                 wave_sync_lds();
             }
