@@ -141,6 +141,7 @@ struct KArgs {
     int32_t k, b;
     int32_t n_ftiles;
     int32_t log2_fl;                   // lanes covering one function tile = 1 << log2_fl
+    int32_t ftile_size;                // functions per tile: (1 << log2_fl) * functions per lane (hash kernels), 256 (table)
     int32_t sig_bytes;
     uint32_t target_items;             // work items wanted for a balanced launch (a few per resident wavefront)
     uint32_t validate;
@@ -450,7 +451,7 @@ __device__ __forceinline__ void wave_pack_store(const KArgs& a, const uint32_t* 
 }
 
 // ------------------------------------------------------------------ hash-family policies
-template <class Pol>
+template <class Pol, int NF>
 __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
                                              const uint32_t* wa, const uint32_t* wb, const ModDV& md, uint64_t D);
 
@@ -464,6 +465,7 @@ struct Pol2U31 {
     static constexpr int MIN_WAVES = POW2 ? 5 : 4;   // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -476,6 +478,7 @@ struct Pol2U31 {
         if (POW2) return hash_compl_2u31(f, w[0], md.mask);
         return hash_2u31_raw(f, w[0], md);
     }
+    template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D);
     static constexpr int DEG = 2;
@@ -487,6 +490,7 @@ struct Pol4U31 {
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn4U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -504,6 +508,7 @@ struct Pol4U31 {
         if (POW2) return hash_compl_4u31(f, p, md.mask);
         return hash_4u31_np2(f, p, md);
     }
+    template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D);
     static constexpr int DEG = 4;
@@ -522,6 +527,7 @@ struct Pol2U61 {
     static constexpr int MIN_WAVES = POW2 ? 4 : 5;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool VARIABLE_NF = POW2;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -535,6 +541,7 @@ struct Pol2U61 {
     {
         return hash_2u61<POW2>(f, w[0], md, D);
     }
+    template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D);
     static constexpr int DEG = 2;
@@ -548,6 +555,7 @@ struct Pol4U61 {
     static constexpr int MIN_WAVES = 2;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool VARIABLE_NF = false;
     using Fn = Fn4U61;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -558,10 +566,11 @@ struct Pol4U61 {
     {
         return hash_4u61<POW2>(f, w[0], md, D);
     }
+    template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D)
     {
-        pair_generic<Pol4U61<POW2>>(fn, m, wa, wb, md, D);
+        pair_generic<Pol4U61<POW2>, NF>(fn, m, wa, wb, md, D);
     }
     static constexpr int DEG = 4;
 };
@@ -569,12 +578,12 @@ struct Pol4U61 {
 // ------------------------------------------------------------------ two nonzeros x 8 functions
 // The unit of the hot loop: fold the 16 evaluations of two staged nonzeros into
 // the 8 running extrema.  The generic form leaves the schedule to the compiler.
-template <class Pol>
+template <class Pol, int NF>
 __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
                                              const uint32_t* wa, const uint32_t* wb, const ModDV& md, uint64_t D)
 {
 #pragma unroll
-    for (int r = 0; r < HASH_FPL; ++r) {
+    for (int r = 0; r < NF; ++r) {
         uint32_t k0 = Pol::key(fn[r], wa, md, D);
         uint32_t k1 = Pol::key(fn[r], wb, md, D);
         m[r] = Pol::TRACK_MAX ? umax3(m[r], k0, k1) : umin3(m[r], k0, k1);
@@ -603,34 +612,36 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // normal one (see issue_priority); two such halves, then eight three-operand
 // maxima at raised priority.  The arithmetic is hash_compl_2u31 of mh_arith.h,
 // instruction for instruction.
+template <int NF>
 __device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&x)[HASH_FPL], uint32_t t, uint32_t mask)
 {
     uint64_t p[HASH_FPL];
     uint32_t sg[HASH_FPL];
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"((uint32_t)p[g]));
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"((uint32_t)p[g]));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"((uint32_t)(p[g] >> 32)));
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"((uint32_t)(p[g] >> 32)));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_ashrrev_i32 %0, 31, %1" : "=v"(sg[g]) : "v"(x[g]));
+    for (int g = 0; g < NF; ++g) asm volatile("v_ashrrev_i32 %0, 31, %1" : "=v"(sg[g]) : "v"(x[g]));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_sub_u32 %0, %1, %0" : "+v"(x[g]) : "v"(sg[g]));
+    for (int g = 0; g < NF; ++g) asm volatile("v_sub_u32 %0, %1, %0" : "+v"(x[g]) : "v"(sg[g]));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(x[g]) : "v"(mask));
+    for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(x[g]) : "v"(mask));
 }
+template <int NF>
 __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], uint32_t ta,
                                                uint32_t tb, uint32_t mask)
 {
     uint32_t xa[HASH_FPL], xb[HASH_FPL];
-    half_2u31_pow2(fn, xa, ta, mask);
-    half_2u31_pow2(fn, xb, tb, mask);
+    half_2u31_pow2<NF>(fn, xa, ta, mask);
+    half_2u31_pow2<NF>(fn, xb, tb, mask);
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
 }
 
@@ -638,6 +649,7 @@ __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
 // evaluation are issued function-major so that each waits for a result that is
 // 16 instructions old; the fold of nonzero A overlaps the last multiply-adds of
 // nonzero B.  Arithmetic of hash_compl_4u31 (mh_arith.h), instruction for instruction.
+template <int NF>
 __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], const uint32_t* w,
                                                uint32_t mask, uint32_t p31)
 {
@@ -645,42 +657,43 @@ __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
     uint32_t u[HASH_FPL], v[HASH_FPL];
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         MH_MAD(i64_i32, acc[g], fn[g].c1, w[0], fn[g].add);
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         MH_MAD_ACC(i64_i32, acc[g], fn[g].c2, w[1]);
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         MH_MAD_ACC(i64_i32, acc[g], fn[g].c3, w[2]);
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(y[g]) : "v"((uint32_t)acc[g]));
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(y[g]) : "v"((uint32_t)acc[g]));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(u[g]) : "v"((uint32_t)(acc[g] >> 32)), "v"(p31));
+    for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(u[g]) : "v"((uint32_t)(acc[g] >> 32)), "v"(p31));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(v[g]) : "v"((uint32_t)(acc[g] >> 32)));
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(v[g]) : "v"((uint32_t)(acc[g] >> 32)));
     issue_priority<1>();       // one three-operand add (full issue) instead of two simple adds: fewer instructions in all
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(y[g]) : "v"(u[g]), "v"(v[g]));
+    for (int g = 0; g < NF; ++g) asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(y[g]) : "v"(u[g]), "v"(v[g]));
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_ashrrev_i32 %0, 31, %1" : "=v"(u[g]) : "v"(y[g]));
+    for (int g = 0; g < NF; ++g) asm volatile("v_ashrrev_i32 %0, 31, %1" : "=v"(u[g]) : "v"(y[g]));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_sub_u32 %0, %1, %0" : "+v"(y[g]) : "v"(u[g]));
+    for (int g = 0; g < NF; ++g) asm volatile("v_sub_u32 %0, %1, %0" : "+v"(y[g]) : "v"(u[g]));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(y[g]) : "v"(mask));
+    for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(y[g]) : "v"(mask));
 }
 
+template <int NF>
 __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
                                                const uint32_t* wa, const uint32_t* wb, uint32_t mask, uint32_t p31)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
-    half_4u31_pow2(fn, ya, wa, mask, p31);
-    half_4u31_pow2(fn, yb, wb, mask, p31);
+    half_4u31_pow2<NF>(fn, ya, wa, mask, p31);
+    half_4u31_pow2<NF>(fn, yb, wb, mask, p31);
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
 }
 
@@ -690,97 +703,101 @@ __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
 // r + q (2^32 - D) can take the pair as its 64-bit addend (only the low word of
 // its result is used).  Arithmetic of hash_2u31_raw / hash_4u31_np2.
 
+template <int NF>
 __device__ __forceinline__ void half_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], u32x2 (&p)[HASH_FPL], uint32_t t, const ModDV& md)
 {
     uint32_t x[HASH_FPL], y[HASH_FPL], r;
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"(p[g].x));
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"(p[g].x));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"(p[g].y));
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"(p[g].y));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_sub_u32 %0, %1, %2" : "=v"(y[g]) : "v"(x[g]), "v"(md.p31));
+    for (int g = 0; g < NF; ++g) asm volatile("v_sub_u32 %0, %1, %2" : "=v"(y[g]) : "v"(x[g]), "v"(md.p31));
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) {
+    for (int g = 0; g < NF; ++g) {
         asm volatile("v_min_u32 %0, %1, %2" : "=v"(r) : "v"(x[g]), "v"(y[g]));
         p[g].x = r;
     }
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(x[g]) : "v"(p[g].x), "v"(md.M));
+    for (int g = 0; g < NF; ++g) asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(x[g]) : "v"(p[g].x), "v"(md.M));
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(x[g]) : "v"(md.sh));
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(x[g]) : "v"(md.sh));
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) MH_MAD_ACC(u64_u32, p[g], x[g], md.negD);
+    for (int g = 0; g < NF; ++g) MH_MAD_ACC(u64_u32, p[g], x[g], md.negD);
 }
+template <int NF>
 __device__ __forceinline__ void pair_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], uint32_t ta,
                                               uint32_t tb, const ModDV& md)
 {
     u32x2 pa[HASH_FPL], pb[HASH_FPL];
-    half_2u31_np2(fn, pa, ta, md);
-    half_2u31_np2(fn, pb, tb, md);
+    half_2u31_np2<NF>(fn, pa, ta, md);
+    half_2u31_np2<NF>(fn, pb, tb, md);
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(pa[g].x), "v"(pb[g].x));
 }
 
+template <int NF>
 __device__ __forceinline__ void half_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], u32x2 (&acc)[HASH_FPL], const uint32_t* w,
                                               const ModDV& md)
 {
     uint32_t y[HASH_FPL], u[HASH_FPL], v[HASH_FPL], r;
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         MH_MAD(i64_i32, acc[g], fn[g].c1, w[0], fn[g].add);
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         MH_MAD_ACC(i64_i32, acc[g], fn[g].c2, w[1]);
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         MH_MAD_ACC(i64_i32, acc[g], fn[g].c3, w[2]);
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(y[g]) : "v"(acc[g].x));
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(y[g]) : "v"(acc[g].x));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(u[g]) : "v"(acc[g].y), "v"(md.p31));
+    for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(u[g]) : "v"(acc[g].y), "v"(md.p31));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(v[g]) : "v"(acc[g].y));
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(v[g]) : "v"(acc[g].y));
     issue_priority<1>();       // one three-operand add (full issue) instead of two simple adds: fewer instructions in all
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(y[g]) : "v"(u[g]), "v"(v[g]));
+    for (int g = 0; g < NF; ++g) asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(y[g]) : "v"(u[g]), "v"(v[g]));
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_add_u32 %0, -1, %1" : "=v"(u[g]) : "v"(y[g]));
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, -1, %1" : "=v"(u[g]) : "v"(y[g]));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_xor_b32 %0, %0, %1" : "+v"(y[g]) : "v"(md.sign));
+    for (int g = 0; g < NF; ++g) asm volatile("v_xor_b32 %0, %0, %1" : "+v"(y[g]) : "v"(md.sign));
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) {
+    for (int g = 0; g < NF; ++g) {
         asm volatile("v_min_u32 %0, %1, %2" : "=v"(r) : "v"(u[g]), "v"(y[g]));
         acc[g].x = r;
     }
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(u[g]) : "v"(acc[g].x), "v"(md.M));
+    for (int g = 0; g < NF; ++g) asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(u[g]) : "v"(acc[g].x), "v"(md.M));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(u[g]) : "v"(md.sh));
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(u[g]) : "v"(md.sh));
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         MH_MAD_ACC(u64_u32, acc[g], u[g], md.negD);
 }
 
+template <int NF>
 __device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                               const uint32_t* wb, const ModDV& md)
 {
     u32x2 ya[HASH_FPL], yb[HASH_FPL];
-    half_4u31_np2(fn, ya, wa, md);
-    half_4u31_np2(fn, yb, wb, md);
+    half_4u31_np2<NF>(fn, ya, wa, md);
+    half_4u31_np2<NF>(fn, yb, wb, md);
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g].x), "v"(yb[g].x));
 }
 
@@ -789,6 +806,7 @@ __device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint
 // register pairs: c1 out of x_lo = L_lo + (H >> 29), c2 out of
 // (H_lo | 0xE0000000) + c1, which is set exactly when bit 61 of x is; the last
 // add-with-carry forms x_lo + c2 - 1.
+template <int NF>
 __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t t,
                                                const ModDV& md)
 {
@@ -797,37 +815,37 @@ __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], ui
     uint64_t c1[HASH_FPL], c2[HASH_FPL], c3;
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) MH_MAD(u64_u32, L[g], fn[g].e0, t, fn[g].add);
+    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, L[g], fn[g].e0, t, fn[g].add);
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) {
+    for (int g = 0; g < NF; ++g) {
         asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "v"(L[g].y));
         fn[g].hz.x = r;
     }
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) MH_MAD(u64_u32, H[g], fn[g].e1, t, fn[g].hz);
+    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, H[g], fn[g].e1, t, fn[g].hz);
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
+    for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_or_b32 %0, %1, %2" : "=v"(o[g]) : "v"(H[g].x), "v"(md.top3));
+    for (int g = 0; g < NF; ++g) asm volatile("v_or_b32 %0, %1, %2" : "=v"(o[g]) : "v"(H[g].x), "v"(md.top3));
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         asm volatile("v_add_co_u32 %0, %1, %2, %3" : "=v"(s[g]), "=s"(c1[g]) : "v"(L[g].x), "v"(s[g]));
     // the two add-with-carry stages run two evaluations apart, so that no statement
     // reads what its predecessor wrote
 #pragma unroll
-    for (int g = 0; g < HASH_FPL + 2; ++g) {
-        if (g < HASH_FPL)
+    for (int g = 0; g < NF + 2; ++g) {
+        if (g < NF)
             asm volatile("v_addc_co_u32 %0, %1, %2, 0, %3" : "=v"(o[g]), "=s"(c2[g]) : "v"(o[g]), "s"(c1[g]));
         if (g >= 2)
             asm volatile("v_addc_co_u32 %0, %1, %2, -1, %3" : "=v"(y[g - 2]), "=s"(c3) : "v"(s[g - 2]), "s"(c2[g - 2]));
     }
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(y[g]) : "v"(md.mask));
+    for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(y[g]) : "v"(md.mask));
 }
 
 // Ablation: the definition evaluated with the % operator on runtime moduli (Horner
@@ -839,6 +857,7 @@ struct PolGenericMod {
     static constexpr int MIN_WAVES = 3;        // no spills, so that the ablation times the arithmetic only
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool VARIABLE_NF = false;
     static constexpr int DEG = DEGREE;
     struct Fn { uint64_t c[DEGREE]; uint64_t p; };
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
@@ -858,10 +877,11 @@ struct PolGenericMod {
         for (int i = DEGREE - 2; i >= 0; --i) acc = (acc * t + f.c[i]) % f.p;
         return (uint32_t)(acc % D);
     }
+    template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D)
     {
-        pair_generic<PolGenericMod<DEGREE>>(fn, m, wa, wb, md, D);
+        pair_generic<PolGenericMod<DEGREE>, NF>(fn, m, wa, wb, md, D);
     }
 };
 
@@ -874,6 +894,7 @@ struct Pol2UMS32 {
     static constexpr int MIN_WAVES = 5;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFT_END = true;
+    static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn2UMS32;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
@@ -884,65 +905,72 @@ struct Pol2UMS32 {
     {
         return key_2ums32(f, w[0]);
     }
+    template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV&, uint64_t)
     {
         uint64_t pa[HASH_FPL], pb[HASH_FPL];
 #pragma unroll
-        for (int g = 0; g < HASH_FPL; ++g)
+        for (int g = 0; g < NF; ++g)
             MH_MAD(u64_u32, pa[g], fn[g].c1, wa[0], fn[g].add);
 #pragma unroll
-        for (int g = 0; g < HASH_FPL; ++g)
+        for (int g = 0; g < NF; ++g)
             MH_MAD(u64_u32, pb[g], fn[g].c1, wb[0], fn[g].add);
 #pragma unroll
-        for (int g = 0; g < HASH_FPL; ++g)
+        for (int g = 0; g < NF; ++g)
             asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"((uint32_t)pa[g]), "v"((uint32_t)pb[g]));
     }
     static constexpr int DEG = 2;
 };
 
 template <>
+template <int NF>
 __device__ __forceinline__ void Pol2U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                     const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_2u31_pow2(fn, m, wa[0], wb[0], md.mask);
+    pair_2u31_pow2<NF>(fn, m, wa[0], wb[0], md.mask);
 }
 template <>
+template <int NF>
 __device__ __forceinline__ void Pol2U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t D)
 {
-    pair_2u31_np2(fn, m, wa[0], wb[0], md);
+    pair_2u31_np2<NF>(fn, m, wa[0], wb[0], md);
 }
 
 template <>
+template <int NF>
 __device__ __forceinline__ void Pol4U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                     const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_4u31_pow2(fn, m, wa, wb, md.mask, md.p31);
+    pair_4u31_pow2<NF>(fn, m, wa, wb, md.mask, md.p31);
 }
 template <>
+template <int NF>
 __device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t D)
 {
-    pair_4u31_np2(fn, m, wa, wb, md);
+    pair_4u31_np2<NF>(fn, m, wa, wb, md);
 }
 
 template <>
+template <int NF>
 __device__ __forceinline__ void Pol2U61<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                     const uint32_t* wb, const ModDV& md, uint64_t)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
-    half_2u61_pow2(fn, ya, wa[0], md);
-    half_2u61_pow2(fn, yb, wb[0], md);
+    half_2u61_pow2<NF>(fn, ya, wa[0], md);
+    half_2u61_pow2<NF>(fn, yb, wb[0], md);
 #pragma unroll
-    for (int g = 0; g < HASH_FPL; ++g)
+    for (int g = 0; g < NF; ++g)
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
 }
 template <>
+template <int NF>
 __device__ __forceinline__ void Pol2U61<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t D)
 {
-    pair_generic<Pol2U61<false>>(fn, m, wa, wb, md, D);
+    pair_generic<Pol2U61<false>, NF>(fn, m, wa, wb, md, D);
 }
 
 // ------------------------------------------------------------------ staging
@@ -960,7 +988,7 @@ __device__ __forceinline__ void load_tile(const uint32_t* col, int64_t begin, ui
 }
 
 // ------------------------------------------------------------------ the hash kernel
-template <class Pol>
+template <class Pol, int NF>
 __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_WAVES, 8))) void mh_hash_kernel(KArgs a)
 {
     __shared__ uint32_t s_tile[WAVES_PER_BLOCK][Pol::NW][TILE];
@@ -993,11 +1021,11 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
         if (!units.take(&a.hdr->ticket, lane, &ticket)) break;
         const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
         const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
-        const int j_base = ftile * HASH_FTILE + fl * HASH_FPL;
+        const int j_base = ftile * a.ftile_size + fl * NF;
         if (ftile != cur_ftile) {
             const uint64_t* coeffs = static_cast<const uint64_t*>(a.params);
 #pragma unroll
-            for (int r = 0; r < HASH_FPL; ++r) {
+            for (int r = 0; r < NF; ++r) {
                 int j = j_base + r;
                 bool valid = j < a.k;
                 fn[r] = Pol::load(coeffs + (size_t)(valid ? j : 0) * Pol::DEG, valid, a);
@@ -1010,7 +1038,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 
         uint32_t m[HASH_FPL];
 #pragma unroll
-        for (int r = 0; r < HASH_FPL; ++r) m[r] = Pol::TRACK_MAX ? 0u : EMPTY_MIN;
+        for (int r = 0; r < NF; ++r) m[r] = Pol::TRACK_MAX ? 0u : EMPTY_MIN;
 
         if (len > 0) {
             uint32_t pad = a.col_idx[begin];
@@ -1043,44 +1071,44 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                         uint4 v = *reinterpret_cast<const uint4*>(&tile[i][e]);
                         w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
                     }
-                    Pol::pair(fn, m, w[0], w[1], md, a.D);
-                    Pol::pair(fn, m, w[2], w[3], md, a.D);
+                    Pol::template pair<NF>(fn, m, w[0], w[1], md, a.D);
+                    Pol::template pair<NF>(fn, m, w[2], w[3], md, a.D);
                 }
                 wave_sync_lds();
             }
             if (Pol::TRACK_MAX) {      // back from complements to the minimum location
 #pragma unroll
-                for (int r = 0; r < HASH_FPL; ++r) m[r] = md.mask - m[r];
+                for (int r = 0; r < NF; ++r) m[r] = md.mask - m[r];
             }
             if (Pol::SHIFT_END) {      // from the order-preserving key back to the hashed location
 #pragma unroll
-                for (int r = 0; r < HASH_FPL; ++r) m[r] = finish_2ums32(m[r], a.md.M);
+                for (int r = 0; r < NF; ++r) m[r] = finish_2ums32(m[r], a.md.M);
             }
         } else if (Pol::TRACK_MAX) {
 #pragma unroll
-            for (int r = 0; r < HASH_FPL; ++r) m[r] = EMPTY_MIN;
+            for (int r = 0; r < NF; ++r) m[r] = EMPTY_MIN;
         }
         // merge the slices of nonzeros (lanes that share fl)
         for (int d = fl_lanes; d < WAVE; d <<= 1) {
 #pragma unroll
-            for (int r = 0; r < HASH_FPL; ++r) {
+            for (int r = 0; r < NF; ++r) {
                 uint32_t o = (uint32_t)__shfl_xor((int)m[r], d, WAVE);
                 m[r] = o < m[r] ? o : m[r];
             }
         }
-        const int nf_tile = a.k - ftile * HASH_FTILE < HASH_FTILE ? a.k - ftile * HASH_FTILE : HASH_FTILE;
+        const int nf_tile = a.k - ftile * a.ftile_size < a.ftile_size ? a.k - ftile * a.ftile_size : a.ftile_size;
         if (it.slot == NO_SLOT) {
             if (slice == 0) {
 #pragma unroll
-                for (int r = 0; r < HASH_FPL; ++r) mins[fl * HASH_FPL + r] = m[r];
+                for (int r = 0; r < NF; ++r) mins[fl * NF + r] = m[r];
             }
             wave_sync_lds();
-            wave_pack_store(a, mins, it.row, ftile * HASH_FTILE, nf_tile, ftile == a.n_ftiles - 1, lane);
+            wave_pack_store(a, mins, it.row, ftile * a.ftile_size, nf_tile, ftile == a.n_ftiles - 1, lane);
             wave_sync_lds();
         } else if (slice == 0) {
             uint32_t* part = a.scratch + (size_t)it.slot * (size_t)a.k;
 #pragma unroll
-            for (int r = 0; r < HASH_FPL; ++r)
+            for (int r = 0; r < NF; ++r)
                 if (j_base + r < a.k) part[j_base + r] = m[r];
         }
     }
@@ -1297,11 +1325,48 @@ int resident_blocks(K kernel, int cus)
     return cus * per_cu;
 }
 
-template <class Pol>
-void launch_hash(const KArgs& a, int cus, hipStream_t s)
+template <class Pol, int NF>
+void launch_hash_nf(const KArgs& a, int cus, hipStream_t s)
 {
-    static const int blocks = resident_blocks(mh_hash_kernel<Pol>, cus);
-    hipLaunchKernelGGL(mh_hash_kernel<Pol>, dim3(blocks), dim3(BLOCK), 0, s, a);
+    static const int blocks = resident_blocks(mh_hash_kernel<Pol, NF>, cus);
+    hipLaunchKernelGGL((mh_hash_kernel<Pol, NF>), dim3(blocks), dim3(BLOCK), 0, s, a);
+}
+// nf = functions per lane of this launch (see functions_per_lane); the hand-ordered
+// policies exist for 5..8, the compiler-scheduled ones for 8 only
+template <class Pol>
+void launch_hash(const KArgs& a, int nf, int cus, hipStream_t s)
+{
+    if constexpr (Pol::VARIABLE_NF) {
+        switch (nf) {
+        case 5: launch_hash_nf<Pol, 5>(a, cus, s); return;
+        case 6: launch_hash_nf<Pol, 6>(a, cus, s); return;
+        case 7: launch_hash_nf<Pol, 7>(a, cus, s); return;
+        default: break;
+        }
+    }
+    launch_hash_nf<Pol, HASH_FPL>(a, cus, s);
+}
+
+// How many of its HASH_FPL function slots a lane uses.  A tile of functions spans
+// 2^log2_fl lanes; with 8 functions per lane k = 300 would occupy 64 lanes x 8 = 512
+// slots and k = 200 32 x 8 = 256, although 64 x 5 and 32 x 7 suffice.  For k up to
+// one tile the pair (lanes, functions per lane) with the fewest slots is taken,
+// functions per lane in 5..8 (fewer would only halve the lanes again).
+void functions_per_lane(int k, bool variable, int* nf, int* log2_fl)
+{
+    *nf = HASH_FPL;
+    int lanes_needed = ((k < HASH_FTILE ? k : HASH_FTILE) + HASH_FPL - 1) / HASH_FPL;
+    int lg = 0;
+    while ((1 << lg) < lanes_needed) ++lg;
+    *log2_fl = lg;
+    if (!variable || k > HASH_FTILE) return;
+    int best = (1 << lg) * HASH_FPL;
+    for (int f = HASH_FPL - 1; f >= 5; --f) {
+        int need = (k + f - 1) / f, l = 0;
+        while ((1 << l) < need) ++l;
+        if ((1 << l) > WAVE) continue;
+        if ((1 << l) * f < best) { best = (1 << l) * f; *nf = f; *log2_fl = l; }
+    }
 }
 
 int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_t D, int32_t k, int32_t b,
@@ -1369,16 +1434,22 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     a.target_items = 0;
 
     const bool perm = family == MINHASH_PERM;
-    const int ftile_size = perm ? PERM_FTILE : HASH_FTILE;
-    a.n_ftiles = (k + ftile_size - 1) / ftile_size;
+    const bool pow2 = a.md.pow2 != 0;
+    int nf = HASH_FPL;
+    int ftile_size = PERM_FTILE;
     if (!perm) {
-        int lanes_needed = ((k < HASH_FTILE ? k : HASH_FTILE) + HASH_FPL - 1) / HASH_FPL;
+        // the kernels ordered by hand come with 5..8 functions per lane
+        const bool variable = !generic_mod && family != MINHASH_4U_M61 &&
+                              !(family == MINHASH_2U_M61 && !(pow2 && D <= (1ull << 31)));
         int lg = 0;
-        while ((1 << lg) < lanes_needed) ++lg;
+        functions_per_lane(k, variable, &nf, &lg);
         a.log2_fl = lg;
+        ftile_size = k > HASH_FTILE ? HASH_FTILE : (1 << lg) * nf;
     } else {
         a.log2_fl = 6;
     }
+    a.ftile_size = ftile_size;
+    a.n_ftiles = (k + ftile_size - 1) / ftile_size;
 
     // tickets and unit numbers are 32 bits wide; tickets run past the last unit by one per resident wavefront
     if ((L.cap_long + L.cap_short) * (uint64_t)a.n_ftiles >= (1ull << 32) - (1ull << 24)) return MINHASH_ERR_ARG;
@@ -1398,26 +1469,25 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         hipEventRecord(e0, s);
     }
     const int main_blocks = cus;
-    const bool pow2 = a.md.pow2 != 0;
     switch (generic_mod ? -family - 1 : family) {
-    case -MINHASH_2U_M31 - 1: launch_hash<PolGenericMod<2>>(a, main_blocks, s); break;
-    case -MINHASH_4U_M31 - 1: launch_hash<PolGenericMod<4>>(a, main_blocks, s); break;
+    case -MINHASH_2U_M31 - 1: launch_hash<PolGenericMod<2>>(a, nf, main_blocks, s); break;
+    case -MINHASH_4U_M31 - 1: launch_hash<PolGenericMod<4>>(a, nf, main_blocks, s); break;
     case MINHASH_2U_M31:
-        if (pow2) launch_hash<Pol2U31<true>>(a, main_blocks, s); else launch_hash<Pol2U31<false>>(a, main_blocks, s);
+        if (pow2) launch_hash<Pol2U31<true>>(a, nf, main_blocks, s); else launch_hash<Pol2U31<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_4U_M31:
-        if (pow2) launch_hash<Pol4U31<true>>(a, main_blocks, s); else launch_hash<Pol4U31<false>>(a, main_blocks, s);
+        if (pow2) launch_hash<Pol4U31<true>>(a, nf, main_blocks, s); else launch_hash<Pol4U31<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_2U_M61:
         // the 32-bit-multiplicand arithmetic needs t < 2^31
-        if (pow2 && D <= (1ull << 31)) launch_hash<Pol2U61<true>>(a, main_blocks, s);
-        else launch_hash<Pol2U61<false>>(a, main_blocks, s);
+        if (pow2 && D <= (1ull << 31)) launch_hash<Pol2U61<true>>(a, nf, main_blocks, s);
+        else launch_hash<Pol2U61<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_4U_M61:
-        if (pow2) launch_hash<Pol4U61<true>>(a, main_blocks, s); else launch_hash<Pol4U61<false>>(a, main_blocks, s);
+        if (pow2) launch_hash<Pol4U61<true>>(a, nf, main_blocks, s); else launch_hash<Pol4U61<false>>(a, nf, main_blocks, s);
         break;
-    case MINHASH_2U_MS32: launch_hash<Pol2UMS32<false>>(a, main_blocks, s); break;
-    case MINHASH_2U_MS32_HIGH: launch_hash<Pol2UMS32<true>>(a, main_blocks, s); break;
+    case MINHASH_2U_MS32: launch_hash<Pol2UMS32<false>>(a, nf, main_blocks, s); break;
+    case MINHASH_2U_MS32_HIGH: launch_hash<Pol2UMS32<true>>(a, nf, main_blocks, s); break;
     case MINHASH_PERM: {
         const bool vec4 = (perm_ld % 4 == 0) && (reinterpret_cast<uintptr_t>(params) % 16 == 0);
         static const int blocks_v = resident_blocks(mh_perm_kernel<true>, cus);

@@ -105,6 +105,19 @@ def test_function_counts(k):
     check_case(rp, col, D, k, 8, mh.FAMILY_2U_M31, W.coefficients(k, mh.FAMILY_2U_M31, seed=k))
 
 
+@pytest.mark.parametrize("family,D", [(mh.FAMILY_2U_M31, 1 << 24), (mh.FAMILY_2U_M31, 16609143), (mh.FAMILY_4U_M31, 1 << 24),
+                                      (mh.FAMILY_4U_M31, 16609143), (mh.FAMILY_2U_M61, 1 << 30), (mh.FAMILY_2U_MS32, 1 << 24),
+                                      (mh.FAMILY_2U_MS32_HIGH, 1 << 24)])
+@pytest.mark.parametrize("k", [40, 100, 200, 300, 320, 400, 448, 449])
+def test_functions_per_lane_variants(family, D, k):
+    """k decides how many of its eight function slots a lane uses (5 to 8) and how many
+    lanes a tile spans; every hand-ordered kernel exists once per count."""
+    rp, col = edge_rows(1 << 24, seed=61)
+    if D & (D - 1):
+        col = (col % np.uint32(D)).astype(np.uint32)
+    check_case(rp, col, D, k, 8, family, W.coefficients(k, family, seed=62 + k))
+
+
 @pytest.mark.parametrize("b", [1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 16, 24, 31, 32])
 def test_bit_widths_and_unaligned_rows(b):
     D, k = 1 << 24, 77
