@@ -195,6 +195,39 @@ def test_m61_large_universes():
             check_case(rp, col, D, 24, 32, family, c)
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_random_configurations(seed):
+    """Family, universe, k, b, row pitch and the mix of row lengths drawn from a seeded
+    generator: combinations the structured cases above do not enumerate."""
+    rng = np.random.Generator(np.random.PCG64(9000 + seed))
+    family = int(rng.choice([mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61, mh.FAMILY_4U_M61,
+                             mh.FAMILY_2U_MS32, mh.FAMILY_2U_MS32_HIGH]))
+    s_bits = int(rng.integers(8, 31))
+    D = 1 << s_bits
+    if family in (mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61, mh.FAMILY_4U_M61) and rng.random() < 0.4:
+        D = int(rng.integers((1 << (s_bits - 1)) + 1, 1 << s_bits))          # not a power of two
+    k = int(rng.choice([1, 3, 17, 64, 100, 129, 200, 257, 300, 333, 500, 512, 513, 700]))
+    if family == mh.FAMILY_4U_M61:
+        k = min(k, 200)
+    b = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 32]))
+    n = int(rng.integers(1, 400))
+    kind = rng.random()
+    if kind < 0.3:
+        nnz = rng.integers(0, 40, size=n)
+    elif kind < 0.7:
+        nnz = np.rint(np.exp(rng.normal(5.0, 1.5, size=n))).astype(np.int64)
+    else:
+        nnz = np.concatenate([rng.integers(0, 300, size=n), rng.integers(8000, 40000, size=3)])
+    nnz = np.minimum(nnz, min(D, 60000)).astype(np.int64)
+    rp = W.row_ptr_from_nnz(nnz)
+    gen_D = 1 << max(s_bits, 16)
+    col = W.csr_indices_np(np.minimum(nnz, gen_D), gen_D, seed=seed)
+    col = (col % np.uint32(D)).astype(np.uint32) if D < gen_D else col
+    sig = (k * b + 7) // 8
+    stride = sig + int(rng.choice([0, 0, 1, 3, 8]))
+    check_case(rp, col, D, k, b, family, W.coefficients(k, family, seed=100 + seed), out_stride=stride)
+
+
 def test_m61_fold_carries_engineered():
     """Coefficients chosen so that W = c1 t + c0 + 1 has bits 32..60 all ones (or all but
     one) and the fold's low-word addition lands just below, at and above a carry: the
