@@ -933,7 +933,7 @@ __device__ __forceinline__ void Pol2U31<true>::pair(const Fn (&fn)[HASH_FPL], ui
 template <>
 template <int NF>
 __device__ __forceinline__ void Pol2U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                     const uint32_t* wb, const ModDV& md, uint64_t D)
+                                                     const uint32_t* wb, const ModDV& md, uint64_t)
 {
     pair_2u31_np2<NF>(fn, m, wa[0], wb[0], md);
 }
@@ -948,7 +948,7 @@ __device__ __forceinline__ void Pol4U31<true>::pair(const Fn (&fn)[HASH_FPL], ui
 template <>
 template <int NF>
 __device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
-                                                     const uint32_t* wb, const ModDV& md, uint64_t D)
+                                                     const uint32_t* wb, const ModDV& md, uint64_t)
 {
     pair_4u31_np2<NF>(fn, m, wa, wb, md);
 }
@@ -1465,8 +1465,9 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         hipError_t e = hipEventCreate(&e0);
         if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
         e = hipEventCreate(&e1);
-        if (e != hipSuccess) { hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
-        hipEventRecord(e0, s);
+        if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
+        e = hipEventRecord(e0, s);
+        if (e != hipSuccess) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return hip_fail(e, "hipEventRecord"); }
     }
     const int main_blocks = cus;
     switch (generic_mod ? -family - 1 : family) {
@@ -1497,20 +1498,23 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         break;
     }
     default:                                       // unreachable: the family was validated above
-        if (profiled) { hipEventDestroy(e0); hipEventDestroy(e1); }
+        if (profiled) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); }
         return MINHASH_ERR_FAMILY;
     }
-    if (profiled) hipEventRecord(e1, s);
+    hipError_t re = profiled ? hipEventRecord(e1, s) : hipSuccess;
     if (L.cap_split > 0) hipLaunchKernelGGL(mh_finalize_kernel, dim3(cus * 2), dim3(BLOCK), 0, s, a, ftile_size);
 
     hipError_t le = hipGetLastError();
     if (profiled) {
         hipError_t se = hipStreamSynchronize(s);
         float ms = 0.0f;
-        if (se == hipSuccess && le == hipSuccess) hipEventElapsedTime(&ms, e0, e1);
-        hipEventDestroy(e0);
-        hipEventDestroy(e1);
+        hipError_t te = hipSuccess;
+        if (se == hipSuccess && le == hipSuccess && re == hipSuccess) te = hipEventElapsedTime(&ms, e0, e1);
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
         if (se != hipSuccess) return hip_fail(se, "hipStreamSynchronize");
+        if (re != hipSuccess) return hip_fail(re, "hipEventRecord");
+        if (te != hipSuccess) return hip_fail(te, "hipEventElapsedTime");
         if (kernel_ms) *kernel_ms = ms;
     }
     if (le != hipSuccess) return hip_fail(le, "kernel launch");
