@@ -7,9 +7,12 @@ example) as one command.
 writes ``out_prefix.sig.npy`` (uint8 [n, ceil(k*b/8)], value j of a row in bits
 [j*b, (j+1)*b) of its little-endian bit string), ``out_prefix.labels.npy``
 (float32 [n]) and ``out_prefix.json`` (k, b, family, D, seed, so that the hash
-functions can be drawn again).  ``--expand`` also writes ``out_prefix.expanded.npy``
-(int32 [n, k]): the positions of the k ones of each example in the 2^b * k
-dimensional binary vector that Section 1.1 feeds to a linear learner.
+functions can be drawn again).  ``--expand`` also writes
+``out_prefix.expanded.npy`` (int32 [n, k]): the positions of the k ones of each
+example in the 2^b * k dimensional binary vector that Section 1.1 feeds to a
+linear learner.  ``--save-csr file`` keeps a binary copy of the parsed data,
+which is accepted as input in place of the text, so that trying other k, b or
+hash families (the experiments of Section 4) parses the text once.
 
 This module only moves buffers: parsing is the library's threaded parser,
 hashing and expansion are its kernels.
@@ -19,6 +22,7 @@ from __future__ import annotations
 import argparse
 import json
 import mmap
+import os
 import sys
 import time
 
@@ -28,6 +32,45 @@ import torch
 from . import minhash as mh
 from . import workloads as W
 
+CSR_MAGIC = b"MHCSR1\0\0"
+
+
+def save_csr(path: str, row_ptr: np.ndarray, col_idx: np.ndarray, labels: np.ndarray, max_index: int) -> None:
+    """Binary copy of a parsed data set: magic, n_rows, nnz, largest index (three
+    little-endian int64), then row_ptr int64[n+1], col_idx uint32[nnz], labels
+    float32[n].  Parsing text runs at a few GB/s; reading this back runs at the
+    speed of the file system, so a data set is parsed once."""
+    n, nnz = int(row_ptr.shape[0]) - 1, int(col_idx.shape[0])
+    with open(path, "wb") as f:
+        f.write(CSR_MAGIC)
+        f.write(np.array([n, nnz, max_index], dtype="<i8").tobytes())
+        f.write(np.ascontiguousarray(row_ptr, dtype="<i8").tobytes())
+        f.write(np.ascontiguousarray(col_idx).view(np.uint32).astype("<u4", copy=False).tobytes())
+        f.write(np.ascontiguousarray(labels, dtype="<f4").tobytes())
+
+
+def load_csr(path: str):
+    """Memory-maps a file written by save_csr; returns (row_ptr, col_idx, labels, max_index)
+    as NumPy views of the file, or None when the file does not start with the magic."""
+    with open(path, "rb") as f:
+        head = f.read(len(CSR_MAGIC) + 24)
+    if len(head) < len(CSR_MAGIC) + 24 or head[:len(CSR_MAGIC)] != CSR_MAGIC:
+        return None
+    n, nnz, max_index = (int(v) for v in np.frombuffer(head[len(CSR_MAGIC):], dtype="<i8"))
+    if n < 0 or nnz < 0:
+        raise ValueError("corrupt CSR file header")
+    off = len(CSR_MAGIC) + 24
+    need = off + 8 * (n + 1) + 4 * nnz + 4 * n
+    if os.path.getsize(path) != need:
+        raise ValueError("CSR file has %d bytes, its header announces %d" % (os.path.getsize(path), need))
+    row_ptr = np.memmap(path, dtype="<i8", mode="r", offset=off, shape=(n + 1,))
+    col_idx = np.memmap(path, dtype="<u4", mode="r", offset=off + 8 * (n + 1), shape=(nnz,)) if nnz else np.zeros(0, "<u4")
+    labels = np.memmap(path, dtype="<f4", mode="r", offset=off + 8 * (n + 1) + 4 * nnz, shape=(n,)) if n else np.zeros(0, "<f4")
+    if n and (int(row_ptr[0]) != 0 or int(row_ptr[-1]) != nnz):
+        raise ValueError("corrupt CSR file: row_ptr does not span the index array")
+    return row_ptr, col_idx, labels, max_index
+
+
 FAMILIES = {
     "2u": mh.FAMILY_2U_M31, "4u": mh.FAMILY_4U_M31, "2u61": mh.FAMILY_2U_M61, "4u61": mh.FAMILY_4U_M61,
     "ms32": mh.FAMILY_2U_MS32, "ms32high": mh.FAMILY_2U_MS32_HIGH,
@@ -35,30 +78,41 @@ FAMILIES = {
 
 
 def _pinned_copy(a: np.ndarray) -> torch.Tensor:
-    t = torch.empty(a.shape, dtype=torch.from_numpy(a[:0]).dtype, pin_memory=True)
+    t = torch.empty(a.shape, dtype=torch.from_numpy(np.empty(0, dtype=a.dtype)).dtype, pin_memory=True)
     t.numpy()[...] = a
     return t
 
 
 def run(path: str, prefix: str, k: int, b: int, family_name: str, seed: int, universe: int, batch_rows: int,
-        index_base: int, threads: int, expand: bool, log=print) -> dict:
+        index_base: int, threads: int, expand: bool, log=print, save_csr_path: str = "") -> dict:
     family = FAMILIES[family_name]
     dev = torch.device("cuda:0")
     t0 = time.perf_counter()
-    with open(path, "rb") as f:
-        size = f.seek(0, 2)
-        if size == 0:
-            raise SystemExit("empty input file")
-        mm = mmap.mmap(f.fileno(), 0, access=mmap.ACCESS_READ)
-        try:
-            row_ptr, col_idx, labels, max_index = mh.parse_libsvm(mm, index_base=index_base, n_threads=threads)
-        finally:
-            mm.close()
-    n = row_ptr.numel() - 1
-    nnz = col_idx.numel()
+    binary = load_csr(path)
+    if binary is not None:
+        rp, col, lab_np, max_index = binary
+        size = 0
+    else:
+        with open(path, "rb") as f:
+            size = f.seek(0, 2)
+            if size == 0:
+                raise SystemExit("empty input file")
+            mm = mmap.mmap(f.fileno(), 0, access=mmap.ACCESS_READ)
+            try:
+                row_ptr, col_idx, labels, max_index = mh.parse_libsvm(mm, index_base=index_base, n_threads=threads)
+            finally:
+                mm.close()
+        rp, col, lab_np = row_ptr.numpy(), col_idx.numpy().view(np.uint32), labels.numpy()
+        if save_csr_path:
+            save_csr(save_csr_path, rp, col, lab_np, max_index)
+    n = int(rp.shape[0]) - 1
+    nnz = int(col.shape[0])
     t_parse = time.perf_counter() - t0
-    log("parsed %d rows, %d nonzeros, largest index %d in %.2f s (%.2f GB/s)"
-        % (n, nnz, max_index, t_parse, size / t_parse / 1e9))
+    if binary is not None:
+        log("mapped %d rows, %d nonzeros, largest index %d from the binary copy" % (n, nnz, max_index))
+    else:
+        log("parsed %d rows, %d nonzeros, largest index %d in %.2f s (%.2f GB/s)"
+            % (n, nnz, max_index, t_parse, size / t_parse / 1e9))
 
     D = universe or (max_index + 1)
     if max_index >= D:
@@ -73,13 +127,11 @@ def run(path: str, prefix: str, k: int, b: int, family_name: str, seed: int, uni
     mh.check_coeffs(coeffs, family)
     params = torch.from_numpy(coeffs.view(np.int64)).to(dev)
 
-    rp = row_ptr.numpy()
-    col = col_idx.numpy()
     batches, max_rows, max_nnz = [], 1, 1
     for lo in range(0, n, batch_rows):
         hi = min(n, lo + batch_rows)
         a, z = int(rp[lo]), int(rp[hi])
-        batches.append((_pinned_copy(rp[lo:hi + 1] - a), _pinned_copy(col[a:z])))
+        batches.append((_pinned_copy(np.asarray(rp[lo:hi + 1]) - a), _pinned_copy(np.asarray(col[a:z]).view(np.int32))))
         max_rows, max_nnz = max(max_rows, hi - lo), max(max_nnz, z - a)
     t1 = time.perf_counter()
     outs = mh.stream_batches(batches, D, k, b, family, params, max_rows, max_nnz) if batches else []
@@ -89,7 +141,7 @@ def run(path: str, prefix: str, k: int, b: int, family_name: str, seed: int, uni
     log("hashed in %.3f s (%.3g evaluations/s, copies included)" % (t_hash, nnz * k / max(t_hash, 1e-9)))
 
     np.save(prefix + ".sig.npy", sig)
-    np.save(prefix + ".labels.npy", labels.numpy())
+    np.save(prefix + ".labels.npy", np.asarray(lab_np, dtype=np.float32))
     meta = {"rows": n, "nonzeros": nnz, "k": k, "b": b, "family": family_name, "D": D, "seed": seed,
             "sig_bytes": sig_bytes, "parse_s": round(t_parse, 3), "hash_s": round(t_hash, 3)}
     if expand:
@@ -119,12 +171,14 @@ def main(argv=None) -> int:
     ap.add_argument("--index-base", type=int, default=1, choices=[0, 1])
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--expand", action="store_true", help="also write the positions of the ones of the 2^b*k expansion")
+    ap.add_argument("--save-csr", default="", help="also write the parsed data as a binary CSR file; such a file is "
+                                                   "accepted as input in place of the text")
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():
         print("preprocess needs a GPU", file=sys.stderr)
         return 2
     meta = run(a.input, a.prefix, a.k, a.b, a.family, a.seed, a.universe, a.batch_rows, a.index_base, a.threads,
-               a.expand)
+               a.expand, save_csr_path=a.save_csr)
     print(json.dumps(meta))
     return 0
 

@@ -46,3 +46,23 @@ def test_file_to_signatures(tmp_path, family_name, universe):
     assert np.array_equal(sig, want)
     assert np.array_equal(np.load(prefix + ".labels.npy"), labels.astype(np.float32))
     assert np.array_equal(np.load(prefix + ".expanded.npy").view(np.uint32), oracle.expand(want, k, b))
+
+
+def test_binary_copy_gives_the_same_signatures(tmp_path):
+    from paper_1205_2958_amd import preprocess
+
+    nnz = np.array([5, 0, 300, 2500, 1, 77], dtype=np.int64)
+    rp = W.row_ptr_from_nnz(nnz)
+    col = W.csr_indices_np(nnz, 1 << 20, seed=9)
+    labels = np.array([1, -1, 1, 1, -1, 1])
+    src = tmp_path / "data.svm"
+    _write_libsvm(src, rp, col, labels)
+    quiet = dict(log=lambda *_: None)
+    m1 = preprocess.run(str(src), str(tmp_path / "a"), 64, 8, "2u", 3, 0, 4, 1, 2, False,
+                        save_csr_path=str(tmp_path / "data.csr"), **quiet)
+    m2 = preprocess.run(str(tmp_path / "data.csr"), str(tmp_path / "b"), 64, 8, "2u", 3, 0, 4, 1, 2, False, **quiet)
+    assert m1["D"] == m2["D"] and m1["nonzeros"] == m2["nonzeros"] == int(rp[-1])
+    assert np.array_equal(np.load(str(tmp_path / "a.sig.npy")), np.load(str(tmp_path / "b.sig.npy")))
+    assert np.array_equal(np.load(str(tmp_path / "b.labels.npy")), labels.astype(np.float32))
+    want = oracle.signatures(rp, col, m2["D"], 64, 8, preprocess.FAMILIES["2u"], W.coefficients(64, preprocess.FAMILIES["2u"], 3))
+    assert np.array_equal(np.load(str(tmp_path / "b.sig.npy")), want)
