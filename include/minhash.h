@@ -181,15 +181,22 @@ int minhash_resemblance_estimates(const uint32_t *counts, const int64_t *f1, con
 
 /* Pass 1: number of rows, of nonzeros, and the largest stored index (so that the
  * caller can choose D > max_index and allocate, e.g., pinned arrays).
+ * share_counts is NULL or host memory for 2*n_threads values: it receives the
+ * rows and nonzeros of each thread's share of the text, which pass 2 takes back
+ * so that it does not have to count again.
  * MINHASH_ERR_DATA for a malformed line or an index below index_base / above 2^32-1+index_base. */
 int minhash_libsvm_count(const char *text, size_t len, int32_t index_base, int32_t n_threads,
-                         int64_t *n_rows, int64_t *nnz, uint32_t *max_index);
+                         int64_t *n_rows, int64_t *nnz, uint32_t *max_index, int64_t *share_counts);
 
 /* Pass 2: fills row_ptr[n_rows+1] (offsets from 0), col_idx[nnz] (order as
  * written in the file) and, if not NULL, labels[n_rows], all host memory of the
- * sizes pass 1 returned (MINHASH_ERR_ARG if they do not match this text). */
+ * sizes pass 1 returned.  share_counts is NULL (the shares are counted again) or
+ * what pass 1 wrote for the same text, len, index_base and n_threads.
+ * MINHASH_ERR_ARG if the sizes or share_counts do not match this text; nothing
+ * is written outside the three arrays in that case either. */
 int minhash_libsvm_parse(const char *text, size_t len, int32_t index_base, int32_t n_threads,
-                         int64_t n_rows, int64_t nnz, int64_t *row_ptr, uint32_t *col_idx, float *labels);
+                         int64_t n_rows, int64_t nnz, const int64_t *share_counts,
+                         int64_t *row_ptr, uint32_t *col_idx, float *labels);
 
 /* Static text for a return code; never NULL. */
 const char *minhash_error_string(int code);

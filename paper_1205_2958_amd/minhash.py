@@ -82,9 +82,9 @@ def lib() -> ctypes.CDLL:
         L.minhash_resemblance_estimates.argtypes = [vp, vp, vp, i64, u64, i32, i32, vp, vp]
         L.minhash_resemblance_estimates.restype = ctypes.c_int
         L.minhash_libsvm_count.argtypes = [vp, sz, i32, i32, ctypes.POINTER(i64), ctypes.POINTER(i64),
-                                           ctypes.POINTER(u32)]
+                                           ctypes.POINTER(ctypes.c_uint32), vp]
         L.minhash_libsvm_count.restype = ctypes.c_int
-        L.minhash_libsvm_parse.argtypes = [vp, sz, i32, i32, i64, i64, vp, vp, vp]
+        L.minhash_libsvm_parse.argtypes = [vp, sz, i32, i32, i64, i64, vp, vp, vp, vp]
         L.minhash_libsvm_parse.restype = ctypes.c_int
         L.minhash_error_string.argtypes = [ctypes.c_int]
         L.minhash_error_string.restype = ctypes.c_char_p
@@ -251,15 +251,17 @@ def parse_libsvm(buf, index_base: int = 1, n_threads: int = 16, pin_memory: bool
     view = np.frombuffer(buf, dtype=np.uint8)
     ptr = view.ctypes.data if view.size else 0
     n_rows, nnz, mx = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_uint32(0)
+    n_threads = max(1, int(n_threads))
+    shares = np.zeros(2 * n_threads, dtype=np.int64)                   # per-thread counts, handed from pass 1 to pass 2
     rc = lib().minhash_libsvm_count(ptr, view.size, index_base, n_threads, ctypes.byref(n_rows), ctypes.byref(nnz),
-                                    ctypes.byref(mx))
+                                    ctypes.byref(mx), shares.ctypes.data)
     if rc != 0:
         _raise(rc)
     row_ptr = torch.empty(n_rows.value + 1, dtype=torch.int64, pin_memory=pin_memory)
     col_idx = torch.empty(nnz.value, dtype=torch.int32, pin_memory=pin_memory)
     lab = torch.empty(n_rows.value, dtype=torch.float32) if labels else None
-    rc = lib().minhash_libsvm_parse(ptr, view.size, index_base, n_threads, n_rows.value, nnz.value, row_ptr.data_ptr(),
-                                    col_idx.data_ptr(), lab.data_ptr() if labels else 0)
+    rc = lib().minhash_libsvm_parse(ptr, view.size, index_base, n_threads, n_rows.value, nnz.value, shares.ctypes.data,
+                                    row_ptr.data_ptr(), col_idx.data_ptr(), lab.data_ptr() if labels else 0)
     if rc != 0:
         _raise(rc)
     return row_ptr, col_idx, lab, int(mx.value)
