@@ -174,6 +174,33 @@ MH_HD uint32_t hash_compl_2u31(const Fn2U31& f, uint32_t t2, uint32_t mask)
     return m31_complement(fold_2u31(f, t2), mask);
 }
 
+// Power-of-two D = 2^s again, one instruction shorter: evaluate the NEGATED
+// polynomial.  With c1' = -c1 mod p and the constant p - c0 in [1, p] the folded
+// value x lies in [1, 2p] and is congruent to -X, so its representative in [1, p]
+// is p - (X mod p), whose low s bits are the complement of the hashed location
+// (2^31 - 1 - r = ~r modulo 2^s).  That representative is x for x <= p and
+// x - p = x + 1 - 2^31 otherwise, i.e. x + (x >> 31) modulo 2^s.  Shifting left by
+// 32 - s instead of masking keeps the order of the low s bits, and shift, add and
+// shift fuse into a logical shift and one add-then-shift instruction.  The running
+// MAXIMUM of these keys gives the minimum location: mask - (max >> (32 - s)).
+// For s = 0 the shift count is held at 31 and the final "& mask" clears the bit.
+MH_HD Fn2U31 prep_2u31_neg(uint64_t c0, uint64_t c1)
+{
+    Fn2U31 f;
+    f.c1 = c1 ? (uint32_t)(P31 - c1) : 0u;
+    f.add = 2 * ((uint64_t)P31 - c0);
+    return f;
+}
+MH_HD uint32_t neg_key_shift(uint32_t mask)          // 32 - s for mask = 2^s - 1, at most 31
+{
+    uint32_t s = 0;
+    while (s < 32 && ((mask >> s) & 1u)) ++s;
+    return s == 0 ? 31u : 32u - s;
+}
+MH_HD uint32_t m31_neg_key(uint32_t x, uint32_t shift) { return (x + (x >> 31)) << shift; }
+MH_HD uint32_t key_neg_2u31(const Fn2U31& f, uint32_t t2, uint32_t shift) { return m31_neg_key(fold_2u31(f, t2), shift); }
+MH_HD uint32_t finish_neg_key(uint32_t key, uint32_t shift, uint32_t mask) { return mask - ((key >> shift) & mask); }
+
 // ---------------------------------------------------------------- 4U, p = 2^31 - 1
 // K31 p is added to the constant term so that the centred sum stays positive:
 // three products of magnitude at most ((p-1)/2)^2 need K31 p >= 3 ((p-1)/2)^2.
@@ -235,6 +262,19 @@ MH_HD uint32_t hash_compl_4u31(const Fn4U31& f, const Pow4U31& w, uint32_t mask)
 {
     return m31_complement(fold_4u31(f, w), mask);
 }
+// Power-of-two D, negated cubic (see prep_2u31_neg): the centred coefficients change
+// sign (their range is symmetric) and the constant becomes p - c0 in [1, p], so the
+// folded value is congruent to -X and lies in [1, 2^32 - 2] as before.
+MH_HD Fn4U31 prep_4u31_neg(uint64_t c0, uint64_t c1, uint64_t c2, uint64_t c3)
+{
+    Fn4U31 f;
+    f.c1 = -m31_centre((uint32_t)c1);
+    f.c2 = -m31_centre((uint32_t)c2);
+    f.c3 = -m31_centre((uint32_t)c3);
+    f.add = 2 * (((uint64_t)P31 - c0) + K31 * (uint64_t)P31);
+    return f;
+}
+MH_HD uint32_t key_neg_4u31(const Fn4U31& f, const Pow4U31& w, uint32_t shift) { return m31_neg_key(fold_4u31(f, w), shift); }
 
 // ---------------------------------------------------------------- 2U, p = 2^61 - 1
 // W = c1 t + c0 + 1 with c1 = 2^32 e1 + e0, t < 2^31:
