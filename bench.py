@@ -29,31 +29,34 @@ if ROOT not in sys.path:
 
 from paper_1205_2958_amd import workloads as W  # noqa: E402
 
-# Issue model of one hash evaluation: (full, simple) instruction counts per evaluation.
-# A SIMD issues one 64-lane instruction of the full-issue class (multiply-add, multiply-high,
-# three-operand ops, min/max, add with carry, funnel shift) per 4 clocks: 16 lanes/clk, the rate
-# behind the published fp64 vector peak.  The simple two-operand integer instructions on vector
-# registers (add, sub, and, or, xor, shift right, move) issue at twice that rate, the rate behind
-# the published fp32 peak, and the simple instructions of one wavefront issue alongside the
-# full-issue instructions of another.  A kernel therefore needs at least
-#     max(full, (full + simple) / 2)
+# Issue model of one hash evaluation: (multiply, full, simple) instruction counts per evaluation.
+# A SIMD issues one 64-lane instruction of the full-issue class (three-operand ops, min/max, add
+# with carry, funnel shift, shift left) per 4 clocks: 16 lanes/clk, the rate behind the published
+# fp64 vector peak.  The simple two-operand integer instructions on vector registers (add, sub,
+# and, or, xor, shift right, move) issue at twice that rate, the rate behind the published fp32
+# peak, and a simple instruction of one wavefront issues beside a full-issue instruction of
+# another.  The 32-bit multiplies (v_mad_u64_u32, v_mad_i64_i32, v_mul_hi_u32) take a full slot and
+# let nothing issue beside them (measured: loops of one such instruction and n simple ones take
+# the sum of their separate times, loops with a three-operand instruction in its place do not).
+# A kernel therefore needs at least
+#     multiply + max(full, (full + simple) / 2)
 # issue slots per evaluation, one slot = one 64-lane instruction at 16 lanes/clk/SIMD.
 ISSUE_MIX = {
-    W.FAMILY_2U_M31: (1.0 + 0.5, 5.0),         # mad, half a max3; shr,add,ashr,sub,and
-    W.FAMILY_4U_M31: (3.0 + 1.0 + 0.5, 6.0),   # 3 mad, add3, half a max3; shr,and,shr,ashr,sub,and
-    W.FAMILY_2U_M61: (2.0 + 1.0 + 3.0 + 0.5, 3.0),   # 2 mad, funnel shift, add + 2 add-with-carry, half a min3; mov,or,and
-    W.FAMILY_2U_MS32: (1.0 + 0.5, 0.0),        # mad, half a min3 (mask or shift once per row)
+    W.FAMILY_2U_M31: (1.0, 1.0 + 0.5, 3.0),         # mad | add-then-shift, half a max3 | shr,add,shr
+    W.FAMILY_4U_M31: (3.0, 1.0 + 1.0 + 0.5, 4.0),   # 3 mad | add3, add-then-shift, half a max3 | shr,and,shr,shr
+    W.FAMILY_2U_M61: (2.0, 1.0 + 3.0 + 0.5, 3.0),   # 2 mad | funnel shift, add + 2 add-with-carry, half a min3 | mov,or,and
+    W.FAMILY_2U_MS32: (1.0, 0.5, 0.0),              # mad | half a min3 (mask or shift once per row)
 }
 # other D (--universe): exact multiply-high quotient appended
 ISSUE_MIX_OTHER_D = {
-    W.FAMILY_2U_M31: (1.0 + 1.0 + 1.0 + 1.0 + 0.5, 4.0),     # mad, min, mulhi, mad, half a min3; shr,add,sub,shr
-    W.FAMILY_4U_M31: (3.0 + 1.0 + 1.0 + 1.0 + 1.0 + 0.5, 6.0),   # 3 mad, add3, min, mulhi, mad, half a min3; shr,and,shr, add,xor, shr
+    W.FAMILY_2U_M31: (3.0, 1.0 + 0.5, 4.0),         # mad, mulhi, mad | min, half a min3 | shr,add,sub,shr
+    W.FAMILY_4U_M31: (5.0, 1.0 + 1.0 + 0.5, 6.0),   # 3 mad, mulhi, mad | add3, min, half a min3 | shr,and,shr,add,xor,shr
 }
 
 
 def issue_slots(mix):
-    full, simple = mix
-    return max(full, (full + simple) / 2.0)
+    mul, full, simple = mix
+    return mul + max(full, (full + simple) / 2.0)
 
 
 ALU_PEAK_SLOTS = 256 * 4 * 16 * 2.4e9                      # 39.3e12 lane-slots/s
@@ -61,7 +64,7 @@ HBM_PEAK = 8.0e12
 # HBM bytes per launch of the dominant kernel on the full workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for a plain 1 GiB streaming kernel
 # (profiles/mh_hash_kernel_2u_m31__large_2u.txt, profiles/mh_perm_kernel__perm_table.txt).
-MEASURED_TRAFFIC_BYTES = {"large_2u": 6.064e9, "perm_table": 1.1654e12}
+MEASURED_TRAFFIC_BYTES = {"large_2u": 6.083e9, "perm_table": 1.1654e12}
 
 
 def _oracle_worker(args):
@@ -395,9 +398,10 @@ def main() -> int:
         slots = issue_slots(mix)
         roof = {"bound": "alu", "achieved": evals * slots / (k_ms * 1e-3) / 1e12, "peak": ALU_PEAK_SLOTS / 1e12,
                 "unit": "TOP/s", "traffic": None, "kernel": "mh_hash_kernel", "kernel_ms": k_ms,
-                "model": "%.2f issue slots per hash evaluation = max(full, (full + simple) / 2) with %.1f full-issue and "
-                         "%.1f simple instructions; peak = 256 CU x 4 SIMD x 16 lanes x 2.4 GHz full-issue lane-slots/s, "
-                         "simple instructions issuing at twice that rate alongside them" % (slots, mix[0], mix[1])}
+                "model": "%.2f issue slots per hash evaluation = multiply + max(full, (full + simple) / 2) with %.1f "
+                         "multiplies (nothing issues beside them), %.1f other full-issue and %.1f simple instructions; "
+                         "peak = 256 CU x 4 SIMD x 16 lanes x 2.4 GHz full-issue lane-slots/s, simple instructions "
+                         "issuing at twice that rate and beside full-issue ones" % (slots, mix[0], mix[1], mix[2])}
     roof["frac"] = roof["achieved"] / roof["peak"]
     if not args.rows and not args.universe:
         roof["traffic"] = MEASURED_TRAFFIC_BYTES.get(w.name)

@@ -260,9 +260,9 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
 // raise it for their runs of full-issue instructions (multiply-adds, three-operand
 // adds and extrema, carry chains) and lower it for their runs of simple ones.  A
 // SIMD issues the simple instructions of two wavefronts together, and a simple
-// instruction alongside another wavefront's full-issue one, so the issue port
-// should go to whoever has full-issue work while simple instructions fill in
-// around it.  2U: 78-82 ms without, 67.5 ms with; the reverse assignment takes
+// instruction alongside another wavefront's full-issue one (not alongside a
+// 32-bit multiply, which issues alone), so the issue port should go to whoever
+// has full-issue work while simple instructions fill in around it.  2U: 78-82 ms without, 67.5 ms with; the reverse assignment takes
 // 96 ms; the level (1..3) makes no difference.  Without priorities the same loop
 // ran anywhere between 78 and 87 ms depending on where the compiler placed it
 // and on idle cycles inserted into an iteration; with them neither matters.
