@@ -343,6 +343,38 @@ MH_HD uint32_t hash_2u61(const Fn2U61& f, uint32_t t, const ModD& md, uint64_t D
     return reduce61_mod_d(residue_wide_2u61(f, t), md, D);
 }
 
+// Power-of-two D <= 2^31, negated form with a guard (compare prep_2u31_neg).  With
+// c1' = -c1 mod p and the constant p - c0 in [1, p], V = c1' t + (p - c0) is congruent
+// to -X and the folded x = y + (H >> 29) lies in [1, 2^61 + 2^31 + 4).  As long as
+// bit 61 of x is clear, x itself is the representative p - (X mod p) in [1, p], whose
+// low s bits are the complement of the hashed location: the key is
+// (L_lo + (H >> 29)) & mask, one add and one and, no carries.  Bit 61 can only be set
+// if bits 32..60 of the bracket, i.e. the low 29 bits of H, are all ones and the
+// low-word addition carries into them.  `guard` = H_lo | 0xE0000000 is all ones in
+// exactly the first case: an evaluation whose guard is not 0xFFFFFFFF has an exact key;
+// about one evaluation in 2^29 has such a guard, and the caller then falls back on
+// the exact path (hash_2u61) for the data at hand.
+MH_HD Fn2U61 prep_2u61_neg(uint64_t c0, uint64_t c1)
+{
+    const uint64_t n = c1 ? P61 - c1 : 0;
+    Fn2U61 f;
+    f.e0 = (uint32_t)n;
+    f.e1 = (uint32_t)(n >> 32);
+    f.add = P61 - c0;
+    return f;
+}
+struct GuardedKey61 { uint32_t key, guard; };
+MH_HD GuardedKey61 key_neg_2u61(const Fn2U61& f, uint32_t t, uint32_t mask)   // t < 2^31
+{
+    const uint64_t L = (uint64_t)f.e0 * t + f.add;
+    const uint64_t H = (uint64_t)f.e1 * t + (L >> 32);
+    GuardedKey61 k;
+    k.key = ((uint32_t)L + (uint32_t)(H >> 29)) & mask;
+    k.guard = (uint32_t)H | 0xE0000000u;
+    return k;
+}
+constexpr uint32_t GUARD61_HIT = 0xFFFFFFFFu;
+
 // ---------------------------------------------------------------- 4U, p = 2^61-1 (eq. eqn_4U with the prime of Section 3.4's last paragraph)
 // Horner form: three steps acc <- acc t + c, each one 62-bit x 32-bit product
 // built from two widening multiply-adds (the low word of the addend joins the low

@@ -52,6 +52,7 @@ constexpr int WAVES_PER_BLOCK = 4;
 constexpr int BLOCK = WAVE * WAVES_PER_BLOCK;
 constexpr int TILE = 256;              // nonzeros staged per wavefront per step (4 per lane)
 constexpr int HASH_FPL = 8;            // hash functions per lane
+constexpr int HASH_ACC = HASH_FPL + 2;     // the running extrema of a lane's functions plus two words a policy may use as guards
 constexpr int HASH_FTILE = WAVE * HASH_FPL;   // 512 functions per wavefront pass
 constexpr int PERM_FPL = 4;            // permutations per lane (one 16-byte load)
 constexpr int PERM_FTILE = WAVE * PERM_FPL;   // 256
@@ -454,7 +455,7 @@ __device__ __forceinline__ void wave_pack_store(const KArgs& a, const uint32_t* 
 
 // ------------------------------------------------------------------ hash-family policies
 template <class Pol, int NF>
-__device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
+__device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC],
                                              const uint32_t* wa, const uint32_t* wb, const ModDV& md, uint64_t D);
 
 // A policy evaluates one function on one staged nonzero and returns a value that
@@ -468,6 +469,7 @@ struct Pol2U31 {
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = POW2;    // the running maximum is a key shifted left by md.kshift
     static constexpr bool SHIFT_END = false;
+    static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
@@ -482,7 +484,7 @@ struct Pol2U31 {
         return hash_2u31_raw(f, w[0], md);
     }
     template <int NF>
-    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D);
     static constexpr int DEG = 2;
 };
@@ -494,6 +496,7 @@ struct Pol4U31 {
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = POW2;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn4U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
@@ -514,7 +517,7 @@ struct Pol4U31 {
         return hash_4u31_np2(f, p, md);
     }
     template <int NF>
-    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D);
     static constexpr int DEG = 4;
 };
@@ -526,16 +529,33 @@ struct Fn2U61V : Fn2U61 {
     mutable u32x2 hz;
 };
 
+// For power-of-two D <= 2^31 the fast path evaluates the negated function without
+// carries (key_neg_2u61 of mh_arith.h) and keeps the running maximum of the keys
+// and of the guard words; an item whose guard was hit, about one evaluation in
+// 2^29, is evaluated again with the exact arithmetic (GUARDED, see the kernel).
 template <bool POW2>
 struct Pol2U61 {
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = POW2 ? 4 : 5;
-    static constexpr bool TRACK_MAX = false;
-    static constexpr bool SHIFTED_KEY = false;
+    static constexpr bool TRACK_MAX = POW2;
+    static constexpr bool SHIFTED_KEY = POW2;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool GUARDED = POW2;
     static constexpr bool VARIABLE_NF = POW2;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
+    {
+        Fn f;
+        if constexpr (POW2) {
+            // an unused slot takes a constant whose guard word is not all ones (c0 = c1 = 0 would hit it every time)
+            static_cast<Fn2U61&>(f) = valid ? prep_2u61_neg(c[0], c[1]) : prep_2u61_neg(1ull << 60, 0);
+            f.hz = u32x2{0u, 0u};
+        } else {
+            static_cast<Fn2U61&>(f) = valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
+        }
+        return f;
+    }
+    static __device__ __forceinline__ Fn load_exact(const uint64_t* c, bool valid, const KArgs&)
     {
         Fn f;
         static_cast<Fn2U61&>(f) = valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
@@ -543,13 +563,26 @@ struct Pol2U61 {
         return f;
     }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
+    // the exact hashed location (the fast path of POW2 does not come through here)
     static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t D)
     {
         return hash_2u61<POW2>(f, w[0], md, D);
     }
+    static __device__ __forceinline__ bool guard_hit(const uint32_t (&m)[HASH_ACC])
+    {
+        return m[HASH_FPL] == GUARD61_HIT || m[HASH_FPL + 1] == GUARD61_HIT;
+    }
     template <int NF>
-    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D);
+    // running minimum of the exact locations, schedule left to the compiler
+    template <int NF>
+    static __device__ __forceinline__ void pair_exact(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                      const uint32_t* wb, const ModDV& md, uint64_t D)
+    {
+#pragma unroll
+        for (int r = 0; r < NF; ++r) m[r] = umin3(m[r], key(fn[r], wa, md, D), key(fn[r], wb, md, D));
+    }
     static constexpr int DEG = 2;
 };
 
@@ -562,6 +595,7 @@ struct Pol4U61 {
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = false;
     using Fn = Fn4U61;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
@@ -574,7 +608,7 @@ struct Pol4U61 {
         return hash_4u61<POW2>(f, w[0], md, D);
     }
     template <int NF>
-    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D)
     {
         pair_generic<Pol4U61<POW2>, NF>(fn, m, wa, wb, md, D);
@@ -586,7 +620,7 @@ struct Pol4U61 {
 // The unit of the hot loop: fold the 16 evaluations of two staged nonzeros into
 // the 8 running extrema.  The generic form leaves the schedule to the compiler.
 template <class Pol, int NF>
-__device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
+__device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC],
                                              const uint32_t* wa, const uint32_t* wb, const ModDV& md, uint64_t D)
 {
 #pragma unroll
@@ -640,7 +674,7 @@ __device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
     for (int g = 0; g < NF; ++g) asm volatile("v_add_lshl_u32 %0, %0, %1, %2" : "+v"(x[g]) : "v"(c[g]), "s"(kshift));
 }
 template <int NF>
-__device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], uint32_t ta,
+__device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta,
                                                uint32_t tb, uint32_t kshift)
 {
     uint32_t xa[HASH_FPL], xb[HASH_FPL];
@@ -690,7 +724,7 @@ __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
 }
 
 template <int NF>
-__device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL],
+__device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC],
                                                const uint32_t* wa, const uint32_t* wb, uint32_t kshift, uint32_t p31)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
@@ -737,7 +771,7 @@ __device__ __forceinline__ void half_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], u32x
     for (int g = 0; g < NF; ++g) MH_MAD_ACC(u64_u32, p[g], x[g], md.negD);
 }
 template <int NF>
-__device__ __forceinline__ void pair_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], uint32_t ta,
+__device__ __forceinline__ void pair_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta,
                                               uint32_t tb, const ModDV& md)
 {
     u32x2 pa[HASH_FPL], pb[HASH_FPL];
@@ -794,7 +828,7 @@ __device__ __forceinline__ void half_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], u32x
 }
 
 template <int NF>
-__device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+__device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                               const uint32_t* wb, const ModDV& md)
 {
     u32x2 ya[HASH_FPL], yb[HASH_FPL];
@@ -805,18 +839,17 @@ __device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g].x), "v"(yb[g].x));
 }
 
-// 2U, p = 2^61-1, power-of-two D <= 2^31: residue_lo_2u61 of mh_arith.h, eight
-// functions on one nonzero, stage by stage.  The two carries travel in scalar
-// register pairs: c1 out of x_lo = L_lo + (H >> 29), c2 out of
-// (H_lo | 0xE0000000) + c1, which is set exactly when bit 61 of x is; the last
-// add-with-carry forms x_lo + c2 - 1.
+// 2U, p = 2^61-1, power-of-two D <= 2^31: key_neg_2u61 of mh_arith.h, eight
+// functions on one nonzero, stage by stage: two multiply-adds, the funnel shift
+// H >> 29, one add and one and for the key, one or for the guard word.  The guard
+// words go into two running maxima (m[HASH_FPL], m[HASH_FPL + 1]) right away, two
+// per three-operand maximum; the keys leave in y.
 template <int NF>
-__device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t t,
-                                               const ModDV& md)
+__device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t (&m)[HASH_ACC],
+                                               uint32_t t, const ModDV& md)
 {
     u32x2 L[HASH_FPL], H[HASH_FPL];
-    uint32_t s[HASH_FPL], o[HASH_FPL], r;
-    uint64_t c1[HASH_FPL], c2[HASH_FPL], c3;
+    uint32_t s[HASH_FPL], z[HASH_FPL + 1], r;
     issue_priority<1>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, L[g], fn[g].e0, t, fn[g].add);
@@ -831,25 +864,16 @@ __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], ui
     for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, H[g], fn[g].e1, t, fn[g].hz);
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_lshl_u32 %0, %1, %2, %3" : "=v"(y[g]) : "v"(L[g].x), "v"(s[g]), "s"(md.kshift));
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_or_b32 %0, %1, %2" : "=v"(o[g]) : "v"(H[g].x), "v"(md.top3));
+    for (int g = 0; g < NF; ++g) asm volatile("v_or_b32 %0, %1, %2" : "=v"(z[g]) : "v"(H[g].x), "v"(md.top3));
     issue_priority<1>();
+    if (NF & 1) z[NF] = z[NF - 1];
 #pragma unroll
-    for (int g = 0; g < NF; ++g)
-        asm volatile("v_add_co_u32 %0, %1, %2, %3" : "=v"(s[g]), "=s"(c1[g]) : "v"(L[g].x), "v"(s[g]));
-    // the two add-with-carry stages run two evaluations apart, so that no statement
-    // reads what its predecessor wrote
-#pragma unroll
-    for (int g = 0; g < NF + 2; ++g) {
-        if (g < NF)
-            asm volatile("v_addc_co_u32 %0, %1, %2, 0, %3" : "=v"(o[g]), "=s"(c2[g]) : "v"(o[g]), "s"(c1[g]));
-        if (g >= 2)
-            asm volatile("v_addc_co_u32 %0, %1, %2, -1, %3" : "=v"(y[g - 2]), "=s"(c3) : "v"(s[g - 2]), "s"(c2[g - 2]));
-    }
-    issue_priority<0>();
-#pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %0, %1" : "+v"(y[g]) : "v"(md.mask));
+    for (int g = 0; g < NF; g += 2)
+        asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[HASH_FPL + ((g >> 1) & 1)]) : "v"(z[g]), "v"(z[g + 1]));
 }
 
 // Ablation: the definition evaluated with the % operator on runtime moduli (Horner
@@ -862,6 +886,7 @@ struct PolGenericMod {
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = false;
     static constexpr int DEG = DEGREE;
     struct Fn { uint64_t c[DEGREE]; uint64_t p; };
@@ -883,7 +908,7 @@ struct PolGenericMod {
         return (uint32_t)(acc % D);
     }
     template <int NF>
-    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D)
     {
         pair_generic<PolGenericMod<DEGREE>, NF>(fn, m, wa, wb, md, D);
@@ -900,6 +925,7 @@ struct Pol2UMS32 {
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
     static constexpr bool SHIFT_END = true;
+    static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn2UMS32;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
@@ -912,7 +938,7 @@ struct Pol2UMS32 {
         return key_2ums32(f, w[0]);
     }
     template <int NF>
-    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV&, uint64_t)
     {
         uint64_t pa[HASH_FPL], pb[HASH_FPL];
@@ -931,14 +957,14 @@ struct Pol2UMS32 {
 
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol2U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+__device__ __forceinline__ void Pol2U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                     const uint32_t* wb, const ModDV& md, uint64_t)
 {
     pair_2u31_pow2<NF>(fn, m, wa[0], wb[0], md.kshift);
 }
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol2U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+__device__ __forceinline__ void Pol2U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t)
 {
     pair_2u31_np2<NF>(fn, m, wa[0], wb[0], md);
@@ -946,14 +972,14 @@ __device__ __forceinline__ void Pol2U31<false>::pair(const Fn (&fn)[HASH_FPL], u
 
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol4U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+__device__ __forceinline__ void Pol4U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                     const uint32_t* wb, const ModDV& md, uint64_t)
 {
     pair_4u31_pow2<NF>(fn, m, wa, wb, md.kshift, md.p31);
 }
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+__device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t)
 {
     pair_4u31_np2<NF>(fn, m, wa, wb, md);
@@ -961,19 +987,19 @@ __device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], u
 
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol2U61<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+__device__ __forceinline__ void Pol2U61<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                     const uint32_t* wb, const ModDV& md, uint64_t)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
-    half_2u61_pow2<NF>(fn, ya, wa[0], md);
-    half_2u61_pow2<NF>(fn, yb, wb[0], md);
+    half_2u61_pow2<NF>(fn, ya, m, wa[0], md);
+    half_2u61_pow2<NF>(fn, yb, m, wb[0], md);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
-        asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
+        asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
 }
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol2U61<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_FPL], const uint32_t* wa,
+__device__ __forceinline__ void Pol2U61<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t D)
 {
     pair_generic<Pol2U61<false>, NF>(fn, m, wa, wb, md, D);
@@ -1042,58 +1068,86 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
         const int64_t begin = it.begin;
         const uint32_t len = it.len;
 
-        uint32_t m[HASH_FPL];
+        // A GUARDED policy computes keys that are exact unless a guard word says otherwise
+        // (rarely); then the item is evaluated once more with the policy's exact arithmetic.
+        uint32_t m[HASH_ACC];
+        bool exact = false;     // wave-uniform
+        for (;;) {
 #pragma unroll
-        for (int r = 0; r < NF; ++r) m[r] = Pol::TRACK_MAX ? 0u : EMPTY_MIN;
+            for (int r = 0; r < NF; ++r) m[r] = (Pol::TRACK_MAX && !exact) ? 0u : EMPTY_MIN;
+            m[HASH_FPL] = m[HASH_FPL + 1] = 0u;
 
-        if (len > 0) {
-            uint32_t pad = a.col_idx[begin];
-            uint32_t regs[4];
-            load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
-            for (uint32_t off = 0; off < len; off += TILE) {
-                // stage: pre-compute what depends on t alone, one nonzero per lane and register
+            if (len > 0) {
+                uint32_t pad = a.col_idx[begin];
+                uint32_t regs[4];
+                load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
+                for (uint32_t off = 0; off < len; off += TILE) {
+                    // stage: pre-compute what depends on t alone, one nonzero per lane and register
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    uint32_t t = regs[q];
-                    if (a.validate && (uint64_t)t >= a.D) {
-                        atomicOr(&a.hdr->status, 2u);
-                        t = 0;
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t t = regs[q];
+                        if (a.validate && (uint64_t)t >= a.D) {
+                            atomicOr(&a.hdr->status, 2u);
+                            t = 0;
+                        }
+                        uint32_t w[Pol::NW];
+                        Pol::stage(t, w);
+#pragma unroll
+                        for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
                     }
-                    uint32_t w[Pol::NW];
-                    Pol::stage(t, w);
-#pragma unroll
-                    for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
-                }
-                wave_sync_lds();
-                if (off + TILE < len) load_tile(a.col_idx, begin, len, off + TILE, pad, lane, regs);
+                    wave_sync_lds();
+                    if (off + TILE < len) load_tile(a.col_idx, begin, len, off + TILE, pad, lane, regs);
 
-                const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
-                const int n_steps = (int)((in_tile + 4u * n_slices - 1u) / (4u * n_slices));
-                for (int s = 0; s < n_steps; ++s) {
-                    const int e = 4 * (s * n_slices + slice);
-                    uint32_t w[4][Pol::NW];
+                    const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
+                    const int n_steps = (int)((in_tile + 4u * n_slices - 1u) / (4u * n_slices));
+                    for (int s = 0; s < n_steps; ++s) {
+                        const int e = 4 * (s * n_slices + slice);
+                        uint32_t w[4][Pol::NW];
 #pragma unroll
-                    for (int i = 0; i < Pol::NW; ++i) {
-                        uint4 v = *reinterpret_cast<const uint4*>(&tile[i][e]);
-                        w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
+                        for (int i = 0; i < Pol::NW; ++i) {
+                            uint4 v = *reinterpret_cast<const uint4*>(&tile[i][e]);
+                            w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
+                        }
+                        if constexpr (Pol::GUARDED) {
+                            if (exact) {
+                                Pol::template pair_exact<NF>(fn, m, w[0], w[1], md, a.D);
+                                Pol::template pair_exact<NF>(fn, m, w[2], w[3], md, a.D);
+                                continue;
+                            }
+                        }
+                        Pol::template pair<NF>(fn, m, w[0], w[1], md, a.D);
+                        Pol::template pair<NF>(fn, m, w[2], w[3], md, a.D);
                     }
-                    Pol::template pair<NF>(fn, m, w[0], w[1], md, a.D);
-                    Pol::template pair<NF>(fn, m, w[2], w[3], md, a.D);
+                    wave_sync_lds();
                 }
-                wave_sync_lds();
-            }
-            if (Pol::TRACK_MAX) {      // back from complements to the minimum location
+                if (Pol::TRACK_MAX && !exact) {      // back from complements to the minimum location
 #pragma unroll
-                for (int r = 0; r < NF; ++r)
-                    m[r] = Pol::SHIFTED_KEY ? finish_neg_key(m[r], md.kshift, md.mask) : md.mask - m[r];
-            }
-            if (Pol::SHIFT_END) {      // from the order-preserving key back to the hashed location
+                    for (int r = 0; r < NF; ++r)
+                        m[r] = Pol::SHIFTED_KEY ? finish_neg_key(m[r], md.kshift, md.mask) : md.mask - m[r];
+                }
+                if (Pol::SHIFT_END) {      // from the order-preserving key back to the hashed location
 #pragma unroll
-                for (int r = 0; r < NF; ++r) m[r] = finish_2ums32(m[r], a.md.M);
-            }
-        } else if (Pol::TRACK_MAX) {
+                    for (int r = 0; r < NF; ++r) m[r] = finish_2ums32(m[r], a.md.M);
+                }
+            } else if (Pol::TRACK_MAX) {
 #pragma unroll
-            for (int r = 0; r < NF; ++r) m[r] = EMPTY_MIN;
+                for (int r = 0; r < NF; ++r) m[r] = EMPTY_MIN;
+            }
+            if constexpr (Pol::GUARDED) {
+                if (!exact && __builtin_amdgcn_ballot_w64(Pol::guard_hit(m)) != 0ull) {
+                    const uint64_t* coeffs = static_cast<const uint64_t*>(a.params);
+#pragma unroll
+                    for (int r = 0; r < NF; ++r) {
+                        int j = j_base + r;
+                        bool valid = j < a.k;
+                        fn[r] = Pol::load_exact(coeffs + (size_t)(valid ? j : 0) * Pol::DEG, valid, a);
+                    }
+                    cur_ftile = -1;     // the next item loads the fast form again
+                    exact = true;
+                    continue;
+                }
+            }
+            break;
         }
         // merge the slices of nonzeros (lanes that share fl)
         for (int d = fl_lanes; d < WAVE; d <<= 1) {

@@ -24,7 +24,7 @@ static uint64_t ref_poly(const uint64_t* c, int deg, uint64_t p, uint64_t D, uin
     return (uint64_t)(acc % D);
 }
 
-static long checks = 0;
+static long checks = 0, guard_hits = 0, guard_saves = 0;
 #define FAIL(...) do { printf("MISMATCH " __VA_ARGS__); printf("\n"); exit(1); } while (0)
 
 static void check31(uint64_t D, const uint64_t* c, uint32_t t)
@@ -81,6 +81,16 @@ static void check61(uint64_t D, const uint64_t* c, uint32_t t)
     if (g != want) FAIL("2U61 D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
                         (unsigned long long)c[0], (unsigned long long)c[1], g, (unsigned long long)want);
     ++checks;
+    if (md.pow2 && D <= (1ull << 31)) {
+        // the guarded key of the negated form: exact whenever the guard is not hit
+        GuardedKey61 gk = key_neg_2u61(prep_2u61_neg(c[0], c[1]), t, md.mask);
+        if (gk.guard != GUARD61_HIT && md.mask - gk.key != want)
+            FAIL("2U61 guarded key D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
+                 (unsigned long long)c[0], (unsigned long long)c[1], md.mask - gk.key, (unsigned long long)want);
+        if (gk.guard == GUARD61_HIT) ++guard_hits;
+        if (gk.guard == GUARD61_HIT && md.mask - gk.key != want) ++guard_saves;
+        ++checks;
+    }
     // 4U with the same prime: Horner form against the power-sum definition
     uint64_t want4 = ref_poly(c, 4, P61, D, t);
     Fn4U61 f4 = prep_4u61(c[0], c[1], c[2], c[3]);
@@ -155,6 +165,37 @@ int main()
             uint32_t t = (uint32_t)(rnd() % D);
             check61(D, c, t);
         }
+    }
+    // Guarded 2U-M61 key: coefficients built so that the negated form's H has its low 29 bits all
+    // ones (the only case in which the unguarded key can be wrong), with the low-word sum on
+    // either side of a carry.  The guard must fire on every one of them, and some must be cases
+    // in which the plain key is indeed wrong.
+    {
+        const long hits_before = guard_hits, saves_before = guard_saves;
+        int built = 0;
+        for (uint64_t D : {1ull << 30, 1ull << 31, 1ull << 24, 1ull << 1}) {
+            for (int i = 0; i < 20000; ++i) {
+                const uint32_t t = (uint32_t)(rnd() % D);
+                if (t == 0) continue;
+                const uint64_t n = 1 + rnd() % (p61 - 1);                    // the negated linear coefficient, in [1, p)
+                const uint32_t e0 = (uint32_t)n, e1 = (uint32_t)(n >> 32);
+                uint64_t add = 1 + rnd() % p61;                                 // p - c0, in [1, p]
+                if (i % 3 == 0) add = (add & ~0xFFFFFFFFull) | (0xFFFFFFFFull - (rnd() % 5));   // low word near the top
+                uint64_t L = (uint64_t)e0 * t + add;
+                uint64_t H = (uint64_t)e1 * t + (L >> 32);
+                const uint64_t d = ((1ull << 29) - 1 - H) & ((1ull << 29) - 1);  // raise H by d: add d 2^32 to L
+                uint64_t add2 = add + (d << 32);
+                if (add2 > p61) { if (add < (((1ull << 29) - d) << 32) + 1) continue; add2 = add - (((1ull << 29) - d) << 32); }
+                if (add2 < 1 || add2 > p61) continue;
+                uint64_t c[4] = {p61 - add2, p61 - n, rnd() % p61, rnd() % p61};
+                Fn2U61 f = prep_2u61_neg(c[0], c[1]);
+                if (key_neg_2u61(f, t, (uint32_t)(D - 1)).guard != GUARD61_HIT) FAIL("engineered guard case not built");
+                check61(D, c, t);
+                ++built;
+            }
+        }
+        if (built < 10000 || guard_hits - hits_before != built) FAIL("guarded key: %d built, %ld hits", built, guard_hits - hits_before);
+        if (guard_saves - saves_before < 100) FAIL("guarded key: only %ld engineered cases needed the guard", guard_saves - saves_before);
     }
     // multiply-shift 2U (Section 3.3): ((c0 + c1 t) mod 2^32) mod 2^s, lowest or highest s bits
     for (int sbits = 0; sbits <= 32; ++sbits) {

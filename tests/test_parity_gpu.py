@@ -229,12 +229,16 @@ def test_seeded_random_configurations(seed):
 
 
 def test_m61_fold_carries_engineered():
-    """Coefficients chosen so that W = c1 t + c0 + 1 has bits 32..60 all ones (or all but
-    one) and the fold's low-word addition lands just below, at and above a carry: the
-    cases in which bit 61 of the folded value is set, which random inputs never reach."""
+    """Coefficients chosen so that the 93-bit value behind an evaluation has bits 32..60 all
+    ones (or all but one) and the fold's low-word addition lands just below, at and above a
+    carry: the cases in which bit 61 of the folded value is set, which random inputs never
+    reach.  Built twice: for W = c1 t + c0 + 1, and for V = (p - c1) t + (p - c0), the value
+    the kernel's fast path for power-of-two D forms; there these are the evaluations whose
+    guard word sends the row to the exact path, and a model of the unguarded key confirms that
+    some of them would come out wrong without it."""
     D, p = 1 << 30, W.M61
     ts = [(1 << 29) - 1, (1 << 30) - 1, 12345677, 3]
-    rows, n_hit = [], 0
+    rows, n_hit, n_neg, n_unguarded_wrong = [], 0, 0, 0
     for t in ts:
         for A in (1, 5, 1 << 20, (t * (p - 1)) >> 61):
             for s in (-1, 0, 1, 7):
@@ -242,18 +246,35 @@ def test_m61_fold_carries_engineered():
                     B = (1 << 32) + s - A                       # B + A = 2^32 + s: carry iff s >= 0
                     if not 0 <= B < (1 << 32):
                         continue
-                    T = (A << 61) + middle + B                  # the value W must take
+                    T = (A << 61) + middle + B                  # the value W (or V) must take
                     c1 = min(T // t, p - 1)
                     c0 = T - c1 * t - 1
                     if 0 <= c0 < p:
                         rows.append([c0, c1])
                         n_hit += 1
-    assert n_hit >= 60
+                    n1 = min(T // t, p - 1)                     # negated form: V = n1 t + add
+                    add = T - n1 * t
+                    if 1 <= n1 and 1 <= add <= p:
+                        rows.append([p - add, p - n1])
+                        n_neg += 1
+                        L = (n1 & 0xFFFFFFFF) * t + add
+                        H = (n1 >> 32) * t + (L >> 32)
+                        key = ((L & 0xFFFFFFFF) + (H >> 29)) & (D - 1)
+                        want = (((p - n1) * t + (p - add)) % p) % D
+                        n_unguarded_wrong += (D - 1 - key) != want
+    assert n_hit >= 60 and n_neg >= 60 and n_unguarded_wrong >= 10
     c = np.array(rows, dtype=np.uint64)
     col = np.array(ts, dtype=np.uint32)
     rp = np.arange(len(ts) + 1, dtype=np.int64)
     check_case(rp, col, D, c.shape[0], 32, mh.FAMILY_2U_M61, c)
     check_case(np.array([0, len(ts)], dtype=np.int64), col, D, c.shape[0], 32, mh.FAMILY_2U_M61, c)
+    # one engineered evaluation inside long rows (several tiles, split rows): the redo covers them
+    nnz = np.array([5000, 1, 300000, 700], dtype=np.int64)
+    rp2 = W.row_ptr_from_nnz(nnz)
+    col2 = W.csr_indices_np(nnz, D, seed=77)
+    for i, t in enumerate(ts):
+        col2[rp2[i] + (int(nnz[i]) * 2) // 3] = t
+    check_case(rp2, col2, D, c.shape[0], 32, mh.FAMILY_2U_M61, c)
 
 
 def test_extreme_coefficients_and_indices():
