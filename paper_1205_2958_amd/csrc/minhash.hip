@@ -1454,9 +1454,10 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     }
     const int64_t sig_bytes = ((int64_t)k * b + 7) / 8;
     if (out_stride < sig_bytes) return MINHASH_ERR_STRIDE;
-    if (flags & ~(MINHASH_FLAG_VALIDATE | MINHASH_FLAG_GENERIC_MOD)) return MINHASH_ERR_ARG;
+    if (flags & ~(MINHASH_FLAG_VALIDATE | MINHASH_FLAG_GENERIC_MOD | MINHASH_FLAG_EXACT_FOLD)) return MINHASH_ERR_ARG;
     const bool generic_mod = (flags & MINHASH_FLAG_GENERIC_MOD) != 0;
     if (generic_mod && family != MINHASH_2U_M31 && family != MINHASH_4U_M31) return MINHASH_ERR_ARG;
+    if ((flags & MINHASH_FLAG_EXACT_FOLD) && family != MINHASH_2U_M61) return MINHASH_ERR_ARG;
     if (n_rows == 0) return MINHASH_OK;
     if (!row_ptr || !params || !out) return MINHASH_ERR_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % MINHASH_WORKSPACE_ALIGN) != 0) return MINHASH_ERR_WORKSPACE;
@@ -1496,12 +1497,13 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
 
     const bool perm = family == MINHASH_PERM;
     const bool pow2 = a.md.pow2 != 0;
+    // 2U with p = 2^61-1: the guarded fast path needs a power-of-two D and t < 2^31
+    const bool guarded61 = pow2 && D <= (1ull << 31) && !(flags & MINHASH_FLAG_EXACT_FOLD);
     int nf = HASH_FPL;
     int ftile_size = PERM_FTILE;
     if (!perm) {
         // the kernels ordered by hand come with 5..8 functions per lane
-        const bool variable = !generic_mod && family != MINHASH_4U_M61 &&
-                              !(family == MINHASH_2U_M61 && !(pow2 && D <= (1ull << 31)));
+        const bool variable = !generic_mod && family != MINHASH_4U_M61 && !(family == MINHASH_2U_M61 && !guarded61);
         int lg = 0;
         functions_per_lane(k, variable, &nf, &lg);
         a.log2_fl = lg;
@@ -1541,8 +1543,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         if (pow2) launch_hash<Pol4U31<true>>(a, nf, main_blocks, s); else launch_hash<Pol4U31<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_2U_M61:
-        // the 32-bit-multiplicand arithmetic needs t < 2^31
-        if (pow2 && D <= (1ull << 31)) launch_hash<Pol2U61<true>>(a, nf, main_blocks, s);
+        if (guarded61) launch_hash<Pol2U61<true>>(a, nf, main_blocks, s);
         else launch_hash<Pol2U61<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_4U_M61:

@@ -22,6 +22,7 @@ FAMILY_2U_MS32 = 5
 FAMILY_2U_MS32_HIGH = 6
 FLAG_VALIDATE = 1
 FLAG_GENERIC_MOD = 2
+FLAG_EXACT_FOLD = 4
 WORKSPACE_ALIGN = 256
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

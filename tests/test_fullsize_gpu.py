@@ -102,3 +102,31 @@ def test_heavy_tailed_m61_batch_sampled_rows(batch):
     _check_rows(w, nnz, rp_np, seed, col, params, params_np, out, list(dict.fromkeys(rows)))
     # b = 1, k = 500: 63 bytes per row, the last 4 bits of the last byte are pad and must be 0
     assert int((out[:, 62] & 0xF0).max().item()) == 0
+
+
+def test_guarded_m61_path_equals_the_exact_fold_on_a_whole_batch():
+    """10^12 evaluations hit the guard of the carry-free 2U-M61 form about 2 000 times, so this
+    batch exercises the exact re-evaluation on ordinary data.  Its full 32-bit minima must equal,
+    row for row, those of the carry-propagating form (which the sampled rows above and the
+    engineered cases pin to the oracle)."""
+    w = W.WORKLOADS["huge_2u_m61"]
+    nnz = w.nnz(0)
+    rp_np = W.row_ptr_from_nnz(nnz)
+    col = W.csr_indices_torch(nnz, w.D, w.data_seed, DEV)
+    rp = torch.from_numpy(rp_np).to(DEV)
+    params_np = W.coefficients(w.k, w.family, w.param_seed)
+    params = torch.from_numpy(params_np.view(np.int64)).to(DEV)
+    ws = mh.alloc_workspace(len(nnz), int(rp_np[-1]), w.k, w.family, DEV)
+    outs = []
+    for flags in (0, mh.FLAG_EXACT_FOLD):
+        out = torch.full((len(nnz), 4 * w.k), 0xAA, dtype=torch.uint8, device=DEV)
+        mh.minhash_signatures(rp, col, w.D, w.k, 32, w.family, params, out=out, workspace=ws, flags=flags)
+        assert mh.status(ws) == 0
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1])
+    # and one short row of it against the oracle at full width
+    r = int(np.argsort(nnz, kind="stable")[len(nnz) // 2])
+    lo, hi = int(rp_np[r]), int(rp_np[r + 1])
+    idx = col[lo:hi].cpu().numpy().view(np.uint32)
+    want = oracle.signatures(np.array([0, hi - lo], dtype=np.int64), idx, w.D, w.k, 32, w.family, params_np)
+    assert np.array_equal(outs[0][r].cpu().numpy(), want[0])
