@@ -52,6 +52,7 @@ constexpr int WAVES_PER_BLOCK = 4;
 constexpr int BLOCK = WAVE * WAVES_PER_BLOCK;
 constexpr int TILE = 256;              // nonzeros staged per wavefront per step (4 per lane)
 constexpr int HASH_FPL = 8;            // hash functions per lane
+constexpr int ROTATED_KEY_MIN_LOG2_D = 20;
 constexpr int HASH_ACC = HASH_FPL + 2;     // the running extrema of a lane's functions plus two words a policy may use as guards
 constexpr int HASH_FTILE = WAVE * HASH_FPL;   // 512 functions per wavefront pass
 constexpr int PERM_FPL = 4;            // permutations per lane (one 16-byte load)
@@ -239,7 +240,8 @@ struct ModDV : ModD {
     uint32_t sign;   // 2^31
     uint32_t negD;   // 2^32 - D
     uint32_t top3;   // 0xE0000000
-    uint32_t kshift; // 32 - log2 D: left shift of the order-preserving keys of the negated 2U form
+    uint32_t kshift; // 32 - log2 D: left shift of the order-preserving keys of the negated forms
+    uint32_t rbits;  // log2 D (at least 1): right rotation of the rotated keys
 };
 __device__ __forceinline__ ModDV vector_constants(const ModD& src)
 {
@@ -255,6 +257,7 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
     v.negD = in_vgpr_if_used(0u - src.D);
     v.top3 = in_vgpr_if_used(0xE0000000u);
     v.kshift = src.pow2 ? neg_key_shift(src.mask) : 0u;
+    v.rbits = src.pow2 ? rot_key_bits(src.mask) : 1u;
     return v;
 }
 // Issue priority of this wavefront among those of its SIMD.  The hand-ordered steps
@@ -462,14 +465,20 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // the kernel folds into a running extremum: the hashed location itself (running
 // minimum), or, when TRACK_MAX, its complement mask - h(t) (running maximum),
 // which saves one instruction per evaluation for power-of-two D.
-template <bool POW2>
+// ROT (power-of-two D only): rotated keys with their guard instead of shifted keys, one
+// instruction fewer per evaluation.  For 2U the guard cannot be hit as long as t < D (see
+// the launch code), so the host always picks ROT; for 4U it picks ROT for D >= 2^20, where
+// a key asks to be looked at again once in 2^21 evaluations or less.
+template <bool POW2, bool ROT = false>
 struct Pol2U31 {
+    static_assert(POW2 || !ROT, "rotated keys are for power-of-two D");
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = POW2 ? 5 : 4;   // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool TRACK_MAX = POW2;
-    static constexpr bool SHIFTED_KEY = POW2;    // the running maximum is a key shifted left by md.kshift
+    static constexpr bool SHIFTED_KEY = POW2 && !ROT;   // the running maximum is a key shifted left by md.kshift
+    static constexpr bool ROTATED_KEY = ROT;            // ... or a rotated key (m31_rot_key),
     static constexpr bool SHIFT_END = false;
-    static constexpr bool GUARDED = false;
+    static constexpr bool GUARDED = ROT;                // which can say that it may have wrapped
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
@@ -480,8 +489,22 @@ struct Pol2U31 {
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = stage_2u31(t); }
     static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModDV& md, uint64_t)
     {
+        if (ROT) return key_rot_2u31(f, w[0], md.rbits);
         if (POW2) return key_neg_2u31(f, w[0], md.kshift);
         return hash_2u31_raw(f, w[0], md);
+    }
+    template <int NF>
+    static __device__ __forceinline__ uint32_t doubtful(const uint32_t (&m)[HASH_ACC], const ModDV& md)
+    {
+        uint32_t bits = 0;
+#pragma unroll
+        for (int r = 0; r < NF; ++r) bits |= rot_key_wrapped(m[r], md.rbits) ? 1u << r : 0u;
+        return bits;
+    }
+    // the hashed location from the definition's arithmetic (canonical residue, then mod D)
+    static __device__ __forceinline__ uint32_t exact_hash(const uint64_t* c, uint32_t t, const ModD& md, uint64_t)
+    {
+        return hash_2u31<POW2>(prep_2u31(c[0], c[1]), stage_2u31(t), md);
     }
     template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
@@ -489,14 +512,16 @@ struct Pol2U31 {
     static constexpr int DEG = 2;
 };
 
-template <bool POW2>
+template <bool POW2, bool ROT = false>
 struct Pol4U31 {
+    static_assert(POW2 || !ROT, "rotated keys are for power-of-two D");
     static constexpr int NW = 3;
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool TRACK_MAX = POW2;
-    static constexpr bool SHIFTED_KEY = POW2;
+    static constexpr bool SHIFTED_KEY = POW2 && !ROT;
+    static constexpr bool ROTATED_KEY = ROT;
     static constexpr bool SHIFT_END = false;
-    static constexpr bool GUARDED = false;
+    static constexpr bool GUARDED = ROT;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn4U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
@@ -513,8 +538,21 @@ struct Pol4U31 {
     {
         Pow4U31 p;
         p.t1 = (int32_t)w[0]; p.t2 = (int32_t)w[1]; p.t3 = (int32_t)w[2];
+        if (ROT) return key_rot_4u31(f, p, md.rbits);
         if (POW2) return key_neg_4u31(f, p, md.kshift);
         return hash_4u31_np2(f, p, md);
+    }
+    template <int NF>
+    static __device__ __forceinline__ uint32_t doubtful(const uint32_t (&m)[HASH_ACC], const ModDV& md)
+    {
+        uint32_t bits = 0;
+#pragma unroll
+        for (int r = 0; r < NF; ++r) bits |= rot_key_wrapped(m[r], md.rbits) ? 1u << r : 0u;
+        return bits;
+    }
+    static __device__ __forceinline__ uint32_t exact_hash(const uint64_t* c, uint32_t t, const ModD& md, uint64_t)
+    {
+        return hash_4u31<POW2>(prep_4u31(c[0], c[1], c[2], c[3]), stage_4u31(t), md);
     }
     template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
@@ -531,14 +569,16 @@ struct Fn2U61V : Fn2U61 {
 
 // For power-of-two D <= 2^31 the fast path evaluates the negated function without
 // carries (key_neg_2u61 of mh_arith.h) and keeps the running maximum of the keys
-// and of the guard words; an item whose guard was hit, about one evaluation in
-// 2^29, is evaluated again with the exact arithmetic (GUARDED, see the kernel).
+// and of the guard words; when a lane's guard was hit, about one evaluation in
+// 2^29, its values are computed again from the exact arithmetic (GUARDED, see
+// the kernel).
 template <bool POW2>
 struct Pol2U61 {
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = POW2 ? 4 : 5;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = POW2;
+    static constexpr bool ROTATED_KEY = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = POW2;
     static constexpr bool VARIABLE_NF = POW2;    // hand-ordered steps exist for 5..8 functions per lane
@@ -555,34 +595,24 @@ struct Pol2U61 {
         }
         return f;
     }
-    static __device__ __forceinline__ Fn load_exact(const uint64_t* c, bool valid, const KArgs&)
-    {
-        Fn f;
-        static_cast<Fn2U61&>(f) = valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
-        if constexpr (POW2) f.hz = u32x2{0u, 0u};
-        return f;
-    }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
     // the exact hashed location (the fast path of POW2 does not come through here)
     static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t D)
     {
         return hash_2u61<POW2>(f, w[0], md, D);
     }
-    static __device__ __forceinline__ bool guard_hit(const uint32_t (&m)[HASH_ACC])
+    template <int NF>
+    static __device__ __forceinline__ uint32_t doubtful(const uint32_t (&m)[HASH_ACC], const ModDV&)
     {
-        return m[HASH_FPL] == GUARD61_HIT || m[HASH_FPL + 1] == GUARD61_HIT;
+        return (m[HASH_FPL] == GUARD61_HIT || m[HASH_FPL + 1] == GUARD61_HIT) ? (1u << NF) - 1u : 0u;
+    }
+    static __device__ __forceinline__ uint32_t exact_hash(const uint64_t* c, uint32_t t, const ModD& md, uint64_t D)
+    {
+        return hash_2u61<POW2>(prep_2u61(c[0], c[1]), t, md, D);
     }
     template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                 const uint32_t* wb, const ModDV& md, uint64_t D);
-    // running minimum of the exact locations, schedule left to the compiler
-    template <int NF>
-    static __device__ __forceinline__ void pair_exact(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                      const uint32_t* wb, const ModDV& md, uint64_t D)
-    {
-#pragma unroll
-        for (int r = 0; r < NF; ++r) m[r] = umin3(m[r], key(fn[r], wa, md, D), key(fn[r], wb, md, D));
-    }
     static constexpr int DEG = 2;
 };
 
@@ -594,6 +624,7 @@ struct Pol4U61 {
     static constexpr int MIN_WAVES = 2;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
+    static constexpr bool ROTATED_KEY = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = false;
@@ -650,15 +681,14 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // another wavefront's simple instruction go beside it, and a multiply lets
 // nothing go beside it.  The eight evaluations of one nonzero are therefore
 // emitted stage by stage, so that neighbouring instructions never depend on each
-// other: eight multiply-adds at raised priority, twenty-four simple instructions
-// at the normal one, eight add-then-shift instructions at raised priority again
-// (see issue_priority); two such halves, then eight three-operand maxima.  The
-// arithmetic is key_neg_2u31 of mh_arith.h, instruction for instruction.
-template <int NF>
-__device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&x)[HASH_FPL], uint32_t t, uint32_t kshift)
+// other: eight multiply-adds at raised priority, sixteen simple instructions at
+// the normal one, eight funnel shifts at raised priority again (see
+// issue_priority); two such halves, then eight three-operand maxima.  The
+// arithmetic is key_rot_2u31 of mh_arith.h, instruction for instruction.
+template <int NF, bool ROT>
+__device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&x)[HASH_FPL], uint32_t t, uint32_t amount)
 {
     uint64_t p[HASH_FPL];
-    uint32_t c[HASH_FPL];
     issue_priority<1>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
@@ -667,19 +697,26 @@ __device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
     for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"((uint32_t)p[g]));
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"((uint32_t)(p[g] >> 32)));
+    if constexpr (ROT) {       // key_rot_2u31: amount = log2 D
+        issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(c[g]) : "v"(x[g]));
-    issue_priority<1>();
+        for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %0, %0, %1" : "+v"(x[g]) : "s"(amount));
+    } else {                   // key_neg_2u31: amount = 32 - log2 D
+        uint32_t c[HASH_FPL];
 #pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_add_lshl_u32 %0, %0, %1, %2" : "+v"(x[g]) : "v"(c[g]), "s"(kshift));
+        for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(c[g]) : "v"(x[g]));
+        issue_priority<1>();
+#pragma unroll
+        for (int g = 0; g < NF; ++g) asm volatile("v_add_lshl_u32 %0, %0, %1, %2" : "+v"(x[g]) : "v"(c[g]), "s"(amount));
+    }
 }
-template <int NF>
+template <int NF, bool ROT>
 __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta,
-                                               uint32_t tb, uint32_t kshift)
+                                               uint32_t tb, uint32_t amount)
 {
     uint32_t xa[HASH_FPL], xb[HASH_FPL];
-    half_2u31_pow2<NF>(fn, xa, ta, kshift);
-    half_2u31_pow2<NF>(fn, xb, tb, kshift);
+    half_2u31_pow2<NF, ROT>(fn, xa, ta, amount);
+    half_2u31_pow2<NF, ROT>(fn, xb, tb, amount);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
@@ -688,10 +725,10 @@ __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
 // 4U, p = 2^31-1, power-of-two D, same idea: three chained multiply-adds per
 // evaluation are issued function-major so that each waits for a result that is
 // 16 instructions old; the fold of nonzero A overlaps the last multiply-adds of
-// nonzero B.  Arithmetic of key_neg_4u31 (mh_arith.h), instruction for instruction.
-template <int NF>
+// nonzero B.  Arithmetic of key_rot_4u31 (mh_arith.h), instruction for instruction.
+template <int NF, bool ROT>
 __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], const uint32_t* w,
-                                               uint32_t kshift, uint32_t p31)
+                                               uint32_t amount, uint32_t p31)
 {
     uint64_t acc[HASH_FPL];
     uint32_t u[HASH_FPL], v[HASH_FPL];
@@ -715,21 +752,26 @@ __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
     issue_priority<1>();       // one three-operand add (full issue) instead of two simple adds: fewer instructions in all
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(y[g]) : "v"(u[g]), "v"(v[g]));
-    issue_priority<0>();
+    if constexpr (ROT) {       // key_rot_4u31: amount = log2 D
 #pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(u[g]) : "v"(y[g]));
-    issue_priority<1>();
+        for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %0, %0, %1" : "+v"(y[g]) : "s"(amount));
+    } else {                   // key_neg_4u31: amount = 32 - log2 D
+        issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_add_lshl_u32 %0, %0, %1, %2" : "+v"(y[g]) : "v"(u[g]), "s"(kshift));
+        for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(u[g]) : "v"(y[g]));
+        issue_priority<1>();
+#pragma unroll
+        for (int g = 0; g < NF; ++g) asm volatile("v_add_lshl_u32 %0, %0, %1, %2" : "+v"(y[g]) : "v"(u[g]), "s"(amount));
+    }
 }
 
-template <int NF>
+template <int NF, bool ROT>
 __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC],
-                                               const uint32_t* wa, const uint32_t* wb, uint32_t kshift, uint32_t p31)
+                                               const uint32_t* wa, const uint32_t* wb, uint32_t amount, uint32_t p31)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
-    half_4u31_pow2<NF>(fn, ya, wa, kshift, p31);
-    half_4u31_pow2<NF>(fn, yb, wb, kshift, p31);
+    half_4u31_pow2<NF, ROT>(fn, ya, wa, amount, p31);
+    half_4u31_pow2<NF, ROT>(fn, yb, wb, amount, p31);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
@@ -885,6 +927,7 @@ struct PolGenericMod {
     static constexpr int MIN_WAVES = 3;        // no spills, so that the ablation times the arithmetic only
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
+    static constexpr bool ROTATED_KEY = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = false;
@@ -924,6 +967,7 @@ struct Pol2UMS32 {
     static constexpr int MIN_WAVES = 5;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
+    static constexpr bool ROTATED_KEY = false;
     static constexpr bool SHIFT_END = true;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
@@ -957,10 +1001,17 @@ struct Pol2UMS32 {
 
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol2U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                    const uint32_t* wb, const ModDV& md, uint64_t)
+__device__ __forceinline__ void Pol2U31<true, true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                          const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_2u31_pow2<NF>(fn, m, wa[0], wb[0], md.kshift);
+    pair_2u31_pow2<NF, true>(fn, m, wa[0], wb[0], md.rbits);
+}
+template <>
+template <int NF>
+__device__ __forceinline__ void Pol2U31<true, false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                           const uint32_t* wb, const ModDV& md, uint64_t)
+{
+    pair_2u31_pow2<NF, false>(fn, m, wa[0], wb[0], md.kshift);
 }
 template <>
 template <int NF>
@@ -972,10 +1023,17 @@ __device__ __forceinline__ void Pol2U31<false>::pair(const Fn (&fn)[HASH_FPL], u
 
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol4U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                    const uint32_t* wb, const ModDV& md, uint64_t)
+__device__ __forceinline__ void Pol4U31<true, true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                          const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_4u31_pow2<NF>(fn, m, wa, wb, md.kshift, md.p31);
+    pair_4u31_pow2<NF, true>(fn, m, wa, wb, md.rbits, md.p31);
+}
+template <>
+template <int NF>
+__device__ __forceinline__ void Pol4U31<true, false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                           const uint32_t* wb, const ModDV& md, uint64_t)
+{
+    pair_4u31_pow2<NF, false>(fn, m, wa, wb, md.kshift, md.p31);
 }
 template <>
 template <int NF>
@@ -1068,86 +1126,99 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
         const int64_t begin = it.begin;
         const uint32_t len = it.len;
 
-        // A GUARDED policy computes keys that are exact unless a guard word says otherwise
-        // (rarely); then the item is evaluated once more with the policy's exact arithmetic.
         uint32_t m[HASH_ACC];
-        bool exact = false;     // wave-uniform
-        for (;;) {
 #pragma unroll
-            for (int r = 0; r < NF; ++r) m[r] = (Pol::TRACK_MAX && !exact) ? 0u : EMPTY_MIN;
-            m[HASH_FPL] = m[HASH_FPL + 1] = 0u;
+        for (int r = 0; r < NF; ++r) m[r] = Pol::TRACK_MAX ? 0u : EMPTY_MIN;
+        m[HASH_FPL] = m[HASH_FPL + 1] = 0u;
 
-            if (len > 0) {
-                uint32_t pad = a.col_idx[begin];
-                uint32_t regs[4];
-                load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
-                for (uint32_t off = 0; off < len; off += TILE) {
-                    // stage: pre-compute what depends on t alone, one nonzero per lane and register
+        if (len > 0) {
+            uint32_t pad = a.col_idx[begin];
+            uint32_t regs[4];
+            load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
+            for (uint32_t off = 0; off < len; off += TILE) {
+                // stage: pre-compute what depends on t alone, one nonzero per lane and register
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        uint32_t t = regs[q];
-                        if (a.validate && (uint64_t)t >= a.D) {
-                            atomicOr(&a.hdr->status, 2u);
-                            t = 0;
-                        }
-                        uint32_t w[Pol::NW];
-                        Pol::stage(t, w);
-#pragma unroll
-                        for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
+                for (int q = 0; q < 4; ++q) {
+                    uint32_t t = regs[q];
+                    if (a.validate && (uint64_t)t >= a.D) {
+                        atomicOr(&a.hdr->status, 2u);
+                        t = 0;
                     }
-                    wave_sync_lds();
-                    if (off + TILE < len) load_tile(a.col_idx, begin, len, off + TILE, pad, lane, regs);
+                    uint32_t w[Pol::NW];
+                    Pol::stage(t, w);
+#pragma unroll
+                    for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
+                }
+                wave_sync_lds();
+                if (off + TILE < len) load_tile(a.col_idx, begin, len, off + TILE, pad, lane, regs);
 
-                    const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
-                    const int n_steps = (int)((in_tile + 4u * n_slices - 1u) / (4u * n_slices));
-                    for (int s = 0; s < n_steps; ++s) {
-                        const int e = 4 * (s * n_slices + slice);
-                        uint32_t w[4][Pol::NW];
+                const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
+                const int n_steps = (int)((in_tile + 4u * n_slices - 1u) / (4u * n_slices));
+                for (int s = 0; s < n_steps; ++s) {
+                    const int e = 4 * (s * n_slices + slice);
+                    uint32_t w[4][Pol::NW];
 #pragma unroll
-                        for (int i = 0; i < Pol::NW; ++i) {
-                            uint4 v = *reinterpret_cast<const uint4*>(&tile[i][e]);
-                            w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
-                        }
-                        if constexpr (Pol::GUARDED) {
-                            if (exact) {
-                                Pol::template pair_exact<NF>(fn, m, w[0], w[1], md, a.D);
-                                Pol::template pair_exact<NF>(fn, m, w[2], w[3], md, a.D);
-                                continue;
-                            }
-                        }
-                        Pol::template pair<NF>(fn, m, w[0], w[1], md, a.D);
-                        Pol::template pair<NF>(fn, m, w[2], w[3], md, a.D);
+                    for (int i = 0; i < Pol::NW; ++i) {
+                        uint4 v = *reinterpret_cast<const uint4*>(&tile[i][e]);
+                        w[0][i] = v.x; w[1][i] = v.y; w[2][i] = v.z; w[3][i] = v.w;
                     }
-                    wave_sync_lds();
+                    Pol::template pair<NF>(fn, m, w[0], w[1], md, a.D);
+                    Pol::template pair<NF>(fn, m, w[2], w[3], md, a.D);
                 }
-                if (Pol::TRACK_MAX && !exact) {      // back from complements to the minimum location
+                wave_sync_lds();
+            }
+            // A GUARDED policy keeps keys that are exact unless the running value itself, or a guard
+            // word beside it, says otherwise (rarely); bit r of `doubt` marks such a value.
+            uint32_t doubt = 0;
+            if constexpr (Pol::GUARDED) doubt = Pol::template doubtful<NF>(m, md);
+            if (Pol::TRACK_MAX) {      // back from keys to the minimum location
 #pragma unroll
-                    for (int r = 0; r < NF; ++r)
-                        m[r] = Pol::SHIFTED_KEY ? finish_neg_key(m[r], md.kshift, md.mask) : md.mask - m[r];
+                for (int r = 0; r < NF; ++r) {
+                    if (Pol::ROTATED_KEY) m[r] = finish_rot_key(m[r], md.rbits, md.mask);
+                    else m[r] = Pol::SHIFTED_KEY ? finish_neg_key(m[r], md.kshift, md.mask) : md.mask - m[r];
                 }
-                if (Pol::SHIFT_END) {      // from the order-preserving key back to the hashed location
+            }
+            if (Pol::SHIFT_END) {      // from the order-preserving key back to the hashed location
 #pragma unroll
-                    for (int r = 0; r < NF; ++r) m[r] = finish_2ums32(m[r], a.md.M);
-                }
-            } else if (Pol::TRACK_MAX) {
-#pragma unroll
-                for (int r = 0; r < NF; ++r) m[r] = EMPTY_MIN;
+                for (int r = 0; r < NF; ++r) m[r] = finish_2ums32(m[r], a.md.M);
             }
             if constexpr (Pol::GUARDED) {
-                if (!exact && __builtin_amdgcn_ballot_w64(Pol::guard_hit(m)) != 0ull) {
-                    const uint64_t* coeffs = static_cast<const uint64_t*>(a.params);
+                // Every doubtful value is computed again from the definition: the whole wavefront
+                // evaluates that one function on all nonzeros of the item, a lane each, and the
+                // owner takes the minimum (over the whole item, which its slice is part of).
+                uint64_t owners = __builtin_amdgcn_ballot_w64(doubt != 0u);
+                while (owners) {
+                    const int owner = __builtin_ctzll(owners);
+                    owners &= owners - 1;
+                    uint32_t which = (uint32_t)__builtin_amdgcn_readlane((int)doubt, owner);
+                    const int j0 = __builtin_amdgcn_readlane(j_base, owner);
+                    while (which) {
+                        const int r = __builtin_ctz(which);
+                        which &= which - 1;
+                        if (j0 + r >= a.k) continue;                    // an unused slot: never stored
+                        const uint64_t* c = static_cast<const uint64_t*>(a.params) + (size_t)(j0 + r) * Pol::DEG;
+                        uint32_t best = EMPTY_MIN;
+                        for (uint32_t e = (uint32_t)lane; e < len; e += WAVE) {
+                            uint32_t t = a.col_idx[begin + e];
+                            if (a.validate && (uint64_t)t >= a.D) t = 0;
+                            const uint32_t h = Pol::exact_hash(c, t, a.md, a.D);
+                            best = h < best ? h : best;
+                        }
+                        for (int d = 1; d < WAVE; d <<= 1) {
+                            const uint32_t o = (uint32_t)__shfl_xor((int)best, d, WAVE);
+                            best = o < best ? o : best;
+                        }
+                        if (lane == owner) {
 #pragma unroll
-                    for (int r = 0; r < NF; ++r) {
-                        int j = j_base + r;
-                        bool valid = j < a.k;
-                        fn[r] = Pol::load_exact(coeffs + (size_t)(valid ? j : 0) * Pol::DEG, valid, a);
+                            for (int q = 0; q < NF; ++q)
+                                if (q == r) m[q] = best;
+                        }
                     }
-                    cur_ftile = -1;     // the next item loads the fast form again
-                    exact = true;
-                    continue;
                 }
             }
-            break;
+        } else if (Pol::TRACK_MAX) {
+#pragma unroll
+            for (int r = 0; r < NF; ++r) m[r] = EMPTY_MIN;
         }
         // merge the slices of nonzeros (lanes that share fl)
         for (int d = fl_lanes; d < WAVE; d <<= 1) {
@@ -1497,6 +1568,10 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
 
     const bool perm = family == MINHASH_PERM;
     const bool pow2 = a.md.pow2 != 0;
+    // 4U, p = 2^31-1: a rotated key asks for a second look once in 2D evaluations, so they are for
+    // large D.  2U: never, for t < D (the folded value exceeds 2^31 by less than D - 1 when it does,
+    // so its low bits are not all ones), and every power-of-two D takes them.
+    const bool rotated4 = pow2 && D >= (1ull << ROTATED_KEY_MIN_LOG2_D);
     // 2U with p = 2^61-1: the guarded fast path needs a power-of-two D and t < 2^31
     const bool guarded61 = pow2 && D <= (1ull << 31) && !(flags & MINHASH_FLAG_EXACT_FOLD);
     int nf = HASH_FPL;
@@ -1537,10 +1612,13 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     case -MINHASH_2U_M31 - 1: launch_hash<PolGenericMod<2>>(a, nf, main_blocks, s); break;
     case -MINHASH_4U_M31 - 1: launch_hash<PolGenericMod<4>>(a, nf, main_blocks, s); break;
     case MINHASH_2U_M31:
-        if (pow2) launch_hash<Pol2U31<true>>(a, nf, main_blocks, s); else launch_hash<Pol2U31<false>>(a, nf, main_blocks, s);
+        if (pow2) launch_hash<Pol2U31<true, true>>(a, nf, main_blocks, s);
+        else launch_hash<Pol2U31<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_4U_M31:
-        if (pow2) launch_hash<Pol4U31<true>>(a, nf, main_blocks, s); else launch_hash<Pol4U31<false>>(a, nf, main_blocks, s);
+        if (rotated4) launch_hash<Pol4U31<true, true>>(a, nf, main_blocks, s);
+        else if (pow2) launch_hash<Pol4U31<true, false>>(a, nf, main_blocks, s);
+        else launch_hash<Pol4U31<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_2U_M61:
         if (guarded61) launch_hash<Pol2U61<true>>(a, nf, main_blocks, s);

@@ -24,7 +24,7 @@ static uint64_t ref_poly(const uint64_t* c, int deg, uint64_t p, uint64_t D, uin
     return (uint64_t)(acc % D);
 }
 
-static long checks = 0, guard_hits = 0, guard_saves = 0;
+static long checks = 0, guard_hits = 0, guard_saves = 0, rot_flagged = 0;
 #define FAIL(...) do { printf("MISMATCH " __VA_ARGS__); printf("\n"); exit(1); } while (0)
 
 static void check31(uint64_t D, const uint64_t* c, uint32_t t)
@@ -44,6 +44,27 @@ static void check31(uint64_t D, const uint64_t* c, uint32_t t)
         uint32_t n2 = finish_neg_key(key_neg_2u31(prep_2u31_neg(c[0], c[1]), stage_2u31(t), ks), ks, md.mask);
         if (n2 != want2) FAIL("2U31 negated key D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
                               (unsigned long long)c[0], (unsigned long long)c[1], n2, (unsigned long long)want2);
+        // rotated keys: exact unless the word says that it may have wrapped, and then the location is D - 1
+        {
+            const uint32_t rs = rot_key_bits(md.mask);
+            const uint32_t w2 = key_rot_2u31(prep_2u31_neg(c[0], c[1]), stage_2u31(t), rs);
+            const uint32_t w4 = key_rot_4u31(prep_4u31_neg(c[0], c[1], c[2], c[3]), stage_4u31(t), rs);
+            if (!rot_key_wrapped(w2, rs) && finish_rot_key(w2, rs, md.mask) != want2) FAIL("2U31 rotated key D=%llu t=%u", (unsigned long long)D, t);
+            if (!rot_key_wrapped(w4, rs) && finish_rot_key(w4, rs, md.mask) != want4) FAIL("4U31 rotated key D=%llu t=%u", (unsigned long long)D, t);
+            // 2U: for t < D the folded value exceeds 2^31 by less than D - 1, so its key never wraps
+            if (rot_key_wrapped(w2, rs) && D > 1) FAIL("2U31 rotated key flagged D=%llu t=%u", (unsigned long long)D, t);
+            if (rot_key_wrapped(w4, rs) && D > 1 && want4 != md.mask) FAIL("4U31 rotated key flagged without a wrap D=%llu t=%u", (unsigned long long)D, t);
+            rot_flagged += rot_key_wrapped(w2, rs) + rot_key_wrapped(w4, rs);
+            // order: of two unflagged evaluations, the one with the smaller location has the larger word
+            static uint32_t prev_w = 0, prev_s = 0; static uint64_t prev_want = 0, prev_D = 0;
+            if (prev_D == D && prev_s == rs && !rot_key_wrapped(w2, rs) && !rot_key_wrapped(prev_w, rs)) {
+                if (want2 < prev_want && !(w2 > prev_w)) FAIL("rotated key order D=%llu", (unsigned long long)D);
+                if (want2 > prev_want && !(w2 < prev_w)) FAIL("rotated key order D=%llu", (unsigned long long)D);
+                ++checks;
+            }
+            prev_w = w2; prev_s = rs; prev_want = want2; prev_D = D;
+            checks += 2;
+        }
         uint32_t n4 = finish_neg_key(key_neg_4u31(prep_4u31_neg(c[0], c[1], c[2], c[3]), stage_4u31(t), ks), ks, md.mask);
         if (n4 != want4) FAIL("4U31 negated key D=%llu t=%u c=(%llu,%llu,%llu,%llu) got %u want %llu", (unsigned long long)D, t,
                               (unsigned long long)c[0], (unsigned long long)c[1], (unsigned long long)c[2],
@@ -231,6 +252,7 @@ int main()
             checks += 2;
         }
     }
+    if (rot_flagged < 1000) FAIL("rotated keys: only %ld flagged evaluations seen", rot_flagged);
     printf("OK %ld\n", checks);
     return 0;
 }

@@ -475,3 +475,39 @@ def test_call_is_capturable_in_a_hip_graph_and_replays_exactly():
         graph.replay()
         torch.cuda.synchronize()
         assert np.array_equal(out.cpu().numpy(), wants[i]), "replay with input %d" % i
+
+
+@pytest.mark.parametrize("family", [mh.FAMILY_2U_M31, mh.FAMILY_4U_M31])
+def test_rotated_key_wraps_engineered(family):
+    """The kernels for p = 2^31-1 keep rotated keys (4U: for D >= 2^20), which are right unless
+    an evaluation hashes to D - 1 while its folded value has bit 31 set; the running maximum then
+    says so and the value is computed again.  Rows built to contain, for most functions, an index
+    that hashes to D - 1 among ordinary ones: all of [0, D) is scanned per function.  For 4U about
+    half of them have bit 31 set; for 2U none can (the folded value of an index below D exceeds
+    2^31 by less than D - 1), which the model below confirms."""
+    D, p, k = 1 << 20, W.M31, 96
+    deg = W.family_degree(family)
+    c = W.coefficients(k, family, seed=91)
+    t = np.arange(D, dtype=np.uint64)
+    hits, n_bit31 = [], 0
+    for j in range(k):
+        acc = np.zeros(D, dtype=np.uint64)
+        for i in range(deg - 1, -1, -1):                      # Horner, every product below 2^62
+            acc = (acc * t + np.uint64(c[j, i])) % np.uint64(p)
+        found = np.nonzero(acc % np.uint64(D) == np.uint64(D - 1))[0]
+        hits.extend(int(v) for v in found[:2])
+        if family == mh.FAMILY_2U_M31:
+            for v in found[:2]:                                # the folded value of the negated function
+                V = ((p - int(c[j, 1])) % p) * int(v) + (p - int(c[j, 0]))
+                n_bit31 += ((V >> 31) + (V & p)) >> 31
+    assert len(hits) >= k // 2
+    assert n_bit31 == 0
+    rng = np.random.Generator(np.random.PCG64(92))
+    planted = np.array(sorted(set(hits)), dtype=np.uint32)
+    rows = [planted,                                            # only such indices
+            np.unique(np.concatenate([planted, rng.integers(0, D, size=3000).astype(np.uint32)])),
+            np.unique(np.concatenate([planted[:7], rng.integers(0, D, size=20000).astype(np.uint32)])),   # a split row
+            planted[:1]]
+    nnz = np.array([r.shape[0] for r in rows], dtype=np.int64)
+    check_case(W.row_ptr_from_nnz(nnz), np.concatenate(rows), D, k, 32, family, c)
+    check_case(W.row_ptr_from_nnz(nnz), np.concatenate(rows), D, k, 8, family, c)
