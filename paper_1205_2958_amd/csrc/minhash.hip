@@ -465,20 +465,17 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // the kernel folds into a running extremum: the hashed location itself (running
 // minimum), or, when TRACK_MAX, its complement mask - h(t) (running maximum),
 // which saves one instruction per evaluation for power-of-two D.
-// ROT (power-of-two D only): rotated keys with their guard instead of shifted keys, one
-// instruction fewer per evaluation.  For 2U the guard cannot be hit as long as t < D (see
-// the launch code), so the host always picks ROT; for 4U it picks ROT for D >= 2^20, where
-// a key asks to be looked at again once in 2^21 evaluations or less.
-template <bool POW2, bool ROT = false>
+// Power-of-two D: rotated keys (m31_rot_key) with their guard, which cannot be hit as long
+// as t < D (see the launch code).
+template <bool POW2>
 struct Pol2U31 {
-    static_assert(POW2 || !ROT, "rotated keys are for power-of-two D");
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = POW2 ? 5 : 4;   // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool TRACK_MAX = POW2;
-    static constexpr bool SHIFTED_KEY = POW2 && !ROT;   // the running maximum is a key shifted left by md.kshift
-    static constexpr bool ROTATED_KEY = ROT;            // ... or a rotated key (m31_rot_key),
+    static constexpr bool SHIFTED_KEY = false;
+    static constexpr bool ROTATED_KEY = POW2;        // the running maximum is a rotated key (m31_rot_key),
     static constexpr bool SHIFT_END = false;
-    static constexpr bool GUARDED = ROT;                // which can say that it may have wrapped
+    static constexpr bool GUARDED = POW2;            // which can say that it may have wrapped
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
@@ -489,8 +486,7 @@ struct Pol2U31 {
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = stage_2u31(t); }
     static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModDV& md, uint64_t)
     {
-        if (ROT) return key_rot_2u31(f, w[0], md.rbits);
-        if (POW2) return key_neg_2u31(f, w[0], md.kshift);
+        if (POW2) return key_rot_2u31(f, w[0], md.rbits);
         return hash_2u31_raw(f, w[0], md);
     }
     template <int NF>
@@ -512,16 +508,19 @@ struct Pol2U31 {
     static constexpr int DEG = 2;
 };
 
+// ROT (power-of-two D only): rotated keys with their guard instead of shifted keys, one
+// instruction fewer per evaluation; the host picks ROT for D >= 2^20, where a key asks to be
+// looked at again once in 2^21 evaluations or less.
 template <bool POW2, bool ROT = false>
 struct Pol4U31 {
     static_assert(POW2 || !ROT, "rotated keys are for power-of-two D");
     static constexpr int NW = 3;
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool TRACK_MAX = POW2;
-    static constexpr bool SHIFTED_KEY = POW2 && !ROT;
-    static constexpr bool ROTATED_KEY = ROT;
+    static constexpr bool SHIFTED_KEY = POW2 && !ROT;   // the running maximum is a key shifted left by md.kshift
+    static constexpr bool ROTATED_KEY = ROT;            // ... or a rotated key,
     static constexpr bool SHIFT_END = false;
-    static constexpr bool GUARDED = ROT;
+    static constexpr bool GUARDED = ROT;                // which can say that it may have wrapped
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn4U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
@@ -685,8 +684,8 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // the normal one, eight funnel shifts at raised priority again (see
 // issue_priority); two such halves, then eight three-operand maxima.  The
 // arithmetic is key_rot_2u31 of mh_arith.h, instruction for instruction.
-template <int NF, bool ROT>
-__device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&x)[HASH_FPL], uint32_t t, uint32_t amount)
+template <int NF>
+__device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&x)[HASH_FPL], uint32_t t, uint32_t rbits)
 {
     uint64_t p[HASH_FPL];
     issue_priority<1>();
@@ -697,26 +696,17 @@ __device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
     for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"((uint32_t)p[g]));
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"((uint32_t)(p[g] >> 32)));
-    if constexpr (ROT) {       // key_rot_2u31: amount = log2 D
-        issue_priority<1>();
+    issue_priority<1>();
 #pragma unroll
-        for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %0, %0, %1" : "+v"(x[g]) : "s"(amount));
-    } else {                   // key_neg_2u31: amount = 32 - log2 D
-        uint32_t c[HASH_FPL];
-#pragma unroll
-        for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(c[g]) : "v"(x[g]));
-        issue_priority<1>();
-#pragma unroll
-        for (int g = 0; g < NF; ++g) asm volatile("v_add_lshl_u32 %0, %0, %1, %2" : "+v"(x[g]) : "v"(c[g]), "s"(amount));
-    }
+    for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %0, %0, %1" : "+v"(x[g]) : "s"(rbits));
 }
-template <int NF, bool ROT>
+template <int NF>
 __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta,
-                                               uint32_t tb, uint32_t amount)
+                                               uint32_t tb, uint32_t rbits)
 {
     uint32_t xa[HASH_FPL], xb[HASH_FPL];
-    half_2u31_pow2<NF, ROT>(fn, xa, ta, amount);
-    half_2u31_pow2<NF, ROT>(fn, xb, tb, amount);
+    half_2u31_pow2<NF>(fn, xa, ta, rbits);
+    half_2u31_pow2<NF>(fn, xb, tb, rbits);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
@@ -1001,17 +991,10 @@ struct Pol2UMS32 {
 
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol2U31<true, true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                          const uint32_t* wb, const ModDV& md, uint64_t)
+__device__ __forceinline__ void Pol2U31<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                    const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_2u31_pow2<NF, true>(fn, m, wa[0], wb[0], md.rbits);
-}
-template <>
-template <int NF>
-__device__ __forceinline__ void Pol2U31<true, false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                           const uint32_t* wb, const ModDV& md, uint64_t)
-{
-    pair_2u31_pow2<NF, false>(fn, m, wa[0], wb[0], md.kshift);
+    pair_2u31_pow2<NF>(fn, m, wa[0], wb[0], md.rbits);
 }
 template <>
 template <int NF>
@@ -1612,7 +1595,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     case -MINHASH_2U_M31 - 1: launch_hash<PolGenericMod<2>>(a, nf, main_blocks, s); break;
     case -MINHASH_4U_M31 - 1: launch_hash<PolGenericMod<4>>(a, nf, main_blocks, s); break;
     case MINHASH_2U_M31:
-        if (pow2) launch_hash<Pol2U31<true, true>>(a, nf, main_blocks, s);
+        if (pow2) launch_hash<Pol2U31<true>>(a, nf, main_blocks, s);
         else launch_hash<Pol2U31<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_4U_M31:
