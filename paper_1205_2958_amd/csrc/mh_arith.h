@@ -372,33 +372,41 @@ MH_HD uint32_t hash_2u61(const Fn2U61& f, uint32_t t, const ModD& md, uint64_t D
     return reduce61_mod_d(residue_wide_2u61(f, t), md, D);
 }
 
-// Power-of-two D <= 2^31, negated form with a guard (compare prep_2u31_neg).  With
-// c1' = -c1 mod p and the constant p - c0 in [1, p], V = c1' t + (p - c0) is congruent
-// to -X and the folded x = y + (H >> 29) lies in [1, 2^61 + 2^31 + 4).  As long as
-// bit 61 of x is clear, x itself is the representative p - (X mod p) in [1, p], whose
-// low s bits are the complement of the hashed location: the key is
-// (L_lo + (H >> 29)) & mask, one add and one and, no carries.  Bit 61 can only be set
-// if bits 32..60 of the bracket, i.e. the low 29 bits of H, are all ones and the
-// low-word addition carries into them.  `guard` = H_lo | 0xE0000000 is all ones in
-// exactly the first case: an evaluation whose guard is not 0xFFFFFFFF has an exact key;
-// about one evaluation in 2^29 has such a guard, and the caller then falls back on
-// the exact path (hash_2u61) for the data at hand.
-MH_HD Fn2U61 prep_2u61_neg(uint64_t c0, uint64_t c1)
+// Power-of-two D = 2^s <= 2^31, negated and rotated form with a guard (compare
+// prep_2u31_neg).  With c1' = -c1 mod p and the constant p - c0 in [1, p],
+// V = c1' t + (p - c0) is congruent to -X, and its representative in [1, p] is
+// p - (X mod p), whose low s bits are the complement of the hashed location.
+// Multiplying by 2^j modulo p = 2^61-1 rotates a 61-bit residue left by j bits, so
+// with both coefficients multiplied by 2^j, j = 32 - s, those s bits arrive at the top
+// of the low 32-bit word of the representative: that word, with whatever lies below
+// the s bits, is an order-preserving key as it stands.  The folded x = y + (H >> 29)
+// lies in [1, 2^61 + 2^31 + 4), and as long as its bit 61 is clear it is that
+// representative, so the key is L_lo + (H >> 29), one add, no carries, no shift.  Bit
+// 61 can only be set if bits 32..60 of the bracket, i.e. the low 29 bits of H, are all
+// ones and the low-word addition carries into them.  `guard` = H_lo | 0xE0000000 is
+// all ones in exactly the first case: an evaluation whose guard is not 0xFFFFFFFF has
+// an exact key; about one evaluation in 2^29 has such a guard, and the caller then
+// falls back on the exact path (hash_2u61) for the data at hand.
+MH_HD uint64_t rotl61(uint64_t v, uint32_t j)      // v <= p, 1 <= j <= 32: v 2^j modulo p (p stays p)
 {
-    const uint64_t n = c1 ? P61 - c1 : 0;
+    return ((v << j) | (v >> (61u - j))) & P61;
+}
+MH_HD Fn2U61 prep_2u61_neg(uint64_t c0, uint64_t c1, uint32_t shift)   // shift = neg_key_shift(mask)
+{
+    const uint64_t n = rotl61(c1 ? P61 - c1 : 0, shift);
     Fn2U61 f;
     f.e0 = (uint32_t)n;
     f.e1 = (uint32_t)(n >> 32);
-    f.add = P61 - c0;
+    f.add = rotl61(P61 - c0, shift);
     return f;
 }
 struct GuardedKey61 { uint32_t key, guard; };
-MH_HD GuardedKey61 key_neg_2u61(const Fn2U61& f, uint32_t t, uint32_t mask)   // t < 2^31
+MH_HD GuardedKey61 key_neg_2u61(const Fn2U61& f, uint32_t t)   // t < 2^31; the location is finish_neg_key(key, shift, mask)
 {
     const uint64_t L = (uint64_t)f.e0 * t + f.add;
     const uint64_t H = (uint64_t)f.e1 * t + (L >> 32);
     GuardedKey61 k;
-    k.key = ((uint32_t)L + (uint32_t)(H >> 29)) & mask;
+    k.key = (uint32_t)L + (uint32_t)(H >> 29);
     k.guard = (uint32_t)H | 0xE0000000u;
     return k;
 }

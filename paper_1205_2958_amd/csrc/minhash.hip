@@ -582,12 +582,13 @@ struct Pol2U61 {
     static constexpr bool GUARDED = POW2;
     static constexpr bool VARIABLE_NF = POW2;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
         Fn f;
         if constexpr (POW2) {
-            // an unused slot takes a constant whose guard word is not all ones (c0 = c1 = 0 would hit it every time)
-            static_cast<Fn2U61&>(f) = valid ? prep_2u61_neg(c[0], c[1]) : prep_2u61_neg(1ull << 60, 0);
+            // an unused slot takes a constant whose guard word is never all ones (c0 = c1 = 0 would hit it every time)
+            const uint32_t shift = neg_key_shift(a.md.mask);
+            static_cast<Fn2U61&>(f) = valid ? prep_2u61_neg(c[0], c[1], shift) : prep_2u61_neg(P61 - 1, 0, shift);
             f.hz = u32x2{0u, 0u};
         } else {
             static_cast<Fn2U61&>(f) = valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
@@ -873,9 +874,10 @@ __device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint
 
 // 2U, p = 2^61-1, power-of-two D <= 2^31: key_neg_2u61 of mh_arith.h, eight
 // functions on one nonzero, stage by stage: two multiply-adds, the funnel shift
-// H >> 29, one add and one and for the key, one or for the guard word.  The guard
-// words go into two running maxima (m[HASH_FPL], m[HASH_FPL + 1]) right away, two
-// per three-operand maximum; the keys leave in y.
+// H >> 29, one add for the key (the coefficients were rotated so that it needs no
+// shift), one or for the guard word.  The guard words go into two running maxima
+// (m[HASH_FPL], m[HASH_FPL + 1]) right away, two per three-operand maximum; the
+// keys leave in y.
 template <int NF>
 __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t (&m)[HASH_ACC],
                                                uint32_t t, const ModDV& md)
@@ -896,11 +898,11 @@ __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], ui
     for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, H[g], fn[g].e1, t, fn[g].hz);
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
-#pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_add_lshl_u32 %0, %1, %2, %3" : "=v"(y[g]) : "v"(L[g].x), "v"(s[g]), "s"(md.kshift));
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_or_b32 %0, %1, %2" : "=v"(z[g]) : "v"(H[g].x), "v"(md.top3));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %1, %2" : "=v"(y[g]) : "v"(L[g].x), "v"(s[g]));
     issue_priority<1>();
     if (NF & 1) z[NF] = z[NF - 1];
 #pragma unroll

@@ -104,12 +104,14 @@ static void check61(uint64_t D, const uint64_t* c, uint32_t t)
     ++checks;
     if (md.pow2 && D <= (1ull << 31)) {
         // the guarded key of the negated form: exact whenever the guard is not hit
-        GuardedKey61 gk = key_neg_2u61(prep_2u61_neg(c[0], c[1]), t, md.mask);
-        if (gk.guard != GUARD61_HIT && md.mask - gk.key != want)
+        const uint32_t ks61 = neg_key_shift(md.mask);
+        GuardedKey61 gk = key_neg_2u61(prep_2u61_neg(c[0], c[1], ks61), t);
+        const uint32_t loc = finish_neg_key(gk.key, ks61, md.mask);
+        if (gk.guard != GUARD61_HIT && loc != want)
             FAIL("2U61 guarded key D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
-                 (unsigned long long)c[0], (unsigned long long)c[1], md.mask - gk.key, (unsigned long long)want);
+                 (unsigned long long)c[0], (unsigned long long)c[1], loc, (unsigned long long)want);
         if (gk.guard == GUARD61_HIT) ++guard_hits;
-        if (gk.guard == GUARD61_HIT && md.mask - gk.key != want) ++guard_saves;
+        if (gk.guard == GUARD61_HIT && loc != want) ++guard_saves;
         ++checks;
     }
     // 4U with the same prime: Horner form against the power-sum definition
@@ -208,9 +210,14 @@ int main()
                 uint64_t add2 = add + (d << 32);
                 if (add2 > p61) { if (add < (((1ull << 29) - d) << 32) + 1) continue; add2 = add - (((1ull << 29) - d) << 32); }
                 if (add2 < 1 || add2 > p61) continue;
-                uint64_t c[4] = {p61 - add2, p61 - n, rnd() % p61, rnd() % p61};
-                Fn2U61 f = prep_2u61_neg(c[0], c[1]);
-                if (key_neg_2u61(f, t, (uint32_t)(D - 1)).guard != GUARD61_HIT) FAIL("engineered guard case not built");
+                // n and add2 are what the kernel multiplies and adds: the caller's coefficients, negated and
+                // rotated left by the key shift; rotate back and negate to get those
+                const uint32_t ks = neg_key_shift((uint32_t)(D - 1));
+                auto rotr61 = [&](uint64_t v) { return ((v >> ks) | (v << (61u - ks))) & p61; };
+                uint64_t c[4] = {p61 - rotr61(add2), p61 - rotr61(n), rnd() % p61, rnd() % p61};
+                Fn2U61 f = prep_2u61_neg(c[0], c[1], ks);
+                if (((uint64_t)f.e1 << 32 | f.e0) != n || f.add != add2) FAIL("engineered coefficients do not rotate back");
+                if (key_neg_2u61(f, t).guard != GUARD61_HIT) FAIL("engineered guard case not built");
                 check61(D, c, t);
                 ++built;
             }

@@ -232,16 +232,21 @@ def test_m61_fold_carries_engineered():
     """Coefficients chosen so that the 93-bit value behind an evaluation has bits 32..60 all
     ones (or all but one) and the fold's low-word addition lands just below, at and above a
     carry: the cases in which bit 61 of the folded value is set, which random inputs never
-    reach.  Built twice: for W = c1 t + c0 + 1, and for V = (p - c1) t + (p - c0), the value
-    the kernel's fast path for power-of-two D forms; there these are the evaluations whose
+    reach.  Built twice: for W = c1 t + c0 + 1, and for V = 2^shift ((p - c1) t + (p - c0)) mod p
+    taken coefficient by coefficient, the value the kernel's fast path for power-of-two D forms;
+    there these are the evaluations whose
     guard word sends the row to the exact path, and a model of the unguarded key confirms that
     some of them would come out wrong without it."""
     D, p = 1 << 30, W.M61
+    shift = 2                                                   # 32 - log2 D
+
+    def rotr61(v):
+        return v if v == p else ((v >> shift) | (v << (61 - shift))) & p
     ts = [(1 << 29) - 1, (1 << 30) - 1, 12345677, 3]
     rows, n_hit, n_neg, n_unguarded_wrong = [], 0, 0, 0
     for t in ts:
         for A in (1, 5, 1 << 20, (t * (p - 1)) >> 61):
-            for s in (-1, 0, 1, 7):
+            for s in (-1, 0, 1, 3, 7, 11, 255):
                 for middle in ((1 << 61) - (1 << 32), (1 << 61) - (1 << 32) - (1 << 45)):
                     B = (1 << 32) + s - A                       # B + A = 2^32 + s: carry iff s >= 0
                     if not 0 <= B < (1 << 32):
@@ -252,15 +257,16 @@ def test_m61_fold_carries_engineered():
                     if 0 <= c0 < p:
                         rows.append([c0, c1])
                         n_hit += 1
-                    n1 = min(T // t, p - 1)                     # negated form: V = n1 t + add
-                    add = T - n1 * t
+                    n1 = min(T // t, p - 1)                     # the kernel's form: V = n1 t + add, where n1 and
+                    add = T - n1 * t                            # add are the negated coefficients times 2^shift mod p
                     if 1 <= n1 and 1 <= add <= p:
-                        rows.append([p - add, p - n1])
+                        c1, c0 = p - rotr61(n1), p - rotr61(add)
+                        rows.append([c0, c1])
                         n_neg += 1
                         L = (n1 & 0xFFFFFFFF) * t + add
                         H = (n1 >> 32) * t + (L >> 32)
-                        key = ((L & 0xFFFFFFFF) + (H >> 29)) & (D - 1)
-                        want = (((p - n1) * t + (p - add)) % p) % D
+                        key = (((L & 0xFFFFFFFF) + (H >> 29)) & 0xFFFFFFFF) >> shift
+                        want = ((c1 * t + c0) % p) % D
                         n_unguarded_wrong += (D - 1 - key) != want
     assert n_hit >= 60 and n_neg >= 60 and n_unguarded_wrong >= 10
     c = np.array(rows, dtype=np.uint64)
