@@ -158,25 +158,9 @@ MH_HD uint32_t hash_2u31_raw(const Fn2U31& f, uint32_t t2, const ModD& md)
     return reduce_mod_d<false>(y < x ? y : x, md);
 }
 
-// Power-of-two D = mask + 1: the complement  mask - h(t)  of the hashed location.
-// With x in [1, 2^32) congruent to X + 1 and c = x >> 31 the location is
-// (x + c - 1) & mask, so its complement is (-(x + c)) & mask = (s - x) & mask with
-// s = -c the arithmetic shift of x: three half-cost instructions, no "- 1".
-// Keeping the running MAXIMUM of complements and taking mask - max at the end
-// gives the minimum location.
-MH_HD uint32_t m31_complement(uint32_t x, uint32_t mask)
-{
-    uint32_t s = (uint32_t)((int32_t)x >> 31);
-    return (s - x) & mask;
-}
-MH_HD uint32_t hash_compl_2u31(const Fn2U31& f, uint32_t t2, uint32_t mask)
-{
-    return m31_complement(fold_2u31(f, t2), mask);
-}
-
-// Power-of-two D = 2^s again, one instruction shorter: evaluate the NEGATED
-// polynomial.  With c1' = -c1 mod p and the constant p - c0 in [1, p] the folded
-// value x lies in [1, 2p] and is congruent to -X, so its representative in [1, p]
+// Power-of-two D = 2^s: evaluate the NEGATED polynomial.  With c1' = -c1 mod p and
+// the constant p - c0 in [1, p] the folded value x lies in [1, 2p] and is congruent
+// to -X, so its representative in [1, p]
 // is p - (X mod p), whose low s bits are the complement of the hashed location
 // (2^31 - 1 - r = ~r modulo 2^s).  That representative is x for x <= p and
 // x - p = x + 1 - 2^31 otherwise, i.e. x + (x >> 31) modulo 2^s.  Shifting left by
@@ -226,7 +210,6 @@ MH_HD uint32_t finish_rot_key(uint32_t w, uint32_t s, uint32_t mask)
     return mask - (((w >> k) + ((w >> (k - 1u)) & 1u)) & mask);
 }
 MH_HD uint32_t key_rot_2u31(const Fn2U31& f, uint32_t t2, uint32_t s) { return m31_rot_key(fold_2u31(f, t2), s); }
-MH_HD uint32_t key_neg_2u31(const Fn2U31& f, uint32_t t2, uint32_t shift) { return m31_neg_key(fold_2u31(f, t2), shift); }
 MH_HD uint32_t finish_neg_key(uint32_t key, uint32_t shift, uint32_t mask) { return mask - ((key >> shift) & mask); }
 
 // ---------------------------------------------------------------- 4U, p = 2^31 - 1
@@ -285,10 +268,6 @@ MH_HD uint32_t hash_4u31_np2(const Fn4U31& f, const Pow4U31& w, const ModD& md)
     uint32_t x = fold_4u31(f, w);
     uint32_t a = x - 1u, b = x ^ 0x80000000u;
     return reduce_mod_d<false>(b < a ? b : a, md);
-}
-MH_HD uint32_t hash_compl_4u31(const Fn4U31& f, const Pow4U31& w, uint32_t mask)
-{
-    return m31_complement(fold_4u31(f, w), mask);
 }
 // Power-of-two D, negated cubic (see prep_2u31_neg): the centred coefficients change
 // sign (their range is symmetric) and the constant becomes p - c0 in [1, p], so the
