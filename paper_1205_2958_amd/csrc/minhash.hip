@@ -1513,7 +1513,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     if (flags & ~(MINHASH_FLAG_VALIDATE | MINHASH_FLAG_GENERIC_MOD | MINHASH_FLAG_EXACT_FOLD)) return MINHASH_ERR_ARG;
     const bool generic_mod = (flags & MINHASH_FLAG_GENERIC_MOD) != 0;
     if (generic_mod && family != MINHASH_2U_M31 && family != MINHASH_4U_M31) return MINHASH_ERR_ARG;
-    if ((flags & MINHASH_FLAG_EXACT_FOLD) && family != MINHASH_2U_M61) return MINHASH_ERR_ARG;
+    if ((flags & MINHASH_FLAG_EXACT_FOLD) && family != MINHASH_2U_M61 && family != MINHASH_4U_M31) return MINHASH_ERR_ARG;
     if (n_rows == 0) return MINHASH_OK;
     if (!row_ptr || !params || !out) return MINHASH_ERR_ARG;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % MINHASH_WORKSPACE_ALIGN) != 0) return MINHASH_ERR_WORKSPACE;
@@ -1556,7 +1556,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     // 4U, p = 2^31-1: a rotated key asks for a second look once in 2D evaluations, so they are for
     // large D.  2U: never, for t < D (the folded value exceeds 2^31 by less than D - 1 when it does,
     // so its low bits are not all ones), and every power-of-two D takes them.
-    const bool rotated4 = pow2 && D >= (1ull << ROTATED_KEY_MIN_LOG2_D);
+    const bool rotated4 = pow2 && D >= (1ull << ROTATED_KEY_MIN_LOG2_D) && !(flags & MINHASH_FLAG_EXACT_FOLD);
     // 2U with p = 2^61-1: the guarded fast path needs a power-of-two D and t < 2^31
     const bool guarded61 = pow2 && D <= (1ull << 31) && !(flags & MINHASH_FLAG_EXACT_FOLD);
     int nf = HASH_FPL;

@@ -130,3 +130,23 @@ def test_guarded_m61_path_equals_the_exact_fold_on_a_whole_batch():
     idx = col[lo:hi].cpu().numpy().view(np.uint32)
     want = oracle.signatures(np.array([0, hi - lo], dtype=np.int64), idx, w.D, w.k, 32, w.family, params_np)
     assert np.array_equal(outs[0][r].cpu().numpy(), want[0])
+
+
+def test_rotated_4u_keys_equal_the_shifted_ones_on_a_whole_batch():
+    """`large_4u` wraps a rotated key about 19 000 times (once in 2D evaluations), so the values
+    marked doubtful and computed again are spread over the whole batch.  Its full 32-bit minima
+    must equal, row for row, those of the form without a guard."""
+    w = W.WORKLOADS["large_4u"]
+    nnz = w.nnz(0)
+    rp_np = W.row_ptr_from_nnz(nnz)
+    col = W.csr_indices_torch(nnz, w.D, w.data_seed, DEV)
+    rp = torch.from_numpy(rp_np).to(DEV)
+    params = torch.from_numpy(W.coefficients(w.k, w.family, w.param_seed).view(np.int64)).to(DEV)
+    ws = mh.alloc_workspace(len(nnz), int(rp_np[-1]), w.k, w.family, DEV)
+    outs = []
+    for flags in (0, mh.FLAG_EXACT_FOLD):
+        out = torch.full((len(nnz), 4 * w.k), 0xAA, dtype=torch.uint8, device=DEV)
+        mh.minhash_signatures(rp, col, w.D, w.k, 32, w.family, params, out=out, workspace=ws, flags=flags)
+        assert mh.status(ws) == 0
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1])
