@@ -84,7 +84,8 @@ def _pinned_copy(a: np.ndarray) -> torch.Tensor:
 
 
 def run(path: str, prefix: str, k: int, b: int, family_name: str, seed: int, universe: int, batch_rows: int,
-        index_base: int, threads: int, expand: bool, log=print, save_csr_path: str = "") -> dict:
+        index_base: int, threads: int, expand: bool, log=print, save_csr_path: str = "",
+        round_universe: bool = False) -> dict:
     family = FAMILIES[family_name]
     dev = torch.device("cuda:0")
     t0 = time.perf_counter()
@@ -115,6 +116,8 @@ def run(path: str, prefix: str, k: int, b: int, family_name: str, seed: int, uni
             % (n, nnz, max_index, t_parse, size / t_parse / 1e9))
 
     D = universe or (max_index + 1)
+    if round_universe and D & (D - 1) and (1 << (D - 1).bit_length()) < W.family_prime(family):
+        D = 1 << (D - 1).bit_length()
     if max_index >= D:
         raise SystemExit("the data holds index %d, beyond the universe size %d" % (max_index, D))
     if family in (mh.FAMILY_2U_MS32, mh.FAMILY_2U_MS32_HIGH):
@@ -171,6 +174,10 @@ def main(argv=None) -> int:
     ap.add_argument("--index-base", type=int, default=1, choices=[0, 1])
     ap.add_argument("--threads", type=int, default=16)
     ap.add_argument("--expand", action="store_true", help="also write the positions of the ones of the 2^b*k expansion")
+    ap.add_argument("--round-universe", action="store_true",
+                    help="hash into the next power of two above D (the functions then map the indices into a "
+                         "superset of the universe, Section 3.3 assumes D = 2^s anyway): the kernels for "
+                         "power-of-two D are up to twice as fast")
     ap.add_argument("--save-csr", default="", help="also write the parsed data as a binary CSR file; such a file is "
                                                    "accepted as input in place of the text")
     a = ap.parse_args(argv)
@@ -178,7 +185,7 @@ def main(argv=None) -> int:
         print("preprocess needs a GPU", file=sys.stderr)
         return 2
     meta = run(a.input, a.prefix, a.k, a.b, a.family, a.seed, a.universe, a.batch_rows, a.index_base, a.threads,
-               a.expand, save_csr_path=a.save_csr)
+               a.expand, save_csr_path=a.save_csr, round_universe=a.round_universe)
     print(json.dumps(meta))
     return 0
 

@@ -66,3 +66,18 @@ def test_binary_copy_gives_the_same_signatures(tmp_path):
     assert np.array_equal(np.load(str(tmp_path / "b.labels.npy")), labels.astype(np.float32))
     want = oracle.signatures(rp, col, m2["D"], 64, 8, preprocess.FAMILIES["2u"], W.coefficients(64, preprocess.FAMILIES["2u"], 3))
     assert np.array_equal(np.load(str(tmp_path / "b.sig.npy")), want)
+
+
+def test_round_universe_hashes_into_the_next_power_of_two(tmp_path):
+    from paper_1205_2958_amd import preprocess
+
+    nnz = np.array([40, 3, 900], dtype=np.int64)
+    rp = W.row_ptr_from_nnz(nnz)
+    col = (W.csr_indices_np(nnz, 1 << 20, seed=19) % np.uint32(1000003)).astype(np.uint32)
+    src = tmp_path / "data.svm"
+    _write_libsvm(src, rp, col, np.array([1, 1, -1]))
+    meta = preprocess.run(str(src), str(tmp_path / "r"), 64, 8, "4u", 4, 1000003, 8, 1, 2, False, log=lambda *_: None,
+                          round_universe=True)
+    assert meta["D"] == 1 << 20
+    want = oracle.signatures(rp, col, 1 << 20, 64, 8, preprocess.FAMILIES["4u"], W.coefficients(64, preprocess.FAMILIES["4u"], 4))
+    assert np.array_equal(np.load(str(tmp_path / "r.sig.npy")), want)
