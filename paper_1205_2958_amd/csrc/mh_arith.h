@@ -210,6 +210,41 @@ MH_HD uint32_t finish_rot_key(uint32_t w, uint32_t s, uint32_t mask)
     return mask - (((w >> k) + ((w >> (k - 1u)) & 1u)) & mask);
 }
 MH_HD uint32_t key_rot_2u31(const Fn2U31& f, uint32_t t2, uint32_t s) { return m31_rot_key(fold_2u31(f, t2), s); }
+
+// 2U, power-of-two D = 2^s, without any instruction after the fold.  Multiplying by
+// 2^j modulo p = 2^31-1 rotates a 31-bit residue left by j bits, so with both negated
+// coefficients multiplied by 2^(31-s) the s wanted bits (the complement of the hashed
+// location) are the top s bits of the representative in [1, p], and the 31-bit
+// representative itself is an order-preserving key.  The folded x = hi + y is that
+// representative whenever x <= p, i.e. whenever bit 31 of x is clear.  When it is set,
+// the representative is x - p <= hi <= D - 1 (hi = V >> 31 with V < p D for t < D): a
+// small value.  So x is compared as a SIGNED word: evaluations with bit 31 set drop out
+// of the running maximum, and that is right as long as the maximum of the others is at
+// least D - 1.  A running maximum below D - 1 (negative if no evaluation had bit 31
+// clear) marks the value as doubtful; it is then computed again exactly.  With n
+// evaluations behind a value that happens with probability (D / 2^31)^n.
+MH_HD uint32_t rotl31(uint32_t v, uint32_t j)        // v <= p, 0 <= j <= 31: v 2^j modulo p (p stays p)
+{
+    j %= 31u;
+    return j ? ((v << j) | (v >> (31u - j))) & (uint32_t)P31 : v;
+}
+MH_HD uint32_t full_key_rotation(uint32_t mask)     // 31 - s for mask = 2^s - 1
+{
+    uint32_t s = 0;
+    while (s < 32 && ((mask >> s) & 1u)) ++s;
+    return 31u - s;
+}
+MH_HD Fn2U31 prep_2u31_full(uint64_t c0, uint64_t c1, uint32_t rotation)
+{
+    Fn2U31 f;
+    f.c1 = rotl31(c1 ? (uint32_t)(P31 - c1) : 0u, rotation);
+    f.add = 2 * (uint64_t)rotl31((uint32_t)((uint64_t)P31 - c0), rotation);
+    return f;
+}
+MH_HD int32_t key_full_2u31(const Fn2U31& f, uint32_t t2) { return (int32_t)fold_2u31(f, t2); }
+MH_HD bool full_key_doubtful(int32_t key, uint32_t mask) { return key < (int32_t)mask; }                  // mask = D - 1 < 2^30
+MH_HD uint32_t finish_full_key(int32_t key, uint32_t rotation, uint32_t mask) { return mask - (((uint32_t)key >> rotation) & mask); }
+constexpr int32_t FULL_KEY_INIT = INT32_MIN;
 MH_HD uint32_t finish_neg_key(uint32_t key, uint32_t shift, uint32_t mask) { return mask - ((key >> shift) & mask); }
 
 // ---------------------------------------------------------------- 4U, p = 2^31 - 1

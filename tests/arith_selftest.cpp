@@ -24,7 +24,7 @@ static uint64_t ref_poly(const uint64_t* c, int deg, uint64_t p, uint64_t D, uin
     return (uint64_t)(acc % D);
 }
 
-static long checks = 0, guard_hits = 0, guard_saves = 0, rot_flagged = 0;
+static long checks = 0, guard_hits = 0, guard_saves = 0, rot_flagged = 0, full_bit31 = 0, full_doubtful = 0;
 #define FAIL(...) do { printf("MISMATCH " __VA_ARGS__); printf("\n"); exit(1); } while (0)
 
 static void check31(uint64_t D, const uint64_t* c, uint32_t t)
@@ -58,6 +58,22 @@ static void check31(uint64_t D, const uint64_t* c, uint32_t t)
                 ++checks;
             }
             prev_w = w2; prev_s = rs; prev_want = want2; prev_D = D;
+            checks += 2;
+        }
+        // 2U full keys: a key that is not doubtful is exact; a doubtful one either has bit 31 set or lies below D - 1,
+        // and an evaluation with bit 31 set never has a representative above D - 1
+        {
+            const uint32_t rot = full_key_rotation(md.mask);
+            const int32_t fk = key_full_2u31(prep_2u31_full(c[0], c[1], rot), stage_2u31(t));
+            if (fk >= 0 && finish_full_key(fk, rot, md.mask) != want2) FAIL("2U31 full key D=%llu t=%u c=(%llu,%llu)", (unsigned long long)D, t,
+                                                                            (unsigned long long)c[0], (unsigned long long)c[1]);
+            if (fk < 0) {
+                const uint32_t rep = (uint32_t)fk - (uint32_t)P31;             // x - p, the representative in [1, p]
+                if (rep > md.mask) FAIL("2U31 full key: representative %u above D - 1 with bit 31 set, D=%llu t=%u", rep, (unsigned long long)D, t);
+                if (md.mask - ((rep >> rot) & md.mask) != want2) FAIL("2U31 full key: x - p is not the representative D=%llu t=%u", (unsigned long long)D, t);
+                ++full_bit31;
+            }
+            full_doubtful += full_key_doubtful(fk, md.mask);
             checks += 2;
         }
         uint32_t n4 = finish_neg_key(key_neg_4u31(prep_4u31_neg(c[0], c[1], c[2], c[3]), stage_4u31(t), ks), ks, md.mask);
@@ -250,6 +266,7 @@ int main()
             checks += 2;
         }
     }
+    if (full_bit31 < 1000 || full_doubtful < full_bit31) FAIL("full keys: %ld with bit 31 set, %ld doubtful", full_bit31, full_doubtful);
     if (rot_flagged < 1000) FAIL("rotated keys: only %ld flagged evaluations seen", rot_flagged);
     printf("OK %ld\n", checks);
     return 0;
