@@ -57,12 +57,14 @@ enum {
                                          (runtime moduli, Horner form) instead of the Mersenne reduction.  Same
                                          results; exists to measure what Section 3.4 saves ("4U (Mod)" against
                                          "4U (Bit)" in the paper's timing tables)                              */
-#define MINHASH_FLAG_EXACT_FOLD  4u   /* MINHASH_2U_M61 and MINHASH_4U_M31 only: evaluate every row with the
-                                         form of the reduction modulo the Mersenne prime (Section 3.4) that is
-                                         exact evaluation by evaluation, instead of the shorter form that
-                                         marks the rare values it may have got wrong and computes those again.
-                                         Same results; exists so that whole batches of the shorter form can be
-                                         compared with it, and to time the difference                        */
+#define MINHASH_FLAG_EXACT_FOLD  4u   /* MINHASH_2U_M61 and MINHASH_4U_M31 with a power-of-two D only: evaluate
+                                         every row with the form of the reduction modulo the Mersenne prime
+                                         (Section 3.4) that yields the hashed location evaluation by
+                                         evaluation, instead of the shorter forms (2U, p = 2^61-1: a carry-free
+                                         key with a guard word, the rare doubtful values computed again;
+                                         4U: the folded value kept in two running maxima).  Same results;
+                                         exists so that whole batches of the shorter forms can be compared
+                                         with it, and to time the difference                                  */
 #define MINHASH_WORKSPACE_ALIGN  256
 
 /*

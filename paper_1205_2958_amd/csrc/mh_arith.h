@@ -317,7 +317,31 @@ MH_HD Fn4U31 prep_4u31_neg(uint64_t c0, uint64_t c1, uint64_t c2, uint64_t c3)
     return f;
 }
 MH_HD uint32_t key_neg_4u31(const Fn4U31& f, const Pow4U31& w, uint32_t shift) { return m31_neg_key(fold_4u31(f, w), shift); }
-MH_HD uint32_t key_rot_4u31(const Fn4U31& f, const Pow4U31& w, uint32_t s) { return m31_rot_key(fold_4u31(f, w), s); }
+
+// 4U, power-of-two D, without any instruction after the fold and without a guard: the
+// negated coefficients are multiplied by 2^(31-s) as in prep_2u31_full, so that the
+// representative in [1, p] of the folded x is an order-preserving key.  Here x is
+// spread over all of [1, 2p], so neither half can be dropped: the caller keeps two
+// running maxima of x, one comparing signed words (it ends on the largest x <= p, if
+// any) and one comparing unsigned words (it ends on the largest x > p, if any), and
+// the largest representative is the larger of the first and the second minus p.
+MH_HD Fn4U31 prep_4u31_full(uint64_t c0, uint64_t c1, uint64_t c2, uint64_t c3, uint32_t rotation)
+{
+    Fn4U31 f;
+    f.c1 = -m31_centre(rotl31((uint32_t)c1, rotation));
+    f.c2 = -m31_centre(rotl31((uint32_t)c2, rotation));
+    f.c3 = -m31_centre(rotl31((uint32_t)c3, rotation));
+    f.add = 2 * ((uint64_t)rotl31((uint32_t)((uint64_t)P31 - c0), rotation) + K31 * (uint64_t)P31);
+    return f;
+}
+constexpr uint32_t FULL_KEY_INIT_UNSIGNED = 0u;
+MH_HD uint32_t finish_full_keys(int32_t smax, uint32_t umax, uint32_t rotation, uint32_t mask)
+{
+    const uint32_t low = smax > 0 ? (uint32_t)smax : 0u;                          // largest x in [1, p]
+    const uint32_t high = umax > (uint32_t)P31 ? umax - (uint32_t)P31 : 0u;       // largest x in (p, 2p], less p
+    const uint32_t rep = low > high ? low : high;
+    return mask - ((rep >> rotation) & mask);
+}
 
 // ---------------------------------------------------------------- 2U, p = 2^61 - 1
 // W = c1 t + c0 + 1 with c1 = 2^32 e1 + e0, t < 2^31:

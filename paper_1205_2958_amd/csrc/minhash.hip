@@ -52,9 +52,8 @@ constexpr int WAVES_PER_BLOCK = 4;
 constexpr int BLOCK = WAVE * WAVES_PER_BLOCK;
 constexpr int TILE = 256;              // nonzeros staged per wavefront per step (4 per lane)
 constexpr int HASH_FPL = 8;            // hash functions per lane
-constexpr int ROTATED_KEY_MIN_LOG2_D = 20;
 constexpr int FULL_KEY_MAX_LOG2_D = 26;
-constexpr int HASH_ACC = HASH_FPL + 2;     // the running extrema of a lane's functions plus two words a policy may use as guards
+constexpr int HASH_ACC = 2 * HASH_FPL + 2;     // the running extrema of a lane's functions, two words a policy may use as guards, and room for a second set of extrema
 constexpr int HASH_FTILE = WAVE * HASH_FPL;   // 512 functions per wavefront pass
 constexpr int PERM_FPL = 4;            // permutations per lane (one 16-byte load)
 constexpr int PERM_FTILE = WAVE * PERM_FPL;   // 256
@@ -482,6 +481,7 @@ struct Pol2U31 {
     static constexpr bool SHIFTED_KEY = false;
     static constexpr bool ROTATED_KEY = FORM == FORM_ROTATED;
     static constexpr bool FULL_KEY = FORM == FORM_FULL;
+    static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = POW2;            // both keys can say that they may be wrong
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
@@ -524,24 +524,31 @@ struct Pol2U31 {
     static constexpr int DEG = 2;
 };
 
-// ROT (power-of-two D only): rotated keys with their guard instead of shifted keys, one
-// instruction fewer per evaluation; the host picks ROT for D >= 2^20, where a key asks to be
-// looked at again once in 2^21 evaluations or less.
-template <bool POW2, bool ROT = false>
+// FULL (power-of-two D only): the coefficients are rotated so that the folded value itself
+// is the key, kept as a signed and an unsigned running maximum (prep_4u31_full,
+// finish_full_keys): no instruction after the fold, nothing to look at twice.  Without FULL
+// the key is the shifted one of key_neg_4u31, one shift and one add-then-shift after the
+// fold; the host picks it only when asked for the evaluation-by-evaluation form.
+template <bool POW2, bool FULL = false>
 struct Pol4U31 {
-    static_assert(POW2 || !ROT, "rotated keys are for power-of-two D");
+    static_assert(POW2 || !FULL, "full keys are for power-of-two D");
     static constexpr int NW = 3;
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool TRACK_MAX = POW2;
-    static constexpr bool SHIFTED_KEY = POW2 && !ROT;   // the running maximum is a key shifted left by md.kshift
-    static constexpr bool ROTATED_KEY = ROT;            // ... or a rotated key,
-    static constexpr bool FULL_KEY = false;
+    static constexpr bool SHIFTED_KEY = POW2 && !FULL;  // the running maximum is a key shifted left by md.kshift
+    static constexpr bool ROTATED_KEY = false;
+    static constexpr bool FULL_KEY = FULL;              // ... or the folded value itself,
+    static constexpr bool TWO_MAXIMA = FULL;            // kept as a signed and an unsigned maximum
     static constexpr bool SHIFT_END = false;
-    static constexpr bool GUARDED = ROT;                // which can say that it may have wrapped
+    static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn4U31;
-    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
+        if (FULL) {
+            const uint32_t rotation = full_key_rotation(a.md.mask);
+            return valid ? prep_4u31_full(c[0], c[1], c[2], c[3], rotation) : prep_4u31_full(0, 0, 0, 0, rotation);
+        }
         if (POW2) return valid ? prep_4u31_neg(c[0], c[1], c[2], c[3]) : prep_4u31_neg(0, 0, 0, 0);
         return valid ? prep_4u31(c[0], c[1], c[2], c[3]) : prep_4u31(0, 0, 0, 0);
     }
@@ -554,21 +561,9 @@ struct Pol4U31 {
     {
         Pow4U31 p;
         p.t1 = (int32_t)w[0]; p.t2 = (int32_t)w[1]; p.t3 = (int32_t)w[2];
-        if (ROT) return key_rot_4u31(f, p, md.rbits);
+        if (FULL) return fold_4u31(f, p);
         if (POW2) return key_neg_4u31(f, p, md.kshift);
         return hash_4u31_np2(f, p, md);
-    }
-    template <int NF>
-    static __device__ __forceinline__ uint32_t doubtful(const uint32_t (&m)[HASH_ACC], const ModDV& md)
-    {
-        uint32_t bits = 0;
-#pragma unroll
-        for (int r = 0; r < NF; ++r) bits |= rot_key_wrapped(m[r], md.rbits) ? 1u << r : 0u;
-        return bits;
-    }
-    static __device__ __forceinline__ uint32_t exact_hash(const uint64_t* c, uint32_t t, const ModD& md, uint64_t)
-    {
-        return hash_4u31<POW2>(prep_4u31(c[0], c[1], c[2], c[3]), stage_4u31(t), md);
     }
     template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
@@ -596,6 +591,7 @@ struct Pol2U61 {
     static constexpr bool SHIFTED_KEY = POW2;
     static constexpr bool ROTATED_KEY = false;
     static constexpr bool FULL_KEY = false;
+    static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = POW2;
     static constexpr bool VARIABLE_NF = POW2;    // hand-ordered steps exist for 5..8 functions per lane
@@ -644,6 +640,7 @@ struct Pol4U61 {
     static constexpr bool SHIFTED_KEY = false;
     static constexpr bool ROTATED_KEY = false;
     static constexpr bool FULL_KEY = false;
+    static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = false;
@@ -740,8 +737,9 @@ __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
 // 4U, p = 2^31-1, power-of-two D, same idea: three chained multiply-adds per
 // evaluation are issued function-major so that each waits for a result that is
 // 16 instructions old; the fold of nonzero A overlaps the last multiply-adds of
-// nonzero B.  Arithmetic of key_rot_4u31 (mh_arith.h), instruction for instruction.
-template <int NF, bool ROT>
+// nonzero B.  Arithmetic of fold_4u31 (mh_arith.h), instruction for instruction; FULL
+// ends there and keeps two maxima, otherwise key_neg_4u31's two instructions follow.
+template <int NF, bool FULL>
 __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], const uint32_t* w,
                                                uint32_t amount, uint32_t p31)
 {
@@ -767,10 +765,7 @@ __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
     issue_priority<1>();       // one three-operand add (full issue) instead of two simple adds: fewer instructions in all
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_add3_u32 %0, %0, %1, %2" : "+v"(y[g]) : "v"(u[g]), "v"(v[g]));
-    if constexpr (ROT) {       // key_rot_4u31: amount = log2 D
-#pragma unroll
-        for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %0, %0, %1" : "+v"(y[g]) : "s"(amount));
-    } else {                   // key_neg_4u31: amount = 32 - log2 D
+    if constexpr (!FULL) {      // key_neg_4u31: amount = 32 - log2 D; the full key is the folded value as it stands
         issue_priority<0>();
 #pragma unroll
         for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 31, %1" : "=v"(u[g]) : "v"(y[g]));
@@ -780,13 +775,22 @@ __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
     }
 }
 
-template <int NF, bool ROT>
+template <int NF, bool FULL>
 __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC],
                                                const uint32_t* wa, const uint32_t* wb, uint32_t amount, uint32_t p31)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
-    half_4u31_pow2<NF, ROT>(fn, ya, wa, amount, p31);
-    half_4u31_pow2<NF, ROT>(fn, yb, wb, amount, p31);
+    half_4u31_pow2<NF, FULL>(fn, ya, wa, amount, p31);
+    half_4u31_pow2<NF, FULL>(fn, yb, wb, amount, p31);
+    if constexpr (FULL) {
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+            asm volatile("v_max3_i32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+            asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[HASH_FPL + 2 + g]) : "v"(ya[g]), "v"(yb[g]));
+        return;
+    }
 #pragma unroll
     for (int g = 0; g < NF; ++g)
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
@@ -945,6 +949,7 @@ struct PolGenericMod {
     static constexpr bool SHIFTED_KEY = false;
     static constexpr bool ROTATED_KEY = false;
     static constexpr bool FULL_KEY = false;
+    static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = false;
@@ -986,6 +991,7 @@ struct Pol2UMS32 {
     static constexpr bool SHIFTED_KEY = false;
     static constexpr bool ROTATED_KEY = false;
     static constexpr bool FULL_KEY = false;
+    static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = true;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
@@ -1148,6 +1154,10 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 #pragma unroll
         for (int r = 0; r < NF; ++r) m[r] = Pol::FULL_KEY ? (uint32_t)FULL_KEY_INIT : Pol::TRACK_MAX ? 0u : EMPTY_MIN;
         m[HASH_FPL] = m[HASH_FPL + 1] = 0u;
+        if (Pol::TWO_MAXIMA) {
+#pragma unroll
+            for (int r = 0; r < NF; ++r) m[HASH_FPL + 2 + r] = FULL_KEY_INIT_UNSIGNED;
+        }
 
         if (len > 0) {
             uint32_t pad = a.col_idx[begin];
@@ -1192,7 +1202,8 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             if (Pol::TRACK_MAX) {      // back from keys to the minimum location
 #pragma unroll
                 for (int r = 0; r < NF; ++r) {
-                    if (Pol::FULL_KEY) m[r] = finish_full_key((int32_t)m[r], md.frot, md.mask);
+                    if (Pol::TWO_MAXIMA) m[r] = finish_full_keys((int32_t)m[r], m[HASH_FPL + 2 + r], md.frot, md.mask);
+                    else if (Pol::FULL_KEY) m[r] = finish_full_key((int32_t)m[r], md.frot, md.mask);
                     else if (Pol::ROTATED_KEY) m[r] = finish_rot_key(m[r], md.rbits, md.mask);
                     else m[r] = Pol::SHIFTED_KEY ? finish_neg_key(m[r], md.kshift, md.mask) : md.mask - m[r];
                 }
@@ -1587,12 +1598,11 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
 
     const bool perm = family == MINHASH_PERM;
     const bool pow2 = a.md.pow2 != 0;
-    // 4U, p = 2^31-1: a rotated key asks for a second look once in 2D evaluations, so they are for
-    // large D.  2U: never, for t < D (the folded value exceeds 2^31 by less than D - 1 when it does,
-    // so its low bits are not all ones); D <= 2^26 takes the full keys instead, which cost no
-    // instruction after the fold and ask for a second look with probability (D / 2^31)^n for a value
-    // with n evaluations behind it.
-    const bool rotated4 = pow2 && D >= (1ull << ROTATED_KEY_MIN_LOG2_D) && !(flags & MINHASH_FLAG_EXACT_FOLD);
+    // 2U, p = 2^31-1, power-of-two D: full keys for D <= 2^26, where they ask for a second look with
+    // probability (D / 2^31)^n for a value with n evaluations behind it; rotated keys beyond, whose
+    // guard cannot be hit while t < D (the folded value exceeds 2^31 by less than D - 1 when it does,
+    // so its low bits are not all ones).  4U: full keys with two maxima for every power-of-two D.
+    const bool full4 = pow2 && !(flags & MINHASH_FLAG_EXACT_FOLD);
     // 2U with p = 2^61-1: the guarded fast path needs a power-of-two D and t < 2^31
     const bool guarded61 = pow2 && D <= (1ull << 31) && !(flags & MINHASH_FLAG_EXACT_FOLD);
     int nf = HASH_FPL;
@@ -1638,7 +1648,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         else launch_hash<Pol2U31<FORM_ANY_D>>(a, nf, main_blocks, s);
         break;
     case MINHASH_4U_M31:
-        if (rotated4) launch_hash<Pol4U31<true, true>>(a, nf, main_blocks, s);
+        if (full4) launch_hash<Pol4U31<true, true>>(a, nf, main_blocks, s);
         else if (pow2) launch_hash<Pol4U31<true, false>>(a, nf, main_blocks, s);
         else launch_hash<Pol4U31<false>>(a, nf, main_blocks, s);
         break;

@@ -24,7 +24,7 @@ static uint64_t ref_poly(const uint64_t* c, int deg, uint64_t p, uint64_t D, uin
     return (uint64_t)(acc % D);
 }
 
-static long checks = 0, guard_hits = 0, guard_saves = 0, rot_flagged = 0, full_bit31 = 0, full_doubtful = 0;
+static long checks = 0, guard_hits = 0, guard_saves = 0, rot_flagged = 0, full_bit31 = 0, full_doubtful = 0, full4_high = 0;
 #define FAIL(...) do { printf("MISMATCH " __VA_ARGS__); printf("\n"); exit(1); } while (0)
 
 static void check31(uint64_t D, const uint64_t* c, uint32_t t)
@@ -43,7 +43,7 @@ static void check31(uint64_t D, const uint64_t* c, uint32_t t)
         {
             const uint32_t rs = rot_key_bits(md.mask);
             const uint32_t w2 = key_rot_2u31(prep_2u31_neg(c[0], c[1]), stage_2u31(t), rs);
-            const uint32_t w4 = key_rot_4u31(prep_4u31_neg(c[0], c[1], c[2], c[3]), stage_4u31(t), rs);
+            const uint32_t w4 = m31_rot_key(fold_4u31(prep_4u31_neg(c[0], c[1], c[2], c[3]), stage_4u31(t)), rs);   // a value spread over all of [1, 2p]
             if (!rot_key_wrapped(w2, rs) && finish_rot_key(w2, rs, md.mask) != want2) FAIL("2U31 rotated key D=%llu t=%u", (unsigned long long)D, t);
             if (!rot_key_wrapped(w4, rs) && finish_rot_key(w4, rs, md.mask) != want4) FAIL("4U31 rotated key D=%llu t=%u", (unsigned long long)D, t);
             // 2U: for t < D the folded value exceeds 2^31 by less than D - 1, so its key never wraps
@@ -75,6 +75,17 @@ static void check31(uint64_t D, const uint64_t* c, uint32_t t)
             }
             full_doubtful += full_key_doubtful(fk, md.mask);
             checks += 2;
+        }
+        // 4U full keys: either half of [1, 2p] gives the location once reduced to [1, p]
+        {
+            const uint32_t rot = full_key_rotation(md.mask);
+            const uint32_t x = fold_4u31(prep_4u31_full(c[0], c[1], c[2], c[3], rot), stage_4u31(t));
+            if (x == 0 || x > 2u * (uint32_t)P31) FAIL("4U31 full key out of range");
+            const uint32_t got = (int32_t)x > 0 ? finish_full_keys((int32_t)x, FULL_KEY_INIT_UNSIGNED, rot, md.mask)
+                                                : finish_full_keys(FULL_KEY_INIT, x, rot, md.mask);
+            if (got != want4) FAIL("4U31 full key D=%llu t=%u", (unsigned long long)D, t);
+            full4_high += (int32_t)x < 0;
+            ++checks;
         }
         uint32_t n4 = finish_neg_key(key_neg_4u31(prep_4u31_neg(c[0], c[1], c[2], c[3]), stage_4u31(t), ks), ks, md.mask);
         if (n4 != want4) FAIL("4U31 negated key D=%llu t=%u c=(%llu,%llu,%llu,%llu) got %u want %llu", (unsigned long long)D, t,
@@ -267,6 +278,7 @@ int main()
         }
     }
     if (full_bit31 < 1000 || full_doubtful < full_bit31) FAIL("full keys: %ld with bit 31 set, %ld doubtful", full_bit31, full_doubtful);
+    if (full4_high < 100000) FAIL("4U full keys: only %ld evaluations above p", full4_high);
     if (rot_flagged < 1000) FAIL("rotated keys: only %ld flagged evaluations seen", rot_flagged);
     printf("OK %ld\n", checks);
     return 0;

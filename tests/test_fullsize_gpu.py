@@ -132,10 +132,10 @@ def test_guarded_m61_path_equals_the_exact_fold_on_a_whole_batch():
     assert np.array_equal(outs[0][r].cpu().numpy(), want[0])
 
 
-def test_rotated_4u_keys_equal_the_shifted_ones_on_a_whole_batch():
-    """`large_4u` wraps a rotated key about 19 000 times (once in 2D evaluations), so the values
-    marked doubtful and computed again are spread over the whole batch.  Its full 32-bit minima
-    must equal, row for row, those of the form without a guard."""
+def test_4u_full_keys_equal_the_shifted_ones_on_a_whole_batch():
+    """`large_4u` with the folded values kept in a signed and an unsigned running maximum (the
+    default for power-of-two D) against the same batch with the shifted keys that are formed
+    evaluation by evaluation: full 32-bit minima, row for row."""
     w = W.WORKLOADS["large_4u"]
     nnz = w.nnz(0)
     rp_np = W.row_ptr_from_nnz(nnz)

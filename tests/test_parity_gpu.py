@@ -129,7 +129,7 @@ def test_bit_widths_and_unaligned_rows(b):
 
 
 @pytest.mark.parametrize("family", [mh.FAMILY_2U_M31, mh.FAMILY_4U_M31, mh.FAMILY_2U_M61, mh.FAMILY_4U_M61])
-@pytest.mark.parametrize("D", [1, 2, 1 << 10, 1 << 20, 1 << 30, 3, 1000003, 16609143, 1010017424])
+@pytest.mark.parametrize("D", [1, 2, 1 << 10, 1 << 20, 1 << 26, 1 << 27, 1 << 30, 3, 1000003, 16609143, 1010017424])
 def test_universe_sizes_including_non_powers_of_two(family, D):
     nnz = np.minimum(np.array([0, 1, 2, 5, 64, 300, 1000, 9000], dtype=np.int64), D)
     if D & (D - 1):
@@ -484,13 +484,13 @@ def test_call_is_capturable_in_a_hip_graph_and_replays_exactly():
 
 
 @pytest.mark.parametrize("family", [mh.FAMILY_2U_M31, mh.FAMILY_4U_M31])
-def test_rotated_key_wraps_engineered(family):
-    """The kernels for p = 2^31-1 keep rotated keys (4U: for D >= 2^20), which are right unless
-    an evaluation hashes to D - 1 while its folded value has bit 31 set; the running maximum then
-    says so and the value is computed again.  Rows built to contain, for most functions, an index
-    that hashes to D - 1 among ordinary ones: all of [0, D) is scanned per function.  For 4U about
-    half of them have bit 31 set; for 2U none can (the folded value of an index below D exceeds
-    2^31 by less than D - 1), which the model below confirms."""
+def test_indices_that_hash_to_the_last_location_engineered(family):
+    """The kernels for p = 2^31-1 and power-of-two D keep keys whose edge cases sit at the hashed
+    location D - 1 (complement 0, representative p or 2^s aligned): rows built to contain, for
+    most functions, an index that hashes to D - 1 among ordinary ones; all of [0, D) is scanned per
+    function.  For 2U the folded value of such an index never has bit 31 set (an index below D
+    makes it exceed 2^31 by less than D - 1), which the model below confirms; 2U values whose
+    other evaluations all fall below D - 1 are the ones computed again."""
     D, p, k = 1 << 20, W.M31, 96
     deg = W.family_degree(family)
     c = W.coefficients(k, family, seed=91)
