@@ -183,34 +183,6 @@ MH_HD uint32_t neg_key_shift(uint32_t mask)          // 32 - s for mask = 2^s - 
 }
 MH_HD uint32_t m31_neg_key(uint32_t x, uint32_t shift) { return (x + (x >> 31)) << shift; }
 
-// The same key in one instruction less, with a guard.  Rotating x right by s bits
-// (a funnel shift of x with itself) puts its low s bits y on top, then c = x >> 31,
-// then the rest: [y][c][...].  The value wanted is y + c, and comparing rotated
-// words compares y + c/2 (plus less than half a unit): whenever y + c differs
-// between two evaluations, their rotated words are ordered the same way, so the
-// running maximum of rotated words ends on an evaluation that attains the maximum
-// of y + c, which is then read off it as (w >> k) + ((w >> (k-1)) & 1), k = 32 - s.
-// The exception is y = 2^s - 1 with c = 1, where y + c wraps to 0 modulo 2^s (the
-// smallest value) while its rotated word is among the largest.  Such a word has its
-// top s+1 bits all ones, and no other word does: a running maximum of that form
-// says that the evaluations behind it have to be looked at again with the exact
-// arithmetic (one evaluation in 2^(s+1)), any other maximum is right as it stands.
-// For s = 0 the arithmetic runs with s = 1 and the final mask clears the bit.
-MH_HD uint32_t rot_key_bits(uint32_t mask)
-{
-    uint32_t s = 0;
-    while (s < 32 && ((mask >> s) & 1u)) ++s;
-    return s == 0 ? 1u : s;
-}
-MH_HD uint32_t m31_rot_key(uint32_t x, uint32_t s) { return (x >> s) | (x << (32u - s)); }          // 1 <= s <= 30
-MH_HD bool rot_key_wrapped(uint32_t w, uint32_t s) { return (w >> (31u - s)) == (2u << s) - 1u; }
-MH_HD uint32_t finish_rot_key(uint32_t w, uint32_t s, uint32_t mask)
-{
-    const uint32_t k = 32u - s;
-    return mask - (((w >> k) + ((w >> (k - 1u)) & 1u)) & mask);
-}
-MH_HD uint32_t key_rot_2u31(const Fn2U31& f, uint32_t t2, uint32_t s) { return m31_rot_key(fold_2u31(f, t2), s); }
-
 // 2U, power-of-two D = 2^s, without any instruction after the fold.  Multiplying by
 // 2^j modulo p = 2^31-1 rotates a 31-bit residue left by j bits, so with both negated
 // coefficients multiplied by 2^(31-s) the s wanted bits (the complement of the hashed

@@ -241,7 +241,6 @@ struct ModDV : ModD {
     uint32_t negD;   // 2^32 - D
     uint32_t top3;   // 0xE0000000
     uint32_t kshift; // 32 - log2 D: left shift of the order-preserving keys of the negated forms
-    uint32_t rbits;  // log2 D (at least 1): right rotation of the rotated keys
     uint32_t frot;   // 31 - log2 D: what the coefficients of the full-key form are rotated by
 };
 __device__ __forceinline__ ModDV vector_constants(const ModD& src)
@@ -258,7 +257,6 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
     v.negD = in_vgpr_if_used(0u - src.D);
     v.top3 = in_vgpr_if_used(0xE0000000u);
     v.kshift = src.pow2 ? neg_key_shift(src.mask) : 0u;
-    v.rbits = src.pow2 ? rot_key_bits(src.mask) : 1u;
     v.frot = src.pow2 ? full_key_rotation(src.mask) : 0u;
     return v;
 }
@@ -467,11 +465,12 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // the kernel folds into a running extremum: the hashed location itself (running
 // minimum), or, when TRACK_MAX, its complement mask - h(t) (running maximum),
 // which saves one instruction per evaluation for power-of-two D.
-// FORM 0: any D, exact quotient.  Power-of-two D: FORM 1 keeps rotated keys (m31_rot_key),
-// whose guard cannot be hit as long as t < D (see the launch code); FORM 2 keeps the folded
-// value itself as a signed key (key_full_2u31), which needs no instruction after the fold but
-// more second looks the closer D is to p, so the host picks it for D <= 2^26.
-constexpr int FORM_ANY_D = 0, FORM_ROTATED = 1, FORM_FULL = 2;
+// FORM_ANY_D: exact quotient.  Power-of-two D: the coefficients are rotated so that the folded
+// value itself is the key (prep_2u31_full).  FORM_FULL keeps one signed running maximum
+// (key_full_2u31), which needs no instruction after the fold but a second look at a value with
+// probability (D / 2^31)^n, n the evaluations behind it, so the host picks it for D <= 2^26;
+// FORM_FULL_TWO keeps a signed and an unsigned maximum (finish_full_keys), nothing to look at twice.
+constexpr int FORM_ANY_D = 0, FORM_FULL_TWO = 1, FORM_FULL = 2;
 template <int FORM>
 struct Pol2U31 {
     static constexpr bool POW2 = FORM != FORM_ANY_D;
@@ -479,27 +478,22 @@ struct Pol2U31 {
     static constexpr int MIN_WAVES = POW2 ? 5 : 4;   // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = false;
-    static constexpr bool ROTATED_KEY = FORM == FORM_ROTATED;
-    static constexpr bool FULL_KEY = FORM == FORM_FULL;
-    static constexpr bool TWO_MAXIMA = false;
+    static constexpr bool FULL_KEY = POW2;
+    static constexpr bool TWO_MAXIMA = FORM == FORM_FULL_TWO;
     static constexpr bool SHIFT_END = false;
-    static constexpr bool GUARDED = POW2;            // both keys can say that they may be wrong
+    static constexpr bool GUARDED = FORM == FORM_FULL;   // a single maximum can say that it may be wrong
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn2U31;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
-        if (FORM == FORM_FULL) {
-            const uint32_t rotation = full_key_rotation(a.md.mask);
-            return valid ? prep_2u31_full(c[0], c[1], rotation) : prep_2u31_full(0, 0, rotation);
-        }
         if (!POW2) return valid ? prep_2u31_raw(c[0], c[1]) : prep_2u31_raw(0, 0);
-        return valid ? prep_2u31_neg(c[0], c[1]) : prep_2u31_neg(0, 0);
+        const uint32_t rotation = full_key_rotation(a.md.mask);
+        return valid ? prep_2u31_full(c[0], c[1], rotation) : prep_2u31_full(0, 0, rotation);
     }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = stage_2u31(t); }
     static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModDV& md, uint64_t)
     {
-        if (FORM == FORM_FULL) return (uint32_t)key_full_2u31(f, w[0]);
-        if (POW2) return key_rot_2u31(f, w[0], md.rbits);
+        if (POW2) return (uint32_t)key_full_2u31(f, w[0]);
         return hash_2u31_raw(f, w[0], md);
     }
     template <int NF>
@@ -507,10 +501,7 @@ struct Pol2U31 {
     {
         uint32_t bits = 0;
 #pragma unroll
-        for (int r = 0; r < NF; ++r) {
-            const bool d = FORM == FORM_FULL ? full_key_doubtful((int32_t)m[r], md.mask) : rot_key_wrapped(m[r], md.rbits);
-            bits |= d ? 1u << r : 0u;
-        }
+        for (int r = 0; r < NF; ++r) bits |= full_key_doubtful((int32_t)m[r], md.mask) ? 1u << r : 0u;
         return bits;
     }
     // the hashed location from the definition's arithmetic (canonical residue, then mod D)
@@ -536,7 +527,6 @@ struct Pol4U31 {
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = POW2 && !FULL;  // the running maximum is a key shifted left by md.kshift
-    static constexpr bool ROTATED_KEY = false;
     static constexpr bool FULL_KEY = FULL;              // ... or the folded value itself,
     static constexpr bool TWO_MAXIMA = FULL;            // kept as a signed and an unsigned maximum
     static constexpr bool SHIFT_END = false;
@@ -589,7 +579,6 @@ struct Pol2U61 {
     static constexpr int MIN_WAVES = POW2 ? 4 : 5;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = POW2;
-    static constexpr bool ROTATED_KEY = false;
     static constexpr bool FULL_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
@@ -638,7 +627,6 @@ struct Pol4U61 {
     static constexpr int MIN_WAVES = 2;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
-    static constexpr bool ROTATED_KEY = false;
     static constexpr bool FULL_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
@@ -698,12 +686,11 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // nothing go beside it.  The eight evaluations of one nonzero are therefore
 // emitted stage by stage, so that neighbouring instructions never depend on each
 // other: eight multiply-adds at raised priority, sixteen simple instructions at
-// the normal one, eight funnel shifts at raised priority again (see
-// issue_priority); two such halves, then eight three-operand maxima.  The
-// arithmetic is key_rot_2u31 of mh_arith.h, instruction for instruction; FULL
-// (key_full_2u31) leaves the funnel shifts out and compares signed words.
-template <int NF, bool FULL>
-__device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&x)[HASH_FPL], uint32_t t, uint32_t rbits)
+// the normal one (see issue_priority); two such halves, then eight three-operand
+// signed maxima (and eight unsigned ones when two maxima are kept).  The
+// arithmetic is key_full_2u31 of mh_arith.h, instruction for instruction.
+template <int NF>
+__device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&x)[HASH_FPL], uint32_t t)
 {
     uint64_t p[HASH_FPL];
     issue_priority<1>();
@@ -715,22 +702,20 @@ __device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"((uint32_t)(p[g] >> 32)));
     issue_priority<1>();
-    if constexpr (!FULL) {     // key_rot_2u31; the full key is the folded value as it stands
-#pragma unroll
-        for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %0, %0, %1" : "+v"(x[g]) : "s"(rbits));
-    }
 }
-template <int NF, bool FULL>
-__device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta,
-                                               uint32_t tb, uint32_t rbits)
+template <int NF, bool TWO>
+__device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta, uint32_t tb)
 {
     uint32_t xa[HASH_FPL], xb[HASH_FPL];
-    half_2u31_pow2<NF, FULL>(fn, xa, ta, rbits);
-    half_2u31_pow2<NF, FULL>(fn, xb, tb, rbits);
+    half_2u31_pow2<NF>(fn, xa, ta);
+    half_2u31_pow2<NF>(fn, xb, tb);
 #pragma unroll
-    for (int g = 0; g < NF; ++g) {
-        if constexpr (FULL) asm volatile("v_max3_i32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
-        else asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
+    for (int g = 0; g < NF; ++g)
+        asm volatile("v_max3_i32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
+    if constexpr (TWO) {
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+            asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[HASH_FPL + 2 + g]) : "v"(xa[g]), "v"(xb[g]));
     }
 }
 
@@ -947,7 +932,6 @@ struct PolGenericMod {
     static constexpr int MIN_WAVES = 3;        // no spills, so that the ablation times the arithmetic only
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
-    static constexpr bool ROTATED_KEY = false;
     static constexpr bool FULL_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
@@ -989,7 +973,6 @@ struct Pol2UMS32 {
     static constexpr int MIN_WAVES = 5;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
-    static constexpr bool ROTATED_KEY = false;
     static constexpr bool FULL_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = true;
@@ -1025,17 +1008,17 @@ struct Pol2UMS32 {
 
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol2U31<FORM_ROTATED>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                            const uint32_t* wb, const ModDV& md, uint64_t)
+__device__ __forceinline__ void Pol2U31<FORM_FULL_TWO>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                             const uint32_t* wb, const ModDV&, uint64_t)
 {
-    pair_2u31_pow2<NF, false>(fn, m, wa[0], wb[0], md.rbits);
+    pair_2u31_pow2<NF, true>(fn, m, wa[0], wb[0]);
 }
 template <>
 template <int NF>
 __device__ __forceinline__ void Pol2U31<FORM_FULL>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                         const uint32_t* wb, const ModDV& md, uint64_t)
+                                                         const uint32_t* wb, const ModDV&, uint64_t)
 {
-    pair_2u31_pow2<NF, true>(fn, m, wa[0], wb[0], md.rbits);
+    pair_2u31_pow2<NF, false>(fn, m, wa[0], wb[0]);
 }
 template <>
 template <int NF>
@@ -1050,7 +1033,7 @@ template <int NF>
 __device__ __forceinline__ void Pol4U31<true, true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                           const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_4u31_pow2<NF, true>(fn, m, wa, wb, md.rbits, md.p31);
+    pair_4u31_pow2<NF, true>(fn, m, wa, wb, 0u, md.p31);
 }
 template <>
 template <int NF>
@@ -1204,7 +1187,6 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                 for (int r = 0; r < NF; ++r) {
                     if (Pol::TWO_MAXIMA) m[r] = finish_full_keys((int32_t)m[r], m[HASH_FPL + 2 + r], md.frot, md.mask);
                     else if (Pol::FULL_KEY) m[r] = finish_full_key((int32_t)m[r], md.frot, md.mask);
-                    else if (Pol::ROTATED_KEY) m[r] = finish_rot_key(m[r], md.rbits, md.mask);
                     else m[r] = Pol::SHIFTED_KEY ? finish_neg_key(m[r], md.kshift, md.mask) : md.mask - m[r];
                 }
             }
@@ -1598,10 +1580,9 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
 
     const bool perm = family == MINHASH_PERM;
     const bool pow2 = a.md.pow2 != 0;
-    // 2U, p = 2^31-1, power-of-two D: full keys for D <= 2^26, where they ask for a second look with
-    // probability (D / 2^31)^n for a value with n evaluations behind it; rotated keys beyond, whose
-    // guard cannot be hit while t < D (the folded value exceeds 2^31 by less than D - 1 when it does,
-    // so its low bits are not all ones).  4U: full keys with two maxima for every power-of-two D.
+    // 2U, p = 2^31-1, power-of-two D: one signed maximum for D <= 2^26, where a value asks for a
+    // second look with probability (D / 2^31)^n, n the evaluations behind it; two maxima beyond.
+    // 4U: two maxima for every power-of-two D.
     const bool full4 = pow2 && !(flags & MINHASH_FLAG_EXACT_FOLD);
     // 2U with p = 2^61-1: the guarded fast path needs a power-of-two D and t < 2^31
     const bool guarded61 = pow2 && D <= (1ull << 31) && !(flags & MINHASH_FLAG_EXACT_FOLD);
@@ -1644,7 +1625,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     case -MINHASH_4U_M31 - 1: launch_hash<PolGenericMod<4>>(a, nf, main_blocks, s); break;
     case MINHASH_2U_M31:
         if (pow2 && D <= (1ull << FULL_KEY_MAX_LOG2_D)) launch_hash<Pol2U31<FORM_FULL>>(a, nf, main_blocks, s);
-        else if (pow2) launch_hash<Pol2U31<FORM_ROTATED>>(a, nf, main_blocks, s);
+        else if (pow2) launch_hash<Pol2U31<FORM_FULL_TWO>>(a, nf, main_blocks, s);
         else launch_hash<Pol2U31<FORM_ANY_D>>(a, nf, main_blocks, s);
         break;
     case MINHASH_4U_M31:

@@ -24,7 +24,7 @@ static uint64_t ref_poly(const uint64_t* c, int deg, uint64_t p, uint64_t D, uin
     return (uint64_t)(acc % D);
 }
 
-static long checks = 0, guard_hits = 0, guard_saves = 0, rot_flagged = 0, full_bit31 = 0, full_doubtful = 0, full4_high = 0;
+static long checks = 0, guard_hits = 0, guard_saves = 0, full_bit31 = 0, full_doubtful = 0, full4_high = 0;
 #define FAIL(...) do { printf("MISMATCH " __VA_ARGS__); printf("\n"); exit(1); } while (0)
 
 static void check31(uint64_t D, const uint64_t* c, uint32_t t)
@@ -39,27 +39,6 @@ static void check31(uint64_t D, const uint64_t* c, uint32_t t)
         g2 = hash_2u31<true>(f2, stage_2u31(t), md);
         g4 = hash_4u31<true>(f4, stage_4u31(t), md);
         const uint32_t ks = neg_key_shift(md.mask);
-        // rotated keys: exact unless the word says that it may have wrapped, and then the location is D - 1
-        {
-            const uint32_t rs = rot_key_bits(md.mask);
-            const uint32_t w2 = key_rot_2u31(prep_2u31_neg(c[0], c[1]), stage_2u31(t), rs);
-            const uint32_t w4 = m31_rot_key(fold_4u31(prep_4u31_neg(c[0], c[1], c[2], c[3]), stage_4u31(t)), rs);   // a value spread over all of [1, 2p]
-            if (!rot_key_wrapped(w2, rs) && finish_rot_key(w2, rs, md.mask) != want2) FAIL("2U31 rotated key D=%llu t=%u", (unsigned long long)D, t);
-            if (!rot_key_wrapped(w4, rs) && finish_rot_key(w4, rs, md.mask) != want4) FAIL("4U31 rotated key D=%llu t=%u", (unsigned long long)D, t);
-            // 2U: for t < D the folded value exceeds 2^31 by less than D - 1, so its key never wraps
-            if (rot_key_wrapped(w2, rs) && D > 1) FAIL("2U31 rotated key flagged D=%llu t=%u", (unsigned long long)D, t);
-            if (rot_key_wrapped(w4, rs) && D > 1 && want4 != md.mask) FAIL("4U31 rotated key flagged without a wrap D=%llu t=%u", (unsigned long long)D, t);
-            rot_flagged += rot_key_wrapped(w2, rs) + rot_key_wrapped(w4, rs);
-            // order: of two unflagged evaluations, the one with the smaller location has the larger word
-            static uint32_t prev_w = 0, prev_s = 0; static uint64_t prev_want = 0, prev_D = 0;
-            if (prev_D == D && prev_s == rs && !rot_key_wrapped(w2, rs) && !rot_key_wrapped(prev_w, rs)) {
-                if (want2 < prev_want && !(w2 > prev_w)) FAIL("rotated key order D=%llu", (unsigned long long)D);
-                if (want2 > prev_want && !(w2 < prev_w)) FAIL("rotated key order D=%llu", (unsigned long long)D);
-                ++checks;
-            }
-            prev_w = w2; prev_s = rs; prev_want = want2; prev_D = D;
-            checks += 2;
-        }
         // 2U full keys: a key that is not doubtful is exact; a doubtful one either has bit 31 set or lies below D - 1,
         // and an evaluation with bit 31 set never has a representative above D - 1
         {
@@ -73,6 +52,10 @@ static void check31(uint64_t D, const uint64_t* c, uint32_t t)
                 if (md.mask - ((rep >> rot) & md.mask) != want2) FAIL("2U31 full key: x - p is not the representative D=%llu t=%u", (unsigned long long)D, t);
                 ++full_bit31;
             }
+            // the same value through the two-maxima finish, which D > 2^26 uses
+            const uint32_t two = fk > 0 ? finish_full_keys(fk, FULL_KEY_INIT_UNSIGNED, rot, md.mask)
+                                        : finish_full_keys(FULL_KEY_INIT, (uint32_t)fk, rot, md.mask);
+            if (two != want2) FAIL("2U31 two-maxima finish D=%llu t=%u", (unsigned long long)D, t);
             full_doubtful += full_key_doubtful(fk, md.mask);
             checks += 2;
         }
@@ -279,7 +262,6 @@ int main()
     }
     if (full_bit31 < 1000 || full_doubtful < full_bit31) FAIL("full keys: %ld with bit 31 set, %ld doubtful", full_bit31, full_doubtful);
     if (full4_high < 100000) FAIL("4U full keys: only %ld evaluations above p", full4_high);
-    if (rot_flagged < 1000) FAIL("rotated keys: only %ld flagged evaluations seen", rot_flagged);
     printf("OK %ld\n", checks);
     return 0;
 }
