@@ -42,7 +42,7 @@ from paper_1205_2958_amd import workloads as W  # noqa: E402
 #     multiply + max(full, (full + simple) / 2)
 # issue slots per evaluation, one slot = one 64-lane instruction at 16 lanes/clk/SIMD.
 ISSUE_MIX = {
-    W.FAMILY_2U_M31: (1.0, 0.5, 2.0),               # mad | half a max3 | shr,add
+    W.FAMILY_2U_M31: (1.0, 0.5 + 0.5, 1.0),         # mad | half a shift-then-add, half a max3 | half of add,add
     W.FAMILY_4U_M31: (3.0, 1.0 + 0.5 + 0.5, 3.0),   # 3 mad | add3, half a signed and half an unsigned max3 | shr,and,shr
     W.FAMILY_2U_M61: (2.0, 1.0 + 0.5 + 0.5, 3.0),   # 2 mad | funnel shift, half a max3 each for key and guard | mov,or,add
     W.FAMILY_2U_MS32: (1.0, 0.5, 0.0),              # mad | half a min3 (mask or shift once per row)
@@ -64,7 +64,7 @@ HBM_PEAK = 8.0e12
 # HBM bytes per launch of the dominant kernel on the full workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for a plain 1 GiB streaming kernel
 # (profiles/mh_hash_kernel_2u_m31__large_2u.txt, profiles/mh_perm_kernel__perm_table.txt).
-MEASURED_TRAFFIC_BYTES = {"large_2u": 6.082e9, "perm_table": 1.1654e12}
+MEASURED_TRAFFIC_BYTES = {"large_2u": 6.087e9, "perm_table": 1.1654e12}
 
 
 def _oracle_worker(args):

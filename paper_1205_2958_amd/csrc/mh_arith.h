@@ -183,18 +183,14 @@ MH_HD uint32_t neg_key_shift(uint32_t mask)          // 32 - s for mask = 2^s - 
 }
 MH_HD uint32_t m31_neg_key(uint32_t x, uint32_t shift) { return (x + (x >> 31)) << shift; }
 
-// 2U, power-of-two D = 2^s, without any instruction after the fold.  Multiplying by
-// 2^j modulo p = 2^31-1 rotates a 31-bit residue left by j bits, so with both negated
+// 2U, power-of-two D = 2^s, with the folded value as the key.  Multiplying by 2^j
+// modulo p = 2^31-1 rotates a 31-bit residue left by j bits, so with both negated
 // coefficients multiplied by 2^(31-s) the s wanted bits (the complement of the hashed
 // location) are the top s bits of the representative in [1, p], and the 31-bit
 // representative itself is an order-preserving key.  The folded x = hi + y is that
 // representative whenever x <= p, i.e. whenever bit 31 of x is clear.  When it is set,
 // the representative is x - p <= hi <= D - 1 (hi = V >> 31 with V < p D for t < D): a
-// small value.  So x is compared as a SIGNED word: evaluations with bit 31 set drop out
-// of the running maximum, and that is right as long as the maximum of the others is at
-// least D - 1.  A running maximum below D - 1 (negative if no evaluation had bit 31
-// clear) marks the value as doubtful; it is then computed again exactly.  With n
-// evaluations behind a value that happens with probability (D / 2^31)^n.
+// small value.
 MH_HD uint32_t rotl31(uint32_t v, uint32_t j)        // v <= p, 0 <= j <= 31: v 2^j modulo p (p stays p)
 {
     j %= 31u;
@@ -213,9 +209,24 @@ MH_HD Fn2U31 prep_2u31_full(uint64_t c0, uint64_t c1, uint32_t rotation)
     f.add = 2 * (uint64_t)rotl31((uint32_t)((uint64_t)P31 - c0), rotation);
     return f;
 }
+// x itself, for callers that keep a signed and an unsigned running maximum of it
+// (finish_full_keys, further down): nothing is ever doubtful then.
 MH_HD int32_t key_full_2u31(const Fn2U31& f, uint32_t t2) { return (int32_t)fold_2u31(f, t2); }
-MH_HD bool full_key_doubtful(int32_t key, uint32_t mask) { return key < (int32_t)mask; }                  // mask = D - 1 < 2^30
-MH_HD uint32_t finish_full_key(int32_t key, uint32_t rotation, uint32_t mask) { return mask - (((uint32_t)key >> rotation) & mask); }
+// One running maximum is enough if x is doubled: 2x modulo 2^32 = 2 hi + lo (lo = 2y is
+// even) is 2x exactly for x <= p, and for x > p it wraps to 2 (x - 2^31) =
+// 2 (representative - 1) <= 2 (D - 2).  So an UNSIGNED running maximum of at least
+// 2 (D - 1) ends on an evaluation with x <= p and is exact; a smaller one marks the
+// value as doubtful, and it is then computed again exactly.  With n evaluations behind
+// a value that happens with probability (D / 2^31)^n.  The doubled key can be formed
+// with two simple instructions (hi + hi, + lo) or with one shift-then-add; the kernel
+// uses one form for each nonzero of a pair, which balances its instruction classes.
+MH_HD uint32_t key_full2_2u31(const Fn2U31& f, uint32_t t2)
+{
+    const uint64_t w2 = (uint64_t)f.c1 * t2 + f.add;
+    return ((uint32_t)(w2 >> 32) << 1) + (uint32_t)w2;
+}
+MH_HD bool full2_key_doubtful(uint32_t key, uint32_t mask) { return key < 2u * mask; }                     // mask = D - 1 < 2^30
+MH_HD uint32_t finish_full2_key(uint32_t key, uint32_t rotation, uint32_t mask) { return mask - ((key >> (rotation + 1u)) & mask); }
 constexpr int32_t FULL_KEY_INIT = INT32_MIN;
 MH_HD uint32_t finish_neg_key(uint32_t key, uint32_t shift, uint32_t mask) { return mask - ((key >> shift) & mask); }
 

@@ -466,10 +466,10 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // minimum), or, when TRACK_MAX, its complement mask - h(t) (running maximum),
 // which saves one instruction per evaluation for power-of-two D.
 // FORM_ANY_D: exact quotient.  Power-of-two D: the coefficients are rotated so that the folded
-// value itself is the key (prep_2u31_full).  FORM_FULL keeps one signed running maximum
-// (key_full_2u31), which needs no instruction after the fold but a second look at a value with
-// probability (D / 2^31)^n, n the evaluations behind it, so the host picks it for D <= 2^26;
-// FORM_FULL_TWO keeps a signed and an unsigned maximum (finish_full_keys), nothing to look at twice.
+// value itself is the key (prep_2u31_full).  FORM_FULL keeps one unsigned running maximum of the
+// doubled value (key_full2_2u31), which needs a second look at a value with probability
+// (D / 2^31)^n, n the evaluations behind it, so the host picks it for D <= 2^26; FORM_FULL_TWO
+// keeps a signed and an unsigned maximum of the value (finish_full_keys), nothing to look at twice.
 constexpr int FORM_ANY_D = 0, FORM_FULL_TWO = 1, FORM_FULL = 2;
 template <int FORM>
 struct Pol2U31 {
@@ -478,7 +478,7 @@ struct Pol2U31 {
     static constexpr int MIN_WAVES = POW2 ? 5 : 4;   // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = false;
-    static constexpr bool FULL_KEY = POW2;
+    static constexpr bool DOUBLED_KEY = FORM == FORM_FULL;   // one unsigned maximum of twice the folded value
     static constexpr bool TWO_MAXIMA = FORM == FORM_FULL_TWO;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = FORM == FORM_FULL;   // a single maximum can say that it may be wrong
@@ -493,6 +493,7 @@ struct Pol2U31 {
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = stage_2u31(t); }
     static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModDV& md, uint64_t)
     {
+        if (FORM == FORM_FULL) return key_full2_2u31(f, w[0]);
         if (POW2) return (uint32_t)key_full_2u31(f, w[0]);
         return hash_2u31_raw(f, w[0], md);
     }
@@ -501,7 +502,7 @@ struct Pol2U31 {
     {
         uint32_t bits = 0;
 #pragma unroll
-        for (int r = 0; r < NF; ++r) bits |= full_key_doubtful((int32_t)m[r], md.mask) ? 1u << r : 0u;
+        for (int r = 0; r < NF; ++r) bits |= full2_key_doubtful(m[r], md.mask) ? 1u << r : 0u;
         return bits;
     }
     // the hashed location from the definition's arithmetic (canonical residue, then mod D)
@@ -527,8 +528,8 @@ struct Pol4U31 {
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = POW2 && !FULL;  // the running maximum is a key shifted left by md.kshift
-    static constexpr bool FULL_KEY = FULL;              // ... or the folded value itself,
-    static constexpr bool TWO_MAXIMA = FULL;            // kept as a signed and an unsigned maximum
+    static constexpr bool DOUBLED_KEY = false;
+    static constexpr bool TWO_MAXIMA = FULL;            // ... or the folded value itself, kept as a signed and an unsigned maximum
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
@@ -579,7 +580,7 @@ struct Pol2U61 {
     static constexpr int MIN_WAVES = POW2 ? 4 : 5;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = POW2;
-    static constexpr bool FULL_KEY = false;
+    static constexpr bool DOUBLED_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = POW2;
@@ -627,7 +628,7 @@ struct Pol4U61 {
     static constexpr int MIN_WAVES = 2;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
-    static constexpr bool FULL_KEY = false;
+    static constexpr bool DOUBLED_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = false;
@@ -685,10 +686,10 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // another wavefront's simple instruction go beside it, and a multiply lets
 // nothing go beside it.  The eight evaluations of one nonzero are therefore
 // emitted stage by stage, so that neighbouring instructions never depend on each
-// other: eight multiply-adds at raised priority, sixteen simple instructions at
-// the normal one (see issue_priority); two such halves, then eight three-operand
-// signed maxima (and eight unsigned ones when two maxima are kept).  The
-// arithmetic is key_full_2u31 of mh_arith.h, instruction for instruction.
+// other: eight multiply-adds at raised priority, the simple instructions at the
+// normal one (see issue_priority); two such halves, then eight three-operand
+// maxima.  half_2u31_pow2 is key_full_2u31 of mh_arith.h, instruction for
+// instruction, for the form with two maxima.
 template <int NF>
 __device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&x)[HASH_FPL], uint32_t t)
 {
@@ -703,19 +704,50 @@ __device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
     for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"((uint32_t)(p[g] >> 32)));
     issue_priority<1>();
 }
+// The doubled key 2 hi + lo (key_full2_2u31), formed with two simple instructions
+// (SIMPLE) or with one shift-then-add.  A pair uses one form for each of its nonzeros:
+// per evaluation that is one simple and one full-issue instruction (half a maximum
+// included), which issue beside each other, where either form alone leaves one class
+// without partners.
+template <int NF, bool SIMPLE>
+__device__ __forceinline__ void half_2u31_doubled(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&x)[HASH_FPL], uint32_t t)
+{
+    uint64_t p[HASH_FPL];
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    if constexpr (SIMPLE) {
+        issue_priority<0>();
+#pragma unroll
+        for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %1, %1" : "=v"(x[g]) : "v"((uint32_t)(p[g] >> 32)));
+#pragma unroll
+        for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"((uint32_t)p[g]));
+        issue_priority<1>();
+    } else {
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+            asm volatile("v_lshl_add_u32 %0, %1, 1, %2" : "=v"(x[g]) : "v"((uint32_t)(p[g] >> 32)), "v"((uint32_t)p[g]));
+    }
+}
 template <int NF, bool TWO>
 __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta, uint32_t tb)
 {
     uint32_t xa[HASH_FPL], xb[HASH_FPL];
-    half_2u31_pow2<NF>(fn, xa, ta);
-    half_2u31_pow2<NF>(fn, xb, tb);
-#pragma unroll
-    for (int g = 0; g < NF; ++g)
-        asm volatile("v_max3_i32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
     if constexpr (TWO) {
+        half_2u31_pow2<NF>(fn, xa, ta);
+        half_2u31_pow2<NF>(fn, xb, tb);
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+            asm volatile("v_max3_i32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
 #pragma unroll
         for (int g = 0; g < NF; ++g)
             asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[HASH_FPL + 2 + g]) : "v"(xa[g]), "v"(xb[g]));
+    } else {
+        half_2u31_doubled<NF, true>(fn, xa, ta);
+        half_2u31_doubled<NF, false>(fn, xb, tb);
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+            asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
     }
 }
 
@@ -932,7 +964,7 @@ struct PolGenericMod {
     static constexpr int MIN_WAVES = 3;        // no spills, so that the ablation times the arithmetic only
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
-    static constexpr bool FULL_KEY = false;
+    static constexpr bool DOUBLED_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = false;
@@ -973,7 +1005,7 @@ struct Pol2UMS32 {
     static constexpr int MIN_WAVES = 5;
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
-    static constexpr bool FULL_KEY = false;
+    static constexpr bool DOUBLED_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = true;
     static constexpr bool GUARDED = false;
@@ -1135,7 +1167,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 
         uint32_t m[HASH_ACC];
 #pragma unroll
-        for (int r = 0; r < NF; ++r) m[r] = Pol::FULL_KEY ? (uint32_t)FULL_KEY_INIT : Pol::TRACK_MAX ? 0u : EMPTY_MIN;
+        for (int r = 0; r < NF; ++r) m[r] = Pol::TWO_MAXIMA ? (uint32_t)FULL_KEY_INIT : Pol::TRACK_MAX ? 0u : EMPTY_MIN;
         m[HASH_FPL] = m[HASH_FPL + 1] = 0u;
         if (Pol::TWO_MAXIMA) {
 #pragma unroll
@@ -1186,7 +1218,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 #pragma unroll
                 for (int r = 0; r < NF; ++r) {
                     if (Pol::TWO_MAXIMA) m[r] = finish_full_keys((int32_t)m[r], m[HASH_FPL + 2 + r], md.frot, md.mask);
-                    else if (Pol::FULL_KEY) m[r] = finish_full_key((int32_t)m[r], md.frot, md.mask);
+                    else if (Pol::DOUBLED_KEY) m[r] = finish_full2_key(m[r], md.frot, md.mask);
                     else m[r] = Pol::SHIFTED_KEY ? finish_neg_key(m[r], md.kshift, md.mask) : md.mask - m[r];
                 }
             }

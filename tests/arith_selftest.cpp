@@ -44,19 +44,26 @@ static void check31(uint64_t D, const uint64_t* c, uint32_t t)
         {
             const uint32_t rot = full_key_rotation(md.mask);
             const int32_t fk = key_full_2u31(prep_2u31_full(c[0], c[1], rot), stage_2u31(t));
-            if (fk >= 0 && finish_full_key(fk, rot, md.mask) != want2) FAIL("2U31 full key D=%llu t=%u c=(%llu,%llu)", (unsigned long long)D, t,
-                                                                            (unsigned long long)c[0], (unsigned long long)c[1]);
+            if (fk >= 0 && md.mask - (((uint32_t)fk >> rot) & md.mask) != want2) FAIL("2U31 full key D=%llu t=%u c=(%llu,%llu)", (unsigned long long)D, t,
+                                                                                      (unsigned long long)c[0], (unsigned long long)c[1]);
             if (fk < 0) {
                 const uint32_t rep = (uint32_t)fk - (uint32_t)P31;             // x - p, the representative in [1, p]
                 if (rep > md.mask) FAIL("2U31 full key: representative %u above D - 1 with bit 31 set, D=%llu t=%u", rep, (unsigned long long)D, t);
                 if (md.mask - ((rep >> rot) & md.mask) != want2) FAIL("2U31 full key: x - p is not the representative D=%llu t=%u", (unsigned long long)D, t);
                 ++full_bit31;
             }
+            // the doubled key: twice the signed key when bit 31 is clear, at most 2 (D - 2) otherwise
+            {
+                const uint32_t k2x = key_full2_2u31(prep_2u31_full(c[0], c[1], rot), stage_2u31(t));
+                if (fk >= 0 && (k2x != 2u * (uint32_t)fk || finish_full2_key(k2x, rot, md.mask) != want2)) FAIL("2U31 doubled key D=%llu t=%u", (unsigned long long)D, t);
+                if (fk < 0 && (D < 2 || k2x > 2u * (md.mask - 1u)) && D > 1) FAIL("2U31 doubled key: wrapped value %u above 2 (D - 2), D=%llu", k2x, (unsigned long long)D);
+                if (fk < 0 && !full2_key_doubtful(k2x, md.mask) && D > 1) FAIL("2U31 doubled key: wrapped value not doubtful");
+            }
             // the same value through the two-maxima finish, which D > 2^26 uses
             const uint32_t two = fk > 0 ? finish_full_keys(fk, FULL_KEY_INIT_UNSIGNED, rot, md.mask)
                                         : finish_full_keys(FULL_KEY_INIT, (uint32_t)fk, rot, md.mask);
             if (two != want2) FAIL("2U31 two-maxima finish D=%llu t=%u", (unsigned long long)D, t);
-            full_doubtful += full_key_doubtful(fk, md.mask);
+            full_doubtful += full2_key_doubtful(key_full2_2u31(prep_2u31_full(c[0], c[1], rot), stage_2u31(t)), md.mask);
             checks += 2;
         }
         // 4U full keys: either half of [1, 2p] gives the location once reduced to [1, p]
