@@ -44,7 +44,7 @@ from paper_1205_2958_amd import workloads as W  # noqa: E402
 ISSUE_MIX = {
     W.FAMILY_2U_M31: (1.0, 0.5 + 0.5, 1.0),         # mad | half a shift-then-add, half a max3 | half of add,add
     W.FAMILY_4U_M31: (3.0, 1.0 + 0.5 + 0.5, 3.0),   # 3 mad | add3, half a signed and half an unsigned max3 | shr,and,shr
-    W.FAMILY_2U_M61: (2.0, 1.0 + 0.5 + 0.5, 3.0),   # 2 mad | funnel shift, half a max3 each for key and guard | mov,or,add
+    W.FAMILY_2U_M61: (2.0, 1.0 + 0.5, 2.0),         # 2 mad | funnel shift, half a max3 | mov,add
     W.FAMILY_2U_MS32: (1.0, 0.5, 0.0),              # mad | half a min3 (mask or shift once per row)
 }
 # other D (--universe): exact multiply-high quotient appended

@@ -158,23 +158,17 @@ MH_HD uint32_t hash_2u31_raw(const Fn2U31& f, uint32_t t2, const ModD& md)
     return reduce_mod_d<false>(y < x ? y : x, md);
 }
 
-// Power-of-two D = 2^s: evaluate the NEGATED polynomial.  With c1' = -c1 mod p and
-// the constant p - c0 in [1, p] the folded value x lies in [1, 2p] and is congruent
-// to -X, so its representative in [1, p]
-// is p - (X mod p), whose low s bits are the complement of the hashed location
-// (2^31 - 1 - r = ~r modulo 2^s).  That representative is x for x <= p and
-// x - p = x + 1 - 2^31 otherwise, i.e. x + (x >> 31) modulo 2^s.  Shifting left by
-// 32 - s instead of masking keeps the order of the low s bits, and shift, add and
-// shift fuse into a logical shift and one add-then-shift instruction.  The running
-// MAXIMUM of these keys gives the minimum location: mask - (max >> (32 - s)).
-// For s = 0 the shift count is held at 31 and the final "& mask" clears the bit.
-MH_HD Fn2U31 prep_2u31_neg(uint64_t c0, uint64_t c1)
-{
-    Fn2U31 f;
-    f.c1 = c1 ? (uint32_t)(P31 - c1) : 0u;
-    f.add = 2 * ((uint64_t)P31 - c0);
-    return f;
-}
+// Power-of-two D = 2^s: the kernels evaluate the NEGATED polynomial.  With c1' = -c1
+// mod p and the constant p - c0 in [1, p] the folded value x lies in [1, 2p] and is
+// congruent to -X, so its representative in [1, p] is p - (X mod p), whose low s bits
+// are the complement of the hashed location (2^31 - 1 - r = ~r modulo 2^s).  That
+// representative is x for x <= p and x - p = x + 1 - 2^31 otherwise, i.e.
+// x + (x >> 31) modulo 2^s.  Shifting left by 32 - s instead of masking keeps the
+// order of the low s bits, and shift, add and shift fuse into a logical shift and one
+// add-then-shift instruction.  The running MAXIMUM of these keys gives the minimum
+// location: mask - (max >> (32 - s)).  For s = 0 the shift count is held at 31 and
+// the final "& mask" clears the bit.  (4U uses this form when asked for keys that are
+// formed evaluation by evaluation; otherwise see prep_2u31_full.)
 MH_HD uint32_t neg_key_shift(uint32_t mask)          // 32 - s for mask = 2^s - 1, at most 31
 {
     uint32_t s = 0;
@@ -287,7 +281,7 @@ MH_HD uint32_t hash_4u31_np2(const Fn4U31& f, const Pow4U31& w, const ModD& md)
     uint32_t a = x - 1u, b = x ^ 0x80000000u;
     return reduce_mod_d<false>(b < a ? b : a, md);
 }
-// Power-of-two D, negated cubic (see prep_2u31_neg): the centred coefficients change
+// Power-of-two D, negated cubic (see above neg_key_shift): the centred coefficients change
 // sign (their range is symmetric) and the constant becomes p - c0 in [1, p], so the
 // folded value is congruent to -X and lies in [1, 2^32 - 2] as before.
 MH_HD Fn4U31 prep_4u31_neg(uint64_t c0, uint64_t c1, uint64_t c2, uint64_t c3)
@@ -394,7 +388,7 @@ MH_HD uint32_t hash_2u61(const Fn2U61& f, uint32_t t, const ModD& md, uint64_t D
 }
 
 // Power-of-two D = 2^s <= 2^31, negated and rotated form with a guard (compare
-// prep_2u31_neg).  With c1' = -c1 mod p and the constant p - c0 in [1, p],
+// prep_2u31_full).  With c1' = -c1 mod p and the constant p - c0 in [1, p],
 // V = c1' t + (p - c0) is congruent to -X, and its representative in [1, p] is
 // p - (X mod p), whose low s bits are the complement of the hashed location.
 // Multiplying by 2^j modulo p = 2^61-1 rotates a 61-bit residue left by j bits, so
@@ -402,12 +396,14 @@ MH_HD uint32_t hash_2u61(const Fn2U61& f, uint32_t t, const ModD& md, uint64_t D
 // of the low 32-bit word of the representative: that word, with whatever lies below
 // the s bits, is an order-preserving key as it stands.  The folded x = y + (H >> 29)
 // lies in [1, 2^61 + 2^31 + 4), and as long as its bit 61 is clear it is that
-// representative, so the key is L_lo + (H >> 29), one add, no carries, no shift.  Bit
-// 61 can only be set if bits 32..60 of the bracket, i.e. the low 29 bits of H, are all
-// ones and the low-word addition carries into them.  `guard` = H_lo | 0xE0000000 is
-// all ones in exactly the first case: an evaluation whose guard is not 0xFFFFFFFF has
-// an exact key; about one evaluation in 2^29 has such a guard, and the caller then
-// falls back on the exact path (hash_2u61) for the data at hand.
+// representative, so the key is L_lo + (H >> 29), one add, no carries, no shift.  When
+// bit 61 is set, x = 2^61 + d with d < 2^31 + 4, the representative is x - p = d + 1,
+// and the key comes out as d: one too small, and in any case below 2^31 + 5.  So an
+// unsigned running maximum of at least GUARD61_FLOOR = 2^31 + 5 ends on an evaluation
+// with bit 61 clear, is exact, and no evaluation with bit 61 set has a representative
+// above it; a smaller maximum marks the value as doubtful, and it is then computed
+// again with the exact path (hash_2u61).  With n evaluations behind a value that
+// happens with probability about 2^-n.
 MH_HD uint64_t rotl61(uint64_t v, uint32_t j)      // v <= p, 1 <= j <= 32: v 2^j modulo p (p stays p)
 {
     return ((v << j) | (v >> (61u - j))) & P61;
@@ -421,17 +417,13 @@ MH_HD Fn2U61 prep_2u61_neg(uint64_t c0, uint64_t c1, uint32_t shift)   // shift 
     f.add = rotl61(P61 - c0, shift);
     return f;
 }
-struct GuardedKey61 { uint32_t key, guard; };
-MH_HD GuardedKey61 key_neg_2u61(const Fn2U61& f, uint32_t t)   // t < 2^31; the location is finish_neg_key(key, shift, mask)
+MH_HD uint32_t key_neg_2u61(const Fn2U61& f, uint32_t t)   // t < 2^31; the location is finish_neg_key(key, shift, mask)
 {
     const uint64_t L = (uint64_t)f.e0 * t + f.add;
     const uint64_t H = (uint64_t)f.e1 * t + (L >> 32);
-    GuardedKey61 k;
-    k.key = (uint32_t)L + (uint32_t)(H >> 29);
-    k.guard = (uint32_t)H | 0xE0000000u;
-    return k;
+    return (uint32_t)L + (uint32_t)(H >> 29);
 }
-constexpr uint32_t GUARD61_HIT = 0xFFFFFFFFu;
+constexpr uint32_t GUARD61_FLOOR = 0x80000005u;
 
 // ---------------------------------------------------------------- 4U, p = 2^61-1 (eq. eqn_4U with the prime of Section 3.4's last paragraph)
 // Horner form: three steps acc <- acc t + c, each one 62-bit x 32-bit product

@@ -53,7 +53,7 @@ constexpr int BLOCK = WAVE * WAVES_PER_BLOCK;
 constexpr int TILE = 256;              // nonzeros staged per wavefront per step (4 per lane)
 constexpr int HASH_FPL = 8;            // hash functions per lane
 constexpr int FULL_KEY_MAX_LOG2_D = 26;
-constexpr int HASH_ACC = 2 * HASH_FPL + 2;     // the running extrema of a lane's functions, two words a policy may use as guards, and room for a second set of extrema
+constexpr int HASH_ACC = 2 * HASH_FPL;      // the running extrema of a lane's functions and room for a second set of them
 constexpr int HASH_FTILE = WAVE * HASH_FPL;   // 512 functions per wavefront pass
 constexpr int PERM_FPL = 4;            // permutations per lane (one 16-byte load)
 constexpr int PERM_FTILE = WAVE * PERM_FPL;   // 256
@@ -239,7 +239,6 @@ struct ModDV : ModD {
     uint32_t p31;    // 2^31 - 1
     uint32_t sign;   // 2^31
     uint32_t negD;   // 2^32 - D
-    uint32_t top3;   // 0xE0000000
     uint32_t kshift; // 32 - log2 D: left shift of the order-preserving keys of the negated forms
     uint32_t frot;   // 31 - log2 D: what the coefficients of the full-key form are rotated by
 };
@@ -255,7 +254,6 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
     v.p31 = in_vgpr_if_used(P31);
     v.sign = in_vgpr_if_used(0x80000000u);
     v.negD = in_vgpr_if_used(0u - src.D);
-    v.top3 = in_vgpr_if_used(0xE0000000u);
     v.kshift = src.pow2 ? neg_key_shift(src.mask) : 0u;
     v.frot = src.pow2 ? full_key_rotation(src.mask) : 0u;
     return v;
@@ -569,11 +567,11 @@ struct Fn2U61V : Fn2U61 {
     mutable u32x2 hz;
 };
 
-// For power-of-two D <= 2^31 the fast path evaluates the negated function without
-// carries (key_neg_2u61 of mh_arith.h) and keeps the running maximum of the keys
-// and of the guard words; when a lane's guard was hit, about one evaluation in
-// 2^29, its values are computed again from the exact arithmetic (GUARDED, see
-// the kernel).
+// For power-of-two D <= 2^31 the fast path evaluates the negated, rotated function
+// without carries (key_neg_2u61 of mh_arith.h) and keeps the unsigned running maximum
+// of the keys; a maximum below GUARD61_FLOOR, which about one value in 2^n with n
+// evaluations behind it has, is computed again from the exact arithmetic (GUARDED,
+// see the kernel).
 template <bool POW2>
 struct Pol2U61 {
     static constexpr int NW = 1;
@@ -590,9 +588,8 @@ struct Pol2U61 {
     {
         Fn f;
         if constexpr (POW2) {
-            // an unused slot takes a constant whose guard word is never all ones (c0 = c1 = 0 would hit it every time)
             const uint32_t shift = neg_key_shift(a.md.mask);
-            static_cast<Fn2U61&>(f) = valid ? prep_2u61_neg(c[0], c[1], shift) : prep_2u61_neg(P61 - 1, 0, shift);
+            static_cast<Fn2U61&>(f) = valid ? prep_2u61_neg(c[0], c[1], shift) : prep_2u61_neg(0, 0, shift);
             f.hz = u32x2{0u, 0u};
         } else {
             static_cast<Fn2U61&>(f) = valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
@@ -608,7 +605,10 @@ struct Pol2U61 {
     template <int NF>
     static __device__ __forceinline__ uint32_t doubtful(const uint32_t (&m)[HASH_ACC], const ModDV&)
     {
-        return (m[HASH_FPL] == GUARD61_HIT || m[HASH_FPL + 1] == GUARD61_HIT) ? (1u << NF) - 1u : 0u;
+        uint32_t bits = 0;
+#pragma unroll
+        for (int r = 0; r < NF; ++r) bits |= m[r] < GUARD61_FLOOR ? 1u << r : 0u;
+        return bits;
     }
     static __device__ __forceinline__ uint32_t exact_hash(const uint64_t* c, uint32_t t, const ModD& md, uint64_t D)
     {
@@ -741,7 +741,7 @@ __device__ __forceinline__ void pair_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
             asm volatile("v_max3_i32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(xa[g]), "v"(xb[g]));
 #pragma unroll
         for (int g = 0; g < NF; ++g)
-            asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[HASH_FPL + 2 + g]) : "v"(xa[g]), "v"(xb[g]));
+            asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[HASH_FPL + g]) : "v"(xa[g]), "v"(xb[g]));
     } else {
         half_2u31_doubled<NF, true>(fn, xa, ta);
         half_2u31_doubled<NF, false>(fn, xb, tb);
@@ -805,7 +805,7 @@ __device__ __forceinline__ void pair_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
             asm volatile("v_max3_i32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
 #pragma unroll
         for (int g = 0; g < NF; ++g)
-            asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[HASH_FPL + 2 + g]) : "v"(ya[g]), "v"(yb[g]));
+            asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[HASH_FPL + g]) : "v"(ya[g]), "v"(yb[g]));
         return;
     }
 #pragma unroll
@@ -920,15 +920,12 @@ __device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint
 // 2U, p = 2^61-1, power-of-two D <= 2^31: key_neg_2u61 of mh_arith.h, eight
 // functions on one nonzero, stage by stage: two multiply-adds, the funnel shift
 // H >> 29, one add for the key (the coefficients were rotated so that it needs no
-// shift), one or for the guard word.  The guard words go into two running maxima
-// (m[HASH_FPL], m[HASH_FPL + 1]) right away, two per three-operand maximum; the
-// keys leave in y.
+// shift).
 template <int NF>
-__device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t (&m)[HASH_ACC],
-                                               uint32_t t, const ModDV& md)
+__device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t t)
 {
     u32x2 L[HASH_FPL], H[HASH_FPL];
-    uint32_t s[HASH_FPL], z[HASH_FPL + 1], r;
+    uint32_t s[HASH_FPL], r;
     issue_priority<1>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, L[g], fn[g].e0, t, fn[g].add);
@@ -945,14 +942,8 @@ __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], ui
     for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
     issue_priority<0>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_or_b32 %0, %1, %2" : "=v"(z[g]) : "v"(H[g].x), "v"(md.top3));
-#pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %1, %2" : "=v"(y[g]) : "v"(L[g].x), "v"(s[g]));
     issue_priority<1>();
-    if (NF & 1) z[NF] = z[NF - 1];
-#pragma unroll
-    for (int g = 0; g < NF; g += 2)
-        asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[HASH_FPL + ((g >> 1) & 1)]) : "v"(z[g]), "v"(z[g + 1]));
 }
 
 // Ablation: the definition evaluated with the % operator on runtime moduli (Horner
@@ -1088,8 +1079,8 @@ __device__ __forceinline__ void Pol2U61<true>::pair(const Fn (&fn)[HASH_FPL], ui
                                                     const uint32_t* wb, const ModDV& md, uint64_t)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
-    half_2u61_pow2<NF>(fn, ya, m, wa[0], md);
-    half_2u61_pow2<NF>(fn, yb, m, wb[0], md);
+    half_2u61_pow2<NF>(fn, ya, wa[0]);
+    half_2u61_pow2<NF>(fn, yb, wb[0]);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
         asm volatile("v_max3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
@@ -1168,10 +1159,9 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
         uint32_t m[HASH_ACC];
 #pragma unroll
         for (int r = 0; r < NF; ++r) m[r] = Pol::TWO_MAXIMA ? (uint32_t)FULL_KEY_INIT : Pol::TRACK_MAX ? 0u : EMPTY_MIN;
-        m[HASH_FPL] = m[HASH_FPL + 1] = 0u;
         if (Pol::TWO_MAXIMA) {
 #pragma unroll
-            for (int r = 0; r < NF; ++r) m[HASH_FPL + 2 + r] = FULL_KEY_INIT_UNSIGNED;
+            for (int r = 0; r < NF; ++r) m[HASH_FPL + r] = FULL_KEY_INIT_UNSIGNED;
         }
 
         if (len > 0) {
@@ -1217,7 +1207,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             if (Pol::TRACK_MAX) {      // back from keys to the minimum location
 #pragma unroll
                 for (int r = 0; r < NF; ++r) {
-                    if (Pol::TWO_MAXIMA) m[r] = finish_full_keys((int32_t)m[r], m[HASH_FPL + 2 + r], md.frot, md.mask);
+                    if (Pol::TWO_MAXIMA) m[r] = finish_full_keys((int32_t)m[r], m[HASH_FPL + r], md.frot, md.mask);
                     else if (Pol::DOUBLED_KEY) m[r] = finish_full2_key(m[r], md.frot, md.mask);
                     else m[r] = Pol::SHIFTED_KEY ? finish_neg_key(m[r], md.kshift, md.mask) : md.mask - m[r];
                 }

@@ -111,15 +111,24 @@ static void check61(uint64_t D, const uint64_t* c, uint32_t t)
                         (unsigned long long)c[0], (unsigned long long)c[1], g, (unsigned long long)want);
     ++checks;
     if (md.pow2 && D <= (1ull << 31)) {
-        // the guarded key of the negated form: exact whenever the guard is not hit
+        // the carry-free key of the negated, rotated form: exact whenever bit 61 of the folded value is clear;
+        // otherwise one too small and below GUARD61_FLOOR
         const uint32_t ks61 = neg_key_shift(md.mask);
-        GuardedKey61 gk = key_neg_2u61(prep_2u61_neg(c[0], c[1], ks61), t);
-        const uint32_t loc = finish_neg_key(gk.key, ks61, md.mask);
-        if (gk.guard != GUARD61_HIT && loc != want)
-            FAIL("2U61 guarded key D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
-                 (unsigned long long)c[0], (unsigned long long)c[1], loc, (unsigned long long)want);
-        if (gk.guard == GUARD61_HIT) ++guard_hits;
-        if (gk.guard == GUARD61_HIT && loc != want) ++guard_saves;
+        const Fn2U61 fn = prep_2u61_neg(c[0], c[1], ks61);
+        const uint32_t key = key_neg_2u61(fn, t);
+        const u128 V = (u128)(((uint64_t)fn.e1 << 32) | fn.e0) * t + fn.add;
+        const uint64_t x = (uint64_t)(V & P61) + (uint64_t)(V >> 61);
+        const uint32_t loc = finish_neg_key(key, ks61, md.mask);
+        if ((x >> 61) == 0) {
+            if (loc != want) FAIL("2U61 carry-free key D=%llu t=%u c=(%llu,%llu) got %u want %llu", (unsigned long long)D, t,
+                                  (unsigned long long)c[0], (unsigned long long)c[1], loc, (unsigned long long)want);
+        } else {
+            if (key >= GUARD61_FLOOR) FAIL("2U61 carry-free key: bit 61 set and key %u not below the floor", key);
+            if (key + 1u != (uint32_t)(x - P61)) FAIL("2U61 carry-free key: not one below the representative");
+            if (finish_neg_key(key + 1u, ks61, md.mask) != want) FAIL("2U61: representative of a folded value with bit 61 set");
+            ++guard_hits;
+            if (loc != want) ++guard_saves;
+        }
         ++checks;
     }
     // 4U with the same prime: Horner form against the power-sum definition
@@ -197,10 +206,10 @@ int main()
             check61(D, c, t);
         }
     }
-    // Guarded 2U-M61 key: coefficients built so that the negated form's H has its low 29 bits all
-    // ones (the only case in which the unguarded key can be wrong), with the low-word sum on
-    // either side of a carry.  The guard must fire on every one of them, and some must be cases
-    // in which the plain key is indeed wrong.
+    // Carry-free 2U-M61 key: coefficients built so that the negated form's H has its low 29 bits all
+    // ones (the only case in which bit 61 of the folded value can be set), with the low-word sum on
+    // either side of a carry.  Many of them must have bit 61 set, and some must be cases in which the
+    // key as it stands gives the wrong location.
     {
         const long hits_before = guard_hits, saves_before = guard_saves;
         int built = 0;
@@ -225,13 +234,13 @@ int main()
                 uint64_t c[4] = {p61 - rotr61(add2), p61 - rotr61(n), rnd() % p61, rnd() % p61};
                 Fn2U61 f = prep_2u61_neg(c[0], c[1], ks);
                 if (((uint64_t)f.e1 << 32 | f.e0) != n || f.add != add2) FAIL("engineered coefficients do not rotate back");
-                if (key_neg_2u61(f, t).guard != GUARD61_HIT) FAIL("engineered guard case not built");
+                if ((((uint64_t)f.e1 * t + (((uint64_t)f.e0 * t + f.add) >> 32)) & 0x1FFFFFFFull) != 0x1FFFFFFFull) FAIL("engineered case not built");
                 check61(D, c, t);
                 ++built;
             }
         }
-        if (built < 10000 || guard_hits - hits_before != built) FAIL("guarded key: %d built, %ld hits", built, guard_hits - hits_before);
-        if (guard_saves - saves_before < 100) FAIL("guarded key: only %ld engineered cases needed the guard", guard_saves - saves_before);
+        if (built < 10000 || guard_hits - hits_before < 1000) FAIL("carry-free key: %d built, %ld with bit 61 set", built, guard_hits - hits_before);
+        if (guard_saves - saves_before < 100) FAIL("carry-free key: only %ld engineered cases came out wrong", guard_saves - saves_before);
     }
     // multiply-shift 2U (Section 3.3): ((c0 + c1 t) mod 2^32) mod 2^s, lowest or highest s bits
     for (int sbits = 0; sbits <= 32; ++sbits) {
