@@ -53,6 +53,7 @@ constexpr int BLOCK = WAVE * WAVES_PER_BLOCK;
 constexpr int TILE = 256;              // nonzeros staged per wavefront per step (4 per lane)
 constexpr int HASH_FPL = 8;            // hash functions per lane
 constexpr int FULL_KEY_MAX_LOG2_D = 26;
+constexpr uint32_t SHORT_ITEM = 16;         // nonzeros up to which a lane recomputes its doubtful values by itself
 constexpr int HASH_ACC = 2 * HASH_FPL;      // the running extrema of a lane's functions and room for a second set of them
 constexpr int HASH_FTILE = WAVE * HASH_FPL;   // 512 functions per wavefront pass
 constexpr int PERM_FPL = 4;            // permutations per lane (one 16-byte load)
@@ -1221,6 +1222,29 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                 // evaluates that one function on all nonzeros of the item, a lane each, and the
                 // owner takes the minimum (over the whole item, which its slice is part of).
                 uint64_t owners = __builtin_amdgcn_ballot_w64(doubt != 0u);
+                if (owners != 0ull && len <= SHORT_ITEM) {
+                    // A short item makes many of its values doubtful (few evaluations stand behind
+                    // each) and is cheap to go through: every lane sees to its own values.
+                    for (uint32_t which = doubt; which; which &= which - 1) {
+                        const int r = __builtin_ctz(which);
+                        if (j_base + r >= a.k) continue;
+                        const uint64_t* src = static_cast<const uint64_t*>(a.params) + (size_t)(j_base + r) * Pol::DEG;
+                        uint64_t c[Pol::DEG];
+#pragma unroll
+                        for (int i = 0; i < Pol::DEG; ++i) c[i] = src[i];
+                        uint32_t best = EMPTY_MIN;
+                        for (uint32_t e = 0; e < len; ++e) {
+                            uint32_t t = a.col_idx[begin + e];
+                            if (a.validate && (uint64_t)t >= a.D) t = 0;
+                            const uint32_t h = Pol::exact_hash(c, t, a.md, a.D);
+                            best = h < best ? h : best;
+                        }
+#pragma unroll
+                        for (int q = 0; q < NF; ++q)
+                            if (q == r) m[q] = best;
+                    }
+                    owners = 0ull;
+                }
                 while (owners) {
                     const int owner = __builtin_ctzll(owners);
                     owners &= owners - 1;

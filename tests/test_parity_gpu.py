@@ -517,3 +517,17 @@ def test_indices_that_hash_to_the_last_location_engineered(family):
     nnz = np.array([r.shape[0] for r in rows], dtype=np.int64)
     check_case(W.row_ptr_from_nnz(nnz), np.concatenate(rows), D, k, 32, family, c)
     check_case(W.row_ptr_from_nnz(nnz), np.concatenate(rows), D, k, 8, family, c)
+
+
+@pytest.mark.parametrize("family,D", [(mh.FAMILY_2U_M31, 1 << 26), (mh.FAMILY_2U_M31, 1 << 24), (mh.FAMILY_2U_M61, 1 << 30),
+                                      (mh.FAMILY_2U_M61, 1 << 31), (mh.FAMILY_2U_M61, 1 << 12)])
+def test_very_short_rows_whose_values_are_mostly_doubtful(family, D):
+    """Rows of 0 to 40 nonzeros: with so few evaluations behind a value, the kernels whose keys
+    rely on the running maximum being large mark many values as doubtful (2U-M61: one in 2^n
+    for n nonzeros) and compute them again, lane by lane up to 16 nonzeros, wave-wide beyond."""
+    nnz = np.array(list(range(41)) * 3, dtype=np.int64)
+    rp = W.row_ptr_from_nnz(nnz)
+    rng = np.random.Generator(np.random.PCG64(123))
+    col = rng.integers(0, D, size=int(rp[-1]), dtype=np.uint64).astype(np.uint32)
+    k = 200
+    check_case(rp, col, D, k, 32, family, W.coefficients(k, family, seed=124))
