@@ -1077,7 +1077,7 @@ __device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], u
 template <>
 template <int NF>
 __device__ __forceinline__ void Pol2U61<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                    const uint32_t* wb, const ModDV& md, uint64_t)
+                                                    const uint32_t* wb, const ModDV&, uint64_t)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
     half_2u61_pow2<NF>(fn, ya, wa[0]);
