@@ -18,7 +18,12 @@
 //                        on each staged nonzero, read back as LDS broadcasts,
 //                        keeping 8 running minima in registers (Section 2, last
 //                        paragraph: map every nonzero t to h_j(t), keep the
-//                        minimum).  When k needs fewer than 64 lanes the spare
+//                        minimum); for power-of-two D the running values are
+//                        maxima of order-preserving keys for the complement of
+//                        h_j(t), turned into the minimum once per row, and the
+//                        rare values such a key cannot vouch for are computed
+//                        again from the exact arithmetic before they are
+//                        stored.  When k needs fewer than 64 lanes the spare
 //                        lanes take slices of the nonzeros and are merged by a
 //                        butterfly of cross-lane minima.  Whole rows are
 //                        truncated to b bits, packed and stored by the same
@@ -52,7 +57,7 @@ constexpr int WAVES_PER_BLOCK = 4;
 constexpr int BLOCK = WAVE * WAVES_PER_BLOCK;
 constexpr int TILE = 256;              // nonzeros staged per wavefront per step (4 per lane)
 constexpr int HASH_FPL = 8;            // hash functions per lane
-constexpr int FULL_KEY_MAX_LOG2_D = 26;
+constexpr int FULL_KEY_MAX_LOG2_D = 26;     // largest power-of-two D for which 2U keeps a single maximum
 constexpr uint32_t SHORT_ITEM = 16;         // nonzeros up to which a lane recomputes its doubtful values by itself
 constexpr int HASH_ACC = 2 * HASH_FPL;      // the running extrema of a lane's functions and room for a second set of them
 constexpr int HASH_FTILE = WAVE * HASH_FPL;   // 512 functions per wavefront pass
