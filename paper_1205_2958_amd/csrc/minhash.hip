@@ -439,14 +439,21 @@ __device__ __forceinline__ void wave_pack_store(const KArgs& a, const uint32_t* 
     const int ndw = (nbytes + 3) >> 2;
     uint8_t* base = dst + byte0;
     const bool aligned = ((reinterpret_cast<uintptr_t>(base) & 3u) == 0);
+    const bool b_pow2 = (b & (b - 1)) == 0;                 // 1, 2, 4, 8, 16, 32: fields do not straddle words
+    const int lg_b = __builtin_ctz((unsigned)b);
     for (int w = lane; w < ndw; w += WAVE) {
-        const int bit_lo = w * 32;
-        int j = bit_lo / b;
         uint32_t word = 0;
-        for (; j < nf && j * b < bit_lo + 32; ++j) {
-            uint32_t v = mins[j] & maskb;
-            int pos = j * b - bit_lo;
-            word |= pos >= 0 ? (v << pos) : (v >> (-pos));
+        if (b_pow2) {
+            const int per = 32 >> lg_b;
+            const int j = w << (5 - lg_b);
+            for (int i = 0; i < per && j + i < nf; ++i) word |= (mins[j + i] & maskb) << (i << lg_b);
+        } else {
+            const int bit_lo = w * 32;
+            for (int j = bit_lo / b; j < nf && j * b < bit_lo + 32; ++j) {
+                uint32_t v = mins[j] & maskb;
+                int pos = j * b - bit_lo;
+                word |= pos >= 0 ? (v << pos) : (v >> (-pos));
+            }
         }
         if (aligned && 4 * w + 3 < nbytes) {
             *reinterpret_cast<uint32_t*>(base + 4 * w) = word;
