@@ -47,7 +47,12 @@ ISSUE_MIX = {
     W.FAMILY_2U_M61: (2.0, 1.0 + 0.5, 2.0),         # 2 mad | funnel shift, half a max3 | mov,add
     W.FAMILY_2U_MS32: (1.0, 0.5, 0.0),              # mad | half a min3 (mask or shift once per row)
 }
-# other D (--universe): exact multiply-high quotient appended
+# other D (--universe) below 2^28: fractional key (one multiply-add and one funnel shift after the canonical residue)
+ISSUE_MIX_OTHER_D_FRAC = {
+    W.FAMILY_2U_M31: (2.0, 1.0 + 1.0 + 0.5, 3.0),         # mad, mad | min, funnel shift, half a min3 | shr,add,sub
+    W.FAMILY_4U_M31: (4.0, 1.0 + 1.0 + 1.0 + 0.5, 5.0),   # 3 mad, mad | add3, min, funnel shift, half a min3 | shr,and,shr,add,xor
+}
+# other D from 2^28 up: exact multiply-high quotient appended
 ISSUE_MIX_OTHER_D = {
     W.FAMILY_2U_M31: (3.0, 1.0 + 0.5, 4.0),         # mad, mulhi, mad | min, half a min3 | shr,add,sub,shr
     W.FAMILY_4U_M31: (5.0, 1.0 + 1.0 + 0.5, 6.0),   # 3 mad, mulhi, mad | add3, min, half a min3 | shr,and,shr,add,xor,shr
@@ -402,7 +407,10 @@ def main() -> int:
                 "traffic": None, "kernel": "mh_perm_kernel", "kernel_ms": k_ms,
                 "model": "4k+4 bytes per nonzero (one table row + the index) + row_ptr + packed output"}
     else:
-        mix = ISSUE_MIX_OTHER_D[family] if (D & (D - 1)) else ISSUE_MIX[family]
+        if D & (D - 1):
+            mix = ISSUE_MIX_OTHER_D_FRAC[family] if D < (1 << 28) else ISSUE_MIX_OTHER_D[family]
+        else:
+            mix = ISSUE_MIX[family]
         slots = issue_slots(mix)
         roof = {"bound": "alu", "achieved": evals * slots / (k_ms * 1e-3) / 1e12, "peak": ALU_PEAK_SLOTS / 1e12,
                 "unit": "TOP/s", "traffic": None, "kernel": "mh_hash_kernel", "kernel_ms": k_ms,

@@ -84,6 +84,38 @@ MH_HD uint32_t reduce_mod_d(uint32_t r, const ModD& md)   // r < 2^31
     return r - q * md.D;
 }
 
+// Any D below 2^28 that is not a power of two: a key that orders residues r < 2^31 by
+// r mod D without computing r mod D.  With l = ceil(log2 D), N = 32 + l and
+// M = floor(2^N / D) = 2^32 + m_low (33 bits), P = r M + bias = r m_low + (r 2^32 + bias)
+// is one multiply-add whose 64-bit addend carries r in its high word.  Then
+// P / 2^N = r / D + b - e with b = bias / 2^N = 2^-(l+1) + 2^-30 and the shortfall
+// e = r (2^N / D - M) / 2^N in [0, 2^-(l+1)), so the fraction of P / 2^N lies in
+// (v / D + 2^-30, v / D + 2^-(l+1) + 2^-30] for v = r mod D, which is inside
+// (v / D, (v + 1) / D) for l <= 28.  Its top 32 bits, bits [l, 32 + l) of P, are the
+// key: keys of different v differ by more than 2^-(l+1) - 2^-32 in the same direction,
+// and floor(key D / 2^32), one multiply-high per row, gives v back.
+struct FracD {
+    uint32_t m_low;   // floor(2^(32+l) / D) - 2^32
+    uint32_t bias;    // 2^31 + 2^(l+2) < 2^32
+    uint32_t l;       // ceil(log2 D), 2..28
+};
+MH_HD bool frac_key_serves(uint64_t D) { return D >= 3 && D < (1ull << 28) && (D & (D - 1)) != 0; }
+MH_HD FracD make_frac_d(uint64_t D)
+{
+    FracD f;
+    f.l = 0;
+    while ((1ull << f.l) < D) ++f.l;
+    f.m_low = (uint32_t)((1ull << (32 + f.l)) / D);      // the quotient lies in (2^32, 2^33): its low word
+    f.bias = (1u << 31) + (1u << (f.l + 2));
+    return f;
+}
+MH_HD uint32_t frac_key(uint32_t r, const FracD& f)      // r < 2^31
+{
+    const uint64_t P = (uint64_t)r * f.m_low + (((uint64_t)r << 32) | f.bias);
+    return (uint32_t)(P >> f.l);
+}
+MH_HD uint32_t finish_frac_key(uint32_t key, uint32_t D) { return mulhi_u32(key, D); }
+
 // r mod D for r < 2^61 and any D in [1, 2^32] (the p = 2^61-1 families with a D that
 // the mask path cannot serve): q = floor(r M64 / 2^64) falls short of the true
 // quotient by at most one, because r (2^64 / D - M64) < 2 r < 2^64 / 4; one

@@ -247,6 +247,8 @@ struct ModDV : ModD {
     uint32_t negD;   // 2^32 - D
     uint32_t kshift; // 32 - log2 D: left shift of the order-preserving keys of the negated forms
     uint32_t frot;   // 31 - log2 D: what the coefficients of the full-key form are rotated by
+    uint32_t frac_m; // fractional keys (FracD of mh_arith.h): low word of the 33-bit multiplier,
+    uint32_t frac_l; // and the bit at which the key starts
 };
 __device__ __forceinline__ ModDV vector_constants(const ModD& src)
 {
@@ -262,6 +264,10 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
     v.negD = in_vgpr_if_used(0u - src.D);
     v.kshift = src.pow2 ? neg_key_shift(src.mask) : 0u;
     v.frot = src.pow2 ? full_key_rotation(src.mask) : 0u;
+    const bool frac = frac_key_serves(src.D);
+    const FracD fd = frac ? make_frac_d(src.D) : FracD{0u, 0u, 0u};
+    v.frac_m = in_vgpr_if_used(fd.m_low);
+    v.frac_l = fd.l;
     return v;
 }
 // Issue priority of this wavefront among those of its SIMD.  The hand-ordered steps
@@ -481,10 +487,18 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // doubled value (key_full2_2u31), which needs a second look at a value with probability
 // (D / 2^31)^n, n the evaluations behind it, so the host picks it for D <= 2^26; FORM_FULL_TWO
 // keeps a signed and an unsigned maximum of the value (finish_full_keys), nothing to look at twice.
-constexpr int FORM_ANY_D = 0, FORM_FULL_TWO = 1, FORM_FULL = 2;
+// FORM_FRAC_D (D below 2^28, not a power of two): the running minimum of fractional keys
+// (frac_key), one multiply-add and one funnel shift after the canonical residue, instead of the
+// exact quotient's multiply-high, shift and multiply-add; the location comes back once per row.
+// The function keeps a register pair {bias, r} per slot whose low word stays put.
+struct Fn2U31F : Fn2U31 {
+    mutable u32x2 bq;
+};
+constexpr int FORM_ANY_D = 0, FORM_FULL_TWO = 1, FORM_FULL = 2, FORM_FRAC_D = 3;
 template <int FORM>
 struct Pol2U31 {
-    static constexpr bool POW2 = FORM != FORM_ANY_D;
+    static constexpr bool POW2 = FORM == FORM_FULL || FORM == FORM_FULL_TWO;
+    static constexpr bool FRAC_KEY = FORM == FORM_FRAC_D;   // the running minimum is a fractional key (finish_frac_key)
     static constexpr int NW = 1;
     static constexpr int MIN_WAVES = POW2 ? 5 : 4;   // wavefronts per SIMD the register allocation must leave room for
     static constexpr bool TRACK_MAX = POW2;
@@ -494,18 +508,30 @@ struct Pol2U31 {
     static constexpr bool SHIFT_END = false;
     static constexpr bool GUARDED = FORM == FORM_FULL;   // a single maximum can say that it may be wrong
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
-    using Fn = Fn2U31;
+    using Fn = std::conditional_t<FRAC_KEY, Fn2U31F, Fn2U31>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
-        if (!POW2) return valid ? prep_2u31_raw(c[0], c[1]) : prep_2u31_raw(0, 0);
-        const uint32_t rotation = full_key_rotation(a.md.mask);
-        return valid ? prep_2u31_full(c[0], c[1], rotation) : prep_2u31_full(0, 0, rotation);
+        if constexpr (FRAC_KEY) {
+            Fn f;
+            static_cast<Fn2U31&>(f) = valid ? prep_2u31_raw(c[0], c[1]) : prep_2u31_raw(0, 0);
+            f.bq = u32x2{make_frac_d(a.D).bias, 0u};
+            return f;
+        } else if constexpr (!POW2) {
+            return valid ? prep_2u31_raw(c[0], c[1]) : prep_2u31_raw(0, 0);
+        } else {
+            const uint32_t rotation = full_key_rotation(a.md.mask);
+            return valid ? prep_2u31_full(c[0], c[1], rotation) : prep_2u31_full(0, 0, rotation);
+        }
     }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = stage_2u31(t); }
     static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModDV& md, uint64_t)
     {
         if (FORM == FORM_FULL) return key_full2_2u31(f, w[0]);
         if (POW2) return (uint32_t)key_full_2u31(f, w[0]);
+        if (FRAC_KEY) {
+            const uint32_t x = fold_2u31(f, w[0]), y = x - (uint32_t)P31;
+            return frac_key(y < x ? y : x, make_frac_d(md.D));
+        }
         return hash_2u31_raw(f, w[0], md);
     }
     template <int NF>
@@ -532,9 +558,14 @@ struct Pol2U31 {
 // finish_full_keys): no instruction after the fold, nothing to look at twice.  Without FULL
 // the key is the shifted one of key_neg_4u31, one shift and one add-then-shift after the
 // fold; the host picks it only when asked for the evaluation-by-evaluation form.
-template <bool POW2, bool FULL = false>
+// FRAC (D below 2^28, not a power of two): fractional keys as in Pol2U31<FORM_FRAC_D>.
+struct Fn4U31F : Fn4U31 {
+    mutable u32x2 bq;
+};
+template <bool POW2, bool FULL = false, bool FRAC = false>
 struct Pol4U31 {
     static_assert(POW2 || !FULL, "full keys are for power-of-two D");
+    static_assert(!POW2 || !FRAC, "fractional keys are for D that is not a power of two");
     static constexpr int NW = 3;
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool TRACK_MAX = POW2;
@@ -542,17 +573,25 @@ struct Pol4U31 {
     static constexpr bool DOUBLED_KEY = false;
     static constexpr bool TWO_MAXIMA = FULL;            // ... or the folded value itself, kept as a signed and an unsigned maximum
     static constexpr bool SHIFT_END = false;
+    static constexpr bool FRAC_KEY = FRAC;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
-    using Fn = Fn4U31;
+    using Fn = std::conditional_t<FRAC, Fn4U31F, Fn4U31>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
-        if (FULL) {
+        if constexpr (FRAC) {
+            Fn f;
+            static_cast<Fn4U31&>(f) = valid ? prep_4u31(c[0], c[1], c[2], c[3]) : prep_4u31(0, 0, 0, 0);
+            f.bq = u32x2{make_frac_d(a.D).bias, 0u};
+            return f;
+        } else if constexpr (FULL) {
             const uint32_t rotation = full_key_rotation(a.md.mask);
             return valid ? prep_4u31_full(c[0], c[1], c[2], c[3], rotation) : prep_4u31_full(0, 0, 0, 0, rotation);
+        } else if constexpr (POW2) {
+            return valid ? prep_4u31_neg(c[0], c[1], c[2], c[3]) : prep_4u31_neg(0, 0, 0, 0);
+        } else {
+            return valid ? prep_4u31(c[0], c[1], c[2], c[3]) : prep_4u31(0, 0, 0, 0);
         }
-        if (POW2) return valid ? prep_4u31_neg(c[0], c[1], c[2], c[3]) : prep_4u31_neg(0, 0, 0, 0);
-        return valid ? prep_4u31(c[0], c[1], c[2], c[3]) : prep_4u31(0, 0, 0, 0);
     }
     static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w)
     {
@@ -564,6 +603,10 @@ struct Pol4U31 {
         Pow4U31 p;
         p.t1 = (int32_t)w[0]; p.t2 = (int32_t)w[1]; p.t3 = (int32_t)w[2];
         if (FULL) return fold_4u31(f, p);
+        if (FRAC) {
+            const uint32_t x = fold_4u31(f, p), u = x - 1u, v = x ^ 0x80000000u;
+            return frac_key(v < u ? v : u, make_frac_d(md.D));
+        }
         if (POW2) return key_neg_4u31(f, p, md.kshift);
         return hash_4u31_np2(f, p, md);
     }
@@ -594,6 +637,7 @@ struct Pol2U61 {
     static constexpr bool DOUBLED_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool FRAC_KEY = false;
     static constexpr bool GUARDED = POW2;
     static constexpr bool VARIABLE_NF = POW2;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
@@ -644,6 +688,7 @@ struct Pol4U61 {
     static constexpr bool DOUBLED_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool FRAC_KEY = false;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = false;
     using Fn = Fn4U61;
@@ -861,6 +906,47 @@ __device__ __forceinline__ void half_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], u32x
 #pragma unroll
     for (int g = 0; g < NF; ++g) MH_MAD_ACC(u64_u32, p[g], x[g], md.negD);
 }
+// The same up to the canonical residue, which is written into the high word of the
+// function's {bias, r} pair; one multiply-add r m_low + {bias, r} and one funnel shift
+// give the fractional key (frac_key of mh_arith.h).
+template <int NF>
+__device__ __forceinline__ void half_2u31_frac(const Fn2U31F (&fn)[HASH_FPL], uint32_t (&key)[HASH_FPL], uint32_t t, const ModDV& md)
+{
+    u32x2 p[HASH_FPL];
+    uint32_t x[HASH_FPL], y[HASH_FPL], r;
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"(p[g].x));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"(p[g].y));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_sub_u32 %0, %1, %2" : "=v"(y[g]) : "v"(x[g]), "v"(md.p31));
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) {
+        asm volatile("v_min_u32 %0, %1, %2" : "=v"(r) : "v"(x[g]), "v"(y[g]));
+        fn[g].bq.y = r;
+    }
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].bq.y, md.frac_m, fn[g].bq);
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, %3" : "=v"(key[g]) : "v"(p[g].y), "v"(p[g].x), "s"(md.frac_l));
+}
+template <int NF>
+__device__ __forceinline__ void pair_2u31_frac(const Fn2U31F (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta,
+                                               uint32_t tb, const ModDV& md)
+{
+    uint32_t ka[HASH_FPL], kb[HASH_FPL];
+    half_2u31_frac<NF>(fn, ka, ta, md);
+    half_2u31_frac<NF>(fn, kb, tb, md);
+#pragma unroll
+    for (int g = 0; g < NF; ++g)
+        asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ka[g]), "v"(kb[g]));
+}
+
 template <int NF>
 __device__ __forceinline__ void pair_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta,
                                               uint32_t tb, const ModDV& md)
@@ -873,8 +959,8 @@ __device__ __forceinline__ void pair_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], uint
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(pa[g].x), "v"(pb[g].x));
 }
 
-template <int NF>
-__device__ __forceinline__ void half_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], u32x2 (&acc)[HASH_FPL], const uint32_t* w,
+template <int NF, bool FRAC, class FnT>
+__device__ __forceinline__ void half_4u31_np2(const FnT (&fn)[HASH_FPL], u32x2 (&acc)[HASH_FPL], const uint32_t* w,
                                               const ModDV& md)
 {
     uint32_t y[HASH_FPL], u[HASH_FPL], v[HASH_FPL], r;
@@ -907,24 +993,34 @@ __device__ __forceinline__ void half_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], u32x
 #pragma unroll
     for (int g = 0; g < NF; ++g) {
         asm volatile("v_min_u32 %0, %1, %2" : "=v"(r) : "v"(u[g]), "v"(y[g]));
-        acc[g].x = r;
+        if constexpr (FRAC) fn[g].bq.y = r; else acc[g].x = r;
     }
+    if constexpr (FRAC) {      // frac_key: r m_low + {bias, r}, then the 32 bits from bit l up
 #pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(u[g]) : "v"(acc[g].x), "v"(md.M));
+        for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, acc[g], fn[g].bq.y, md.frac_m, fn[g].bq);
 #pragma unroll
-    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(u[g]) : "v"(md.sh));
+        for (int g = 0; g < NF; ++g) {
+            asm volatile("v_alignbit_b32 %0, %1, %2, %3" : "=v"(r) : "v"(acc[g].y), "v"(acc[g].x), "s"(md.frac_l));
+            acc[g].x = r;
+        }
+    } else {
 #pragma unroll
-    for (int g = 0; g < NF; ++g)
-        MH_MAD_ACC(u64_u32, acc[g], u[g], md.negD);
+        for (int g = 0; g < NF; ++g) asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(u[g]) : "v"(acc[g].x), "v"(md.M));
+#pragma unroll
+        for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(u[g]) : "v"(md.sh));
+#pragma unroll
+        for (int g = 0; g < NF; ++g)
+            MH_MAD_ACC(u64_u32, acc[g], u[g], md.negD);
+    }
 }
 
-template <int NF>
-__device__ __forceinline__ void pair_4u31_np2(const Fn4U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+template <int NF, bool FRAC, class FnT>
+__device__ __forceinline__ void pair_4u31_np2(const FnT (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                               const uint32_t* wb, const ModDV& md)
 {
     u32x2 ya[HASH_FPL], yb[HASH_FPL];
-    half_4u31_np2<NF>(fn, ya, wa, md);
-    half_4u31_np2<NF>(fn, yb, wb, md);
+    half_4u31_np2<NF, FRAC>(fn, ya, wa, md);
+    half_4u31_np2<NF, FRAC>(fn, yb, wb, md);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g].x), "v"(yb[g].x));
@@ -971,6 +1067,7 @@ struct PolGenericMod {
     static constexpr bool DOUBLED_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = false;
+    static constexpr bool FRAC_KEY = false;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = false;
     static constexpr int DEG = DEGREE;
@@ -1012,6 +1109,7 @@ struct Pol2UMS32 {
     static constexpr bool DOUBLED_KEY = false;
     static constexpr bool TWO_MAXIMA = false;
     static constexpr bool SHIFT_END = true;
+    static constexpr bool FRAC_KEY = false;
     static constexpr bool GUARDED = false;
     static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn2UMS32;
@@ -1058,6 +1156,13 @@ __device__ __forceinline__ void Pol2U31<FORM_FULL>::pair(const Fn (&fn)[HASH_FPL
 }
 template <>
 template <int NF>
+__device__ __forceinline__ void Pol2U31<FORM_FRAC_D>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                           const uint32_t* wb, const ModDV& md, uint64_t)
+{
+    pair_2u31_frac<NF>(fn, m, wa[0], wb[0], md);
+}
+template <>
+template <int NF>
 __device__ __forceinline__ void Pol2U31<FORM_ANY_D>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t)
 {
@@ -1083,7 +1188,14 @@ template <int NF>
 __device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_4u31_np2<NF>(fn, m, wa, wb, md);
+    pair_4u31_np2<NF, false>(fn, m, wa, wb, md);
+}
+template <>
+template <int NF>
+__device__ __forceinline__ void Pol4U31<false, false, true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                                  const uint32_t* wb, const ModDV& md, uint64_t)
+{
+    pair_4u31_np2<NF, true>(fn, m, wa, wb, md);
 }
 
 template <>
@@ -1224,6 +1336,10 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                     else if (Pol::DOUBLED_KEY) m[r] = finish_full2_key(m[r], md.frot, md.mask);
                     else m[r] = Pol::SHIFTED_KEY ? finish_neg_key(m[r], md.kshift, md.mask) : md.mask - m[r];
                 }
+            }
+            if (Pol::FRAC_KEY) {       // from the fractional key back to the hashed location
+#pragma unroll
+                for (int r = 0; r < NF; ++r) m[r] = finish_frac_key(m[r], (uint32_t)a.D);
             }
             if (Pol::SHIFT_END) {      // from the order-preserving key back to the hashed location
 #pragma unroll
@@ -1684,11 +1800,13 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     case MINHASH_2U_M31:
         if (pow2 && D <= (1ull << FULL_KEY_MAX_LOG2_D)) launch_hash<Pol2U31<FORM_FULL>>(a, nf, main_blocks, s);
         else if (pow2) launch_hash<Pol2U31<FORM_FULL_TWO>>(a, nf, main_blocks, s);
+        else if (frac_key_serves(D)) launch_hash<Pol2U31<FORM_FRAC_D>>(a, nf, main_blocks, s);
         else launch_hash<Pol2U31<FORM_ANY_D>>(a, nf, main_blocks, s);
         break;
     case MINHASH_4U_M31:
         if (full4) launch_hash<Pol4U31<true, true>>(a, nf, main_blocks, s);
         else if (pow2) launch_hash<Pol4U31<true, false>>(a, nf, main_blocks, s);
+        else if (frac_key_serves(D)) launch_hash<Pol4U31<false, false, true>>(a, nf, main_blocks, s);
         else launch_hash<Pol4U31<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_2U_M61:

@@ -242,6 +242,33 @@ int main()
         if (built < 10000 || guard_hits - hits_before < 1000) FAIL("carry-free key: %d built, %ld with bit 61 set", built, guard_hits - hits_before);
         if (guard_saves - saves_before < 100) FAIL("carry-free key: only %ld engineered cases came out wrong", guard_saves - saves_before);
     }
+    // Fractional keys for D < 2^28 that is not a power of two: the location comes back exactly, and
+    // keys are ordered like the locations, on edge residues and random ones
+    {
+        long n = 0;
+        for (uint64_t D : {3ull, 5ull, 6ull, 7ull, 1000003ull, 16609143ull, (1ull << 28) - 1, (1ull << 27) + 1, (1ull << 24) - 1,
+                           (1ull << 24) + 1, 65537ull, 100ull}) {
+            if (!frac_key_serves(D)) FAIL("fractional key refuses D=%llu", (unsigned long long)D);
+            const FracD fd = make_frac_d(D);
+            std::vector<uint32_t> rs = {0, 1, (uint32_t)(D - 1), (uint32_t)D, (uint32_t)(D + 1), (uint32_t)(2 * D - 1), (uint32_t)(2 * D),
+                                        (uint32_t)(p31 - 1), (uint32_t)(p31 - 2), (uint32_t)((p31 - 1) / D * D), (uint32_t)((p31 - 1) / D * D - 1),
+                                        (uint32_t)((p31 - 1) / D * D + 1 < p31 ? (p31 - 1) / D * D + 1 : 0)};
+            for (int i = 0; i < 200000; ++i) rs.push_back((uint32_t)(rnd() % p31));
+            for (int i = 0; i < 2000; ++i) { uint64_t q = rnd() % ((p31 - 1) / D + 1); uint64_t r = q * D + (rnd() % 3) - 1 + (i & 1 ? D - 1 : 0); if (r < p31) rs.push_back((uint32_t)r); }
+            uint32_t prev_key = 0; uint64_t prev_v = 0; bool have = false;
+            for (uint32_t r : rs) {
+                const uint32_t key = frac_key(r, fd);
+                const uint64_t v = r % D;
+                if (finish_frac_key(key, (uint32_t)D) != v) FAIL("fractional key D=%llu r=%u gives %u want %llu", (unsigned long long)D, r,
+                                                                 finish_frac_key(key, (uint32_t)D), (unsigned long long)v);
+                if (have && ((v < prev_v && !(key < prev_key)) || (v > prev_v && !(key > prev_key)))) FAIL("fractional key order D=%llu", (unsigned long long)D);
+                prev_key = key; prev_v = v; have = true;
+                ++n;
+            }
+        }
+        if (frac_key_serves(1ull << 20) || frac_key_serves(1ull << 28) || frac_key_serves(1010017424ull) || frac_key_serves(2)) FAIL("fractional key accepts a D it cannot serve");
+        checks += n;
+    }
     // multiply-shift 2U (Section 3.3): ((c0 + c1 t) mod 2^32) mod 2^s, lowest or highest s bits
     for (int sbits = 0; sbits <= 32; ++sbits) {
         uint64_t D = 1ull << sbits;
