@@ -116,6 +116,18 @@ MH_HD uint32_t frac_key(uint32_t r, const FracD& f)      // r < 2^31
 }
 MH_HD uint32_t finish_frac_key(uint32_t key, uint32_t D) { return mulhi_u32(key, D); }
 
+// D of at least p / 3 (and below p = 2^31-1): the quotient of a residue r < p by D is 0, 1
+// or 2, so r mod D is the smallest of r, r - D and r - 2D as unsigned words: a difference
+// that would be negative wraps to the true difference plus 2^32 - D or 2^32 - 2D, both
+// positive, and so exceeds the one that is right.
+MH_HD bool small_quotient_serves(uint64_t D) { return 3 * D >= (uint64_t)P31 && D < (uint64_t)P31 && (D & (D - 1)) != 0; }
+MH_HD uint32_t reduce_small_quotient(uint32_t r, uint32_t D)      // r < p
+{
+    const uint32_t a = r - D, b = a - D;
+    const uint32_t m = a < b ? a : b;
+    return r < m ? r : m;
+}
+
 // r mod D for r < 2^61 and any D in [1, 2^32] (the p = 2^61-1 families with a D that
 // the mask path cannot serve): q = floor(r M64 / 2^64) falls short of the true
 // quotient by at most one, because r (2^64 / D - M64) < 2 r < 2^64 / 4; one

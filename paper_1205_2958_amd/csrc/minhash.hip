@@ -491,10 +491,12 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // (frac_key), one multiply-add and one funnel shift after the canonical residue, instead of the
 // exact quotient's multiply-high, shift and multiply-add; the location comes back once per row.
 // The function keeps a register pair {bias, r} per slot whose low word stays put.
+// FORM_BIG_D (D of at least p / 3): the quotient is 0, 1 or 2, so r mod D is the smallest of r,
+// r - D and r - 2D (reduce_small_quotient): two subtractions and a three-operand minimum.
 struct Fn2U31F : Fn2U31 {
     mutable u32x2 bq;
 };
-constexpr int FORM_ANY_D = 0, FORM_FULL_TWO = 1, FORM_FULL = 2, FORM_FRAC_D = 3;
+constexpr int FORM_ANY_D = 0, FORM_FULL_TWO = 1, FORM_FULL = 2, FORM_FRAC_D = 3, FORM_BIG_D = 4;
 template <int FORM>
 struct Pol2U31 {
     static constexpr bool POW2 = FORM == FORM_FULL || FORM == FORM_FULL_TWO;
@@ -532,6 +534,10 @@ struct Pol2U31 {
             const uint32_t x = fold_2u31(f, w[0]), y = x - (uint32_t)P31;
             return frac_key(y < x ? y : x, make_frac_d(md.D));
         }
+        if (FORM == FORM_BIG_D) {
+            const uint32_t x = fold_2u31(f, w[0]), y = x - (uint32_t)P31;
+            return reduce_small_quotient(y < x ? y : x, md.D);
+        }
         return hash_2u31_raw(f, w[0], md);
     }
     template <int NF>
@@ -562,10 +568,13 @@ struct Pol2U31 {
 struct Fn4U31F : Fn4U31 {
     mutable u32x2 bq;
 };
-template <bool POW2, bool FULL = false, bool FRAC = false>
+// MODE, for D that is not a power of two: 0 exact quotient, 1 fractional keys, 2 the quotient of
+// at most 2 of Pol2U31<FORM_BIG_D>.
+template <bool POW2, bool FULL = false, int MODE = 0>
 struct Pol4U31 {
+    static constexpr bool FRAC = MODE == 1;
     static_assert(POW2 || !FULL, "full keys are for power-of-two D");
-    static_assert(!POW2 || !FRAC, "fractional keys are for D that is not a power of two");
+    static_assert(!POW2 || MODE == 0, "the modes are for D that is not a power of two");
     static constexpr int NW = 3;
     static constexpr int MIN_WAVES = POW2 ? 4 : 3;
     static constexpr bool TRACK_MAX = POW2;
@@ -603,9 +612,9 @@ struct Pol4U31 {
         Pow4U31 p;
         p.t1 = (int32_t)w[0]; p.t2 = (int32_t)w[1]; p.t3 = (int32_t)w[2];
         if (FULL) return fold_4u31(f, p);
-        if (FRAC) {
-            const uint32_t x = fold_4u31(f, p), u = x - 1u, v = x ^ 0x80000000u;
-            return frac_key(v < u ? v : u, make_frac_d(md.D));
+        if (MODE != 0) {
+            const uint32_t x = fold_4u31(f, p), u = x - 1u, v = x ^ 0x80000000u, r = v < u ? v : u;
+            return FRAC ? frac_key(r, make_frac_d(md.D)) : reduce_small_quotient(r, md.D);
         }
         if (POW2) return key_neg_4u31(f, p, md.kshift);
         return hash_4u31_np2(f, p, md);
@@ -947,6 +956,47 @@ __device__ __forceinline__ void pair_2u31_frac(const Fn2U31F (&fn)[HASH_FPL], ui
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ka[g]), "v"(kb[g]));
 }
 
+// D of at least p / 3: the same up to the canonical residue r, then r - D, r - 2D and the
+// smallest of the three (reduce_small_quotient of mh_arith.h).
+template <int NF>
+__device__ __forceinline__ void half_2u31_bigd(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&v)[HASH_FPL], uint32_t t, const ModDV& md)
+{
+    u32x2 p[HASH_FPL];
+    uint32_t x[HASH_FPL], y[HASH_FPL];
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"(p[g].x));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %0, %1" : "+v"(x[g]) : "v"(p[g].y));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_sub_u32 %0, %1, %2" : "=v"(y[g]) : "v"(x[g]), "v"(md.p31));
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_min_u32 %0, %1, %2" : "=v"(v[g]) : "v"(x[g]), "v"(y[g]));
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %1, %2" : "=v"(x[g]) : "v"(v[g]), "v"(md.negD));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %1, %2" : "=v"(y[g]) : "v"(x[g]), "v"(md.negD));
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(v[g]) : "v"(x[g]), "v"(y[g]));
+}
+template <int NF>
+__device__ __forceinline__ void pair_2u31_bigd(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta,
+                                               uint32_t tb, const ModDV& md)
+{
+    uint32_t va[HASH_FPL], vb[HASH_FPL];
+    half_2u31_bigd<NF>(fn, va, ta, md);
+    half_2u31_bigd<NF>(fn, vb, tb, md);
+#pragma unroll
+    for (int g = 0; g < NF; ++g)
+        asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(va[g]), "v"(vb[g]));
+}
+
 template <int NF>
 __device__ __forceinline__ void pair_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], uint32_t ta,
                                               uint32_t tb, const ModDV& md)
@@ -959,7 +1009,7 @@ __device__ __forceinline__ void pair_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], uint
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(pa[g].x), "v"(pb[g].x));
 }
 
-template <int NF, bool FRAC, class FnT>
+template <int NF, int MODE, class FnT>      // MODE 0: exact quotient, 1: fractional key, 2: quotient of at most 2
 __device__ __forceinline__ void half_4u31_np2(const FnT (&fn)[HASH_FPL], u32x2 (&acc)[HASH_FPL], const uint32_t* w,
                                               const ModDV& md)
 {
@@ -993,9 +1043,22 @@ __device__ __forceinline__ void half_4u31_np2(const FnT (&fn)[HASH_FPL], u32x2 (
 #pragma unroll
     for (int g = 0; g < NF; ++g) {
         asm volatile("v_min_u32 %0, %1, %2" : "=v"(r) : "v"(u[g]), "v"(y[g]));
-        if constexpr (FRAC) fn[g].bq.y = r; else acc[g].x = r;
+        if constexpr (MODE == 1) fn[g].bq.y = r; else acc[g].x = r;
     }
-    if constexpr (FRAC) {      // frac_key: r m_low + {bias, r}, then the 32 bits from bit l up
+    if constexpr (MODE == 2) {        // reduce_small_quotient: the smallest of r, r - D, r - 2D
+        issue_priority<0>();
+#pragma unroll
+        for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %1, %2" : "=v"(u[g]) : "v"(acc[g].x), "v"(md.negD));
+#pragma unroll
+        for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %1, %2" : "=v"(y[g]) : "v"(u[g]), "v"(md.negD));
+        issue_priority<1>();
+#pragma unroll
+        for (int g = 0; g < NF; ++g) {
+            r = acc[g].x;
+            asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(r) : "v"(u[g]), "v"(y[g]));
+            acc[g].x = r;
+        }
+    } else if constexpr (MODE == 1) { // frac_key: r m_low + {bias, r}, then the 32 bits from bit l up
 #pragma unroll
         for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, acc[g], fn[g].bq.y, md.frac_m, fn[g].bq);
 #pragma unroll
@@ -1014,13 +1077,13 @@ __device__ __forceinline__ void half_4u31_np2(const FnT (&fn)[HASH_FPL], u32x2 (
     }
 }
 
-template <int NF, bool FRAC, class FnT>
+template <int NF, int MODE, class FnT>
 __device__ __forceinline__ void pair_4u31_np2(const FnT (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                               const uint32_t* wb, const ModDV& md)
 {
     u32x2 ya[HASH_FPL], yb[HASH_FPL];
-    half_4u31_np2<NF, FRAC>(fn, ya, wa, md);
-    half_4u31_np2<NF, FRAC>(fn, yb, wb, md);
+    half_4u31_np2<NF, MODE>(fn, ya, wa, md);
+    half_4u31_np2<NF, MODE>(fn, yb, wb, md);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g].x), "v"(yb[g].x));
@@ -1163,6 +1226,13 @@ __device__ __forceinline__ void Pol2U31<FORM_FRAC_D>::pair(const Fn (&fn)[HASH_F
 }
 template <>
 template <int NF>
+__device__ __forceinline__ void Pol2U31<FORM_BIG_D>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                          const uint32_t* wb, const ModDV& md, uint64_t)
+{
+    pair_2u31_bigd<NF>(fn, m, wa[0], wb[0], md);
+}
+template <>
+template <int NF>
 __device__ __forceinline__ void Pol2U31<FORM_ANY_D>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t)
 {
@@ -1188,14 +1258,21 @@ template <int NF>
 __device__ __forceinline__ void Pol4U31<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                      const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_4u31_np2<NF, false>(fn, m, wa, wb, md);
+    pair_4u31_np2<NF, 0>(fn, m, wa, wb, md);
 }
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol4U31<false, false, true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+__device__ __forceinline__ void Pol4U31<false, false, 2>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                               const uint32_t* wb, const ModDV& md, uint64_t)
+{
+    pair_4u31_np2<NF, 2>(fn, m, wa, wb, md);
+}
+template <>
+template <int NF>
+__device__ __forceinline__ void Pol4U31<false, false, 1>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
                                                                   const uint32_t* wb, const ModDV& md, uint64_t)
 {
-    pair_4u31_np2<NF, true>(fn, m, wa, wb, md);
+    pair_4u31_np2<NF, 1>(fn, m, wa, wb, md);
 }
 
 template <>
@@ -1801,12 +1878,14 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         if (pow2 && D <= (1ull << FULL_KEY_MAX_LOG2_D)) launch_hash<Pol2U31<FORM_FULL>>(a, nf, main_blocks, s);
         else if (pow2) launch_hash<Pol2U31<FORM_FULL_TWO>>(a, nf, main_blocks, s);
         else if (frac_key_serves(D)) launch_hash<Pol2U31<FORM_FRAC_D>>(a, nf, main_blocks, s);
+        else if (small_quotient_serves(D)) launch_hash<Pol2U31<FORM_BIG_D>>(a, nf, main_blocks, s);
         else launch_hash<Pol2U31<FORM_ANY_D>>(a, nf, main_blocks, s);
         break;
     case MINHASH_4U_M31:
         if (full4) launch_hash<Pol4U31<true, true>>(a, nf, main_blocks, s);
         else if (pow2) launch_hash<Pol4U31<true, false>>(a, nf, main_blocks, s);
-        else if (frac_key_serves(D)) launch_hash<Pol4U31<false, false, true>>(a, nf, main_blocks, s);
+        else if (frac_key_serves(D)) launch_hash<Pol4U31<false, false, 1>>(a, nf, main_blocks, s);
+        else if (small_quotient_serves(D)) launch_hash<Pol4U31<false, false, 2>>(a, nf, main_blocks, s);
         else launch_hash<Pol4U31<false>>(a, nf, main_blocks, s);
         break;
     case MINHASH_2U_M61:

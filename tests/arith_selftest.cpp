@@ -269,6 +269,20 @@ int main()
         if (frac_key_serves(1ull << 20) || frac_key_serves(1ull << 28) || frac_key_serves(1010017424ull) || frac_key_serves(2)) FAIL("fractional key accepts a D it cannot serve");
         checks += n;
     }
+    // Small quotients for D >= p / 3: the smallest of r, r - D, r - 2D
+    {
+        for (uint64_t D : {715827883ull, 715827884ull, 1010017424ull, 1073741823ull, 1073741825ull, 2000000011ull, (unsigned long long)(p31 - 1), (unsigned long long)(p31 - 2)}) {
+            if (!small_quotient_serves(D)) FAIL("small quotient refuses D=%llu", (unsigned long long)D);
+            std::vector<uint32_t> rs = {0, 1, (uint32_t)(D - 1), (uint32_t)D, (uint32_t)(D + 1), (uint32_t)(p31 - 1), (uint32_t)(p31 - 2)};
+            if (2 * D < p31) { rs.push_back((uint32_t)(2 * D - 1)); rs.push_back((uint32_t)(2 * D)); rs.push_back((uint32_t)(2 * D + 1)); }
+            for (int i = 0; i < 200000; ++i) rs.push_back((uint32_t)(rnd() % p31));
+            for (uint32_t r : rs) {
+                if (reduce_small_quotient(r, (uint32_t)D) != r % D) FAIL("small quotient D=%llu r=%u", (unsigned long long)D, r);
+                ++checks;
+            }
+        }
+        if (small_quotient_serves(715827882ull) || small_quotient_serves(1ull << 30) || small_quotient_serves(p31)) FAIL("small quotient accepts a D it cannot serve");
+    }
     // multiply-shift 2U (Section 3.3): ((c0 + c1 t) mod 2^32) mod 2^s, lowest or highest s bits
     for (int sbits = 0; sbits <= 32; ++sbits) {
         uint64_t D = 1ull << sbits;
