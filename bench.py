@@ -52,7 +52,12 @@ ISSUE_MIX_OTHER_D_FRAC = {
     W.FAMILY_2U_M31: (2.0, 1.0 + 1.0 + 0.5, 3.0),         # mad, mad | min, funnel shift, half a min3 | shr,add,sub
     W.FAMILY_4U_M31: (4.0, 1.0 + 1.0 + 1.0 + 0.5, 5.0),   # 3 mad, mad | add3, min, funnel shift, half a min3 | shr,and,shr,add,xor
 }
-# other D from 2^28 up: exact multiply-high quotient appended
+# other D of at least p/3: the smallest of r, r - D, r - 2D, no multiply after the canonical residue
+ISSUE_MIX_OTHER_D_BIG = {
+    W.FAMILY_2U_M31: (1.0, 1.0 + 1.0 + 0.5, 5.0),         # mad | min, min3, half a min3 | shr,add,sub,add,add
+    W.FAMILY_4U_M31: (3.0, 1.0 + 1.0 + 1.0 + 0.5, 7.0),   # 3 mad | add3, min, min3, half a min3 | shr,and,shr,add,xor,add,add
+}
+# other D from 2^28 to p/3: exact multiply-high quotient appended
 ISSUE_MIX_OTHER_D = {
     W.FAMILY_2U_M31: (3.0, 1.0 + 0.5, 4.0),         # mad, mulhi, mad | min, half a min3 | shr,add,sub,shr
     W.FAMILY_4U_M31: (5.0, 1.0 + 1.0 + 0.5, 6.0),   # 3 mad, mulhi, mad | add3, min, half a min3 | shr,and,shr,add,xor,shr
@@ -408,7 +413,8 @@ def main() -> int:
                 "model": "4k+4 bytes per nonzero (one table row + the index) + row_ptr + packed output"}
     else:
         if D & (D - 1):
-            mix = ISSUE_MIX_OTHER_D_FRAC[family] if D < (1 << 28) else ISSUE_MIX_OTHER_D[family]
+            mix = (ISSUE_MIX_OTHER_D_FRAC if D < (1 << 28) else
+                   ISSUE_MIX_OTHER_D_BIG if 3 * D >= (1 << 31) - 1 else ISSUE_MIX_OTHER_D)[family]
         else:
             mix = ISSUE_MIX[family]
         slots = issue_slots(mix)
