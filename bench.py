@@ -292,7 +292,8 @@ def main() -> int:
                          "evaluation instead of the shorter form with its guard")
     ap.add_argument("--universe", type=int, default=0,
                     help="hash families with p = 2^31-1: run with this universe size D instead of the workload's power of "
-                         "two (indices are folded into [0, D)), e.g. 16609143, to time the path for other D")
+                         "two (indices are folded into [0, D); a larger D leaves them as they are), e.g. 16609143 or "
+                         "1010017424, to time the paths for other D")
     ap.add_argument("--calib", action="store_true",
                     help="also launch one plain streaming kernel of known size (reads 1 GiB, writes 1 GiB) so that "
                          "FETCH_SIZE / WRITE_SIZE counters of a profiler run can be scaled")
@@ -307,8 +308,8 @@ def main() -> int:
     w = W.WORKLOADS[args.workload]
     family = w.family
     if args.universe and (family not in ISSUE_MIX_OTHER_D or args.stream or args.generic_mod
-                          or not 1 <= args.universe < w.D):
-        print("bench.py: --universe needs a 2U/4U workload with p = 2^31-1 and a D below the workload's", file=sys.stderr)
+                          or not 1 <= args.universe < (1 << 31) - 1):
+        print("bench.py: --universe needs a 2U/4U workload with p = 2^31-1 and a D below the prime", file=sys.stderr)
         return 2
     D = args.universe or w.D
     if family == W.FAMILY_PERM:
