@@ -572,4 +572,69 @@ MH_HD Fn2UMS32 prep_2ums32_key(uint64_t c0, uint64_t c1, uint32_t shift)    // s
 MH_HD uint32_t key_2ums32(const Fn2UMS32& f, uint32_t t) { return (uint32_t)((uint64_t)f.c1 * t + f.add); }
 MH_HD uint32_t finish_2ums32(uint32_t min_key, uint32_t shift) { return shift >= 32 ? 0u : min_key >> shift; }
 
+// ------------------------------------------------------------------ tickets to work units
+// Which units of the work list a ticket stands for.  Tickets map to units in
+// regions: units of long items, one per ticket (they are listed first); then
+// runs of `run` consecutive units (a power of two of at most 32, sized so that a
+// wavefront still draws about 12 of them); then, level by level, runs of half
+// that size, a quarter, ... down to one unit, LEVEL_DRAWS tickets per wavefront
+// and level; then what is left, unit by unit.  A launch so ends on single short
+// items without all wavefronts drawing tickets for single items at once: one
+// address takes fewer than 10^8 atomics a second, and some thousand wavefronts
+// that each finish a short row in a few microseconds ask for more.  The
+// wavefronts still busy with the last tickets of one level are matched by two
+// draws of half the size for the others.  Batches of long rows get runs of one
+// and are handed out unit by unit.  A ticket beyond the last unit gets the empty
+// range [n_units, n_units + 1).
+struct TicketMap {
+    static constexpr uint32_t LEVEL_DRAWS = 2;
+    uint32_t n_units;       // fits 32 bits (the host refuses larger batches)
+    uint32_t single;        // tickets below this are units of long items
+    uint32_t n_runs;        // then n_runs tickets of 1 << lg_run units each
+    uint32_t lg_run;
+    uint32_t per_level;     // tickets of each level of shorter runs
+
+    MH_HD void range(uint32_t tk, uint32_t* first, uint32_t* end) const
+    {
+        if (tk < single) {
+            *first = tk;
+            *end = tk + 1;
+            return;
+        }
+        uint32_t t = tk - single;
+        if (t < n_runs) {
+            *first = single + (t << lg_run);
+            *end = *first + (1u << lg_run);
+            return;
+        }
+        t -= n_runs;
+        const uint32_t run = 1u << lg_run;
+        uint64_t base = (uint64_t)single + ((uint64_t)n_runs << lg_run);
+        const uint32_t level = lg_run ? t / per_level : 0u;     // level 0: runs of run / 2, level 1: run / 4, ...
+        if (level < lg_run) {
+            const uint32_t r_lg = lg_run - 1u - level;
+            base += (uint64_t)per_level * (run - (run >> level));   // the levels before took run/2 + ... + run/2^level units per ticket column
+            *first = (uint32_t)(base + ((uint64_t)(t - level * per_level) << r_lg));
+            *end = *first + (1u << r_lg);
+            return;
+        }
+        const uint64_t u = base + (uint64_t)per_level * (run - 1u) + (t - lg_run * per_level);
+        *first = u < n_units ? (uint32_t)u : n_units;
+        *end = *first + 1;
+    }
+};
+MH_HD TicketMap make_ticket_map(uint64_t units, uint64_t single_units, uint32_t waves)
+{
+    TicketMap m;
+    m.n_units = (uint32_t)units;
+    m.single = (uint32_t)(single_units < units ? single_units : units);
+    const uint32_t rest = m.n_units - m.single;
+    const uint32_t want = rest / (waves * 12u);
+    m.lg_run = want < 2 ? 0u : (want >= 32 ? 5u : 31u - (uint32_t)__builtin_clz(want));
+    m.per_level = waves * TicketMap::LEVEL_DRAWS;
+    // the levels take per_level * (run - 1) units, fewer than rest / 6 by the choice of run
+    m.n_runs = m.lg_run ? (rest - m.per_level * ((1u << m.lg_run) - 1u)) >> m.lg_run : 0u;
+    return m;
+}
+
 }  // namespace mh

@@ -166,50 +166,21 @@ __device__ __forceinline__ uint32_t first_lane_value(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
 }
 
-// Hands work units to a persistent wavefront by ticket.  The first ticket of a
-// wavefront is its own index in the grid, later ones come from an atomic counter
-// that starts behind the grid, so a call with fewer units than resident
-// wavefronts costs no atomic at all.  Tickets map to units in three regions:
-// units of long items, one per ticket (they are listed first); then runs of
-// consecutive units, sized so that a wavefront still draws about 32 of them; then
-// the last 16 units per wavefront one per ticket again, so that the tail is made
-// of single short items.  A single address takes fewer than 10^8 atomics a
-// second, which bounded a batch of millions of short rows when every unit cost
-// one; batches of the benchmark's size get runs of one and are handed out unit
-// by unit as before.  All values are wavefront-uniform.
+// Hands work units to a persistent wavefront by ticket (TicketMap of mh_arith.h
+// says which units a ticket stands for).  The first ticket of a wavefront is its
+// own index in the grid, later ones come from an atomic counter that starts
+// behind the grid, so a call with fewer units than resident wavefronts costs no
+// atomic at all.  All values are wavefront-uniform.
 struct UnitDispenser {
-    uint32_t n_units;       // the host refuses batches whose unit count does not fit 32 bits
-    uint32_t single;        // tickets below this are units of long items
-    uint32_t n_runs, run;   // then n_runs tickets of `run` units each
+    TicketMap map;
     uint32_t grid_waves;
     uint32_t next, end;     // units of the current ticket still to do
 
     __device__ __forceinline__ void init(uint64_t units, uint64_t single_units, uint32_t waves, uint32_t index)
     {
-        n_units = (uint32_t)units;
-        single = (uint32_t)(single_units < units ? single_units : units);
+        map = make_ticket_map(units, single_units, waves);
         grid_waves = waves;
-        const uint32_t rest = n_units - single;
-        const uint32_t want = rest / (waves * 32u);
-        run = want < 1 ? 1u : (want > 32 ? 32u : want);
-        const uint32_t tail = rest < waves * 16u ? rest : waves * 16u;
-        n_runs = run > 1 ? (rest - tail) / run : 0u;
-        next = end = 0;
-        set_ticket(index);          // the first ticket needs no atomic
-    }
-    __device__ __forceinline__ void set_ticket(uint32_t tk)
-    {
-        if (tk < single) {
-            next = tk;
-            end = tk + 1;
-        } else if (tk - single < n_runs) {
-            next = single + (tk - single) * run;
-            end = next + run;
-        } else {
-            const uint64_t u = (uint64_t)single + (uint64_t)n_runs * run + (tk - single - n_runs);
-            next = u < n_units ? (uint32_t)u : n_units;
-            end = next + 1;
-        }
+        map.range(index, &next, &end);          // the first ticket needs no atomic
     }
     // false when nothing is left; every wavefront gets there because tickets only grow
     __device__ __forceinline__ bool take(uint32_t* counter, int lane, uint32_t* unit)
@@ -217,9 +188,9 @@ struct UnitDispenser {
         if (next >= end) {
             uint32_t tk = 0;
             if (lane == 0) tk = grid_waves + atomicAdd(counter, 1u);
-            set_ticket(first_lane_value(tk));
+            map.range(first_lane_value(tk), &next, &end);
         }
-        if (next >= n_units) return false;
+        if (next >= map.n_units) return false;
         *unit = next++;
         return true;
     }

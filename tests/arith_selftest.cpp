@@ -317,6 +317,46 @@ int main()
             checks += 2;
         }
     }
+    // TicketMap: the ranges of tickets 0, 1, 2, ... tile [0, units) in order, one unit per ticket among the
+    // long items, runs of at most 32 elsewhere that never grow again once they shrank; later tickets are empty
+    {
+        const uint32_t wave_counts[] = {1, 4, 7, 64, 5120, 8192};
+        const uint64_t unit_counts[] = {0, 1, 2, 63, 64, 65, 1000, 4095, 61440, 61441, 122880, 200000, 262144, 983040, 2000000, 2236962, 5000001};
+        for (uint32_t waves : wave_counts)
+            for (uint64_t units : unit_counts)
+                for (int sv = 0; sv < 4; ++sv) {
+                    const uint64_t single = sv == 0 ? 0 : sv == 1 ? units / 3 : sv == 2 ? units : units + 5;
+                    const TicketMap tm = make_ticket_map(units, single, waves);
+                    uint64_t covered = 0;
+                    uint32_t tk = 0, prev_len = 32, n_tickets_past_long = 0;
+                    for (; covered < units; ++tk) {
+                        uint32_t a, b;
+                        tm.range(tk, &a, &b);
+                        if (a != covered || b <= a || b - a > 32 || b > units)
+                            FAIL("ticket map: waves %u units %llu single %llu ticket %u covers [%u, %u), expected a range from %llu",
+                                 waves, (unsigned long long)units, (unsigned long long)single, tk, a, b, (unsigned long long)covered);
+                        if (a < (single < units ? single : units)) {
+                            if (b - a != 1) FAIL("ticket map: long item in a run of %u", b - a);
+                        } else {
+                            if (b - a > prev_len) FAIL("ticket map: run grows from %u to %u at ticket %u", prev_len, b - a, tk);
+                            prev_len = b - a;
+                            ++n_tickets_past_long;
+                        }
+                        covered = b;
+                        ++checks;
+                    }
+                    for (uint32_t extra = 0; extra < 3 * waves + 3; extra += waves / 2 + 1) {
+                        uint32_t a, b;
+                        tm.range(tk + extra, &a, &b);
+                        if (a < units) FAIL("ticket map: ticket %u past the end covers unit %u", tk + extra, a);
+                        ++checks;
+                    }
+                    // many short units: far fewer tickets than units, and only a few single ones at the end
+                    const uint64_t rest = units - (single < units ? single : units);
+                    if (rest >= (uint64_t)waves * 12 * 32 && n_tickets_past_long > rest / 32 + (uint64_t)waves * 2 * 5 + 32)
+                        FAIL("ticket map: %u tickets for %llu short units on %u waves", n_tickets_past_long, (unsigned long long)rest, waves);
+                }
+    }
     if (full_bit31 < 1000 || full_doubtful < full_bit31) FAIL("full keys: %ld with bit 31 set, %ld doubtful", full_bit31, full_doubtful);
     if (full4_high < 100000) FAIL("4U full keys: only %ld evaluations above p", full4_high);
     printf("OK %ld\n", checks);
