@@ -82,6 +82,8 @@ struct WorkHeader {                    // first 256 bytes of the workspace
     uint32_t pad[57];
 };
 static_assert(sizeof(WorkHeader) == 256, "header size");
+static_assert(offsetof(WorkHeader, n_short) == 4 && offsetof(WorkHeader, n_split) == 8 && offsetof(WorkHeader, n_parts) == 12,
+              "the row-binning kernel addresses the four counters as an array");
 
 struct Item {                          // one unit of row work
     int64_t begin;                     // offset of the first nonzero in col_idx
@@ -305,14 +307,21 @@ __global__ void mh_reset_kernel(KArgs a)
     }
 }
 
-// One thread per row.  Wave-level prefix sums make one atomic per wavefront and
-// counter.  Items longer than LONG_ITEM go to the front of the work list, the
-// rest behind them: the persistent wavefronts draw tickets in list order, so the
-// long items start first and the short ones fill the tail of the launch.
-__global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
+// One thread per row.  Prefix sums over the wavefront and then over the block's
+// wavefronts make one atomic per block of 1024 rows and counter (one per
+// wavefront made 31 000 atomics on one address for 2x10^6 rows, and those took
+// all of the kernel's 0.36 ms).  Items longer than LONG_ITEM go to the front of
+// the work list, the rest behind them: the persistent wavefronts draw tickets in
+// list order, so the long items start first and the short ones fill the tail of
+// the launch.
+constexpr int BIN_BLOCK = 1024;
+__global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
 {
+    __shared__ uint32_t s_wave_tot[BIN_BLOCK / WAVE][4];     // totals per wavefront, then their exclusive prefix sums
+    __shared__ uint32_t s_block_base[4];
     const int lane = threadIdx.x & (WAVE - 1);
-    const int64_t row = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+    const int wave = threadIdx.x >> 6;
+    const int64_t row = (int64_t)blockIdx.x * BIN_BLOCK + threadIdx.x;
     uint32_t CHUNK = a.hdr->chunk;
     if (CHUNK < MIN_CHUNK || CHUNK > MAX_CHUNK) CHUNK = MAX_CHUNK;
     uint32_t n_it = 0, is_split = 0;
@@ -343,19 +352,26 @@ __global__ __launch_bounds__(BLOCK) void mh_bin_rows_kernel(KArgs a)
         uint32_t v3 = (uint32_t)__shfl_up((int)inc_pt, d, WAVE);
         if (lane >= d) { inc_lg += v0; inc_sh += v1; inc_sp += v2; inc_pt += v3; }
     }
-    const uint32_t tot_lg = wave_bcast(inc_lg, WAVE - 1), tot_sh = wave_bcast(inc_sh, WAVE - 1);
-    const uint32_t tot_sp = wave_bcast(inc_sp, WAVE - 1), tot_pt = wave_bcast(inc_pt, WAVE - 1);
-    uint32_t base_lg = 0, base_sh = 0, base_sp = 0, base_pt = 0;
     if (lane == WAVE - 1) {
-        if (tot_lg) base_lg = atomicAdd(&a.hdr->n_long, tot_lg);
-        if (tot_sh) base_sh = atomicAdd(&a.hdr->n_short, tot_sh);
-        if (tot_sp) base_sp = atomicAdd(&a.hdr->n_split, tot_sp);
-        if (tot_pt) base_pt = atomicAdd(&a.hdr->n_parts, tot_pt);
+        s_wave_tot[wave][0] = inc_lg; s_wave_tot[wave][1] = inc_sh;
+        s_wave_tot[wave][2] = inc_sp; s_wave_tot[wave][3] = inc_pt;
     }
-    base_lg = wave_bcast(base_lg, WAVE - 1);
-    base_sh = wave_bcast(base_sh, WAVE - 1);
-    base_sp = wave_bcast(base_sp, WAVE - 1);
-    base_pt = wave_bcast(base_pt, WAVE - 1);
+    __syncthreads();
+    if (threadIdx.x < 4) {             // thread c: counter c of the block
+        uint32_t* const counter = &a.hdr->n_long + threadIdx.x;   // n_long, n_short, n_split, n_parts lie in a row
+        uint32_t run = 0;
+        for (int w = 0; w < BIN_BLOCK / WAVE; ++w) {
+            const uint32_t t = s_wave_tot[w][threadIdx.x];
+            s_wave_tot[w][threadIdx.x] = run;
+            run += t;
+        }
+        s_block_base[threadIdx.x] = run ? atomicAdd(counter, run) : 0u;
+    }
+    __syncthreads();
+    const uint32_t base_lg = s_block_base[0] + s_wave_tot[wave][0];
+    const uint32_t base_sh = s_block_base[1] + s_wave_tot[wave][1];
+    const uint32_t base_sp = s_block_base[2] + s_wave_tot[wave][2];
+    const uint32_t base_pt = s_block_base[3] + s_wave_tot[wave][3];
     if (row >= a.n_rows) return;
     const uint64_t first_lg = (uint64_t)base_lg + inc_lg - n_lg;
     const uint64_t first_sh = (uint64_t)base_sh + inc_sh - n_sh;
@@ -1829,8 +1845,8 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     const int cus = device_cus();
     a.target_items = (uint32_t)cus * 24u * 2u;     // two items per wavefront of a fully occupied launch
     hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, s, a);
-    const int bin_blocks = (int)((n_rows + BLOCK - 1) / BLOCK);
-    hipLaunchKernelGGL(mh_bin_rows_kernel, dim3(bin_blocks), dim3(BLOCK), 0, s, a);
+    const int bin_blocks = (int)((n_rows + BIN_BLOCK - 1) / BIN_BLOCK);
+    hipLaunchKernelGGL(mh_bin_rows_kernel, dim3(bin_blocks), dim3(BIN_BLOCK), 0, s, a);
 
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (profiled) {
