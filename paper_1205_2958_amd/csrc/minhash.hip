@@ -1638,6 +1638,7 @@ __global__ __launch_bounds__(BLOCK) void mh_finalize_kernel(KArgs a, int ftile_s
         const SplitRow sr = a.split_rows[sidx];
         for (int j = lane; j < nf; j += WAVE) {
             uint32_t v = EMPTY_MIN;
+#pragma unroll 4
             for (uint32_t c = 0; c < sr.n_parts; ++c) {
                 uint32_t o = a.scratch[(size_t)(sr.first_part + c) * (size_t)a.k + j0 + j];
                 v = o < v ? o : v;
@@ -1897,7 +1898,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         return MINHASH_ERR_FAMILY;
     }
     hipError_t re = profiled ? hipEventRecord(e1, s) : hipSuccess;
-    if (L.cap_split > 0) hipLaunchKernelGGL(mh_finalize_kernel, dim3(cus * 2), dim3(BLOCK), 0, s, a, ftile_size);
+    if (L.cap_split > 0) hipLaunchKernelGGL(mh_finalize_kernel, dim3(cus * 8), dim3(BLOCK), 0, s, a, ftile_size);   // latency-bound: fill the chip
 
     hipError_t le = hipGetLastError();
     if (profiled) {

@@ -92,6 +92,25 @@ def test_large_workloads_sampled_rows(name, n_random, budget):
     assert bool((out != 0xAA).any(dim=1).all().item())
 
 
+def test_many_short_rows_do_not_depend_on_how_units_are_handed_out():
+    """A batch of 2x10^6 short rows is handed to the wavefronts in runs of 32 rows that halve
+    towards the end of the launch; slices of 3 000 rows (fewer than there are resident wavefronts:
+    no run, hardly a ticket) are handed out row by row.  Every row of a slice must get the
+    signature it has in the whole batch, wherever the slice lies: in the long runs, across the
+    levels of shorter runs and among the last single rows.  Two larger slices get runs of their own
+    sizes."""
+    w, nnz, rp_np, seed, col, params, params_np, out = _run_workload("short_rows_2u")
+    n = len(nnz)
+    slices = [(lo, 3_000) for lo in (0, 1_000_003, n - 700_000, n - 200_000, n - 60_000, n - 12_000, n - 3_000)]
+    slices += [(500_000, 150_000), (1_200_000, 520_000)]      # batches that get runs of 2 and of 8 rows
+    for lo, size in slices:
+        hi = min(n, lo + size)
+        rp_part = torch.from_numpy(rp_np[lo:hi + 1] - rp_np[lo]).to(DEV)
+        col_part = col[int(rp_np[lo]):int(rp_np[hi])]
+        part = mh.minhash_signatures(rp_part, col_part, w.D, w.k, w.b, w.family, params)
+        assert torch.equal(part, out[lo:hi]), "rows %d..%d differ between the whole batch and a slice of it" % (lo, hi)
+
+
 @pytest.mark.parametrize("batch", [0, 9])
 def test_heavy_tailed_m61_batch_sampled_rows(batch):
     w, nnz, rp_np, seed, col, params, params_np, out = _run_workload("huge_2u_m61", batch)
