@@ -1292,7 +1292,9 @@ __device__ __forceinline__ void load_tile(const uint32_t* col, int64_t begin, ui
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         uint32_t e = off + (uint32_t)lane + (uint32_t)(WAVE * q);
-        r[q] = e < len ? __builtin_nontemporal_load(col + begin + e) : pad;
+        r[q] = pad;
+        if (off + (uint32_t)(WAVE * q) < len)          // wavefront-uniform: a short row issues no load for the groups it lacks
+            r[q] = e < len ? __builtin_nontemporal_load(col + begin + e) : pad;
     }
 }
 
@@ -1358,9 +1360,13 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             uint32_t regs[4];
             load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
             for (uint32_t off = 0; off < len; off += TILE) {
+                const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
+                const int n_steps = (int)((in_tile + 4u * n_slices - 1u) / (4u * n_slices));
+                const int extent = n_steps * 4 * n_slices;      // tile entries the steps below read (pad included)
                 // stage: pre-compute what depends on t alone, one nonzero per lane and register
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
+                    if (WAVE * q >= extent) break;               // wavefront-uniform: never read, not staged
                     uint32_t t = regs[q];
                     if (a.validate && (uint64_t)t >= a.D) {
                         atomicOr(&a.hdr->status, 2u);
@@ -1374,8 +1380,6 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                 wave_sync_lds();
                 if (off + TILE < len) load_tile(a.col_idx, begin, len, off + TILE, pad, lane, regs);
 
-                const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
-                const int n_steps = (int)((in_tile + 4u * n_slices - 1u) / (4u * n_slices));
                 for (int s = 0; s < n_steps; ++s) {
                     const int e = 4 * (s * n_slices + slice);
                     uint32_t w[4][Pol::NW];
