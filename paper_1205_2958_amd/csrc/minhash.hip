@@ -721,16 +721,26 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
     }
 }
 
-// widening multiply-add; the carry-out pair it must name is never read
+// Widening multiply-add of function slot g (the loop variable at every use).  The
+// carry-out it must name is never read; it goes to one of four scalar register pairs in
+// turn (vcc as one of them still got a wait state before it).  With one destination for all, the compiler sees each statement redefine
+// a register of the one before and, not knowing what the text holds, puts a wait
+// state between any two of them (28 per step of the 2U loop); it asks for three
+// other instructions between statements that name the same register.
+#define MH_MAD_TEXT(KIND, SDST, LAST) "v_mad_" #KIND " %0, " SDST ", %1, %2, " LAST
 #define MH_MAD(KIND, DST, A, B, C)                                                                                 \
     do {                                                                                                           \
-        uint64_t cy_;                                                                                              \
-        asm volatile("v_mad_" #KIND " %0, %1, %2, %3, %4" : "=v"(DST), "=s"(cy_) : "v"(A), "v"(B), "v"(C));        \
+        if ((g & 3) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s94", "s95"); \
+        else if ((g & 3) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s96", "s97"); \
+        else if ((g & 3) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s98", "s99"); \
+        else asm volatile(MH_MAD_TEXT(KIND, "s[100:101]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s100", "s101"); \
     } while (0)
 #define MH_MAD_ACC(KIND, ACC, A, B)                                                                                \
     do {                                                                                                           \
-        uint64_t cy_;                                                                                              \
-        asm volatile("v_mad_" #KIND " %0, %1, %2, %3, %0" : "+v"(ACC), "=s"(cy_) : "v"(A), "v"(B));                \
+        if ((g & 3) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s94", "s95"); \
+        else if ((g & 3) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s96", "s97"); \
+        else if ((g & 3) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s98", "s99"); \
+        else asm volatile(MH_MAD_TEXT(KIND, "s[100:101]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s100", "s101"); \
     } while (0)
 
 // 2U, p = 2^31-1, power-of-two D, with the instruction order fixed by hand.
