@@ -722,11 +722,11 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 }
 
 // Widening multiply-add of function slot g (the loop variable at every use).  The
-// carry-out it must name is never read; it goes to one of four scalar register pairs in
-// turn (vcc as one of them still got a wait state before it).  With one destination for all, the compiler sees each statement redefine
-// a register of the one before and, not knowing what the text holds, puts a wait
-// state between any two of them (28 per step of the 2U loop); it asks for three
-// other instructions between statements that name the same register.
+// carry-out it must name is never read; it goes to one of four scalar register
+// pairs in turn.  With one destination for all (a pair of the compiler's choice,
+// or vcc) the compiler sees each statement redefine a register of the one before
+// and, not knowing what the text holds, puts a wait state between any two of
+// them: 28 per step of the 2U loop.
 #define MH_MAD_TEXT(KIND, SDST, LAST) "v_mad_" #KIND " %0, " SDST ", %1, %2, " LAST
 #define MH_MAD(KIND, DST, A, B, C)                                                                                 \
     do {                                                                                                           \
