@@ -722,24 +722,33 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 }
 
 // Widening multiply-add of function slot g (the loop variable at every use).  The
-// carry-out it must name is never read; it goes to one of four scalar register
-// pairs in turn.  With one destination for all (a pair of the compiler's choice,
+// carry-out it must name is never read; each slot sends it to a scalar register
+// pair of its own, s[86:87] to s[100:101].  With one destination for all (a pair of the compiler's choice,
 // or vcc) the compiler sees each statement redefine a register of the one before
 // and, not knowing what the text holds, puts a wait state between any two of
-// them: 28 per step of the 2U loop.
+// them: 28 per step of the 2U loop (with four pairs in turn it still put one before
+// every fifth).
 #define MH_MAD_TEXT(KIND, SDST, LAST) "v_mad_" #KIND " %0, " SDST ", %1, %2, " LAST
 #define MH_MAD(KIND, DST, A, B, C)                                                                                 \
     do {                                                                                                           \
-        if ((g & 3) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s94", "s95"); \
-        else if ((g & 3) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s96", "s97"); \
-        else if ((g & 3) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s98", "s99"); \
+        if ((g & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s86", "s87"); \
+        else if ((g & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s88", "s89"); \
+        else if ((g & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s90", "s91"); \
+        else if ((g & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s92", "s93"); \
+        else if ((g & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s94", "s95"); \
+        else if ((g & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s96", "s97"); \
+        else if ((g & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s98", "s99"); \
         else asm volatile(MH_MAD_TEXT(KIND, "s[100:101]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s100", "s101"); \
     } while (0)
 #define MH_MAD_ACC(KIND, ACC, A, B)                                                                                \
     do {                                                                                                           \
-        if ((g & 3) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s94", "s95"); \
-        else if ((g & 3) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s96", "s97"); \
-        else if ((g & 3) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s98", "s99"); \
+        if ((g & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s86", "s87"); \
+        else if ((g & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s88", "s89"); \
+        else if ((g & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s90", "s91"); \
+        else if ((g & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s92", "s93"); \
+        else if ((g & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s94", "s95"); \
+        else if ((g & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s96", "s97"); \
+        else if ((g & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s98", "s99"); \
         else asm volatile(MH_MAD_TEXT(KIND, "s[100:101]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s100", "s101"); \
     } while (0)
 
