@@ -74,7 +74,7 @@ HBM_PEAK = 8.0e12
 # HBM bytes per launch of the dominant kernel on the full workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the counter reads for a plain 1 GiB streaming kernel
 # (profiles/mh_hash_kernel_2u_m31__large_2u.txt, profiles/mh_perm_kernel__perm_table.txt).
-MEASURED_TRAFFIC_BYTES = {"large_2u": 6.083e9, "perm_table": 1.1654e12}
+MEASURED_TRAFFIC_BYTES = {"large_2u": 6.066e9, "perm_table": 1.1655e12}
 
 
 def _oracle_worker(args):
