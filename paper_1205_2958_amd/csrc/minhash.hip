@@ -721,7 +721,7 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
     }
 }
 
-// Widening multiply-add of function slot g (the loop variable at every use).  The
+// Widening multiply-add of function slot SLOT.  The
 // carry-out it must name is never read; each slot sends it to a scalar register
 // pair of its own, s[86:87] to s[100:101].  With one destination for all (a pair of the compiler's choice,
 // or vcc) the compiler sees each statement redefine a register of the one before
@@ -729,26 +729,26 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 // them: 28 per step of the 2U loop (with four pairs in turn it still put one before
 // every fifth).
 #define MH_MAD_TEXT(KIND, SDST, LAST) "v_mad_" #KIND " %0, " SDST ", %1, %2, " LAST
-#define MH_MAD(KIND, DST, A, B, C)                                                                                 \
+#define MH_MAD(SLOT, KIND, DST, A, B, C)                                                                                 \
     do {                                                                                                           \
-        if ((g & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s86", "s87"); \
-        else if ((g & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s88", "s89"); \
-        else if ((g & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s90", "s91"); \
-        else if ((g & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s92", "s93"); \
-        else if ((g & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s94", "s95"); \
-        else if ((g & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s96", "s97"); \
-        else if ((g & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s98", "s99"); \
+        if (((SLOT) & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s86", "s87"); \
+        else if (((SLOT) & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s88", "s89"); \
+        else if (((SLOT) & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s90", "s91"); \
+        else if (((SLOT) & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s92", "s93"); \
+        else if (((SLOT) & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s94", "s95"); \
+        else if (((SLOT) & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s96", "s97"); \
+        else if (((SLOT) & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s98", "s99"); \
         else asm volatile(MH_MAD_TEXT(KIND, "s[100:101]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s100", "s101"); \
     } while (0)
-#define MH_MAD_ACC(KIND, ACC, A, B)                                                                                \
+#define MH_MAD_ACC(SLOT, KIND, ACC, A, B)                                                                                \
     do {                                                                                                           \
-        if ((g & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s86", "s87"); \
-        else if ((g & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s88", "s89"); \
-        else if ((g & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s90", "s91"); \
-        else if ((g & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s92", "s93"); \
-        else if ((g & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s94", "s95"); \
-        else if ((g & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s96", "s97"); \
-        else if ((g & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s98", "s99"); \
+        if (((SLOT) & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s86", "s87"); \
+        else if (((SLOT) & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s88", "s89"); \
+        else if (((SLOT) & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s90", "s91"); \
+        else if (((SLOT) & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s92", "s93"); \
+        else if (((SLOT) & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s94", "s95"); \
+        else if (((SLOT) & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s96", "s97"); \
+        else if (((SLOT) & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s98", "s99"); \
         else asm volatile(MH_MAD_TEXT(KIND, "s[100:101]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s100", "s101"); \
     } while (0)
 
@@ -769,7 +769,7 @@ __device__ __forceinline__ void half_2u31_pow2(const Fn2U31 (&fn)[HASH_FPL], uin
     uint64_t p[HASH_FPL];
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, p[g], fn[g].c1, t, fn[g].add);
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"((uint32_t)p[g]));
@@ -788,7 +788,7 @@ __device__ __forceinline__ void half_2u31_doubled(const Fn2U31 (&fn)[HASH_FPL], 
     uint64_t p[HASH_FPL];
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, p[g], fn[g].c1, t, fn[g].add);
     if constexpr (SIMPLE) {
         issue_priority<0>();
 #pragma unroll
@@ -838,13 +838,13 @@ __device__ __forceinline__ void half_4u31_pow2(const Fn4U31 (&fn)[HASH_FPL], uin
     issue_priority<1>();
 #pragma unroll
     for (int g = 0; g < NF; ++g)
-        MH_MAD(i64_i32, acc[g], fn[g].c1, w[0], fn[g].add);
+        MH_MAD(g, i64_i32, acc[g], fn[g].c1, w[0], fn[g].add);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
-        MH_MAD_ACC(i64_i32, acc[g], fn[g].c2, w[1]);
+        MH_MAD_ACC(g, i64_i32, acc[g], fn[g].c2, w[1]);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
-        MH_MAD_ACC(i64_i32, acc[g], fn[g].c3, w[2]);
+        MH_MAD_ACC(g, i64_i32, acc[g], fn[g].c3, w[2]);
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(y[g]) : "v"((uint32_t)acc[g]));
@@ -898,7 +898,7 @@ __device__ __forceinline__ void half_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], u32x
     uint32_t x[HASH_FPL], y[HASH_FPL], r;
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, p[g], fn[g].c1, t, fn[g].add);
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"(p[g].x));
@@ -919,7 +919,7 @@ __device__ __forceinline__ void half_2u31_np2(const Fn2U31 (&fn)[HASH_FPL], u32x
     for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(x[g]) : "v"(md.sh));
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_MAD_ACC(u64_u32, p[g], x[g], md.negD);
+    for (int g = 0; g < NF; ++g) MH_MAD_ACC(g, u64_u32, p[g], x[g], md.negD);
 }
 // The same up to the canonical residue, which is written into the high word of the
 // function's {bias, r} pair; one multiply-add r m_low + {bias, r} and one funnel shift
@@ -931,7 +931,7 @@ __device__ __forceinline__ void half_2u31_frac(const Fn2U31F (&fn)[HASH_FPL], ui
     uint32_t x[HASH_FPL], y[HASH_FPL], r;
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, p[g], fn[g].c1, t, fn[g].add);
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"(p[g].x));
@@ -946,7 +946,7 @@ __device__ __forceinline__ void half_2u31_frac(const Fn2U31F (&fn)[HASH_FPL], ui
         fn[g].bq.y = r;
     }
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].bq.y, md.frac_m, fn[g].bq);
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, p[g], fn[g].bq.y, md.frac_m, fn[g].bq);
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, %3" : "=v"(key[g]) : "v"(p[g].y), "v"(p[g].x), "s"(md.frac_l));
 }
@@ -971,7 +971,7 @@ __device__ __forceinline__ void half_2u31_bigd(const Fn2U31 (&fn)[HASH_FPL], uin
     uint32_t x[HASH_FPL], y[HASH_FPL];
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, p[g], fn[g].c1, t, fn[g].add);
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, p[g], fn[g].c1, t, fn[g].add);
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(x[g]) : "v"(p[g].x));
@@ -1023,13 +1023,13 @@ __device__ __forceinline__ void half_4u31_np2(const FnT (&fn)[HASH_FPL], u32x2 (
     issue_priority<1>();
 #pragma unroll
     for (int g = 0; g < NF; ++g)
-        MH_MAD(i64_i32, acc[g], fn[g].c1, w[0], fn[g].add);
+        MH_MAD(g, i64_i32, acc[g], fn[g].c1, w[0], fn[g].add);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
-        MH_MAD_ACC(i64_i32, acc[g], fn[g].c2, w[1]);
+        MH_MAD_ACC(g, i64_i32, acc[g], fn[g].c2, w[1]);
 #pragma unroll
     for (int g = 0; g < NF; ++g)
-        MH_MAD_ACC(i64_i32, acc[g], fn[g].c3, w[2]);
+        MH_MAD_ACC(g, i64_i32, acc[g], fn[g].c3, w[2]);
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 1, %1" : "=v"(y[g]) : "v"(acc[g].x));
@@ -1066,7 +1066,7 @@ __device__ __forceinline__ void half_4u31_np2(const FnT (&fn)[HASH_FPL], u32x2 (
         }
     } else if constexpr (MODE == 1) { // frac_key: r m_low + {bias, r}, then the 32 bits from bit l up
 #pragma unroll
-        for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, acc[g], fn[g].bq.y, md.frac_m, fn[g].bq);
+        for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, acc[g], fn[g].bq.y, md.frac_m, fn[g].bq);
 #pragma unroll
         for (int g = 0; g < NF; ++g) {
             asm volatile("v_alignbit_b32 %0, %1, %2, %3" : "=v"(r) : "v"(acc[g].y), "v"(acc[g].x), "s"(md.frac_l));
@@ -1079,7 +1079,7 @@ __device__ __forceinline__ void half_4u31_np2(const FnT (&fn)[HASH_FPL], u32x2 (
         for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(u[g]) : "v"(md.sh));
 #pragma unroll
         for (int g = 0; g < NF; ++g)
-            MH_MAD_ACC(u64_u32, acc[g], u[g], md.negD);
+            MH_MAD_ACC(g, u64_u32, acc[g], u[g], md.negD);
     }
 }
 
@@ -1106,7 +1106,7 @@ __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], ui
     uint32_t s[HASH_FPL], r;
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, L[g], fn[g].e0, t, fn[g].add);
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, L[g], fn[g].e0, t, fn[g].add);
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) {
@@ -1115,7 +1115,7 @@ __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], ui
     }
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_MAD(u64_u32, H[g], fn[g].e1, t, fn[g].hz);
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, H[g], fn[g].e1, t, fn[g].hz);
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
     issue_priority<0>();
@@ -1198,10 +1198,10 @@ struct Pol2UMS32 {
         uint64_t pa[HASH_FPL], pb[HASH_FPL];
 #pragma unroll
         for (int g = 0; g < NF; ++g)
-            MH_MAD(u64_u32, pa[g], fn[g].c1, wa[0], fn[g].add);
+            MH_MAD(g, u64_u32, pa[g], fn[g].c1, wa[0], fn[g].add);
 #pragma unroll
         for (int g = 0; g < NF; ++g)
-            MH_MAD(u64_u32, pb[g], fn[g].c1, wb[0], fn[g].add);
+            MH_MAD(g, u64_u32, pb[g], fn[g].c1, wb[0], fn[g].add);
 #pragma unroll
         for (int g = 0; g < NF; ++g)
             asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"((uint32_t)pa[g]), "v"((uint32_t)pb[g]));
