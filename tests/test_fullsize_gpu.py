@@ -92,6 +92,34 @@ def test_large_workloads_sampled_rows(name, n_random, budget):
     assert bool((out != 0xAA).any(dim=1).all().item())
 
 
+@pytest.mark.parametrize("name", ["large_2u", "large_4u"])
+@pytest.mark.parametrize("D", [16_609_143, 500_000_003, 1_010_017_424])
+def test_universe_sizes_of_the_papers_datasets_sampled_rows(name, D):
+    """The headline rows hashed into a universe that is not a power of two (Table tab_data: webspam's
+    16 609 143 and the expanded rcv1's 1 010 017 424, and one size in between), each of which takes
+    a kernel form of its own; indices are folded into [0, D) as bench.py --universe does."""
+    w = W.WORKLOADS[name]
+    nnz = w.nnz(0)
+    rp_np = W.row_ptr_from_nnz(nnz)
+    col = W.csr_indices_torch(nnz, w.D, w.data_seed, DEV)
+    col.remainder_(D)
+    rp = torch.from_numpy(rp_np).to(DEV)
+    params_np = W.coefficients(w.k, w.family, w.param_seed)
+    params = torch.from_numpy(params_np.view(np.int64)).to(DEV)
+    out = torch.full((len(nnz), w.sig_bytes()), 0xAA, dtype=torch.uint8, device=DEV)
+    ws = mh.alloc_workspace(len(nnz), int(rp_np[-1]), w.k, w.family, DEV)
+    mh.minhash_signatures(rp, col, D, w.k, w.b, w.family, params, out=out, workspace=ws)
+    assert mh.status(ws) == 0
+    rows = _sample_rows(nnz, 12, seed=23, eval_budget=1.2e8, k=w.k)
+    assert len(rows) >= 8
+    for r in rows:
+        lo, hi = int(rp_np[r]), int(rp_np[r + 1])
+        idx = col[lo:hi].cpu().numpy().view(np.uint32)
+        want = oracle.signatures(np.array([0, hi - lo], dtype=np.int64), idx, D, w.k, w.b, w.family, params_np)
+        assert np.array_equal(out[r].cpu().numpy(), want[0]), "row %d (nnz %d) differs from the oracle at D = %d" % (r, hi - lo, D)
+    assert bool((out != 0xAA).any(dim=1).all().item())
+
+
 def test_many_short_rows_do_not_depend_on_how_units_are_handed_out():
     """A batch of 2x10^6 short rows is handed to the wavefronts in runs of 32 rows that halve
     towards the end of the launch; slices of 3 000 rows (fewer than there are resident wavefronts:
