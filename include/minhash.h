@@ -6,8 +6,10 @@
  * for each of k hash functions (or explicit permutations) the minimum hashed
  * location over the row's nonzeros, of which only the lowest b bits are kept.
  * All pointers are plain pointers; which side of the bus they live on is stated
- * per argument.  The library owns no memory: every buffer, including the
- * workspace, belongs to the caller.  No call throws; errors are return codes.
+ * per argument.  Every buffer, including the workspace, belongs to the caller.
+ * Between calls the library keeps only launch constants per
+ * device (number of compute units, resident blocks per kernel).  No call throws;
+ * errors are return codes.
  */
 #ifndef MINHASH_H
 #define MINHASH_H
@@ -57,14 +59,15 @@ enum {
                                          (runtime moduli, Horner form) instead of the Mersenne reduction.  Same
                                          results; exists to measure what Section 3.4 saves ("4U (Mod)" against
                                          "4U (Bit)" in the paper's timing tables)                              */
-#define MINHASH_FLAG_EXACT_FOLD  4u   /* MINHASH_2U_M61 and MINHASH_4U_M31 with a power-of-two D only: evaluate
-                                         every row with the form of the reduction modulo the Mersenne prime
-                                         (Section 3.4) that yields the hashed location evaluation by
-                                         evaluation, instead of the shorter forms (2U, p = 2^61-1: a carry-free
-                                         key with a guard word, the rare doubtful values computed again;
-                                         4U: the folded value kept in two running maxima).  Same results;
-                                         exists so that whole batches of the shorter forms can be compared
-                                         with it, and to time the difference                                  */
+#define MINHASH_FLAG_EXACT_FOLD  4u   /* MINHASH_2U_M31, MINHASH_4U_M31 and MINHASH_2U_M61 with a power-of-two D
+                                         (ignored for other D): evaluate every row with a form of the reduction
+                                         modulo the Mersenne prime (Section 3.4) that needs no second look at
+                                         any value, instead of the shorter forms (2U, p = 2^31-1, D <= 2^26: one
+                                         running maximum of a doubled key, the rare doubtful values computed
+                                         again; 2U, p = 2^61-1: a carry-free key, likewise; 4U: the folded value
+                                         kept in two running maxima).  Same results; exists so that whole
+                                         batches of the shorter forms can be compared with it, and to time the
+                                         difference                                                           */
 #define MINHASH_WORKSPACE_ALIGN  256
 
 /*
@@ -107,11 +110,19 @@ enum {
  *             it and the call returns without synchronising
  *   flags     0 or an OR of MINHASH_FLAG_* values
  *
- * Returns MINHASH_OK once everything is enqueued, or a negative code found
- * before any launch (nothing has been enqueued then).  Indices >= D or a
- * decreasing row_ptr are undefined behaviour unless MINHASH_FLAG_VALIDATE is
- * set; then no access leaves the buffers, minhash_status reports
- * MINHASH_ERR_DATA, and the signatures of the affected rows are unspecified.
+ * Returns MINHASH_OK once everything is enqueued, or a negative code.  Every
+ * code but MINHASH_ERR_HIP is found before any launch (nothing has been enqueued
+ * then); MINHASH_ERR_HIP reports a failed launch, after which earlier kernels of
+ * the call may already be on the stream.  Indices >= D or offsets in row_ptr
+ * that decrease or leave [row_ptr[0], row_ptr[n_rows]] are undefined behaviour
+ * unless MINHASH_FLAG_VALIDATE is set.  With it, col_idx is read only inside
+ * [row_ptr[0], row_ptr[n_rows]), and only if that range is non-negative and
+ * holds no more nonzeros than the workspace was sized for (that the range lies
+ * inside the col_idx allocation remains the caller's promise: the library is
+ * not told its length); an index >= D is hashed as 0; the table of
+ * MINHASH_PERM is then read at row 0 instead.  minhash_status reports
+ * MINHASH_ERR_DATA (MINHASH_ERR_WORKSPACE for too many nonzeros), and the
+ * signatures of the affected rows are unspecified.
  */
 int minhash_signatures(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows,
                        uint64_t D, int32_t k, int32_t b, int32_t family,

@@ -637,4 +637,22 @@ MH_HD TicketMap make_ticket_map(uint64_t units, uint64_t single_units, uint32_t 
     return m;
 }
 
+// ---------------------------------------------------------------- row offsets
+// What the row-binning kernel makes of one row's offsets.  A row is [begin, end) in
+// col_idx; lo = row_ptr[0] and hi = row_ptr[n_rows] bound the part of col_idx the
+// caller vouches for, nnz_cap is the number of nonzeros the workspace was sized
+// for.  Returns 0 for a row that may be read, 1 for offsets that decrease or
+// leave [lo, hi] (an offset that overshoots and comes back, as in [0, 1000, 5],
+// gives its row a positive length that a test of neighbours alone accepts),
+// 4 when [lo, hi) itself holds more than nnz_cap nonzeros.  Without `validate`
+// only a negative length is caught (the row is then treated as empty, silently).
+MH_HD uint32_t row_extent_status(int64_t begin, int64_t end, int64_t lo, int64_t hi, uint64_t nnz_cap, bool validate)
+{
+    if (end < begin) return 1u;
+    if (!validate) return 0u;
+    if (lo < 0 || hi < lo || begin < lo || begin > hi || end > hi) return 1u;
+    if ((uint64_t)(hi - lo) > nnz_cap) return 4u;
+    return 0u;
+}
+
 }  // namespace mh

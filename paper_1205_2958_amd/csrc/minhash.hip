@@ -39,6 +39,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
 #include <type_traits>
 
 #include "minhash.h"
@@ -102,7 +103,7 @@ struct SplitRow {                      // a row processed as several chunks
 };
 
 struct Layout {                        // host and device agree on the workspace layout through this
-    size_t items_off, split_rows_off, scratch_off, total;
+    size_t items_off, split_rows_off, partials_off, total;
     uint64_t cap_long, cap_short, cap_split, cap_parts;
 };
 
@@ -128,8 +129,8 @@ inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k)
     L.cap_short = n + L.cap_parts + 1;                                // whole rows, plus chunks not longer than LONG_ITEM
     L.items_off = sizeof(WorkHeader);
     L.split_rows_off = align_up(L.items_off + (L.cap_long + L.cap_short) * sizeof(Item), 256);
-    L.scratch_off = align_up(L.split_rows_off + L.cap_split * sizeof(SplitRow), 256);
-    L.total = align_up(L.scratch_off + L.cap_parts * (size_t)k * sizeof(uint32_t), 256);
+    L.partials_off = align_up(L.split_rows_off + L.cap_split * sizeof(SplitRow), 256);
+    L.total = align_up(L.partials_off + L.cap_parts * (size_t)k * sizeof(uint32_t), 256);
     return L;
 }
 
@@ -143,9 +144,10 @@ struct KArgs {
     WorkHeader* hdr;
     Item* items;
     SplitRow* split_rows;
-    uint32_t* scratch;                 // [cap_parts][k] partial minima of chunks
+    uint32_t* partials;                // [cap_parts][k] partial minima of chunks
     uint64_t D;
     uint64_t cap_long, cap_short, cap_split, cap_parts;
+    uint64_t nnz_cap;                  // nonzeros the workspace was sized for (checked under VALIDATE)
     ModD md;
     int64_t n_rows;
     int32_t k, b;
@@ -328,11 +330,14 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
     int64_t begin = 0, nnz = 0;
     if (row < a.n_rows) {
         begin = a.row_ptr[row];
-        nnz = a.row_ptr[row + 1] - begin;
-        if (nnz < 0) {                 // decreasing row_ptr: treat as empty, flag it
-            if (a.validate) atomicOr(&a.hdr->status, 1u);
-            nnz = 0;
-        }
+        const int64_t end = a.row_ptr[row + 1];
+        nnz = end - begin;
+        // under VALIDATE the row must lie inside [row_ptr[0], row_ptr[n_rows]] and that range must not
+        // hold more nonzeros than the workspace was sized for (row_extent_status of mh_arith.h)
+        const int64_t lo = a.validate ? a.row_ptr[0] : 0, hi = a.validate ? a.row_ptr[a.n_rows] : 0;
+        const uint32_t bad = row_extent_status(begin, end, lo, hi, a.nnz_cap, a.validate != 0);
+        if (bad && a.validate) atomicOr(&a.hdr->status, bad);
+        if (bad) nnz = 0;              // treated as an empty row
         is_split = nnz > (int64_t)CHUNK ? 1u : 0u;
         n_it = is_split ? (uint32_t)((nnz + CHUNK - 1) / CHUNK) : 1u;
     }
@@ -723,7 +728,7 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 
 // Widening multiply-add of function slot SLOT.  The
 // carry-out it must name is never read; each slot sends it to a scalar register
-// pair of its own, s[86:87] to s[100:101].  With one destination for all (a pair of the compiler's choice,
+// pair of its own, s[84:85] to s[98:99].  With one destination for all (a pair of the compiler's choice,
 // or vcc) the compiler sees each statement redefine a register of the one before
 // and, not knowing what the text holds, puts a wait state between any two of
 // them: 28 per step of the 2U loop (with four pairs in turn it still put one before
@@ -731,25 +736,25 @@ __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_F
 #define MH_MAD_TEXT(KIND, SDST, LAST) "v_mad_" #KIND " %0, " SDST ", %1, %2, " LAST
 #define MH_MAD(SLOT, KIND, DST, A, B, C)                                                                                 \
     do {                                                                                                           \
-        if (((SLOT) & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s86", "s87"); \
-        else if (((SLOT) & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s88", "s89"); \
-        else if (((SLOT) & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s90", "s91"); \
-        else if (((SLOT) & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s92", "s93"); \
-        else if (((SLOT) & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s94", "s95"); \
-        else if (((SLOT) & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s96", "s97"); \
-        else if (((SLOT) & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s98", "s99"); \
-        else asm volatile(MH_MAD_TEXT(KIND, "s[100:101]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s100", "s101"); \
+        if (((SLOT) & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[84:85]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s84", "s85"); \
+        else if (((SLOT) & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s86", "s87"); \
+        else if (((SLOT) & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s88", "s89"); \
+        else if (((SLOT) & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s90", "s91"); \
+        else if (((SLOT) & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s92", "s93"); \
+        else if (((SLOT) & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s94", "s95"); \
+        else if (((SLOT) & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s96", "s97"); \
+        else asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%3") : "=v"(DST) : "v"(A), "v"(B), "v"(C) : "s98", "s99"); \
     } while (0)
 #define MH_MAD_ACC(SLOT, KIND, ACC, A, B)                                                                                \
     do {                                                                                                           \
-        if (((SLOT) & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s86", "s87"); \
-        else if (((SLOT) & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s88", "s89"); \
-        else if (((SLOT) & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s90", "s91"); \
-        else if (((SLOT) & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s92", "s93"); \
-        else if (((SLOT) & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s94", "s95"); \
-        else if (((SLOT) & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s96", "s97"); \
-        else if (((SLOT) & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s98", "s99"); \
-        else asm volatile(MH_MAD_TEXT(KIND, "s[100:101]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s100", "s101"); \
+        if (((SLOT) & 7) == 0) asm volatile(MH_MAD_TEXT(KIND, "s[84:85]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s84", "s85"); \
+        else if (((SLOT) & 7) == 1) asm volatile(MH_MAD_TEXT(KIND, "s[86:87]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s86", "s87"); \
+        else if (((SLOT) & 7) == 2) asm volatile(MH_MAD_TEXT(KIND, "s[88:89]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s88", "s89"); \
+        else if (((SLOT) & 7) == 3) asm volatile(MH_MAD_TEXT(KIND, "s[90:91]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s90", "s91"); \
+        else if (((SLOT) & 7) == 4) asm volatile(MH_MAD_TEXT(KIND, "s[92:93]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s92", "s93"); \
+        else if (((SLOT) & 7) == 5) asm volatile(MH_MAD_TEXT(KIND, "s[94:95]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s94", "s95"); \
+        else if (((SLOT) & 7) == 6) asm volatile(MH_MAD_TEXT(KIND, "s[96:97]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s96", "s97"); \
+        else asm volatile(MH_MAD_TEXT(KIND, "s[98:99]", "%0") : "+v"(ACC) : "v"(A), "v"(B) : "s98", "s99"); \
     } while (0)
 
 // 2U, p = 2^31-1, power-of-two D, with the instruction order fixed by hand.
@@ -1511,7 +1516,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             wave_pack_store(a, mins, it.row, ftile * a.ftile_size, nf_tile, ftile == a.n_ftiles - 1, lane);
             wave_sync_lds();
         } else if (slice == 0) {
-            uint32_t* part = a.scratch + (size_t)it.slot * (size_t)a.k;
+            uint32_t* part = a.partials + (size_t)it.slot * (size_t)a.k;
 #pragma unroll
             for (int r = 0; r < NF; ++r)
                 if (j_base + r < a.k) part[j_base + r] = m[r];
@@ -1635,7 +1640,7 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
             wave_pack_store(a, mins, it.row, j0, nf_tile, ftile == a.n_ftiles - 1, lane);
             wave_sync_lds();
         } else {
-            uint32_t* part = a.scratch + (size_t)it.slot * (size_t)a.k + j0;
+            uint32_t* part = a.partials + (size_t)it.slot * (size_t)a.k + j0;
 #pragma unroll
             for (int r = 0; r < PERM_FPL; ++r)
                 if (ok[r]) part[jl[r]] = m[r];
@@ -1663,7 +1668,7 @@ __global__ __launch_bounds__(BLOCK) void mh_finalize_kernel(KArgs a, int ftile_s
             uint32_t v = EMPTY_MIN;
 #pragma unroll 4
             for (uint32_t c = 0; c < sr.n_parts; ++c) {
-                uint32_t o = a.scratch[(size_t)(sr.first_part + c) * (size_t)a.k + j0 + j];
+                uint32_t o = a.partials[(size_t)(sr.first_part + c) * (size_t)a.k + j0 + j];
                 v = o < v ? o : v;
             }
             mins[j] = v;
@@ -1709,48 +1714,74 @@ int validate_shape(int64_t n_rows, int64_t nnz_ub, int32_t k, int32_t family)
     return MINHASH_OK;
 }
 
-int query_cus()
+// Launch constants are kept per device (the library may be called with any device
+// current): the number of compute units, and per kernel instantiation the number of
+// blocks that are resident at once.  Slots are filled on first use; two threads that
+// fill one at the same time write the same value.
+constexpr int MAX_DEVICES = 64;
+
+int current_device()
 {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
-    return cus;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return 0;
+    return dev;
 }
-int device_cus()
+int device_cus(int dev)
 {
-    static const int cus = query_cus();    // one GPU per process
+    static std::atomic<int> cache[MAX_DEVICES];
+    int cus = cache[dev].load(std::memory_order_relaxed);
+    if (cus > 0) return cus;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    cache[dev].store(cus, std::memory_order_relaxed);
     return cus;
 }
 
 // persistent grid: as many blocks as are resident at once, no more
 template <class K>
-int resident_blocks(K kernel, int cus)
+int resident_blocks(K kernel, int dev, int cus, std::atomic<int>* cache)
 {
+    int blocks = cache[dev].load(std::memory_order_relaxed);
+    if (blocks > 0) return blocks;
     int per_cu = 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, BLOCK, 0) != hipSuccess || per_cu < 1) per_cu = 2;
-    return cus * per_cu;
+    blocks = cus * per_cu;
+    cache[dev].store(blocks, std::memory_order_relaxed);
+    return blocks;
 }
 
+struct Launch {                        // where a call's kernels go
+    int dev, cus;
+    hipStream_t s;
+};
+
 template <class Pol, int NF>
-void launch_hash_nf(const KArgs& a, int cus, hipStream_t s)
+void launch_hash_nf(const KArgs& a, const Launch& l)
 {
-    static const int blocks = resident_blocks(mh_hash_kernel<Pol, NF>, cus);
-    hipLaunchKernelGGL((mh_hash_kernel<Pol, NF>), dim3(blocks), dim3(BLOCK), 0, s, a);
+    static std::atomic<int> cache[MAX_DEVICES];
+    const int blocks = resident_blocks(mh_hash_kernel<Pol, NF>, l.dev, l.cus, cache);
+    hipLaunchKernelGGL((mh_hash_kernel<Pol, NF>), dim3(blocks), dim3(BLOCK), 0, l.s, a);
 }
 // nf = functions per lane of this launch (see functions_per_lane); the hand-ordered
 // policies exist for 5..8, the compiler-scheduled ones for 8 only
 template <class Pol>
-void launch_hash(const KArgs& a, int nf, int cus, hipStream_t s)
+void launch_hash(const KArgs& a, int nf, const Launch& l)
 {
     if constexpr (Pol::VARIABLE_NF) {
         switch (nf) {
-        case 5: launch_hash_nf<Pol, 5>(a, cus, s); return;
-        case 6: launch_hash_nf<Pol, 6>(a, cus, s); return;
-        case 7: launch_hash_nf<Pol, 7>(a, cus, s); return;
+        case 5: launch_hash_nf<Pol, 5>(a, l); return;
+        case 6: launch_hash_nf<Pol, 6>(a, l); return;
+        case 7: launch_hash_nf<Pol, 7>(a, l); return;
         default: break;
         }
     }
-    launch_hash_nf<Pol, HASH_FPL>(a, cus, s);
+    launch_hash_nf<Pol, HASH_FPL>(a, l);
+}
+template <bool VEC4>
+void launch_perm(const KArgs& a, const Launch& l)
+{
+    static std::atomic<int> cache[MAX_DEVICES];
+    const int blocks = resident_blocks(mh_perm_kernel<VEC4>, l.dev, l.cus, cache);
+    hipLaunchKernelGGL(mh_perm_kernel<VEC4>, dim3(blocks), dim3(BLOCK), 0, l.s, a);
 }
 
 // How many of its HASH_FPL function slots a lane uses.  A tile of functions spans
@@ -1775,12 +1806,22 @@ void functions_per_lane(int k, bool variable, int* nf, int* log2_fl)
     }
 }
 
-int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_t D, int32_t k, int32_t b,
-        int32_t family, const void* params, int64_t perm_ld, uint8_t* out, int64_t out_stride, void* workspace,
-        size_t workspace_bytes, void* stream, uint32_t flags, float* kernel_ms, bool profiled)
+// What a call needs beyond its arguments, all of it worked out on the host without
+// touching the GPU.
+struct Plan {
+    KArgs a;
+    int nf;                            // functions per lane (hash families)
+    int ftile_size;
+    bool generic_mod, full4, guarded61, has_split;
+};
+
+// Everything that can be rejected without touching the GPU.  MINHASH_OK with
+// *empty set means a successful no-op.
+int check_arguments(const int64_t* row_ptr, int64_t n_rows, uint64_t D, int32_t k, int32_t b, int32_t family,
+                    const void* params, int64_t perm_ld, const uint8_t* out, int64_t out_stride, uint32_t flags,
+                    bool* empty)
 {
-    if (kernel_ms) *kernel_ms = 0.0f;
-    // ---- everything that can be rejected without touching the GPU
+    *empty = false;
     int rc = validate_shape(n_rows, 0, k, family);
     if (rc != MINHASH_OK) return rc;
     if (b < 1 || b > 32) return MINHASH_ERR_KB;
@@ -1802,9 +1843,166 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     if (flags & ~(MINHASH_FLAG_VALIDATE | MINHASH_FLAG_GENERIC_MOD | MINHASH_FLAG_EXACT_FOLD)) return MINHASH_ERR_ARG;
     const bool generic_mod = (flags & MINHASH_FLAG_GENERIC_MOD) != 0;
     if (generic_mod && family != MINHASH_2U_M31 && family != MINHASH_4U_M31) return MINHASH_ERR_ARG;
-    if ((flags & MINHASH_FLAG_EXACT_FOLD) && family != MINHASH_2U_M61 && family != MINHASH_4U_M31) return MINHASH_ERR_ARG;
-    if (n_rows == 0) return MINHASH_OK;
+    if ((flags & MINHASH_FLAG_EXACT_FOLD) && family != MINHASH_2U_M61 && family != MINHASH_4U_M31 &&
+        family != MINHASH_2U_M31)
+        return MINHASH_ERR_ARG;
+    if (n_rows == 0) { *empty = true; return MINHASH_OK; }
     if (!row_ptr || !params || !out) return MINHASH_ERR_ARG;
+    return MINHASH_OK;
+}
+
+// Fills the plan for a workspace at `ws` laid out for at most nnz_cap nonzeros.
+int make_plan(Plan* plan, const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_t D, int32_t k, int32_t b,
+              int32_t family, const void* params, int64_t perm_ld, uint8_t* out, int64_t out_stride, void* workspace,
+              int64_t nnz_cap, uint32_t flags)
+{
+    const Layout L = make_layout(n_rows, nnz_cap, k);
+    char* ws = static_cast<char*>(workspace);
+    KArgs& a = plan->a;
+    memset(&a, 0, sizeof(a));
+    a.row_ptr = row_ptr; a.col_idx = col_idx; a.params = params; a.out = out;
+    a.out_stride = out_stride; a.perm_ld = perm_ld;
+    a.hdr = reinterpret_cast<WorkHeader*>(ws);
+    a.items = reinterpret_cast<Item*>(ws + L.items_off);
+    a.split_rows = reinterpret_cast<SplitRow*>(ws + L.split_rows_off);
+    a.partials = reinterpret_cast<uint32_t*>(ws + L.partials_off);
+    a.D = D; a.cap_long = L.cap_long; a.cap_short = L.cap_short; a.cap_split = L.cap_split; a.cap_parts = L.cap_parts;
+    a.nnz_cap = (uint64_t)nnz_cap;
+    a.md = make_mod_d(D);
+    if (is_multiply_shift(family)) {
+        int sbits = 0;
+        while ((1ull << sbits) < D) ++sbits;
+        a.md.M = (uint32_t)(32 - sbits);                                // shift that keeps the s highest bits
+    }
+    a.n_rows = n_rows; a.k = k; a.b = b;
+    a.sig_bytes = (int32_t)(((int64_t)k * b + 7) / 8);
+    a.validate = (flags & MINHASH_FLAG_VALIDATE) ? 1u : 0u;
+    a.prime = P31;
+    a.target_items = 0;
+
+    const bool pow2 = a.md.pow2 != 0;
+    plan->generic_mod = (flags & MINHASH_FLAG_GENERIC_MOD) != 0;
+    // 4U: two maxima of the folded value for every power-of-two D, unless the caller asks for the
+    // form that yields the location evaluation by evaluation
+    plan->full4 = pow2 && !(flags & MINHASH_FLAG_EXACT_FOLD);
+    // 2U with p = 2^61-1: the guarded fast path needs a power-of-two D and t < 2^31
+    plan->guarded61 = pow2 && D <= (1ull << 31) && !(flags & MINHASH_FLAG_EXACT_FOLD);
+    plan->has_split = L.cap_split > 0;
+    plan->nf = HASH_FPL;
+    plan->ftile_size = PERM_FTILE;
+    if (family != MINHASH_PERM) {
+        // the kernels ordered by hand come with 5..8 functions per lane
+        const bool variable = !plan->generic_mod && family != MINHASH_4U_M61 &&
+                              !(family == MINHASH_2U_M61 && !plan->guarded61);
+        int lg = 0;
+        functions_per_lane(k, variable, &plan->nf, &lg);
+        a.log2_fl = lg;
+        plan->ftile_size = k > HASH_FTILE ? HASH_FTILE : (1 << lg) * plan->nf;
+    } else {
+        a.log2_fl = 6;
+    }
+    a.ftile_size = plan->ftile_size;
+    a.n_ftiles = (k + plan->ftile_size - 1) / plan->ftile_size;
+
+    // tickets and unit numbers are 32 bits wide; tickets run past the last unit by one per resident wavefront
+    if ((L.cap_long + L.cap_short) * (uint64_t)a.n_ftiles >= (1ull << 32) - (1ull << 24)) return MINHASH_ERR_ARG;
+    return MINHASH_OK;
+}
+
+// Enqueues the kernels of a planned call.  Events of the profiled variant exist
+// before the first launch, so that a failure to create them leaves nothing enqueued.
+int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream, float* kernel_ms, bool profiled)
+{
+    KArgs& a = plan.a;
+    Launch l;
+    l.dev = current_device();
+    l.cus = device_cus(l.dev);
+    l.s = static_cast<hipStream_t>(stream);
+    (void)hipGetLastError();           // an error left behind by an earlier, unrelated call is not this call's
+
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (profiled) {
+        hipError_t e = hipEventCreate(&e0);
+        if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
+        e = hipEventCreate(&e1);
+        if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
+    }
+    a.target_items = (uint32_t)l.cus * 24u * 2u;   // two items per wavefront of a fully occupied launch
+    hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, l.s, a);
+    const int bin_blocks = (int)((a.n_rows + BIN_BLOCK - 1) / BIN_BLOCK);
+    hipLaunchKernelGGL(mh_bin_rows_kernel, dim3(bin_blocks), dim3(BIN_BLOCK), 0, l.s, a);
+
+    hipError_t r0 = profiled ? hipEventRecord(e0, l.s) : hipSuccess;
+    const bool pow2 = a.md.pow2 != 0;
+    const int nf = plan.nf;
+    switch (plan.generic_mod ? -family - 1 : family) {
+    case -MINHASH_2U_M31 - 1: launch_hash<PolGenericMod<2>>(a, nf, l); break;
+    case -MINHASH_4U_M31 - 1: launch_hash<PolGenericMod<4>>(a, nf, l); break;
+    case MINHASH_2U_M31:
+        // power-of-two D: one maximum of the doubled key for D <= 2^26, where a value asks for a second
+        // look with probability (D / 2^31)^n, n the evaluations behind it; a signed and an unsigned
+        // maximum of the key beyond, or when the caller asks for the form that needs no second look
+        if (pow2 && D <= (1ull << FULL_KEY_MAX_LOG2_D) && !(flags & MINHASH_FLAG_EXACT_FOLD))
+            launch_hash<Pol2U31<FORM_FULL>>(a, nf, l);
+        else if (pow2) launch_hash<Pol2U31<FORM_FULL_TWO>>(a, nf, l);
+        else if (frac_key_serves(D)) launch_hash<Pol2U31<FORM_FRAC_D>>(a, nf, l);
+        else if (small_quotient_serves(D)) launch_hash<Pol2U31<FORM_BIG_D>>(a, nf, l);
+        else launch_hash<Pol2U31<FORM_ANY_D>>(a, nf, l);
+        break;
+    case MINHASH_4U_M31:
+        if (plan.full4) launch_hash<Pol4U31<true, true>>(a, nf, l);
+        else if (pow2) launch_hash<Pol4U31<true, false>>(a, nf, l);
+        else if (frac_key_serves(D)) launch_hash<Pol4U31<false, false, 1>>(a, nf, l);
+        else if (small_quotient_serves(D)) launch_hash<Pol4U31<false, false, 2>>(a, nf, l);
+        else launch_hash<Pol4U31<false>>(a, nf, l);
+        break;
+    case MINHASH_2U_M61:
+        if (plan.guarded61) launch_hash<Pol2U61<true>>(a, nf, l);
+        else launch_hash<Pol2U61<false>>(a, nf, l);
+        break;
+    case MINHASH_4U_M61:
+        if (pow2) launch_hash<Pol4U61<true>>(a, nf, l); else launch_hash<Pol4U61<false>>(a, nf, l);
+        break;
+    case MINHASH_2U_MS32: launch_hash<Pol2UMS32<false>>(a, nf, l); break;
+    case MINHASH_2U_MS32_HIGH: launch_hash<Pol2UMS32<true>>(a, nf, l); break;
+    case MINHASH_PERM: {
+        const bool vec4 = (a.perm_ld % 4 == 0) && (reinterpret_cast<uintptr_t>(a.params) % 16 == 0);
+        if (vec4) launch_perm<true>(a, l); else launch_perm<false>(a, l);
+        break;
+    }
+    default: break;                                // unreachable: the family was validated before planning
+    }
+    hipError_t r1 = profiled ? hipEventRecord(e1, l.s) : hipSuccess;
+    if (plan.has_split)
+        hipLaunchKernelGGL(mh_finalize_kernel, dim3(l.cus * 8), dim3(BLOCK), 0, l.s, a, plan.ftile_size);   // latency-bound: fill the chip
+
+    hipError_t le = hipGetLastError();
+    if (profiled) {
+        hipError_t se = hipStreamSynchronize(l.s);
+        float ms = 0.0f;
+        hipError_t te = hipSuccess;
+        if (se == hipSuccess && le == hipSuccess && r0 == hipSuccess && r1 == hipSuccess) te = hipEventElapsedTime(&ms, e0, e1);
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
+        if (le != hipSuccess) return hip_fail(le, "kernel launch");
+        if (se != hipSuccess) return hip_fail(se, "hipStreamSynchronize");
+        if (r0 != hipSuccess) return hip_fail(r0, "hipEventRecord");
+        if (r1 != hipSuccess) return hip_fail(r1, "hipEventRecord");
+        if (te != hipSuccess) return hip_fail(te, "hipEventElapsedTime");
+        if (kernel_ms) *kernel_ms = ms;
+    }
+    if (le != hipSuccess) return hip_fail(le, "kernel launch");
+    return MINHASH_OK;
+}
+
+int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_t D, int32_t k, int32_t b,
+        int32_t family, const void* params, int64_t perm_ld, uint8_t* out, int64_t out_stride, void* workspace,
+        size_t workspace_bytes, void* stream, uint32_t flags, float* kernel_ms, bool profiled)
+{
+    if (kernel_ms) *kernel_ms = 0.0f;
+    bool empty = false;
+    int rc = check_arguments(row_ptr, n_rows, D, k, b, family, params, perm_ld, out, out_stride, flags, &empty);
+    if (rc != MINHASH_OK || empty) return rc;
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % MINHASH_WORKSPACE_ALIGN) != 0) return MINHASH_ERR_WORKSPACE;
     // The nonzero bound the workspace was sized for is not passed in; recover the
     // largest bound this workspace can serve and let the device-side capacity
@@ -1815,129 +2013,10 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
         int64_t mid = lo + (hi - lo + 1) / 2;
         if (make_layout(n_rows, mid, k).total <= workspace_bytes) lo = mid; else hi = mid - 1;
     }
-    const Layout L = make_layout(n_rows, lo, k);
-
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    char* ws = static_cast<char*>(workspace);
-    KArgs a;
-    memset(&a, 0, sizeof(a));
-    a.row_ptr = row_ptr; a.col_idx = col_idx; a.params = params; a.out = out;
-    a.out_stride = out_stride; a.perm_ld = perm_ld;
-    a.hdr = reinterpret_cast<WorkHeader*>(ws);
-    a.items = reinterpret_cast<Item*>(ws + L.items_off);
-    a.split_rows = reinterpret_cast<SplitRow*>(ws + L.split_rows_off);
-    a.scratch = reinterpret_cast<uint32_t*>(ws + L.scratch_off);
-    a.D = D; a.cap_long = L.cap_long; a.cap_short = L.cap_short; a.cap_split = L.cap_split; a.cap_parts = L.cap_parts;
-    a.md = make_mod_d(D);
-    if (is_multiply_shift(family)) {
-        int sbits = 0;
-        while ((1ull << sbits) < D) ++sbits;
-        a.md.M = (uint32_t)(32 - sbits);                                // shift that keeps the s highest bits
-    }
-    a.n_rows = n_rows; a.k = k; a.b = b;
-    a.sig_bytes = (int32_t)sig_bytes;
-    a.validate = (flags & MINHASH_FLAG_VALIDATE) ? 1u : 0u;
-    a.prime = P31;
-    a.target_items = 0;
-
-    const bool perm = family == MINHASH_PERM;
-    const bool pow2 = a.md.pow2 != 0;
-    // 2U, p = 2^31-1, power-of-two D: one signed maximum for D <= 2^26, where a value asks for a
-    // second look with probability (D / 2^31)^n, n the evaluations behind it; two maxima beyond.
-    // 4U: two maxima for every power-of-two D.
-    const bool full4 = pow2 && !(flags & MINHASH_FLAG_EXACT_FOLD);
-    // 2U with p = 2^61-1: the guarded fast path needs a power-of-two D and t < 2^31
-    const bool guarded61 = pow2 && D <= (1ull << 31) && !(flags & MINHASH_FLAG_EXACT_FOLD);
-    int nf = HASH_FPL;
-    int ftile_size = PERM_FTILE;
-    if (!perm) {
-        // the kernels ordered by hand come with 5..8 functions per lane
-        const bool variable = !generic_mod && family != MINHASH_4U_M61 && !(family == MINHASH_2U_M61 && !guarded61);
-        int lg = 0;
-        functions_per_lane(k, variable, &nf, &lg);
-        a.log2_fl = lg;
-        ftile_size = k > HASH_FTILE ? HASH_FTILE : (1 << lg) * nf;
-    } else {
-        a.log2_fl = 6;
-    }
-    a.ftile_size = ftile_size;
-    a.n_ftiles = (k + ftile_size - 1) / ftile_size;
-
-    // tickets and unit numbers are 32 bits wide; tickets run past the last unit by one per resident wavefront
-    if ((L.cap_long + L.cap_short) * (uint64_t)a.n_ftiles >= (1ull << 32) - (1ull << 24)) return MINHASH_ERR_ARG;
-
-    const int cus = device_cus();
-    a.target_items = (uint32_t)cus * 24u * 2u;     // two items per wavefront of a fully occupied launch
-    hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, s, a);
-    const int bin_blocks = (int)((n_rows + BIN_BLOCK - 1) / BIN_BLOCK);
-    hipLaunchKernelGGL(mh_bin_rows_kernel, dim3(bin_blocks), dim3(BIN_BLOCK), 0, s, a);
-
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (profiled) {
-        hipError_t e = hipEventCreate(&e0);
-        if (e != hipSuccess) return hip_fail(e, "hipEventCreate");
-        e = hipEventCreate(&e1);
-        if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
-        e = hipEventRecord(e0, s);
-        if (e != hipSuccess) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); return hip_fail(e, "hipEventRecord"); }
-    }
-    const int main_blocks = cus;
-    switch (generic_mod ? -family - 1 : family) {
-    case -MINHASH_2U_M31 - 1: launch_hash<PolGenericMod<2>>(a, nf, main_blocks, s); break;
-    case -MINHASH_4U_M31 - 1: launch_hash<PolGenericMod<4>>(a, nf, main_blocks, s); break;
-    case MINHASH_2U_M31:
-        if (pow2 && D <= (1ull << FULL_KEY_MAX_LOG2_D)) launch_hash<Pol2U31<FORM_FULL>>(a, nf, main_blocks, s);
-        else if (pow2) launch_hash<Pol2U31<FORM_FULL_TWO>>(a, nf, main_blocks, s);
-        else if (frac_key_serves(D)) launch_hash<Pol2U31<FORM_FRAC_D>>(a, nf, main_blocks, s);
-        else if (small_quotient_serves(D)) launch_hash<Pol2U31<FORM_BIG_D>>(a, nf, main_blocks, s);
-        else launch_hash<Pol2U31<FORM_ANY_D>>(a, nf, main_blocks, s);
-        break;
-    case MINHASH_4U_M31:
-        if (full4) launch_hash<Pol4U31<true, true>>(a, nf, main_blocks, s);
-        else if (pow2) launch_hash<Pol4U31<true, false>>(a, nf, main_blocks, s);
-        else if (frac_key_serves(D)) launch_hash<Pol4U31<false, false, 1>>(a, nf, main_blocks, s);
-        else if (small_quotient_serves(D)) launch_hash<Pol4U31<false, false, 2>>(a, nf, main_blocks, s);
-        else launch_hash<Pol4U31<false>>(a, nf, main_blocks, s);
-        break;
-    case MINHASH_2U_M61:
-        if (guarded61) launch_hash<Pol2U61<true>>(a, nf, main_blocks, s);
-        else launch_hash<Pol2U61<false>>(a, nf, main_blocks, s);
-        break;
-    case MINHASH_4U_M61:
-        if (pow2) launch_hash<Pol4U61<true>>(a, nf, main_blocks, s); else launch_hash<Pol4U61<false>>(a, nf, main_blocks, s);
-        break;
-    case MINHASH_2U_MS32: launch_hash<Pol2UMS32<false>>(a, nf, main_blocks, s); break;
-    case MINHASH_2U_MS32_HIGH: launch_hash<Pol2UMS32<true>>(a, nf, main_blocks, s); break;
-    case MINHASH_PERM: {
-        const bool vec4 = (perm_ld % 4 == 0) && (reinterpret_cast<uintptr_t>(params) % 16 == 0);
-        static const int blocks_v = resident_blocks(mh_perm_kernel<true>, cus);
-        static const int blocks_s = resident_blocks(mh_perm_kernel<false>, cus);
-        if (vec4) hipLaunchKernelGGL(mh_perm_kernel<true>, dim3(blocks_v), dim3(BLOCK), 0, s, a);
-        else hipLaunchKernelGGL(mh_perm_kernel<false>, dim3(blocks_s), dim3(BLOCK), 0, s, a);
-        break;
-    }
-    default:                                       // unreachable: the family was validated above
-        if (profiled) { (void)hipEventDestroy(e0); (void)hipEventDestroy(e1); }
-        return MINHASH_ERR_FAMILY;
-    }
-    hipError_t re = profiled ? hipEventRecord(e1, s) : hipSuccess;
-    if (L.cap_split > 0) hipLaunchKernelGGL(mh_finalize_kernel, dim3(cus * 8), dim3(BLOCK), 0, s, a, ftile_size);   // latency-bound: fill the chip
-
-    hipError_t le = hipGetLastError();
-    if (profiled) {
-        hipError_t se = hipStreamSynchronize(s);
-        float ms = 0.0f;
-        hipError_t te = hipSuccess;
-        if (se == hipSuccess && le == hipSuccess && re == hipSuccess) te = hipEventElapsedTime(&ms, e0, e1);
-        (void)hipEventDestroy(e0);
-        (void)hipEventDestroy(e1);
-        if (se != hipSuccess) return hip_fail(se, "hipStreamSynchronize");
-        if (re != hipSuccess) return hip_fail(re, "hipEventRecord");
-        if (te != hipSuccess) return hip_fail(te, "hipEventElapsedTime");
-        if (kernel_ms) *kernel_ms = ms;
-    }
-    if (le != hipSuccess) return hip_fail(le, "kernel launch");
-    return MINHASH_OK;
+    Plan plan;
+    rc = make_plan(&plan, row_ptr, col_idx, n_rows, D, k, b, family, params, perm_ld, out, out_stride, workspace, lo, flags);
+    if (rc != MINHASH_OK) return rc;
+    return enqueue(plan, family, D, flags, stream, kernel_ms, profiled);
 }
 
 }  // namespace

@@ -145,19 +145,47 @@ def _stream_handle(stream) -> int:
     return stream.cuda_stream
 
 
-def _marshal(row_ptr, col_idx, D, k, b, family, params, out, out_stride, perm_ld, workspace, stream):
+def _check_common(row_ptr, col_idx, params, family):
     if row_ptr.dtype != torch.int64 or not row_ptr.is_contiguous():
         raise TypeError("row_ptr must be a contiguous int64 tensor")
     if col_idx.element_size() != 4 or not col_idx.is_contiguous():
         raise TypeError("col_idx must be a contiguous tensor of 4-byte unsigned indices (int32/uint32 storage)")
     if not params.is_contiguous():
         raise TypeError("params must be contiguous")
+    want = 4 if family == FAMILY_PERM else 8
+    if params.element_size() != want:
+        raise TypeError("params must hold %d-byte elements for this family (uint64 coefficients, uint32 table entries)"
+                        % want)
+    for name, t in (("col_idx", col_idx), ("params", params)):
+        if t.device != row_ptr.device:
+            raise TypeError("%s must be on the device of row_ptr" % name)
+
+
+def _check_out(out, row_ptr):
+    """The library writes every byte of a row's pitch (signature, then zeros), so the
+    tensor must own all of them: 2-d uint8, contiguous, one row per data row."""
+    if out.dtype != torch.uint8 or out.dim() != 2 or out.device != row_ptr.device:
+        raise TypeError("out must be a 2-d uint8 tensor on the device of row_ptr")
+    if out.shape[0] != row_ptr.numel() - 1:
+        raise TypeError("out must have one row per data row")
+    if not out.is_contiguous():
+        raise TypeError("out must be contiguous (the row pitch is its second dimension)")
+
+
+def _marshal(row_ptr, col_idx, D, k, b, family, params, out, out_stride, perm_ld, workspace, stream):
+    _check_common(row_ptr, col_idx, params, family)
     n_rows = row_ptr.numel() - 1
     sig_bytes = (k * b + 7) // 8
-    if out_stride is None:
-        out_stride = out.shape[1] if out is not None else sig_bytes
     if out is None:
+        out_stride = sig_bytes if out_stride is None else out_stride
         out = torch.empty((n_rows, out_stride), dtype=torch.uint8, device=row_ptr.device)
+    else:
+        _check_out(out, row_ptr)
+        if out_stride is not None and out_stride != out.shape[1]:
+            raise TypeError("out_stride %d does not match the row pitch %d of out" % (out_stride, out.shape[1]))
+        out_stride = out.shape[1]
+    if workspace is not None and (workspace.device != row_ptr.device or not workspace.is_contiguous()):
+        raise TypeError("workspace must be a contiguous tensor on the device of row_ptr")
     if family == FAMILY_PERM:
         if perm_ld is None:
             perm_ld = params.shape[1]
@@ -330,4 +358,10 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
     for s in (s_in, s_run, s_out):
         s.synchronize()
     now.wait_stream(s_out)
+    # the deferred checks of the last non-empty batch (work-list overflow, MINHASH_FLAG_VALIDATE findings); every
+    # batch was bounded by max_rows / max_nnz above, so an overflow can only come from offsets that contradict the sizes
+    if any(r.shape[0] > 0 for r in results):
+        rc = status(ws, s_run)
+        if rc != 0:
+            _raise(rc)
     return results

@@ -357,6 +357,40 @@ int main()
                         FAIL("ticket map: %u tickets for %llu short units on %u waves", n_tickets_past_long, (unsigned long long)rest, waves);
                 }
     }
+    // Row offsets as the row-binning kernel reads them: which rows of a row_ptr array may be read.
+    // Each case is {row_ptr, nonzeros the workspace was sized for, status bits expected with
+    // validation on, rows that must come out empty}.
+    {
+        struct Case { std::vector<int64_t> rp; uint64_t cap; uint32_t want; std::vector<int> emptied; };
+        const std::vector<Case> cases = {
+            {{0, 3, 3, 10}, 10, 0u, {}},                       // well-formed
+            {{7, 9, 20}, 13, 0u, {}},                          // row_ptr[0] need not be 0
+            {{0, 1000, 5}, 5, 1u, {0, 1}},                     // overshoots and comes back: row 0 would read 1000 indices
+            {{0, 4, 3, 8}, 8, 1u, {1}},                        // an adjacent decrease inside the buffer
+            {{-2, 1, 4}, 6, 1u, {0, 1}},                       // negative first offset
+            {{5, 2, 9}, 9, 1u, {0, 1}},                        // second offset below the first: row 0 decreases, row 1 starts below lo
+            {{0, 6, 12}, 11, 4u, {0, 1}},                      // more nonzeros than the workspace serves
+            {{0, 0, 0}, 0, 0u, {}},                            // empty rows only
+        };
+        for (const Case& c : cases) {
+            const int n = (int)c.rp.size() - 1;
+            uint32_t status = 0;
+            std::vector<int> emptied;
+            for (int r = 0; r < n; ++r) {
+                const uint32_t st = row_extent_status(c.rp[r], c.rp[r + 1], c.rp[0], c.rp[n], c.cap, true);
+                status |= st;
+                if (st) emptied.push_back(r);
+                // without validation only a negative length is caught
+                const uint32_t plain = row_extent_status(c.rp[r], c.rp[r + 1], 0, 0, c.cap, false);
+                if (plain != (c.rp[r + 1] < c.rp[r] ? 1u : 0u)) FAIL("row extent without validation, row %d", r);
+                // a row that passes is read inside [lo, hi) only and is no longer than the workspace's bound
+                if (!st && (c.rp[r] < c.rp[0] || c.rp[r + 1] > c.rp[n] || (uint64_t)(c.rp[r + 1] - c.rp[r]) > c.cap))
+                    FAIL("row extent: row %d accepted outside the vouched range", r);
+                ++checks;
+            }
+            if (status != c.want || emptied != c.emptied) FAIL("row extent: status %u, expected %u (first offset %lld)", status, c.want, (long long)c.rp[0]);
+        }
+    }
     if (full_bit31 < 1000 || full_doubtful < full_bit31) FAIL("full keys: %ld with bit 31 set, %ld doubtful", full_bit31, full_doubtful);
     if (full4_high < 100000) FAIL("4U full keys: only %ld evaluations above p", full4_high);
     printf("OK %ld\n", checks);

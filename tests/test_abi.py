@@ -110,7 +110,9 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert _call(lib, family=mh.FAMILY_PERM, perm_ld=63) == -5
     assert _call(lib, perm_ld=64) == -5                               # perm_ld must be 0 for hash families
     assert _call(lib, flags=8) == -1
-    assert _call(lib, flags=4) == -1                                  # the exact-fold switch: 2U p = 2^61-1 and 4U p = 2^31-1 only
+    assert _call(lib, flags=4, family=mh.FAMILY_4U_M61, D=1 << 30) == -1   # the exact-fold switch: not for 4U p = 2^61-1,
+    assert _call(lib, flags=4, family=mh.FAMILY_2U_MS32) == -1             # multiply-shift
+    assert _call(lib, flags=4, family=mh.FAMILY_PERM, perm_ld=64) == -1    # or the permutation table
     assert _call(lib, flags=2, family=mh.FAMILY_2U_M61, D=1 << 30) == -1   # the % ablation exists for p = 2^31-1 only
     assert _call(lib, row_ptr=0) == -1
     assert _call(lib, params=0) == -1

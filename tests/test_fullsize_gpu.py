@@ -144,7 +144,7 @@ def test_heavy_tailed_m61_batch_sampled_rows(batch):
     w, nnz, rp_np, seed, col, params, params_np, out = _run_workload("huge_2u_m61", batch)
     assert nnz.max() == 1_000_000                     # the batch contains rows at the cap
     order = np.argsort(nnz, kind="stable")
-    rows = [int(order[-1])]                           # one row at the 10^6 cap: 122 chunks merged by atomicMin
+    rows = [int(order[-1])]                           # one row at the 10^6 cap: 123 chunks, each with a vector of partial minima, merged by the finalize kernel
     rows += _sample_rows(nnz, 24, seed=18 + batch, eval_budget=4.0e8, k=w.k)
     _check_rows(w, nnz, rp_np, seed, col, params, params_np, out, list(dict.fromkeys(rows)))
     # b = 1, k = 500: 63 bytes per row, the last 4 bits of the last byte are pad and must be 0
@@ -177,6 +177,35 @@ def test_guarded_m61_path_equals_the_exact_fold_on_a_whole_batch():
     idx = col[lo:hi].cpu().numpy().view(np.uint32)
     want = oracle.signatures(np.array([0, hi - lo], dtype=np.int64), idx, w.D, w.k, 32, w.family, params_np)
     assert np.array_equal(outs[0][r].cpu().numpy(), want[0])
+
+
+def test_2u_doubled_key_equals_the_two_maxima_form_on_a_whole_batch():
+    """The headline kernel (`large_2u`: one running maximum of the doubled key, doubtful values
+    computed again) against the same batch under MINHASH_FLAG_EXACT_FOLD, which keeps a signed
+    and an unsigned maximum of the key and never looks twice: full 32-bit minima of all
+    350 000 rows.  (GPU against GPU; the sampled rows above pin both forms to the oracle.)"""
+    w = W.WORKLOADS["large_2u"]
+    nnz = w.nnz(0)
+    rp_np = W.row_ptr_from_nnz(nnz)
+    col = W.csr_indices_torch(nnz, w.D, w.data_seed, DEV)
+    rp = torch.from_numpy(rp_np).to(DEV)
+    params_np = W.coefficients(w.k, w.family, w.param_seed)
+    params = torch.from_numpy(params_np.view(np.int64)).to(DEV)
+    ws = mh.alloc_workspace(len(nnz), int(rp_np[-1]), w.k, w.family, DEV)
+    outs = []
+    for flags in (0, mh.FLAG_EXACT_FOLD):
+        out = torch.full((len(nnz), 4 * w.k), 0xAA, dtype=torch.uint8, device=DEV)
+        mh.minhash_signatures(rp, col, w.D, w.k, 32, w.family, params, out=out, workspace=ws, flags=flags)
+        assert mh.status(ws) == 0
+        outs.append(out)
+    assert torch.equal(outs[0], outs[1])
+    # the two-maxima form itself against the oracle on a few rows at full width
+    order = np.argsort(nnz, kind="stable")
+    for r in (int(order[0]), int(order[len(nnz) // 2]), int(order[-1])):
+        lo, hi = int(rp_np[r]), int(rp_np[r + 1])
+        idx = col[lo:hi].cpu().numpy().view(np.uint32)
+        want = oracle.signatures(np.array([0, hi - lo], dtype=np.int64), idx, w.D, w.k, 32, w.family, params_np)
+        assert np.array_equal(outs[1][r].cpu().numpy(), want[0])
 
 
 def test_4u_full_keys_equal_the_shifted_ones_on_a_whole_batch():

@@ -376,6 +376,38 @@ def test_validate_flag_reports_bad_input():
     assert st == -9
 
 
+def test_validate_flag_keeps_every_row_inside_the_vouched_range():
+    """Offsets that overshoot and come back, a negative first offset, and a range that holds more
+    nonzeros than the workspace was sized for: each is reported, the rows concerned are treated as
+    empty, and the well-formed rows of the same batch still get their signatures."""
+    D, k = 1 << 16, 16
+    c = W.coefficients(k, mh.FAMILY_2U_M31, seed=4)
+    col = W.csr_indices_np(np.array([5], dtype=np.int64), D, seed=31)
+    empty_sig = np.full(k, 0xFF, dtype=np.uint8)
+    for family, params in ((mh.FAMILY_2U_M31, c), (mh.FAMILY_PERM, W.perm_table_np(D, k, seed=5))):
+        got, st = gpu_signatures(np.array([0, 1000, 5], dtype=np.int64), col, D, k, 8, family, params, flags=mh.FLAG_VALIDATE)
+        assert st == -9
+        assert np.array_equal(got[0], empty_sig) and np.array_equal(got[1], empty_sig)
+        got, st = gpu_signatures(np.array([-3, 2, 5], dtype=np.int64), col, D, k, 8, family, params, flags=mh.FLAG_VALIDATE)
+        assert st == -9
+        assert np.array_equal(got[0], empty_sig) and np.array_equal(got[1], empty_sig)
+        # one bad row between two good ones
+        rp = np.array([0, 2, 1, 5], dtype=np.int64)
+        got, st = gpu_signatures(rp, col, D, k, 8, family, params, flags=mh.FLAG_VALIDATE)
+        assert st == -9
+        want0 = oracle.signatures(np.array([0, 2], dtype=np.int64), col[:2], D, k, 8, family, params)
+        want2 = oracle.signatures(np.array([0, 4], dtype=np.int64), col[1:5], D, k, 8, family, params)
+        assert np.array_equal(got[0], want0[0]) and np.array_equal(got[1], empty_sig) and np.array_equal(got[2], want2[0])
+    # a workspace sized for 100 nonzeros and offsets that describe 50 115: with validation nothing is read
+    nnz = np.array([5, 30000, 7, 100, 20000, 3], dtype=np.int64)
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, 1 << 24, seed=21)
+    ws = mh.alloc_workspace(len(nnz), 100, k, mh.FAMILY_2U_M31, DEV)
+    out = mh.minhash_signatures(_to_dev(rp), _to_dev(col), 1 << 24, k, 8, mh.FAMILY_2U_M31, _to_dev(c), workspace=ws,
+                                flags=mh.FLAG_VALIDATE)
+    assert mh.status(ws) == -6
+    assert bool((out == 0xFF).all().item())
+
+
 def test_workspace_sized_for_too_few_nonzeros_is_reported_not_overrun():
     """The work list is bounded by the workspace: a batch that does not fit is
     reported through minhash_status (its output is unspecified) and nothing is
