@@ -6,8 +6,9 @@
  * for each of k hash functions (or explicit permutations) the minimum hashed
  * location over the row's nonzeros, of which only the lowest b bits are kept.
  * All pointers are plain pointers; which side of the bus they live on is stated
- * per argument.  Every buffer, including the workspace, belongs to the caller.
- * Between calls the library keeps only launch constants per
+ * per argument.  Every buffer, including the workspace, belongs to the caller
+ * (the one exception is minhash_signatures_static, which works in a buffer built
+ * into the library).  Between calls the library keeps only launch constants per
  * device (number of compute units, resident blocks per kernel).  No call throws;
  * errors are return codes.
  */
@@ -49,8 +50,10 @@ enum {
     MINHASH_ERR_HIP       = -7,  /* a HIP runtime call failed; see minhash_last_hip_error()    */
     MINHASH_ERR_COEFF     = -8,  /* minhash_check_coeffs: a coefficient is >= p (multiply-shift:
                                     >= 2^32, or the multiplier is even)                        */
-    MINHASH_ERR_DATA      = -9   /* minhash_status: VALIDATE found an index >= D or a
+    MINHASH_ERR_DATA      = -9,  /* minhash_status: VALIDATE found an index >= D or a
                                     decreasing row_ptr                                         */
+    MINHASH_ERR_TOO_LARGE = -10  /* minhash_signatures_static: the batch needs more than
+                                    MINHASH_STATIC_SCRATCH_BYTES of work space                 */
 };
 
 #define MINHASH_MAX_K            65536
@@ -143,6 +146,46 @@ int minhash_signatures_profiled(const int64_t *row_ptr, const uint32_t *col_idx,
                                 uint8_t *out, int64_t out_stride,
                                 void *workspace, size_t workspace_bytes,
                                 void *stream, uint32_t flags, float *kernel_ms);
+
+/*
+ * minhash_signatures_static - for callers that cannot allocate device memory
+ * (code under HIP graph capture, serving loops or harnesses that forbid
+ * hipMalloc and torch allocations): the computation of minhash_signatures with
+ * its work list and partial minima in a buffer of
+ * MINHASH_STATIC_SCRATCH_BYTES that is built into the library's device code
+ * (one copy per GPU the library runs on, held until the process ends), so the
+ * caller passes inputs and outputs only.  The call allocates nothing, on the
+ * host or on the device, and does not synchronise.
+ *
+ *   nnz_upper_bound  >= row_ptr[n_rows] - row_ptr[0].  With P = nnz_upper_bound / 8192
+ *                    + min(n_rows, nnz_upper_bound / 8192), the batch fits whenever
+ *                    32 (n_rows + P + nnz_upper_bound / 2048) + 16 min(n_rows,
+ *                    nnz_upper_bound / 512) + 4 k P + 2048 bytes are at most
+ *                    MINHASH_STATIC_SCRATCH_BYTES (k = 500: 200 000 rows with
+ *                    10^8 nonzeros fit, the 350 000 rows with 1.3x10^9 nonzeros
+ *                    of a whole webspam-sized batch do not); otherwise the call
+ *                    returns MINHASH_ERR_TOO_LARGE and enqueues nothing.
+ *   status           device, one int32, or NULL.  The last kernel of the call
+ *                    stores there what minhash_status would report
+ *                    (MINHASH_OK, MINHASH_ERR_WORKSPACE if row_ptr described more
+ *                    than nnz_upper_bound nonzeros, MINHASH_ERR_DATA for what
+ *                    MINHASH_FLAG_VALIDATE found); minhash_status itself cannot
+ *                    see the built-in buffer.
+ *   all other arguments, the result and the return codes are those of
+ *   minhash_signatures.
+ *
+ * All calls on one GPU share that GPU's buffer: calls on one stream run one
+ * after the other and are safe, calls that overlap on different streams of one
+ * GPU race.  The address of the buffer is looked up once per device, on the
+ * first call with that device current (a caller that captures a graph makes one
+ * call before the capture starts).
+ */
+#define MINHASH_STATIC_SCRATCH_BYTES (64u << 20)
+int minhash_signatures_static(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows,
+                              int64_t nnz_upper_bound, uint64_t D, int32_t k, int32_t b, int32_t family,
+                              const void *params, int64_t perm_ld,
+                              uint8_t *out, int64_t out_stride,
+                              int32_t *status, void *stream, uint32_t flags);
 
 /* Bytes of device workspace a call with at most nnz_upper_bound nonzeros needs
  * (load-balancer work list plus partial minima of rows that are split across

@@ -40,10 +40,15 @@
 #include <string.h>
 
 #include <atomic>
+#include <mutex>
 #include <type_traits>
 
 #include "minhash.h"
 #include "mh_arith.h"
+
+// Work space of minhash_signatures_static: one copy per GPU, held until the process
+// ends.  Host code reaches it only through the address static_scratch() looks up.
+static __device__ __align__(256) unsigned char scratch[MINHASH_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -109,7 +114,7 @@ struct Layout {                        // host and device agree on the workspace
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
-inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k)
+inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k, uint64_t reserve_bytes = SMALL_BATCH_BYTES)
 {
     Layout L;
     const uint64_t n = (uint64_t)n_rows, nnz = (uint64_t)nnz_ub;
@@ -120,7 +125,7 @@ inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k)
     // Large batches use MAX_CHUNK; a reserve lets small batches use smaller chunks (the device picks the size
     // that fits, see mh_reset_kernel).
     const uint64_t by_max = nnz / MAX_CHUNK;
-    uint64_t reserve = SMALL_BATCH_BYTES / (sizeof(uint32_t) * (uint64_t)k);
+    uint64_t reserve = reserve_bytes / (sizeof(uint32_t) * (uint64_t)k);
     if (reserve > SMALL_BATCH_PARTS) reserve = SMALL_BATCH_PARTS;
     uint64_t small_need = by_min + L.cap_split;                       // what MIN_CHUNK would need
     if (reserve > small_need) reserve = small_need;
@@ -1679,6 +1684,16 @@ __global__ __launch_bounds__(BLOCK) void mh_finalize_kernel(KArgs a, int ftile_s
     }
 }
 
+// Copies the deferred status of a call to where the caller wants it (a caller that
+// may not synchronise reads it later, from its own memory).
+__global__ void mh_export_status_kernel(const WorkHeader* hdr, int32_t* status_out)
+{
+    const uint32_t st = hdr->status;
+    *status_out = (st & 4u) ? MINHASH_ERR_WORKSPACE : st ? MINHASH_ERR_DATA : MINHASH_OK;
+}
+
+__global__ void mh_store_ok_kernel(int32_t* status_out) { *status_out = MINHASH_OK; }
+
 // ------------------------------------------------------------------ host side
 thread_local char g_hip_error[256] = "";
 
@@ -1854,9 +1869,9 @@ int check_arguments(const int64_t* row_ptr, int64_t n_rows, uint64_t D, int32_t 
 // Fills the plan for a workspace at `ws` laid out for at most nnz_cap nonzeros.
 int make_plan(Plan* plan, const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_t D, int32_t k, int32_t b,
               int32_t family, const void* params, int64_t perm_ld, uint8_t* out, int64_t out_stride, void* workspace,
-              int64_t nnz_cap, uint32_t flags)
+              int64_t nnz_cap, uint32_t flags, uint64_t reserve_bytes = SMALL_BATCH_BYTES)
 {
-    const Layout L = make_layout(n_rows, nnz_cap, k);
+    const Layout L = make_layout(n_rows, nnz_cap, k, reserve_bytes);
     char* ws = static_cast<char*>(workspace);
     KArgs& a = plan->a;
     memset(&a, 0, sizeof(a));
@@ -1911,7 +1926,8 @@ int make_plan(Plan* plan, const int64_t* row_ptr, const uint32_t* col_idx, int64
 
 // Enqueues the kernels of a planned call.  Events of the profiled variant exist
 // before the first launch, so that a failure to create them leaves nothing enqueued.
-int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream, float* kernel_ms, bool profiled)
+int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream, float* kernel_ms, bool profiled,
+            int32_t* status_out)
 {
     KArgs& a = plan.a;
     Launch l;
@@ -1975,6 +1991,7 @@ int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream
     hipError_t r1 = profiled ? hipEventRecord(e1, l.s) : hipSuccess;
     if (plan.has_split)
         hipLaunchKernelGGL(mh_finalize_kernel, dim3(l.cus * 8), dim3(BLOCK), 0, l.s, a, plan.ftile_size);   // latency-bound: fill the chip
+    if (status_out) hipLaunchKernelGGL(mh_export_status_kernel, dim3(1), dim3(1), 0, l.s, a.hdr, status_out);
 
     hipError_t le = hipGetLastError();
     if (profiled) {
@@ -1992,6 +2009,30 @@ int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream
         if (kernel_ms) *kernel_ms = ms;
     }
     if (le != hipSuccess) return hip_fail(le, "kernel launch");
+    return MINHASH_OK;
+}
+
+// The device address of the built-in work space on the GPU that is current, looked
+// up once per device.  `scratch` names the array for the compiler; on the host that
+// name is a stand-in and not a device address, so host code only ever hands out the
+// pointer found here.
+int static_scratch(void** ptr)
+{
+    static std::mutex lock;
+    static void* address[MAX_DEVICES];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return MINHASH_ERR_ARG;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!address[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress");
+        if (!p || (reinterpret_cast<uintptr_t>(p) % MINHASH_WORKSPACE_ALIGN) != 0) return MINHASH_ERR_WORKSPACE;
+        address[dev] = p;
+    }
+    *ptr = address[dev];
     return MINHASH_OK;
 }
 
@@ -2016,7 +2057,7 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
     Plan plan;
     rc = make_plan(&plan, row_ptr, col_idx, n_rows, D, k, b, family, params, perm_ld, out, out_stride, workspace, lo, flags);
     if (rc != MINHASH_OK) return rc;
-    return enqueue(plan, family, D, flags, stream, kernel_ms, profiled);
+    return enqueue(plan, family, D, flags, stream, kernel_ms, profiled, nullptr);
 }
 
 }  // namespace
@@ -2039,6 +2080,42 @@ int minhash_signatures_profiled(const int64_t* row_ptr, const uint32_t* col_idx,
 {
     return run(row_ptr, col_idx, n_rows, D, k, b, family, params, perm_ld, out, out_stride, workspace,
                workspace_bytes, stream, flags, kernel_ms, true);
+}
+
+int minhash_signatures_static(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, int64_t nnz_upper_bound,
+                              uint64_t D, int32_t k, int32_t b, int32_t family, const void* params, int64_t perm_ld,
+                              uint8_t* out, int64_t out_stride, int32_t* status, void* stream, uint32_t flags)
+{
+    bool empty = false;
+    int rc = check_arguments(row_ptr, n_rows, D, k, b, family, params, perm_ld, out, out_stride, flags, &empty);
+    if (rc != MINHASH_OK) return rc;
+    if (nnz_upper_bound < 0) return MINHASH_ERR_ARG;
+    if (nnz_upper_bound > ((int64_t)1 << 46)) return MINHASH_ERR_TOO_LARGE;
+    // The reserve of partial vectors that lets small batches cut their long rows finely is
+    // what a caller-sized workspace spends most of its bytes on; here it shrinks until the
+    // layout fits the built-in buffer (the device picks the chunk size that the vectors allow).
+    uint64_t reserve = SMALL_BATCH_BYTES;
+    while (make_layout(n_rows, nnz_upper_bound, k, reserve).total > (size_t)MINHASH_STATIC_SCRATCH_BYTES) {
+        if (reserve == 0) return MINHASH_ERR_TOO_LARGE;
+        reserve = reserve > (1u << 20) ? reserve / 2 : 0;
+    }
+    void* ws = nullptr;
+    rc = static_scratch(&ws);          // the device address of `scratch` on the current GPU, never its host-side name
+    if (rc != MINHASH_OK) return rc;
+    if (empty) {                       // nothing to hash; the caller's status word still gets its value
+        if (status) {
+            (void)hipGetLastError();
+            hipLaunchKernelGGL(mh_store_ok_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), status);
+            hipError_t le = hipGetLastError();
+            if (le != hipSuccess) return hip_fail(le, "kernel launch");
+        }
+        return MINHASH_OK;
+    }
+    Plan plan;
+    rc = make_plan(&plan, row_ptr, col_idx, n_rows, D, k, b, family, params, perm_ld, out, out_stride, ws,
+                   nnz_upper_bound, flags, reserve);
+    if (rc != MINHASH_OK) return rc;
+    return enqueue(plan, family, D, flags, stream, nullptr, false, status);
 }
 
 size_t minhash_workspace_bytes(int64_t n_rows, int64_t nnz_upper_bound, int32_t k, int32_t family)
@@ -2087,6 +2164,7 @@ const char* minhash_error_string(int code)
     case MINHASH_ERR_HIP: return "HIP runtime error";
     case MINHASH_ERR_COEFF: return "hash coefficient not below the prime";
     case MINHASH_ERR_DATA: return "input data invalid (index >= D or decreasing row_ptr)";
+    case MINHASH_ERR_TOO_LARGE: return "batch needs more work space than the built-in buffer of minhash_signatures_static holds";
     default: return "unknown error code";
     }
 }

@@ -24,6 +24,8 @@ FLAG_VALIDATE = 1
 FLAG_GENERIC_MOD = 2
 FLAG_EXACT_FOLD = 4
 WORKSPACE_ALIGN = 256
+STATIC_SCRATCH_BYTES = 64 << 20
+ERR_TOO_LARGE = -10
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libminhash.so")
@@ -31,6 +33,7 @@ LIB_PATH = os.path.join(_HERE, "libminhash.so")
 EXPORTS = (
     "minhash_signatures",
     "minhash_signatures_profiled",
+    "minhash_signatures_static",
     "minhash_workspace_bytes",
     "minhash_check_coeffs",
     "minhash_status",
@@ -70,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.minhash_signatures.restype = ctypes.c_int
         L.minhash_signatures_profiled.argtypes = sig + [ctypes.POINTER(ctypes.c_float)]
         L.minhash_signatures_profiled.restype = ctypes.c_int
+        L.minhash_signatures_static.argtypes = [vp, vp, i64, i64, u64, i32, i32, i32, vp, i64, vp, i64, vp, vp, u32]
+        L.minhash_signatures_static.restype = ctypes.c_int
         L.minhash_workspace_bytes.argtypes = [i64, i64, i32, i32]
         L.minhash_workspace_bytes.restype = sz
         L.minhash_check_coeffs.argtypes = [vp, i32, i32]
@@ -224,6 +229,30 @@ def minhash_signatures_profiled(row_ptr, col_idx, D, k, b, family, params, out=N
     if rc != 0:
         _raise(rc)
     return out, float(ms.value)
+
+
+def minhash_signatures_static(row_ptr: torch.Tensor, col_idx: torch.Tensor, nnz_upper_bound: int, D: int, k: int, b: int,
+                              family: int, params: torch.Tensor, out: torch.Tensor, status: Optional[torch.Tensor] = None,
+                              perm_ld: Optional[int] = None, stream=None, flags: int = 0) -> torch.Tensor:
+    """The same computation in the library's built-in work space, for callers that
+    may not allocate: ``out`` (uint8 [n_rows, out_stride]) and the optional
+    ``status`` (one int32 on the device) are the caller's, nothing is allocated
+    here or in the library.  Raises MinhashError(ERR_TOO_LARGE) for a batch the
+    built-in buffer cannot serve."""
+    _check_common(row_ptr, col_idx, params, family)
+    _check_out(out, row_ptr)
+    if status is not None and (status.dtype != torch.int32 or status.numel() < 1 or status.device != row_ptr.device):
+        raise TypeError("status must be an int32 tensor on the device of the inputs")
+    if family == FAMILY_PERM:
+        perm_ld = params.shape[1] if perm_ld is None else perm_ld
+    else:
+        perm_ld = 0
+    rc = lib().minhash_signatures_static(_ptr(row_ptr), _ptr(col_idx), row_ptr.numel() - 1, nnz_upper_bound, D, k, b,
+                                         family, _ptr(params), perm_ld, _ptr(out), out.shape[1], _ptr(status),
+                                         _stream_handle(stream), flags)
+    if rc != 0:
+        _raise(rc)
+    return out
 
 
 def status(workspace: torch.Tensor, stream=None) -> int:

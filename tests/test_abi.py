@@ -122,6 +122,39 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert _call(lib, ws_bytes=128) == -6                             # too small for the work list
 
 
+def _call_static(lib, n_rows=4, nnz_ub=1000, D=1 << 24, k=64, b=8, family=0, perm_ld=0, out_stride=64, row_ptr=0x1000,
+                 col_idx=0x1000, params=0x1000, out=0x1000, status=0, flags=0):
+    return lib.minhash_signatures_static(row_ptr, col_idx, n_rows, nnz_ub, D, k, b, family, params, perm_ld, out,
+                                         out_stride, status, 0, flags)
+
+
+def test_static_entry_point_rejects_bad_arguments_and_oversized_batches_before_any_hip_call(lib):
+    assert _call_static(lib, n_rows=-1) == -1
+    assert _call_static(lib, nnz_ub=-1) == -1
+    assert _call_static(lib, family=9) == -2
+    assert _call_static(lib, D=0) == -3
+    assert _call_static(lib, k=0) == -4
+    assert _call_static(lib, out_stride=63) == -5
+    assert _call_static(lib, flags=8) == -1
+    assert _call_static(lib, out=0) == -1
+    # the built-in buffer holds 64 MiB: a webspam-sized batch does not fit, nor does a bound beyond 2^46
+    assert _call_static(lib, n_rows=350_000, nnz_ub=1_300_000_000, k=500, out_stride=500) == mh.ERR_TOO_LARGE
+    assert _call_static(lib, nnz_ub=(1 << 46) + 1) == mh.ERR_TOO_LARGE
+    assert _call_static(lib, n_rows=3_000_000, nnz_ub=0) == mh.ERR_TOO_LARGE      # the work list alone is too long
+    assert b"built-in" in lib.minhash_error_string(mh.ERR_TOO_LARGE)
+    # the header's sufficient condition, on shapes on both sides of it
+    def bound(n, nnz, k):
+        P = nnz // 8192 + min(n, nnz // 8192)
+        return 32 * (n + P + nnz // 2048) + 16 * min(n, nnz // 512) + 4 * k * P + 2048
+    for n, nnz, k in [(200_000, 100_000_000, 500), (1_000, 650_000, 64), (1_000_000, 30_000_000, 200)]:
+        assert bound(n, nnz, k) <= mh.STATIC_SCRATCH_BYTES
+        # accepted as far as the host-side checks go: without a GPU the call then fails in the HIP runtime
+        # (with one, the made-up pointers must not reach a kernel)
+        import torch
+        if not torch.cuda.is_available():
+            assert _call_static(lib, n_rows=n, nnz_ub=nnz, k=k, out_stride=k) == -7
+
+
 def test_profiled_entry_point_validates_the_same_way(lib):
     ms = ctypes.c_float(-1.0)
     rc = lib.minhash_signatures_profiled(0x1000, 0x1000, 4, 0, 64, 8, 0, 0x1000, 0, 0x1000, 64, 0x1000, 1 << 20, 0, 0,
