@@ -16,6 +16,9 @@ ROOT = os.path.dirname(HERE)
 SRCS = [os.path.join(HERE, "csrc", "minhash.hip"), os.path.join(HERE, "csrc", "consumers.hip"),
         os.path.join(HERE, "csrc", "ingest.hip")]
 LIB = os.path.join(HERE, "libminhash.so")
+# measurement only (instruction-issue and memory probes behind bench.py --probe); the signature library does not use it
+PROBE_SRCS = [os.path.join(HERE, "csrc", "probe.hip")]
+PROBE_LIB = os.path.join(HERE, "libminhash_probe.so")
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-pthread",
@@ -24,10 +27,10 @@ HIPCC_FLAGS = [
 ]
 
 
-def build(verbose: bool = False, extra=()) -> str:
+def _compile(srcs, lib, verbose, extra) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra) + SRCS + ["-o", tmp]
+    tmp = lib + ".tmp%d" % os.getpid()
+    cmd = [hipcc] + HIPCC_FLAGS + list(extra) + srcs + ["-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
@@ -39,8 +42,14 @@ def build(verbose: bool = False, extra=()) -> str:
         raise RuntimeError("hipcc failed:\n" + log)
     if verbose and log.strip():
         print(log)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
+
+
+def build(verbose: bool = False, extra=()) -> str:
+    """Compiles both libraries; returns the path of the signature library."""
+    _compile(PROBE_SRCS, PROBE_LIB, verbose, extra)
+    return _compile(SRCS, LIB, verbose, extra)
 
 
 if __name__ == "__main__":

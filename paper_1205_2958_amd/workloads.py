@@ -129,11 +129,13 @@ def row_ptr_from_nnz(nnz: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------
 # feature indices
 # --------------------------------------------------------------------------
-def csr_indices_np(nnz: np.ndarray, D: int, seed: int, row_offset: int = 0) -> np.ndarray:
+def csr_indices_np(nnz: np.ndarray, D: int, seed: int, row_offset: int = 0, rows: Optional[np.ndarray] = None) -> np.ndarray:
     """Sorted, distinct uint32 indices in [0, D) for every row, concatenated.
 
     ``row_offset`` is added to the row number in the key derivation so that a
-    slice of rows of a large workload can be generated on its own.
+    slice of rows of a large workload can be generated on its own; ``rows``
+    gives the row numbers one by one instead (``nnz[i]`` is then the length of
+    row ``rows[i]``), for a sample of rows that are not neighbours.
     """
     s = _check_pow2(D)
     nnz = np.asarray(nnz, dtype=np.int64)
@@ -146,7 +148,10 @@ def csr_indices_np(nnz: np.ndarray, D: int, seed: int, row_offset: int = 0) -> n
         return np.zeros(0, dtype=np.uint32)
     row_of = np.repeat(np.arange(n, dtype=np.int64), nnz)
     pos = np.arange(total, dtype=np.int64) - row_ptr[row_of]
-    keys = _round_keys_np(seed, np.arange(n, dtype=np.int64) + row_offset)
+    numbers = np.arange(n, dtype=np.int64) + row_offset if rows is None else np.asarray(rows, dtype=np.int64)
+    if numbers.shape[0] != n:
+        raise ValueError("one row number per row length")
+    keys = _round_keys_np(seed, numbers)
     idx = _feistel(pos, lambda r: keys[row_of, r], s)
     order_key = (row_of << 32) | idx
     order_key.sort()
@@ -188,6 +193,100 @@ def csr_indices_torch(nnz: np.ndarray, D: int, seed: int, device, row_offset: in
         out[e0:e1] = (order_key & 0xFFFFFFFF).to(torch.int32)  # wraps to the uint32 bit pattern
         del row_of, pos, idx, order_key
     return out
+
+
+# --------------------------------------------------------------------------
+# which rows of a batch a checker looks at
+# --------------------------------------------------------------------------
+def stratified_rows(nnz: np.ndarray, k: int, eval_budget: float, seed: int, split: int = 8192,
+                    max_row_evals: Optional[float] = None, heavy_from: Optional[int] = None):
+    """A seeded sample of row numbers for comparing a batch's signatures with a
+    slow checker, chosen by row length alone (no hashing here):
+
+      * the first and the last row, the shortest row and the longest row
+        (the longest that ``max_row_evals`` allows, if given);
+      * for m = 1, 2, 4, 8, ... times ``split``, the length at which rows are
+        cut into chunks, the row whose length is closest to m * split from below
+        and the one closest from above;
+      * if ``heavy_from`` is given, rows of at least that many nonzeros, in
+        seeded random order;
+      * then rows drawn in turn from the ten deciles of the length distribution
+        (seeded, without replacement), decile 0 first, until the budget of
+        ``eval_budget`` evaluations (nonzeros * k) is spent.
+
+    The named rows and the heavy ones are taken while they fit three fifths of
+    the budget (the first row always is); the deciles get the rest.  Returns (sorted row numbers, dict with the achieved coverage).
+    """
+    nnz = np.asarray(nnz, dtype=np.int64)
+    n = nnz.shape[0]
+    rng = np.random.Generator(np.random.PCG64(seed))
+    order = np.argsort(nnz, kind="stable")
+    lens = nnz[order]
+    cap = np.inf if max_row_evals is None else max_row_evals
+    ok = lambda r: float(nnz[r]) * k <= cap
+    must = [0, n - 1, int(order[0])]
+    at_cap = n if max_row_evals is None else int(np.searchsorted(lens, max_row_evals / k, side="right"))
+    if at_cap > 0:
+        must.append(int(order[at_cap - 1]))                           # the longest row the cap allows
+    top = int(lens[-1])
+    m = 1
+    while m * split <= top:                                           # m = 1, 2, 4, 8, ...
+        at = int(np.searchsorted(lens, m * split, side="right"))      # lens[at-1] <= m*split < lens[at]
+        if at > 0:
+            must.append(int(order[at - 1]))
+        if at < n:
+            must.append(int(order[at]))
+        m *= 2
+    picked, spent = [], 0.0
+    seen = set()
+
+    def take(r: int, limit: float) -> bool:
+        nonlocal spent
+        if r in seen:
+            return True
+        cost = float(nnz[r]) * k
+        if not ok(r) or (picked and spent + cost > limit):
+            return False
+        seen.add(r)
+        picked.append(r)
+        spent += cost
+        return True
+
+    # the named rows and the heavy ones may spend three fifths of the budget; the deciles get the rest
+    for r in must:
+        take(r, 0.6 * eval_budget)
+    if heavy_from is not None:
+        heavy = np.flatnonzero(nnz >= heavy_from)
+        for r in rng.permutation(heavy):
+            if spent >= 0.6 * eval_budget:
+                break
+            take(int(r), 0.6 * eval_budget)
+    deciles = [rng.permutation(part) for part in np.array_split(order, 10)]
+    at = [0] * 10
+    live = True
+    while live and spent < eval_budget:
+        live = False
+        for d in range(10):
+            while at[d] < len(deciles[d]):
+                r = int(deciles[d][at[d]])
+                at[d] += 1
+                if r in seen:
+                    continue
+                if take(r, eval_budget):
+                    live = True
+                break
+    rows = np.array(sorted(picked), dtype=np.int64)
+    total_evals = float(nnz.sum()) * k
+    cover = {
+        "rows": int(rows.shape[0]),
+        "nonzeros": int(nnz[rows].sum()),
+        "pct_of_evaluations": 100.0 * spent / total_evals if total_evals else 100.0,
+        "longest_row": int(nnz[rows].max()) if rows.size else 0,
+        "rule": "first, last, shortest, longest row; rows next to 1, 2, 4, ... times %d nonzeros; %srows drawn in turn "
+                "from the ten length deciles, seed %d" % (split, "rows of at least %d nonzeros in random order; " % heavy_from
+                                                          if heavy_from is not None else "", seed),
+    }
+    return rows, cover
 
 
 # --------------------------------------------------------------------------

@@ -16,6 +16,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def _bench_module():
     spec = importlib.util.spec_from_file_location("bench_under_test", os.path.join(ROOT, "bench.py"))
     mod = importlib.util.module_from_spec(spec)
+    sys.modules["bench_under_test"] = mod          # forked workers find the module's functions by this name
     spec.loader.exec_module(mod)
     return mod
 
@@ -53,3 +54,30 @@ def test_issue_slots_follow_from_the_mixes():
     assert b.issue_slots(b.ISSUE_MIX_OTHER_D_BIG[W.FAMILY_4U_M31]) == 8.25
     assert b.issue_slots(b.ISSUE_MIX_OTHER_D[W.FAMILY_2U_M31]) == 5.75
     assert b.issue_slots(b.ISSUE_MIX_OTHER_D[W.FAMILY_4U_M31]) == 9.25
+
+
+def test_oracle_pool_deals_rows_to_shards_and_puts_them_back_in_order():
+    """The bench's worker pool only deals rows out and collects them: its result must be what
+    one call of the oracle on the whole sample gives, for a hash family and for the permutation
+    family (where every shard gets the table rows of its own nonzeros, renumbered)."""
+    import numpy as np
+    from oracle import oracle
+
+    b = _bench_module()
+    W = b.W
+    pool = b.OraclePool(3)
+    try:
+        nnz = np.array([5, 0, 900, 17, 1, 300, 64, 0, 2], dtype=np.int64)
+        D, k = 1 << 12, 24
+        rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed=3)
+        c = W.coefficients(k, W.FAMILY_4U_M31, seed=4)
+        got, dt, used = pool.signatures(rp, col, D, k, 6, W.FAMILY_4U_M31, c)
+        assert used == 3 and dt > 0
+        assert np.array_equal(got, oracle.signatures(rp, col, D, k, 6, W.FAMILY_4U_M31, c))
+        got1, _, used1 = pool.signatures(rp, col, D, k, 6, W.FAMILY_4U_M31, c, procs=1)
+        assert used1 == 1 and np.array_equal(got1, got)
+        table = W.perm_table_np(D, k, seed=5)
+        got, _, _ = pool.signatures(rp, col, D, k, 4, W.FAMILY_PERM, None, table_rows=table[col])
+        assert np.array_equal(got, oracle.signatures(rp, col, D, k, 4, W.FAMILY_PERM, table))
+    finally:
+        pool.close()

@@ -87,3 +87,47 @@ def test_planted_pairs_have_the_stated_resemblance():
         s2 = set(col[rp[2 * i + 1]:rp[2 * i + 2]].tolist())
         assert len(s1) == f1 and len(s2) == f2
         assert len(s1 & s2) == 100 and len(s1 | s2) == 400
+
+
+def test_stratified_rows_cover_the_named_rows_every_decile_and_the_budget():
+    w = W.WORKLOADS["large_2u"]
+    nnz = w.nnz(0)[:60_000]
+    k, budget = 500, 2.0e9
+    rows, cover = W.stratified_rows(nnz, k, budget, seed=1)
+    again, _ = W.stratified_rows(nnz, k, budget, seed=1)
+    assert np.array_equal(rows, again)                                   # seeded
+    assert len(set(rows.tolist())) == len(rows) and np.all(np.diff(rows) > 0)
+    spent = float(nnz[rows].sum()) * k
+    assert spent <= budget and spent > 0.9 * budget
+    assert cover["rows"] == len(rows) and cover["nonzeros"] == int(nnz[rows].sum())
+    assert abs(cover["pct_of_evaluations"] - 100.0 * spent / (float(nnz.sum()) * k)) < 1e-9
+    order = np.argsort(nnz, kind="stable")
+    for r in (0, len(nnz) - 1, int(order[0]), int(order[-1])):
+        assert r in rows
+    # both neighbours of the split point and of its double
+    lens = np.sort(nnz[rows])
+    for m in (8192, 16384):
+        assert lens[np.searchsorted(lens, m, side="right") - 1] == nnz[nnz <= m].max()
+        assert lens[np.searchsorted(lens, m, side="right")] == nnz[nnz > m].min()
+    # every decile of the length distribution is represented
+    edges = np.quantile(nnz, np.linspace(0, 1, 11))
+    hist, _ = np.histogram(nnz[rows], bins=edges)
+    assert np.all(hist > 0)
+    # a cap on the cost of one row keeps longer rows out; heavy rows are taken first when asked for
+    rows2, cover2 = W.stratified_rows(nnz, k, budget, seed=1, max_row_evals=20_000 * k, heavy_from=15_000)
+    assert nnz[rows2].max() <= 20_000 and cover2["longest_row"] == nnz[nnz <= 20_000].max()
+    assert (nnz[rows2] >= 15_000).sum() > (nnz[rows] >= 15_000).sum()
+    # everything fits: every row is taken
+    small = nnz[:50]
+    all_rows, cover3 = W.stratified_rows(small, k, 1e15, seed=2)
+    assert np.array_equal(all_rows, np.arange(50)) and cover3["pct_of_evaluations"] == 100.0
+
+
+def test_rows_can_be_generated_one_by_one_by_number():
+    nnz = np.array([7, 0, 300, 12], dtype=np.int64)
+    whole = W.csr_indices_np(nnz, 1 << 16, seed=9)
+    rp = W.row_ptr_from_nnz(nnz)
+    pick = np.array([2, 0, 3])
+    got = W.csr_indices_np(nnz[pick], 1 << 16, seed=9, rows=pick)
+    want = np.concatenate([whole[rp[r]:rp[r + 1]] for r in pick])
+    assert np.array_equal(got, want)
