@@ -162,6 +162,7 @@ struct KArgs {
     int32_t sig_bytes;
     uint32_t target_items;             // work items wanted for a balanced launch (a few per resident wavefront)
     uint32_t validate;
+    uint32_t lane_pack;                // the hash kernel stores packed dwords from registers (see lane_pack_store)
     uint64_t prime;                    // runtime modulus of the generic-% ablation kernels
 };
 
@@ -470,6 +471,49 @@ __device__ __forceinline__ void wave_pack_store(const KArgs& a, const uint32_t* 
     }
 }
 
+// The same for the shapes in which the fields of one lane fill whole dwords: eight
+// functions per lane and b = 8, 16 or 32, a row pitch and an output pointer that are
+// multiples of four (the host checks all of it once per call).  The lane that holds the
+// minima packs them in its own registers and stores its 2, 4 or 8 dwords itself: no trip
+// through the LDS, no loop over fields.  m[0 .. 8) are the minima of functions
+// j_base .. j_base + 7; functions from k on do not exist and are not stored.
+__device__ __forceinline__ void lane_pack_store(const KArgs& a, const uint32_t (&m)[HASH_ACC], uint32_t row, int j_base,
+                                                bool holder)
+{
+    const int valid = a.k - j_base < HASH_FPL ? a.k - j_base : HASH_FPL;
+    if (!holder || valid <= 0) return;
+    const int b = a.b;
+    uint8_t* dst = a.out + (int64_t)row * a.out_stride + (((int64_t)j_base * b) >> 3);
+    uint32_t* dw = reinterpret_cast<uint32_t*>(dst);
+    const int nbytes = (valid * b) >> 3;
+    uint32_t w[HASH_FPL];
+    int nd;
+    if (b == 8) {          // byte 0 of four values per dword
+        w[0] = __builtin_amdgcn_perm(m[1], m[0], 0x0c0c0400u) | __builtin_amdgcn_perm(m[3], m[2], 0x04000c0cu);
+        w[1] = __builtin_amdgcn_perm(m[5], m[4], 0x0c0c0400u) | __builtin_amdgcn_perm(m[7], m[6], 0x04000c0cu);
+        nd = 2;
+    } else if (b == 16) {  // the low halves of two values per dword
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = __builtin_amdgcn_perm(m[2 * i + 1], m[2 * i], 0x05040100u);
+        nd = 4;
+    } else {               // b = 32: the minima as they are
+#pragma unroll
+        for (int i = 0; i < HASH_FPL; ++i) w[i] = m[i];
+        nd = HASH_FPL;
+    }
+#pragma unroll
+    for (int i = 0; i < HASH_FPL; ++i)
+        if (i < nd && 4 * i + 4 <= nbytes) dw[i] = w[i];
+    if (nbytes & 3) {      // the last lane of a k that ends inside a dword: its remaining bytes one by one
+        const int i0 = nbytes >> 2;
+        uint32_t word = 0;
+#pragma unroll
+        for (int i = 0; i < HASH_FPL; ++i)
+            if (i == i0) word = w[i];
+        for (int q = 0; q < (nbytes & 3); ++q) dst[4 * i0 + q] = (uint8_t)(word >> (8 * q));
+    }
+}
+
 // ------------------------------------------------------------------ hash-family policies
 template <class Pol, int NF>
 __device__ __forceinline__ void pair_generic(const typename Pol::Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC],
@@ -537,6 +581,9 @@ struct Pol2U31 {
         }
         return hash_2u31_raw(f, w[0], md);
     }
+    // a running maximum below this is doubtful (full2_key_doubtful): one comparison of a lane's
+    // smallest maximum says whether any of its values is
+    static __device__ __forceinline__ uint32_t doubt_below(const ModDV& md) { return 2u * md.mask; }
     template <int NF>
     static __device__ __forceinline__ uint32_t doubtful(const uint32_t (&m)[HASH_ACC], const ModDV& md)
     {
@@ -665,6 +712,7 @@ struct Pol2U61 {
     {
         return hash_2u61<POW2>(f, w[0], md, D);
     }
+    static __device__ __forceinline__ uint32_t doubt_below(const ModDV&) { return GUARD61_FLOOR; }
     template <int NF>
     static __device__ __forceinline__ uint32_t doubtful(const uint32_t (&m)[HASH_ACC], const ModDV&)
     {
@@ -1390,8 +1438,11 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
             for (uint32_t off = 0; off < len; off += TILE) {
                 const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
-                const int n_steps = (int)((in_tile + 4u * n_slices - 1u) / (4u * n_slices));
-                const int extent = n_steps * 4 * n_slices;      // tile entries the steps below read (pad included)
+                // a step takes four nonzeros per slice (two pairs); when the last step would hold at most
+                // two per slice it is done as a single pair
+                const int n_pairs = (int)((in_tile + 2u * n_slices - 1u) / (2u * n_slices));
+                const int n_steps = n_pairs >> 1;
+                const int extent = (n_steps * 4 + (n_pairs & 1) * 2) * n_slices;      // tile entries read below (pad included)
                 // stage: pre-compute what depends on t alone, one nonzero per lane and register
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -1420,12 +1471,30 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                     Pol::template pair<NF>(fn, m, w[0], w[1], md, a.D);
                     Pol::template pair<NF>(fn, m, w[2], w[3], md, a.D);
                 }
+                if (n_pairs & 1) {
+                    const int e = 4 * n_steps * n_slices + 2 * slice;     // the slices share what is left, two nonzeros each
+                    uint32_t w[2][Pol::NW];
+#pragma unroll
+                    for (int i = 0; i < Pol::NW; ++i) {
+                        uint2 v = *reinterpret_cast<const uint2*>(&tile[i][e]);
+                        w[0][i] = v.x; w[1][i] = v.y;
+                    }
+                    Pol::template pair<NF>(fn, m, w[0], w[1], md, a.D);
+                }
                 wave_sync_lds();
             }
             // A GUARDED policy keeps keys that are exact unless the running value itself, or a guard
             // word beside it, says otherwise (rarely); bit r of `doubt` marks such a value.
             uint32_t doubt = 0;
-            if constexpr (Pol::GUARDED) doubt = Pol::template doubtful<NF>(m, md);
+            if constexpr (Pol::GUARDED) {
+                // hardly ever: the smallest of the lane's maxima decides with one comparison, and the
+                // bit mask is only worked out when some lane of the wavefront has a doubtful value
+                uint32_t lowest = m[0];
+#pragma unroll
+                for (int r = 1; r + 1 < NF; r += 2) lowest = umin3(lowest, m[r], m[r + 1]);
+                if ((NF & 1) == 0) lowest = lowest < m[NF - 1] ? lowest : m[NF - 1];
+                if (__builtin_amdgcn_ballot_w64(lowest < Pol::doubt_below(md)) != 0ull) doubt = Pol::template doubtful<NF>(m, md);
+            }
             if (Pol::TRACK_MAX) {      // back from keys to the minimum location
 #pragma unroll
                 for (int r = 0; r < NF; ++r) {
@@ -1446,7 +1515,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                 // Every doubtful value is computed again from the definition: the whole wavefront
                 // evaluates that one function on all nonzeros of the item, a lane each, and the
                 // owner takes the minimum (over the whole item, which its slice is part of).
-                uint64_t owners = __builtin_amdgcn_ballot_w64(doubt != 0u);
+                uint64_t owners = __builtin_amdgcn_ballot_w64(doubt != 0u);      // doubt is 0 in every lane unless the test above fired
                 if (owners != 0ull && len <= SHORT_ITEM) {
                     // A short item makes many of its values doubtful (few evaluations stand behind
                     // each) and is cheap to go through: every lane sees to its own values.
@@ -1513,13 +1582,26 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
         }
         const int nf_tile = a.k - ftile * a.ftile_size < a.ftile_size ? a.k - ftile * a.ftile_size : a.ftile_size;
         if (it.slot == NO_SLOT) {
-            if (slice == 0) {
-#pragma unroll
-                for (int r = 0; r < NF; ++r) mins[fl * NF + r] = m[r];
+            bool stored = false;
+            if constexpr (NF == HASH_FPL) {
+                if (a.lane_pack) {
+                    lane_pack_store(a, m, it.row, j_base, slice == 0);
+                    if (ftile == a.n_ftiles - 1) {     // pad bytes up to the row pitch are zero
+                        uint8_t* dst = a.out + (int64_t)it.row * a.out_stride;
+                        for (int64_t q = a.sig_bytes + lane; q < a.out_stride; q += WAVE) dst[q] = 0;
+                    }
+                    stored = true;
+                }
             }
-            wave_sync_lds();
-            wave_pack_store(a, mins, it.row, ftile * a.ftile_size, nf_tile, ftile == a.n_ftiles - 1, lane);
-            wave_sync_lds();
+            if (!stored) {
+                if (slice == 0) {
+#pragma unroll
+                    for (int r = 0; r < NF; ++r) mins[fl * NF + r] = m[r];
+                }
+                wave_sync_lds();
+                wave_pack_store(a, mins, it.row, ftile * a.ftile_size, nf_tile, ftile == a.n_ftiles - 1, lane);
+                wave_sync_lds();
+            }
         } else if (slice == 0) {
             uint32_t* part = a.partials + (size_t)it.slot * (size_t)a.k;
 #pragma unroll
@@ -1918,6 +2000,8 @@ int make_plan(Plan* plan, const int64_t* row_ptr, const uint32_t* col_idx, int64
     }
     a.ftile_size = plan->ftile_size;
     a.n_ftiles = (k + plan->ftile_size - 1) / plan->ftile_size;
+    a.lane_pack = family != MINHASH_PERM && plan->nf == HASH_FPL && (b == 8 || b == 16 || b == 32) && out_stride % 4 == 0 &&
+                  reinterpret_cast<uintptr_t>(out) % 4 == 0;
 
     // tickets and unit numbers are 32 bits wide; tickets run past the last unit by one per resident wavefront
     if ((L.cap_long + L.cap_short) * (uint64_t)a.n_ftiles >= (1ull << 32) - (1ull << 24)) return MINHASH_ERR_ARG;
