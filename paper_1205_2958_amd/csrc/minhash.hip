@@ -91,14 +91,14 @@ static_assert(sizeof(WorkHeader) == 256, "header size");
 static_assert(offsetof(WorkHeader, n_short) == 4 && offsetof(WorkHeader, n_split) == 8 && offsetof(WorkHeader, n_parts) == 12,
               "the row-binning kernel addresses the four counters as an array");
 
-struct Item {                          // one unit of row work
+struct alignas(16) Item {              // one unit of row work
     int64_t begin;                     // offset of the first nonzero in col_idx
     uint32_t len;                      // number of nonzeros (at most the chunk size)
     uint32_t row;
     uint32_t slot;                     // NO_SLOT for a whole row, else index of this chunk's vector of partial minima
-    uint32_t pad;
+    uint32_t pad[3];
 };
-static_assert(sizeof(Item) == 24 || sizeof(Item) == 32, "item size");
+static_assert(sizeof(Item) == 32, "item size: one 16-byte load takes begin, len and row");
 
 struct SplitRow {                      // a row processed as several chunks
     uint32_t row;
@@ -176,32 +176,96 @@ __device__ __forceinline__ uint32_t first_lane_value(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
 }
 
+__device__ __forceinline__ void wave_sync_lds()
+{
+    // orders this wavefront's LDS writes before its later LDS reads (the hardware
+    // executes a wavefront's LDS instructions in order; this stops the compiler)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 // Hands work units to a persistent wavefront by ticket (TicketMap of mh_arith.h
-// says which units a ticket stands for).  The first ticket of a wavefront is its
-// own index in the grid, later ones come from an atomic counter that starts
-// behind the grid, so a call with fewer units than resident wavefronts costs no
-// atomic at all.  All values are wavefront-uniform.
-struct UnitDispenser {
+// says which run of consecutive units a ticket stands for, 32 at most).  The first
+// ticket of a wavefront is its own index in the grid, later ones come from an atomic
+// counter that starts behind the grid, so a call with fewer units than resident
+// wavefronts costs no atomic at all.  When a run starts, its item records are fetched
+// with one coalesced load, lane i taking unit i of the run, and parked in the
+// wavefront's LDS; a unit's fields then come from there, so that within a run the next
+// unit is known without waiting on memory and its first nonzeros can be requested
+// while the current unit is still being worked on.  All values are wavefront-uniform.
+constexpr int MAX_RUN = 32;
+struct RunItems {                      // LDS of one wavefront
+    uint4 rec[MAX_RUN];                // begin (low, high word), len, row
+    uint2 meta[MAX_RUN];               // slot, function tile
+};
+struct Unit {
+    int64_t begin;
+    uint32_t len, row, slot;
+    int ftile;
+};
+struct UnitStream {
     TicketMap map;
     uint32_t grid_waves;
-    uint32_t next, end;     // units of the current ticket still to do
+    uint32_t base, next, end;          // the run [base, end) has its records in LDS; next is the first unit not yet handed out
 
-    __device__ __forceinline__ void init(uint64_t units, uint64_t single_units, uint32_t waves, uint32_t index)
+    __device__ __forceinline__ void load_run(const KArgs& a, uint32_t n_long, int lane, RunItems* lds) const
+    {
+        const uint32_t u = base + (uint32_t)lane;
+        if (lane < MAX_RUN && u < end && u < map.n_units) {
+            const uint32_t nft = (uint32_t)a.n_ftiles;
+            const uint32_t item_idx = nft == 1u ? u : u / nft;
+            const Item* p = item_idx < n_long ? a.items + item_idx : a.items + a.cap_long + (item_idx - n_long);
+            const uint4 r = *reinterpret_cast<const uint4*>(p);
+            const uint32_t slot = p->slot;
+            lds->rec[lane] = r;
+            lds->meta[lane] = uint2{slot, u - item_idx * nft};
+        }
+        wave_sync_lds();
+    }
+    __device__ __forceinline__ void read(uint32_t unit, const RunItems* lds, Unit* out) const
+    {
+        const uint4 r = lds->rec[unit - base];
+        const uint2 m = lds->meta[unit - base];
+        out->begin = (int64_t)(((uint64_t)first_lane_value(r.y) << 32) | first_lane_value(r.x));
+        out->len = first_lane_value(r.z);
+        out->row = first_lane_value(r.w);
+        out->slot = first_lane_value(m.x);
+        out->ftile = (int)first_lane_value(m.y);
+    }
+    // the first unit of this wavefront (its own index in the grid is its first ticket); false when there is none
+    __device__ __forceinline__ bool init(const KArgs& a, uint64_t units, uint64_t single_units, uint32_t waves, uint32_t index,
+                                         uint32_t n_long, int lane, RunItems* lds, Unit* out)
     {
         map = make_ticket_map(units, single_units, waves);
         grid_waves = waves;
-        map.range(index, &next, &end);          // the first ticket needs no atomic
+        map.range(index, &base, &end);
+        next = base;
+        if (base >= map.n_units) return false;
+        load_run(a, n_long, lane, lds);
+        read(next++, lds, out);
+        return true;
     }
-    // false when nothing is left; every wavefront gets there because tickets only grow
-    __device__ __forceinline__ bool take(uint32_t* counter, int lane, uint32_t* unit)
+    // the next unit, drawing a ticket and fetching its run when the current run is used up (this waits on
+    // memory); false when nothing is left, where every wavefront gets because tickets only grow
+    __device__ __forceinline__ bool advance(const KArgs& a, uint32_t n_long, int lane, RunItems* lds, Unit* out)
     {
         if (next >= end) {
             uint32_t tk = 0;
-            if (lane == 0) tk = grid_waves + atomicAdd(counter, 1u);
-            map.range(first_lane_value(tk), &next, &end);
+            if (lane == 0) tk = grid_waves + atomicAdd(&a.hdr->ticket, 1u);
+            map.range(first_lane_value(tk), &base, &end);
+            next = base;
+            if (base >= map.n_units) return false;
+            wave_sync_lds();           // the records of the old run have all been read
+            load_run(a, n_long, lane, lds);
         }
-        if (next >= map.n_units) return false;
-        *unit = next++;
+        read(next++, lds, out);
+        return true;
+    }
+    // the next unit if it belongs to the current run: no waiting beyond the LDS
+    __device__ __forceinline__ bool peek_and_take(const RunItems* lds, Unit* out)
+    {
+        if (next >= end || next >= map.n_units) return false;
+        read(next++, lds, out);
         return true;
     }
 };
@@ -266,14 +330,6 @@ __device__ __forceinline__ void issue_priority()
 {
     static_assert(P >= 0 && P <= 3, "priority");
     asm volatile("s_setprio %c0" : : "n"(P));
-}
-__device__ __forceinline__ void wave_sync_lds()
-{
-    // orders this wavefront's LDS writes before its later LDS reads (the hardware
-    // executes a wavefront's LDS instructions in order; this stops the compiler)
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 // three-operand extrema: one instruction folds two new values into the running one
 __device__ __forceinline__ uint32_t umin3(uint32_t a, uint32_t b, uint32_t c)
@@ -400,7 +456,7 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
     Item* short_items = a.items + a.cap_long;
     if (overflow) {
         atomicOr(&a.hdr->status, 4u);
-        Item it; it.begin = begin; it.len = 0; it.row = (uint32_t)row; it.slot = NO_SLOT; it.pad = 1;
+        Item it; it.begin = begin; it.len = 0; it.row = (uint32_t)row; it.slot = NO_SLOT; it.pad[0] = 1; it.pad[1] = 0; it.pad[2] = 0;
         for (uint32_t c = 0; c < n_lg && first_lg + c < a.cap_long; ++c) long_items[first_lg + c] = it;
         for (uint32_t c = 0; c < n_sh && first_sh + c < a.cap_short; ++c) short_items[first_sh + c] = it;
         if (is_split && sidx < a.cap_split) {
@@ -421,7 +477,7 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
         it.len = is_split ? (uint32_t)(rest < (int64_t)CHUNK ? rest : (int64_t)CHUNK) : (uint32_t)nnz;
         it.row = (uint32_t)row;
         it.slot = is_split ? (uint32_t)(first_part + c) : NO_SLOT;
-        it.pad = 0;
+        it.pad[0] = 0; it.pad[1] = 0; it.pad[2] = 0;
         if (it.len > LONG_ITEM) long_items[first_lg + (n_long_done++)] = it;
         else short_items[first_sh + (n_short_done++)] = it;
     }
@@ -1360,19 +1416,38 @@ __device__ __forceinline__ void Pol2U61<false>::pair(const Fn (&fn)[HASH_FPL], u
 }
 
 // ------------------------------------------------------------------ staging
-// Loads up to TILE nonzeros of [begin+off, begin+len) into 4 registers per lane
-// (element lane + 64 q), coalesced.  Slots past the end take `pad`, an element of
-// the same row: the minimum is idempotent, so duplicates change nothing.
-__device__ __forceinline__ void load_tile(const uint32_t* col, int64_t begin, uint32_t len, uint32_t off, uint32_t pad,
+// Requests the nonzeros [begin+off, begin+off+extent) of a row of `len` nonzeros
+// (off < len) into 4 registers per lane (element lane + 64 q), coalesced.  Entries
+// past the end of the row repeat its last nonzero: the minimum is idempotent, so
+// duplicates change nothing and the inner loops need no masks.  Groups of 64 entries
+// from `extent` on are not read by the caller and not loaded.
+__device__ __forceinline__ void load_tile(const uint32_t* col, int64_t begin, uint32_t len, uint32_t off, int extent,
                                           int lane, uint32_t (&r)[4])
 {
+    const uint32_t* src = col + begin;
+    const uint32_t last = len - 1u;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        uint32_t e = off + (uint32_t)lane + (uint32_t)(WAVE * q);
-        r[q] = pad;
-        if (off + (uint32_t)(WAVE * q) < len)          // wavefront-uniform: a short row issues no load for the groups it lacks
-            r[q] = e < len ? __builtin_nontemporal_load(col + begin + e) : pad;
+        if (WAVE * q < extent) {       // wavefront-uniform: a short row issues no load for the groups it lacks
+            const uint32_t e = off + (uint32_t)lane + (uint32_t)(WAVE * q);
+            r[q] = __builtin_nontemporal_load(src + (e < last ? e : last));
+        }
     }
+}
+// How the steps of the hash kernel walk a tile of in_tile nonzeros with n_slices lane slices: a
+// step takes four nonzeros per slice (two pairs); when the last step would hold at most two per
+// slice it is done as a single pair.  extent = tile entries read (repeats of the last one included).
+struct TileWalk {
+    int n_steps, odd_pair, extent;
+};
+__device__ __forceinline__ TileWalk walk_of(uint32_t in_tile, int n_slices)
+{
+    TileWalk t;
+    const int n_pairs = (int)((in_tile + 2u * n_slices - 1u) / (2u * n_slices));
+    t.n_steps = n_pairs >> 1;
+    t.odd_pair = n_pairs & 1;
+    t.extent = (t.n_steps * 4 + t.odd_pair * 2) * n_slices;
+    return t;
 }
 
 // ------------------------------------------------------------------ the hash kernel
@@ -1381,11 +1456,13 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 {
     __shared__ uint32_t s_tile[WAVES_PER_BLOCK][Pol::NW][TILE];
     __shared__ uint32_t s_mins[WAVES_PER_BLOCK][HASH_FTILE];
+    __shared__ RunItems s_items[WAVES_PER_BLOCK];
 
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform: keep it in a scalar register
     uint32_t(*tile)[TILE] = s_tile[wave];
     uint32_t* mins = s_mins[wave];
+    RunItems* run_items = &s_items[wave];
 
     const int fl_lanes = 1 << a.log2_fl;            // lanes that cover one function tile
     const int n_slices = WAVE >> a.log2_fl;         // the other lane bits take slices of the nonzeros
@@ -1401,14 +1478,18 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
     typename Pol::Fn fn[HASH_FPL];
     int cur_ftile = -1;
 
-    UnitDispenser units;
-    units.init(n_units, (uint64_t)n_long * (uint64_t)a.n_ftiles, gridDim.x * WAVES_PER_BLOCK,
-               blockIdx.x * WAVES_PER_BLOCK + wave);
-    for (;;) {
-        uint32_t ticket;
-        if (!units.take(&a.hdr->ticket, lane, &ticket)) break;
-        const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
-        const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
+    // The first nonzeros of a unit are requested before the unit starts: for the first unit
+    // right here, for later ones during the last tile of the unit before (when the next unit
+    // belongs to the same run of the work list) or after a new run has been fetched.
+    UnitStream units;
+    Unit cur;
+    uint32_t regs[4];
+    bool have = units.init(a, n_units, (uint64_t)n_long * (uint64_t)a.n_ftiles, gridDim.x * WAVES_PER_BLOCK,
+                           blockIdx.x * WAVES_PER_BLOCK + wave, n_long, lane, run_items, &cur);
+    if (have && cur.len > 0)
+        load_tile(a.col_idx, cur.begin, cur.len, 0, walk_of(cur.len < (uint32_t)TILE ? cur.len : (uint32_t)TILE, n_slices).extent, lane, regs);
+    while (have) {
+        const int ftile = cur.ftile;
         const int j_base = ftile * a.ftile_size + fl * NF;
         if (ftile != cur_ftile) {
             const uint64_t* coeffs = static_cast<const uint64_t*>(a.params);
@@ -1420,9 +1501,11 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             }
             cur_ftile = ftile;
         }
-        const Item it = item_idx < n_long ? a.items[item_idx] : a.items[a.cap_long + (item_idx - n_long)];
-        const int64_t begin = it.begin;
-        const uint32_t len = it.len;
+        const int64_t begin = cur.begin;
+        const uint32_t len = cur.len;
+        const uint32_t unit_row = cur.row, unit_slot = cur.slot;
+        Unit nxt;
+        bool have_next = false;        // the next unit is known and its first tile is on its way
 
         uint32_t m[HASH_ACC];
 #pragma unroll
@@ -1433,16 +1516,10 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
         }
 
         if (len > 0) {
-            uint32_t pad = a.col_idx[begin];
-            uint32_t regs[4];
-            load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
             for (uint32_t off = 0; off < len; off += TILE) {
                 const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
-                // a step takes four nonzeros per slice (two pairs); when the last step would hold at most
-                // two per slice it is done as a single pair
-                const int n_pairs = (int)((in_tile + 2u * n_slices - 1u) / (2u * n_slices));
-                const int n_steps = n_pairs >> 1;
-                const int extent = (n_steps * 4 + (n_pairs & 1) * 2) * n_slices;      // tile entries read below (pad included)
+                const TileWalk walk = walk_of(in_tile, n_slices);
+                const int n_steps = walk.n_steps, extent = walk.extent;
                 // stage: pre-compute what depends on t alone, one nonzero per lane and register
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
@@ -1458,7 +1535,16 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                     for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
                 }
                 wave_sync_lds();
-                if (off + TILE < len) load_tile(a.col_idx, begin, len, off + TILE, pad, lane, regs);
+                if (off + TILE < len) {
+                    const uint32_t rest = len - off - TILE;
+                    load_tile(a.col_idx, begin, len, off + TILE, walk_of(rest < (uint32_t)TILE ? rest : (uint32_t)TILE, n_slices).extent,
+                              lane, regs);
+                } else {               // last tile: the registers are free for the first tile of the next unit
+                    have_next = units.peek_and_take(run_items, &nxt);
+                    if (have_next && nxt.len > 0)
+                        load_tile(a.col_idx, nxt.begin, nxt.len, 0,
+                                  walk_of(nxt.len < (uint32_t)TILE ? nxt.len : (uint32_t)TILE, n_slices).extent, lane, regs);
+                }
 
                 for (int s = 0; s < n_steps; ++s) {
                     const int e = 4 * (s * n_slices + slice);
@@ -1471,7 +1557,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                     Pol::template pair<NF>(fn, m, w[0], w[1], md, a.D);
                     Pol::template pair<NF>(fn, m, w[2], w[3], md, a.D);
                 }
-                if (n_pairs & 1) {
+                if (walk.odd_pair) {
                     const int e = 4 * n_steps * n_slices + 2 * slice;     // the slices share what is left, two nonzeros each
                     uint32_t w[2][Pol::NW];
 #pragma unroll
@@ -1581,13 +1667,13 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             }
         }
         const int nf_tile = a.k - ftile * a.ftile_size < a.ftile_size ? a.k - ftile * a.ftile_size : a.ftile_size;
-        if (it.slot == NO_SLOT) {
+        if (unit_slot == NO_SLOT) {
             bool stored = false;
             if constexpr (NF == HASH_FPL) {
                 if (a.lane_pack) {
-                    lane_pack_store(a, m, it.row, j_base, slice == 0);
+                    lane_pack_store(a, m, unit_row, j_base, slice == 0);
                     if (ftile == a.n_ftiles - 1) {     // pad bytes up to the row pitch are zero
-                        uint8_t* dst = a.out + (int64_t)it.row * a.out_stride;
+                        uint8_t* dst = a.out + (int64_t)unit_row * a.out_stride;
                         for (int64_t q = a.sig_bytes + lane; q < a.out_stride; q += WAVE) dst[q] = 0;
                     }
                     stored = true;
@@ -1599,14 +1685,23 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                     for (int r = 0; r < NF; ++r) mins[fl * NF + r] = m[r];
                 }
                 wave_sync_lds();
-                wave_pack_store(a, mins, it.row, ftile * a.ftile_size, nf_tile, ftile == a.n_ftiles - 1, lane);
+                wave_pack_store(a, mins, unit_row, ftile * a.ftile_size, nf_tile, ftile == a.n_ftiles - 1, lane);
                 wave_sync_lds();
             }
         } else if (slice == 0) {
-            uint32_t* part = a.partials + (size_t)it.slot * (size_t)a.k;
+            uint32_t* part = a.partials + (size_t)unit_slot * (size_t)a.k;
 #pragma unroll
             for (int r = 0; r < NF; ++r)
                 if (j_base + r < a.k) part[j_base + r] = m[r];
+        }
+        // on to the next unit: already under way, or drawn now (which waits for the ticket and the run's records)
+        if (have_next) {
+            cur = nxt;
+        } else {
+            have = units.advance(a, n_long, lane, run_items, &cur);
+            if (have && cur.len > 0)
+                load_tile(a.col_idx, cur.begin, cur.len, 0, walk_of(cur.len < (uint32_t)TILE ? cur.len : (uint32_t)TILE, n_slices).extent,
+                          lane, regs);
         }
     }
 }
@@ -1622,10 +1717,12 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
 {
     __shared__ uint32_t s_tile[WAVES_PER_BLOCK][TILE];
     __shared__ uint32_t s_mins[WAVES_PER_BLOCK][PERM_FTILE];
+    __shared__ RunItems s_items[WAVES_PER_BLOCK];
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     uint32_t* tile = s_tile[wave];
     uint32_t* mins = s_mins[wave];
+    RunItems* run_items = &s_items[wave];
     const uint32_t* table = static_cast<const uint32_t*>(a.params);
 
     const uint32_t n_long = a.hdr->n_long < a.cap_long ? a.hdr->n_long : (uint32_t)a.cap_long;
@@ -1633,17 +1730,21 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
     const uint64_t n_units = ((uint64_t)n_long + n_short) * (uint64_t)a.n_ftiles;
     constexpr int U = 8;               // nonzeros in flight per lane
 
-    UnitDispenser units;
-    units.init(n_units, (uint64_t)n_long * (uint64_t)a.n_ftiles, gridDim.x * WAVES_PER_BLOCK,
-               blockIdx.x * WAVES_PER_BLOCK + wave);
-    for (;;) {
-        uint32_t ticket;
-        if (!units.take(&a.hdr->ticket, lane, &ticket)) break;
-        const uint32_t item_idx = ticket / (uint32_t)a.n_ftiles;
-        const int ftile = (int)(ticket - item_idx * (uint32_t)a.n_ftiles);
-        const Item it = item_idx < n_long ? a.items[item_idx] : a.items[a.cap_long + (item_idx - n_long)];
-        const int64_t begin = it.begin;
-        const uint32_t len = it.len;
+    // the steps read whole groups of U entries: what a tile of n nonzeros needs staged
+    auto extent_of = [](uint32_t n) { return (int)(((n < (uint32_t)TILE ? n : (uint32_t)TILE) + U - 1) / U * U); };
+    UnitStream units;
+    Unit cur;
+    uint32_t regs[4];
+    bool have = units.init(a, n_units, (uint64_t)n_long * (uint64_t)a.n_ftiles, gridDim.x * WAVES_PER_BLOCK,
+                           blockIdx.x * WAVES_PER_BLOCK + wave, n_long, lane, run_items, &cur);
+    if (have && cur.len > 0) load_tile(a.col_idx, cur.begin, cur.len, 0, extent_of(cur.len), lane, regs);
+    while (have) {
+        const int ftile = cur.ftile;
+        const int64_t begin = cur.begin;
+        const uint32_t len = cur.len;
+        const uint32_t unit_row = cur.row, unit_slot = cur.slot;
+        Unit nxt;
+        bool have_next = false;
         const int j0 = ftile * PERM_FTILE;
         const int nf_tile = a.k - j0 < PERM_FTILE ? a.k - j0 : PERM_FTILE;
 
@@ -1660,12 +1761,11 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
         for (int r = 0; r < PERM_FPL; ++r) m[r] = EMPTY_MIN;
 
         if (len > 0) {
-            uint32_t pad = a.col_idx[begin];
-            uint32_t regs[4];
-            load_tile(a.col_idx, begin, len, 0, pad, lane, regs);
             for (uint32_t off = 0; off < len; off += TILE) {
+                const int extent = extent_of(len - off);
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
+                    if (WAVE * q >= extent) break;               // wavefront-uniform: never read, not staged
                     uint32_t t = regs[q];
                     if (a.validate && (uint64_t)t >= a.D) {
                         atomicOr(&a.hdr->status, 2u);
@@ -1674,7 +1774,12 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
                     tile[lane + WAVE * q] = t;
                 }
                 wave_sync_lds();
-                if (off + TILE < len) load_tile(a.col_idx, begin, len, off + TILE, pad, lane, regs);
+                if (off + TILE < len) {
+                    load_tile(a.col_idx, begin, len, off + TILE, extent_of(len - off - TILE), lane, regs);
+                } else {               // last tile: request the first tile of the next unit of this run
+                    have_next = units.peek_and_take(run_items, &nxt);
+                    if (have_next && nxt.len > 0) load_tile(a.col_idx, nxt.begin, nxt.len, 0, extent_of(nxt.len), lane, regs);
+                }
                 const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
                 const int n_steps = (int)((in_tile + U - 1) / U);
                 for (int s = 0; s < n_steps; ++s) {
@@ -1720,17 +1825,23 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
                 wave_sync_lds();
             }
         }
-        if (it.slot == NO_SLOT) {
+        if (unit_slot == NO_SLOT) {
 #pragma unroll
             for (int r = 0; r < PERM_FPL; ++r) mins[jl[r]] = m[r];
             wave_sync_lds();
-            wave_pack_store(a, mins, it.row, j0, nf_tile, ftile == a.n_ftiles - 1, lane);
+            wave_pack_store(a, mins, unit_row, j0, nf_tile, ftile == a.n_ftiles - 1, lane);
             wave_sync_lds();
         } else {
-            uint32_t* part = a.partials + (size_t)it.slot * (size_t)a.k + j0;
+            uint32_t* part = a.partials + (size_t)unit_slot * (size_t)a.k + j0;
 #pragma unroll
             for (int r = 0; r < PERM_FPL; ++r)
                 if (ok[r]) part[jl[r]] = m[r];
+        }
+        if (have_next) {
+            cur = nxt;
+        } else {
+            have = units.advance(a, n_long, lane, run_items, &cur);
+            if (have && cur.len > 0) load_tile(a.col_idx, cur.begin, cur.len, 0, extent_of(cur.len), lane, regs);
         }
     }
 }
