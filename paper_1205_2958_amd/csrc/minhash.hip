@@ -351,7 +351,7 @@ __device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c)
 // partial vectors of the resulting chunks fit the workspace.  Large batches get
 // MAX_CHUNK; a batch of a few hundred rows gets its long rows cut finely enough to
 // occupy the whole GPU instead of waiting for one wavefront per row.
-__global__ void mh_reset_kernel(KArgs a)
+__device__ __forceinline__ void reset_header(const KArgs& a)      // threads 0..63 of one block
 {
     uint32_t* words = reinterpret_cast<uint32_t*>(a.hdr);
     if (threadIdx.x < 64 && threadIdx.x != offsetof(WorkHeader, chunk) / 4) words[threadIdx.x] = 0;
@@ -370,6 +370,7 @@ __global__ void mh_reset_kernel(KArgs a)
         a.hdr->chunk = chunk;
     }
 }
+__global__ void mh_reset_kernel(KArgs a) { reset_header(a); }
 
 // One thread per row.  Prefix sums over the wavefront and then over the block's
 // wavefronts make one atomic per block of 1024 rows and counter (one per
@@ -386,6 +387,11 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = threadIdx.x >> 6;
     const int64_t row = (int64_t)blockIdx.x * BIN_BLOCK + threadIdx.x;
+    if (gridDim.x == 1) {              // a batch of one block clears the header itself: one launch fewer for small batches
+        reset_header(a);
+        __threadfence();
+        __syncthreads();
+    }
     uint32_t CHUNK = a.hdr->chunk;
     if (CHUNK < MIN_CHUNK || CHUNK > MAX_CHUNK) CHUNK = MAX_CHUNK;
     uint32_t n_it = 0, is_split = 0;
@@ -1450,6 +1456,36 @@ __device__ __forceinline__ TileWalk walk_of(uint32_t in_tile, int n_slices)
     return t;
 }
 
+// Minimum over lanes that are a power of two apart, without the LDS: the upper half of the
+// wavefront comes down with a lane swap, the upper 16 of 32 lanes with a swizzle, smaller
+// distances with data-parallel row shifts.  After min_from_above<D> lane i (i mod 2D < D) holds
+// the minimum of its own value and that of lane i + D; the other lanes hold nothing of use.
+template <int D>
+__device__ __forceinline__ uint32_t min_from_above(uint32_t v)
+{
+    uint32_t o;
+    if constexpr (D == 32) {
+        o = __builtin_amdgcn_permlane32_swap(v, v, false, false)[1];      // lanes 0..31 receive lanes 32..63
+    } else if constexpr (D == 16) {
+        o = (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F);        // swap neighbouring groups of 16 lanes
+    } else {
+        static_assert(D == 8 || D == 4 || D == 2 || D == 1, "distance");
+        o = (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x100 + D, 0xf, 0xf, false);   // row_shl:D, lanes without a source keep v
+    }
+    return o < v ? o : v;
+}
+// the minimum of v over all 64 lanes, in every lane
+__device__ __forceinline__ uint32_t wave_min(uint32_t v)
+{
+    v = min_from_above<32>(v);
+    v = min_from_above<16>(v);
+    v = min_from_above<8>(v);
+    v = min_from_above<4>(v);
+    v = min_from_above<2>(v);
+    v = min_from_above<1>(v);
+    return first_lane_value(v);
+}
+
 // ------------------------------------------------------------------ the hash kernel
 template <class Pol, int NF>
 __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_WAVES, 8))) void mh_hash_kernel(KArgs a)
@@ -1642,10 +1678,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                             const uint32_t h = Pol::exact_hash(c, t, a.md, a.D);
                             best = h < best ? h : best;
                         }
-                        for (int d = 1; d < WAVE; d <<= 1) {
-                            const uint32_t o = (uint32_t)__shfl_xor((int)best, d, WAVE);
-                            best = o < best ? o : best;
-                        }
+                        best = wave_min(best);
                         if (lane == owner) {
 #pragma unroll
                             for (int q = 0; q < NF; ++q)
@@ -1658,13 +1691,30 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 #pragma unroll
             for (int r = 0; r < NF; ++r) m[r] = EMPTY_MIN;
         }
-        // merge the slices of nonzeros (lanes that share fl)
-        for (int d = fl_lanes; d < WAVE; d <<= 1) {
+        // merge the slices of nonzeros (lanes that share fl): the values come down to slice 0, which stores them
+        if (n_slices >= 2) {
 #pragma unroll
-            for (int r = 0; r < NF; ++r) {
-                uint32_t o = (uint32_t)__shfl_xor((int)m[r], d, WAVE);
-                m[r] = o < m[r] ? o : m[r];
-            }
+            for (int r = 0; r < NF; ++r) m[r] = min_from_above<32>(m[r]);
+        }
+        if (n_slices >= 4) {
+#pragma unroll
+            for (int r = 0; r < NF; ++r) m[r] = min_from_above<16>(m[r]);
+        }
+        if (n_slices >= 8) {
+#pragma unroll
+            for (int r = 0; r < NF; ++r) m[r] = min_from_above<8>(m[r]);
+        }
+        if (n_slices >= 16) {
+#pragma unroll
+            for (int r = 0; r < NF; ++r) m[r] = min_from_above<4>(m[r]);
+        }
+        if (n_slices >= 32) {
+#pragma unroll
+            for (int r = 0; r < NF; ++r) m[r] = min_from_above<2>(m[r]);
+        }
+        if (n_slices >= 64) {
+#pragma unroll
+            for (int r = 0; r < NF; ++r) m[r] = min_from_above<1>(m[r]);
         }
         const int nf_tile = a.k - ftile * a.ftile_size < a.ftile_size ? a.k - ftile * a.ftile_size : a.ftile_size;
         if (unit_slot == NO_SLOT) {
@@ -2139,8 +2189,8 @@ int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream
         if (e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e, "hipEventCreate"); }
     }
     a.target_items = (uint32_t)l.cus * 24u * 2u;   // two items per wavefront of a fully occupied launch
-    hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, l.s, a);
     const int bin_blocks = (int)((a.n_rows + BIN_BLOCK - 1) / BIN_BLOCK);
+    if (bin_blocks > 1) hipLaunchKernelGGL(mh_reset_kernel, dim3(1), dim3(64), 0, l.s, a);   // one block of rows resets for itself
     hipLaunchKernelGGL(mh_bin_rows_kernel, dim3(bin_blocks), dim3(BIN_BLOCK), 0, l.s, a);
 
     hipError_t r0 = profiled ? hipEventRecord(e0, l.s) : hipSuccess;
