@@ -279,3 +279,88 @@ int minhash_resemblance_oracle(const uint32_t *counts, const int64_t *f1, const 
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------ packed index rows
+ * Not from the paper: the GPU library can take sorted rows over the host link as
+ * tiles of differences (its answer to Section 3.6's finding that moving the data
+ * dominates once hashing is fast).  The checker holds the plain definition of
+ * that form, one bit at a time:
+ *
+ *   a row of n non-decreasing indices is cut into tiles of 256 (the last one
+ *   shorter); a tile is one 32-bit word holding its first index, then the
+ *   differences between neighbours inside the tile, w bits each, written
+ *   LSB-first into 32-bit words, the last word padded with zeros; w is the bit
+ *   length of the largest such difference of the row; word_ptr[r] is where row
+ *   r's words start.
+ *
+ * Returns 0, -1 for bad arguments, -9 for a row that is not sorted, -6 when
+ * `capacity` words do not suffice.
+ */
+int minhash_pack_indices_oracle(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows, uint32_t *width,
+                                int64_t *word_ptr, uint32_t *words, int64_t capacity)
+{
+    if (!row_ptr || !word_ptr || n_rows < 0) return -1;
+    int64_t at = 0;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        const uint32_t *row = col_idx + row_ptr[r];
+        const int64_t n = row_ptr[r + 1] - row_ptr[r];
+        if (n < 0) return -1;
+        /* the widest difference between neighbours that share a tile */
+        uint32_t widest = 0;
+        for (int64_t i = 1; i < n; ++i) {
+            if (row[i] < row[i - 1]) return -9;
+            if (i % 256 != 0 && row[i] - row[i - 1] > widest) widest = row[i] - row[i - 1];
+        }
+        uint32_t w = 0;
+        while (w < 32 && (widest >> w) != 0) ++w;
+        width[r] = w;
+        word_ptr[r] = at;
+        for (int64_t first = 0; first < n; first += 256) {
+            const int64_t m = n - first < 256 ? n - first : 256;
+            const int64_t n_words = 1 + ((m - 1) * (int64_t)w + 31) / 32;
+            if (at + n_words > capacity) return -6;
+            for (int64_t j = 0; j < n_words; ++j) words[at + j] = 0;
+            words[at] = row[first];
+            int64_t bit = 0;                         /* position in the bit string that starts at word 1 */
+            for (int64_t i = 1; i < m; ++i) {
+                const uint32_t d = row[first + i] - row[first + i - 1];
+                for (uint32_t q = 0; q < w; ++q, ++bit)
+                    if ((d >> q) & 1u) words[at + 1 + bit / 32] |= 1u << (bit % 32);
+            }
+            at += n_words;
+        }
+    }
+    word_ptr[n_rows] = at;
+    return 0;
+}
+
+/* The inverse: col_idx from the tiles.  Returns -6 if an offset leaves the `n_words` words given. */
+int minhash_unpack_indices_oracle(const int64_t *row_ptr, const uint32_t *width, const int64_t *word_ptr,
+                                  const uint32_t *words, int64_t n_words, int64_t n_rows, uint32_t *col_idx)
+{
+    if (!row_ptr || !word_ptr || n_rows < 0) return -1;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        uint32_t *row = col_idx + row_ptr[r];
+        const int64_t n = row_ptr[r + 1] - row_ptr[r];
+        const uint32_t w = width[r];
+        if (n < 0 || w > 32) return -1;
+        int64_t at = word_ptr[r];
+        for (int64_t first = 0; first < n; first += 256) {
+            const int64_t m = n - first < 256 ? n - first : 256;
+            const int64_t tile_words = 1 + ((m - 1) * (int64_t)w + 31) / 32;
+            if (at < 0 || at + tile_words > n_words) return -6;
+            uint32_t value = words[at];
+            row[first] = value;
+            int64_t bit = 0;
+            for (int64_t i = 1; i < m; ++i) {
+                uint32_t d = 0;
+                for (uint32_t q = 0; q < w; ++q, ++bit)
+                    if ((words[at + 1 + bit / 32] >> (bit % 32)) & 1u) d |= 1u << q;
+                value += d;
+                row[first + i] = value;
+            }
+            at += tile_words;
+        }
+    }
+    return 0;
+}

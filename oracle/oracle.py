@@ -45,6 +45,10 @@ def _bind(path: str):
     lib.minhash_match_counts_oracle.restype = ctypes.c_int
     lib.minhash_resemblance_oracle.argtypes = [vp, vp, vp, i64, u64, i32, i32, vp]
     lib.minhash_resemblance_oracle.restype = ctypes.c_int
+    lib.minhash_pack_indices_oracle.argtypes = [vp, vp, i64, vp, vp, vp, i64]
+    lib.minhash_pack_indices_oracle.restype = ctypes.c_int
+    lib.minhash_unpack_indices_oracle.argtypes = [vp, vp, vp, vp, i64, i64, vp]
+    lib.minhash_unpack_indices_oracle.restype = ctypes.c_int
     return lib
 
 
@@ -145,6 +149,36 @@ class Oracle:
         return out
 
 
+    def pack_indices(self, row_ptr, col_idx):
+        """(width uint32 [n], word_ptr int64 [n+1], words uint32 [word_ptr[n]]): rows as tiles of differences."""
+        row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+        col_idx = np.ascontiguousarray(col_idx, dtype=np.uint32)
+        n = row_ptr.shape[0] - 1
+        width = np.zeros(max(n, 1), dtype=np.uint32)
+        word_ptr = np.zeros(n + 1, dtype=np.int64)
+        cap = int(row_ptr[-1] - row_ptr[0]) + 1
+        words = np.full(cap, 0xAAAAAAAA, dtype=np.uint32)
+        rc = self._lib.minhash_pack_indices_oracle(_ptr(row_ptr), _ptr(col_idx), n, _ptr(width), _ptr(word_ptr),
+                                                   _ptr(words), cap)
+        if rc != 0:
+            raise ValueError("oracle rejected the arguments: %d" % rc)
+        return width[:n], word_ptr, words[: int(word_ptr[-1])].copy()
+
+    def unpack_indices(self, row_ptr, width, word_ptr, words) -> np.ndarray:
+        """uint32 [nnz]: the index array the tiles stand for."""
+        row_ptr = np.ascontiguousarray(row_ptr, dtype=np.int64)
+        width = np.ascontiguousarray(width, dtype=np.uint32)
+        word_ptr = np.ascontiguousarray(word_ptr, dtype=np.int64)
+        words = np.ascontiguousarray(words, dtype=np.uint32)
+        n = row_ptr.shape[0] - 1
+        out = np.full(max(int(row_ptr[-1]), 1), 0xAAAAAAAA, dtype=np.uint32)
+        rc = self._lib.minhash_unpack_indices_oracle(_ptr(row_ptr), _ptr(width), _ptr(word_ptr), _ptr(words),
+                                                     words.shape[0], n, _ptr(out))
+        if rc != 0:
+            raise ValueError("oracle rejected the arguments: %d" % rc)
+        return out[: int(row_ptr[-1])]
+
+
 _default = None
 
 
@@ -177,6 +211,14 @@ def match_counts(sig, k, b, pairs) -> np.ndarray:
 
 def resemblance(counts, f1, f2, D, k, b) -> np.ndarray:
     return default().resemblance(counts, f1, f2, D, k, b)
+
+
+def pack_indices(row_ptr, col_idx):
+    return default().pack_indices(row_ptr, col_idx)
+
+
+def unpack_indices(row_ptr, width, word_ptr, words) -> np.ndarray:
+    return default().unpack_indices(row_ptr, width, word_ptr, words)
 
 
 def unpack(packed: np.ndarray, k: int, b: int) -> np.ndarray:

@@ -508,6 +508,93 @@ def pin_estimator_is_unbiased_for_unequal_set_sizes(o, n_pairs=150, k=400):
         assert abs(mean - f1 / f2) <= tol, (b, mean, tol)
 
 
+# ---------------------------------------------------------------- packed index rows
+def _bits_of_words(words):
+    """The little-endian bit string of a word array, as a Python int (bit q of word j is bit 32 j + q)."""
+    v = 0
+    for j, x in enumerate(words):
+        v |= int(x) << (32 * j)
+    return v
+
+
+def pin_packed_rows_by_hand(o):
+    """The tile form of a row, written out by hand: first index as it is, then the differences
+    inside the tile at the bit length of the widest one, LSB-first."""
+    # differences 2, 0, 13: widest 13 -> 4 bits; fields 0x2, 0x0, 0xD from bit 0 of the second word
+    width, word_ptr, words = o.pack_indices(np.array([0, 4]), np.array([5, 7, 7, 20], dtype=np.uint32))
+    assert width.tolist() == [4] and word_ptr.tolist() == [0, 2] and words.tolist() == [5, 0xD02]
+    # two rows; the second has one index (no differences: width 0, one word)
+    width, word_ptr, words = o.pack_indices(np.array([0, 3, 4]), np.array([1, 2, 4, 9], dtype=np.uint32))
+    assert width.tolist() == [2, 0] and word_ptr.tolist() == [0, 2, 3] and words.tolist() == [1, 0b1001, 9]
+    # an empty row takes no words; equal indices give width 0
+    width, word_ptr, words = o.pack_indices(np.array([0, 0, 3]), np.array([6, 6, 6], dtype=np.uint32))
+    assert width.tolist() == [0, 0] and word_ptr.tolist() == [0, 0, 1] and words.tolist() == [6]
+    # full width: difference 2^32 - 1
+    width, word_ptr, words = o.pack_indices(np.array([0, 2]), np.array([0, 0xFFFFFFFF], dtype=np.uint32))
+    assert width.tolist() == [32] and words.tolist() == [0, 0xFFFFFFFF]
+    # 11 fields of 3 bits straddle the first word boundary: 33 bits -> two words after the first index
+    idx = np.cumsum(np.array([10, 7, 1, 2, 3, 4, 5, 6, 7, 0, 1, 5], dtype=np.uint32)).astype(np.uint32)
+    width, word_ptr, words = o.pack_indices(np.array([0, 12]), idx)
+    assert width.tolist() == [3] and word_ptr.tolist() == [0, 3] and int(words[0]) == 10
+    want = 0
+    for i, d in enumerate([7, 1, 2, 3, 4, 5, 6, 7, 0, 1, 5]):
+        want |= d << (3 * i)
+    assert _bits_of_words(words[1:]) == want
+    assert o.unpack_indices(np.array([0, 12]), width, word_ptr, words).tolist() == idx.tolist()
+
+
+def pin_packed_rows_tiles_are_independent(o):
+    """A row of 600 indices is three tiles (256, 256, 88).  The jump between two tiles is stored
+    nowhere (each tile starts with its first index as it is) and does not widen the fields; every
+    tile can be read without the others."""
+    steps = np.ones(600, dtype=np.int64)
+    steps[0] = 1000
+    steps[256] = 5_000_000          # between tile 0 and tile 1: not a difference inside a tile
+    steps[300] = 9                  # the widest difference inside a tile: 4 bits
+    idx = np.cumsum(steps).astype(np.uint32)
+    rp = np.array([0, 600])
+    width, word_ptr, words = o.pack_indices(rp, idx)
+    assert width.tolist() == [4]
+    per_full = 1 + (255 * 4 + 31) // 32
+    assert word_ptr.tolist() == [0, 2 * per_full + 1 + (87 * 4 + 31) // 32]
+    for t, first in enumerate((0, 256, 512)):
+        assert int(words[t * per_full]) == int(idx[first])
+    # reading tile 1 alone, by the definition: first index plus running sum of 4-bit fields
+    bits = _bits_of_words(words[per_full + 1: 2 * per_full])
+    got = [int(words[per_full])]
+    for i in range(255):
+        got.append(got[-1] + ((bits >> (4 * i)) & 15))
+    assert got == idx[256:512].tolist()
+    assert o.unpack_indices(rp, width, word_ptr, words).tolist() == idx.tolist()
+
+
+def pin_packed_rows_round_trip(o):
+    """Unpacking what was packed gives the rows back, for rows of every length around the tile size
+    and gaps of every magnitude; a tile never takes more words than it has indices."""
+    rng = np.random.Generator(np.random.PCG64(515))
+    lens = [0, 1, 2, 3, 255, 256, 257, 511, 512, 513, 1000, 0, 5, 2049]
+    rows = []
+    for n in lens:
+        top = int(rng.choice([4, 1 << 8, 1 << 16, 1 << 24, (1 << 32) - 1]))
+        gaps = rng.integers(0, max(top // max(n, 1), 1) + 1, size=n, dtype=np.uint64)
+        rows.append(np.minimum(np.cumsum(gaps), (1 << 32) - 1).astype(np.uint32))
+    rp = W.row_ptr_from_nnz(np.array(lens, dtype=np.int64))
+    col = np.concatenate(rows) if rows else np.zeros(0, np.uint32)
+    width, word_ptr, words = o.pack_indices(rp, col)
+    assert int(word_ptr[-1]) == words.shape[0] <= col.shape[0]
+    assert np.all(np.diff(word_ptr) >= 0) and np.all(width <= 32)
+    for r, n in enumerate(lens):
+        assert (word_ptr[r + 1] - word_ptr[r] == 0) == (n == 0)
+    assert np.array_equal(o.unpack_indices(rp, width, word_ptr, words), col)
+    # a row that is not sorted is refused
+    try:
+        o.pack_indices(np.array([0, 3]), np.array([5, 4, 6], dtype=np.uint32))
+    except ValueError:
+        pass
+    else:
+        raise AssertionError("an unsorted row was packed")
+
+
 FAST_PINS = [
     pin_explicit_permutations_all_subsets,
     pin_explicit_permutations_random_sets,
@@ -531,6 +618,9 @@ FAST_PINS = [
     pin_expansion_has_k_ones_and_inner_product_counts_matches,
     pin_estimator_closed_forms,
     pin_estimator_is_unbiased_for_unequal_set_sizes,
+    pin_packed_rows_by_hand,
+    pin_packed_rows_tiles_are_independent,
+    pin_packed_rows_round_trip,
 ]
 STAT_PINS = [pin_collision_probability_permutations, pin_collision_probability_hashes]
 ALL_PINS = FAST_PINS + STAT_PINS

@@ -57,15 +57,16 @@ def test_issue_slots_follow_from_the_mixes():
 
 
 def test_oracle_pool_deals_rows_to_shards_and_puts_them_back_in_order():
-    """The bench's worker pool only deals rows out and collects them: its result must be what
+    """The worker pool of bench.py and the GPU tests only deals rows out and collects them: its result must be what
     one call of the oracle on the whole sample gives, for a hash family and for the permutation
     family (where every shard gets the table rows of its own nonzeros, renumbered)."""
     import numpy as np
     from oracle import oracle
 
-    b = _bench_module()
-    W = b.W
-    pool = b.OraclePool(3)
+    from oracle.pool import OraclePool
+    from paper_1205_2958_amd import workloads as W
+
+    pool = OraclePool(3)
     try:
         nnz = np.array([5, 0, 900, 17, 1, 300, 64, 0, 2], dtype=np.int64)
         D, k = 1 << 12, 24

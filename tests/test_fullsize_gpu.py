@@ -16,25 +16,12 @@ DEV = "cuda:0"
 SPLIT = 8192          # rows longer than this are processed in chunks and merged
 
 
-def _sample_rows(nnz, n_random, seed, eval_budget, k):
-    order = np.argsort(nnz, kind="stable")
-    picks = list(order[:3]) + list(order[-2:])
-    near = np.argsort(np.abs(nnz - SPLIT), kind="stable")[:4]          # both sides of the split point
-    picks += list(near)
-    above = np.where(nnz > SPLIT)[0]
-    if above.size:
-        picks += list(above[:2])
-    rng = np.random.Generator(np.random.PCG64(seed))
-    picks += list(rng.integers(0, len(nnz), size=n_random))
-    picks += [0, len(nnz) - 1]
-    out, spent = [], 0.0
-    for r in dict.fromkeys(int(p) for p in picks):
-        cost = float(nnz[r]) * k
-        if out and spent + cost > eval_budget:
-            continue
-        out.append(r)
-        spent += cost
-    return out
+def _sample_rows(nnz, seed, eval_budget, k, heavy_from=None):
+    """The rows the oracle looks at: W.stratified_rows (first, last, shortest, longest row, the
+    rows next to 1, 2, 4, ... times the split point, optionally the heaviest rows, then rows
+    drawn in turn from the ten deciles of the length distribution until the budget is spent)."""
+    rows, cover = W.stratified_rows(nnz, k, eval_budget, seed=seed, split=SPLIT, heavy_from=heavy_from)
+    return rows, cover
 
 
 def _run_workload(name, batch=0):
@@ -57,36 +44,42 @@ def _run_workload(name, batch=0):
     return w, nnz, rp_np, seed, col, params, params_np, out
 
 
-def _check_rows(w, nnz, rp_np, seed, col, params, params_np, out, rows):
-    for r in rows:
-        lo, hi = int(rp_np[r]), int(rp_np[r + 1])
-        idx = col[lo:hi].cpu().numpy().view(np.uint32)
-        regenerated = W.csr_indices_np(nnz[r:r + 1], w.D, seed, row_offset=r)
-        assert np.array_equal(idx, regenerated), "generators disagree on row %d" % r
-        one_rp = np.array([0, hi - lo], dtype=np.int64)
-        if w.family == W.FAMILY_PERM:
-            # only the table rows this set touches travel to the host: table[t] for t in the set,
-            # re-indexed 0..nnz-1 (the oracle just reads table[t][j])
-            sub = params[col[lo:hi].long()].cpu().numpy().view(np.uint32)
-            want = oracle.signatures(one_rp, np.arange(hi - lo, dtype=np.uint32), max(hi - lo, 1), w.k, w.b, w.family, sub)
-        else:
-            want = oracle.signatures(one_rp, idx, w.D, w.k, w.b, w.family, params_np)
-        got = out[r].cpu().numpy()
-        assert np.array_equal(got, want[0]), "row %d (nnz %d) differs from the oracle" % (r, hi - lo)
+def _check_rows(pool, w, nnz, rp_np, seed, col, params, params_np, out, rows, D=None):
+    """Signatures of `rows` from the device output against the oracle (rows dealt to the worker
+    processes).  The rows' indices come from the device buffer; each is also generated again with
+    the NumPy generator, which must give the same indices (unless D folds them)."""
+    rows = np.asarray(rows, dtype=np.int64)
+    take = torch.from_numpy(np.concatenate([np.arange(rp_np[r], rp_np[r + 1]) for r in rows])).to(DEV)
+    idx = col[take].cpu().numpy().view(np.uint32)
+    s_rp = W.row_ptr_from_nnz(nnz[rows])
+    if D is None:
+        D = w.D
+        assert np.array_equal(idx, W.csr_indices_np(nnz[rows], w.D, seed, rows=rows)), "generators disagree"
+    if w.family == W.FAMILY_PERM:
+        # only the table rows these sets touch travel to the host: table[t] for every nonzero, in CSR order
+        table_rows = params[col[take].long()].cpu().numpy().view(np.uint32)
+        want, _, _ = pool.signatures(s_rp, idx, D, w.k, w.b, w.family, None, table_rows=table_rows)
+    else:
+        want, _, _ = pool.signatures(s_rp, idx, D, w.k, w.b, w.family, params_np)
+    got = out[torch.from_numpy(rows).to(DEV)].cpu().numpy()
+    if not np.array_equal(got, want):
+        bad = np.flatnonzero((got != want).any(axis=1))
+        raise AssertionError("%d of %d sampled rows differ from the oracle, first: row %d (nnz %d)"
+                             % (len(bad), len(rows), rows[bad[0]], nnz[rows[bad[0]]]))
 
 
-@pytest.mark.parametrize("name,n_random,budget", [
-    ("large_2u", 24, 3.0e8),
-    ("large_4u", 16, 2.0e8),
-    ("perm_table", 16, 1.5e8),
-    ("large_2u_ms32", 24, 3.0e8),
-    ("short_rows_2u", 200, 3.0e8),
+@pytest.mark.parametrize("name,budget", [
+    ("large_2u", 1.5e10),
+    ("large_4u", 6.0e9),
+    ("perm_table", 1.2e8),          # every sampled nonzero brings an 800-byte table row to the host
+    ("large_2u_ms32", 6.0e9),
+    ("short_rows_2u", 3.0e9),
 ])
-def test_large_workloads_sampled_rows(name, n_random, budget):
+def test_large_workloads_sampled_rows(name, budget, oracle_pool):
     w, nnz, rp_np, seed, col, params, params_np, out = _run_workload(name)
-    rows = _sample_rows(nnz, n_random, seed=17, eval_budget=budget, k=w.k)
-    assert len(rows) >= 8
-    _check_rows(w, nnz, rp_np, seed, col, params, params_np, out, rows)
+    rows, cover = _sample_rows(nnz, seed=17, eval_budget=budget, k=w.k)
+    assert cover["rows"] >= 100 and cover["longest_row"] == nnz.max()
+    _check_rows(oracle_pool, w, nnz, rp_np, seed, col, params, params_np, out, rows)
     # every row was written: none still holds the poison pattern the buffer was filled with
     assert out.shape == (w.n_rows, w.sig_bytes())
     assert bool((out != 0xAA).any(dim=1).all().item())
@@ -94,7 +87,7 @@ def test_large_workloads_sampled_rows(name, n_random, budget):
 
 @pytest.mark.parametrize("name", ["large_2u", "large_4u"])
 @pytest.mark.parametrize("D", [16_609_143, 500_000_003, 1_010_017_424])
-def test_universe_sizes_of_the_papers_datasets_sampled_rows(name, D):
+def test_universe_sizes_of_the_papers_datasets_sampled_rows(name, D, oracle_pool):
     """The headline rows hashed into a universe that is not a power of two (Table tab_data: webspam's
     16 609 143 and the expanded rcv1's 1 010 017 424, and one size in between), each of which takes
     a kernel form of its own; indices are folded into [0, D) as bench.py --universe does."""
@@ -110,13 +103,9 @@ def test_universe_sizes_of_the_papers_datasets_sampled_rows(name, D):
     ws = mh.alloc_workspace(len(nnz), int(rp_np[-1]), w.k, w.family, DEV)
     mh.minhash_signatures(rp, col, D, w.k, w.b, w.family, params, out=out, workspace=ws)
     assert mh.status(ws) == 0
-    rows = _sample_rows(nnz, 12, seed=23, eval_budget=1.2e8, k=w.k)
-    assert len(rows) >= 8
-    for r in rows:
-        lo, hi = int(rp_np[r]), int(rp_np[r + 1])
-        idx = col[lo:hi].cpu().numpy().view(np.uint32)
-        want = oracle.signatures(np.array([0, hi - lo], dtype=np.int64), idx, D, w.k, w.b, w.family, params_np)
-        assert np.array_equal(out[r].cpu().numpy(), want[0]), "row %d (nnz %d) differs from the oracle at D = %d" % (r, hi - lo, D)
+    rows, cover = _sample_rows(nnz, seed=23, eval_budget=1.5e9, k=w.k)
+    assert cover["rows"] >= 100
+    _check_rows(oracle_pool, w, nnz, rp_np, w.data_seed, col, params, params_np, out, rows, D=D)
     assert bool((out != 0xAA).any(dim=1).all().item())
 
 
@@ -140,13 +129,17 @@ def test_many_short_rows_do_not_depend_on_how_units_are_handed_out():
 
 
 @pytest.mark.parametrize("batch", [0, 9])
-def test_heavy_tailed_m61_batch_sampled_rows(batch):
+def test_heavy_tailed_m61_batch_sampled_rows(batch, oracle_pool):
+    """First and last batch of the heavy-tailed workload: the longest row (10^6 nonzeros: 123 chunks,
+    each with a vector of partial minima, merged by the finalize kernel), rows of at least 10^5
+    nonzeros in seeded random order while they fit three fifths of the budget, and rows from every
+    decile of the length distribution."""
     w, nnz, rp_np, seed, col, params, params_np, out = _run_workload("huge_2u_m61", batch)
     assert nnz.max() == 1_000_000                     # the batch contains rows at the cap
-    order = np.argsort(nnz, kind="stable")
-    rows = [int(order[-1])]                           # one row at the 10^6 cap: 123 chunks, each with a vector of partial minima, merged by the finalize kernel
-    rows += _sample_rows(nnz, 24, seed=18 + batch, eval_budget=4.0e8, k=w.k)
-    _check_rows(w, nnz, rp_np, seed, col, params, params_np, out, list(dict.fromkeys(rows)))
+    rows, cover = _sample_rows(nnz, seed=18 + batch, eval_budget=2.0e10, k=w.k, heavy_from=100_000)
+    assert cover["longest_row"] == 1_000_000 and cover["rows"] >= 300
+    assert int((nnz[rows] >= 100_000).sum()) >= 40
+    _check_rows(oracle_pool, w, nnz, rp_np, seed, col, params, params_np, out, rows)
     # b = 1, k = 500: 63 bytes per row, the last 4 bits of the last byte are pad and must be 0
     assert int((out[:, 62] & 0xF0).max().item()) == 0
 

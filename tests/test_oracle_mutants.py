@@ -48,6 +48,13 @@ MUTANTS = [
     ("match_counts_compare_wrong_field", "packed_field(sig + (size_t)r2 * (size_t)sig_stride, j, b)) ++c;",
      "packed_field(sig + (size_t)r2 * (size_t)sig_stride, (j + 1) % k, b)) ++c;"),
     ("wrong_prime_31", "case ORACLE_2U_M31: *p = 2147483647ull;", "case ORACLE_2U_M31: *p = 2147483648ull;"),
+    ("packed_fields_msb_first", "if ((d >> q) & 1u) words[at + 1 + bit / 32] |= 1u << (bit % 32);",
+     "if ((d >> (w - 1 - q)) & 1u) words[at + 1 + bit / 32] |= 1u << (bit % 32);"),
+    ("packed_width_counts_tile_boundaries", "if (i % 256 != 0 && row[i] - row[i - 1] > widest)", "if (row[i] - row[i - 1] > widest)"),
+    ("packed_tile_of_255", "for (int64_t first = 0; first < n; first += 256) {\n            const int64_t m = n - first < 256 ? n - first : 256;\n            const int64_t n_words",
+     "for (int64_t first = 0; first < n; first += 255) {\n            const int64_t m = n - first < 255 ? n - first : 255;\n            const int64_t n_words"),
+    ("packed_first_index_as_difference", "words[at] = row[first];", "words[at] = first ? row[first] - row[first - 1] : row[first];"),
+    ("unpack_forgets_to_accumulate", "value += d;", "value = d;"),
     ("wrong_prime_61", "case ORACLE_2U_M61: *p = 2305843009213693951ull;", "case ORACLE_2U_M61: *p = 2305843009213693953ull;"),
 ]
 
