@@ -205,6 +205,40 @@ int minhash_check_coeffs(const uint64_t *host_coeffs, int32_t k, int32_t family)
  * bad input, else MINHASH_OK. */
 int minhash_status(const void *workspace, void *stream);
 
+/* ---------------------------------------------------------------- packed index rows
+ * Section 3.2's batch loop copies every chunk of sets to the GPU before hashing
+ * it, and Section 3.6 finds the movement of the data dominant once the hashing
+ * is fast.  Rows whose indices are sorted (non-decreasing) can cross the host
+ * link as tiles of differences, about half the bytes for the heavy-tailed
+ * workload, and be turned back into col_idx on the device:
+ *
+ *   a row of n indices is cut into tiles of 256 (the last one shorter); a tile
+ *   is one 32-bit word holding its first index as it is, then the differences
+ *   between neighbours inside the tile, w bits each, LSB-first in 32-bit words,
+ *   the last word padded with zeros; w = width[r] is the bit length of the
+ *   largest such difference of row r (0..32); word_ptr[r] is the offset of row
+ *   r's first word in `words`, word_ptr[n_rows] the total.  A tile never takes
+ *   more words than it has indices, so row_ptr[n_rows] - row_ptr[0] words
+ *   always suffice.
+ *
+ * Both calls enqueue on `stream` and return without synchronising; all pointers
+ * are device pointers owned by the caller.  The last kernel of a call stores
+ * MINHASH_OK, MINHASH_ERR_DATA (a row is not sorted; its tiles are unspecified)
+ * or MINHASH_ERR_WORKSPACE (words_capacity / words_len too small for what
+ * row_ptr, width and word_ptr describe; nothing is accessed outside the
+ * buffers) in *status (device, one int32, required).  row_ptr must be
+ * non-decreasing. */
+
+/* col_idx -> (width[n_rows], word_ptr[n_rows+1], words[<= words_capacity]). */
+int minhash_pack_indices(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows,
+                         uint32_t *width, int64_t *word_ptr, uint32_t *words, int64_t words_capacity,
+                         int32_t *status, void *stream);
+
+/* (width, word_ptr, words[words_len]) -> col_idx[row_ptr[0] .. row_ptr[n_rows]), ready for minhash_signatures. */
+int minhash_unpack_indices(const int64_t *row_ptr, const uint32_t *width, const int64_t *word_ptr,
+                           const uint32_t *words, int64_t words_len, int64_t n_rows,
+                           uint32_t *col_idx, int32_t *status, void *stream);
+
 /* ---------------------------------------------------------------- consumers
  * What Section 1.1 does with a signature.  `sig` is the output of
  * minhash_signatures: device, rows sig_stride bytes apart, k values of b bits.

@@ -14,7 +14,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SRCS = [os.path.join(HERE, "csrc", "minhash.hip"), os.path.join(HERE, "csrc", "consumers.hip"),
-        os.path.join(HERE, "csrc", "ingest.hip")]
+        os.path.join(HERE, "csrc", "ingest.hip"), os.path.join(HERE, "csrc", "packed.hip")]
 LIB = os.path.join(HERE, "libminhash.so")
 # measurement only (instruction-issue and memory probes behind bench.py --probe); the signature library does not use it
 PROBE_SRCS = [os.path.join(HERE, "csrc", "probe.hip")]

@@ -219,10 +219,15 @@ __global__ __launch_bounds__(BLOCK) void pk_unpack_kernel(const int64_t* row_ptr
             if (lane >= d) below += o;
         }
         below -= run;
+        // through the LDS once more, so that neighbouring lanes store neighbouring indices
+        wave_sync_lds();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) buf[4 * lane + q] = below + v[q];
+        wave_sync_lds();
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const uint32_t i = 4u * (uint32_t)lane + (uint32_t)q;
-            if (i < m) col[s + i] = below + v[q];
+            const uint32_t i = (uint32_t)lane + (uint32_t)(WAVE * q);
+            if (i < m) __builtin_nontemporal_store(buf[i], col + s + i);
         }
         wave_sync_lds();
     });
@@ -287,18 +292,6 @@ int minhash_unpack_indices(const int64_t* row_ptr, const uint32_t* width, const 
                            col_idx, flags);
     hipLaunchKernelGGL(pk_export_status_kernel, dim3(1), dim3(1), 0, s, flags, status);
     return hipGetLastError() == hipSuccess ? MINHASH_OK : MINHASH_ERR_HIP;
-}
-
-int64_t minhash_packed_words(const int64_t* host_row_ptr, const uint32_t* host_width, int64_t n_rows)
-{
-    if (!host_row_ptr || n_rows < 0 || (n_rows > 0 && !host_width)) return -1;
-    uint64_t total = 0;
-    for (int64_t r = 0; r < n_rows; ++r) {
-        const int64_t n = host_row_ptr[r + 1] - host_row_ptr[r];
-        if (n < 0 || host_width[r] > 32u) return -1;
-        total += row_words((uint64_t)n, host_width[r]);
-    }
-    return (int64_t)total;
 }
 
 }  // extern "C"

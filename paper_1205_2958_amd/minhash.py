@@ -37,6 +37,8 @@ EXPORTS = (
     "minhash_workspace_bytes",
     "minhash_check_coeffs",
     "minhash_status",
+    "minhash_pack_indices",
+    "minhash_unpack_indices",
     "minhash_expand_indices",
     "minhash_match_counts",
     "minhash_resemblance_estimates",
@@ -81,6 +83,10 @@ def lib() -> ctypes.CDLL:
         L.minhash_check_coeffs.restype = ctypes.c_int
         L.minhash_status.argtypes = [vp, vp]
         L.minhash_status.restype = ctypes.c_int
+        L.minhash_pack_indices.argtypes = [vp, vp, i64, vp, vp, vp, i64, vp, vp]
+        L.minhash_pack_indices.restype = ctypes.c_int
+        L.minhash_unpack_indices.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp]
+        L.minhash_unpack_indices.restype = ctypes.c_int
         L.minhash_expand_indices.argtypes = [vp, i64, i64, i32, i32, vp, vp]
         L.minhash_expand_indices.restype = ctypes.c_int
         L.minhash_match_counts.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp, vp]
@@ -260,6 +266,46 @@ def status(workspace: torch.Tensor, stream=None) -> int:
     return int(lib().minhash_status(_ptr(workspace), _stream_handle(stream)))
 
 
+def pack_indices(row_ptr: torch.Tensor, col_idx: torch.Tensor, stream=None):
+    """Sorted rows as tiles of differences (see include/minhash.h).  Returns device tensors
+    (width int32-storage [n], word_ptr int64 [n+1], words int32-storage [word_ptr[n]]); waits
+    for the stream to learn the size and raises if a row was not sorted."""
+    if row_ptr.dtype != torch.int64 or not row_ptr.is_contiguous() or col_idx.element_size() != 4 or not col_idx.is_contiguous():
+        raise TypeError("row_ptr must be contiguous int64, col_idx contiguous with 4-byte elements")
+    n = row_ptr.numel() - 1
+    dev = row_ptr.device
+    width = torch.empty(max(n, 1), dtype=torch.int32, device=dev)
+    word_ptr = torch.empty(n + 1, dtype=torch.int64, device=dev)
+    words = torch.empty(max(col_idx.numel(), 1), dtype=torch.int32, device=dev)
+    st = torch.empty(1, dtype=torch.int32, device=dev)
+    rc = lib().minhash_pack_indices(_ptr(row_ptr), _ptr(col_idx), n, _ptr(width), _ptr(word_ptr), _ptr(words),
+                                    col_idx.numel(), _ptr(st), _stream_handle(stream))
+    if rc != 0:
+        _raise(rc)
+    code = int(st.item())
+    if code != 0:
+        _raise(code)
+    return width[:n], word_ptr, words[: int(word_ptr[-1].item())]
+
+
+def unpack_indices(row_ptr: torch.Tensor, width: torch.Tensor, word_ptr: torch.Tensor, words: torch.Tensor,
+                   out: torch.Tensor, status: torch.Tensor, stream=None) -> torch.Tensor:
+    """Enqueues the decoding of packed rows into ``out`` (4-byte elements, at least
+    row_ptr[-1] of them); ``status`` (one int32 on the device) receives the result code.
+    Does not synchronise."""
+    for t in (width, word_ptr, words, out):
+        if not t.is_contiguous() or t.device != row_ptr.device:
+            raise TypeError("packed arrays must be contiguous tensors on the device of row_ptr")
+    if width.element_size() != 4 or words.element_size() != 4 or out.element_size() != 4 or word_ptr.dtype != torch.int64:
+        raise TypeError("width, words and out hold 4-byte elements, word_ptr int64")
+    n = row_ptr.numel() - 1
+    rc = lib().minhash_unpack_indices(_ptr(row_ptr), _ptr(width), _ptr(word_ptr), _ptr(words), words.numel(), n, _ptr(out),
+                                      _ptr(status), _stream_handle(stream))
+    if rc != 0:
+        _raise(rc)
+    return out
+
+
 def expand_indices(sig: torch.Tensor, k: int, b: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """int32-storage [n_rows, k] tensor of uint32 positions j*2^b + s_ij (see include/minhash.h)."""
     n = sig.shape[0]
@@ -394,3 +440,82 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
         if rc != 0:
             _raise(rc)
     return results
+
+
+def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: torch.Tensor, max_rows: int, max_nnz: int,
+                          max_words: int, flags: int = 0):
+    """``stream_batches`` for rows that cross the host link as tiles of differences
+    (``pack_indices``): about half the bytes for sorted heavy-tailed rows, so that
+    the copies hide under the kernels again.
+
+    ``batches`` is a sequence of ``(row_ptr, width, word_ptr, words)`` of pinned host
+    tensors (``words`` may be a list of pinned pieces).  Per batch: copy on one
+    stream, decode into a col_idx buffer and hash on a second (the decoder runs right
+    before the hash kernels of its batch: launched on a stream of its own it would
+    wait for the persistent hash kernel of the batch before anyway, and start late),
+    signatures back on a third; two sets of packed buffers alternate.  Returns the
+    pinned uint8 host tensors [n_rows_i, ceil(k*b/8)], complete on return.
+    """
+    dev = params.device
+    sig = (k * b + 7) // 8
+    n_buf = 2
+    rp_d = [torch.empty(max_rows + 1, dtype=torch.int64, device=dev) for _ in range(n_buf)]
+    wp_d = [torch.empty(max_rows + 1, dtype=torch.int64, device=dev) for _ in range(n_buf)]
+    wd_d = [torch.empty(max(max_rows, 1), dtype=torch.int32, device=dev) for _ in range(n_buf)]
+    words_d = [torch.empty(max(max_words, 1), dtype=torch.int32, device=dev) for _ in range(n_buf)]
+    col_d = torch.empty(max(max_nnz, 1), dtype=torch.int32, device=dev)      # decoded and hashed on one stream: one buffer
+    out_d = [torch.empty((max_rows, sig), dtype=torch.uint8, device=dev) for _ in range(n_buf)]
+    codes = torch.zeros(max(len(batches), 1), dtype=torch.int32, device=dev)
+    ws = alloc_workspace(max_rows, max_nnz, k, family, dev)
+    s_in, s_run, s_out = (torch.cuda.Stream(dev) for _ in range(3))
+    now = torch.cuda.current_stream(dev)
+    for s in (s_in, s_run, s_out):
+        s.wait_stream(now)
+    in_done = [torch.cuda.Event() for _ in range(n_buf)]
+    run_done = [torch.cuda.Event() for _ in range(n_buf)]
+    out_done = [torch.cuda.Event() for _ in range(n_buf)]
+    results = []
+    for i, (rp_h, width_h, wp_h, words_h) in enumerate(batches):
+        n = rp_h.numel() - 1
+        pieces = list(words_h) if isinstance(words_h, (list, tuple)) else [words_h]
+        n_words = sum(p.numel() for p in pieces)
+        nnz = int(rp_h[-1]) - int(rp_h[0])
+        if n > max_rows or nnz > max_nnz or n_words > max_words or int(rp_h[0]) != 0:
+            raise ValueError("batch %d exceeds max_rows / max_nnz / max_words, or its row_ptr does not start at 0" % i)
+        u = i % n_buf
+        out_h = torch.empty((n, sig), dtype=torch.uint8, pin_memory=True)
+        results.append(out_h)
+        if i >= n_buf:
+            s_in.wait_event(run_done[u])          # decoder and kernels that read this set of buffers (row_ptr too) have finished
+        with torch.cuda.stream(s_in):
+            rp_d[u][: n + 1].copy_(rp_h, non_blocking=True)
+            wp_d[u][: n + 1].copy_(wp_h, non_blocking=True)
+            wd_d[u][:n].copy_(width_h.view(torch.int32), non_blocking=True)
+            at = 0
+            for p in pieces:
+                words_d[u][at: at + p.numel()].copy_(p.view(torch.int32), non_blocking=True)
+                at += p.numel()
+            in_done[u].record(s_in)
+        s_run.wait_event(in_done[u])
+        if i >= n_buf:
+            s_run.wait_event(out_done[u])         # the previous signatures left this output buffer
+        unpack_indices(rp_d[u][: n + 1], wd_d[u][:n], wp_d[u][: n + 1], words_d[u][:n_words], col_d, codes[i: i + 1], stream=s_run)
+        minhash_signatures(rp_d[u][: n + 1], col_d[:nnz], D, k, b, family, params, out=out_d[u][:n],
+                           out_stride=sig, workspace=ws, stream=s_run, flags=flags)
+        run_done[u].record(s_run)
+        s_out.wait_event(run_done[u])
+        with torch.cuda.stream(s_out):
+            out_h.copy_(out_d[u][:n], non_blocking=True)
+            out_done[u].record(s_out)
+    for s in (s_in, s_run, s_out):
+        s.synchronize()
+    now.wait_stream(s_out)
+    bad = [int(c) for c in codes[: len(batches)].cpu().tolist() if c != 0]
+    if bad:
+        _raise(bad[0])
+    if any(r.shape[0] > 0 for r in results):
+        rc = status(ws, s_run)
+        if rc != 0:
+            _raise(rc)
+    return results
+

@@ -155,6 +155,21 @@ def test_static_entry_point_rejects_bad_arguments_and_oversized_batches_before_a
             assert _call_static(lib, n_rows=n, nnz_ub=nnz, k=k, out_stride=k) == -7
 
 
+def test_packed_row_entry_points_validate_before_any_launch(lib):
+    P = 0x1000
+    lib.minhash_pack_indices.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_int64] + [ctypes.c_void_p] * 3 + [ctypes.c_int64] + [ctypes.c_void_p] * 2
+    lib.minhash_unpack_indices.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int64] * 2 + [ctypes.c_void_p] * 3
+    assert lib.minhash_pack_indices(P, P, -1, P, P, P, 10, P, 0) == -1
+    assert lib.minhash_pack_indices(P, P, 4, P, P, P, -1, P, 0) == -1
+    assert lib.minhash_pack_indices(0, P, 4, P, P, P, 10, P, 0) == -1
+    assert lib.minhash_pack_indices(P, P, 4, P, P, P, 10, 0, 0) == -1          # the status word is required
+    assert lib.minhash_pack_indices(P, 0, 4, P, P, P, 10, P, 0) == -1
+    assert lib.minhash_unpack_indices(P, P, P, P, 10, -1, P, P, 0) == -1
+    assert lib.minhash_unpack_indices(P, P, P, P, -1, 4, P, P, 0) == -1
+    assert lib.minhash_unpack_indices(P, P, P, P, 10, 4, 0, P, 0) == -1
+    assert lib.minhash_unpack_indices(P, P, P, P, 10, 4, P, 0, 0) == -1
+
+
 def test_profiled_entry_point_validates_the_same_way(lib):
     ms = ctypes.c_float(-1.0)
     rc = lib.minhash_signatures_profiled(0x1000, 0x1000, 4, 0, 64, 8, 0, 0x1000, 0, 0x1000, 64, 0x1000, 1 << 20, 0, 0,

@@ -1,0 +1,162 @@
+"""Packed index rows on the GPU (minhash_pack_indices / minhash_unpack_indices) against the
+CPU checker's plain definition of the same form, word for word, and signatures computed from
+unpacked rows against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_1205_2958_amd import minhash as mh
+from paper_1205_2958_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _dev(a):
+    if a.dtype == np.uint32:
+        return torch.from_numpy(a.view(np.int32)).to(DEV)
+    return torch.from_numpy(a).to(DEV)
+
+
+def _host_u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def _round_trip(rp, col):
+    rp_d, col_d = _dev(rp), _dev(col)
+    width, word_ptr, words = mh.pack_indices(rp_d, col_d)
+    w_o, wp_o, words_o = oracle.pack_indices(rp, col)
+    assert np.array_equal(_host_u32(width), w_o)
+    assert np.array_equal(word_ptr.cpu().numpy(), wp_o)
+    assert np.array_equal(_host_u32(words), words_o)
+    out = torch.full((max(col.shape[0], 1),), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+    st = torch.full((1,), 99, dtype=torch.int32, device=DEV)
+    mh.unpack_indices(rp_d, width, word_ptr, words, out, st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    assert np.array_equal(_host_u32(out)[: col.shape[0]], col)
+    return width, word_ptr, words
+
+
+def test_rows_around_the_tile_size_and_gaps_of_every_magnitude():
+    rng = np.random.Generator(np.random.PCG64(717))
+    lens = [0, 1, 2, 3, 4, 5, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1000, 0, 4095, 4096, 4097, 8192, 20000, 1, 0]
+    rows = []
+    for n in lens:
+        top = int(rng.choice([4, 1 << 8, 1 << 16, 1 << 24, (1 << 32) - 1]))
+        gaps = rng.integers(0, max(top // max(n, 1), 1) + 1, size=n, dtype=np.uint64)
+        rows.append(np.minimum(np.cumsum(gaps), (1 << 32) - 1).astype(np.uint32))
+    rp = W.row_ptr_from_nnz(np.array(lens, dtype=np.int64))
+    _round_trip(rp, np.concatenate(rows))
+
+
+def test_widths_from_0_to_32_bits():
+    rows = []
+    for w in range(0, 33):
+        d = (1 << w) - 1 if w else 0
+        n = 300
+        steps = np.zeros(n, dtype=np.uint64)
+        steps[5] = d                                   # the widest difference decides the width of the whole row
+        steps[299] = d >> 1
+        if w == 32:
+            steps[299] = 0
+        rows.append(np.cumsum(steps).astype(np.uint32))
+    rp = W.row_ptr_from_nnz(np.full(33, 300, dtype=np.int64))
+    width, _, _ = _round_trip(rp, np.concatenate(rows))
+    assert _host_u32(width).tolist() == list(range(33))
+
+
+def test_many_short_rows_and_one_long_row_share_spans():
+    """Spans of 4 096 positions cut across rows: thousands of rows of one to three indices, empty
+    rows, and one row of 100 000 indices whose tiles are decoded by many wavefronts."""
+    rng = np.random.Generator(np.random.PCG64(81))
+    lens = np.concatenate([rng.integers(0, 4, size=6000), [100_000], rng.integers(0, 4, size=3000), [700, 0, 0, 1]]).astype(np.int64)
+    rp = W.row_ptr_from_nnz(lens)
+    col = W.csr_indices_np(lens, 1 << 30, seed=5)
+    _round_trip(rp, col)
+
+
+def test_row_ptr_need_not_start_at_zero():
+    lens = np.array([10, 600, 0, 3], dtype=np.int64)
+    col_all = np.concatenate([np.arange(7, dtype=np.uint32), W.csr_indices_np(lens, 1 << 20, seed=9)])
+    rp = W.row_ptr_from_nnz(lens) + 7
+    rp_d, col_d = _dev(rp), _dev(col_all)
+    width, word_ptr, words = mh.pack_indices(rp_d, col_d)
+    w_o, wp_o, words_o = oracle.pack_indices(rp, col_all)
+    assert np.array_equal(_host_u32(words), words_o) and np.array_equal(word_ptr.cpu().numpy(), wp_o)
+    out = torch.zeros(col_all.shape[0], dtype=torch.int32, device=DEV)
+    st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    mh.unpack_indices(rp_d, width, word_ptr, words, out, st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0 and np.array_equal(_host_u32(out)[7:], col_all[7:]) and not _host_u32(out)[:7].any()
+
+
+def test_bad_input_is_reported_and_nothing_is_written_outside_the_buffers():
+    rp = np.array([0, 3], dtype=np.int64)
+    with pytest.raises(mh.MinhashError) as e:
+        mh.pack_indices(_dev(rp), _dev(np.array([5, 4, 6], dtype=np.uint32)))        # not sorted
+    assert e.value.code == -9
+    # unpacking with a word buffer that is shorter than the offsets say
+    lens = np.array([600, 300], dtype=np.int64)
+    rp = W.row_ptr_from_nnz(lens)
+    col = W.csr_indices_np(lens, 1 << 24, seed=3)
+    width, word_ptr, words = mh.pack_indices(_dev(rp), _dev(col))
+    out = torch.full((900,), -1, dtype=torch.int32, device=DEV)
+    st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    mh.unpack_indices(_dev(rp), width, word_ptr, words[: words.numel() - 5].contiguous(), out, st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == -6
+    # an empty batch
+    st.fill_(5)
+    mh.unpack_indices(torch.zeros(1, dtype=torch.int64, device=DEV), width[:0], word_ptr[:1], words[:0], out, st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+
+
+def test_signatures_from_unpacked_rows_equal_the_oracle(oracle_pool):
+    """The path the streamed workload takes: packed rows -> col_idx on the device -> signatures."""
+    w = W.WORKLOADS["huge_2u_m61"]
+    nnz = w.nnz(3)[:3000]
+    rp = W.row_ptr_from_nnz(nnz)
+    col = W.csr_indices_np(nnz, w.D, w.data_seed + 3)
+    c = W.coefficients(w.k, w.family, w.param_seed)
+    rp_d = _dev(rp)
+    width, word_ptr, words = mh.pack_indices(rp_d, _dev(col))
+    assert words.numel() < 0.75 * col.shape[0]                # the form is denser than 32 bits per index
+    out = torch.empty(col.shape[0], dtype=torch.int32, device=DEV)
+    st = torch.zeros(1, dtype=torch.int32, device=DEV)
+    mh.unpack_indices(rp_d, width, word_ptr, words, out, st)
+    sig = mh.minhash_signatures(rp_d, out, w.D, w.k, w.b, w.family, torch.from_numpy(c.view(np.int64)).to(DEV))
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    want, _, _ = oracle_pool.signatures(rp, col, w.D, w.k, w.b, w.family, c)
+    assert np.array_equal(sig.cpu().numpy(), want)
+
+
+def test_streamed_packed_batches_equal_the_oracle():
+    """Five batches of unequal size, packed on the device, parked in pinned host memory and
+    streamed back through copy / decode / hash / copy-back on four streams."""
+    D, k, b, family = 1 << 30, 500, 1, mh.FAMILY_2U_M61
+    nnz = W.lomax_nnz(900, scale=580.4, tail=0.8, lo=1, hi=40_000, seed=77)
+    nnz[13] = 0
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed=78)
+    c = W.coefficients(k, family, seed=79)
+    want = oracle.signatures(rp, col, D, k, b, family, c)
+    bounds = [0, 200, 201, 450, 700, 900]
+    batches, max_words = [], 0
+    for lo, hi in zip(bounds[:-1], bounds[1:]):
+        rp_b = (rp[lo:hi + 1] - rp[lo]).copy()
+        width, word_ptr, words = mh.pack_indices(_dev(rp_b), _dev(col[rp[lo]:rp[hi]].copy()))
+        words_h = words.cpu().pin_memory()
+        if lo == 450:                                           # words handed over in pieces
+            cut = words_h.numel() // 3
+            words_h = [words_h[:cut].clone().pin_memory(), words_h[cut:].clone().pin_memory()]
+        batches.append((torch.from_numpy(rp_b).pin_memory(), width.cpu().pin_memory(), word_ptr.cpu().pin_memory(), words_h))
+        max_words = max(max_words, words.numel())
+    max_rows = max(h - l for l, h in zip(bounds[:-1], bounds[1:]))
+    max_nnz = max(int(rp[h] - rp[l]) for l, h in zip(bounds[:-1], bounds[1:]))
+    outs = mh.stream_batches_packed(batches, D, k, b, family, torch.from_numpy(c.view(np.int64)).to(DEV), max_rows, max_nnz,
+                                    max_words)
+    got = np.concatenate([o.numpy() for o in outs], axis=0)
+    assert np.array_equal(got, want)
