@@ -83,8 +83,8 @@ HBM_PEAK = 8.0e12
 # size.  A profiler cannot run inside this process, so the figure is carried over from the committed
 # summary named beside it and holds for the kernels of that summary.
 PROFILED_TRAFFIC = {
-    "large_2u": (6.070e9, "profiles/mh_hash_kernel_2u_m31__large_2u.txt"),
-    "perm_table": (1.16545e12, "profiles/mh_perm_kernel__perm_table.txt"),
+    "large_2u": (6.080e9, "profiles/mh_hash_kernel_2u_m31__large_2u.txt"),
+    "perm_table": (1.16641e12, "profiles/mh_perm_kernel__perm_table.txt"),
 }
 # counter summaries (SQ_INSTS_VALU per evaluation against the model's instruction count) per family
 ISSUE_MODEL_EVIDENCE = "profiles/issue_rates__probe.txt, profiles/sq_counters__hash_kernels.txt"

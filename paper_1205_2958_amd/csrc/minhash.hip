@@ -351,13 +351,13 @@ __device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c)
 // partial vectors of the resulting chunks fit the workspace.  Large batches get
 // MAX_CHUNK; a batch of a few hundred rows gets its long rows cut finely enough to
 // occupy the whole GPU instead of waiting for one wavefront per row.
-__device__ __forceinline__ void reset_header(const KArgs& a)      // threads 0..63 of one block
+__device__ __forceinline__ uint32_t reset_header(const KArgs& a)      // threads 0..63 of one block; thread 0 returns the chunk size
 {
     uint32_t* words = reinterpret_cast<uint32_t*>(a.hdr);
     if (threadIdx.x < 64 && threadIdx.x != offsetof(WorkHeader, chunk) / 4) words[threadIdx.x] = 0;
+    uint32_t chunk = MAX_CHUNK;
     if (threadIdx.x == 0) {
         const int64_t total = a.row_ptr[a.n_rows] - a.row_ptr[0];
-        uint32_t chunk = MAX_CHUNK;
         if (total > 0) {
             const uint64_t nnz = (uint64_t)total, n = (uint64_t)a.n_rows;
             while (chunk > MIN_CHUNK) {
@@ -369,8 +369,9 @@ __device__ __forceinline__ void reset_header(const KArgs& a)      // threads 0..
         }
         a.hdr->chunk = chunk;
     }
+    return chunk;
 }
-__global__ void mh_reset_kernel(KArgs a) { reset_header(a); }
+__global__ void mh_reset_kernel(KArgs a) { (void)reset_header(a); }
 
 // One thread per row.  Prefix sums over the wavefront and then over the block's
 // wavefronts make one atomic per block of 1024 rows and counter (one per
@@ -387,12 +388,15 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = threadIdx.x >> 6;
     const int64_t row = (int64_t)blockIdx.x * BIN_BLOCK + threadIdx.x;
-    if (gridDim.x == 1) {              // a batch of one block clears the header itself: one launch fewer for small batches
-        reset_header(a);
-        __threadfence();
+    __shared__ uint32_t s_chunk;
+    const bool own_reset = gridDim.x == 1;             // a batch of one block clears the header itself: one launch fewer
+    if (own_reset) {
+        const uint32_t chunk = reset_header(a);
+        if (threadIdx.x == 0) s_chunk = chunk;
+        __threadfence();                               // the cleared counters are in place before any wavefront of the block adds to them
         __syncthreads();
     }
-    uint32_t CHUNK = a.hdr->chunk;
+    uint32_t CHUNK = own_reset ? s_chunk : a.hdr->chunk;
     if (CHUNK < MIN_CHUNK || CHUNK > MAX_CHUNK) CHUNK = MAX_CHUNK;
     uint32_t n_it = 0, is_split = 0;
     int64_t begin = 0, nnz = 0;
