@@ -8,6 +8,7 @@
 #include <stdint.h>
 
 #include "minhash.h"
+#include "mh_host.h"
 
 namespace {
 
@@ -153,9 +154,10 @@ int minhash_expand_indices(const uint8_t* sig, int64_t n_rows, int64_t sig_strid
     if (((unsigned __int128)k << b) > ((unsigned __int128)1 << 32)) return MINHASH_ERR_KB;
     if (n_rows == 0) return MINHASH_OK;
     if (!sig || !out_idx) return MINHASH_ERR_ARG;
+    (void)hipGetLastError();           // an error left by an earlier, unrelated call is not this call's
     hipLaunchKernelGGL(mh_expand_kernel, dim3(grid_for(n_rows)), dim3(BLOCK), 0, static_cast<hipStream_t>(stream), v,
                        n_rows, out_idx);
-    return hipGetLastError() == hipSuccess ? MINHASH_OK : MINHASH_ERR_HIP;
+    return mh::launches_ok();
 }
 
 int minhash_match_counts(const uint8_t* sig, int64_t n_rows, int64_t sig_stride, int32_t k, int32_t b,
@@ -167,9 +169,10 @@ int minhash_match_counts(const uint8_t* sig, int64_t n_rows, int64_t sig_stride,
     if (n_pairs < 0) return MINHASH_ERR_ARG;
     if (n_pairs == 0) return MINHASH_OK;
     if (!sig || !pairs || !counts) return MINHASH_ERR_ARG;
+    (void)hipGetLastError();           // an error left by an earlier, unrelated call is not this call's
     hipLaunchKernelGGL(mh_match_kernel, dim3(grid_for(n_pairs)), dim3(BLOCK), 0, static_cast<hipStream_t>(stream), v,
                        n_rows, pairs, n_pairs, counts);
-    return hipGetLastError() == hipSuccess ? MINHASH_OK : MINHASH_ERR_HIP;
+    return mh::launches_ok();
 }
 
 int minhash_resemblance_estimates(const uint32_t* counts, const int64_t* f1, const int64_t* f2, int64_t n_pairs,
@@ -181,9 +184,10 @@ int minhash_resemblance_estimates(const uint32_t* counts, const int64_t* f1, con
     if (n_pairs == 0) return MINHASH_OK;
     if (!counts || !f1 || !f2 || !r_hat) return MINHASH_ERR_ARG;
     const int blocks = (int)((n_pairs + BLOCK - 1) / BLOCK);
+    (void)hipGetLastError();           // an error left by an earlier, unrelated call is not this call's
     hipLaunchKernelGGL(mh_estimate_kernel, dim3(blocks), dim3(BLOCK), 0, static_cast<hipStream_t>(stream), counts, f1,
                        f2, n_pairs, (double)D, k, b, r_hat);
-    return hipGetLastError() == hipSuccess ? MINHASH_OK : MINHASH_ERR_HIP;
+    return mh::launches_ok();
 }
 
 }  // extern "C"

@@ -45,6 +45,7 @@
 
 #include "minhash.h"
 #include "mh_arith.h"
+#include "mh_host.h"
 
 // Work space of minhash_signatures_static: one copy per GPU, held until the process
 // ends.  Host code reaches it only through the address static_scratch() looks up.
@@ -2310,6 +2311,15 @@ int run(const int64_t* row_ptr, const uint32_t* col_idx, int64_t n_rows, uint64_
 }
 
 }  // namespace
+
+namespace mh {
+int report_hip_error(hipError_t e, const char* what) { return hip_fail(e, what); }
+int launches_ok()
+{
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? MINHASH_OK : hip_fail(e, "kernel launch");
+}
+}  // namespace mh
 
 // ==================================================================== C ABI
 extern "C" {

@@ -25,6 +25,7 @@
 #include <stdint.h>
 
 #include "minhash.h"
+#include "mh_host.h"
 
 namespace {
 
@@ -275,7 +276,7 @@ int minhash_pack_indices(const int64_t* row_ptr, const uint32_t* col_idx, int64_
         hipLaunchKernelGGL(pk_fill_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(word_ptr), (int64_t)2, 0u);
     }
     hipLaunchKernelGGL(pk_export_status_kernel, dim3(1), dim3(1), 0, s, flags, status);
-    return hipGetLastError() == hipSuccess ? MINHASH_OK : MINHASH_ERR_HIP;
+    return mh::launches_ok();
 }
 
 int minhash_unpack_indices(const int64_t* row_ptr, const uint32_t* width, const int64_t* word_ptr, const uint32_t* words,
@@ -291,7 +292,7 @@ int minhash_unpack_indices(const int64_t* row_ptr, const uint32_t* width, const 
         hipLaunchKernelGGL(pk_unpack_kernel, dim3(grid_blocks()), dim3(BLOCK), 0, s, row_ptr, width, word_ptr, words, words_len, n_rows,
                            col_idx, flags);
     hipLaunchKernelGGL(pk_export_status_kernel, dim3(1), dim3(1), 0, s, flags, status);
-    return hipGetLastError() == hipSuccess ? MINHASH_OK : MINHASH_ERR_HIP;
+    return mh::launches_ok();
 }
 
 }  // extern "C"

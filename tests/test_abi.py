@@ -199,3 +199,25 @@ def test_consumer_entry_points_validate_before_any_launch(lib):
     assert lib.minhash_resemblance_estimates(P, P, P, 5, 0, 500, 8, P, 0) == -3
     assert lib.minhash_resemblance_estimates(P, P, P, 5, 1 << 24, 500, 33, P, 0) == -4
     assert lib.minhash_resemblance_estimates(0, P, P, 5, 1 << 24, 500, 8, P, 0) == -1
+
+
+def test_probe_library_loads_and_exports_its_entry_points():
+    """The measurement library behind bench.py --probe: loads without a GPU, exports what its binding
+    declares, names its instruction kinds, and refuses bad arguments before any launch."""
+    from paper_1205_2958_amd import probe
+    L = probe.lib()
+    for name in probe.EXPORTS:
+        assert hasattr(L, name), name
+    kinds = probe.kinds()
+    assert "v_mad_u64_u32" in kinds and "v_min3_u32" in kinds and "v_add_u32" in kinds
+    P = 0x1000
+    ms, slots = ctypes.c_float(0), ctypes.c_double(0)
+    assert L.mh_probe_issue(len(kinds), 0, 0, 4, 2.4, P, 0, 1, ctypes.byref(ms), ctypes.byref(slots)) == -1     # no such kind
+    assert L.mh_probe_issue(0, 4, 0, 4, 2.4, P, 0, 1, ctypes.byref(ms), ctypes.byref(slots)) == -1              # n_simple not offered
+    assert L.mh_probe_issue(0, 1, 0, 9, 2.4, P, 0, 1, ctypes.byref(ms), ctypes.byref(slots)) == -1              # waves per SIMD
+    assert L.mh_probe_stream_read(P, 100, 8, 0, 1, ctypes.byref(ms)) == -1                                       # too small
+    assert L.mh_probe_stream_read(P + 4, 1 << 20, 8, 0, 1, ctypes.byref(ms)) == -1                               # misaligned
+    assert L.mh_probe_copy(0, P, 1 << 20, 0, 1, ctypes.byref(ms)) == -1
+    assert L.mh_probe_gather_rows(P, 100, 800, 808, P, 1000, 8, 8, 0, 1, ctypes.byref(ms)) == -1                 # row longer than the pitch
+    assert L.mh_probe_gather_rows(P, 100, 800, 800, P, 1000, 12, 8, 0, 1, ctypes.byref(ms)) == -1                # rows in flight
+
