@@ -239,6 +239,21 @@ int minhash_unpack_indices(const int64_t *row_ptr, const uint32_t *width, const 
                            const uint32_t *words, int64_t words_len, int64_t n_rows,
                            uint32_t *col_idx, int32_t *status, void *stream);
 
+/* minhash_signatures for rows that are given in the packed form above instead of as col_idx: a tile of
+ * that form is what the hash kernels stage at a time, so its words are fetched in place of the indices
+ * and decoded while they are staged, with no pass over the data in between.  Every argument that
+ * minhash_signatures also has means the same (row_ptr still gives the rows' lengths and must start
+ * the tiles where pack_indices started them: row r has row_ptr[r+1] - row_ptr[r] indices);
+ * MINHASH_PERM is not served this way (MINHASH_ERR_FAMILY: unpack first).  A width above 32 or a tile
+ * that would leave words[0 .. words_len) is never followed; minhash_status then reports
+ * MINHASH_ERR_DATA and the rows concerned get unspecified signatures.  The workspace is sized with
+ * minhash_workspace_bytes for at least row_ptr[n_rows] - row_ptr[0] nonzeros, as for minhash_signatures. */
+int minhash_signatures_packed(const int64_t *row_ptr, const uint32_t *width, const int64_t *word_ptr,
+                              const uint32_t *words, int64_t words_len, int64_t n_rows,
+                              uint64_t D, int32_t k, int32_t b, int32_t family, const void *params,
+                              uint8_t *out, int64_t out_stride,
+                              void *workspace, size_t workspace_bytes, void *stream, uint32_t flags);
+
 /* ---------------------------------------------------------------- consumers
  * What Section 1.1 does with a signature.  `sig` is the output of
  * minhash_signatures: device, rows sig_stride bytes apart, k values of b bits.

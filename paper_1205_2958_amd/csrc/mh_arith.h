@@ -637,6 +637,12 @@ MH_HD TicketMap make_ticket_map(uint64_t units, uint64_t single_units, uint32_t 
     return m;
 }
 
+// ---------------------------------------------------------------- packed index rows
+// A tile of m indices (1..256) whose in-tile differences are w bits wide takes one word for
+// its first index and ceil((m - 1) w / 32) words of differences.
+constexpr uint32_t PACKED_TILE = 256;
+MH_HD uint32_t packed_tile_words(uint32_t m, uint32_t w) { return 1u + ((m - 1u) * w + 31u) / 32u; }
+
 // ---------------------------------------------------------------- row offsets
 // What the row-binning kernel makes of one row's offsets.  A row is [begin, end) in
 // col_idx; lo = row_ptr[0] and hi = row_ptr[n_rows] bound the part of col_idx the

@@ -97,7 +97,8 @@ struct alignas(16) Item {              // one unit of row work
     uint32_t len;                      // number of nonzeros (at most the chunk size)
     uint32_t row;
     uint32_t slot;                     // NO_SLOT for a whole row, else index of this chunk's vector of partial minima
-    uint32_t pad[3];
+    uint32_t wlo, whi;                 // packed input only: offset of the item's first tile in the word array,
+    uint32_t w;                        // and the bit width of the row's differences
 };
 static_assert(sizeof(Item) == 32, "item size: one 16-byte load takes begin, len and row");
 
@@ -165,6 +166,11 @@ struct KArgs {
     uint32_t validate;
     uint32_t lane_pack;                // the hash kernel stores packed dwords from registers (see lane_pack_store)
     uint64_t prime;                    // runtime modulus of the generic-% ablation kernels
+    // packed input (minhash_signatures_packed): rows as tiles of differences instead of col_idx
+    const uint32_t* pk_width;
+    const int64_t* pk_word_ptr;
+    const uint32_t* pk_words;
+    int64_t pk_words_len;
 };
 
 // ------------------------------------------------------------------ small helpers
@@ -195,16 +201,42 @@ __device__ __forceinline__ void wave_sync_lds()
 // unit is known without waiting on memory and its first nonzeros can be requested
 // while the current unit is still being worked on.  All values are wavefront-uniform.
 constexpr int MAX_RUN = 32;
-struct RunItems {                      // LDS of one wavefront
+// (Two forms of each structure: with packed input a unit also carries where its words start and
+// how wide its differences are.  The form without is kept exactly as it was, so that the kernels for
+// plain col_idx input compile to the same code whether or not the packed form exists.)
+template <bool PACKED>
+struct RunItemsT;
+template <>
+struct RunItemsT<false> {              // LDS of one wavefront
     uint4 rec[MAX_RUN];                // begin (low, high word), len, row
     uint2 meta[MAX_RUN];               // slot, function tile
 };
-struct Unit {
+template <>
+struct RunItemsT<true> {
+    uint4 rec[MAX_RUN];
+    uint4 meta[MAX_RUN];               // slot, function tile, the item's first word (low, high)
+    uint32_t width[MAX_RUN];           // bit width of the row's differences
+};
+template <bool PACKED>
+struct UnitT;
+template <>
+struct UnitT<false> {
     int64_t begin;
     uint32_t len, row, slot;
     int ftile;
 };
-struct UnitStream {
+template <>
+struct UnitT<true> {
+    int64_t begin;
+    uint32_t len, row, slot;
+    int ftile;
+    int64_t wbegin;                    // offset of the item's first tile in the word array,
+    uint32_t w;                        // width of its differences
+};
+template <bool PACKED>
+struct UnitStreamT {
+    using RunItems = RunItemsT<PACKED>;
+    using Unit = UnitT<PACKED>;
     TicketMap map;
     uint32_t grid_waves;
     uint32_t base, next, end;          // the run [base, end) has its records in LDS; next is the first unit not yet handed out
@@ -217,21 +249,32 @@ struct UnitStream {
             const uint32_t item_idx = nft == 1u ? u : u / nft;
             const Item* p = item_idx < n_long ? a.items + item_idx : a.items + a.cap_long + (item_idx - n_long);
             const uint4 r = *reinterpret_cast<const uint4*>(p);
-            const uint32_t slot = p->slot;
-            lds->rec[lane] = r;
-            lds->meta[lane] = uint2{slot, u - item_idx * nft};
+            if constexpr (PACKED) {
+                const uint4 t = *(reinterpret_cast<const uint4*>(p) + 1);      // slot, first word (low, high), width
+                lds->rec[lane] = r;
+                lds->meta[lane] = uint4{t.x, u - item_idx * nft, t.y, t.z};
+                lds->width[lane] = t.w;
+            } else {
+                const uint32_t slot = p->slot;
+                lds->rec[lane] = r;
+                lds->meta[lane] = uint2{slot, u - item_idx * nft};
+            }
         }
         wave_sync_lds();
     }
     __device__ __forceinline__ void read(uint32_t unit, const RunItems* lds, Unit* out) const
     {
         const uint4 r = lds->rec[unit - base];
-        const uint2 m = lds->meta[unit - base];
+        const auto m = lds->meta[unit - base];
         out->begin = (int64_t)(((uint64_t)first_lane_value(r.y) << 32) | first_lane_value(r.x));
         out->len = first_lane_value(r.z);
         out->row = first_lane_value(r.w);
         out->slot = first_lane_value(m.x);
         out->ftile = (int)first_lane_value(m.y);
+        if constexpr (PACKED) {
+            out->wbegin = (int64_t)(((uint64_t)first_lane_value(m.w) << 32) | first_lane_value(m.z));
+            out->w = first_lane_value(lds->width[unit - base]);
+        }
     }
     // the first unit of this wavefront (its own index in the grid is its first ticket); false when there is none
     __device__ __forceinline__ bool init(const KArgs& a, uint64_t units, uint64_t single_units, uint32_t waves, uint32_t index,
@@ -467,7 +510,7 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
     Item* short_items = a.items + a.cap_long;
     if (overflow) {
         atomicOr(&a.hdr->status, 4u);
-        Item it; it.begin = begin; it.len = 0; it.row = (uint32_t)row; it.slot = NO_SLOT; it.pad[0] = 1; it.pad[1] = 0; it.pad[2] = 0;
+        Item it; it.begin = begin; it.len = 0; it.row = (uint32_t)row; it.slot = NO_SLOT; it.wlo = 0; it.whi = 0; it.w = 0;
         for (uint32_t c = 0; c < n_lg && first_lg + c < a.cap_long; ++c) long_items[first_lg + c] = it;
         for (uint32_t c = 0; c < n_sh && first_sh + c < a.cap_short; ++c) short_items[first_sh + c] = it;
         if (is_split && sidx < a.cap_split) {
@@ -480,6 +523,17 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
         SplitRow sr; sr.row = (uint32_t)row; sr.first_part = (uint32_t)first_part; sr.n_parts = n_it; sr.pad = 0;
         a.split_rows[sidx] = sr;
     }
+    // packed input: where the row's words start and how wide its differences are (chunks are whole numbers of tiles)
+    int64_t pk_first = 0;
+    uint32_t pk_w = 0;
+    if (a.pk_words) {
+        pk_first = a.pk_word_ptr[row];
+        pk_w = a.pk_width[row];
+        if (pk_w > 32u) {              // not a width: the row is reported and read as if its differences were 0 bits wide
+            atomicOr(&a.hdr->status, 1u);
+            pk_w = 0;
+        }
+    }
     uint32_t n_long_done = 0, n_short_done = 0;
     for (uint32_t c = 0; c < n_it; ++c) {
         Item it;
@@ -488,7 +542,8 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
         it.len = is_split ? (uint32_t)(rest < (int64_t)CHUNK ? rest : (int64_t)CHUNK) : (uint32_t)nnz;
         it.row = (uint32_t)row;
         it.slot = is_split ? (uint32_t)(first_part + c) : NO_SLOT;
-        it.pad[0] = 0; it.pad[1] = 0; it.pad[2] = 0;
+        const int64_t wbegin = pk_first + (int64_t)c * (int64_t)(CHUNK / PACKED_TILE) * (int64_t)packed_tile_words(PACKED_TILE, pk_w);
+        it.wlo = (uint32_t)wbegin; it.whi = (uint32_t)((uint64_t)wbegin >> 32); it.w = pk_w;
         if (it.len > LONG_ITEM) long_items[first_lg + (n_long_done++)] = it;
         else short_items[first_sh + (n_short_done++)] = it;
     }
@@ -1461,6 +1516,73 @@ __device__ __forceinline__ TileWalk walk_of(uint32_t in_tile, int n_slices)
     return t;
 }
 
+// Packed input: requests the words of the tile that starts `off` nonzeros into an item (off a multiple of
+// 256) into 4 registers per lane (word lane + 64 q).  A tile that would leave the word array is reported
+// and read as zeros.
+__device__ __forceinline__ void load_packed_tile(const KArgs& a, int64_t wbegin, uint32_t w, uint32_t len, uint32_t off, int lane,
+                                                 uint32_t (&r)[4])
+{
+    const uint32_t m = len - off < PACKED_TILE ? len - off : PACKED_TILE;
+    const uint32_t nw = packed_tile_words(m, w);
+    const int64_t at = wbegin + (int64_t)(off / PACKED_TILE) * (int64_t)packed_tile_words(PACKED_TILE, w);
+    const bool inside = at >= 0 && at + (int64_t)nw <= a.pk_words_len;
+    if (!inside && lane == 0) atomicOr(&a.hdr->status, 1u);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t j = (uint32_t)lane + (uint32_t)(WAVE * q);
+        r[q] = 0;
+        if ((uint32_t)(WAVE * q) < nw && inside && j < nw) r[q] = __builtin_nontemporal_load(a.pk_words + at + j);
+    }
+}
+// The 256 indices of such a tile from its words: lane l gets indices 4l .. 4l+3 in v.  The words pass
+// through `buf` (LDS of this wavefront, at least 258 words); a field is w bits at bit (i - 1) w of the
+// bit string that starts at word 1, the index is the first word plus the running sum of the fields.
+// Indices past the end of the item repeat its last one (their fields read as 0).
+__device__ __forceinline__ void decode_packed_tile(uint32_t* buf, const uint32_t (&r)[4], uint32_t w, uint32_t len, uint32_t off, int lane_in,
+                                                   uint32_t (&v)[4])
+{
+    // Everything below that depends on the lane number alone would otherwise be worked out once, ahead of
+    // the loops over units and tiles, and sit in registers through the steps where they are scarcest.
+    int lane = lane_in;
+    asm volatile("" : "+v"(lane));
+    const uint32_t m = len - off < PACKED_TILE ? len - off : PACKED_TILE;
+    const uint32_t nw = packed_tile_words(m, w);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+        if ((uint32_t)(WAVE * q) < nw + 2u) buf[lane + WAVE * q] = r[q];     // words from nw on are zeros: a field may reach one word further
+    if (lane < 2) buf[PACKED_TILE + lane] = 0;
+    wave_sync_lds();
+    const uint32_t mask = w >= 32u ? 0xFFFFFFFFu : (1u << w) - 1u;
+    uint32_t run = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t i = 4u * (uint32_t)lane + (uint32_t)q;
+        uint32_t d = 0;
+        if (i == 0) {
+            d = buf[0];
+        } else if (i < m && w > 0) {
+            const uint32_t bit = (i - 1u) * w, j = 1u + (bit >> 5), sh = bit & 31u;
+            d = (uint32_t)((((uint64_t)buf[j + 1] << 32) | buf[j]) >> sh) & mask;
+        }
+        run += d;
+        v[q] = run;
+    }
+    // Inclusive sums of the lanes' totals over the wavefront with data-parallel shifts: within each row of
+    // 16 lanes by 1, 2, 4 and 8 (a lane without a source adds 0), then lane 15 of rows 0 and 2 goes to the
+    // row after it, then lane 31 to the upper 32 lanes.
+    uint32_t below = run;
+    below += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)below, 0x111, 0xf, 0xf, false);    // row_shr:1
+    below += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)below, 0x112, 0xf, 0xf, false);    // row_shr:2
+    below += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)below, 0x114, 0xf, 0xf, false);    // row_shr:4
+    below += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)below, 0x118, 0xf, 0xf, false);    // row_shr:8
+    below += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)below, 0x142, 0xa, 0xf, false);    // row_bcast:15 into rows 1 and 3
+    below += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)below, 0x143, 0xc, 0xf, false);    // row_bcast:31 into rows 2 and 3
+    below -= run;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) v[q] += below;
+    wave_sync_lds();
+}
+
 // Minimum over lanes that are a power of two apart, without the LDS: the upper half of the
 // wavefront comes down with a lane swap, the upper 16 of 32 lanes with a swizzle, smaller
 // distances with data-parallel row shifts.  After min_from_above<D> lane i (i mod 2D < D) holds
@@ -1492,11 +1614,15 @@ __device__ __forceinline__ uint32_t wave_min(uint32_t v)
 }
 
 // ------------------------------------------------------------------ the hash kernel
-template <class Pol, int NF>
+// PACKED: the rows arrive as tiles of differences (a.pk_*) instead of a.col_idx; a tile of that form is a
+// staging tile, so its words are what is requested ahead and it is decoded while it is staged.
+template <class Pol, int NF, bool PACKED>
 __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_WAVES, 8))) void mh_hash_kernel(KArgs a)
 {
     __shared__ uint32_t s_tile[WAVES_PER_BLOCK][Pol::NW][TILE];
     __shared__ uint32_t s_mins[WAVES_PER_BLOCK][HASH_FTILE];
+    using RunItems = RunItemsT<PACKED>;
+    using Unit = UnitT<PACKED>;
     __shared__ RunItems s_items[WAVES_PER_BLOCK];
 
     const int lane = threadIdx.x & (WAVE - 1);
@@ -1522,13 +1648,18 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
     // The first nonzeros of a unit are requested before the unit starts: for the first unit
     // right here, for later ones during the last tile of the unit before (when the next unit
     // belongs to the same run of the work list) or after a new run has been fetched.
-    UnitStream units;
+    UnitStreamT<PACKED> units;
     Unit cur;
     uint32_t regs[4];
+    // the first tile of a unit: its nonzeros, or the words they are packed in
+    auto request_first_tile = [&](const Unit& u) {
+        if (u.len == 0) return;
+        if constexpr (PACKED) load_packed_tile(a, u.wbegin, u.w, u.len, 0, lane, regs);
+        else load_tile(a.col_idx, u.begin, u.len, 0, walk_of(u.len < (uint32_t)TILE ? u.len : (uint32_t)TILE, n_slices).extent, lane, regs);
+    };
     bool have = units.init(a, n_units, (uint64_t)n_long * (uint64_t)a.n_ftiles, gridDim.x * WAVES_PER_BLOCK,
                            blockIdx.x * WAVES_PER_BLOCK + wave, n_long, lane, run_items, &cur);
-    if (have && cur.len > 0)
-        load_tile(a.col_idx, cur.begin, cur.len, 0, walk_of(cur.len < (uint32_t)TILE ? cur.len : (uint32_t)TILE, n_slices).extent, lane, regs);
+    if (have) request_first_tile(cur);
     while (have) {
         const int ftile = cur.ftile;
         const int j_base = ftile * a.ftile_size + fl * NF;
@@ -1545,6 +1676,12 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
         const int64_t begin = cur.begin;
         const uint32_t len = cur.len;
         const uint32_t unit_row = cur.row, unit_slot = cur.slot;
+        int64_t unit_wbegin = 0;
+        uint32_t unit_w = 0;
+        if constexpr (PACKED) {
+            unit_wbegin = cur.wbegin;
+            unit_w = cur.w;
+        }
         Unit nxt;
         bool have_next = false;        // the next unit is known and its first tile is on its way
 
@@ -1561,30 +1698,49 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                 const uint32_t in_tile = len - off < (uint32_t)TILE ? len - off : (uint32_t)TILE;
                 const TileWalk walk = walk_of(in_tile, n_slices);
                 const int n_steps = walk.n_steps, extent = walk.extent;
-                // stage: pre-compute what depends on t alone, one nonzero per lane and register
+                // stage: pre-compute what depends on t alone
+                if constexpr (PACKED) {
+                    uint32_t vals[4];  // lane l decodes nonzeros 4l .. 4l+3 of the tile (all 256 entries get a value)
+                    decode_packed_tile(mins, regs, unit_w, len, off, lane, vals);
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (WAVE * q >= extent) break;               // wavefront-uniform: never read, not staged
-                    uint32_t t = regs[q];
-                    if (a.validate && (uint64_t)t >= a.D) {
-                        atomicOr(&a.hdr->status, 2u);
-                        t = 0;
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t t = vals[q];
+                        if (a.validate && (uint64_t)t >= a.D) {
+                            atomicOr(&a.hdr->status, 2u);
+                            t = 0;
+                        }
+                        uint32_t w[Pol::NW];
+                        Pol::stage(t, w);
+#pragma unroll
+                        for (int i = 0; i < Pol::NW; ++i) tile[i][4 * lane + q] = w[i];
                     }
-                    uint32_t w[Pol::NW];
-                    Pol::stage(t, w);
+                } else {               // one nonzero per lane and register
 #pragma unroll
-                    for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
+                    for (int q = 0; q < 4; ++q) {
+                        if (WAVE * q >= extent) break;               // wavefront-uniform: never read, not staged
+                        uint32_t t = regs[q];
+                        if (a.validate && (uint64_t)t >= a.D) {
+                            atomicOr(&a.hdr->status, 2u);
+                            t = 0;
+                        }
+                        uint32_t w[Pol::NW];
+                        Pol::stage(t, w);
+#pragma unroll
+                        for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
+                    }
                 }
                 wave_sync_lds();
                 if (off + TILE < len) {
-                    const uint32_t rest = len - off - TILE;
-                    load_tile(a.col_idx, begin, len, off + TILE, walk_of(rest < (uint32_t)TILE ? rest : (uint32_t)TILE, n_slices).extent,
-                              lane, regs);
+                    if constexpr (PACKED) {
+                        load_packed_tile(a, unit_wbegin, unit_w, len, off + TILE, lane, regs);
+                    } else {
+                        const uint32_t rest = len - off - TILE;
+                        load_tile(a.col_idx, begin, len, off + TILE, walk_of(rest < (uint32_t)TILE ? rest : (uint32_t)TILE, n_slices).extent,
+                                  lane, regs);
+                    }
                 } else {               // last tile: the registers are free for the first tile of the next unit
                     have_next = units.peek_and_take(run_items, &nxt);
-                    if (have_next && nxt.len > 0)
-                        load_tile(a.col_idx, nxt.begin, nxt.len, 0,
-                                  walk_of(nxt.len < (uint32_t)TILE ? nxt.len : (uint32_t)TILE, n_slices).extent, lane, regs);
+                    if (have_next) request_first_tile(nxt);
                 }
 
                 for (int s = 0; s < n_steps; ++s) {
@@ -1643,7 +1799,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                 // evaluates that one function on all nonzeros of the item, a lane each, and the
                 // owner takes the minimum (over the whole item, which its slice is part of).
                 uint64_t owners = __builtin_amdgcn_ballot_w64(doubt != 0u);      // doubt is 0 in every lane unless the test above fired
-                if (owners != 0ull && len <= SHORT_ITEM) {
+                if (!PACKED && owners != 0ull && len <= SHORT_ITEM) {
                     // A short item makes many of its values doubtful (few evaluations stand behind
                     // each) and is cheap to go through: every lane sees to its own values.
                     for (uint32_t which = doubt; which; which &= which - 1) {
@@ -1677,11 +1833,29 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                         if (j0 + r >= a.k) continue;                    // an unused slot: never stored
                         const uint64_t* c = static_cast<const uint64_t*>(a.params) + (size_t)(j0 + r) * Pol::DEG;
                         uint32_t best = EMPTY_MIN;
-                        for (uint32_t e = (uint32_t)lane; e < len; e += WAVE) {
-                            uint32_t t = a.col_idx[begin + e];
-                            if (a.validate && (uint64_t)t >= a.D) t = 0;
-                            const uint32_t h = Pol::exact_hash(c, t, a.md, a.D);
-                            best = h < best ? h : best;
+                        if constexpr (PACKED) {    // the item's tiles once more (the registers of the main loop may hold the next unit's words)
+                            for (uint32_t off2 = 0; off2 < len; off2 += TILE) {
+                                uint32_t words2[4], vals[4];
+                                load_packed_tile(a, unit_wbegin, unit_w, len, off2, lane, words2);
+                                decode_packed_tile(mins, words2, unit_w, len, off2, lane, vals);
+                                *reinterpret_cast<uint4*>(&tile[0][4 * lane]) = uint4{vals[0], vals[1], vals[2], vals[3]};
+                                wave_sync_lds();
+#pragma unroll 1
+                                for (int e = lane; e < TILE; e += WAVE) {      // entries past the end repeat the last nonzero: harmless
+                                    uint32_t t = tile[0][e];
+                                    if (a.validate && (uint64_t)t >= a.D) t = 0;
+                                    const uint32_t h = Pol::exact_hash(c, t, a.md, a.D);
+                                    best = h < best ? h : best;
+                                }
+                                wave_sync_lds();
+                            }
+                        } else {
+                            for (uint32_t e = (uint32_t)lane; e < len; e += WAVE) {
+                                uint32_t t = a.col_idx[begin + e];
+                                if (a.validate && (uint64_t)t >= a.D) t = 0;
+                                const uint32_t h = Pol::exact_hash(c, t, a.md, a.D);
+                                best = h < best ? h : best;
+                            }
                         }
                         best = wave_min(best);
                         if (lane == owner) {
@@ -1754,9 +1928,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
             cur = nxt;
         } else {
             have = units.advance(a, n_long, lane, run_items, &cur);
-            if (have && cur.len > 0)
-                load_tile(a.col_idx, cur.begin, cur.len, 0, walk_of(cur.len < (uint32_t)TILE ? cur.len : (uint32_t)TILE, n_slices).extent,
-                          lane, regs);
+            if (have) request_first_tile(cur);
         }
     }
 }
@@ -1772,6 +1944,8 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
 {
     __shared__ uint32_t s_tile[WAVES_PER_BLOCK][TILE];
     __shared__ uint32_t s_mins[WAVES_PER_BLOCK][PERM_FTILE];
+    using RunItems = RunItemsT<false>;
+    using Unit = UnitT<false>;
     __shared__ RunItems s_items[WAVES_PER_BLOCK];
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1787,7 +1961,7 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
 
     // the steps read whole groups of U entries: what a tile of n nonzeros needs staged
     auto extent_of = [](uint32_t n) { return (int)(((n < (uint32_t)TILE ? n : (uint32_t)TILE) + U - 1) / U * U); };
-    UnitStream units;
+    UnitStreamT<false> units;
     Unit cur;
     uint32_t regs[4];
     bool have = units.init(a, n_units, (uint64_t)n_long * (uint64_t)a.n_ftiles, gridDim.x * WAVES_PER_BLOCK,
@@ -2017,12 +2191,18 @@ struct Launch {                        // where a call's kernels go
     hipStream_t s;
 };
 
+template <class Pol, int NF, bool PACKED>
+void launch_hash_form(const KArgs& a, const Launch& l)
+{
+    static std::atomic<int> cache[MAX_DEVICES];
+    const int blocks = resident_blocks(mh_hash_kernel<Pol, NF, PACKED>, l.dev, l.cus, cache);
+    hipLaunchKernelGGL((mh_hash_kernel<Pol, NF, PACKED>), dim3(blocks), dim3(BLOCK), 0, l.s, a);
+}
 template <class Pol, int NF>
 void launch_hash_nf(const KArgs& a, const Launch& l)
 {
-    static std::atomic<int> cache[MAX_DEVICES];
-    const int blocks = resident_blocks(mh_hash_kernel<Pol, NF>, l.dev, l.cus, cache);
-    hipLaunchKernelGGL((mh_hash_kernel<Pol, NF>), dim3(blocks), dim3(BLOCK), 0, l.s, a);
+    if (a.pk_words) launch_hash_form<Pol, NF, true>(a, l);       // rows given as tiles of differences
+    else launch_hash_form<Pol, NF, false>(a, l);
 }
 // nf = functions per lane of this launch (see functions_per_lane); the hand-ordered
 // policies exist for 5..8, the compiler-scheduled ones for 8 only
@@ -2375,6 +2555,35 @@ int minhash_signatures_static(const int64_t* row_ptr, const uint32_t* col_idx, i
                    nnz_upper_bound, flags, reserve);
     if (rc != MINHASH_OK) return rc;
     return enqueue(plan, family, D, flags, stream, nullptr, false, status);
+}
+
+int minhash_signatures_packed(const int64_t* row_ptr, const uint32_t* width, const int64_t* word_ptr, const uint32_t* words,
+                              int64_t words_len, int64_t n_rows, uint64_t D, int32_t k, int32_t b, int32_t family,
+                              const void* params, uint8_t* out, int64_t out_stride, void* workspace, size_t workspace_bytes,
+                              void* stream, uint32_t flags)
+{
+    if (family == MINHASH_PERM) return MINHASH_ERR_FAMILY;       // the table kernel takes col_idx: unpack first
+    bool empty = false;
+    int rc = check_arguments(row_ptr, n_rows, D, k, b, family, params, 0, out, out_stride, flags, &empty);
+    if (rc != MINHASH_OK) return rc;
+    if (words_len < 0) return MINHASH_ERR_ARG;
+    if (empty) return MINHASH_OK;
+    if (!width || !word_ptr || !words) return MINHASH_ERR_ARG;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % MINHASH_WORKSPACE_ALIGN) != 0) return MINHASH_ERR_WORKSPACE;
+    if (workspace_bytes < make_layout(n_rows, 0, k).total) return MINHASH_ERR_WORKSPACE;
+    int64_t lo = 0, hi = (int64_t)1 << 46;
+    while (lo < hi) {                              // largest nnz bound whose layout fits
+        int64_t mid = lo + (hi - lo + 1) / 2;
+        if (make_layout(n_rows, mid, k).total <= workspace_bytes) lo = mid; else hi = mid - 1;
+    }
+    Plan plan;
+    rc = make_plan(&plan, row_ptr, nullptr, n_rows, D, k, b, family, params, 0, out, out_stride, workspace, lo, flags);
+    if (rc != MINHASH_OK) return rc;
+    plan.a.pk_width = width;
+    plan.a.pk_word_ptr = word_ptr;
+    plan.a.pk_words = words;
+    plan.a.pk_words_len = words_len;
+    return enqueue(plan, family, D, flags, stream, nullptr, false, nullptr);
 }
 
 size_t minhash_workspace_bytes(int64_t n_rows, int64_t nnz_upper_bound, int32_t k, int32_t family)

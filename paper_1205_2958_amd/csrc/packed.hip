@@ -25,6 +25,7 @@
 #include <stdint.h>
 
 #include "minhash.h"
+#include "mh_arith.h"
 #include "mh_host.h"
 
 namespace {
@@ -32,10 +33,10 @@ namespace {
 constexpr int WAVE = 64;
 constexpr int BLOCK = 256;
 constexpr int WAVES_PER_BLOCK = BLOCK / WAVE;
-constexpr uint32_t PK_TILE = 256;
+constexpr uint32_t PK_TILE = mh::PACKED_TILE;
 constexpr int64_t SPAN = 4096;
 
-__host__ __device__ inline uint32_t tile_words(uint32_t m, uint32_t w) { return 1u + ((m - 1u) * w + 31u) / 32u; }
+__host__ __device__ inline uint32_t tile_words(uint32_t m, uint32_t w) { return mh::packed_tile_words(m, w); }
 __host__ __device__ inline uint64_t row_words(uint64_t n, uint32_t w)
 {
     const uint64_t full = n / PK_TILE;

@@ -39,6 +39,7 @@ EXPORTS = (
     "minhash_status",
     "minhash_pack_indices",
     "minhash_unpack_indices",
+    "minhash_signatures_packed",
     "minhash_expand_indices",
     "minhash_match_counts",
     "minhash_resemblance_estimates",
@@ -87,6 +88,8 @@ def lib() -> ctypes.CDLL:
         L.minhash_pack_indices.restype = ctypes.c_int
         L.minhash_unpack_indices.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp]
         L.minhash_unpack_indices.restype = ctypes.c_int
+        L.minhash_signatures_packed.argtypes = [vp, vp, vp, vp, i64, i64, u64, i32, i32, i32, vp, vp, i64, vp, sz, vp, u32]
+        L.minhash_signatures_packed.restype = ctypes.c_int
         L.minhash_expand_indices.argtypes = [vp, i64, i64, i32, i32, vp, vp]
         L.minhash_expand_indices.restype = ctypes.c_int
         L.minhash_match_counts.argtypes = [vp, i64, i64, i32, i32, vp, i64, vp, vp]
@@ -306,6 +309,39 @@ def unpack_indices(row_ptr: torch.Tensor, width: torch.Tensor, word_ptr: torch.T
     return out
 
 
+def minhash_signatures_packed(row_ptr: torch.Tensor, width: torch.Tensor, word_ptr: torch.Tensor, words: torch.Tensor, D: int,
+                              k: int, b: int, family: int, params: torch.Tensor, out: Optional[torch.Tensor] = None,
+                              workspace: Optional[torch.Tensor] = None, nnz_upper_bound: Optional[int] = None, stream=None,
+                              flags: int = 0) -> torch.Tensor:
+    """Signatures of rows given as tiles of differences (``pack_indices``), decoded inside the hash
+    kernels.  ``nnz_upper_bound`` sizes the workspace when none is passed (a tile never takes more
+    words than it has indices, but it may take fewer, so the word count is no bound); without it the
+    last entry of row_ptr is read from the device.  Does not synchronise otherwise."""
+    for t in (width, word_ptr, words, params):
+        if not t.is_contiguous() or t.device != row_ptr.device:
+            raise TypeError("arrays must be contiguous tensors on the device of row_ptr")
+    if row_ptr.dtype != torch.int64 or word_ptr.dtype != torch.int64 or width.element_size() != 4 or words.element_size() != 4:
+        raise TypeError("row_ptr and word_ptr are int64, width and words hold 4-byte elements")
+    if params.element_size() != 8:
+        raise TypeError("params must hold uint64 coefficients")
+    n = row_ptr.numel() - 1
+    sig = (k * b + 7) // 8
+    if out is None:
+        out = torch.empty((n, sig), dtype=torch.uint8, device=row_ptr.device)
+    else:
+        _check_out(out, row_ptr)
+    if workspace is None:
+        if nnz_upper_bound is None:
+            nnz_upper_bound = int((row_ptr[-1] - row_ptr[0]).item()) if n > 0 else 0
+        workspace = alloc_workspace(n, nnz_upper_bound, k, family, row_ptr.device)
+    rc = lib().minhash_signatures_packed(_ptr(row_ptr), _ptr(width), _ptr(word_ptr), _ptr(words), words.numel(), n, D, k, b,
+                                         family, _ptr(params), _ptr(out), out.shape[1], _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream_handle(stream), flags)
+    if rc != 0:
+        _raise(rc)
+    return out
+
+
 def expand_indices(sig: torch.Tensor, k: int, b: int, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     """int32-storage [n_rows, k] tensor of uint32 positions j*2^b + s_ij (see include/minhash.h)."""
     n = sig.shape[0]
@@ -443,7 +479,7 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
 
 
 def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: torch.Tensor, max_rows: int, max_nnz: int,
-                          max_words: int, flags: int = 0):
+                          max_words: int, flags: int = 0, decode_in_kernel: bool = True):
     """``stream_batches`` for rows that cross the host link as tiles of differences
     (``pack_indices``): about half the bytes for sorted heavy-tailed rows, so that
     the copies hide under the kernels again.
@@ -455,6 +491,10 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
     wait for the persistent hash kernel of the batch before anyway, and start late),
     signatures back on a third; two sets of packed buffers alternate.  Returns the
     pinned uint8 host tensors [n_rows_i, ceil(k*b/8)], complete on return.
+
+    With ``decode_in_kernel`` (the default) there is no decoder pass at all: the
+    hash kernels fetch the words and decode each tile while they stage it
+    (``minhash_signatures_packed``).
     """
     dev = params.device
     sig = (k * b + 7) // 8
@@ -463,7 +503,7 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
     wp_d = [torch.empty(max_rows + 1, dtype=torch.int64, device=dev) for _ in range(n_buf)]
     wd_d = [torch.empty(max(max_rows, 1), dtype=torch.int32, device=dev) for _ in range(n_buf)]
     words_d = [torch.empty(max(max_words, 1), dtype=torch.int32, device=dev) for _ in range(n_buf)]
-    col_d = torch.empty(max(max_nnz, 1), dtype=torch.int32, device=dev)      # decoded and hashed on one stream: one buffer
+    col_d = None if decode_in_kernel else torch.empty(max(max_nnz, 1), dtype=torch.int32, device=dev)    # one stream: one buffer
     out_d = [torch.empty((max_rows, sig), dtype=torch.uint8, device=dev) for _ in range(n_buf)]
     codes = torch.zeros(max(len(batches), 1), dtype=torch.int32, device=dev)
     ws = alloc_workspace(max_rows, max_nnz, k, family, dev)
@@ -499,9 +539,14 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
         s_run.wait_event(in_done[u])
         if i >= n_buf:
             s_run.wait_event(out_done[u])         # the previous signatures left this output buffer
-        unpack_indices(rp_d[u][: n + 1], wd_d[u][:n], wp_d[u][: n + 1], words_d[u][:n_words], col_d, codes[i: i + 1], stream=s_run)
-        minhash_signatures(rp_d[u][: n + 1], col_d[:nnz], D, k, b, family, params, out=out_d[u][:n],
-                           out_stride=sig, workspace=ws, stream=s_run, flags=flags)
+        if decode_in_kernel:
+            minhash_signatures_packed(rp_d[u][: n + 1], wd_d[u][:n], wp_d[u][: n + 1], words_d[u][:n_words], D, k, b, family, params,
+                                      out=out_d[u][:n], workspace=ws, stream=s_run, flags=flags)
+        else:
+            unpack_indices(rp_d[u][: n + 1], wd_d[u][:n], wp_d[u][: n + 1], words_d[u][:n_words], col_d, codes[i: i + 1],
+                           stream=s_run)
+            minhash_signatures(rp_d[u][: n + 1], col_d[:nnz], D, k, b, family, params, out=out_d[u][:n],
+                               out_stride=sig, workspace=ws, stream=s_run, flags=flags)
         run_done[u].record(s_run)
         s_out.wait_event(run_done[u])
         with torch.cuda.stream(s_out):

@@ -168,6 +168,22 @@ def test_packed_row_entry_points_validate_before_any_launch(lib):
     assert lib.minhash_unpack_indices(P, P, P, P, -1, 4, P, P, 0) == -1
     assert lib.minhash_unpack_indices(P, P, P, P, 10, 4, 0, P, 0) == -1
     assert lib.minhash_unpack_indices(P, P, P, P, 10, 4, P, 0, 0) == -1
+    u64, i32, sz, u32 = ctypes.c_uint64, ctypes.c_int32, ctypes.c_size_t, ctypes.c_uint32
+    lib.minhash_signatures_packed.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int64] * 2 + [u64, i32, i32, i32, ctypes.c_void_p,
+                                                                                         ctypes.c_void_p, ctypes.c_int64,
+                                                                                         ctypes.c_void_p, sz, ctypes.c_void_p, u32]
+    call = lambda **kw: lib.minhash_signatures_packed(*[kw.get(n, d) for n, d in (
+        ("row_ptr", P), ("width", P), ("word_ptr", P), ("words", P), ("words_len", 100), ("n_rows", 4), ("D", 1 << 24), ("k", 64),
+        ("b", 8), ("family", 0), ("params", P), ("out", P), ("out_stride", 64), ("ws", P), ("ws_bytes", 1 << 20), ("stream", 0),
+        ("flags", 0))])
+    assert call(family=mh.FAMILY_PERM) == -2                      # the table kernel takes col_idx
+    assert call(words_len=-1) == -1
+    assert call(width=0) == -1
+    assert call(words=0) == -1
+    assert call(n_rows=0) == 0
+    assert call(D=0) == -3
+    assert call(out_stride=63) == -5
+    assert call(ws=0) == -6
 
 
 def test_profiled_entry_point_validates_the_same_way(lib):

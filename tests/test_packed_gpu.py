@@ -156,7 +156,90 @@ def test_streamed_packed_batches_equal_the_oracle():
         max_words = max(max_words, words.numel())
     max_rows = max(h - l for l, h in zip(bounds[:-1], bounds[1:]))
     max_nnz = max(int(rp[h] - rp[l]) for l, h in zip(bounds[:-1], bounds[1:]))
-    outs = mh.stream_batches_packed(batches, D, k, b, family, torch.from_numpy(c.view(np.int64)).to(DEV), max_rows, max_nnz,
-                                    max_words)
-    got = np.concatenate([o.numpy() for o in outs], axis=0)
-    assert np.array_equal(got, want)
+    for decode_in_kernel in (True, False):
+        outs = mh.stream_batches_packed(batches, D, k, b, family, torch.from_numpy(c.view(np.int64)).to(DEV), max_rows, max_nnz,
+                                        max_words, decode_in_kernel=decode_in_kernel)
+        got = np.concatenate([o.numpy() for o in outs], axis=0)
+        assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ decoded inside the hash kernels
+EDGE_NNZ = [0, 1, 2, 3, 4, 5, 7, 8, 9, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1000, 0, 4095, 8191, 8192, 8193, 16384,
+            16385, 20000, 1, 0, 50000]
+
+
+def _packed_signatures(rp, col, D, k, b, family, c, flags=0):
+    rp_d = _dev(rp)
+    width, word_ptr, words = mh.pack_indices(rp_d, _dev(col))
+    n = rp.shape[0] - 1
+    out = torch.full((n, (k * b + 7) // 8), 0xAA, dtype=torch.uint8, device=DEV)
+    ws = mh.alloc_workspace(n, int(col.shape[0]), k, family, DEV)
+    ws.fill_(0xCD)
+    mh.minhash_signatures_packed(rp_d, width, word_ptr, words, D, k, b, family, torch.from_numpy(c.view(np.int64)).to(DEV),
+                                 out=out, workspace=ws, flags=flags)
+    st = mh.status(ws)
+    return out.cpu().numpy(), st
+
+
+@pytest.mark.parametrize("family,D,k,b", [
+    (mh.FAMILY_2U_M31, 1 << 24, 500, 8),          # one maximum of a doubled key: second looks read the tiles again
+    (mh.FAMILY_2U_M31, 1 << 30, 500, 8),          # two maxima
+    (mh.FAMILY_4U_M31, 1 << 24, 500, 8),
+    (mh.FAMILY_2U_M61, 1 << 30, 500, 1),
+    (mh.FAMILY_4U_M61, 1 << 30, 100, 2),
+    (mh.FAMILY_2U_MS32, 1 << 24, 500, 8),
+    (mh.FAMILY_2U_M31, 16609143, 500, 8),
+    (mh.FAMILY_4U_M31, 1010017424, 500, 8),
+    (mh.FAMILY_2U_M31, 1 << 24, 64, 8),           # eight slices of the nonzeros per tile
+    (mh.FAMILY_2U_M31, 1 << 24, 200, 12),         # seven functions per lane, fields that straddle bytes
+    (mh.FAMILY_2U_M61, 1 << 30, 1030, 1),         # three function tiles per row
+])
+def test_signatures_decoded_in_the_kernel_equal_the_oracle(family, D, k, b):
+    nnz = np.minimum(np.array(EDGE_NNZ, dtype=np.int64), D)
+    rp = W.row_ptr_from_nnz(nnz)
+    gen_D = D if D & (D - 1) == 0 else 1 << 30
+    col = W.csr_indices_np(nnz, gen_D, seed=400 + family + k)
+    if gen_D != D:                                   # fold into [0, D) and sort again: the packed form needs sorted rows
+        col = (col % np.uint32(D)).astype(np.uint32)
+        col = np.concatenate([np.sort(col[rp[r]:rp[r + 1]]) for r in range(len(nnz))])
+    c = W.coefficients(k, family, seed=500 + k)
+    got, st = _packed_signatures(rp, col, D, k, b, family, c)
+    assert st == 0
+    want = oracle.signatures(rp, col, D, k, b, family, c)
+    if not np.array_equal(got, want):
+        bad = np.flatnonzero((got != want).any(axis=1))
+        raise AssertionError("rows %s differ (nnz %s)" % (bad[:8].tolist(), nnz[bad[:8]].tolist()))
+
+
+def test_very_short_packed_rows_whose_values_are_mostly_doubtful():
+    """Rows of 0 to 40 nonzeros at D = 2^24: most running maxima of the doubled key are doubtful, so
+    nearly every value takes the second look, which reads the packed tile again."""
+    D, k = 1 << 24, 500
+    nnz = np.array(list(range(0, 41)) * 3, dtype=np.int64)
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed=909)
+    for family, b in ((mh.FAMILY_2U_M31, 8), (mh.FAMILY_2U_M61, 1)):
+        c = W.coefficients(k, family, seed=910)
+        got, st = _packed_signatures(rp, col, D, k, b, family, c)
+        assert st == 0 and np.array_equal(got, oracle.signatures(rp, col, D, k, b, family, c))
+
+
+def test_packed_input_that_does_not_fit_its_word_array_is_reported_not_followed():
+    D, k, family = 1 << 24, 64, mh.FAMILY_2U_M31
+    nnz = np.array([600, 300, 5], dtype=np.int64)
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed=3)
+    c = torch.from_numpy(W.coefficients(k, family, seed=4).view(np.int64)).to(DEV)
+    rp_d = _dev(rp)
+    width, word_ptr, words = mh.pack_indices(rp_d, _dev(col))
+    ws = mh.alloc_workspace(3, 905, k, family, DEV)
+    # the word array handed over is shorter than the offsets say
+    mh.minhash_signatures_packed(rp_d, width, word_ptr, words[: words.numel() - 5].contiguous(), D, k, 8, family, c, workspace=ws)
+    assert mh.status(ws) == -9
+    # a width that is no width
+    bad = width.clone()
+    bad[1] = 40
+    mh.minhash_signatures_packed(rp_d, bad, word_ptr, words, D, k, 8, family, c, workspace=ws)
+    assert mh.status(ws) == -9
+    # and the permutation table is not served this way
+    with pytest.raises(mh.MinhashError) as e:
+        mh.minhash_signatures_packed(rp_d, width, word_ptr, words, D, k, 8, mh.FAMILY_PERM, c, workspace=ws)
+    assert e.value.code == -2
