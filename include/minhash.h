@@ -229,7 +229,8 @@ int minhash_status(const void *workspace, void *stream);
  * buffers) in *status (device, one int32, required).  row_ptr must be
  * non-decreasing. */
 
-/* col_idx -> (width[n_rows], word_ptr[n_rows+1], words[<= words_capacity]). */
+/* col_idx -> (width[n_rows], word_ptr[n_rows+1], words[<= words_capacity]).  With words_capacity 0 (no row
+ * has an index) col_idx and words may be null; neither is then read or written. */
 int minhash_pack_indices(const int64_t *row_ptr, const uint32_t *col_idx, int64_t n_rows,
                          uint32_t *width, int64_t *word_ptr, uint32_t *words, int64_t words_capacity,
                          int32_t *status, void *stream);
@@ -247,7 +248,8 @@ int minhash_unpack_indices(const int64_t *row_ptr, const uint32_t *width, const 
  * MINHASH_PERM is not served this way (MINHASH_ERR_FAMILY: unpack first).  A width above 32 or a tile
  * that would leave words[0 .. words_len) is never followed; minhash_status then reports
  * MINHASH_ERR_DATA and the rows concerned get unspecified signatures.  The workspace is sized with
- * minhash_workspace_bytes for at least row_ptr[n_rows] - row_ptr[0] nonzeros, as for minhash_signatures. */
+ * minhash_workspace_bytes for at least row_ptr[n_rows] - row_ptr[0] nonzeros, as for minhash_signatures.
+ * `words` may be null when words_len is 0 (every row empty), here and in minhash_unpack_indices. */
 int minhash_signatures_packed(const int64_t *row_ptr, const uint32_t *width, const int64_t *word_ptr,
                               const uint32_t *words, int64_t words_len, int64_t n_rows,
                               uint64_t D, int32_t k, int32_t b, int32_t family, const void *params,

@@ -27,6 +27,12 @@ def _oracle_worker(args):
     return oracle.signatures(rp, col, D, k, b, family, params)
 
 
+def _oracle_case_worker(args):
+    from oracle import oracle
+    rp, col, D, k, b, family, params, out_stride = args
+    return oracle.signatures(rp, col, D, k, b, family, params, out_stride)
+
+
 class OraclePool:
     """Worker processes that run the unchanged single-threaded C oracle, one shard of
     rows each.  Forked before this process touches the GPU; jobs are sent later."""
@@ -44,6 +50,11 @@ class OraclePool:
     def close(self):
         self.pool.close()
         self.pool.join()
+
+    def cases_async(self, cases):
+        """Starts one oracle call per case (rp, col, D, k, b, family, params, out_stride), each whole in one
+        worker; returns the pending result, whose get() gives the signature arrays in order."""
+        return self.pool.map_async(_oracle_case_worker, cases, chunksize=1)
 
     def signatures(self, rp, col, D, k, b, family, params, procs=None, table_rows=None):
         """Signatures of all rows of the CSR (rp, col), rows dealt to `procs` shards of

@@ -2568,7 +2568,8 @@ int minhash_signatures_packed(const int64_t* row_ptr, const uint32_t* width, con
     if (rc != MINHASH_OK) return rc;
     if (words_len < 0) return MINHASH_ERR_ARG;
     if (empty) return MINHASH_OK;
-    if (!width || !word_ptr || !words) return MINHASH_ERR_ARG;
+    if (!width || !word_ptr || (!words && words_len > 0)) return MINHASH_ERR_ARG;
+    if (!words) words = reinterpret_cast<const uint32_t*>(word_ptr);      // no words at all (every row empty): any address will do, none is read
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) % MINHASH_WORKSPACE_ALIGN) != 0) return MINHASH_ERR_WORKSPACE;
     if (workspace_bytes < make_layout(n_rows, 0, k).total) return MINHASH_ERR_WORKSPACE;
     int64_t lo = 0, hi = (int64_t)1 << 46;

@@ -261,7 +261,8 @@ int minhash_pack_indices(const int64_t* row_ptr, const uint32_t* col_idx, int64_
                          uint32_t* words, int64_t words_capacity, int32_t* status, void* stream)
 {
     if (n_rows < 0 || n_rows >= (1ll << 31) || words_capacity < 0) return MINHASH_ERR_ARG;
-    if (!row_ptr || !word_ptr || !status || (n_rows > 0 && (!width || !col_idx || !words))) return MINHASH_ERR_ARG;
+    // without capacity there are no indices to pack (anything else is reported by the kernels): col_idx and words may then be null
+    if (!row_ptr || !word_ptr || !status || (n_rows > 0 && (!width || (words_capacity > 0 && (!col_idx || !words))))) return MINHASH_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     (void)hipGetLastError();
     uint32_t* flags = reinterpret_cast<uint32_t*>(status);     // the status word doubles as the flag word until the last kernel
@@ -269,7 +270,8 @@ int minhash_pack_indices(const int64_t* row_ptr, const uint32_t* col_idx, int64_
     if (n_rows > 0) {
         const int blocks = grid_blocks();
         hipLaunchKernelGGL(pk_fill_kernel, dim3(blocks), dim3(BLOCK), 0, s, width, n_rows, 0u);
-        hipLaunchKernelGGL(pk_width_kernel, dim3(blocks), dim3(BLOCK), 0, s, row_ptr, col_idx, n_rows, width, flags);
+        if (words_capacity > 0)       // (with no capacity every tile is reported by the packing kernel before it reads an index)
+            hipLaunchKernelGGL(pk_width_kernel, dim3(blocks), dim3(BLOCK), 0, s, row_ptr, col_idx, n_rows, width, flags);
         hipLaunchKernelGGL(pk_offsets_kernel, dim3(1), dim3(SCAN_BLOCK), 0, s, row_ptr, width, n_rows, word_ptr);
         hipLaunchKernelGGL(pk_pack_kernel, dim3(blocks), dim3(BLOCK), 0, s, row_ptr, col_idx, n_rows, width, word_ptr, words,
                            words_capacity, flags);
@@ -284,7 +286,7 @@ int minhash_unpack_indices(const int64_t* row_ptr, const uint32_t* width, const 
                            int64_t words_len, int64_t n_rows, uint32_t* col_idx, int32_t* status, void* stream)
 {
     if (n_rows < 0 || n_rows >= (1ll << 31) || words_len < 0) return MINHASH_ERR_ARG;
-    if (!row_ptr || !status || (n_rows > 0 && (!width || !word_ptr || !words || !col_idx))) return MINHASH_ERR_ARG;
+    if (!row_ptr || !status || (n_rows > 0 && (!width || !word_ptr || (!words && words_len > 0) || !col_idx))) return MINHASH_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     (void)hipGetLastError();
     uint32_t* flags = reinterpret_cast<uint32_t*>(status);

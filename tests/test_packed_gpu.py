@@ -223,6 +223,30 @@ def test_very_short_packed_rows_whose_values_are_mostly_doubtful():
         assert st == 0 and np.array_equal(got, oracle.signatures(rp, col, D, k, b, family, c))
 
 
+def test_packed_batch_of_empty_rows_has_no_words_and_is_still_served():
+    """Every row empty: the word array has length 0 (a null pointer from the binding); the rows get
+    the signature of the empty set, and unpacking writes nothing."""
+    D, k, b, family = 71, 257, 3, mh.FAMILY_2U_M31
+    nnz = np.zeros(3, dtype=np.int64)
+    rp, col = W.row_ptr_from_nnz(nnz), np.zeros(0, dtype=np.uint32)
+    c = W.coefficients(k, family, seed=12)
+    rp_d = _dev(rp)
+    width, word_ptr, words = mh.pack_indices(rp_d, torch.zeros(1, dtype=torch.int32, device=DEV)[:0])
+    assert words.numel() == 0 and int(word_ptr[-1].item()) == 0
+    n = 3
+    out = torch.full((n, (k * b + 7) // 8), 0xAA, dtype=torch.uint8, device=DEV)
+    ws = mh.alloc_workspace(n, 0, k, family, DEV)
+    mh.minhash_signatures_packed(rp_d, width, word_ptr, words, D, k, b, family, torch.from_numpy(c.view(np.int64)).to(DEV),
+                                 out=out, workspace=ws)
+    assert mh.status(ws) == 0
+    assert np.array_equal(out.cpu().numpy(), oracle.signatures(rp, col, D, k, b, family, c))
+    st = torch.full((1,), 99, dtype=torch.int32, device=DEV)
+    sink = torch.full((4,), 0x5A5A5A5A, dtype=torch.int32, device=DEV)
+    mh.unpack_indices(rp_d, width, word_ptr, words, sink, st)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0 and bool((sink == 0x5A5A5A5A).all())
+
+
 def test_packed_input_that_does_not_fit_its_word_array_is_reported_not_followed():
     D, k, family = 1 << 24, 64, mh.FAMILY_2U_M31
     nnz = np.array([600, 300, 5], dtype=np.int64)
