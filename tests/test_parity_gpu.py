@@ -105,6 +105,16 @@ def test_function_counts(k):
     check_case(rp, col, D, k, 8, mh.FAMILY_2U_M31, W.coefficients(k, mh.FAMILY_2U_M31, seed=k))
 
 
+@pytest.mark.parametrize("family,k,b", [(mh.FAMILY_2U_M31, 4096, 8), (mh.FAMILY_2U_M31, 65536, 1), (mh.FAMILY_2U_M31, 65536, 32),
+                                        (mh.FAMILY_4U_M31, 10000, 3), (mh.FAMILY_2U_M61, 65536, 8), (mh.FAMILY_2U_MS32, 65535, 5)])
+def test_very_many_functions_up_to_the_largest_k(family, k, b):
+    """k up to MINHASH_MAX_K: 128 function tiles per row, signatures of up to 256 KiB, a split row among them."""
+    D = 1 << 24
+    nnz = np.array([0, 1, 5, 300, 0, 9000] if k <= 4096 else [0, 1, 5, 300, 0, 700], dtype=np.int64)
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed=k + b)
+    check_case(rp, col, D, k, b, family, W.coefficients(k, family, seed=k))
+
+
 @pytest.mark.parametrize("family,D", [(mh.FAMILY_2U_M31, 1 << 24), (mh.FAMILY_2U_M31, 16609143), (mh.FAMILY_4U_M31, 1 << 24),
                                       (mh.FAMILY_4U_M31, 16609143), (mh.FAMILY_2U_M61, 1 << 30), (mh.FAMILY_2U_MS32, 1 << 24),
                                       (mh.FAMILY_2U_MS32_HIGH, 1 << 24)])
