@@ -179,6 +179,32 @@ def measure(w: W.Workload, args, pool, dev, cpu_seconds: float, universe: int = 
     ms_per_step = dt / args.steps * 1e3
     status = mh.status(ws)
 
+    # ---- a call this short is launch-bound: the same call captured in a HIP graph and replayed
+    graph_rec = None
+    if ms_per_step < 1.0:
+        eager = out.clone()
+        reps = max(args.steps, 200)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            mh.minhash_signatures(rp, col, D, w.k, w.b, family, params, **call)
+        torch.cuda.synchronize()
+        eager_ms = (time.perf_counter() - t0) / reps * 1e3
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.graph(graph, stream=side):
+            mh.minhash_signatures(rp, col, D, w.k, w.b, family, params, **dict(call, stream=None))
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        same = bool(torch.equal(out, eager))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) / reps * 1e3
+        graph_rec = {"calls": reps, "eager_ms_per_step": eager_ms, "graph_replay_ms_per_step": graph_ms,
+                     "replay_equals_eager": same}
+        del graph, eager
+
     # ---- parity of the sampled rows
     parity = None
     if sample is not None:
@@ -245,6 +271,8 @@ def measure(w: W.Workload, args, pool, dev, cpu_seconds: float, universe: int = 
         "parity_sample_pct_of_evaluations": cover["pct_of_evaluations"] if parity is not None else 0.0,
         "parity_sample_ok": parity,
     }
+    if graph_rec is not None:
+        rec["hip_graph"] = graph_rec
     del col, rp, params, out, ws
     torch.cuda.empty_cache()
     return rec
@@ -597,11 +625,14 @@ def main() -> int:
         "parity_sample_pct_of_evaluations": head["parity_sample_pct_of_evaluations"],
         "parity_sample_ok": head["parity_sample_ok"],
     }
+    if "hip_graph" in head:
+        rec["hip_graph"] = head["hip_graph"]
+        ok = ok and head["hip_graph"]["replay_equals_eager"]
     if args.workload == "all":
         subs = {}
         for name in SUB_WORKLOADS:
             sub = measure(W.WORKLOADS[name], args, pool, dev, args.cpu_seconds / 5.0)
-            ok = ok and sub["parity_sample_ok"] in (None, True)
+            ok = ok and sub["parity_sample_ok"] in (None, True) and sub.get("hip_graph", {}).get("replay_equals_eager", True)
             subs[name] = sub
             print("bench.py: %s done, %.3f ms per step" % (name, sub["ms_per_step"]), file=sys.stderr, flush=True)
         rec["workloads"] = subs
