@@ -72,7 +72,7 @@ constexpr int PERM_FPL = 4;            // permutations per lane (one 16-byte loa
 constexpr int PERM_FTILE = WAVE * PERM_FPL;   // 256
 constexpr int MAX_FTILE = HASH_FTILE;
 constexpr uint32_t MAX_CHUNK = 8192;   // rows longer than the chunk size are split into chunks of that many nonzeros;
-constexpr uint32_t MIN_CHUNK = 512;    // the size is chosen per call on the device (see mh_reset_kernel)
+constexpr uint32_t MIN_CHUNK = 64;     // the size is chosen per call on the device (see mh_reset_kernel), not below chunk_floor(k)
 constexpr uint64_t SMALL_BATCH_PARTS = 32768;           // partial vectors reserved so that small batches can use
 constexpr uint64_t SMALL_BATCH_BYTES = 64ull << 20;     // small chunks, capped to this many bytes
 constexpr uint32_t LONG_ITEM = 2048;   // work items with more nonzeros than this are handed out first
@@ -83,7 +83,7 @@ struct WorkHeader {                    // first 256 bytes of the workspace
     uint32_t n_short;                  // the others: items[cap_long .. cap_long + n_short)
     uint32_t n_split;
     uint32_t n_parts;
-    uint32_t chunk;                    // chunk size of this call, a power of two in [MIN_CHUNK, MAX_CHUNK]
+    uint32_t chunk;                    // chunk size of this call, a power of two in [chunk_floor(k), MAX_CHUNK]
     uint32_t ticket;
     uint32_t status;                   // bit 0: bad row_ptr, bit 1: index >= D, bit 2: work list overflow
     uint32_t pad[57];
@@ -116,12 +116,23 @@ struct Layout {                        // host and device agree on the workspace
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// The smallest chunk a call with k functions may use: a power of two with about 512 evaluations per lane
+// behind every vector of partial minima (k >= 257: 64 nonzeros; 256: 128; 128: 256; up to 64: 512), so
+// that a chunk is worth the k words its partial vector costs to write and to merge.
+inline uint32_t chunk_floor(int32_t k)
+{
+    uint32_t slots = 64;
+    while (slots < 512u && slots < (uint32_t)k) slots *= 2;
+    const uint32_t c = 32768u / slots;
+    return c < MIN_CHUNK ? MIN_CHUNK : c;
+}
+
 inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k, uint64_t reserve_bytes = SMALL_BATCH_BYTES)
 {
     Layout L;
     const uint64_t n = (uint64_t)n_rows, nnz = (uint64_t)nnz_ub;
     L.cap_long = nnz / LONG_ITEM + 1;                                 // items with more than LONG_ITEM nonzeros
-    const uint64_t by_min = nnz / MIN_CHUNK;
+    const uint64_t by_min = nnz / chunk_floor(k);
     L.cap_split = by_min < n ? by_min : n;                            // rows longer than the smallest chunk size
     // one partial vector per chunk of a split row: at most nnz/chunk + (split rows) for the chunk size in use.
     // Large batches use MAX_CHUNK; a reserve lets small batches use smaller chunks (the device picks the size
@@ -129,7 +140,7 @@ inline Layout make_layout(int64_t n_rows, int64_t nnz_ub, int32_t k, uint64_t re
     const uint64_t by_max = nnz / MAX_CHUNK;
     uint64_t reserve = reserve_bytes / (sizeof(uint32_t) * (uint64_t)k);
     if (reserve > SMALL_BATCH_PARTS) reserve = SMALL_BATCH_PARTS;
-    uint64_t small_need = by_min + L.cap_split;                       // what MIN_CHUNK would need
+    uint64_t small_need = by_min + L.cap_split;                       // what the smallest chunk would need
     if (reserve > small_need) reserve = small_need;
     L.cap_parts = by_max + (by_max < n ? by_max : n);
     if (L.cap_parts < reserve) L.cap_parts = reserve;
@@ -165,6 +176,7 @@ struct KArgs {
     uint32_t target_items;             // work items wanted for a balanced launch (a few per resident wavefront)
     uint32_t validate;
     uint32_t lane_pack;                // the hash kernel stores packed dwords from registers (see lane_pack_store)
+    uint32_t min_chunk;                // chunk_floor(k); with packed input at least one tile
     uint64_t prime;                    // runtime modulus of the generic-% ablation kernels
     // packed input (minhash_signatures_packed): rows as tiles of differences instead of col_idx
     const uint32_t* pk_width;
@@ -294,6 +306,9 @@ struct UnitStreamT {
     __device__ __forceinline__ bool advance(const KArgs& a, uint32_t n_long, int lane, RunItems* lds, Unit* out)
     {
         if (next >= end) {
+            // Every unit had a wavefront of its own: no further ticket stands for anything, and a small batch is
+            // spared some thousand atomics on one address at its end (15 of 42 microseconds for 1 000 rows).
+            if (map.lg_run == 0u && map.n_units <= grid_waves) return false;
             uint32_t tk = 0;
             if (lane == 0) tk = grid_waves + atomicAdd(&a.hdr->ticket, 1u);
             map.range(first_lane_value(tk), &base, &end);
@@ -391,31 +406,32 @@ __device__ __forceinline__ uint32_t umax3(uint32_t a, uint32_t b, uint32_t c)
 
 // ------------------------------------------------------------------ reset / bin / fill
 // Clears the header and picks the chunk size of this call: the largest power of two
-// in [MIN_CHUNK, MAX_CHUNK] that still yields target_items work items, as long as the
+// in [chunk_floor(k), MAX_CHUNK] that still yields target_items work items, as long as the
 // partial vectors of the resulting chunks fit the workspace.  Large batches get
 // MAX_CHUNK; a batch of a few hundred rows gets its long rows cut finely enough to
 // occupy the whole GPU instead of waiting for one wavefront per row.
-__device__ __forceinline__ uint32_t reset_header(const KArgs& a)      // threads 0..63 of one block; thread 0 returns the chunk size
+__device__ __forceinline__ uint32_t pick_chunk(const KArgs& a)      // one thread
 {
-    uint32_t* words = reinterpret_cast<uint32_t*>(a.hdr);
-    if (threadIdx.x < 64 && threadIdx.x != offsetof(WorkHeader, chunk) / 4) words[threadIdx.x] = 0;
     uint32_t chunk = MAX_CHUNK;
-    if (threadIdx.x == 0) {
-        const int64_t total = a.row_ptr[a.n_rows] - a.row_ptr[0];
-        if (total > 0) {
-            const uint64_t nnz = (uint64_t)total, n = (uint64_t)a.n_rows;
-            while (chunk > MIN_CHUNK) {
-                if (nnz / chunk >= a.target_items) break;
-                const uint64_t by_next = nnz / (chunk / 2);
-                if (by_next + (by_next < n ? by_next : n) > a.cap_parts) break;
-                chunk /= 2;
-            }
+    const int64_t total = a.row_ptr[a.n_rows] - a.row_ptr[0];
+    if (total > 0) {
+        const uint64_t nnz = (uint64_t)total, n = (uint64_t)a.n_rows;
+        while (chunk > a.min_chunk) {
+            if (nnz / chunk >= a.target_items) break;
+            const uint64_t by_next = nnz / (chunk / 2);
+            if (by_next + (by_next < n ? by_next : n) > a.cap_parts) break;
+            chunk /= 2;
         }
-        a.hdr->chunk = chunk;
     }
     return chunk;
 }
-__global__ void mh_reset_kernel(KArgs a) { (void)reset_header(a); }
+__device__ __forceinline__ void reset_header(const KArgs& a)          // threads 0..63 of one block
+{
+    uint32_t* words = reinterpret_cast<uint32_t*>(a.hdr);
+    if (threadIdx.x < 64 && threadIdx.x != offsetof(WorkHeader, chunk) / 4) words[threadIdx.x] = 0;
+    if (threadIdx.x == 0) a.hdr->chunk = pick_chunk(a);
+}
+__global__ void mh_reset_kernel(KArgs a) { reset_header(a); }
 
 // One thread per row.  Prefix sums over the wavefront and then over the block's
 // wavefronts make one atomic per block of 1024 rows and counter (one per
@@ -425,35 +441,75 @@ __global__ void mh_reset_kernel(KArgs a) { (void)reset_header(a); }
 // list order, so the long items start first and the short ones fill the tail of
 // the launch.
 constexpr int BIN_BLOCK = 1024;
+constexpr uint32_t MAX_ROW_PARTS = 512;    // chunks per row at most, unless the largest chunk size still leaves more
+constexpr uint32_t BIN_TEAM_FROM = 32;     // rows of more chunks than this have their items written by the whole block,
+constexpr int BIN_TEAM_ROWS = 64;          // up to this many rows per block (further ones by their own thread)
+struct RowJob {                            // what writing the items of one row needs
+    int64_t begin, nnz, pk_first;
+    uint32_t row, first_part, first_lg, first_sh, n_it, pk_w, is_split, chunk;
+};
+// Item c of a row.  Full chunks are long items when the chunk size exceeds LONG_ITEM, so all items before a
+// full chunk are long ones (or none is); the last or only item goes by its own length.
+__device__ __forceinline__ void write_item(const KArgs& a, const RowJob& j, uint32_t c)
+{
+    const uint32_t CHUNK = j.chunk;
+    Item it;
+    it.begin = j.begin + (int64_t)c * CHUNK;
+    const int64_t rest = j.nnz - (int64_t)c * CHUNK;
+    it.len = j.is_split ? (uint32_t)(rest < (int64_t)CHUNK ? rest : (int64_t)CHUNK) : (uint32_t)j.nnz;
+    it.row = j.row;
+    it.slot = j.is_split ? j.first_part + c : NO_SLOT;
+    const int64_t wbegin = j.pk_first + (int64_t)c * (int64_t)(CHUNK / PACKED_TILE) * (int64_t)packed_tile_words(PACKED_TILE, j.pk_w);
+    it.wlo = (uint32_t)wbegin; it.whi = (uint32_t)((uint64_t)wbegin >> 32); it.w = j.pk_w;
+    const uint32_t longs_before = CHUNK > LONG_ITEM ? c : 0u;
+    if (it.len > LONG_ITEM) a.items[(uint64_t)j.first_lg + longs_before] = it;
+    else a.items[a.cap_long + (uint64_t)j.first_sh + (c - longs_before)] = it;
+}
 __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
 {
     __shared__ uint32_t s_wave_tot[BIN_BLOCK / WAVE][4];     // totals per wavefront, then their exclusive prefix sums
     __shared__ uint32_t s_block_base[4];
+    __shared__ RowJob s_jobs[BIN_TEAM_ROWS];
+    __shared__ uint32_t s_n_jobs;
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = threadIdx.x >> 6;
     const int64_t row = (int64_t)blockIdx.x * BIN_BLOCK + threadIdx.x;
     __shared__ uint32_t s_chunk;
-    const bool own_reset = gridDim.x == 1;             // a batch of one block clears the header itself: one launch fewer
+    if (threadIdx.x == 0) s_n_jobs = 0;                // (two barriers lie between this and the first use)
+    // A batch of one block needs no header from an earlier launch and no atomics on it: the block's totals are the
+    // call's, what it has to report collects in the LDS, and the whole header is written once, at the end.
+    const bool own_reset = gridDim.x == 1;
+    __shared__ uint32_t s_status;
+    int64_t begin = 0, end = 0;
+    if (row < a.n_rows) {                              // (requested before the chunk size is known: one wait for both)
+        begin = a.row_ptr[row];
+        end = a.row_ptr[row + 1];
+    }
     if (own_reset) {
-        const uint32_t chunk = reset_header(a);
-        if (threadIdx.x == 0) s_chunk = chunk;
-        __threadfence();                               // the cleared counters are in place before any wavefront of the block adds to them
+        if (threadIdx.x == 0) {
+            s_chunk = pick_chunk(a);
+            s_status = 0;
+        }
         __syncthreads();
     }
+    auto report = [&](uint32_t bits) {
+        if (own_reset) atomicOr(&s_status, bits); else atomicOr(&a.hdr->status, bits);
+    };
     uint32_t CHUNK = own_reset ? s_chunk : a.hdr->chunk;
-    if (CHUNK < MIN_CHUNK || CHUNK > MAX_CHUNK) CHUNK = MAX_CHUNK;
+    if (CHUNK < a.min_chunk || CHUNK > MAX_CHUNK) CHUNK = MAX_CHUNK;
+    const uint32_t call_chunk = CHUNK;
     uint32_t n_it = 0, is_split = 0;
-    int64_t begin = 0, nnz = 0;
+    int64_t nnz = 0;
     if (row < a.n_rows) {
-        begin = a.row_ptr[row];
-        const int64_t end = a.row_ptr[row + 1];
         nnz = end - begin;
         // under VALIDATE the row must lie inside [row_ptr[0], row_ptr[n_rows]] and that range must not
         // hold more nonzeros than the workspace was sized for (row_extent_status of mh_arith.h)
         const int64_t lo = a.validate ? a.row_ptr[0] : 0, hi = a.validate ? a.row_ptr[a.n_rows] : 0;
         const uint32_t bad = row_extent_status(begin, end, lo, hi, a.nnz_cap, a.validate != 0);
-        if (bad && a.validate) atomicOr(&a.hdr->status, bad);
+        if (bad && a.validate) report(bad);
         if (bad) nnz = 0;              // treated as an empty row
+        // a very long row of a small batch gets larger chunks than the call's: no more than MAX_ROW_PARTS of them
+        while (nnz > (int64_t)CHUNK * MAX_ROW_PARTS && CHUNK < MAX_CHUNK) CHUNK *= 2;
         is_split = nnz > (int64_t)CHUNK ? 1u : 0u;
         n_it = is_split ? (uint32_t)((nnz + CHUNK - 1) / CHUNK) : 1u;
     }
@@ -478,38 +534,38 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
         s_wave_tot[wave][2] = inc_sp; s_wave_tot[wave][3] = inc_pt;
     }
     __syncthreads();
-    if (threadIdx.x < 4) {             // thread c: counter c of the block
+    uint32_t block_total = 0;          // thread c < 4: counter c of the block
+    if (threadIdx.x < 4) {
         uint32_t* const counter = &a.hdr->n_long + threadIdx.x;   // n_long, n_short, n_split, n_parts lie in a row
-        uint32_t run = 0;
         for (int w = 0; w < BIN_BLOCK / WAVE; ++w) {
             const uint32_t t = s_wave_tot[w][threadIdx.x];
-            s_wave_tot[w][threadIdx.x] = run;
-            run += t;
+            s_wave_tot[w][threadIdx.x] = block_total;
+            block_total += t;
         }
-        s_block_base[threadIdx.x] = run ? atomicAdd(counter, run) : 0u;
+        s_block_base[threadIdx.x] = block_total && !own_reset ? atomicAdd(counter, block_total) : 0u;
     }
     __syncthreads();
     const uint32_t base_lg = s_block_base[0] + s_wave_tot[wave][0];
     const uint32_t base_sh = s_block_base[1] + s_wave_tot[wave][1];
     const uint32_t base_sp = s_block_base[2] + s_wave_tot[wave][2];
     const uint32_t base_pt = s_block_base[3] + s_wave_tot[wave][3];
-    if (row >= a.n_rows) return;
     const uint64_t first_lg = (uint64_t)base_lg + inc_lg - n_lg;
     const uint64_t first_sh = (uint64_t)base_sh + inc_sh - n_sh;
     const uint64_t first_part = (uint64_t)base_pt + inc_pt - n_pt;
+    bool todo = row < a.n_rows;
     // An overflow can only happen when the workspace was sized for fewer nonzeros than
     // row_ptr describes.  Every allocated work-list entry inside the capacity is still
     // written (as an empty row), so that the consumer never reads an undefined entry.
-    bool overflow = first_lg + n_lg > a.cap_long || first_sh + n_sh > a.cap_short;
+    bool overflow = todo && (first_lg + n_lg > a.cap_long || first_sh + n_sh > a.cap_short);
     uint64_t sidx = 0;
-    if (is_split) {
+    if (todo && is_split) {
         sidx = (uint64_t)base_sp + inc_sp - 1;
         overflow = overflow || sidx >= a.cap_split || first_part + n_it > a.cap_parts;
     }
     Item* long_items = a.items;
     Item* short_items = a.items + a.cap_long;
     if (overflow) {
-        atomicOr(&a.hdr->status, 4u);
+        report(4u);
         Item it; it.begin = begin; it.len = 0; it.row = (uint32_t)row; it.slot = NO_SLOT; it.wlo = 0; it.whi = 0; it.w = 0;
         for (uint32_t c = 0; c < n_lg && first_lg + c < a.cap_long; ++c) long_items[first_lg + c] = it;
         for (uint32_t c = 0; c < n_sh && first_sh + c < a.cap_short; ++c) short_items[first_sh + c] = it;
@@ -517,35 +573,47 @@ __global__ __launch_bounds__(BIN_BLOCK) void mh_bin_rows_kernel(KArgs a)
             SplitRow sr; sr.row = (uint32_t)row; sr.first_part = 0; sr.n_parts = 0; sr.pad = 1;
             a.split_rows[sidx] = sr;
         }
-        return;
+        todo = false;
     }
-    if (is_split) {
-        SplitRow sr; sr.row = (uint32_t)row; sr.first_part = (uint32_t)first_part; sr.n_parts = n_it; sr.pad = 0;
-        a.split_rows[sidx] = sr;
-    }
-    // packed input: where the row's words start and how wide its differences are (chunks are whole numbers of tiles)
-    int64_t pk_first = 0;
-    uint32_t pk_w = 0;
-    if (a.pk_words) {
-        pk_first = a.pk_word_ptr[row];
-        pk_w = a.pk_width[row];
-        if (pk_w > 32u) {              // not a width: the row is reported and read as if its differences were 0 bits wide
-            atomicOr(&a.hdr->status, 1u);
-            pk_w = 0;
+    RowJob job;
+    job.begin = begin; job.nnz = nnz; job.pk_first = 0; job.row = (uint32_t)row; job.first_part = (uint32_t)first_part;
+    job.first_lg = (uint32_t)first_lg; job.first_sh = (uint32_t)first_sh; job.n_it = n_it; job.pk_w = 0; job.is_split = is_split; job.chunk = CHUNK;
+    if (todo) {
+        if (is_split) {
+            SplitRow sr; sr.row = (uint32_t)row; sr.first_part = (uint32_t)first_part; sr.n_parts = n_it; sr.pad = 0;
+            a.split_rows[sidx] = sr;
+        }
+        // packed input: where the row's words start and how wide its differences are (chunks are whole numbers of tiles)
+        if (a.pk_words) {
+            job.pk_first = a.pk_word_ptr[row];
+            job.pk_w = a.pk_width[row];
+            if (job.pk_w > 32u) {          // not a width: the row is reported and read as if its differences were 0 bits wide
+                report(1u);
+                job.pk_w = 0;
+            }
+        }
+        // a row of many chunks is left to the whole block (a row of 10^5 nonzeros in a small batch has 1 500 of them)
+        if (n_it > BIN_TEAM_FROM) {
+            const uint32_t q = atomicAdd(&s_n_jobs, 1u);
+            if (q < (uint32_t)BIN_TEAM_ROWS) {
+                s_jobs[q] = job;
+                todo = false;
+            }
         }
     }
-    uint32_t n_long_done = 0, n_short_done = 0;
-    for (uint32_t c = 0; c < n_it; ++c) {
-        Item it;
-        it.begin = begin + (int64_t)c * CHUNK;
-        const int64_t rest = nnz - (int64_t)c * CHUNK;
-        it.len = is_split ? (uint32_t)(rest < (int64_t)CHUNK ? rest : (int64_t)CHUNK) : (uint32_t)nnz;
-        it.row = (uint32_t)row;
-        it.slot = is_split ? (uint32_t)(first_part + c) : NO_SLOT;
-        const int64_t wbegin = pk_first + (int64_t)c * (int64_t)(CHUNK / PACKED_TILE) * (int64_t)packed_tile_words(PACKED_TILE, pk_w);
-        it.wlo = (uint32_t)wbegin; it.whi = (uint32_t)((uint64_t)wbegin >> 32); it.w = pk_w;
-        if (it.len > LONG_ITEM) long_items[first_lg + (n_long_done++)] = it;
-        else short_items[first_sh + (n_short_done++)] = it;
+    if (todo)
+        for (uint32_t c = 0; c < n_it; ++c) write_item(a, job, c);
+    __syncthreads();
+    if (own_reset && threadIdx.x < 64) {               // the header of the call: counters, chunk size, status, zeros elsewhere (the ticket counter among them)
+        uint32_t word = threadIdx.x < 4 ? block_total : 0u;
+        if (threadIdx.x == offsetof(WorkHeader, chunk) / 4) word = call_chunk;
+        if (threadIdx.x == offsetof(WorkHeader, status) / 4) word = s_status;
+        reinterpret_cast<uint32_t*>(a.hdr)[threadIdx.x] = word;
+    }
+    const uint32_t n_jobs = s_n_jobs < (uint32_t)BIN_TEAM_ROWS ? s_n_jobs : (uint32_t)BIN_TEAM_ROWS;
+    for (uint32_t q = 0; q < n_jobs; ++q) {
+        const RowJob j = s_jobs[q];
+        for (uint32_t c = threadIdx.x; c < j.n_it; c += BIN_BLOCK) write_item(a, j, c);
     }
 }
 
@@ -2076,33 +2144,101 @@ __global__ __launch_bounds__(BLOCK) void mh_perm_kernel(KArgs a)
 }
 
 // ------------------------------------------------------------------ finalize split rows
-__global__ __launch_bounds__(BLOCK) void mh_finalize_kernel(KArgs a, int ftile_size)
+// The minimum over the vectors of partial minima of every split row and function tile (a unit), packed
+// and stored.  A block takes 16 units at a time, one per wavefront; a unit of up to FIN_ALONE vectors is
+// its wavefront's alone (large batches have tens of thousands of such rows), a larger one waits until the
+// whole block turns to it: wavefront w then takes vectors w, w + 16, ..., the 16 results meet in the LDS and
+// the first wavefront packs and stores (a row of 10^5 nonzeros in a small batch has some hundred vectors; one
+// wavefront going through them alone, four loads at a time, took 120 microseconds).  Either way two vectors
+// are in flight per round, a lane reading its up to eight functions of each.
+constexpr int FIN_WAVES = 16;
+constexpr int FIN_BLOCK = FIN_WAVES * WAVE;
+constexpr uint32_t FIN_ALONE = 8;
+constexpr int FIN_FPL = MAX_FTILE / WAVE;
+// v[i] = minimum over vectors first, first + step, ... (below n) of function j0 + lane + 64 i; nf functions in the tile
+__device__ __forceinline__ void merge_parts(const KArgs& a, const uint32_t* first_vec, uint32_t first, uint32_t step, uint32_t n, int j0,
+                                            int nf, int lane, uint32_t (&v)[FIN_FPL])
 {
-    __shared__ uint32_t s_mins[WAVES_PER_BLOCK][MAX_FTILE];
+    // (a function past the end of the tile reads the tile's last one instead: loads without conditions all go out together)
+    int at[FIN_FPL];
+#pragma unroll
+    for (int i = 0; i < FIN_FPL; ++i) {
+        at[i] = lane + WAVE * i < nf ? lane + WAVE * i : nf - 1;
+        v[i] = EMPTY_MIN;
+    }
+    const size_t pitch = (size_t)step * (size_t)a.k;
+    const uint32_t* p = first_vec + (size_t)first * (size_t)a.k + j0;
+    for (uint32_t c = first; c < n; c += 2 * step) {           // two vectors a round (the last one perhaps twice)
+        const uint32_t* q = c + step < n ? p + pitch : p;
+        uint32_t o[FIN_FPL], o2[FIN_FPL];
+#pragma unroll
+        for (int i = 0; i < FIN_FPL; ++i) {
+            o[i] = p[at[i]];
+            o2[i] = q[at[i]];
+        }
+#pragma unroll
+        for (int i = 0; i < FIN_FPL; ++i) v[i] = umin3(v[i], o[i], o2[i]);
+        p += 2 * pitch;
+    }
+}
+__global__ __launch_bounds__(FIN_BLOCK) void mh_finalize_kernel(KArgs a, int ftile_size)
+{
+    __shared__ uint32_t s_part[FIN_WAVES][MAX_FTILE];
+    __shared__ uint32_t s_mins[MAX_FTILE];
+    __shared__ uint32_t s_big[FIN_WAVES];
     const int lane = threadIdx.x & (WAVE - 1);
     const int wave = threadIdx.x >> 6;
-    uint32_t* mins = s_mins[wave];
     const uint32_t n_split = a.hdr->n_split < a.cap_split ? a.hdr->n_split : (uint32_t)a.cap_split;
     const uint64_t n_units = (uint64_t)n_split * (uint64_t)a.n_ftiles;
-    const uint64_t n_waves = (uint64_t)gridDim.x * WAVES_PER_BLOCK;
-    for (uint64_t u = (uint64_t)blockIdx.x * WAVES_PER_BLOCK + wave; u < n_units; u += n_waves) {
-        const uint32_t sidx = (uint32_t)(u / (uint64_t)a.n_ftiles);
-        const int ftile = (int)(u - (uint64_t)sidx * (uint64_t)a.n_ftiles);
-        const int j0 = ftile * ftile_size;
-        const int nf = a.k - j0 < ftile_size ? a.k - j0 : ftile_size;
-        const SplitRow sr = a.split_rows[sidx];
-        for (int j = lane; j < nf; j += WAVE) {
-            uint32_t v = EMPTY_MIN;
-#pragma unroll 4
-            for (uint32_t c = 0; c < sr.n_parts; ++c) {
-                uint32_t o = a.partials[(size_t)(sr.first_part + c) * (size_t)a.k + j0 + j];
-                v = o < v ? o : v;
+    for (uint64_t base = (uint64_t)blockIdx.x * FIN_WAVES; base < n_units; base += (uint64_t)gridDim.x * FIN_WAVES) {
+        uint32_t big = 0;
+        if (base + wave < n_units) {
+            const uint64_t u = base + wave;
+            const uint32_t sidx = (uint32_t)(u / (uint64_t)a.n_ftiles);
+            const int ftile = (int)(u - (uint64_t)sidx * (uint64_t)a.n_ftiles);
+            const int j0 = ftile * ftile_size;
+            const int nf = a.k - j0 < ftile_size ? a.k - j0 : ftile_size;
+            const SplitRow sr = a.split_rows[sidx];
+            if (sr.n_parts <= FIN_ALONE) {
+                uint32_t v[FIN_FPL];
+                merge_parts(a, a.partials + (size_t)sr.first_part * (size_t)a.k, 0u, 1u, sr.n_parts, j0, nf, lane, v);
+#pragma unroll
+                for (int i = 0; i < FIN_FPL; ++i)
+                    if (lane + WAVE * i < nf) s_part[wave][lane + WAVE * i] = v[i];
+                wave_sync_lds();
+                wave_pack_store(a, s_part[wave], sr.row, j0, nf, ftile == a.n_ftiles - 1, lane);
+                wave_sync_lds();
+            } else {
+                big = 1;
             }
-            mins[j] = v;
         }
-        wave_sync_lds();
-        wave_pack_store(a, mins, sr.row, j0, nf, ftile == a.n_ftiles - 1, lane);
-        wave_sync_lds();
+        if (lane == 0) s_big[wave] = big;
+        __syncthreads();
+        for (int w = 0; w < FIN_WAVES; ++w) {
+            if (!s_big[w]) continue;                       // the same for every thread of the block
+            const uint64_t u = base + w;
+            const uint32_t sidx = (uint32_t)(u / (uint64_t)a.n_ftiles);
+            const int ftile = (int)(u - (uint64_t)sidx * (uint64_t)a.n_ftiles);
+            const int j0 = ftile * ftile_size;
+            const int nf = a.k - j0 < ftile_size ? a.k - j0 : ftile_size;
+            const SplitRow sr = a.split_rows[sidx];
+            uint32_t v[FIN_FPL];
+            merge_parts(a, a.partials + (size_t)sr.first_part * (size_t)a.k, (uint32_t)wave, (uint32_t)FIN_WAVES, sr.n_parts, j0, nf, lane, v);
+#pragma unroll
+            for (int i = 0; i < FIN_FPL; ++i)
+                if (lane + WAVE * i < nf) s_part[wave][lane + WAVE * i] = v[i];
+            __syncthreads();
+            for (int j = threadIdx.x; j < nf; j += FIN_BLOCK) {
+                uint32_t m = s_part[0][j];
+#pragma unroll
+                for (int x = 1; x < FIN_WAVES; ++x) m = s_part[x][j] < m ? s_part[x][j] : m;
+                s_mins[j] = m;
+            }
+            __syncthreads();
+            if (wave == 0) wave_pack_store(a, s_mins, sr.row, j0, nf, ftile == a.n_ftiles - 1, lane);
+            __syncthreads();
+        }
+        __syncthreads();                                   // before s_big is written again
     }
 }
 
@@ -2311,6 +2447,7 @@ int make_plan(Plan* plan, const int64_t* row_ptr, const uint32_t* col_idx, int64
     a.partials = reinterpret_cast<uint32_t*>(ws + L.partials_off);
     a.D = D; a.cap_long = L.cap_long; a.cap_short = L.cap_short; a.cap_split = L.cap_split; a.cap_parts = L.cap_parts;
     a.nnz_cap = (uint64_t)nnz_cap;
+    a.min_chunk = chunk_floor(k);
     a.md = make_mod_d(D);
     if (is_multiply_shift(family)) {
         int sbits = 0;
@@ -2420,7 +2557,7 @@ int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream
     }
     hipError_t r1 = profiled ? hipEventRecord(e1, l.s) : hipSuccess;
     if (plan.has_split)
-        hipLaunchKernelGGL(mh_finalize_kernel, dim3(l.cus * 8), dim3(BLOCK), 0, l.s, a, plan.ftile_size);   // latency-bound: fill the chip
+        hipLaunchKernelGGL(mh_finalize_kernel, dim3(l.cus * 2), dim3(FIN_BLOCK), 0, l.s, a, plan.ftile_size);   // latency-bound: fill the chip
     if (status_out) hipLaunchKernelGGL(mh_export_status_kernel, dim3(1), dim3(1), 0, l.s, a.hdr, status_out);
 
     hipError_t le = hipGetLastError();
@@ -2584,6 +2721,7 @@ int minhash_signatures_packed(const int64_t* row_ptr, const uint32_t* width, con
     plan.a.pk_word_ptr = word_ptr;
     plan.a.pk_words = words;
     plan.a.pk_words_len = words_len;
+    if (plan.a.min_chunk < PACKED_TILE) plan.a.min_chunk = PACKED_TILE;       // a chunk starts at a tile
     return enqueue(plan, family, D, flags, stream, nullptr, false, nullptr);
 }
 

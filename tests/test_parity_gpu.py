@@ -105,6 +105,17 @@ def test_function_counts(k):
     check_case(rp, col, D, k, 8, mh.FAMILY_2U_M31, W.coefficients(k, mh.FAMILY_2U_M31, seed=k))
 
 
+@pytest.mark.parametrize("n_rows,nnz_each,k", [(1, 1000, 500), (1, 100000, 500), (1, 1000000, 64), (3, 40000, 200), (16, 300, 500)])
+def test_small_batches_of_long_rows(n_rows, nnz_each, k):
+    """A handful of rows, as a query brings them: the rows are cut into chunks as small as 64 nonzeros so that
+    they occupy the GPU, never more than 512 to a row; rows of many chunks have their work items written by
+    the whole binning block and their partial minima merged by a whole block."""
+    D = 1 << 24
+    nnz = np.full(n_rows, nnz_each, dtype=np.int64)
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed=n_rows + k)
+    check_case(rp, col, D, k, 8, mh.FAMILY_2U_M31, W.coefficients(k, mh.FAMILY_2U_M31, seed=nnz_each))
+
+
 @pytest.mark.parametrize("family,k,b", [(mh.FAMILY_2U_M31, 4096, 8), (mh.FAMILY_2U_M31, 65536, 1), (mh.FAMILY_2U_M31, 65536, 32),
                                         (mh.FAMILY_4U_M31, 10000, 3), (mh.FAMILY_2U_M61, 65536, 8), (mh.FAMILY_2U_MS32, 65535, 5)])
 def test_very_many_functions_up_to_the_largest_k(family, k, b):
