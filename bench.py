@@ -69,6 +69,14 @@ ISSUE_MIX_OTHER_D = {
     W.FAMILY_2U_M31: (3.0, 1.0 + 0.5, 4.0),         # mad, mulhi, mad | min, half a min3 | shr,add,sub,shr
     W.FAMILY_4U_M31: (5.0, 1.0 + 1.0 + 0.5, 6.0),   # 3 mad, mulhi, mad | add3, min, half a min3 | shr,and,shr,add,xor,shr
 }
+# 2U with p = 2^61-1 and other D up to 2^32/3 (half_2u61_steps32): the folded 61-bit value, then its residue modulo
+# D' = D 2^j in 32-bit steps; one more exact quotient when D is below 2^29
+ISSUE_MIX_M61_OTHER_D = (
+    # mad, mad, mulhi, mad | funnel shift, add with carry out, add with carry in, funnel shift, min3, min, half a min3 |
+    # mov, and, shr, add, sub, sub, add, add
+    (4.0, 6.5, 8.0),
+    (6.0, 6.5, 10.0),      # D below 2^29: mulhi, mad | | shr, mov
+)
 
 
 def issue_slots(mix):
@@ -96,6 +104,8 @@ SPLIT = 8192                                                # rows longer than t
 
 
 def issue_mix_for(family: int, D: int):
+    if family == W.FAMILY_2U_M61 and D & (D - 1):
+        return ISSUE_MIX_M61_OTHER_D[0 if D > (1 << 29) else 1]
     if D & (D - 1):
         return (ISSUE_MIX_OTHER_D_FRAC if D < (1 << 28) else
                 ISSUE_MIX_OTHER_D_BIG if 3 * D >= (1 << 31) - 1 else ISSUE_MIX_OTHER_D)[family]
@@ -560,9 +570,12 @@ def main() -> int:
     headline = "large_2u" if args.workload == "all" else args.workload
     w = W.WORKLOADS[headline]
     family = w.family
-    if args.universe and (family not in ISSUE_MIX_OTHER_D or args.stream or args.generic_mod
-                          or not 1 <= args.universe < (1 << 31) - 1):
-        print("bench.py: --universe needs a 2U/4U workload with p = 2^31-1 and a D below the prime", file=sys.stderr)
+    if args.universe and family == W.FAMILY_2U_M61 and not args.stream and 3 <= args.universe <= (1 << 32) // 3:
+        pass                                # huge_2u_m61 with another D: served in 32-bit steps up to 2^32 / 3
+    elif args.universe and (family not in ISSUE_MIX_OTHER_D or args.stream or args.generic_mod
+                            or not 1 <= args.universe < (1 << 31) - 1):
+        print("bench.py: --universe needs a 2U/4U workload with p = 2^31-1 and a D below the prime, or huge_2u_m61 and a D of "
+              "at most 2^32 / 3", file=sys.stderr)
         return 2
     flags = 0
     if args.generic_mod:

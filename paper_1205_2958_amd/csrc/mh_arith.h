@@ -53,8 +53,18 @@ struct ModD {
     uint32_t M;      // ceil(2^(31+l) / D) for D >= 3 not a power of two
     uint32_t sh;     // l - 1
     uint32_t pow2;
+    uint32_t M61q;   // floor(2^61 / D'), D' = D 2^j in (2^29, 2^32 / 3]: 61-bit residues mod D in 32-bit steps (0: not served)
     uint64_t M64;    // floor((2^64 - 1) / D): 61-bit residues mod D, see reduce61_mod_d
 };
+static_assert(sizeof(ModD) == 32, "the new word takes the place of padding: kernel arguments keep their offsets");
+
+// D 2^j, the multiple of D in (2^29, 2^30) for D below 2^29 (not a power of two), D itself above that
+MH_HD uint32_t scaled_up_d(uint64_t D)                   // 3 <= D < 2^32
+{
+    const uint32_t d = (uint32_t)D;
+    const int lz = __builtin_clz(d);
+    return lz > 2 ? d << (lz - 2) : d;
+}
 
 MH_HD ModD make_mod_d(uint64_t D)
 {
@@ -65,6 +75,8 @@ MH_HD ModD make_mod_d(uint64_t D)
     m.M = 0;
     m.sh = 0;
     m.M64 = ~0ull / D;
+    m.M61q = 0;
+    if (!m.pow2 && D >= 3 && 3 * D <= (1ull << 32)) m.M61q = (uint32_t)((1ull << 61) / scaled_up_d(D));
     if (!m.pow2 && D < (1ull << 31)) {       // the exact-quotient path serves p = 2^31-1 only (D < p)
         uint32_t l = 0;
         while ((1ull << l) < D) ++l;         // l >= 2
@@ -132,9 +144,25 @@ MH_HD uint32_t reduce_small_quotient(uint32_t r, uint32_t D)      // r < p
 // the mask path cannot serve): q = floor(r M64 / 2^64) falls short of the true
 // quotient by at most one, because r (2^64 / D - M64) < 2 r < 2^64 / 4; one
 // conditional subtraction finishes it.
+//
+// D of at most 2^32 / 3 (not a power of two) needs no 64-bit quotient.  With D' = D 2^j in (2^29, 2^32 / 3]
+// and M = floor(2^61 / D') < 2^32, q = floor(floor(r / 2^29) M / 2^32) is one multiply-high of 32-bit
+// words.  Both factors are rounded down, so q <= floor(r / D'); and with a = r / 2^29, m = 2^61 / D' the
+// rounded factors multiply to more than (a - 1)(m - 1) > a m - a - m, where (a + m) / 2^32 < r / 2^61 +
+// 2^29 / D' < 2, and the floor loses less than one more: q >= floor(r / D') - 2.  So r - q D' lies in
+// [0, 3 D'), fits 32 bits, and is computed in 32-bit words (the low word of r less the low word of q D');
+// the smallest of it, it less D' and it less 2 D' as unsigned words is r mod D' (reduce_small_quotient).
+// For j > 0 that value, below 2^30, is then taken modulo D by the exact quotient that serves p = 2^31-1.
 MH_HD uint64_t mulhi_u64(uint64_t a, uint64_t b) { return (uint64_t)(((unsigned __int128)a * b) >> 64); }
 MH_HD uint32_t reduce61_mod_d(uint64_t r, const ModD& md, uint64_t D)
 {
+    if (md.M61q) {
+        const uint32_t dp = scaled_up_d(D);
+        const uint32_t q = mulhi_u32((uint32_t)(r >> 29), md.M61q);
+        uint32_t v = reduce_small_quotient((uint32_t)r - q * dp, dp);
+        if (dp != (uint32_t)D) v = reduce_mod_d<false>(v, md);
+        return v;
+    }
     uint64_t q = mulhi_u64(r, md.M64);
     uint64_t v = r - q * D;
     return (uint32_t)(v >= D ? v - D : v);

@@ -353,12 +353,17 @@ struct ModDV : ModD {
     uint32_t frot;   // 31 - log2 D: what the coefficients of the full-key form are rotated by
     uint32_t frac_m; // fractional keys (FracD of mh_arith.h): low word of the 33-bit multiplier,
     uint32_t frac_l; // and the bit at which the key starts
+    uint32_t m61q;   // 61-bit residues modulo D in 32-bit steps (reduce61_mod_d of mh_arith.h): floor(2^61 / D'),
+    uint32_t dp;     // D' = D 2^j in (2^29, 2^32 / 3],
+    uint32_t mask29; // 2^29 - 1
+    uint32_t negdp;  // and 2^32 - D'
 };
 __device__ __forceinline__ ModDV vector_constants(const ModD& src)
 {
     ModDV v;
     v.pow2 = src.pow2;
     v.M64 = src.M64;
+    v.M61q = src.M61q;
     v.D = in_vgpr(src.D);
     v.mask = in_vgpr(src.mask);
     v.M = in_vgpr(src.M);
@@ -372,6 +377,10 @@ __device__ __forceinline__ ModDV vector_constants(const ModD& src)
     const FracD fd = frac ? make_frac_d(src.D) : FracD{0u, 0u, 0u};
     v.frac_m = in_vgpr_if_used(fd.m_low);
     v.frac_l = fd.l;
+    v.m61q = in_vgpr_if_used(src.M61q);
+    v.dp = in_vgpr_if_used(src.M61q ? scaled_up_d(src.D) : 0u);
+    v.mask29 = in_vgpr_if_used(0x1FFFFFFFu);
+    v.negdp = in_vgpr_if_used(0u - v.dp);
     return v;
 }
 // Issue priority of this wavefront among those of its SIMD.  The hand-ordered steps
@@ -871,10 +880,12 @@ struct Fn2U61V : Fn2U61 {
 // of the keys; a maximum below GUARD61_FLOOR, which about one value in 2^n with n
 // evaluations behind it has, is computed again from the exact arithmetic (GUARDED,
 // see the kernel).
-template <bool POW2>
+// STEPS32: other D of at most 2^32 / 3, the residue modulo D taken in 32-bit steps, ordered by hand (half_2u61_steps32).
+template <bool POW2, bool STEPS32 = false>
 struct Pol2U61 {
+    static_assert(!(POW2 && STEPS32), "one form or the other");
     static constexpr int NW = 1;
-    static constexpr int MIN_WAVES = POW2 ? 4 : 5;
+    static constexpr int MIN_WAVES = POW2 || STEPS32 ? 4 : 5;
     static constexpr bool TRACK_MAX = POW2;
     static constexpr bool SHIFTED_KEY = POW2;
     static constexpr bool DOUBLED_KEY = false;
@@ -883,13 +894,16 @@ struct Pol2U61 {
     static constexpr bool FRAC_KEY = false;
     static constexpr bool GUARDED = POW2;
     static constexpr bool VARIABLE_NF = POW2;    // hand-ordered steps exist for 5..8 functions per lane
-    using Fn = std::conditional_t<POW2, Fn2U61V, Fn2U61>;
+    using Fn = std::conditional_t<POW2 || STEPS32, Fn2U61V, Fn2U61>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
         Fn f;
         if constexpr (POW2) {
             const uint32_t shift = neg_key_shift(a.md.mask);
             static_cast<Fn2U61&>(f) = valid ? prep_2u61_neg(c[0], c[1], shift) : prep_2u61_neg(0, 0, shift);
+            f.hz = u32x2{0u, 0u};
+        } else if constexpr (STEPS32) {
+            static_cast<Fn2U61&>(f) = valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
             f.hz = u32x2{0u, 0u};
         } else {
             static_cast<Fn2U61&>(f) = valid ? prep_2u61(c[0], c[1]) : prep_2u61(0, 0);
@@ -1372,6 +1386,106 @@ __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], ui
     issue_priority<1>();
 }
 
+// 2U, p = 2^61-1, other D of at most 2^32 / 3 (so t < 2^31): the folded value x = y + (H >> 29) in [1, 2^61 +
+// 2^32), congruent to X + 1 (residue_2u61 of mh_arith.h), with bit 61 folded once more x' = (X mod p) + 1 in
+// [1, p]; then reduce61_mod_d's 32-bit steps on x' (the quotient estimate from bits 29..60 of x, which only
+// makes it a hair smaller; the low word of x' exact), and at the end the 1 comes off: of u = (x' mod D') - 1
+// and u + D' the smaller as unsigned words.  A carry links the two words of x; each function slot keeps it in
+// the scalar pair that its multiply-adds name.
+#define MH_CARRY_OP(SLOT, TEXT, ...)                                                                                       \
+    do {                                                                                                               \
+        if (((SLOT) & 7) == 0) asm volatile(TEXT("s[84:85]") : __VA_ARGS__ : "s84", "s85");                            \
+        else if (((SLOT) & 7) == 1) asm volatile(TEXT("s[86:87]") : __VA_ARGS__ : "s86", "s87");                       \
+        else if (((SLOT) & 7) == 2) asm volatile(TEXT("s[88:89]") : __VA_ARGS__ : "s88", "s89");                       \
+        else if (((SLOT) & 7) == 3) asm volatile(TEXT("s[90:91]") : __VA_ARGS__ : "s90", "s91");                       \
+        else if (((SLOT) & 7) == 4) asm volatile(TEXT("s[92:93]") : __VA_ARGS__ : "s92", "s93");                       \
+        else if (((SLOT) & 7) == 5) asm volatile(TEXT("s[94:95]") : __VA_ARGS__ : "s94", "s95");                       \
+        else if (((SLOT) & 7) == 6) asm volatile(TEXT("s[96:97]") : __VA_ARGS__ : "s96", "s97");                       \
+        else asm volatile(TEXT("s[98:99]") : __VA_ARGS__ : "s98", "s99");                                              \
+    } while (0)
+#define MH_ADD_CO_TEXT(SP) "v_add_co_u32 %0, " SP ", %1, %2"
+#define MH_ADDC0_TEXT(SP) "v_addc_co_u32 %0, " SP ", 0, %0, " SP
+template <int NF>
+__device__ __forceinline__ void half_2u61_steps32(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t t, const ModDV& md)
+{
+    u32x2 L[HASH_FPL], H[HASH_FPL];
+    uint32_t s[HASH_FPL], xlo[HASH_FPL], xhi[HASH_FPL], q[HASH_FPL], r;
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, L[g], fn[g].e0, t, fn[g].add);
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) {
+        asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "v"(L[g].y));
+        fn[g].hz.x = r;
+    }
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, H[g], fn[g].e1, t, fn[g].hz);
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_CARRY_OP(g, MH_ADD_CO_TEXT, "=v"(xlo[g]) : "v"(L[g].x), "v"(s[g]));      // low word of x, carry kept
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(xhi[g]) : "v"(H[g].x), "v"(md.mask29));
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_CARRY_OP(g, MH_ADDC0_TEXT, "+v"(xhi[g]) :);                      // high word: bits 32..61 of x
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(xhi[g]), "v"(xlo[g]));   // bits 29..60 of x
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(q[g]) : "v"(s[g]), "v"(md.m61q));
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 29, %1" : "=v"(xhi[g]) : "v"(xhi[g]));         // bit 61
+#pragma unroll
+    for (int g = 0; g < NF; ++g) {                      // low word of x', into the pair whose high word is zero
+        asm volatile("v_add_u32 %0, %1, %2" : "=v"(r) : "v"(xlo[g]), "v"(xhi[g]));
+        fn[g].hz.x = r;
+    }
+    issue_priority<1>();
+    // x' - q D' in [0, 3 D') is the low word of q (2^32 - D') + x': a widening multiply-add again (the 32-bit
+    // multiply that keeps the low word takes four issue slots, this one takes one)
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, L[g], q[g], md.negdp, fn[g].hz);
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) xlo[g] = L[g].x;
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_sub_u32 %0, %1, %2" : "=v"(s[g]) : "v"(xlo[g]), "v"(md.dp));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_sub_u32 %0, %1, %2" : "=v"(q[g]) : "v"(s[g]), "v"(md.dp));
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(xlo[g]) : "v"(s[g]), "v"(q[g]));   // x' mod D'
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, -1, %0" : "+v"(xlo[g]));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_add_u32 %0, %1, %2" : "=v"(s[g]) : "v"(xlo[g]), "v"(md.dp));
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_min_u32 %0, %1, %2" : "=v"(y[g]) : "v"(xlo[g]), "v"(s[g]));   // (X mod p) mod D'
+    if (md.dp != md.D) {               // D' is a multiple of D: the exact quotient by an invariant divisor finishes it (values below 2^30)
+#pragma unroll
+        for (int g = 0; g < NF; ++g) asm volatile("v_mul_hi_u32 %0, %1, %2" : "=v"(q[g]) : "v"(y[g]), "v"(md.M));
+        issue_priority<0>();
+#pragma unroll
+        for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, %1, %0" : "+v"(q[g]) : "v"(md.sh));
+#pragma unroll
+        for (int g = 0; g < NF; ++g) {
+            asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "v"(y[g]));
+            fn[g].hz.x = r;
+        }
+        issue_priority<1>();
+#pragma unroll
+        for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, L[g], q[g], md.negD, fn[g].hz);      // low word: y - q D
+#pragma unroll
+        for (int g = 0; g < NF; ++g) y[g] = L[g].x;
+    }
+}
+
 // Ablation: the definition evaluated with the % operator on runtime moduli (Horner
 // form keeps every product below 2^62).  This is what Section 3.4's shift/mask
 // routine replaces; it exists only to be timed against the Mersenne kernels.
@@ -1531,8 +1645,8 @@ __device__ __forceinline__ void Pol4U31<false, false, 1>::pair(const Fn (&fn)[HA
 
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol2U61<true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                    const uint32_t* wb, const ModDV&, uint64_t)
+__device__ __forceinline__ void Pol2U61<true, false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                           const uint32_t* wb, const ModDV&, uint64_t)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
     half_2u61_pow2<NF>(fn, ya, wa[0]);
@@ -1543,10 +1657,22 @@ __device__ __forceinline__ void Pol2U61<true>::pair(const Fn (&fn)[HASH_FPL], ui
 }
 template <>
 template <int NF>
-__device__ __forceinline__ void Pol2U61<false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                     const uint32_t* wb, const ModDV& md, uint64_t D)
+__device__ __forceinline__ void Pol2U61<false, false>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                            const uint32_t* wb, const ModDV& md, uint64_t D)
 {
-    pair_generic<Pol2U61<false>, NF>(fn, m, wa, wb, md, D);
+    pair_generic<Pol2U61<false, false>, NF>(fn, m, wa, wb, md, D);
+}
+template <>
+template <int NF>
+__device__ __forceinline__ void Pol2U61<false, true>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                           const uint32_t* wb, const ModDV& md, uint64_t)
+{
+    uint32_t ya[HASH_FPL], yb[HASH_FPL];
+    half_2u61_steps32<NF>(fn, ya, wa[0], md);
+    half_2u61_steps32<NF>(fn, yb, wb[0], md);
+#pragma unroll
+    for (int g = 0; g < NF; ++g)
+        asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
 }
 
 // ------------------------------------------------------------------ staging
@@ -2541,6 +2667,7 @@ int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream
         break;
     case MINHASH_2U_M61:
         if (plan.guarded61) launch_hash<Pol2U61<true>>(a, nf, l);
+        else if (a.md.M61q) launch_hash<Pol2U61<false, true>>(a, nf, l);     // other D of at most 2^32 / 3
         else launch_hash<Pol2U61<false>>(a, nf, l);
         break;
     case MINHASH_4U_M61:

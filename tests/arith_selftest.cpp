@@ -173,7 +173,8 @@ int main()
         }
     }
     std::vector<uint64_t> D31 = {1, 2, 1 << 10, 1 << 24, 1u << 30, 3, 1000003, 16609143, 1010017424, p31 - 1};
-    std::vector<uint64_t> D61 = {1, 2, 1 << 24, 1u << 30, 1ull << 31, 1ull << 32, 3, 1010017424, (1ull << 32) - 1, (1ull << 31) + 7};
+    std::vector<uint64_t> D61 = {1, 2, 1 << 24, 1u << 30, 1ull << 31, 1ull << 32, 3, 1010017424, (1ull << 32) - 1, (1ull << 31) + 7,
+                                 16609143, (1ull << 29) + 1, 1431655765, 1431655766};
     std::vector<uint64_t> edge31 = {0, 1, 2, p31 - 1, p31 - 2, (p31 - 1) / 2, (p31 - 1) / 2 + 1, (p31 + 1) / 2 + 1, 1 << 16, 12345};
     std::vector<uint64_t> edge61 = {0, 1, 2, p61 - 1, p61 - 2, (p61 - 1) / 2, (p61 + 1) / 2, 1ull << 32, (1ull << 32) - 1, 1ull << 60};
     for (uint64_t D : D31) {
@@ -267,6 +268,37 @@ int main()
             }
         }
         if (frac_key_serves(1ull << 20) || frac_key_serves(1ull << 28) || frac_key_serves(1010017424ull) || frac_key_serves(2)) FAIL("fractional key accepts a D it cannot serve");
+        checks += n;
+    }
+    // 61-bit residues modulo D in 32-bit steps (D <= 2^32 / 3, not a power of two) against the 64-bit %
+    {
+        long n = 0;
+        const unsigned long long third = (1ull << 32) / 3;
+        for (uint64_t D : {3ull, 5ull, 6ull, 7ull, 100ull, 65537ull, 1000003ull, 16609143ull, (1ull << 28) - 1, (1ull << 28) + 1, (1ull << 29) - 1,
+                           (1ull << 29) + 1, (1ull << 29) + 12345, (1ull << 30) - 1, (1ull << 30) + 1, 1010017424ull, third - 1, third}) {
+            const ModD md = make_mod_d(D);
+            if (!md.M61q) FAIL("32-bit steps refuse D=%llu", (unsigned long long)D);
+            const uint64_t dp = scaled_up_d(D);
+            if (dp % D != 0 || dp <= (1ull << 29) || 3 * dp > (1ull << 32) || (dp / D & (dp / D - 1)) != 0)
+                FAIL("scaled D=%llu gives %llu", (unsigned long long)D, (unsigned long long)dp);
+            std::vector<uint64_t> rs = {0, 1, D - 1, D, D + 1, dp - 1, dp, dp + 1, 2 * dp - 1, 2 * dp, 3 * dp - 1, 3 * dp, p61 - 1, p61 - 2,
+                                        (p61 - 1) / dp * dp, (p61 - 1) / dp * dp - 1, (1ull << 32) - 1, 1ull << 32, (1ull << 29) - 1, 1ull << 29,
+                                        (1ull << 60) - 1, 1ull << 60};
+            for (int i = 0; i < 300000; ++i) rs.push_back(rnd() % p61);
+            for (int i = 0; i < 100000; ++i) rs.push_back((rnd() % p61) >> (rnd() % 61));
+            for (int i = 0; i < 20000; ++i) {           // next to multiples of D', where a quotient that is off shows
+                const uint64_t q = rnd() % ((p61 - 1) / dp + 1), r = q * dp + (rnd() % 5) - 2;
+                if (r < p61) rs.push_back(r);
+            }
+            for (uint64_t r : rs) {
+                const uint32_t got = reduce61_mod_d(r, md, D);
+                if (got != r % D) FAIL("32-bit steps D=%llu r=%llu give %u want %llu", (unsigned long long)D, (unsigned long long)r, got,
+                                       (unsigned long long)(r % D));
+                ++n;
+            }
+        }
+        for (uint64_t D : {1ull, 2ull, 1ull << 20, 1ull << 31, third + 1, (1ull << 31) + 7, (1ull << 32) - 1, 1ull << 32})
+            if (make_mod_d(D).M61q) FAIL("32-bit steps accept D=%llu", (unsigned long long)D);
         checks += n;
     }
     // Small quotients for D >= p / 3: the smallest of r, r - D, r - 2D

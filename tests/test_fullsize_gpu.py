@@ -85,12 +85,13 @@ def test_large_workloads_sampled_rows(name, budget, oracle_pool):
     assert bool((out != 0xAA).any(dim=1).all().item())
 
 
-@pytest.mark.parametrize("name", ["large_2u", "large_4u"])
+@pytest.mark.parametrize("name", ["large_2u", "large_4u", "huge_2u_m61"])
 @pytest.mark.parametrize("D", [16_609_143, 500_000_003, 1_010_017_424])
 def test_universe_sizes_of_the_papers_datasets_sampled_rows(name, D, oracle_pool):
     """The headline rows hashed into a universe that is not a power of two (Table tab_data: webspam's
     16 609 143 and the expanded rcv1's 1 010 017 424, and one size in between), each of which takes
-    a kernel form of its own; indices are folded into [0, D) as bench.py --universe does."""
+    a kernel form of its own (with p = 2^61-1: the residue modulo D in 32-bit steps, in one stage above
+    2^29 and in two below); indices are folded into [0, D) as bench.py --universe does."""
     w = W.WORKLOADS[name]
     nnz = w.nnz(0)
     rp_np = W.row_ptr_from_nnz(nnz)
@@ -103,7 +104,7 @@ def test_universe_sizes_of_the_papers_datasets_sampled_rows(name, D, oracle_pool
     ws = mh.alloc_workspace(len(nnz), int(rp_np[-1]), w.k, w.family, DEV)
     mh.minhash_signatures(rp, col, D, w.k, w.b, w.family, params, out=out, workspace=ws)
     assert mh.status(ws) == 0
-    rows, cover = _sample_rows(nnz, seed=23, eval_budget=1.5e9, k=w.k)
+    rows, cover = _sample_rows(nnz, seed=23, eval_budget=4e9 if name == "huge_2u_m61" else 1.5e9, k=w.k)
     assert cover["rows"] >= 100
     _check_rows(oracle_pool, w, nnz, rp_np, w.data_seed, col, params, params_np, out, rows, D=D)
     assert bool((out != 0xAA).any(dim=1).all().item())
