@@ -205,6 +205,12 @@ int minhash_check_coeffs(const uint64_t *host_coeffs, int32_t k, int32_t family)
  * bad input, else MINHASH_OK. */
 int minhash_status(const void *workspace, void *stream);
 
+/* The same report without waiting: enqueues on `stream` a kernel that stores the code in *status_out
+ * (device, one int32), after the calls already enqueued there.  For loops that reuse one workspace for
+ * many calls (Section 3.2's batch loop: every call clears what the one before reported) and look at all
+ * the codes at the end.  MINHASH_ERR_ARG for a null pointer, MINHASH_ERR_HIP if the launch failed. */
+int minhash_status_async(const void *workspace, int32_t *status_out, void *stream);
+
 /* ---------------------------------------------------------------- packed index rows
  * Section 3.2's batch loop copies every chunk of sets to the GPU before hashing
  * it, and Section 3.6 finds the movement of the data dominant once the hashing

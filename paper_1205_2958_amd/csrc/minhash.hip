@@ -2885,6 +2885,16 @@ int minhash_status(const void* workspace, void* stream)
     return h.status ? MINHASH_ERR_DATA : MINHASH_OK;
 }
 
+int minhash_status_async(const void* workspace, int32_t* status_out, void* stream)
+{
+    if (!workspace || !status_out) return MINHASH_ERR_ARG;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(mh_export_status_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const WorkHeader*>(workspace), status_out);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? MINHASH_OK : hip_fail(e, "mh_export_status_kernel");
+}
+
 const char* minhash_error_string(int code)
 {
     switch (code) {

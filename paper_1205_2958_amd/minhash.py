@@ -37,6 +37,7 @@ EXPORTS = (
     "minhash_workspace_bytes",
     "minhash_check_coeffs",
     "minhash_status",
+    "minhash_status_async",
     "minhash_pack_indices",
     "minhash_unpack_indices",
     "minhash_signatures_packed",
@@ -84,6 +85,8 @@ def lib() -> ctypes.CDLL:
         L.minhash_check_coeffs.restype = ctypes.c_int
         L.minhash_status.argtypes = [vp, vp]
         L.minhash_status.restype = ctypes.c_int
+        L.minhash_status_async.argtypes = [vp, vp, vp]
+        L.minhash_status_async.restype = ctypes.c_int
         L.minhash_pack_indices.argtypes = [vp, vp, i64, vp, vp, vp, i64, vp, vp]
         L.minhash_pack_indices.restype = ctypes.c_int
         L.minhash_unpack_indices.argtypes = [vp, vp, vp, vp, i64, i64, vp, vp, vp]
@@ -269,6 +272,15 @@ def status(workspace: torch.Tensor, stream=None) -> int:
     return int(lib().minhash_status(_ptr(workspace), _stream_handle(stream)))
 
 
+def status_async(workspace: torch.Tensor, status_out: torch.Tensor, stream=None) -> None:
+    """Enqueues the store of what ``status`` would report into ``status_out`` (one int32 on the device)."""
+    if status_out.dtype != torch.int32 or status_out.numel() < 1 or status_out.device != workspace.device:
+        raise TypeError("status_out must be an int32 tensor on the device of the workspace")
+    rc = lib().minhash_status_async(_ptr(workspace), _ptr(status_out), _stream_handle(stream))
+    if rc != 0:
+        _raise(rc)
+
+
 def pack_indices(row_ptr: torch.Tensor, col_idx: torch.Tensor, stream=None):
     """Sorted rows as tiles of differences (see include/minhash.h).  Returns device tensors
     (width int32-storage [n], word_ptr int64 [n+1], words int32-storage [word_ptr[n]]); waits
@@ -430,6 +442,7 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
     col_d = [torch.empty(max_nnz, dtype=torch.int32, device=dev) for _ in range(n_buf)]
     out_d = [torch.empty((max_rows, sig), dtype=torch.uint8, device=dev) for _ in range(n_buf)]
     ws = alloc_workspace(max_rows, max_nnz, k, family, dev)
+    codes = torch.zeros(max(len(batches), 1), dtype=torch.int32, device=dev)     # what each call reported: the next one clears it
     s_in, s_run, s_out = torch.cuda.Stream(dev), torch.cuda.Stream(dev), torch.cuda.Stream(dev)
     now = torch.cuda.current_stream(dev)
     for s in (s_in, s_run, s_out):
@@ -461,6 +474,8 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
             s_run.wait_event(out_done[u])         # the previous signatures left this output buffer
         minhash_signatures(rp_d[u][: n + 1], col_d[u][:nnz], D, k, b, family, params, out=out_d[u][:n],
                            out_stride=sig, perm_ld=perm_ld, workspace=ws, stream=s_run, flags=flags)
+        if n > 0:
+            status_async(ws, codes[i: i + 1], stream=s_run)
         run_done[u].record(s_run)
         s_out.wait_event(run_done[u])
         with torch.cuda.stream(s_out):
@@ -469,17 +484,16 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
     for s in (s_in, s_run, s_out):
         s.synchronize()
     now.wait_stream(s_out)
-    # the deferred checks of the last non-empty batch (work-list overflow, MINHASH_FLAG_VALIDATE findings); every
-    # batch was bounded by max_rows / max_nnz above, so an overflow can only come from offsets that contradict the sizes
-    if any(r.shape[0] > 0 for r in results):
-        rc = status(ws, s_run)
-        if rc != 0:
-            _raise(rc)
+    # the deferred checks of every batch (work-list overflow, MINHASH_FLAG_VALIDATE findings); every batch was
+    # bounded by max_rows / max_nnz above, so an overflow can only come from offsets that contradict the sizes
+    bad = [int(c) for c in codes[: len(batches)].cpu().tolist() if c != 0]
+    if bad:
+        _raise(bad[0])
     return results
 
 
 def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: torch.Tensor, max_rows: int, max_nnz: int,
-                          max_words: int, flags: int = 0, decode_in_kernel: bool = True):
+                          max_words: int, flags: int = 0, decode_in_kernel: bool = True, first_batch_slices: int = 4):
     """``stream_batches`` for rows that cross the host link as tiles of differences
     (``pack_indices``): about half the bytes for sorted heavy-tailed rows, so that
     the copies hide under the kernels again.
@@ -494,7 +508,11 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
 
     With ``decode_in_kernel`` (the default) there is no decoder pass at all: the
     hash kernels fetch the words and decode each tile while they stage it
-    (``minhash_signatures_packed``).
+    (``minhash_signatures_packed``).  The first batch then goes in
+    ``first_batch_slices`` slices of rows with about equal numbers of words, each
+    hashed as soon as its words have arrived (the offsets in word_ptr are absolute,
+    so a slice is the same arrays from another row on): nothing hides the first
+    copy, so it is made short.
     """
     dev = params.device
     sig = (k * b + 7) // 8
@@ -505,7 +523,11 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
     words_d = [torch.empty(max(max_words, 1), dtype=torch.int32, device=dev) for _ in range(n_buf)]
     col_d = None if decode_in_kernel else torch.empty(max(max_nnz, 1), dtype=torch.int32, device=dev)    # one stream: one buffer
     out_d = [torch.empty((max_rows, sig), dtype=torch.uint8, device=dev) for _ in range(n_buf)]
-    codes = torch.zeros(max(len(batches), 1), dtype=torch.int32, device=dev)
+    codes = torch.zeros(max(len(batches), 1), dtype=torch.int32, device=dev)            # the decoder's reports
+    n_slices = max(1, first_batch_slices) if decode_in_kernel else 1
+    hash_codes = torch.zeros(len(batches) + n_slices, dtype=torch.int32, device=dev)    # the hash calls', one per call
+    n_calls = 0
+    slice_done = [torch.cuda.Event() for _ in range(n_slices)]
     ws = alloc_workspace(max_rows, max_nnz, k, family, dev)
     s_in, s_run, s_out = (torch.cuda.Stream(dev) for _ in range(3))
     now = torch.cuda.current_stream(dev)
@@ -527,26 +549,50 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
         results.append(out_h)
         if i >= n_buf:
             s_in.wait_event(run_done[u])          # decoder and kernels that read this set of buffers (row_ptr too) have finished
+        # rows at which the batch is cut (the first batch only, and only if it has rows to cut)
+        cuts = [0, n]
+        if i == 0 and n_slices > 1 and n >= n_slices and n_words > 0:
+            marks = torch.searchsorted(wp_h, torch.arange(1, n_slices, dtype=torch.int64) * (n_words // n_slices))
+            cuts = sorted(set([0, n] + [int(min(max(int(m), 1), n)) for m in marks]))
         with torch.cuda.stream(s_in):
             rp_d[u][: n + 1].copy_(rp_h, non_blocking=True)
             wp_d[u][: n + 1].copy_(wp_h, non_blocking=True)
             wd_d[u][:n].copy_(width_h.view(torch.int32), non_blocking=True)
-            at = 0
-            for p in pieces:
-                words_d[u][at: at + p.numel()].copy_(p.view(torch.int32), non_blocking=True)
-                at += p.numel()
+            at, next_cut = 0, 1
+            for p in pieces:                      # pieces of the word array, cut again where a slice of rows ends
+                done = 0
+                while done < p.numel():
+                    upto = int(wp_h[cuts[next_cut]]) if next_cut < len(cuts) - 1 else n_words
+                    take = min(p.numel() - done, max(upto - at, 0))
+                    if take > 0:
+                        words_d[u][at: at + take].copy_(p[done: done + take].view(torch.int32), non_blocking=True)
+                        at += take
+                        done += take
+                    if at >= upto and next_cut < len(cuts) - 1:
+                        slice_done[next_cut - 1].record(s_in)
+                        next_cut += 1
             in_done[u].record(s_in)
-        s_run.wait_event(in_done[u])
         if i >= n_buf:
             s_run.wait_event(out_done[u])         # the previous signatures left this output buffer
         if decode_in_kernel:
-            minhash_signatures_packed(rp_d[u][: n + 1], wd_d[u][:n], wp_d[u][: n + 1], words_d[u][:n_words], D, k, b, family, params,
-                                      out=out_d[u][:n], workspace=ws, stream=s_run, flags=flags)
+            for c in range(len(cuts) - 1):
+                r0, r1 = cuts[c], cuts[c + 1]
+                s_run.wait_event(slice_done[c] if c < len(cuts) - 2 else in_done[u])
+                minhash_signatures_packed(rp_d[u][r0: r1 + 1], wd_d[u][r0:r1], wp_d[u][r0: r1 + 1], words_d[u][:n_words], D, k, b,
+                                          family, params, out=out_d[u][r0:r1], workspace=ws,
+                                          nnz_upper_bound=max_nnz, stream=s_run, flags=flags)
+                if r1 > r0:
+                    status_async(ws, hash_codes[n_calls: n_calls + 1], stream=s_run)
+                    n_calls += 1
         else:
+            s_run.wait_event(in_done[u])
             unpack_indices(rp_d[u][: n + 1], wd_d[u][:n], wp_d[u][: n + 1], words_d[u][:n_words], col_d, codes[i: i + 1],
                            stream=s_run)
             minhash_signatures(rp_d[u][: n + 1], col_d[:nnz], D, k, b, family, params, out=out_d[u][:n],
                                out_stride=sig, workspace=ws, stream=s_run, flags=flags)
+            if n > 0:
+                status_async(ws, hash_codes[n_calls: n_calls + 1], stream=s_run)
+                n_calls += 1
         run_done[u].record(s_run)
         s_out.wait_event(run_done[u])
         with torch.cuda.stream(s_out):
@@ -555,12 +601,8 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
     for s in (s_in, s_run, s_out):
         s.synchronize()
     now.wait_stream(s_out)
-    bad = [int(c) for c in codes[: len(batches)].cpu().tolist() if c != 0]
+    bad = [int(c) for c in codes[: len(batches)].cpu().tolist() + hash_codes[:n_calls].cpu().tolist() if c != 0]
     if bad:
         _raise(bad[0])
-    if any(r.shape[0] > 0 for r in results):
-        rc = status(ws, s_run)
-        if rc != 0:
-            _raise(rc)
     return results
 

@@ -43,6 +43,13 @@ def test_version_and_error_strings(lib):
     assert mh.error_string(-99) == "unknown error code"
 
 
+def test_status_calls_reject_null_pointers(lib):
+    import ctypes
+    assert lib.minhash_status(None, None) == -1
+    assert lib.minhash_status_async(None, None, None) == -1
+    assert lib.minhash_status_async(ctypes.c_void_p(256), None, None) == -1
+
+
 def test_workspace_size_query():
     small = mh.workspace_bytes(1000, 650_000, 64, mh.FAMILY_2U_M31)
     big = mh.workspace_bytes(350_000, 1_300_000_000, 500, mh.FAMILY_2U_M31)

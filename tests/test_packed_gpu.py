@@ -149,18 +149,18 @@ def test_streamed_packed_batches_equal_the_oracle():
         rp_b = (rp[lo:hi + 1] - rp[lo]).copy()
         width, word_ptr, words = mh.pack_indices(_dev(rp_b), _dev(col[rp[lo]:rp[hi]].copy()))
         words_h = words.cpu().pin_memory()
-        if lo == 450:                                           # words handed over in pieces
+        if lo in (0, 450):                                      # words handed over in pieces
             cut = words_h.numel() // 3
             words_h = [words_h[:cut].clone().pin_memory(), words_h[cut:].clone().pin_memory()]
         batches.append((torch.from_numpy(rp_b).pin_memory(), width.cpu().pin_memory(), word_ptr.cpu().pin_memory(), words_h))
         max_words = max(max_words, words.numel())
     max_rows = max(h - l for l, h in zip(bounds[:-1], bounds[1:]))
     max_nnz = max(int(rp[h] - rp[l]) for l, h in zip(bounds[:-1], bounds[1:]))
-    for decode_in_kernel in (True, False):
+    for decode_in_kernel, slices in ((True, 4), (True, 1), (True, 7), (True, 500), (False, 4)):    # the first batch goes in slices of rows
         outs = mh.stream_batches_packed(batches, D, k, b, family, torch.from_numpy(c.view(np.int64)).to(DEV), max_rows, max_nnz,
-                                        max_words, decode_in_kernel=decode_in_kernel)
+                                        max_words, decode_in_kernel=decode_in_kernel, first_batch_slices=slices)
         got = np.concatenate([o.numpy() for o in outs], axis=0)
-        assert np.array_equal(got, want)
+        assert np.array_equal(got, want), (decode_in_kernel, slices)
 
 
 # ------------------------------------------------------------------ decoded inside the hash kernels

@@ -503,6 +503,27 @@ def test_streamed_batches_equal_one_shot_and_oracle():
     assert np.array_equal(got, want)
 
 
+def test_a_bad_batch_in_the_middle_of_a_stream_is_reported():
+    """Every call clears what the one before it reported in the shared workspace, so the batch loop
+    collects a code per batch: an index that is not below D in the first of three batches still
+    raises at the end (the other batches are fine)."""
+    D, k, b, family = 1 << 20, 64, 8, mh.FAMILY_2U_M31
+    nnz = np.array([5, 300, 40, 7, 900, 12], dtype=np.int64)
+    rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, D, seed=9)
+    batches = []
+    for lo, hi in ((0, 2), (2, 4), (4, 6)):
+        rp_b = torch.from_numpy((rp[lo:hi + 1] - rp[lo]).copy()).pin_memory()
+        col_b = col[rp[lo]:rp[hi]].copy()
+        if lo == 0:
+            col_b[17] = D + 3
+        batches.append((rp_b, torch.from_numpy(col_b.view(np.int32)).pin_memory()))
+    c = _to_dev(W.coefficients(k, family, seed=10))
+    with pytest.raises(mh.MinhashError) as err:
+        mh.stream_batches(batches, D, k, b, family, c, 2, 1000, flags=mh.FLAG_VALIDATE)
+    assert err.value.code == -9
+    assert len(mh.stream_batches(batches[1:], D, k, b, family, c, 2, 1000, flags=mh.FLAG_VALIDATE)) == 2
+
+
 def test_call_is_capturable_in_a_hip_graph_and_replays_exactly():
     """The entry point only enqueues kernels (no allocation, no memset node, no sync), so a
     serving loop can capture it once and replay it; every replay, with eager work and
