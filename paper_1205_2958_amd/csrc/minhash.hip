@@ -3,7 +3,9 @@
 // One call of minhash_signatures enqueues, on the caller's stream:
 //
 //   mh_reset_kernel      clears the work-list header in the workspace and picks
-//                        the chunk size of this call from the batch's size
+//                        the chunk size of this call from the batch's size (a
+//                        batch of up to 1 024 rows does this inside the next
+//                        kernel, without atomics)
 //   mh_bin_rows_kernel   load balancer: reads row_ptr, emits one work item per
 //                        row, or one per chunk of nonzeros for long rows (each
 //                        chunk gets a vector of k partial minima in the
@@ -24,8 +26,8 @@
 //                        rare values such a key cannot vouch for are computed
 //                        again from the exact arithmetic before they are
 //                        stored.  When k needs fewer than 64 lanes the spare
-//                        lanes take slices of the nonzeros and are merged by a
-//                        butterfly of cross-lane minima.  Whole rows are
+//                        lanes take slices of the nonzeros and are merged by
+//                        cross-lane minima (lane swap, swizzle, row shifts).  Whole rows are
 //                        truncated to b bits, packed and stored by the same
 //                        wavefront; a chunk of a split row stores its k
 //                        partial minima with plain coalesced stores.
@@ -33,8 +35,10 @@
 //                        (exact: the minimum over a union is the minimum of the
 //                        minima of the parts), truncates, packs and stores.
 //
-// Wavefronts never synchronise with each other inside a kernel: each has its
-// own LDS region and its own work units, so there is no barrier anywhere.
+// In the hash and table kernels wavefronts never synchronise with each other:
+// each has its own LDS region and its own work units.  (The row-binning kernel's
+// blocks and the blocks of the finalize kernel that share a row of many chunks
+// do use block barriers.)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
