@@ -972,6 +972,50 @@ struct Pol4U61 {
     static constexpr int DEG = 4;
 };
 
+// 4U with p = 2^61-1 and a power-of-two D <= 2^31 (so t < 2^31), the three Horner steps ordered by hand
+// (half_4u61_pow2).  A function keeps c3 as two words and c2, c1, c0 + 1 as register pairs, the 64-bit addends
+// of the steps' first multiply-adds, and a pair whose high word stays zero for the second ones.
+struct Fn4U61H {
+    uint32_t lo3, hi3;
+    u32x2 c2, c1, a0;
+    mutable u32x2 hz;
+};
+struct Pol4U61Hand {
+    static constexpr int NW = 1;
+    static constexpr int MIN_WAVES = 2;
+    static constexpr bool TRACK_MAX = false;
+    static constexpr bool SHIFTED_KEY = false;
+    static constexpr bool DOUBLED_KEY = false;
+    static constexpr bool TWO_MAXIMA = false;
+    static constexpr bool SHIFT_END = false;
+    static constexpr bool FRAC_KEY = false;
+    static constexpr bool GUARDED = false;
+    static constexpr bool VARIABLE_NF = false;
+    using Fn = Fn4U61H;
+    static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
+    {
+        const uint64_t c0 = valid ? c[0] : 0, c1 = valid ? c[1] : 0, c2 = valid ? c[2] : 0, c3 = valid ? c[3] : 0;
+        Fn f;
+        f.lo3 = (uint32_t)c3; f.hi3 = (uint32_t)(c3 >> 32);
+        f.c2 = u32x2{(uint32_t)c2, (uint32_t)(c2 >> 32)};
+        f.c1 = u32x2{(uint32_t)c1, (uint32_t)(c1 >> 32)};
+        f.a0 = u32x2{(uint32_t)(c0 + 1), (uint32_t)((c0 + 1) >> 32)};
+        f.hz = u32x2{0u, 0u};
+        return f;
+    }
+    static __device__ __forceinline__ void stage(uint32_t t, uint32_t* w) { w[0] = t; }
+    static __device__ __forceinline__ uint32_t key(const Fn& f, const uint32_t* w, const ModD& md, uint64_t D)
+    {
+        Fn4U61 g;
+        g.c3lo = f.lo3; g.c3hi = f.hi3; g.c2lo = f.c2.x; g.c2hi = f.c2.y; g.c1lo = f.c1.x; g.c1hi = f.c1.y; g.a0lo = f.a0.x; g.a0hi = f.a0.y;
+        return hash_4u61<true>(g, w[0], md, D);
+    }
+    template <int NF>
+    static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                const uint32_t* wb, const ModDV& md, uint64_t D);
+    static constexpr int DEG = 4;
+};
+
 // ------------------------------------------------------------------ two nonzeros x 8 functions
 // The unit of the hot loop: fold the 16 evaluations of two staged nonzeros into
 // the 8 running extrema.  The generic form leaves the schedule to the compiler.
@@ -1488,6 +1532,70 @@ __device__ __forceinline__ void half_2u61_steps32(const Fn2U61V (&fn)[HASH_FPL],
 #pragma unroll
         for (int g = 0; g < NF; ++g) y[g] = L[g].x;
     }
+}
+
+// One Horner step of horner_step_61 (mh_arith.h) for t < 2^31, eight functions stage by stage: the value
+// (hi : lo), hi <= 2^29, times t plus a 64-bit coefficient is L = lo t + c (the coefficient is the 64-bit addend:
+// below 2^63 + 2^61) and H = hi t + (L >> 32) < 2^61; bits 61 and up, H >> 29, are added to the 61 bits below
+// them.  The carry of that addition stays in the scalar pair of the function slot.
+template <int NF, class LoOf, class HiOf, class COf>
+__device__ __forceinline__ void horner_step_4u61(const Fn4U61H (&fn)[HASH_FPL], uint32_t (&lo)[HASH_FPL], uint32_t (&hi)[HASH_FPL],
+                                                 LoOf lo_in, HiOf hi_in, COf c, uint32_t t, const ModDV& md)
+{
+    u32x2 L[HASH_FPL], H[HASH_FPL];
+    uint32_t s[HASH_FPL], r;
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, L[g], lo_in(g), t, c(g));
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) {
+        asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "v"(L[g].y));
+        fn[g].hz.x = r;
+    }
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, H[g], hi_in(g), t, fn[g].hz);
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_CARRY_OP(g, MH_ADD_CO_TEXT, "=v"(lo[g]) : "v"(L[g].x), "v"(s[g]));
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(hi[g]) : "v"(H[g].x), "v"(md.mask29));
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) MH_CARRY_OP(g, MH_ADDC0_TEXT, "+v"(hi[g]) :);
+}
+// residue_lo_4u61 of mh_arith.h and the mask: lo + (hi >> 29) - 1, lowest s bits
+template <int NF>
+__device__ __forceinline__ void half_4u61_pow2(const Fn4U61H (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t t, const ModDV& md)
+{
+    uint32_t lo[HASH_FPL], hi[HASH_FPL], lo2[HASH_FPL], hi2[HASH_FPL];
+    horner_step_4u61<NF>(fn, lo, hi, [&](int g) { return fn[g].lo3; }, [&](int g) { return fn[g].hi3; }, [&](int g) { return fn[g].c2; }, t, md);
+    horner_step_4u61<NF>(fn, lo2, hi2, [&](int g) { return lo[g]; }, [&](int g) { return hi[g]; }, [&](int g) { return fn[g].c1; }, t, md);
+    horner_step_4u61<NF>(fn, lo, hi, [&](int g) { return lo2[g]; }, [&](int g) { return hi2[g]; }, [&](int g) { return fn[g].a0; }, t, md);
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_lshrrev_b32 %0, 29, %0" : "+v"(hi[g]));
+    issue_priority<1>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_add3_u32 %0, %0, %1, -1" : "+v"(lo[g]) : "v"(hi[g]));
+    issue_priority<0>();
+#pragma unroll
+    for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(y[g]) : "v"(lo[g]), "v"(md.mask));
+    issue_priority<1>();
+}
+template <int NF>
+__device__ __forceinline__ void Pol4U61Hand::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                  const uint32_t* wb, const ModDV& md, uint64_t)
+{
+    uint32_t ya[HASH_FPL], yb[HASH_FPL];
+    half_4u61_pow2<NF>(fn, ya, wa[0], md);
+    half_4u61_pow2<NF>(fn, yb, wb[0], md);
+#pragma unroll
+    for (int g = 0; g < NF; ++g)
+        asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
 }
 
 // Ablation: the definition evaluated with the % operator on runtime moduli (Horner
@@ -2675,7 +2783,9 @@ int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream
         else launch_hash<Pol2U61<false>>(a, nf, l);
         break;
     case MINHASH_4U_M61:
-        if (pow2) launch_hash<Pol4U61<true>>(a, nf, l); else launch_hash<Pol4U61<false>>(a, nf, l);
+        if (pow2 && D <= (1ull << 31)) launch_hash<Pol4U61Hand>(a, nf, l);       // t < 2^31: the Horner steps ordered by hand
+        else if (pow2) launch_hash<Pol4U61<true>>(a, nf, l);
+        else launch_hash<Pol4U61<false>>(a, nf, l);
         break;
     case MINHASH_2U_MS32: launch_hash<Pol2UMS32<false>>(a, nf, l); break;
     case MINHASH_2U_MS32_HIGH: launch_hash<Pol2UMS32<true>>(a, nf, l); break;
