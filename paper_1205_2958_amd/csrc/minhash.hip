@@ -1438,26 +1438,24 @@ __device__ __forceinline__ void half_2u61_pow2(const Fn2U61V (&fn)[HASH_FPL], ui
 // 2^32), congruent to X + 1 (residue_2u61 of mh_arith.h), with bit 61 folded once more x' = (X mod p) + 1 in
 // [1, p]; then reduce61_mod_d's 32-bit steps on x' (the quotient estimate from bits 29..60 of x, which only
 // makes it a hair smaller; the low word of x' exact), and at the end the 1 comes off: of u = (x' mod D') - 1
-// and u + D' the smaller as unsigned words.  A carry links the two words of x; each function slot keeps it in
-// the scalar pair that its multiply-adds name.
-#define MH_CARRY_OP(SLOT, TEXT, ...)                                                                                       \
-    do {                                                                                                               \
-        if (((SLOT) & 7) == 0) asm volatile(TEXT("s[84:85]") : __VA_ARGS__ : "s84", "s85");                            \
-        else if (((SLOT) & 7) == 1) asm volatile(TEXT("s[86:87]") : __VA_ARGS__ : "s86", "s87");                       \
-        else if (((SLOT) & 7) == 2) asm volatile(TEXT("s[88:89]") : __VA_ARGS__ : "s88", "s89");                       \
-        else if (((SLOT) & 7) == 3) asm volatile(TEXT("s[90:91]") : __VA_ARGS__ : "s90", "s91");                       \
-        else if (((SLOT) & 7) == 4) asm volatile(TEXT("s[92:93]") : __VA_ARGS__ : "s92", "s93");                       \
-        else if (((SLOT) & 7) == 5) asm volatile(TEXT("s[94:95]") : __VA_ARGS__ : "s94", "s95");                       \
-        else if (((SLOT) & 7) == 6) asm volatile(TEXT("s[96:97]") : __VA_ARGS__ : "s96", "s97");                       \
-        else asm volatile(TEXT("s[98:99]") : __VA_ARGS__ : "s98", "s99");                                              \
-    } while (0)
-#define MH_ADD_CO_TEXT(SP) "v_add_co_u32 %0, " SP ", %1, %2"
-#define MH_ADDC0_TEXT(SP) "v_addc_co_u32 %0, " SP ", 0, %0, " SP
+// and u + D' the smaller as unsigned words.  A carry links the two words of x.
+// The two halves of a 64-bit addition.  The carry is an operand of both statements (a scalar pair of the
+// compiler's choice, one per function slot), so that nothing the compiler places between them can take its
+// register.
+__device__ __forceinline__ void add_carry_out(uint32_t& d, uint64_t& carry, uint32_t a, uint32_t b)
+{
+    asm volatile("v_add_co_u32 %0, %1, %2, %3" : "=v"(d), "=s"(carry) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void add_carry_in(uint32_t& d, uint64_t& carry)       // d += carry (0 or 1)
+{
+    asm volatile("v_addc_co_u32 %0, %1, 0, %0, %1" : "+v"(d), "+s"(carry));
+}
 template <int NF>
 __device__ __forceinline__ void half_2u61_steps32(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t t, const ModDV& md)
 {
     u32x2 L[HASH_FPL], H[HASH_FPL];
     uint32_t s[HASH_FPL], xlo[HASH_FPL], xhi[HASH_FPL], q[HASH_FPL], r;
+    uint64_t carry[HASH_FPL];
     issue_priority<1>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, L[g], fn[g].e0, t, fn[g].add);
@@ -1473,13 +1471,13 @@ __device__ __forceinline__ void half_2u61_steps32(const Fn2U61V (&fn)[HASH_FPL],
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_CARRY_OP(g, MH_ADD_CO_TEXT, "=v"(xlo[g]) : "v"(L[g].x), "v"(s[g]));      // low word of x, carry kept
+    for (int g = 0; g < NF; ++g) add_carry_out(xlo[g], carry[g], L[g].x, s[g]);                    // low word of x
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(xhi[g]) : "v"(H[g].x), "v"(md.mask29));
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_CARRY_OP(g, MH_ADDC0_TEXT, "+v"(xhi[g]) :);                      // high word: bits 32..61 of x
+    for (int g = 0; g < NF; ++g) add_carry_in(xhi[g], carry[g]);                                  // high word: bits 32..61 of x
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(xhi[g]), "v"(xlo[g]));   // bits 29..60 of x
 #pragma unroll
@@ -1537,13 +1535,14 @@ __device__ __forceinline__ void half_2u61_steps32(const Fn2U61V (&fn)[HASH_FPL],
 // One Horner step of horner_step_61 (mh_arith.h) for t < 2^31, eight functions stage by stage: the value
 // (hi : lo), hi <= 2^29, times t plus a 64-bit coefficient is L = lo t + c (the coefficient is the 64-bit addend:
 // below 2^63 + 2^61) and H = hi t + (L >> 32) < 2^61; bits 61 and up, H >> 29, are added to the 61 bits below
-// them.  The carry of that addition stays in the scalar pair of the function slot.
+// them, with a carry from the low word to the high one.
 template <int NF, class LoOf, class HiOf, class COf>
 __device__ __forceinline__ void horner_step_4u61(const Fn4U61H (&fn)[HASH_FPL], uint32_t (&lo)[HASH_FPL], uint32_t (&hi)[HASH_FPL],
                                                  LoOf lo_in, HiOf hi_in, COf c, uint32_t t, const ModDV& md)
 {
     u32x2 L[HASH_FPL], H[HASH_FPL];
     uint32_t s[HASH_FPL], r;
+    uint64_t carry[HASH_FPL];
     issue_priority<1>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) MH_MAD(g, u64_u32, L[g], lo_in(g), t, c(g));
@@ -1559,13 +1558,13 @@ __device__ __forceinline__ void horner_step_4u61(const Fn4U61H (&fn)[HASH_FPL], 
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(H[g].y), "v"(H[g].x));
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_CARRY_OP(g, MH_ADD_CO_TEXT, "=v"(lo[g]) : "v"(L[g].x), "v"(s[g]));
+    for (int g = 0; g < NF; ++g) add_carry_out(lo[g], carry[g], L[g].x, s[g]);
     issue_priority<0>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(hi[g]) : "v"(H[g].x), "v"(md.mask29));
     issue_priority<1>();
 #pragma unroll
-    for (int g = 0; g < NF; ++g) MH_CARRY_OP(g, MH_ADDC0_TEXT, "+v"(hi[g]) :);
+    for (int g = 0; g < NF; ++g) add_carry_in(hi[g], carry[g]);
 }
 // residue_lo_4u61 of mh_arith.h and the mask: lo + (hi >> 29) - 1, lowest s bits
 template <int NF>
