@@ -897,7 +897,7 @@ struct Pol2U61 {
     static constexpr bool SHIFT_END = false;
     static constexpr bool FRAC_KEY = false;
     static constexpr bool GUARDED = POW2;
-    static constexpr bool VARIABLE_NF = POW2;    // hand-ordered steps exist for 5..8 functions per lane
+    static constexpr bool VARIABLE_NF = POW2 || STEPS32;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = std::conditional_t<POW2 || STEPS32, Fn2U61V, Fn2U61>;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs& a)
     {
@@ -990,7 +990,7 @@ struct Pol4U61Hand {
     static constexpr bool SHIFT_END = false;
     static constexpr bool FRAC_KEY = false;
     static constexpr bool GUARDED = false;
-    static constexpr bool VARIABLE_NF = false;
+    static constexpr bool VARIABLE_NF = true;    // hand-ordered steps exist for 5..8 functions per lane
     using Fn = Fn4U61H;
     static __device__ __forceinline__ Fn load(const uint64_t* c, bool valid, const KArgs&)
     {
@@ -2709,8 +2709,10 @@ int make_plan(Plan* plan, const int64_t* row_ptr, const uint32_t* col_idx, int64
     plan->ftile_size = PERM_FTILE;
     if (family != MINHASH_PERM) {
         // the kernels ordered by hand come with 5..8 functions per lane
-        const bool variable = !plan->generic_mod && family != MINHASH_4U_M61 &&
-                              !(family == MINHASH_2U_M61 && !plan->guarded61);
+        const bool hand4u61 = family == MINHASH_4U_M61 && pow2 && D <= (1ull << 31);
+        const bool hand2u61 = family == MINHASH_2U_M61 && (plan->guarded61 || a.md.M61q != 0);
+        const bool variable = !plan->generic_mod && (family != MINHASH_4U_M61 || hand4u61) &&
+                              (family != MINHASH_2U_M61 || hand2u61);
         int lg = 0;
         functions_per_lane(k, variable, &plan->nf, &lg);
         a.log2_fl = lg;
