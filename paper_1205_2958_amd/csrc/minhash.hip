@@ -972,17 +972,18 @@ struct Pol4U61 {
     static constexpr int DEG = 4;
 };
 
-// 4U with p = 2^61-1 and a power-of-two D <= 2^31 (so t < 2^31), the three Horner steps ordered by hand
-// (half_4u61_pow2).  A function keeps c3 as two words and c2, c1, c0 + 1 as register pairs, the 64-bit addends
+// 4U with p = 2^61-1 and t < 2^31, the three Horner steps ordered by hand: a power-of-two D <= 2^31
+// (half_4u61_pow2), or another D of at most 2^32 / 3 (half_4u61_steps32).  A function keeps c3 as two words and c2, c1, c0 + 1 as register pairs, the 64-bit addends
 // of the steps' first multiply-adds, and a pair whose high word stays zero for the second ones.
 struct Fn4U61H {
     uint32_t lo3, hi3;
     u32x2 c2, c1, a0;
     mutable u32x2 hz;
 };
+template <bool POW2>
 struct Pol4U61Hand {
     static constexpr int NW = 1;
-    static constexpr int MIN_WAVES = 2;
+    static constexpr int MIN_WAVES = 3;          // 168 registers: the coefficients take 80 of them
     static constexpr bool TRACK_MAX = false;
     static constexpr bool SHIFTED_KEY = false;
     static constexpr bool DOUBLED_KEY = false;
@@ -1008,7 +1009,7 @@ struct Pol4U61Hand {
     {
         Fn4U61 g;
         g.c3lo = f.lo3; g.c3hi = f.hi3; g.c2lo = f.c2.x; g.c2hi = f.c2.y; g.c1lo = f.c1.x; g.c1hi = f.c1.y; g.a0lo = f.a0.x; g.a0hi = f.a0.y;
-        return hash_4u61<true>(g, w[0], md, D);
+        return hash_4u61<POW2>(g, w[0], md, D);
     }
     template <int NF>
     static __device__ __forceinline__ void pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
@@ -1450,11 +1451,14 @@ __device__ __forceinline__ void add_carry_in(uint32_t& d, uint64_t& carry)      
 {
     asm volatile("v_addc_co_u32 %0, %1, 0, %0, %1" : "+v"(d), "+s"(carry));
 }
+template <int NF, class FnT>
+__device__ __forceinline__ void residue_mod_d_steps32(const FnT (&fn)[HASH_FPL], uint32_t (&xlo)[HASH_FPL], uint32_t (&xhi)[HASH_FPL],
+                                                      uint32_t (&y)[HASH_FPL], const ModDV& md);
 template <int NF>
 __device__ __forceinline__ void half_2u61_steps32(const Fn2U61V (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t t, const ModDV& md)
 {
     u32x2 L[HASH_FPL], H[HASH_FPL];
-    uint32_t s[HASH_FPL], xlo[HASH_FPL], xhi[HASH_FPL], q[HASH_FPL], r;
+    uint32_t s[HASH_FPL], xlo[HASH_FPL], xhi[HASH_FPL], r;
     uint64_t carry[HASH_FPL];
     issue_priority<1>();
 #pragma unroll
@@ -1478,6 +1482,16 @@ __device__ __forceinline__ void half_2u61_steps32(const Fn2U61V (&fn)[HASH_FPL],
     issue_priority<1>();
 #pragma unroll
     for (int g = 0; g < NF; ++g) add_carry_in(xhi[g], carry[g]);                                  // high word: bits 32..61 of x
+    residue_mod_d_steps32<NF>(fn, xlo, xhi, y, md);
+}
+// The second part: from the folded value x = (xhi : xlo) in [1, 2^61 + 2^32), congruent to X + 1, to (X mod p) mod D.
+// Entered and left at raised priority.  (4U with p = 2^61-1 ends its Horner steps on the same kind of value.)
+template <int NF, class FnT>
+__device__ __forceinline__ void residue_mod_d_steps32(const FnT (&fn)[HASH_FPL], uint32_t (&xlo)[HASH_FPL], uint32_t (&xhi)[HASH_FPL],
+                                                      uint32_t (&y)[HASH_FPL], const ModDV& md)
+{
+    u32x2 L[HASH_FPL];
+    uint32_t s[HASH_FPL], q[HASH_FPL], r;
 #pragma unroll
     for (int g = 0; g < NF; ++g) asm volatile("v_alignbit_b32 %0, %1, %2, 29" : "=v"(s[g]) : "v"(xhi[g]), "v"(xlo[g]));   // bits 29..60 of x
 #pragma unroll
@@ -1585,13 +1599,29 @@ __device__ __forceinline__ void half_4u61_pow2(const Fn4U61H (&fn)[HASH_FPL], ui
     for (int g = 0; g < NF; ++g) asm volatile("v_and_b32 %0, %1, %2" : "=v"(y[g]) : "v"(lo[g]), "v"(md.mask));
     issue_priority<1>();
 }
+// the same for another D of at most 2^32 / 3: the Horner steps end on the value that residue_mod_d_steps32 starts from
 template <int NF>
-__device__ __forceinline__ void Pol4U61Hand::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
-                                                  const uint32_t* wb, const ModDV& md, uint64_t)
+__device__ __forceinline__ void half_4u61_steps32(const Fn4U61H (&fn)[HASH_FPL], uint32_t (&y)[HASH_FPL], uint32_t t, const ModDV& md)
+{
+    uint32_t lo[HASH_FPL], hi[HASH_FPL], lo2[HASH_FPL], hi2[HASH_FPL];
+    horner_step_4u61<NF>(fn, lo, hi, [&](int g) { return fn[g].lo3; }, [&](int g) { return fn[g].hi3; }, [&](int g) { return fn[g].c2; }, t, md);
+    horner_step_4u61<NF>(fn, lo2, hi2, [&](int g) { return lo[g]; }, [&](int g) { return hi[g]; }, [&](int g) { return fn[g].c1; }, t, md);
+    horner_step_4u61<NF>(fn, lo, hi, [&](int g) { return lo2[g]; }, [&](int g) { return hi2[g]; }, [&](int g) { return fn[g].a0; }, t, md);
+    residue_mod_d_steps32<NF>(fn, lo, hi, y, md);
+}
+template <bool POW2>
+template <int NF>
+__device__ __forceinline__ void Pol4U61Hand<POW2>::pair(const Fn (&fn)[HASH_FPL], uint32_t (&m)[HASH_ACC], const uint32_t* wa,
+                                                        const uint32_t* wb, const ModDV& md, uint64_t)
 {
     uint32_t ya[HASH_FPL], yb[HASH_FPL];
-    half_4u61_pow2<NF>(fn, ya, wa[0], md);
-    half_4u61_pow2<NF>(fn, yb, wb[0], md);
+    if constexpr (POW2) {
+        half_4u61_pow2<NF>(fn, ya, wa[0], md);
+        half_4u61_pow2<NF>(fn, yb, wb[0], md);
+    } else {
+        half_4u61_steps32<NF>(fn, ya, wa[0], md);
+        half_4u61_steps32<NF>(fn, yb, wb[0], md);
+    }
 #pragma unroll
     for (int g = 0; g < NF; ++g)
         asm volatile("v_min3_u32 %0, %0, %1, %2" : "+v"(m[g]) : "v"(ya[g]), "v"(yb[g]));
@@ -2709,7 +2739,7 @@ int make_plan(Plan* plan, const int64_t* row_ptr, const uint32_t* col_idx, int64
     plan->ftile_size = PERM_FTILE;
     if (family != MINHASH_PERM) {
         // the kernels ordered by hand come with 5..8 functions per lane
-        const bool hand4u61 = family == MINHASH_4U_M61 && pow2 && D <= (1ull << 31);
+        const bool hand4u61 = family == MINHASH_4U_M61 && ((pow2 && D <= (1ull << 31)) || a.md.M61q != 0);
         const bool hand2u61 = family == MINHASH_2U_M61 && (plan->guarded61 || a.md.M61q != 0);
         const bool variable = !plan->generic_mod && (family != MINHASH_4U_M61 || hand4u61) &&
                               (family != MINHASH_2U_M61 || hand2u61);
@@ -2784,7 +2814,8 @@ int enqueue(Plan& plan, int32_t family, uint64_t D, uint32_t flags, void* stream
         else launch_hash<Pol2U61<false>>(a, nf, l);
         break;
     case MINHASH_4U_M61:
-        if (pow2 && D <= (1ull << 31)) launch_hash<Pol4U61Hand>(a, nf, l);       // t < 2^31: the Horner steps ordered by hand
+        if (pow2 && D <= (1ull << 31)) launch_hash<Pol4U61Hand<true>>(a, nf, l);       // t < 2^31: the Horner steps ordered by hand
+        else if (a.md.M61q) launch_hash<Pol4U61Hand<false>>(a, nf, l);                // (M61q is 0 for a power of two)
         else if (pow2) launch_hash<Pol4U61<true>>(a, nf, l);
         else launch_hash<Pol4U61<false>>(a, nf, l);
         break;

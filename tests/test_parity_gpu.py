@@ -139,11 +139,12 @@ def test_functions_per_lane_variants(family, D, k):
     check_case(rp, col, D, k, 8, family, W.coefficients(k, family, seed=62 + k))
 
 
-@pytest.mark.parametrize("family,D", [(mh.FAMILY_2U_M61, 1010017424), (mh.FAMILY_2U_M61, 16609143), (mh.FAMILY_4U_M61, 1 << 30)])
+@pytest.mark.parametrize("family,D", [(mh.FAMILY_2U_M61, 1010017424), (mh.FAMILY_2U_M61, 16609143), (mh.FAMILY_4U_M61, 1 << 30),
+                                      (mh.FAMILY_4U_M61, 1010017424), (mh.FAMILY_4U_M61, 16609143)])
 @pytest.mark.parametrize("k", [100, 300, 400])
 def test_functions_per_lane_variants_of_the_m61_kernels(family, D, k):
     """The same for the kernels with p = 2^61-1 that are ordered by hand: 2U with a D that is not a power
-    of two (one and two stages of the residue modulo D), 4U with a power-of-two D."""
+    of two (one and two stages of the residue modulo D), 4U with a power-of-two D and with such a D."""
     nnz = np.array([0, 1, 5, 64, 255, 256, 257, 1000, 4095, 8193, 20000], dtype=np.int64)
     rp, col = W.row_ptr_from_nnz(nnz), W.csr_indices_np(nnz, 1 << 24, seed=63)
     if D & (D - 1):
