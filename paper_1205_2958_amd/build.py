@@ -47,9 +47,14 @@ def _compile(srcs, lib, verbose, extra) -> str:
 
 
 def build(verbose: bool = False, extra=()) -> str:
-    """Compiles both libraries; returns the path of the signature library."""
-    _compile(PROBE_SRCS, PROBE_LIB, verbose, extra)
-    return _compile(SRCS, LIB, verbose, extra)
+    """Compiles both libraries (side by side: the probe library takes a tenth of the time of the other);
+    returns the path of the signature library."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(2) as pool:
+        probe = pool.submit(_compile, PROBE_SRCS, PROBE_LIB, verbose, extra)
+        main = pool.submit(_compile, SRCS, LIB, verbose, tuple(extra) + ("-parallel-jobs=4",))
+        probe.result()
+        return main.result()
 
 
 if __name__ == "__main__":
