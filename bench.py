@@ -14,7 +14,10 @@ length-stratified sample of the same rows (the sample's GPU rows are compared
 with it).  Without --workload the same line carries, under "workloads", the
 same measurements for the other configurations (4U on the same rows, the
 permutation table, one resident batch of the heavy-tailed 2U p = 2^61 - 1
-workload, the 1 000-row batch), each with its own roofline and parity sample.
+workload, the 1 000-row batch), each with its own roofline and parity sample,
+and four batches of the heavy-tailed workload streamed from pinned host memory
+as packed index rows (copies, kernels and copies back overlapped; that rate
+includes PCIe and is never the top-level value).
 
     python bench.py --probe      instruction-issue and memory-system probes
                                  (the denominators the rooflines are set against)
@@ -100,6 +103,7 @@ ISSUE_MODEL_EVIDENCE = "profiles/issue_rates__probe.txt, profiles/sq_counters__h
 ORACLE_RATE_GUESS = {W.FAMILY_2U_M31: 7.0e7, W.FAMILY_4U_M31: 2.8e7, W.FAMILY_2U_M61: 1.6e7, W.FAMILY_2U_MS32: 1.0e8,
                      W.FAMILY_PERM: 6.0e7}
 SUB_WORKLOADS = ("large_4u", "perm_table", "huge_2u_m61", "tiny_2u")
+STREAMED_BATCHES = 4                    # batches of the streamed sub-record of a default run (all ten: --workload huge_2u_m61 --stream --packed)
 SPLIT = 8192                                                # rows longer than this are cut into chunks
 
 
@@ -334,6 +338,14 @@ def probe_mode(args) -> int:
 
 
 def stream_mode(args, w, params_np, pool) -> int:
+    rec = stream_record(args, w, params_np, pool, args.batches or w.n_batches(), args.packed, args.cpu_seconds)
+    if pool is not None:
+        pool.close()
+    print(json.dumps(rec))
+    return 0 if rec["parity_sample_ok"] in (None, True) else 1
+
+
+def stream_record(args, w, params_np, pool, n_batches: int, packed: bool, cpu_seconds: float):
     """The heavy-tailed workload end to end: batches resident in pinned host memory,
     H2D copy / kernels / D2H copy overlapped on three streams.  Sampled rows of the
     first and of the last batch are compared with the oracle."""
@@ -341,7 +353,6 @@ def stream_mode(args, w, params_np, pool) -> int:
     from paper_1205_2958_amd import minhash as mh
 
     dev = torch.device("cuda:0")
-    n_batches = args.batches or w.n_batches()
     params = torch.from_numpy(params_np.view(np.int64)).to(dev)
     batches, total_nnz, total_rows, max_nnz = [], 0, 0, 0
     batch_nnz, batch_bytes = [], []
@@ -349,7 +360,6 @@ def stream_mode(args, w, params_np, pool) -> int:
     # Pinned host memory on the GPU machine is capped near 64 GiB, less than the 80 GB of
     # indices of all ten batches: the first `distinct` batches are staged, later ones
     # re-send the staged bytes of batch (i mod distinct).  Rates are unaffected.
-    packed = args.packed
     distinct = min(n_batches, 10 if packed and args.distinct_batches == 7 else args.distinct_batches)
     data_of = [bi if bi < distinct else bi % distinct for bi in range(n_batches)]    # whose rows batch bi carries
     piece = 1 << 28                         # 1 GiB pieces: the pinned allocator rounds sizes up to powers of two
@@ -410,9 +420,9 @@ def stream_mode(args, w, params_np, pool) -> int:
     dt = time.perf_counter() - t0
     evals = float(total_nnz) * w.k
     parity, n_cmp, cpu_rec, covers = None, 0, None, []
-    if pool is not None:
+    if pool is not None and cpu_seconds > 0:
         parity = True
-        budget = ORACLE_RATE_GUESS[w.family] * args.cpu_seconds * pool.procs / 2.0
+        budget = ORACLE_RATE_GUESS[w.family] * cpu_seconds * pool.procs / 2.0
         for bi in sorted({0, n_batches - 1}):
             src = data_of[bi]
             nnz = w.nnz(src)
@@ -440,10 +450,9 @@ def stream_mode(args, w, params_np, pool) -> int:
         "roofline": None, "cpu_baseline": cpu_rec,
         "parity_sample_rows": n_cmp, "parity_sample_ok": parity,
     }
-    if pool is not None:
-        pool.close()
-    print(json.dumps(rec))
-    return 0 if parity in (None, True) else 1
+    del batches, outs, params
+    torch.cuda.empty_cache()
+    return rec
 
 
 def consumers_mode(args) -> int:
@@ -651,6 +660,12 @@ def main() -> int:
             ok = ok and sub["parity_sample_ok"] in (None, True) and sub.get("hip_graph", {}).get("replay_equals_eager", True)
             subs[name] = sub
             print("bench.py: %s done, %.3f ms per step" % (name, sub["ms_per_step"]), file=sys.stderr, flush=True)
+        # the same workload from pinned host memory, as packed index rows (a few batches: what a default run has time for)
+        hw = W.WORKLOADS["huge_2u_m61"]
+        sub = stream_record(args, hw, W.coefficients(hw.k, hw.family, hw.param_seed), pool, STREAMED_BATCHES, True, args.cpu_seconds / 5.0)
+        ok = ok and sub["parity_sample_ok"] in (None, True)
+        subs["huge_2u_m61_streamed_packed"] = sub
+        print("bench.py: huge_2u_m61 streamed, %d batches in %.1f ms" % (STREAMED_BATCHES, sub["ms_per_step"]), file=sys.stderr, flush=True)
         rec["workloads"] = subs
     if pool is not None:
         pool.close()
