@@ -655,17 +655,30 @@ def main() -> int:
         ok = ok and head["hip_graph"]["replay_equals_eager"]
     if args.workload == "all":
         subs = {}
+        # (a sub-record that fails says so in its place and in the exit status; the headline is printed regardless)
         for name in SUB_WORKLOADS:
-            sub = measure(W.WORKLOADS[name], args, pool, dev, args.cpu_seconds / 5.0)
+            try:
+                sub = measure(W.WORKLOADS[name], args, pool, dev, args.cpu_seconds / 5.0)
+            except Exception as e:          # noqa: BLE001
+                subs[name] = {"error": repr(e)}
+                ok = False
+                torch.cuda.empty_cache()
+                continue
             ok = ok and sub["parity_sample_ok"] in (None, True) and sub.get("hip_graph", {}).get("replay_equals_eager", True)
             subs[name] = sub
             print("bench.py: %s done, %.3f ms per step" % (name, sub["ms_per_step"]), file=sys.stderr, flush=True)
         # the same workload from pinned host memory, as packed index rows (a few batches: what a default run has time for)
         hw = W.WORKLOADS["huge_2u_m61"]
-        sub = stream_record(args, hw, W.coefficients(hw.k, hw.family, hw.param_seed), pool, STREAMED_BATCHES, True, args.cpu_seconds / 5.0)
-        ok = ok and sub["parity_sample_ok"] in (None, True)
+        try:
+            sub = stream_record(args, hw, W.coefficients(hw.k, hw.family, hw.param_seed), pool, STREAMED_BATCHES, True,
+                                args.cpu_seconds / 5.0)
+            ok = ok and sub["parity_sample_ok"] in (None, True)
+            print("bench.py: huge_2u_m61 streamed, %d batches in %.1f ms" % (STREAMED_BATCHES, sub["ms_per_step"]), file=sys.stderr,
+                  flush=True)
+        except Exception as e:              # noqa: BLE001
+            sub = {"error": repr(e)}
+            ok = False
         subs["huge_2u_m61_streamed_packed"] = sub
-        print("bench.py: huge_2u_m61 streamed, %d batches in %.1f ms" % (STREAMED_BATCHES, sub["ms_per_step"]), file=sys.stderr, flush=True)
         rec["workloads"] = subs
     if pool is not None:
         pool.close()
