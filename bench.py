@@ -14,7 +14,8 @@ length-stratified sample of the same rows (the sample's GPU rows are compared
 with it).  Without --workload the same line carries, under "workloads", the
 same measurements for the other configurations (4U on the same rows, the
 permutation table, one resident batch of the heavy-tailed 2U p = 2^61 - 1
-workload, the 1 000-row batch), each with its own roofline and parity sample,
+workload, the 1 000-row batch, the multiply-shift 2U that the paper times, two
+million short rows), each with its own roofline and parity sample,
 and four batches of the heavy-tailed workload streamed from pinned host memory
 as packed index rows (copies, kernels and copies back overlapped; that rate
 includes PCIe and is never the top-level value).
@@ -102,7 +103,7 @@ ISSUE_MODEL_EVIDENCE = "profiles/issue_rates__probe.txt, profiles/sq_counters__h
 # evaluations per second and core the oracle reaches on the GPU machine's host, to size its samples
 ORACLE_RATE_GUESS = {W.FAMILY_2U_M31: 7.0e7, W.FAMILY_4U_M31: 2.8e7, W.FAMILY_2U_M61: 1.6e7, W.FAMILY_2U_MS32: 1.0e8,
                      W.FAMILY_PERM: 6.0e7}
-SUB_WORKLOADS = ("large_4u", "perm_table", "huge_2u_m61", "tiny_2u")
+SUB_WORKLOADS = ("large_4u", "perm_table", "huge_2u_m61", "tiny_2u", "large_2u_ms32", "short_rows_2u")
 STREAMED_BATCHES = 4                    # batches of the streamed sub-record of a default run (all ten: --workload huge_2u_m61 --stream --packed)
 SPLIT = 8192                                                # rows longer than this are cut into chunks
 
