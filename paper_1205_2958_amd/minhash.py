@@ -419,8 +419,39 @@ def parse_libsvm(buf, index_base: int = 1, n_threads: int = 16, pin_memory: bool
     return row_ptr, col_idx, lab, int(mx.value)
 
 
+def _slice_cuts(offsets_h: torch.Tensor, n: int, total: int, n_slices: int):
+    """Rows at which a batch is cut into about n_slices slices of equal payload (offsets_h: the pinned
+    int64 prefix array of the payload, row_ptr or word_ptr, starting at 0)."""
+    if n_slices <= 1 or n < n_slices or total <= 0:
+        return [0, n]
+    marks = torch.searchsorted(offsets_h, torch.arange(1, n_slices, dtype=torch.int64) * (total // n_slices))
+    return sorted(set([0, n] + [int(min(max(int(m), 1), n)) for m in marks]))
+
+
+def _copy_in_slices(dst: torch.Tensor, pieces, offsets_h: torch.Tensor, cuts, total: int, events, stream) -> None:
+    """Copies the pieces of a payload array into dst on `stream`, cutting them again where a slice of rows
+    ends, and records events[c] when the payload of slice c (rows cuts[c] .. cuts[c+1]) is complete; the
+    last slice is complete when the caller's own event after this call is."""
+    at, next_cut = 0, 1
+    for p in pieces:
+        done = 0
+        while done < p.numel():
+            upto = int(offsets_h[cuts[next_cut]]) if next_cut < len(cuts) - 1 else total
+            take = min(p.numel() - done, max(upto - at, 0))
+            if take > 0:
+                dst[at: at + take].copy_(p[done: done + take].view(torch.int32), non_blocking=True)
+                at += take
+                done += take
+            if at >= upto and next_cut < len(cuts) - 1:
+                events[next_cut - 1].record(stream)
+                next_cut += 1
+    while next_cut < len(cuts) - 1:               # slices whose rows are empty at the end of the payload
+        events[next_cut - 1].record(stream)
+        next_cut += 1
+
+
 def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.Tensor, max_rows: int, max_nnz: int,
-                   perm_ld: Optional[int] = None, flags: int = 0):
+                   perm_ld: Optional[int] = None, flags: int = 0, edge_slices: int = 4):
     """Streams host-resident batches through the GPU with copies and kernels
     overlapped (the three-phase batch loop of Section 3.2: copy a chunk of sets to
     the GPU, hash it there, copy the results back, repeat).
@@ -432,7 +463,10 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
     cheaper to pin in 1 GiB pieces).  Batch i+1 is copied host-to-device on
     a side stream while batch i is hashed on the compute stream and the
     signatures of batch i-1 travel back on a third stream; two sets of device
-    buffers alternate.  Returns the list of pinned uint8 host tensors
+    buffers alternate.  The first and the last batch go in ``edge_slices`` slices
+    of rows with about equal numbers of indices, each hashed as soon as its indices
+    have arrived: nothing hides the first copy or the last kernel, so both are made
+    short.  Returns the list of pinned uint8 host tensors
     [n_rows_i, ceil(k*b/8)], complete when the function returns.
     """
     dev = params.device
@@ -442,7 +476,10 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
     col_d = [torch.empty(max_nnz, dtype=torch.int32, device=dev) for _ in range(n_buf)]
     out_d = [torch.empty((max_rows, sig), dtype=torch.uint8, device=dev) for _ in range(n_buf)]
     ws = alloc_workspace(max_rows, max_nnz, k, family, dev)
-    codes = torch.zeros(max(len(batches), 1), dtype=torch.int32, device=dev)     # what each call reported: the next one clears it
+    n_slices = max(1, edge_slices)
+    codes = torch.zeros(len(batches) + 2 * n_slices, dtype=torch.int32, device=dev)     # what each call reported: the next one clears it
+    n_calls = 0
+    slice_done = [torch.cuda.Event() for _ in range(n_slices)]
     s_in, s_run, s_out = torch.cuda.Stream(dev), torch.cuda.Stream(dev), torch.cuda.Stream(dev)
     now = torch.cuda.current_stream(dev)
     for s in (s_in, s_run, s_out):
@@ -462,20 +499,22 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
         results.append(out_h)
         if i >= n_buf:
             s_in.wait_event(run_done[u])          # the kernel that read this input buffer has finished
+        edge = i == 0 or i == len(batches) - 1
+        cuts = _slice_cuts(rp_h, n, nnz, n_slices) if edge and int(rp_h[0]) == 0 else [0, n]
         with torch.cuda.stream(s_in):
             rp_d[u][: n + 1].copy_(rp_h, non_blocking=True)
-            at = 0
-            for p in pieces:
-                col_d[u][at: at + p.numel()].copy_(p.view(torch.int32), non_blocking=True)
-                at += p.numel()
+            _copy_in_slices(col_d[u], pieces, rp_h, cuts, nnz, slice_done, s_in)
             in_done[u].record(s_in)
-        s_run.wait_event(in_done[u])
         if i >= n_buf:
             s_run.wait_event(out_done[u])         # the previous signatures left this output buffer
-        minhash_signatures(rp_d[u][: n + 1], col_d[u][:nnz], D, k, b, family, params, out=out_d[u][:n],
-                           out_stride=sig, perm_ld=perm_ld, workspace=ws, stream=s_run, flags=flags)
-        if n > 0:
-            status_async(ws, codes[i: i + 1], stream=s_run)
+        for c in range(len(cuts) - 1):            # (offsets in row_ptr are absolute: a slice is the same arrays from another row on)
+            r0, r1 = cuts[c], cuts[c + 1]
+            s_run.wait_event(slice_done[c] if c < len(cuts) - 2 else in_done[u])
+            minhash_signatures(rp_d[u][r0: r1 + 1], col_d[u][:nnz], D, k, b, family, params, out=out_d[u][r0:r1],
+                               out_stride=sig, perm_ld=perm_ld, workspace=ws, stream=s_run, flags=flags)
+            if r1 > r0:
+                status_async(ws, codes[n_calls: n_calls + 1], stream=s_run)
+                n_calls += 1
         run_done[u].record(s_run)
         s_out.wait_event(run_done[u])
         with torch.cuda.stream(s_out):
@@ -486,7 +525,7 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
     now.wait_stream(s_out)
     # the deferred checks of every batch (work-list overflow, MINHASH_FLAG_VALIDATE findings); every batch was
     # bounded by max_rows / max_nnz above, so an overflow can only come from offsets that contradict the sizes
-    bad = [int(c) for c in codes[: len(batches)].cpu().tolist() if c != 0]
+    bad = [int(c) for c in codes[:n_calls].cpu().tolist() if c != 0]
     if bad:
         _raise(bad[0])
     return results
@@ -508,11 +547,11 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
 
     With ``decode_in_kernel`` (the default) there is no decoder pass at all: the
     hash kernels fetch the words and decode each tile while they stage it
-    (``minhash_signatures_packed``).  The first batch then goes in
+    (``minhash_signatures_packed``).  The first and the last batch then go in
     ``first_batch_slices`` slices of rows with about equal numbers of words, each
     hashed as soon as its words have arrived (the offsets in word_ptr are absolute,
     so a slice is the same arrays from another row on): nothing hides the first
-    copy, so it is made short.
+    copy or the last kernel, so both are made short.
     """
     dev = params.device
     sig = (k * b + 7) // 8
@@ -525,7 +564,7 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
     out_d = [torch.empty((max_rows, sig), dtype=torch.uint8, device=dev) for _ in range(n_buf)]
     codes = torch.zeros(max(len(batches), 1), dtype=torch.int32, device=dev)            # the decoder's reports
     n_slices = max(1, first_batch_slices) if decode_in_kernel else 1
-    hash_codes = torch.zeros(len(batches) + n_slices, dtype=torch.int32, device=dev)    # the hash calls', one per call
+    hash_codes = torch.zeros(len(batches) + 2 * n_slices, dtype=torch.int32, device=dev)    # the hash calls', one per call
     n_calls = 0
     slice_done = [torch.cuda.Event() for _ in range(n_slices)]
     ws = alloc_workspace(max_rows, max_nnz, k, family, dev)
@@ -549,28 +588,14 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
         results.append(out_h)
         if i >= n_buf:
             s_in.wait_event(run_done[u])          # decoder and kernels that read this set of buffers (row_ptr too) have finished
-        # rows at which the batch is cut (the first batch only, and only if it has rows to cut)
-        cuts = [0, n]
-        if i == 0 and n_slices > 1 and n >= n_slices and n_words > 0:
-            marks = torch.searchsorted(wp_h, torch.arange(1, n_slices, dtype=torch.int64) * (n_words // n_slices))
-            cuts = sorted(set([0, n] + [int(min(max(int(m), 1), n)) for m in marks]))
+        # rows at which the batch is cut (the first and the last batch only)
+        edge = i == 0 or i == len(batches) - 1
+        cuts = _slice_cuts(wp_h, n, n_words, n_slices) if edge else [0, n]
         with torch.cuda.stream(s_in):
             rp_d[u][: n + 1].copy_(rp_h, non_blocking=True)
             wp_d[u][: n + 1].copy_(wp_h, non_blocking=True)
             wd_d[u][:n].copy_(width_h.view(torch.int32), non_blocking=True)
-            at, next_cut = 0, 1
-            for p in pieces:                      # pieces of the word array, cut again where a slice of rows ends
-                done = 0
-                while done < p.numel():
-                    upto = int(wp_h[cuts[next_cut]]) if next_cut < len(cuts) - 1 else n_words
-                    take = min(p.numel() - done, max(upto - at, 0))
-                    if take > 0:
-                        words_d[u][at: at + take].copy_(p[done: done + take].view(torch.int32), non_blocking=True)
-                        at += take
-                        done += take
-                    if at >= upto and next_cut < len(cuts) - 1:
-                        slice_done[next_cut - 1].record(s_in)
-                        next_cut += 1
+            _copy_in_slices(words_d[u], pieces, wp_h, cuts, n_words, slice_done, s_in)
             in_done[u].record(s_in)
         if i >= n_buf:
             s_run.wait_event(out_done[u])         # the previous signatures left this output buffer
