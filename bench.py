@@ -57,6 +57,8 @@ ISSUE_MIX = {
     W.FAMILY_4U_M31: (3.0, 1.0 + 0.5 + 0.5, 3.0),   # 3 mad | add3, half a signed and half an unsigned max3 | shr,and,shr
     W.FAMILY_2U_M61: (2.0, 1.0 + 0.5, 2.0),         # 2 mad | funnel shift, half a max3 | mov,add
     W.FAMILY_2U_MS32: (1.0, 0.5, 0.0),              # mad | half a min3 (mask or shift once per row)
+    # three Horner steps of 2 mad | funnel shift, add with carry out, add with carry in | mov, and; then add3, half a min3 | shr, and
+    W.FAMILY_4U_M61: (6.0, 9.0 + 1.0 + 0.5, 6.0 + 2.0),
 }
 # other D (--universe) below 2^28: fractional key (one multiply-add and one funnel shift after the canonical residue)
 ISSUE_MIX_OTHER_D_FRAC = {
@@ -81,6 +83,12 @@ ISSUE_MIX_M61_OTHER_D = (
     (4.0, 6.5, 8.0),
     (6.0, 6.5, 10.0),      # D below 2^29: mulhi, mad | | shr, mov
 )
+# 4U with p = 2^61-1 and such a D: the three Horner steps (6 mad | 9 | 6), then the same second part (mulhi, mad |
+# funnel shift, min3, min, half a min3 | shr, add, sub, sub, add, add)
+ISSUE_MIX_4U_M61_OTHER_D = (
+    (8.0, 12.5, 12.0),
+    (10.0, 12.5, 14.0),
+)
 
 
 def issue_slots(mix):
@@ -102,7 +110,7 @@ PROFILED_TRAFFIC = {
 ISSUE_MODEL_EVIDENCE = "profiles/issue_rates__probe.txt, profiles/sq_counters__hash_kernels.txt"
 # evaluations per second and core the oracle reaches on the GPU machine's host, to size its samples
 ORACLE_RATE_GUESS = {W.FAMILY_2U_M31: 7.0e7, W.FAMILY_4U_M31: 2.8e7, W.FAMILY_2U_M61: 1.6e7, W.FAMILY_2U_MS32: 1.0e8,
-                     W.FAMILY_PERM: 6.0e7}
+                     W.FAMILY_PERM: 6.0e7, W.FAMILY_4U_M61: 6.0e6}
 SUB_WORKLOADS = ("large_4u", "perm_table", "huge_2u_m61", "tiny_2u", "large_2u_ms32", "short_rows_2u")
 STREAMED_BATCHES = 4                    # batches of the streamed sub-record of a default run (all ten: --workload huge_2u_m61 --stream --packed)
 SPLIT = 8192                                                # rows longer than this are cut into chunks
@@ -111,6 +119,8 @@ SPLIT = 8192                                                # rows longer than t
 def issue_mix_for(family: int, D: int):
     if family == W.FAMILY_2U_M61 and D & (D - 1):
         return ISSUE_MIX_M61_OTHER_D[0 if D > (1 << 29) else 1]
+    if family == W.FAMILY_4U_M61 and D & (D - 1):
+        return ISSUE_MIX_4U_M61_OTHER_D[0 if D > (1 << 29) else 1]
     if D & (D - 1):
         return (ISSUE_MIX_OTHER_D_FRAC if D < (1 << 28) else
                 ISSUE_MIX_OTHER_D_BIG if 3 * D >= (1 << 31) - 1 else ISSUE_MIX_OTHER_D)[family]
@@ -533,7 +543,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="all", choices=["all", "tiny_2u", "large_2u", "large_4u", "perm_table",
-                                                           "huge_2u_m61", "large_2u_ms32", "short_rows_2u", "consumers"],
+                                                           "huge_2u_m61", "large_2u_ms32", "short_rows_2u", "large_4u_m61", "consumers"],
                     help="all (default): large_2u as the headline plus the other configurations as sub-records")
     ap.add_argument("--pairs", type=int, default=20_000_000, help="consumers: number of random row pairs")
     ap.add_argument("--rows", type=int, default=0, help="use only the first ROWS rows (debugging; invalidates the metric)")
@@ -583,7 +593,7 @@ def main() -> int:
     headline = "large_2u" if args.workload == "all" else args.workload
     w = W.WORKLOADS[headline]
     family = w.family
-    if args.universe and family == W.FAMILY_2U_M61 and not args.stream and 3 <= args.universe <= (1 << 32) // 3:
+    if args.universe and family in (W.FAMILY_2U_M61, W.FAMILY_4U_M61) and not args.stream and 3 <= args.universe <= (1 << 32) // 3:
         pass                                # huge_2u_m61 with another D: served in 32-bit steps up to 2^32 / 3
     elif args.universe and (family not in ISSUE_MIX_OTHER_D or args.stream or args.generic_mod
                             or not 1 <= args.universe < (1 << 31) - 1):

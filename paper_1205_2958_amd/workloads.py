@@ -429,6 +429,9 @@ WORKLOADS = {
     # the hash the paper itself times as "GPU 2U" (Section 3.3), on the webspam-shaped rows
     "large_2u_ms32": Workload("large_2u_ms32", 350_000, 1 << 24, FAMILY_2U_MS32, 500, 8, 1002, 2006, "lognormal",
                               dict(median=math.exp(7.721), sigma=1.0, lo=1, hi=50_000)),
+    # 4U with the larger prime on the webspam-shaped rows (no configuration of the paper; times the Horner-form kernels)
+    "large_4u_m61": Workload("large_4u_m61", 350_000, 1 << 24, FAMILY_4U_M61, 500, 8, 1002, 2008, "lognormal",
+                             dict(median=math.exp(7.721), sigma=1.0, lo=1, hi=50_000)),
     # many short rows (the unexpanded rcv1 has about 73 nonzeros per document): per-row costs, not arithmetic
     "short_rows_2u": Workload("short_rows_2u", 2_000_000, 1 << 24, FAMILY_2U_M31, 500, 8, 1007, 2007, "lognormal",
                               dict(median=60.0, sigma=0.6, lo=1, hi=5_000)),

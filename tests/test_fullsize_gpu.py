@@ -74,6 +74,7 @@ def _check_rows(pool, w, nnz, rp_np, seed, col, params, params_np, out, rows, D=
     ("perm_table", 1.2e8),          # every sampled nonzero brings an 800-byte table row to the host
     ("large_2u_ms32", 6.0e9),
     ("short_rows_2u", 3.0e9),
+    ("large_4u_m61", 1.5e9),
 ])
 def test_large_workloads_sampled_rows(name, budget, oracle_pool):
     w, nnz, rp_np, seed, col, params, params_np, out = _run_workload(name)
@@ -85,7 +86,7 @@ def test_large_workloads_sampled_rows(name, budget, oracle_pool):
     assert bool((out != 0xAA).any(dim=1).all().item())
 
 
-@pytest.mark.parametrize("name", ["large_2u", "large_4u", "huge_2u_m61"])
+@pytest.mark.parametrize("name", ["large_2u", "large_4u", "huge_2u_m61", "large_4u_m61"])
 @pytest.mark.parametrize("D", [16_609_143, 500_000_003, 1_010_017_424])
 def test_universe_sizes_of_the_papers_datasets_sampled_rows(name, D, oracle_pool):
     """The headline rows hashed into a universe that is not a power of two (Table tab_data: webspam's
@@ -104,7 +105,7 @@ def test_universe_sizes_of_the_papers_datasets_sampled_rows(name, D, oracle_pool
     ws = mh.alloc_workspace(len(nnz), int(rp_np[-1]), w.k, w.family, DEV)
     mh.minhash_signatures(rp, col, D, w.k, w.b, w.family, params, out=out, workspace=ws)
     assert mh.status(ws) == 0
-    rows, cover = _sample_rows(nnz, seed=23, eval_budget=4e9 if name == "huge_2u_m61" else 1.5e9, k=w.k)
+    rows, cover = _sample_rows(nnz, seed=23, eval_budget={"huge_2u_m61": 4e9, "large_4u_m61": 7e8}.get(name, 1.5e9), k=w.k)
     assert cover["rows"] >= 100
     _check_rows(oracle_pool, w, nnz, rp_np, w.data_seed, col, params, params_np, out, rows, D=D)
     assert bool((out != 0xAA).any(dim=1).all().item())
