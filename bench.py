@@ -420,8 +420,8 @@ def stream_record(args, w, params_np, pool, n_batches: int, packed: bool, cpu_se
     def run(bs):
         if packed:
             return mh.stream_batches_packed(bs, w.D, w.k, w.b, w.family, params, w.batch_rows, max_nnz, max_words,
-                                            first_batch_slices=args.first_batch_slices)
-        return mh.stream_batches(bs, w.D, w.k, w.b, w.family, params, w.batch_rows, max_nnz)
+                                            edge_slices=args.edge_slices)
+        return mh.stream_batches(bs, w.D, w.k, w.b, w.family, params, w.batch_rows, max_nnz, edge_slices=args.edge_slices)
 
     run(batches[:1])                        # warm-up
     torch.cuda.synchronize()
@@ -559,8 +559,8 @@ def main() -> int:
                     help="with --stream: the batches cross the host link as tiles of differences (about 17 bits per index "
                          "instead of 32) and are decoded on the device; all ten batches then fit pinned host memory")
     ap.add_argument("--batches", type=int, default=0, help="with --stream: number of batches (default: all)")
-    ap.add_argument("--first-batch-slices", type=int, default=4,
-                    help="with --stream --packed: slices of rows the first batch is copied and hashed in")
+    ap.add_argument("--edge-slices", type=int, default=4,
+                    help="with --stream: slices of rows the first and the last batch are copied and hashed in")
     ap.add_argument("--distinct-batches", type=int, default=7,
                     help="with --stream: batches held in pinned host memory (8 GB each)")
     ap.add_argument("--generic-mod", action="store_true",

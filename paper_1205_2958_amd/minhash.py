@@ -532,7 +532,7 @@ def stream_batches(batches, D: int, k: int, b: int, family: int, params: torch.T
 
 
 def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: torch.Tensor, max_rows: int, max_nnz: int,
-                          max_words: int, flags: int = 0, decode_in_kernel: bool = True, first_batch_slices: int = 4):
+                          max_words: int, flags: int = 0, decode_in_kernel: bool = True, edge_slices: int = 4):
     """``stream_batches`` for rows that cross the host link as tiles of differences
     (``pack_indices``): about half the bytes for sorted heavy-tailed rows, so that
     the copies hide under the kernels again.
@@ -548,7 +548,7 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
     With ``decode_in_kernel`` (the default) there is no decoder pass at all: the
     hash kernels fetch the words and decode each tile while they stage it
     (``minhash_signatures_packed``).  The first and the last batch then go in
-    ``first_batch_slices`` slices of rows with about equal numbers of words, each
+    ``edge_slices`` slices of rows with about equal numbers of words, each
     hashed as soon as its words have arrived (the offsets in word_ptr are absolute,
     so a slice is the same arrays from another row on): nothing hides the first
     copy or the last kernel, so both are made short.
@@ -563,7 +563,7 @@ def stream_batches_packed(batches, D: int, k: int, b: int, family: int, params: 
     col_d = None if decode_in_kernel else torch.empty(max(max_nnz, 1), dtype=torch.int32, device=dev)    # one stream: one buffer
     out_d = [torch.empty((max_rows, sig), dtype=torch.uint8, device=dev) for _ in range(n_buf)]
     codes = torch.zeros(max(len(batches), 1), dtype=torch.int32, device=dev)            # the decoder's reports
-    n_slices = max(1, first_batch_slices) if decode_in_kernel else 1
+    n_slices = max(1, edge_slices) if decode_in_kernel else 1
     hash_codes = torch.zeros(len(batches) + 2 * n_slices, dtype=torch.int32, device=dev)    # the hash calls', one per call
     n_calls = 0
     slice_done = [torch.cuda.Event() for _ in range(n_slices)]

@@ -158,7 +158,7 @@ def test_streamed_packed_batches_equal_the_oracle():
     max_nnz = max(int(rp[h] - rp[l]) for l, h in zip(bounds[:-1], bounds[1:]))
     for decode_in_kernel, slices in ((True, 4), (True, 1), (True, 7), (True, 500), (False, 4)):    # the first batch goes in slices of rows
         outs = mh.stream_batches_packed(batches, D, k, b, family, torch.from_numpy(c.view(np.int64)).to(DEV), max_rows, max_nnz,
-                                        max_words, decode_in_kernel=decode_in_kernel, first_batch_slices=slices)
+                                        max_words, decode_in_kernel=decode_in_kernel, edge_slices=slices)
         got = np.concatenate([o.numpy() for o in outs], axis=0)
         assert np.array_equal(got, want), (decode_in_kernel, slices)
 
