@@ -1835,6 +1835,14 @@ __device__ __forceinline__ void load_tile(const uint32_t* col, int64_t begin, ui
         }
     }
 }
+// The same for a tile that lies wholly inside the row (off + 256 <= len): no entry needs the clamp,
+// and the four loads share one lane offset.
+__device__ __forceinline__ void load_full_tile(const uint32_t* col, int64_t begin, uint32_t off, int lane, uint32_t (&r)[4])
+{
+    const uint32_t* src = col + begin + off;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r[q] = __builtin_nontemporal_load(src + lane + WAVE * q);
+}
 // How the steps of the hash kernel walk a tile of in_tile nonzeros with n_slices lane slices: a
 // step takes four nonzeros per slice (two pairs); when the last step would hold at most two per
 // slice it is done as a single pair.  extent = tile entries read (repeats of the last one included).
@@ -2049,6 +2057,14 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 #pragma unroll
                         for (int i = 0; i < Pol::NW; ++i) tile[i][4 * lane + q] = w[i];
                     }
+                } else if (in_tile == (uint32_t)TILE && !a.validate) {      // the usual tile: whole, and nothing to check
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t w[Pol::NW];
+                        Pol::stage(regs[q], w);
+#pragma unroll
+                        for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
+                    }
                 } else {               // one nonzero per lane and register
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
@@ -2070,8 +2086,8 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
                         load_packed_tile(a, unit_wbegin, unit_w, len, off + TILE, lane, regs);
                     } else {
                         const uint32_t rest = len - off - TILE;
-                        load_tile(a.col_idx, begin, len, off + TILE, walk_of(rest < (uint32_t)TILE ? rest : (uint32_t)TILE, n_slices).extent,
-                                  lane, regs);
+                        if (rest >= (uint32_t)TILE) load_full_tile(a.col_idx, begin, off + TILE, lane, regs);
+                        else load_tile(a.col_idx, begin, len, off + TILE, walk_of(rest, n_slices).extent, lane, regs);
                     }
                 } else {               // last tile: the registers are free for the first tile of the next unit
                     have_next = units.peek_and_take(run_items, &nxt);
