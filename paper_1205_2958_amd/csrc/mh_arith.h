@@ -292,7 +292,8 @@ MH_HD uint32_t key_full2_2u31(const Fn2U31& f, uint32_t t2)
     return ((uint32_t)(w2 >> 32) << 1) + (uint32_t)w2;
 }
 MH_HD bool full2_key_doubtful(uint32_t key, uint32_t mask) { return key < 2u * mask; }                     // mask = D - 1 < 2^30
-MH_HD uint32_t finish_full2_key(uint32_t key, uint32_t rotation, uint32_t mask) { return mask - (((key >> 1) >> rotation) & mask); }   // rotation <= 31
+// one shift by rotation + 1 (rotation <= 31, and 31 only for D = 1, where the mask is 0 and the amount does not matter)
+MH_HD uint32_t finish_full2_key(uint32_t key, uint32_t rotation, uint32_t mask) { return mask - ((key >> ((rotation + 1u) & 31u)) & mask); }
 constexpr int32_t FULL_KEY_INIT = INT32_MIN;
 MH_HD uint32_t finish_neg_key(uint32_t key, uint32_t shift, uint32_t mask) { return mask - ((key >> shift) & mask); }
 

@@ -198,6 +198,13 @@ __device__ __forceinline__ uint32_t first_lane_value(uint32_t v)
 {
     return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
 }
+// a 64-bit value that is the same in every lane, moved to scalar registers (an address built on it
+// is then a scalar base, and the loads that use it need no copy per load)
+__device__ __forceinline__ int64_t wave_uniform64(int64_t v)
+{
+    const uint32_t lo = first_lane_value((uint32_t)v), hi = first_lane_value((uint32_t)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
 
 __device__ __forceinline__ void wave_sync_lds()
 {
@@ -1998,7 +2005,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
     auto request_first_tile = [&](const Unit& u) {
         if (u.len == 0) return;
         if constexpr (PACKED) load_packed_tile(a, u.wbegin, u.w, u.len, 0, lane, regs);
-        else load_tile(a.col_idx, u.begin, u.len, 0, walk_of(u.len < (uint32_t)TILE ? u.len : (uint32_t)TILE, n_slices).extent, lane, regs);
+        else load_tile(a.col_idx, wave_uniform64(u.begin), u.len, 0, walk_of(u.len < (uint32_t)TILE ? u.len : (uint32_t)TILE, n_slices).extent, lane, regs);
     };
     bool have = units.init(a, n_units, (uint64_t)n_long * (uint64_t)a.n_ftiles, gridDim.x * WAVES_PER_BLOCK,
                            blockIdx.x * WAVES_PER_BLOCK + wave, n_long, lane, run_items, &cur);
@@ -2065,12 +2072,21 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(Pol::MIN_
 #pragma unroll
                         for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
                     }
+                } else if (!a.validate) {                                   // a partial tile, nothing to check
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        if (WAVE * q >= extent) break;               // wavefront-uniform: never read, not staged
+                        uint32_t w[Pol::NW];
+                        Pol::stage(regs[q], w);
+#pragma unroll
+                        for (int i = 0; i < Pol::NW; ++i) tile[i][lane + WAVE * q] = w[i];
+                    }
                 } else {               // one nonzero per lane and register
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         if (WAVE * q >= extent) break;               // wavefront-uniform: never read, not staged
                         uint32_t t = regs[q];
-                        if (a.validate && (uint64_t)t >= a.D) {
+                        if ((uint64_t)t >= a.D) {
                             atomicOr(&a.hdr->status, 2u);
                             t = 0;
                         }
