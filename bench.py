@@ -104,7 +104,11 @@ HBM_PEAK = 8.0e12
 # summary named beside it and holds for the kernels of that summary.
 PROFILED_TRAFFIC = {
     "large_2u": (6.080e9, "profiles/mh_hash_kernel_2u_m31__large_2u.txt"),
+    "large_4u": (6.077e9, "profiles/mh_hash_kernel_4u_m31__large_4u.txt"),
     "perm_table": (1.16641e12, "profiles/mh_perm_kernel__perm_table.txt"),
+    "huge_2u_m61": (9.374e9, "profiles/mh_hash_kernel_2u_m61__huge_2u_m61_batch0.txt"),
+    "large_2u_ms32": (6.027e9, "profiles/mh_hash_kernel_2u_ms32__large_2u_ms32.txt"),
+    "short_rows_2u": (1.848e9, "profiles/mh_hash_kernel_2u_m31__short_rows_2u.txt"),
 }
 # counter summaries (SQ_INSTS_VALU per evaluation against the model's instruction count) per family
 ISSUE_MODEL_EVIDENCE = "profiles/issue_rates__probe.txt, profiles/sq_counters__hash_kernels.txt"
